@@ -1,0 +1,135 @@
+/*
+ * lessdec: per-decode-step attention over an H2O-evicted, slotted KV cache combined with the
+ * constant-size low-rank state (H, z) of LESS, for AMD MI355X (gfx950).
+ *
+ * One "unit" is one (batch row, head) pair, u = b * heads + h.  Units are independent.
+ * C = n_heavy + n_recent is the slot capacity of a unit's sparse cache, D the head
+ * dimension, R the feature-map rank, R' the feature-map hidden width.
+ *
+ * Ownership and conventions
+ *  - Every pointer in the descriptor and in the call arguments is a DEVICE pointer owned
+ *    by the caller (the descriptor itself is a host struct).  The library allocates
+ *    nothing, keeps no state between calls and never synchronises: all work is enqueued
+ *    on the given HIP stream (`hip_stream` is a hipStream_t; NULL = the default stream).
+ *  - All state of the method lives in the descriptor's buffers, so a checkpoint is a copy
+ *    of them.  Calls on one descriptor must be stream-ordered; calls on different
+ *    descriptors (different buffers) are independent.
+ *  - Entry points return 0 on success and a negative LESSDEC_E* code otherwise.  Argument
+ *    errors are detected on the host before anything is launched.  No C++ exception
+ *    crosses this boundary.
+ *  - The per-unit counter n_seen is read and advanced on the device, so a sequence of
+ *    steps can be recorded into a HIP graph.
+ *
+ * Arithmetic: everything that decides an eviction (scores, exponentials, the
+ * denominator, accumulated probabilities, z, prompt column sums) is computed in fp64;
+ * value-side sums (numerator, H, outputs) in fp32; the feature-map MLPs in fp32 with
+ * fp16 matrix-core products when dtype is fp16.
+ */
+#ifndef LESSDEC_H
+#define LESSDEC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define LESSDEC_DTYPE_F32 0 /* q/k/v, cache, weights and out are float   */
+#define LESSDEC_DTYPE_F16 1 /* q/k/v, cache, weights and out are IEEE half */
+
+/* flags */
+#define LESSDEC_FLAG_SPARSE_DENOM 1u /* H2O accumulates e^s over the sparse-only denominator
+                                        instead of the full denominator of Eq. 3            */
+
+#define LESSDEC_OK 0
+#define LESSDEC_EINVAL (-1)    /* bad shape, NULL or misaligned pointer, unsupported size */
+#define LESSDEC_EWORKSPACE (-2)/* workspace missing or too small                          */
+#define LESSDEC_EHIP (-3)      /* a HIP launch or query failed                            */
+
+#define LESSDEC_MAX_RANK 64
+#define LESSDEC_MAX_CAPACITY 4094
+#define LESSDEC_MAX_HIDDEN 2048
+
+typedef struct lessdec_desc {
+  int32_t batch, heads, head_dim; /* B, Hh, D; D is 64 or 128                              */
+  int32_t n_heavy, n_recent;      /* heavy-hitter and recent slots (Sec. 4: H2O splits its
+                                     budget between the two); 1 <= C <= LESSDEC_MAX_CAPACITY */
+  int32_t rank, hidden;           /* R <= 64, R' <= 2048 (Eq. 1, Eq. 2)                    */
+  int32_t dtype;                  /* LESSDEC_DTYPE_*                                       */
+  uint32_t flags;                 /* LESSDEC_FLAG_*                                        */
+  int32_t reserved;
+  /* sparse cache K_C, V_C (Sec. 3.1) as slots, replaced in place (Sec. 3.2)               */
+  void *k_cache, *v_cache;        /* [B,Hh,C,D] dtype, 16-byte aligned                     */
+  double *acc;                    /* [B,Hh,C] accumulated attention probability (H2O)      */
+  int32_t *pos;                   /* [B,Hh,C] original token index of the slot, -1 = empty */
+  float *psi;                     /* [B,Hh,C,R] psi(k) of the cached key (Eq. 2), kept so
+                                     that an eviction needs no MLP evaluation              */
+  /* low-rank state (Sec. 2.2, Eq. 4-6)                                                    */
+  float *H;                       /* [B,Hh,R,D]                                            */
+  double *z;                      /* [B,Hh,R]                                              */
+  int32_t *n_seen;                /* [B,Hh] tokens seen so far by each unit                */
+  /* feature-map weights, per head (Eq. 1, Eq. 2), row-major, dtype                        */
+  const void *Wq1, *Wq2;          /* phi: [Hh,D,R'], [Hh,R',R]                             */
+  const void *Wk1, *Wk2, *Wk3;    /* psi: [Hh,D,R'], [Hh,R',R], [Hh,R,R]                   */
+  void *workspace;                /* >= lessdec_workspace_bytes(), 256-byte aligned        */
+  size_t workspace_bytes;
+} lessdec_desc;
+
+/*
+ * Bytes of scratch the calls need.  max_prompt = 0: enough for lessdec_step only;
+ * otherwise enough for lessdec_prefill with prompts up to max_prompt tokens as well.
+ * Host only.  Returns 0 if the descriptor's shape fields are invalid.
+ */
+size_t lessdec_workspace_bytes(const lessdec_desc *desc, int32_t max_prompt);
+
+/*
+ * Empty state: H_0 = 0, z_0 = 0 (Sec. 2.2), every slot empty (pos = -1, acc = 0, psi = 0),
+ * n_seen = 0.  Must be called once before the first step on fresh buffers.
+ */
+int lessdec_state_reset(const lessdec_desc *desc, void *hip_stream);
+
+/*
+ * Prompt phase (remark after Eq. 3: with H_0 = z_0 = 0 it is regular attention).
+ * Q, K, V: [B,Hh,P,D] dtype, the P prompt tokens of every unit.
+ * out:     [B,Hh,P,D] dtype or NULL; causal softmax attention of the prompt.
+ * Afterwards each unit's cache holds the n_recent last tokens and the n_heavy tokens with
+ * the largest column sums of the causal attention matrix (their H2O scores; ties keep the
+ * later token), in ascending token order, with acc = column sum; every other prompt pair
+ * is folded into H, z (Eq. 6); n_seen = P.  If P <= C every token is kept.
+ * Overwrites any previous state of the descriptor (no reset needed before it).
+ * P >= 1.  Needs the workspace sized for max_prompt >= P.
+ */
+int lessdec_prefill(const lessdec_desc *desc, const void *Q, const void *K, const void *V,
+                    int32_t P, void *out, void *hip_stream);
+
+/*
+ * One generation step (Algorithm 1) for every unit.
+ * q, k, v: [B,Hh,D] dtype, this step's query/key/value per unit.
+ * out:     [B,Hh,D] dtype, the attention output of Eq. 3 computed with the state from before
+ *          this step's eviction.
+ * evicted_pos: [B,Hh] or NULL; token index of the pair folded into H, z this step (Eq. 4,
+ *          Eq. 5), -1 while the cache is still filling.
+ * Per unit: scores the query against the cached keys and k; adds the low-rank terms
+ * phi(q) H and phi(q) z^T; adds each pair's probability to its accumulated score (the new
+ * pair starts with its own); if the cache is full, discards the pair with the smallest
+ * accumulated score among those not within the n_recent most recent tokens (the new one
+ * counts as recent; ties discard the older), folds it into H, z and writes the new pair
+ * into its slot; advances n_seen.
+ */
+int lessdec_step(const lessdec_desc *desc, const void *q, const void *k, const void *v,
+                 void *out, int32_t *evicted_pos, void *hip_stream);
+
+/* Static message for a return code. */
+const char *lessdec_strerror(int code);
+
+/*
+ * Host helper for Table 1: tokens cached at `percent` of `max_len`, rounded down to an
+ * even number so that heavy and recent halves are equal.
+ */
+int32_t lessdec_budget_tokens(double percent, int32_t max_len);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LESSDEC_H */

@@ -1,0 +1,174 @@
+// C ABI of lessdec: argument checks, workspace carve-up, kernel launches.  Nothing here
+// allocates, synchronises or keeps state between calls.
+#include <math.h>
+
+#include "lessdec_internal.h"
+
+namespace {
+
+using namespace lessdec;
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+struct Shape {
+  size_t U, C, D, R, Rp;
+};
+
+bool shape_ok(const lessdec_desc *d, Shape *s)
+{
+  if (!d) return false;
+  if (d->batch < 1 || d->heads < 1) return false;
+  if (d->head_dim != 64 && d->head_dim != 128) return false;
+  if (d->n_heavy < 0 || d->n_recent < 0) return false;
+  const long C = (long)d->n_heavy + d->n_recent;
+  if (C < 1 || C > LESSDEC_MAX_CAPACITY) return false;
+  if (d->rank < 1 || d->rank > LESSDEC_MAX_RANK) return false;
+  if (d->hidden < 1 || d->hidden > LESSDEC_MAX_HIDDEN) return false;
+  if (d->dtype != LESSDEC_DTYPE_F32 && d->dtype != LESSDEC_DTYPE_F16) return false;
+  if (d->flags & ~LESSDEC_FLAG_SPARSE_DENOM) return false;
+  if ((long)d->batch * d->heads > (1L << 30)) return false;
+  s->U = (size_t)d->batch * d->heads;
+  s->C = (size_t)C;
+  s->D = (size_t)d->head_dim;
+  s->R = (size_t)d->rank;
+  s->Rp = (size_t)d->hidden;
+  return true;
+}
+
+// Workspace: [ f_phi U*R f64 | psi_new U*R f32 | prefill: rowmax, rowsum, colsum U*P f64 |
+//              slot_of U*P i32 | psi_all U*P*R f32 ], every part 256-byte aligned.
+struct Workspace {
+  size_t off_fphi, off_psinew, off_rowmax, off_rowsum, off_colsum, off_slot, off_psiall, total;
+};
+
+Workspace carve(const Shape &s, size_t P)
+{
+  Workspace w;
+  size_t o = 0;
+  w.off_fphi = o; o = align_up(o + s.U * s.R * sizeof(double), 256);
+  w.off_psinew = o; o = align_up(o + s.U * s.R * sizeof(float), 256);
+  w.off_rowmax = o; o = align_up(o + s.U * P * sizeof(double), 256);
+  w.off_rowsum = o; o = align_up(o + s.U * P * sizeof(double), 256);
+  w.off_colsum = o; o = align_up(o + s.U * P * sizeof(double), 256);
+  w.off_slot = o; o = align_up(o + s.U * P * sizeof(int32_t), 256);
+  w.off_psiall = o; o = align_up(o + s.U * P * s.R * sizeof(float), 256);
+  w.total = o;
+  return w;
+}
+
+int check_desc(const lessdec_desc *d, Shape *s, size_t P)
+{
+  if (!shape_ok(d, s)) return LESSDEC_EINVAL;
+  if (!d->k_cache || !d->v_cache || !d->acc || !d->pos || !d->psi || !d->H || !d->z || !d->n_seen)
+    return LESSDEC_EINVAL;
+  if (!d->Wq1 || !d->Wq2 || !d->Wk1 || !d->Wk2 || !d->Wk3) return LESSDEC_EINVAL;
+  if (!aligned(d->k_cache, 16) || !aligned(d->v_cache, 16) || !aligned(d->acc, 8) ||
+      !aligned(d->z, 8) || !aligned(d->H, 16) || !aligned(d->psi, 16) || !aligned(d->pos, 4) ||
+      !aligned(d->n_seen, 4))
+    return LESSDEC_EINVAL;
+  if (!aligned(d->Wq1, 16) || !aligned(d->Wq2, 16) || !aligned(d->Wk1, 16) ||
+      !aligned(d->Wk2, 16) || !aligned(d->Wk3, 4))
+    return LESSDEC_EINVAL;
+  if (!d->workspace || !aligned(d->workspace, 256)) return LESSDEC_EWORKSPACE;
+  if (d->workspace_bytes < carve(*s, P).total) return LESSDEC_EWORKSPACE;
+  return LESSDEC_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t lessdec_workspace_bytes(const lessdec_desc *desc, int32_t max_prompt)
+{
+  Shape s;
+  if (!shape_ok(desc, &s) || max_prompt < 0) return 0;
+  return carve(s, (size_t)max_prompt).total;
+}
+
+int lessdec_state_reset(const lessdec_desc *desc, void *hip_stream)
+{
+  Shape s;
+  int rc = check_desc(desc, &s, 0);
+  if (rc) return rc;
+  return launch_reset(desc, (hipStream_t)hip_stream) == hipSuccess ? LESSDEC_OK : LESSDEC_EHIP;
+}
+
+int lessdec_step(const lessdec_desc *desc, const void *q, const void *k, const void *v, void *out,
+                 int32_t *evicted_pos, void *hip_stream)
+{
+  Shape s;
+  int rc = check_desc(desc, &s, 0);
+  if (rc) return rc;
+  if (!q || !k || !v || !out) return LESSDEC_EINVAL;
+  if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(out, 16) ||
+      !aligned(evicted_pos, 4))
+    return LESSDEC_EINVAL;
+  hipStream_t st = (hipStream_t)hip_stream;
+  const Workspace w = carve(s, 0);
+  char *ws = static_cast<char *>(desc->workspace);
+  double *f_phi = reinterpret_cast<double *>(ws + w.off_fphi);
+  float *psi_new = reinterpret_cast<float *>(ws + w.off_psinew);
+
+  FeatmapArgs fa;
+  fa.B = desc->batch; fa.Hh = desc->heads; fa.rpu = 1;
+  fa.D = desc->head_dim; fa.Rp = desc->hidden; fa.R = desc->rank;
+  fa.x = q; fa.W1 = desc->Wq1; fa.W2 = desc->Wq2; fa.W3 = nullptr; fa.out = f_phi; fa.out_f64 = 1;
+  if (launch_featmap_generic(fa, desc->dtype, st) != hipSuccess) return LESSDEC_EHIP;
+  fa.x = k; fa.W1 = desc->Wk1; fa.W2 = desc->Wk2; fa.W3 = desc->Wk3; fa.out = psi_new; fa.out_f64 = 0;
+  if (launch_featmap_generic(fa, desc->dtype, st) != hipSuccess) return LESSDEC_EHIP;
+
+  StepArgs a;
+  a.C = (int)s.C; a.Nh = desc->n_heavy; a.Nr = desc->n_recent; a.R = desc->rank;
+  a.flags = desc->flags;
+  a.k_cache = desc->k_cache; a.v_cache = desc->v_cache; a.acc = desc->acc; a.pos = desc->pos;
+  a.psi = desc->psi; a.H = desc->H; a.z = desc->z; a.n_seen = desc->n_seen;
+  a.q = q; a.k = k; a.v = v; a.out = out; a.evicted_pos = evicted_pos;
+  a.f_phi = f_phi; a.psi_new = psi_new;
+  if (launch_step(a, (int)s.U, desc->dtype, desc->head_dim, st) != hipSuccess) return LESSDEC_EHIP;
+  return LESSDEC_OK;
+}
+
+int lessdec_prefill(const lessdec_desc *desc, const void *Q, const void *K, const void *V,
+                    int32_t P, void *out, void *hip_stream)
+{
+  Shape s;
+  if (P < 1) return LESSDEC_EINVAL;
+  int rc = check_desc(desc, &s, (size_t)P);
+  if (rc) return rc;
+  if (!Q || !K || !V) return LESSDEC_EINVAL;
+  if (!aligned(Q, 16) || !aligned(K, 16) || !aligned(V, 16) || !aligned(out, 16))
+    return LESSDEC_EINVAL;
+  const Workspace w = carve(s, (size_t)P);
+  char *ws = static_cast<char *>(desc->workspace);
+  PrefillArgs a;
+  a.d = desc; a.Q = Q; a.K = K; a.V = V; a.P = P; a.out = out;
+  a.rowmax = reinterpret_cast<double *>(ws + w.off_rowmax);
+  a.rowsum = reinterpret_cast<double *>(ws + w.off_rowsum);
+  a.colsum = reinterpret_cast<double *>(ws + w.off_colsum);
+  a.slot_of = reinterpret_cast<int32_t *>(ws + w.off_slot);
+  a.psi_all = reinterpret_cast<float *>(ws + w.off_psiall);
+  return launch_prefill(a, (hipStream_t)hip_stream) == hipSuccess ? LESSDEC_OK : LESSDEC_EHIP;
+}
+
+const char *lessdec_strerror(int code)
+{
+  switch (code) {
+    case LESSDEC_OK: return "ok";
+    case LESSDEC_EINVAL: return "invalid argument (shape, NULL or misaligned pointer, unsupported size)";
+    case LESSDEC_EWORKSPACE: return "workspace missing, misaligned or too small";
+    case LESSDEC_EHIP: return "HIP launch failed";
+    default: return "unknown lessdec error";
+  }
+}
+
+int32_t lessdec_budget_tokens(double percent, int32_t max_len)
+{
+  if (!(percent >= 0.0) || max_len < 0) return 0;
+  const double tokens = percent * (double)max_len / 100.0;
+  const double half = floor(tokens * 0.5 + 1e-9);
+  if (half > 1.0e9) return 0;
+  return (int32_t)(2.0 * half);
+}
+
+}  // extern "C"

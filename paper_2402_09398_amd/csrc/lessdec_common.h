@@ -1,0 +1,123 @@
+// Shared device helpers of the lessdec kernels (gfx950, wave64).
+#pragma once
+
+#include <hip/hip_fp16.h>
+#include <hip/hip_runtime.h>
+#include <limits.h>
+#include <stdint.h>
+
+namespace lessdec {
+
+constexpr int kWave = 64;
+
+// ---- 16-byte vector access to the storage type --------------------------------------
+template <typename T> struct Store;
+template <> struct Store<float> {
+  static constexpr int kPerVec = 4;
+  struct Vec { float4 raw; };
+  __device__ static inline float get(const Vec &v, int i) { return (&v.raw.x)[i]; }
+  __device__ static inline float from_float(float x) { return x; }
+  __device__ static inline float to_float(float x) { return x; }
+};
+template <> struct Store<__half> {
+  static constexpr int kPerVec = 8;
+  struct Vec { uint4 raw; };
+  __device__ static inline float get(const Vec &v, int i)
+  {
+    const __half *h = reinterpret_cast<const __half *>(&v.raw);
+    return __half2float(h[i]);
+  }
+  __device__ static inline __half from_float(float x) { return __float2half_rn(x); }
+  __device__ static inline float to_float(__half x) { return __half2float(x); }
+};
+
+template <typename T>
+__device__ inline typename Store<T>::Vec load_vec(const T *p)
+{
+  typename Store<T>::Vec v;
+  v.raw = *reinterpret_cast<const decltype(v.raw) *>(p);
+  return v;
+}
+
+// ---- wave / block reductions (fixed order, so results do not depend on timing) --------
+__device__ inline double wave_sum(double v)
+{
+#pragma unroll
+  for (int o = kWave / 2; o > 0; o >>= 1) v += __shfl_xor(v, o);
+  return v;
+}
+__device__ inline double wave_max(double v)
+{
+#pragma unroll
+  for (int o = kWave / 2; o > 0; o >>= 1) v = fmax(v, __shfl_xor(v, o));
+  return v;
+}
+
+// All threads of the block must call these. `red` has room for one double per wave.
+template <int kWaves>
+__device__ inline double block_sum(double v, double *red)
+{
+  v = wave_sum(v);
+  if ((threadIdx.x & (kWave - 1)) == 0) red[threadIdx.x / kWave] = v;
+  __syncthreads();
+  double r = red[0];
+#pragma unroll
+  for (int w = 1; w < kWaves; ++w) r += red[w];
+  __syncthreads();
+  return r;
+}
+template <int kWaves>
+__device__ inline double block_max(double v, double *red)
+{
+  v = wave_max(v);
+  if ((threadIdx.x & (kWave - 1)) == 0) red[threadIdx.x / kWave] = v;
+  __syncthreads();
+  double r = red[0];
+#pragma unroll
+  for (int w = 1; w < kWaves; ++w) r = fmax(r, red[w]);
+  __syncthreads();
+  return r;
+}
+
+// Eviction candidate: smaller accumulated score first, then the older token.
+struct Cand {
+  double acc;
+  int pos;
+  int slot;
+};
+__device__ inline bool cand_less(const Cand &a, const Cand &b)
+{
+  return a.acc < b.acc || (a.acc == b.acc && a.pos < b.pos);
+}
+__device__ inline Cand cand_none() { return Cand{__builtin_inf(), INT_MAX, -1}; }
+__device__ inline Cand wave_argmin(Cand c)
+{
+#pragma unroll
+  for (int o = kWave / 2; o > 0; o >>= 1) {
+    Cand d;
+    d.acc = __shfl_xor(c.acc, o);
+    d.pos = __shfl_xor(c.pos, o);
+    d.slot = __shfl_xor(c.slot, o);
+    if (cand_less(d, c)) c = d;
+  }
+  return c;
+}
+template <int kWaves>
+__device__ inline Cand block_argmin(Cand c, Cand *red)
+{
+  c = wave_argmin(c);
+  if ((threadIdx.x & (kWave - 1)) == 0) red[threadIdx.x / kWave] = c;
+  __syncthreads();
+  Cand r = red[0];
+#pragma unroll
+  for (int w = 1; w < kWaves; ++w)
+    if (cand_less(red[w], r)) r = red[w];
+  __syncthreads();
+  return r;
+}
+
+// GELU, x * Phi(x) (Sec. 3.2 names GELU as the activation of both feature maps).
+__device__ inline double gelu_f64(double x) { return 0.5 * x * erfc(-x * 0.70710678118654752440); }
+__device__ inline float gelu_f32(float x) { return 0.5f * x * erfcf(-x * 0.70710678118654752440f); }
+
+}  // namespace lessdec

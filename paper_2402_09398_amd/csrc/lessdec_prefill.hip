@@ -1,0 +1,354 @@
+// Prompt phase: regular causal attention (remark after Eq. 3), H2O scores of the prompt
+// tokens (column sums of the attention matrix), one-shot cut to the budget, and the
+// low-rank state of everything cut away (Eq. 6).
+//
+// The scores decide which tokens are kept, so Q K^T runs in fp64 on the matrix cores
+// (v_mfma_f64_16x16x4_f64).  Operand layout of that instruction, wave64, lane = 16 * g + c:
+//   A[i][k] is taken from lane i + 16 k, B[k][j] from lane j + 16 k,
+//   result register v of lane (g, c) holds D[g + 4 v][c].
+// Both passes compute transposed tiles S^T[key][query] = K Q^T, so a lane always owns one
+// query column (c) and four keys (g + 4 v); a head row of D values is split into four
+// contiguous chunks of D / 4, chunk g supplying the k index of the instruction.
+#include "lessdec_common.h"
+#include "lessdec_internal.h"
+
+namespace lessdec {
+
+typedef double v4d __attribute__((ext_vector_type(4)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+template <typename T, int D>
+struct Chunk {
+  static constexpr int CH = D / 4;                       // values per lane group
+  static constexpr int EPV = Store<T>::kPerVec;
+  static constexpr int NV = CH / EPV;                    // 16-byte loads per lane
+  typename Store<T>::Vec v[NV];
+  __device__ inline void load(const T *row, int g)
+  {
+#pragma unroll
+    for (int i = 0; i < NV; ++i) v[i] = load_vec<T>(row + g * CH + i * EPV);
+  }
+  __device__ inline double get(int s) const { return (double)Store<T>::get(v[s / EPV], s % EPV); }
+};
+
+// S^T tile: acc[v] = sum_d K[key g+4v][d] * Q[query c][d]; `a` holds the lane's key chunk,
+// `b` the lane's query chunk (one of them already widened to fp64 by the caller).
+template <typename T, int D>
+__device__ inline v4d tile_kq(const Chunk<T, D> &kraw, const double (&qd)[D / 4])
+{
+  v4d acc = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+  for (int s = 0; s < D / 4; ++s)
+    acc = __builtin_amdgcn_mfma_f64_16x16x4f64(kraw.get(s), qd[s], acc, 0, 0, 0);
+  return acc;
+}
+template <typename T, int D>
+__device__ inline v4d tile_kq(const double (&kd)[D / 4], const Chunk<T, D> &qraw)
+{
+  v4d acc = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+  for (int s = 0; s < D / 4; ++s)
+    acc = __builtin_amdgcn_mfma_f64_16x16x4f64(kd[s], qraw.get(s), acc, 0, 0, 0);
+  return acc;
+}
+
+// -------------------------------------------------------------------------------------
+// Row pass: one wave per block of 16 queries.  Sweeps the key tiles up to the diagonal,
+// keeps the running row maximum m_i and sum L_i = sum_j e^{s_ij - m_i} (fp64), and, if an
+// output is wanted, the flash-style running numerator in fp32 on v_mfma_f32_16x16x4_f32
+// (result register w of lane (g, c) holds D[4 g + w][c]).
+// grid = U * ceil(P/16), block = 64.
+// -------------------------------------------------------------------------------------
+template <typename T, int D>
+__global__ __launch_bounds__(64) void prefill_rowpass_kernel(
+    const T *__restrict__ Q, const T *__restrict__ K, const T *__restrict__ V, int P,
+    double *__restrict__ rowmax, double *__restrict__ rowsum, T *__restrict__ out)
+{
+  constexpr int CH = D / 4, DB = D / 16;
+  const int nblk = (P + 15) / 16;
+  const int it = nblk - 1 - (int)(blockIdx.x % nblk);     // long rows first
+  const size_t u = blockIdx.x / nblk;
+  const int l = threadIdx.x, g = l / 16, c = l % 16;
+  const int qi = it * 16 + c;
+  const int qrow = qi < P ? qi : P - 1;
+  const T *Qu = Q + u * (size_t)P * D, *Ku = K + u * (size_t)P * D, *Vu = V + u * (size_t)P * D;
+  const double sqrt_d = sqrt((double)D);
+
+  double qd[CH];
+  {
+    Chunk<T, D> qraw;
+    qraw.load(Qu + (size_t)qrow * D, g);
+#pragma unroll
+    for (int s = 0; s < CH; ++s) qd[s] = qraw.get(s);
+  }
+  double m_run = -__builtin_inf(), L = 0.0;
+  v4f O[DB];
+#pragma unroll
+  for (int b = 0; b < DB; ++b) O[b] = v4f{0.f, 0.f, 0.f, 0.f};
+
+  for (int jt = 0; jt <= it; ++jt) {
+    const int j0 = jt * 16;
+    Chunk<T, D> kraw;
+    {
+      const int kr = j0 + c;
+      kraw.load(Ku + (size_t)(kr < P ? kr : P - 1) * D, g);
+    }
+    const v4d acc = tile_kq<T, D>(kraw, qd);
+    double s[4], tmax = -__builtin_inf();
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      const int kj = j0 + g + 4 * v;
+      s[v] = (kj <= qi && kj < P) ? acc[v] / sqrt_d : -__builtin_inf();
+      tmax = fmax(tmax, s[v]);
+    }
+    tmax = fmax(tmax, __shfl_xor(tmax, 16));
+    tmax = fmax(tmax, __shfl_xor(tmax, 32));
+    // key j0 <= qi always holds for jt <= it, so tmax is finite for every query with qi >= j0;
+    // queries past the prompt end (qi >= P) still see key j0 < P.
+    const double m_new = fmax(m_run, tmax);
+    const double alpha = exp(m_run - m_new);
+    double e[4], esum = 0.0;
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      e[v] = exp(s[v] - m_new);
+      esum += e[v];
+    }
+    L = L * alpha + esum;
+    m_run = m_new;
+    if (out != nullptr) {
+      const float af = (float)alpha;
+#pragma unroll
+      for (int b = 0; b < DB; ++b) O[b] *= af;
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const int kj = j0 + g + 4 * v;
+        const T *vrow = Vu + (size_t)(kj < P ? kj : P - 1) * D;
+        const float pf = (float)e[v];
+#pragma unroll
+        for (int b = 0; b < DB; ++b)
+          O[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(Store<T>::to_float(vrow[b * 16 + c]), pf, O[b],
+                                                      0, 0, 0);
+      }
+    }
+  }
+  L += __shfl_xor(L, 16);
+  L += __shfl_xor(L, 32);
+  if (qi < P) {
+    if (g == 0) {
+      rowmax[u * (size_t)P + qi] = m_run;
+      rowsum[u * (size_t)P + qi] = L;
+    }
+    if (out != nullptr) {
+      const float inv = (float)(1.0 / L);
+      T *orow = out + (u * (size_t)P + qi) * D;
+#pragma unroll
+      for (int b = 0; b < DB; ++b)
+#pragma unroll
+        for (int w = 0; w < 4; ++w) orow[b * 16 + 4 * g + w] = Store<T>::from_float(O[b][w] * inv);
+    }
+  }
+}
+
+// -------------------------------------------------------------------------------------
+// Column pass: one wave per block of 16 keys.  Sweeps the query tiles from the diagonal
+// down and sums a_ij = e^{s_ij - m_i} / L_i over the queries: the accumulated attention
+// probability of each prompt token (H2O's score, Sec. 2.1).  No atomics: every column is
+// owned by one wave and reduced in a fixed order.
+// grid = U * ceil(P/16), block = 64.
+// -------------------------------------------------------------------------------------
+template <typename T, int D>
+__global__ __launch_bounds__(64) void prefill_colpass_kernel(
+    const T *__restrict__ Q, const T *__restrict__ K, int P, const double *__restrict__ rowmax,
+    const double *__restrict__ rowsum, double *__restrict__ colsum)
+{
+  constexpr int CH = D / 4;
+  const int nblk = (P + 15) / 16;
+  const int jt = blockIdx.x % nblk;              // early columns have the longest sweeps
+  const size_t u = blockIdx.x / nblk;
+  const int l = threadIdx.x, g = l / 16, c = l % 16;
+  const int j0 = jt * 16;
+  const T *Qu = Q + u * (size_t)P * D, *Ku = K + u * (size_t)P * D;
+  const double sqrt_d = sqrt((double)D);
+
+  double kd[CH];
+  {
+    Chunk<T, D> kraw;
+    const int kr = j0 + c;
+    kraw.load(Ku + (size_t)(kr < P ? kr : P - 1) * D, g);
+#pragma unroll
+    for (int s = 0; s < CH; ++s) kd[s] = kraw.get(s);
+  }
+  double cs[4] = {0.0, 0.0, 0.0, 0.0};
+  for (int it = jt; it < nblk; ++it) {
+    const int qi = it * 16 + c;
+    const int qrow = qi < P ? qi : P - 1;
+    Chunk<T, D> qraw;
+    qraw.load(Qu + (size_t)qrow * D, g);
+    const double m = rowmax[u * (size_t)P + qrow];
+    const double Lr = rowsum[u * (size_t)P + qrow];
+    const v4d acc = tile_kq<T, D>(kd, qraw);
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      const int kj = j0 + g + 4 * v;
+      if (qi < P && kj <= qi) cs[v] += exp(acc[v] / sqrt_d - m) / Lr;
+    }
+  }
+#pragma unroll
+  for (int v = 0; v < 4; ++v) {
+#pragma unroll
+    for (int o = 8; o > 0; o >>= 1) cs[v] += __shfl_xor(cs[v], o);
+    const int kj = j0 + g + 4 * v;
+    if (c == 0 && kj < P) colsum[u * (size_t)P + kj] = cs[v];
+  }
+}
+
+// -------------------------------------------------------------------------------------
+// Selection: the last Nr tokens are recent; among the others the Nh largest (column sum,
+// position) pairs are heavy hitters; everything else is discarded.  Exact rank counting,
+// no sort: token j is heavy iff fewer than Nh candidates are larger.  Kept tokens get
+// slots in ascending position.  grid = U, block = 256.
+// -------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void prefill_select_kernel(const double *__restrict__ colsum, int P,
+                                                             int Nh, int Nr, int32_t *__restrict__ slot_of)
+{
+  __shared__ int s_cnt[256];
+  const size_t u = blockIdx.x;
+  const int tid = threadIdx.x;
+  const double *cs = colsum + u * (size_t)P;
+  int32_t *so = slot_of + u * (size_t)P;
+  const int C = Nh + Nr;
+  const int ncand = P - Nr;                     // positions < P - Nr compete for the heavy slots
+  // 1) kept flag (1 / 0) into slot_of
+  for (int j = tid; j < P; j += 256) {
+    int keep = 1;
+    if (P > C && j < ncand) {
+      const double a = cs[j];
+      int larger = 0;
+      for (int i = 0; i < ncand; ++i) {
+        const double b = cs[i];
+        larger += (b > a || (b == a && i > j)) ? 1 : 0;
+      }
+      keep = larger < Nh ? 1 : 0;
+    }
+    so[j] = keep;
+  }
+  __syncthreads();
+  // 2) slot = number of kept tokens before j: per-thread contiguous chunk + scan of 256 counts
+  const int chunk = (P + 255) / 256;
+  const int lo = tid * chunk, hi = (lo + chunk < P) ? lo + chunk : P;
+  int cnt = 0;
+  for (int j = lo; j < hi; ++j) cnt += so[j];
+  s_cnt[tid] = cnt;
+  __syncthreads();
+  int base = 0;
+  for (int t = 0; t < tid; ++t) base += s_cnt[t];
+  for (int j = lo; j < hi; ++j) {
+    const int keep = so[j];
+    so[j] = keep ? base : -1;
+    base += keep;
+  }
+}
+
+// -------------------------------------------------------------------------------------
+// Finalize: gather the kept pairs into their slots (acc = column sum, pos, psi), clear the
+// unused slots, and build H = sum psi(k)^T v, z = sum psi(k) over the discarded pairs
+// (Eq. 6).  grid = U, block = 256 (threads < D own a column of H; threads D..D+R-1 own an
+// entry of z).
+// -------------------------------------------------------------------------------------
+template <typename T, int D>
+__global__ __launch_bounds__(256) void prefill_finalize_kernel(
+    const T *__restrict__ K, const T *__restrict__ V, int P, const double *__restrict__ colsum,
+    const int32_t *__restrict__ slot_of, const float *__restrict__ psi_all, int C, int R,
+    T *__restrict__ k_cache, T *__restrict__ v_cache, double *__restrict__ acc,
+    int32_t *__restrict__ pos, float *__restrict__ psi, float *__restrict__ H,
+    double *__restrict__ z, int32_t *__restrict__ n_seen)
+{
+  const size_t u = blockIdx.x;
+  const int tid = threadIdx.x;
+  const T *Ku = K + u * (size_t)P * D, *Vu = V + u * (size_t)P * D;
+  const int32_t *so = slot_of + u * (size_t)P;
+  const float *pa = psi_all + u * (size_t)P * R;
+  const int kept = P < C ? P : C;
+
+  // gather: one (token, column) element per thread iteration
+  for (size_t idx = tid; idx < (size_t)P * D; idx += 256) {
+    const int j = (int)(idx / D), c = (int)(idx % D);
+    const int s = so[j];
+    if (s >= 0) {
+      k_cache[(u * C + s) * D + c] = Ku[idx];
+      v_cache[(u * C + s) * D + c] = Vu[idx];
+    }
+  }
+  for (int j = tid; j < P; j += 256) {
+    const int s = so[j];
+    if (s >= 0) {
+      acc[u * C + s] = colsum[u * (size_t)P + j];
+      pos[u * C + s] = j;
+      for (int r = 0; r < R; ++r) psi[(u * C + s) * R + r] = pa[(size_t)j * R + r];
+    }
+  }
+  for (int s = kept + tid; s < C; s += 256) {
+    acc[u * C + s] = 0.0;
+    pos[u * C + s] = -1;
+    for (int r = 0; r < R; ++r) psi[(u * C + s) * R + r] = 0.f;
+  }
+  // state of the discarded pairs
+  if (tid < D) {
+    double h[LESSDEC_MAX_RANK];
+#pragma unroll
+    for (int r = 0; r < LESSDEC_MAX_RANK; ++r) h[r] = 0.0;
+    for (int j = 0; j < P; ++j) {
+      if (so[j] >= 0) continue;
+      const double v = (double)Store<T>::to_float(Vu[(size_t)j * D + tid]);
+#pragma unroll
+      for (int r = 0; r < LESSDEC_MAX_RANK; ++r)
+        if (r < R) h[r] = fma((double)pa[(size_t)j * R + r], v, h[r]);
+    }
+#pragma unroll
+    for (int r = 0; r < LESSDEC_MAX_RANK; ++r)
+      if (r < R) H[(u * R + r) * D + tid] = (float)h[r];
+  } else if (tid < D + R) {
+    const int r = tid - D;
+    double a = 0.0;
+    for (int j = 0; j < P; ++j)
+      if (so[j] < 0) a += (double)pa[(size_t)j * R + r];
+    z[u * R + r] = a;
+  }
+  if (tid == 0) n_seen[u] = P;
+}
+
+template <typename T, int D>
+static hipError_t launch_prefill_t(const PrefillArgs &a, hipStream_t st)
+{
+  const lessdec_desc *d = a.d;
+  const int P = a.P, C = d->n_heavy + d->n_recent;
+  const unsigned U = (unsigned)d->batch * d->heads;
+  const unsigned grid = U * (unsigned)((P + 15) / 16);
+  prefill_rowpass_kernel<T, D><<<grid, 64, 0, st>>>((const T *)a.Q, (const T *)a.K, (const T *)a.V, P,
+                                                    a.rowmax, a.rowsum, (T *)a.out);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  prefill_colpass_kernel<T, D><<<grid, 64, 0, st>>>((const T *)a.Q, (const T *)a.K, P, a.rowmax,
+                                                    a.rowsum, a.colsum);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  prefill_select_kernel<<<U, 256, 0, st>>>(a.colsum, P, d->n_heavy, d->n_recent, a.slot_of);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  FeatmapArgs fa;
+  fa.x = a.K; fa.W1 = d->Wk1; fa.W2 = d->Wk2; fa.W3 = d->Wk3; fa.out = a.psi_all; fa.out_f64 = 0;
+  fa.B = d->batch; fa.Hh = d->heads; fa.rpu = P; fa.D = d->head_dim; fa.Rp = d->hidden; fa.R = d->rank;
+  if ((e = launch_featmap_generic(fa, d->dtype, st)) != hipSuccess) return e;
+  prefill_finalize_kernel<T, D><<<U, 256, 0, st>>>(
+      (const T *)a.K, (const T *)a.V, P, a.colsum, a.slot_of, a.psi_all, C, d->rank, (T *)d->k_cache,
+      (T *)d->v_cache, d->acc, d->pos, d->psi, d->H, d->z, d->n_seen);
+  return hipGetLastError();
+}
+
+hipError_t launch_prefill(const PrefillArgs &a, hipStream_t st)
+{
+  const int D = a.d->head_dim;
+  if (a.d->dtype == LESSDEC_DTYPE_F16)
+    return D == 128 ? launch_prefill_t<__half, 128>(a, st) : launch_prefill_t<__half, 64>(a, st);
+  return D == 128 ? launch_prefill_t<float, 128>(a, st) : launch_prefill_t<float, 64>(a, st);
+}
+
+}  // namespace lessdec

@@ -1,0 +1,265 @@
+"""Parity protocol between the HIP library and the CPU oracle (test infrastructure).
+
+The GPU runs every unit of a workload; the oracle runs a sample of the units (units are
+independent).  Both get the same seeded inputs, rounded once to the storage type.
+
+Because one different eviction changes the rest of a unit's trajectory, the oracle is
+driven along the GPU's eviction log: at every step the oracle is told which cached pair
+the GPU discarded, and reports its own two smallest candidates.  A GPU choice that is
+the oracle's smallest is an exact match; one that is the runner-up with a relative score
+gap below 1e-6 is an exempt near-tie; anything else is a failure.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+
+import numpy as np
+
+from oracle import less_oracle as lo
+from paper_2402_09398_amd import workloads as wl
+
+OUT_TOL = 2e-3        # attention outputs, relative to the row's largest magnitude
+STATE_TOL = 1e-4      # H and z, same norm
+SCORE_TOL = 2e-7      # accumulated scores: fp64 sums on both sides, but psi (hence z and the
+                      # denominator) carries the GPU's fp32 rounding of 6e-8 per feature
+TIE_GAP = 1e-6        # exemption for the eviction choice
+
+
+def rel_inf(got, ref, axis=-1):
+    """max|got - ref| / max|ref| along `axis` (0 where ref is all zero and got too)."""
+    got = np.asarray(got, dtype=np.float64); ref = np.asarray(ref, dtype=np.float64)
+    num = np.abs(got - ref).max(axis=axis)
+    den = np.abs(ref).max(axis=axis)
+    return np.where(den > 0, num / np.where(den > 0, den, 1.0), num)
+
+
+def rel_gap(a, b):
+    m = np.maximum(np.abs(a), np.abs(b))
+    return np.where(m > 0, np.abs(a - b) / np.where(m > 0, m, 1.0), 0.0)
+
+
+@dataclass
+class Report:
+    workload: str = ""
+    units_checked: int = 0
+    steps: int = 0
+    decisions: int = 0
+    exact: int = 0
+    exempt: int = 0
+    failures: list = field(default_factory=list)
+    prefill_exempt_units: int = 0
+    max_out_err: float = 0.0
+    max_prefill_out_err: float = 0.0
+    max_H_err: float = 0.0
+    max_z_err: float = 0.0
+    max_acc_err: float = 0.0
+    min_gap: float = np.inf
+    mean_share: float = 0.0
+
+    def ok(self):
+        return not self.failures
+
+    def summary(self):
+        return (f"{self.workload}: units {self.units_checked} steps {self.steps} decisions {self.decisions} "
+                f"exact {self.exact} exempt {self.exempt} failures {len(self.failures)} "
+                f"prefill-exempt-units {self.prefill_exempt_units} | out {self.max_out_err:.2e} "
+                f"prefill-out {self.max_prefill_out_err:.2e} H {self.max_H_err:.2e} z {self.max_z_err:.2e} "
+                f"acc {self.max_acc_err:.2e} | min gap {self.min_gap:.2e} low-rank share {self.mean_share:.3f}")
+
+
+def make_oracle(w, units, flags=0):
+    W = wl.head_weights(w)
+    return lo.OracleState(len(units), w.heads, w.head_dim, w.n_heavy, w.n_recent, w.rank,
+                          w.hidden, W, flags=flags, head_of_unit=[u % w.heads for u in units])
+
+
+def make_gpu(w, flags=0, max_prompt=None, device="cuda:0"):
+    import torch
+    from paper_2402_09398_amd import LessDec
+    W = {k: torch.from_numpy(v).to(device) for k, v in wl.head_weights(w).items()}
+    return LessDec(w.batch, w.heads, w.head_dim, w.n_heavy, w.n_recent, w.rank, w.hidden,
+                   w.dtype, W, flags=flags, max_prompt=w.prompt if max_prompt is None else max_prompt,
+                   device=device)
+
+
+def upload_oracle_state(gpu, st, units_all=True):
+    """Copy an oracle state (covering every unit, in order) into the GPU buffers."""
+    import torch
+    assert st.U == gpu.B * gpu.Hh
+    dev = gpu.device
+    gpu.k_cache.copy_(torch.from_numpy(st.Kc).to(gpu.tdtype))
+    gpu.v_cache.copy_(torch.from_numpy(st.Vc).to(gpu.tdtype))
+    gpu.acc.copy_(torch.from_numpy(st.acc))
+    gpu.pos.copy_(torch.from_numpy(st.pos.astype(np.int32)))
+    gpu.H.copy_(torch.from_numpy(st.H.astype(np.float32)))
+    gpu.z.copy_(torch.from_numpy(st.z))
+    gpu.n_seen.copy_(torch.from_numpy(st.n.astype(np.int32)))
+    psi = np.zeros((st.U, st.C, st.R), dtype=np.float32)
+    for u in range(st.U):
+        h = st.head[u]
+        for j in range(st.C):
+            if st.pos[u, j] >= 0:
+                psi[u, j] = lo.psi(st.Kc[u, j], st.W["Wk1"][h], st.W["Wk2"][h], st.W["Wk3"][h])
+    gpu.psi.copy_(torch.from_numpy(psi))
+    torch.cuda.synchronize(dev)
+
+
+def gpu_run(w, inp, flags=0, with_prefill=True, want_prefill_out=True, gpu=None, device="cuda:0"):
+    """Run the whole workload on the GPU through the C ABI.
+
+    inp: all_inputs() of every unit.  Returns numpy results:
+    prefill_out [U,P,D] or None, state after prefill, outs [T,U,D], evicted [T,U], final state.
+    """
+    import torch
+    gpu = gpu or make_gpu(w, flags=flags, device=device)
+    dev = gpu.device
+    res = {"gpu": gpu}
+    U, D = w.units, w.head_dim
+
+    def snapshot():
+        torch.cuda.synchronize(dev)
+        return {k: getattr(gpu, k).cpu().numpy().copy()
+                for k in ("k_cache", "v_cache", "acc", "pos", "psi", "H", "z", "n_seen")}
+
+    if with_prefill and w.prompt > 0:
+        Q, K, V = (torch.from_numpy(inp[k]).to(dev) for k in ("Q", "K", "V"))
+        pout = torch.empty_like(Q) if want_prefill_out else None
+        gpu.prefill(Q, K, V, out=pout)
+        torch.cuda.synchronize(dev)
+        res["prefill_out"] = None if pout is None else pout.cpu().numpy()
+        del Q, K, V, pout
+    elif with_prefill:
+        gpu.state_reset()
+        res["prefill_out"] = None
+    res["after_prefill"] = snapshot()
+    T = inp["q"].shape[0]
+    if T:
+        q, k, v = (torch.from_numpy(inp[n]).to(dev) for n in ("q", "k", "v"))
+        outs = torch.empty((T, U, D), dtype=gpu.tdtype, device=dev)
+        ev = torch.full((T, U), -7, dtype=torch.int32, device=dev)
+        for t in range(T):
+            gpu.step(q[t], k[t], v[t], outs[t], ev[t])
+        torch.cuda.synchronize(dev)
+        res["outs"] = outs.cpu().numpy(); res["evicted"] = ev.cpu().numpy()
+    else:
+        res["outs"] = np.zeros((0, U, D), dtype=w.np_dtype); res["evicted"] = np.zeros((0, U), dtype=np.int32)
+    res["final"] = snapshot()
+    return res
+
+
+def compare_state(rep, st, snap, units, where):
+    """Oracle state `st` (sampled units) against a GPU snapshot (all units)."""
+    for i, u in enumerate(units):
+        gp, op = snap["pos"][u].astype(np.int64), st.pos[i]
+        if not np.array_equal(gp, op):
+            rep.failures.append(f"{where}: unit {u} slot positions differ")
+            continue
+        live = op >= 0
+        if int(snap["n_seen"][u]) != int(st.n[i]):
+            rep.failures.append(f"{where}: unit {u} n_seen {snap['n_seen'][u]} != {st.n[i]}")
+        kc, vc = snap["k_cache"][u][live].astype(np.float64), snap["v_cache"][u][live].astype(np.float64)
+        if not (np.array_equal(kc, st.Kc[i][live]) and np.array_equal(vc, st.Vc[i][live])):
+            rep.failures.append(f"{where}: unit {u} cached K/V rows differ")
+        if live.any():
+            a = float(rel_gap(snap["acc"][u][live], st.acc[i][live]).max())
+            rep.max_acc_err = max(rep.max_acc_err, a)
+            if a > SCORE_TOL:
+                rep.failures.append(f"{where}: unit {u} accumulated scores off by {a:.2e}")
+        eh = float(rel_inf(snap["H"][u].ravel(), st.H[i].ravel()))
+        ez = float(rel_inf(snap["z"][u], st.z[i]))
+        rep.max_H_err = max(rep.max_H_err, eh); rep.max_z_err = max(rep.max_z_err, ez)
+        if eh > STATE_TOL:
+            rep.failures.append(f"{where}: unit {u} H off by {eh:.2e}")
+        if ez > STATE_TOL:
+            rep.failures.append(f"{where}: unit {u} z off by {ez:.2e}")
+
+
+def check_against_oracle(w, inp_units, units, res, flags=0, with_prefill=True, oracle_state=None,
+                         check_mid_state_every=0):
+    """Drive the oracle over the sampled `units` along the GPU's eviction log and compare.
+
+    inp_units: all_inputs(w, units) (the sampled units only).  res: result of gpu_run().
+    oracle_state: start from this state instead of running the oracle's prompt phase.
+    """
+    rep = Report(workload=w.name, units_checked=len(units), steps=int(res["outs"].shape[0]))
+    st = oracle_state or make_oracle(w, units, flags=flags)
+    active = np.ones(len(units), dtype=bool)
+    if oracle_state is None:
+        if with_prefill and w.prompt > 0:
+            pre = st.prefill(inp_units["Q"], inp_units["K"], inp_units["V"],
+                             want_out=res.get("prefill_out") is not None)
+            if res.get("prefill_out") is not None:
+                err = rel_inf(res["prefill_out"][units], pre["out"])          # [units, P]
+                rep.max_prefill_out_err = float(err.max())
+                if rep.max_prefill_out_err > OUT_TOL:
+                    rep.failures.append(f"prefill out error {rep.max_prefill_out_err:.2e}")
+            # kept sets; a swap of the two boundary tokens within the tie gap is exempt
+            snap = res["after_prefill"]
+            for i, u in enumerate(units):
+                gp = snap["pos"][u].astype(np.int64)
+                if np.array_equal(gp, st.pos[i]):
+                    continue
+                d = pre["dec"][i]
+                gk, ok = set(gp[gp >= 0]), set(st.pos[i][st.pos[i] >= 0])
+                if (gk - ok == {int(d[1])} and ok - gk == {int(d[3])}
+                        and rel_gap(d[0], d[2]) < TIE_GAP):
+                    rep.prefill_exempt_units += 1
+                    active[i] = False                                          # trajectories differ
+                else:
+                    rep.failures.append(f"prefill: unit {u} kept set differs: gpu-only "
+                                        f"{sorted(gk - ok)[:4]} oracle-only {sorted(ok - gk)[:4]}")
+                    active[i] = False
+        else:
+            st.reset()
+    if active.all():
+        compare_state(rep, st, res["after_prefill"], units, "after prefill")
+    T = res["outs"].shape[0]
+    shares = []
+    for t in range(T):
+        gev = res["evicted"][t][units].astype(np.int64)
+        force = np.where(active, gev, -1)
+        r = st.step(inp_units["q"][t], inp_units["k"][t], inp_units["v"][t], force=force)
+        shares.append(r["share"])
+        err = rel_inf(res["outs"][t][units], r["out"])
+        for i, u in enumerate(units):
+            if not active[i]:
+                continue
+            if err[i] > OUT_TOL or not np.isfinite(err[i]):
+                rep.failures.append(f"step {t} unit {u}: out error {err[i]:.2e}")
+            rep.max_out_err = max(rep.max_out_err, float(err[i]))
+            if r["evicted"][i] != gev[i]:
+                rep.failures.append(f"step {t} unit {u}: evicted {gev[i]} but oracle state allows {r['evicted'][i]}")
+                active[i] = False
+                continue
+            if gev[i] < 0:
+                continue
+            rep.decisions += 1
+            d = r["dec"][i]
+            gap = float(rel_gap(d[0], d[2])) if d[3] >= 0 else np.inf
+            rep.min_gap = min(rep.min_gap, gap)
+            if gev[i] == int(d[1]):
+                rep.exact += 1
+            elif gev[i] == int(d[3]) and gap < TIE_GAP:
+                rep.exempt += 1
+            else:
+                rep.failures.append(f"step {t} unit {u}: evicted {gev[i]}, oracle {int(d[1])} "
+                                    f"(runner-up {int(d[3])}, gap {gap:.2e})")
+        if check_mid_state_every and (t + 1) % check_mid_state_every == 0 and t + 1 < T:
+            pass  # mid-run state is only available from the GPU at the end; see final check
+        if len(rep.failures) > 50:
+            break
+    rep.mean_share = float(np.mean(shares)) if shares else 0.0
+    if active.all() and len(rep.failures) == 0:
+        compare_state(rep, st, res["final"], units, "final")
+    return rep
+
+
+def run_workload(w, sample_units, flags=0, with_prefill=True, want_prefill_out=True, workers=16):
+    """GPU over all units of `w`, oracle over `sample_units`; returns the Report."""
+    inp = wl.all_inputs(w, workers=workers)
+    res = gpu_run(w, inp, flags=flags, with_prefill=with_prefill, want_prefill_out=want_prefill_out)
+    units = list(sample_units)
+    inp_units = {k: (v[units] if k in ("Q", "K", "V") else v[:, units]) for k, v in inp.items()}
+    del inp
+    rep = check_against_oracle(w, inp_units, units, res, flags=flags, with_prefill=with_prefill)
+    return rep

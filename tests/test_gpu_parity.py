@@ -1,0 +1,159 @@
+"""GPU parity: the HIP library through its C ABI against the CPU oracle.
+
+Run with `-m gpu` on an MI355X.  The small cases run every unit through both sides; the
+five configurations of the benchmark run every unit on the GPU at full size and a seeded
+sample of units through the oracle (units are independent).
+
+Tolerances (tests/harness.py): attention outputs 2e-3 relative to the row's largest
+magnitude (fp16 storage, fp32 accumulation), H and z 1e-4, accumulated scores 2e-7 (fp64
+sums, fp32 feature maps); eviction positions exact, except where the oracle's two smallest candidate
+scores differ by less than 1e-6 relative.
+"""
+import numpy as np
+import pytest
+
+from paper_2402_09398_amd import workloads as wl
+from tests import harness as hz
+
+pytestmark = pytest.mark.gpu
+
+BASE = wl.WORKLOADS[2]
+
+
+def small(name, **kw):
+    d = dict(name=name, batch=2, heads=3, head_dim=128, prompt=48, steps=40, n_heavy=6,
+             n_recent=6, rank=8, hidden=64, dtype="f16")
+    d.update(kw)
+    return BASE.scaled(**d)
+
+
+def report_ok(rep, min_decisions=0):
+    print("\n" + rep.summary(), flush=True)
+    assert rep.ok(), rep.failures[:10]
+    assert rep.decisions >= min_decisions
+    assert rep.exact + rep.exempt == rep.decisions
+
+
+# ------------------------------------------------------------------ decode alone
+@pytest.mark.parametrize("w", [
+    small("step-f16-d128"),
+    small("step-f32-d64", head_dim=64, dtype="f32", rank=4),
+    small("step-f16-d64", head_dim=64),
+    small("step-f32-d128", dtype="f32"),
+], ids=lambda w: w.name)
+def test_step_from_oracle_state(w):
+    """Only lessdec_step runs on the GPU: the state after the prompt comes from the oracle."""
+    units = list(range(w.units))
+    inp = wl.all_inputs(w)
+    st = hz.make_oracle(w, units)
+    st.prefill(inp["Q"], inp["K"], inp["V"], want_out=False)
+    gpu = hz.make_gpu(w)
+    hz.upload_oracle_state(gpu, st)
+    res = hz.gpu_run(w, inp, with_prefill=False, gpu=gpu)
+    rep = hz.check_against_oracle(w, inp, units, res, oracle_state=st)
+    report_ok(rep, min_decisions=w.units * w.steps)
+
+
+# ------------------------------------------------------------------ whole path, edge cases
+EDGE = [
+    small("ragged-prompt", prompt=37),
+    small("prompt-fits-budget", prompt=5, n_heavy=8, n_recent=8, steps=30),
+    small("no-prompt", prompt=0, n_heavy=4, n_recent=4, steps=30),
+    small("no-recent-window", n_heavy=6, n_recent=0, prompt=20, steps=25),
+    small("no-heavy-hitters", n_heavy=0, n_recent=5, prompt=20, steps=25),
+    small("one-slot-recent", n_heavy=0, n_recent=1, prompt=9, steps=12),
+    small("one-slot-heavy", n_heavy=1, n_recent=0, prompt=9, steps=12),
+    small("rank-64-hidden-48", rank=64, hidden=48),
+    small("rank-1", rank=1, hidden=33),
+    small("hidden-2048", hidden=2048, batch=1, heads=2, steps=8),
+    small("odd-batch-heads", batch=3, heads=5),
+    small("d64-f16", head_dim=64),
+    small("d128-f32", dtype="f32"),
+    small("wide-cache", n_heavy=150, n_recent=150, prompt=400, steps=24, batch=1, heads=2),
+    wl.WORKLOADS[4].scaled(name="heavy-tailed-keys", batch=1, heads=4, prompt=256, steps=64,
+                           n_heavy=10, n_recent=10, hidden=64),
+]
+
+
+@pytest.mark.parametrize("w", EDGE, ids=lambda w: w.name)
+def test_whole_path_edge_cases(w):
+    rep = hz.run_workload(w, range(w.units))
+    expect = w.units * max(0, min(w.steps, w.prompt + w.steps - w.capacity))
+    report_ok(rep, min_decisions=expect)
+
+
+def test_sparse_denominator_reading():
+    w = small("sparse-denominator")
+    rep = hz.run_workload(w, range(w.units), flags=1)
+    report_ok(rep, min_decisions=w.units * w.steps)
+
+
+def test_maximum_capacity():
+    w = small("max-capacity", batch=1, heads=2, n_heavy=2047, n_recent=2047, prompt=4200, steps=6,
+              rank=16, hidden=64)
+    rep = hz.run_workload(w, range(w.units))
+    report_ok(rep, min_decisions=w.units * w.steps)
+
+
+def test_reset_clears_a_used_state():
+    import torch
+    w = small("reset", prompt=20, steps=4)
+    inp = wl.all_inputs(w)
+    res = hz.gpu_run(w, inp)
+    gpu = res["gpu"]
+    gpu.state_reset()
+    torch.cuda.synchronize()
+    assert int(gpu.n_seen.abs().sum()) == 0 and bool((gpu.pos == -1).all())
+    assert float(gpu.H.abs().sum()) == 0 and float(gpu.z.abs().sum()) == 0
+    assert float(gpu.acc.abs().sum()) == 0 and float(gpu.psi.abs().sum()) == 0
+    # and the state is usable again: decode from empty matches the oracle
+    w0 = w.scaled(prompt=0)
+    res2 = hz.gpu_run(w0, {k: (v[:, :0] if k in "QKV" else v) for k, v in inp.items()},
+                      with_prefill=False, gpu=gpu)
+    inp0 = dict(inp); inp0["Q"] = inp["Q"][:, :0]; inp0["K"] = inp["K"][:, :0]; inp0["V"] = inp["V"][:, :0]
+    rep = hz.check_against_oracle(w0, inp0, list(range(w.units)), res2)
+    report_ok(rep)
+
+
+def test_checkpoint_restore_continues_bit_identically():
+    """All state lives in the caller's buffers: a copy of them is a checkpoint."""
+    import torch
+    w = small("checkpoint", steps=30)
+    inp = wl.all_inputs(w)
+    half = 15
+    first = {k: (v if k in "QKV" else v[:half]) for k, v in inp.items()}
+    res = hz.gpu_run(w, first)
+    gpu = res["gpu"]
+    names = ("k_cache", "v_cache", "acc", "pos", "psi", "H", "z", "n_seen")
+    saved = {n: getattr(gpu, n).clone() for n in names}
+    q, k, v = (torch.from_numpy(inp[n][half:]).cuda() for n in ("q", "k", "v"))
+
+    def run_rest():
+        outs = torch.empty_like(q); ev = torch.empty((q.shape[0], w.units), dtype=torch.int32, device="cuda")
+        for t in range(q.shape[0]):
+            gpu.step(q[t], k[t], v[t], outs[t], ev[t])
+        torch.cuda.synchronize()
+        return outs.cpu(), ev.cpu(), {n: getattr(gpu, n).cpu().clone() for n in names}
+
+    a = run_rest()
+    for n in names:
+        getattr(gpu, n).copy_(saved[n])
+    b = run_rest()
+    assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
+    for n in names:
+        assert torch.equal(a[2][n], b[2][n]), n
+
+
+# ------------------------------------------------------------------ the five configurations
+def sample_units(w, count, seed=0):
+    rng = np.random.default_rng(seed)
+    return sorted(int(u) for u in rng.choice(w.units, size=min(count, w.units), replace=False))
+
+
+@pytest.mark.parametrize("cfg,count", [(1, 2), (2, 24), (3, 16), (4, 10), (5, 6)])
+def test_configuration_full_size(cfg, count):
+    w = wl.WORKLOADS[cfg]
+    units = sample_units(w, count, seed=cfg)
+    rep = hz.run_workload(w, units, want_prefill_out=True)
+    report_ok(rep, min_decisions=len(units) * w.steps - rep.prefill_exempt_units * w.steps)
+    assert 0.0 < rep.mean_share < 1.0          # both the sparse and the low-rank term matter
