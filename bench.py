@@ -1,0 +1,165 @@
+#!/usr/bin/env python3
+"""Decode-step benchmark of lessdec on one MI355X.
+
+A step is one lessdec_step call: one generation step of one attention layer for every
+(batch, head) unit of the workload (feature maps, attention over the evicted cache plus
+the low-rank terms, H2O score update, eviction, state update, in-place insert).  The
+default workload is the Llama-2-7B shape at batch 64 (32 heads, head_dim 128, prompt
+1024, 51 heavy + 51 recent slots, rank 8, fp16 cache).  `--layers` independent layer
+states are cycled round-robin so the working set (about 1.1 GB) does not fit the 256 MB
+Infinity Cache, as in a real 32-layer decode.  Inputs are synthetic and resident in HBM
+before the timed region; the state of every layer comes from lessdec_prefill on a
+synthetic prompt.
+
+Prints one JSON line (see the design doc for the fields).  One GPU only.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X published HBM3E bandwidth
+
+
+def algorithmic_bytes_per_unit_step(w) -> float:
+    """Bytes the method itself must move per unit and step ('Roofline')."""
+    e = 2 if w.dtype == "f16" else 4
+    C, D, R, Rp, B = w.capacity, w.head_dim, w.rank, w.hidden, w.batch
+    kv = 2 * C * D * e                       # every retained key and value once
+    io = 3 * D * e + D * e + 2 * D * e       # q,k,v in; out; the inserted pair
+    scores = 2 * 8 * C + 4 * C + 4           # acc (fp64) read+write, pos read, one pos write
+    state = 2 * (R * D * 4 + R * 8)          # H (fp32) and z (fp64) read + write
+    psi = 2 * R * 4                          # psi of the discarded pair read, of the new pair written
+    weights = (2 * (D * Rp + Rp * R) + R * R) * e / B   # per-head weights shared by the batch rows
+    return kv + io + scores + state + psi + weights
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def cpu_baseline(w, n_units, n_steps):
+    """The oracle as it stands, timed on the host cores on a bounded sample of the workload."""
+    from oracle import less_oracle as lo
+    from paper_2402_09398_amd import workloads as wl
+    units = list(range(n_units))
+    inp = wl.all_inputs(w.scaled(steps=n_steps), units, workers=16)
+    W = wl.head_weights(w)
+    st = lo.OracleState(n_units, w.heads, w.head_dim, w.n_heavy, w.n_recent, w.rank, w.hidden, W,
+                        head_of_unit=[u % w.heads for u in units])
+    t0 = time.perf_counter()
+    st.prefill(inp["Q"], inp["K"], inp["V"], want_out=False)
+    t_prefill = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    for t in range(n_steps):
+        st.step(inp["q"][t], inp["k"][t], inp["v"][t])
+    t_dec = time.perf_counter() - t0
+    cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    return {"value": n_units * n_steps / t_dec, "unit": "unit-steps/s", "cores": cores, "kind": "oracle",
+            "sample": f"{n_units} units (batch rows 0..{n_units // w.heads - 1}) x {n_steps} decode steps "
+                      f"after the oracle's own prompt phase ({t_prefill:.1f} s, not counted)",
+            "decode_seconds": t_dec}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=4096)
+    ap.add_argument("--warmup", type=int, default=128)
+    ap.add_argument("--cfg", type=int, default=3, help="workload (1..5), default the batch-64 Llama-2-7B shape")
+    ap.add_argument("--layers", type=int, default=8, help="independent layer states cycled round-robin")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-units", type=int, default=256)
+    ap.add_argument("--cpu-steps", type=int, default=384)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (every unit is independent; "
+                 "see DESIGN.md for how it would shard). Use --gpus 1.")
+
+    import numpy as np
+    import torch
+    from paper_2402_09398_amd import LessDec, workloads as wl
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    dev = torch.device("cuda:0")
+    w = wl.WORKLOADS[args.cfg]
+    L = args.layers
+    U, D, T = w.units, w.head_dim, w.steps
+
+    t0 = time.perf_counter()
+    inp = wl.all_inputs(w, workers=16)
+    log(f"[bench] inputs for {U} units generated in {time.perf_counter() - t0:.1f} s")
+    W = {k: torch.from_numpy(v).to(dev) for k, v in wl.head_weights(w).items()}
+    layers = [LessDec(w.batch, w.heads, D, w.n_heavy, w.n_recent, w.rank, w.hidden, w.dtype, W,
+                      max_prompt=w.prompt if i == 0 else 0, device=dev) for i in range(L)]
+    Q, K, V = (torch.from_numpy(inp[k]).to(dev) for k in ("Q", "K", "V"))
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    layers[0].prefill(Q, K, V, out=None)
+    e1.record(); torch.cuda.synchronize()
+    prefill_ms = e0.elapsed_time(e1)
+    log(f"[bench] lessdec_prefill P={w.prompt}: {prefill_ms:.1f} ms")
+    del Q, K, V
+    names = ("k_cache", "v_cache", "acc", "pos", "psi", "H", "z", "n_seen")
+    for lay in layers[1:]:
+        for n in names:
+            getattr(lay, n).copy_(getattr(layers[0], n))
+    q, k, v = (torch.from_numpy(inp[n]).to(dev) for n in ("q", "k", "v"))      # [T,U,D]
+    del inp
+    outs = [torch.empty((U, D), dtype=layers[0].tdtype, device=dev) for _ in range(L)]
+    torch.cuda.synchronize()
+
+    def run(first, count):
+        for i in range(first, first + count):
+            lay = i % L
+            t = ((i // L) + 37 * lay) % T           # every layer walks the token axis at its own offset
+            layers[lay].step(q[t], k[t], v[t], outs[lay])
+
+    run(0, args.warmup)
+    torch.cuda.synchronize()
+    stream = torch.cuda.current_stream()
+    e0.record(stream)
+    run(args.warmup, args.steps)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1)
+    ms_per_step = ms / args.steps
+    unit_steps_per_s = U * args.steps / (ms * 1e-3)
+    bytes_per_step = algorithmic_bytes_per_unit_step(w) * U
+    achieved = bytes_per_step / (ms_per_step * 1e-3) / 1e9
+
+    result = {
+        "metric": "decode steps/sec (batch x heads), Llama-2-7B attention shape",
+        "value": unit_steps_per_s,
+        "unit": "unit-steps/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "steps_per_s": 1e3 / ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16 storage, f64 scores / f32 values",
+        "data": "synthetic",
+        "config": {"workload": f"cfg{w.cfg} {w.name}: batch {w.batch} x heads {w.heads} x head_dim {D}, "
+                               f"prompt {w.prompt}, {w.n_heavy}+{w.n_recent} slots, rank {w.rank}, hidden {w.hidden}",
+                   "layers_cycled": L, "prefill_ms": prefill_ms},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "bytes_per_launch": bytes_per_step,
+                     "kv_only_frac": 2 * w.capacity * D * (2 if w.dtype == "f16" else 4) * U
+                                     / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS},
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(w, min(args.cpu_units, U), min(args.cpu_steps, T))
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()
