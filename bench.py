@@ -85,7 +85,7 @@ def main():
 
     import numpy as np
     import torch
-    from paper_2402_09398_amd import LessDec, workloads as wl
+    from paper_2402_09398_amd import LessDec, pack_weights, workloads as wl
 
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
@@ -97,7 +97,7 @@ def main():
     t0 = time.perf_counter()
     inp = wl.all_inputs(w, workers=16)
     log(f"[bench] inputs for {U} units generated in {time.perf_counter() - t0:.1f} s")
-    W = {k: torch.from_numpy(v).to(dev) for k, v in wl.head_weights(w).items()}
+    W = pack_weights(wl.head_weights(w), dev)
     layers = [LessDec(w.batch, w.heads, D, w.n_heavy, w.n_recent, w.rank, w.hidden, w.dtype, W,
                       max_prompt=w.prompt if i == 0 else 0, device=dev) for i in range(L)]
     Q, K, V = (torch.from_numpy(inp[k]).to(dev) for k in ("Q", "K", "V"))

@@ -69,9 +69,12 @@ typedef struct lessdec_desc {
   float *H;                       /* [B,Hh,R,D]                                            */
   double *z;                      /* [B,Hh,R]                                              */
   int32_t *n_seen;                /* [B,Hh] tokens seen so far by each unit                */
-  /* feature-map weights, per head (Eq. 1, Eq. 2), row-major, dtype                        */
-  const void *Wq1, *Wq2;          /* phi: [Hh,D,R'], [Hh,R',R]                             */
-  const void *Wk1, *Wk2, *Wk3;    /* psi: [Hh,D,R'], [Hh,R',R], [Hh,R,R]                   */
+  /* feature-map weights, per head (Eq. 1, Eq. 2), dtype, stored output-major like a linear
+     layer's weight: row i of W?1 holds the D input weights of hidden unit i, i.e. each
+     array is the transpose of the matrix of the same name in the equations.  16-byte
+     aligned.                                                                              */
+  const void *Wq1, *Wq2;          /* phi: [Hh,R',D], [Hh,R,R']                             */
+  const void *Wk1, *Wk2, *Wk3;    /* psi: [Hh,R',D], [Hh,R,R'], [Hh,R,R]                   */
   void *workspace;                /* >= lessdec_workspace_bytes(), 256-byte aligned        */
   size_t workspace_bytes;
 } lessdec_desc;

@@ -105,12 +105,22 @@ def lessdec_step(desc: Desc, q, k, v, out, evicted_pos=None, stream=None):
                               _stream(stream)), "lessdec_step")
 
 
+def pack_weights(weights, device="cuda:0"):
+    """Equation-layout numpy weights (Wq1 [Hh,D,R'], Wq2 [Hh,R',R], Wk1, Wk2, Wk3 [Hh,R,R])
+    to the library's output-major device tensors ([Hh,R',D], [Hh,R,R'], [Hh,R,R])."""
+    import numpy as np
+    import torch
+    return {k: torch.from_numpy(np.ascontiguousarray(np.swapaxes(v, 1, 2))).to(device)
+            for k, v in weights.items()}
+
+
 class LessDec:
     """Owns the device buffers of one attention layer's state and its descriptor.
 
     Plumbing only: allocation with torch, pointer marshalling, no arithmetic.
-    weights: dict of torch tensors on the device, Wq1 [Hh,D,R'], Wq2 [Hh,R',R],
-    Wk1 [Hh,D,R'], Wk2 [Hh,R',R], Wk3 [Hh,R,R], in the storage dtype.
+    weights: dict of torch tensors on the device in the library's output-major layout,
+    Wq1 [Hh,R',D], Wq2 [Hh,R,R'], Wk1 [Hh,R',D], Wk2 [Hh,R,R'], Wk3 [Hh,R,R], storage dtype
+    (see pack_weights).
     """
 
     def __init__(self, batch, heads, head_dim, n_heavy, n_recent, rank, hidden, dtype, weights,
@@ -136,8 +146,8 @@ class LessDec:
         self.z = torch.zeros((U, R), dtype=torch.float64, device=dev)
         self.n_seen = torch.zeros((U,), dtype=torch.int32, device=dev)
         self.W = {}
-        for name, shape in (("Wq1", (heads, D, hidden)), ("Wq2", (heads, hidden, R)),
-                            ("Wk1", (heads, D, hidden)), ("Wk2", (heads, hidden, R)),
+        for name, shape in (("Wq1", (heads, hidden, D)), ("Wq2", (heads, R, hidden)),
+                            ("Wk1", (heads, hidden, D)), ("Wk2", (heads, R, hidden)),
                             ("Wk3", (heads, R, R))):
             w = weights[name]
             if tuple(w.shape) != shape or w.dtype != self.tdtype or w.device != self.k_cache.device:

@@ -110,13 +110,23 @@ int lessdec_step(const lessdec_desc *desc, const void *q, const void *k, const v
   double *f_phi = reinterpret_cast<double *>(ws + w.off_fphi);
   float *psi_new = reinterpret_cast<float *>(ws + w.off_psinew);
 
-  FeatmapArgs fa;
-  fa.B = desc->batch; fa.Hh = desc->heads; fa.rpu = 1;
-  fa.D = desc->head_dim; fa.Rp = desc->hidden; fa.R = desc->rank;
-  fa.x = q; fa.W1 = desc->Wq1; fa.W2 = desc->Wq2; fa.W3 = nullptr; fa.out = f_phi; fa.out_f64 = 1;
-  if (launch_featmap_generic(fa, desc->dtype, st) != hipSuccess) return LESSDEC_EHIP;
-  fa.x = k; fa.W1 = desc->Wk1; fa.W2 = desc->Wk2; fa.W3 = desc->Wk3; fa.out = psi_new; fa.out_f64 = 0;
-  if (launch_featmap_generic(fa, desc->dtype, st) != hipSuccess) return LESSDEC_EHIP;
+  if (featmap_mfma_supported(desc->dtype, desc->head_dim, desc->hidden, desc->rank)) {
+    FeatmapMfmaArgs fm;
+    fm.B = desc->batch; fm.Hh = desc->heads; fm.rpu = 1;
+    fm.D = desc->head_dim; fm.Rp = desc->hidden; fm.R = desc->rank; fm.nchunk = 0;
+    fm.map[0] = {(const __half *)q, (const __half *)desc->Wq1, (const __half *)desc->Wq2, nullptr, f_phi, 1};
+    fm.map[1] = {(const __half *)k, (const __half *)desc->Wk1, (const __half *)desc->Wk2,
+                 (const __half *)desc->Wk3, psi_new, 0};
+    if (launch_featmap_mfma(fm, 2, st) != hipSuccess) return LESSDEC_EHIP;
+  } else {
+    FeatmapArgs fa;
+    fa.B = desc->batch; fa.Hh = desc->heads; fa.rpu = 1;
+    fa.D = desc->head_dim; fa.Rp = desc->hidden; fa.R = desc->rank;
+    fa.x = q; fa.W1 = desc->Wq1; fa.W2 = desc->Wq2; fa.W3 = nullptr; fa.out = f_phi; fa.out_f64 = 1;
+    if (launch_featmap_generic(fa, desc->dtype, st) != hipSuccess) return LESSDEC_EHIP;
+    fa.x = k; fa.W1 = desc->Wk1; fa.W2 = desc->Wk2; fa.W3 = desc->Wk3; fa.out = psi_new; fa.out_f64 = 0;
+    if (launch_featmap_generic(fa, desc->dtype, st) != hipSuccess) return LESSDEC_EHIP;
+  }
 
   StepArgs a;
   a.C = (int)s.C; a.Nh = desc->n_heavy; a.Nr = desc->n_recent; a.R = desc->rank;

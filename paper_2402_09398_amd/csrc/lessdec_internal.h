@@ -1,6 +1,7 @@
 // Host-side launch interfaces between the C ABI (lessdec_api.hip) and the kernel files.
 #pragma once
 
+#include <hip/hip_fp16.h>
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -19,6 +20,21 @@ struct FeatmapArgs {
   int D, Rp, R;
 };
 hipError_t launch_featmap_generic(const FeatmapArgs &a, int dtype, hipStream_t st);
+
+// Matrix-core feature maps (fp16 storage): up to two maps (phi of q and psi of k) in one
+// launch, same row-to-unit convention as above.
+struct FeatmapMfmaArgs {
+  struct Map {
+    const __half *x, *W1, *W2, *W3;   // W3 == NULL: Eq. 1, else Eq. 2
+    void *out;
+    int out_f64;
+  };
+  Map map[2];
+  int B, Hh, rpu, D, Rp, R;
+  int nchunk;                           // set by the launcher
+};
+bool featmap_mfma_supported(int dtype, int D, int Rp, int R);
+hipError_t launch_featmap_mfma(FeatmapMfmaArgs a, int n_maps, hipStream_t st);
 
 struct StepArgs {
   int C, Nh, Nr, R;

@@ -333,10 +333,20 @@ static hipError_t launch_prefill_t(const PrefillArgs &a, hipStream_t st)
   if ((e = hipGetLastError()) != hipSuccess) return e;
   prefill_select_kernel<<<U, 256, 0, st>>>(a.colsum, P, d->n_heavy, d->n_recent, a.slot_of);
   if ((e = hipGetLastError()) != hipSuccess) return e;
-  FeatmapArgs fa;
-  fa.x = a.K; fa.W1 = d->Wk1; fa.W2 = d->Wk2; fa.W3 = d->Wk3; fa.out = a.psi_all; fa.out_f64 = 0;
-  fa.B = d->batch; fa.Hh = d->heads; fa.rpu = P; fa.D = d->head_dim; fa.Rp = d->hidden; fa.R = d->rank;
-  if ((e = launch_featmap_generic(fa, d->dtype, st)) != hipSuccess) return e;
+  if (featmap_mfma_supported(d->dtype, d->head_dim, d->hidden, d->rank)) {
+    FeatmapMfmaArgs fm;
+    fm.B = d->batch; fm.Hh = d->heads; fm.rpu = P; fm.D = d->head_dim; fm.Rp = d->hidden; fm.R = d->rank;
+    fm.nchunk = 0;
+    fm.map[0] = {(const __half *)a.K, (const __half *)d->Wk1, (const __half *)d->Wk2,
+                 (const __half *)d->Wk3, a.psi_all, 0};
+    fm.map[1] = fm.map[0];
+    if ((e = launch_featmap_mfma(fm, 1, st)) != hipSuccess) return e;
+  } else {
+    FeatmapArgs fa;
+    fa.x = a.K; fa.W1 = d->Wk1; fa.W2 = d->Wk2; fa.W3 = d->Wk3; fa.out = a.psi_all; fa.out_f64 = 0;
+    fa.B = d->batch; fa.Hh = d->heads; fa.rpu = P; fa.D = d->head_dim; fa.Rp = d->hidden; fa.R = d->rank;
+    if ((e = launch_featmap_generic(fa, d->dtype, st)) != hipSuccess) return e;
+  }
   prefill_finalize_kernel<T, D><<<U, 256, 0, st>>>(
       (const T *)a.K, (const T *)a.V, P, a.colsum, a.slot_of, a.psi_all, C, d->rank, (T *)d->k_cache,
       (T *)d->v_cache, d->acc, d->pos, d->psi, d->H, d->z, d->n_seen);

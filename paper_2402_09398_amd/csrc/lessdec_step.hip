@@ -1,157 +1,225 @@
-// Decode-step kernels: feature maps of the step's q and k (Eq. 1, Eq. 2) and the fused
-// attention / score-accumulate / evict / state-update kernel (Algorithm 1, Eq. 3-5).
+// Decode step (Algorithm 1): feature maps of the step's q and k on the matrix cores, and
+// the fused attention / score-accumulate / evict / state-update kernel (Eq. 3-5).
 #include "lessdec_common.h"
 #include "lessdec_internal.h"
 
 namespace lessdec {
 
-// =====================================================================================
-// Feature maps, generic path: any D, R', R, either storage type, fp64 accumulation in the
-// oracle's summation order.  One block evaluates TM rows that share a head, so the
-// head's weights are read once per TM rows.
-//   x    : rows of D values; row (u * rpu + p) belongs to unit u = b * Hh + h
-//   out  : [rows, R] as double (out_f64) or float
-//   W3   : NULL for phi (Eq. 1), the R x R matrix for psi (Eq. 2)
-// grid = Hh * ceil(B * rpu / TM) (head fastest), block = 256, dynamic LDS = TM * (D + R' + R) doubles
-// =====================================================================================
-template <typename T, int TM>
-__global__ __launch_bounds__(256) void featmap_generic_kernel(
-    const T *__restrict__ x, const T *__restrict__ W1, const T *__restrict__ W2,
-    const T *__restrict__ W3, void *__restrict__ out, int out_f64, int B, int Hh, int rpu, int D,
-    int Rp, int R)
-{
-  extern __shared__ double sm[];
-  double *xs = sm;                 // [TM][D]
-  double *hs = xs + TM * D;        // [TM][Rp]
-  double *h2 = hs + TM * Rp;       // [TM][R]
-  const int h = blockIdx.x % Hh;
-  const long rows_head = (long)B * rpu;
-  const long i0 = (long)(blockIdx.x / Hh) * TM;
-  const int tid = threadIdx.x;
-  const T *W1h = W1 + (size_t)h * D * Rp;
-  const T *W2h = W2 + (size_t)h * Rp * R;
+typedef _Float16 v8h __attribute__((ext_vector_type(8)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef unsigned int u4v __attribute__((ext_vector_type(4)));
 
-  auto global_row = [&](long i) -> long {   // i-th row of this head -> row in x / out
-    long b = i / rpu, p = i % rpu;
-    return (b * Hh + h) * (long)rpu + p;
+// =====================================================================================
+// Feature maps on the matrix cores (fp16 storage only).
+//
+// One block of 4 waves evaluates 16 rows that share a head.  Layer 1 (the only real
+// contraction: 16 x D times D x R') runs on v_mfma_f32_16x16x32_f16 with M = hidden
+// units, N = rows: lane (kg, i) = (lane / 16, lane % 16) supplies 8 consecutive k of
+// matrix row i, result register w of lane (g, c) is element [4 g + w][c].  fp16 x fp16
+// products are exact in fp32, so only the fp32 accumulation rounds.  Wave w owns the
+// hidden units [w R'/4, (w+1) R'/4).  GELU is applied in registers and layer 2
+// (R' x R, R <= 16) is accumulated in fp64 straight from the MFMA result layout, so the
+// hidden activations never leave the registers; partial sums of the 4 waves meet in LDS.
+//
+// grid = n_maps * Hh * ceil(B * rpu / 16), head fastest (so that with Hh a multiple of 8
+// all blocks of a head land on one XCD and share its L2 copy of the weights); block 256.
+// =====================================================================================
+template <int D>
+__global__ __launch_bounds__(256) void featmap_mfma_kernel(const FeatmapMfmaArgs a)
+{
+  constexpr int KS = D / 32;                      // MFMA k-steps
+  __shared__ double s_red[4][16][16];             // [wave][row][r]
+  __shared__ double s_h2[16][16];
+  const int tid = threadIdx.x, wave = tid / 64, l = tid % 64, g = l / 16, c = l % 16;
+  const int Hh = a.Hh, Rp = a.Rp, R = a.R;
+  const int per_map = Hh * a.nchunk;
+  const int map = blockIdx.x / per_map;           // 0: first map in the args, 1: second
+  const int rem = blockIdx.x % per_map;
+  const int h = rem % Hh, chunk = rem / Hh;
+  const FeatmapMfmaArgs::Map mp = a.map[map];
+  const __half *W1 = mp.W1 + (size_t)h * Rp * D;
+  const __half *W2 = mp.W2 + (size_t)h * R * Rp;
+  const long rows_head = (long)a.B * a.rpu;
+  auto global_row = [&](long i) -> long {
+    long b = i / a.rpu, p = i % a.rpu;
+    return (b * Hh + h) * (long)a.rpu + p;
   };
 
-  for (int idx = tid; idx < TM * D; idx += 256) {
-    int m = idx / D, d = idx % D;
-    long i = i0 + m;
-    xs[idx] = (i < rows_head) ? (double)Store<T>::to_float(x[global_row(i) * D + d]) : 0.0;
-  }
-  __syncthreads();
-
-  for (int i = tid; i < Rp; i += 256) {
-    double a[TM];
+  // B operand: this lane's row (c) of x, k = 32 ks + 8 g .. + 8
+  v8h bx[KS];
+  {
+    const long i = (long)chunk * 16 + c;
+    if (i < rows_head) {
+      const __half *xr = mp.x + global_row(i) * D;
 #pragma unroll
-    for (int m = 0; m < TM; ++m) a[m] = 0.0;
-    for (int d = 0; d < D; ++d) {
-      double w = (double)Store<T>::to_float(W1h[(size_t)d * Rp + i]);
-#pragma unroll
-      for (int m = 0; m < TM; ++m) a[m] = fma(xs[m * D + d], w, a[m]);
-    }
-#pragma unroll
-    for (int m = 0; m < TM; ++m) hs[m * Rp + i] = gelu_f64(a[m]);
-  }
-  __syncthreads();
-
-  for (int pr = tid; pr < TM * R; pr += 256) {
-    int m = pr / R, r = pr % R;
-    double a = 0.0;
-    for (int i = 0; i < Rp; ++i)
-      a = fma(hs[m * Rp + i], (double)Store<T>::to_float(W2h[(size_t)i * R + r]), a);
-    h2[pr] = gelu_f64(a);
-  }
-  __syncthreads();
-
-  for (int pr = tid; pr < TM * R; pr += 256) {
-    int m = pr / R, r = pr % R;
-    long i = i0 + m;
-    if (i >= rows_head) continue;
-    double g;
-    if (W3 == nullptr) {
-      g = fabs(h2[pr]);
+      for (int ks = 0; ks < KS; ++ks) bx[ks] = *reinterpret_cast<const v8h *>(xr + 32 * ks + 8 * g);
     } else {
-      const T *W3h = W3 + (size_t)h * R * R;
-      double a = 0.0;
-      for (int j = 0; j < R; ++j)
-        a = fma(h2[m * R + j], (double)Store<T>::to_float(W3h[(size_t)j * R + r]), a);
-      g = fabs(a);
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) bx[ks] = v8h{0, 0, 0, 0, 0, 0, 0, 0};
     }
-    size_t o = (size_t)global_row(i) * R + r;
-    if (out_f64) reinterpret_cast<double *>(out)[o] = g;
-    else reinterpret_cast<float *>(out)[o] = (float)g;
+  }
+  double part[16];
+#pragma unroll
+  for (int r = 0; r < 16; ++r) part[r] = 0.0;
+
+  const int HW = Rp / 4;                          // hidden units of this wave (multiple of 16)
+  const int hid0 = wave * HW;
+  for (int mt = 0; mt < HW / 16; ++mt) {
+    const __half *w1r = W1 + (size_t)(hid0 + 16 * mt + c) * D + 8 * g;
+    v4f acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      const v8h av = *reinterpret_cast<const v8h *>(w1r + 32 * ks);
+      acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, bx[ks], acc, 0, 0, 0);
+    }
+    // acc[w] = pre-activation of hidden unit hid0 + 16 mt + 4 g + w for row c
+    double gl[4];
+#pragma unroll
+    for (int w = 0; w < 4; ++w) gl[w] = (double)gelu_f32(acc[w]);
+    const __half *w2p = W2 + hid0 + 16 * mt + 4 * g;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      if (r < R) {
+        const uint2 raw = *reinterpret_cast<const uint2 *>(w2p + (size_t)r * Rp);
+        const __half *wh = reinterpret_cast<const __half *>(&raw);
+#pragma unroll
+        for (int w = 0; w < 4; ++w) part[r] = fma(gl[w], (double)__half2float(wh[w]), part[r]);
+      }
+    }
+  }
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    part[r] += __shfl_xor(part[r], 16);
+    part[r] += __shfl_xor(part[r], 32);
+  }
+  if (g == 0) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s_red[wave][c][r] = part[r];
+  }
+  __syncthreads();
+  // one thread per (row, r)
+  const int row = tid / 16, r = tid % 16;
+  const long i = (long)chunk * 16 + row;
+  double val = 0.0;
+  if (r < R) val = gelu_f64(((s_red[0][row][r] + s_red[1][row][r]) + s_red[2][row][r]) + s_red[3][row][r]);
+  if (mp.W3 != nullptr) {                          // psi: one more R x R matrix, no activation (Eq. 2)
+    s_h2[row][r] = val;
+    __syncthreads();
+    if (r < R) {
+      const __half *W3 = mp.W3 + ((size_t)h * R + r) * R;
+      double acc3 = 0.0;
+      for (int j = 0; j < R; ++j) acc3 = fma(s_h2[row][j], (double)__half2float(W3[j]), acc3);
+      val = acc3;
+    }
+  }
+  if (r < R && i < rows_head) {
+    const size_t o = (size_t)global_row(i) * R + r;
+    if (mp.out_f64) reinterpret_cast<double *>(mp.out)[o] = fabs(val);
+    else reinterpret_cast<float *>(mp.out)[o] = (float)fabs(val);
   }
 }
 
-template <typename T>
-static hipError_t launch_featmap_generic_t(const FeatmapArgs &a, hipStream_t st)
+bool featmap_mfma_supported(int dtype, int D, int Rp, int R)
+{
+  return dtype == LESSDEC_DTYPE_F16 && (D == 64 || D == 128) && Rp % 64 == 0 && Rp >= 64 && R <= 16;
+}
+
+hipError_t launch_featmap_mfma(FeatmapMfmaArgs a, int n_maps, hipStream_t st)
 {
   const long rows_head = (long)a.B * a.rpu;
-  if (a.Rp <= 512) {
-    constexpr int TM = 8;
-    const unsigned grid = (unsigned)(a.Hh * ((rows_head + TM - 1) / TM));
-    size_t lds = sizeof(double) * TM * (size_t)(a.D + a.Rp + a.R);
-    featmap_generic_kernel<T, TM><<<grid, 256, lds, st>>>(
-        (const T *)a.x, (const T *)a.W1, (const T *)a.W2, (const T *)a.W3, a.out, a.out_f64, a.B,
-        a.Hh, a.rpu, a.D, a.Rp, a.R);
-  } else {
-    constexpr int TM = 2;
-    const unsigned grid = (unsigned)(a.Hh * ((rows_head + TM - 1) / TM));
-    size_t lds = sizeof(double) * TM * (size_t)(a.D + a.Rp + a.R);
-    featmap_generic_kernel<T, TM><<<grid, 256, lds, st>>>(
-        (const T *)a.x, (const T *)a.W1, (const T *)a.W2, (const T *)a.W3, a.out, a.out_f64, a.B,
-        a.Hh, a.rpu, a.D, a.Rp, a.R);
-  }
+  a.nchunk = (int)((rows_head + 15) / 16);
+  const unsigned grid = (unsigned)((long)n_maps * a.Hh * a.nchunk);
+  if (a.D == 128) featmap_mfma_kernel<128><<<grid, 256, 0, st>>>(a);
+  else featmap_mfma_kernel<64><<<grid, 256, 0, st>>>(a);
   return hipGetLastError();
-}
-
-hipError_t launch_featmap_generic(const FeatmapArgs &a, int dtype, hipStream_t st)
-{
-  return dtype == LESSDEC_DTYPE_F16 ? launch_featmap_generic_t<__half>(a, st)
-                                    : launch_featmap_generic_t<float>(a, st);
 }
 
 // =====================================================================================
 // Fused step kernel: one block of 256 threads per unit.
 //
-// Phase 1  scores s_j = q . K_j / sqrt(D) of the live slots and of the appended key, fp64.
-//          A cache row is D * sizeof(T) bytes = LPR lanes of 16 bytes; the block reads
-//          256 / LPR rows per iteration with fully coalesced 16-byte loads.
-// Phase 2  one thread per row: shift, exponentials, denominator of Eq. 3 including
-//          phi(q) z^T, probabilities, H2O score accumulation, eviction argmin.
-// Phase 3  p . V in fp32 with the same row mapping as phase 1.
+// A cache row is D * sizeof(T) bytes = LPR lanes of 16 bytes; the block covers RPB =
+// 256 / LPR rows per iteration with fully coalesced 16-byte loads.  With NIT > 0 every K
+// and V row of the unit is requested at kernel entry (NIT loads of each per thread,
+// non-temporal: a row is not touched again before the same layer's next token), so the
+// memory system sees the whole unit at once; NIT = 0 is the looped form for any capacity.
+//
+// Phase 1  all waves: scores s_j = q . K_j / sqrt(D) of the live slots and of the appended
+//          key, fp64, reduced over the LPR lanes of a row.
+// Phase 2  wave 0, one lane per row: shift, exponentials, the denominator of Eq. 3 with
+//          phi(q) z^T, probabilities, H2O score accumulation, eviction argmin (Sec. 2.1),
+//          all by wave shuffles.
+// Phase 3  all waves: p . V in fp32 with the row mapping of phase 1.
 // Phase 4  one thread per column: out = p V + phi(q) H / den (Eq. 3), H += psi_e^T v_e,
-//          z += psi_e (Eq. 4, Eq. 5), new pair written into the freed slot.
+//          z += psi_e (Eq. 4, Eq. 5), the new pair written into the freed slot (Sec. 3.2).
 // =====================================================================================
-template <typename T, int D>
-__global__ __launch_bounds__(256) void step_kernel(const StepArgs a)
+// Adds to x the value of another lane of its 16-lane DPP row (both halves of the double).
+#define LESSDEC_DPP_ADD(x, ctrl)                                                         \
+  do {                                                                                   \
+    int lo_ = __double2loint(x), hi_ = __double2hiint(x);                                \
+    lo_ = __builtin_amdgcn_update_dpp(0, lo_, (ctrl), 0xf, 0xf, true);                   \
+    hi_ = __builtin_amdgcn_update_dpp(0, hi_, (ctrl), 0xf, 0xf, true);                   \
+    (x) += __hiloint2double(hi_, lo_);                                                   \
+  } while (0)
+
+__device__ inline double dpp_sum16(double v)
 {
-  constexpr int kThreads = 256, kWaves = kThreads / kWave;
+  // sum over the 16 lanes of a DPP row; every lane ends with the total
+  LESSDEC_DPP_ADD(v, 0xB1);    // quad_perm [1,0,3,2]
+  LESSDEC_DPP_ADD(v, 0x4E);    // quad_perm [2,3,0,1]
+  LESSDEC_DPP_ADD(v, 0x124);   // row_ror 4: the quad four lanes over
+  LESSDEC_DPP_ADD(v, 0x128);   // row_ror 8: the pair of quads eight lanes over
+  return v;
+}
+
+template <int LPR>
+__device__ inline double row_sum(double v)
+{
+  if constexpr (LPR == 16) {
+    return dpp_sum16(v);
+  } else {
+#pragma unroll
+    for (int o = LPR / 2; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+  }
+}
+
+template <typename T>
+__device__ inline typename Store<T>::Vec load_vec_nt(const T *p)
+{
+  typename Store<T>::Vec v;
+  const u4v t = __builtin_nontemporal_load(reinterpret_cast<const u4v *>(p));
+  __builtin_memcpy(&v.raw, &t, 16);
+  return v;
+}
+
+// Waves per SIMD the register allocation aims for: the K and V rows held in registers grow
+// with NIT (8 VGPRs per iteration), the rest of the kernel needs about 70.
+constexpr int step_waves_per_simd(int nit) { return nit == 0 ? 6 : nit <= 2 ? 5 : nit <= 7 ? 3 : nit <= 11 ? 2 : 1; }
+
+template <typename T, int D, int NIT>
+__global__ __launch_bounds__(256, step_waves_per_simd(NIT)) void step_unit_kernel(const StepArgs a)
+{
+  constexpr int kThreads = 256;
   constexpr int EPL = Store<T>::kPerVec;   // elements per lane
   constexpr int LPR = D / EPL;             // lanes per row
   constexpr int RPB = kThreads / LPR;      // rows per block iteration
+  constexpr int NBUF = NIT > 0 ? NIT : 1;
   static_assert(LPR >= 8 && LPR <= 32, "row must span 8..32 lanes");
+  using Vec = typename Store<T>::Vec;
 
   extern __shared__ double dyn[];
   const int C = a.C;
-  double *s_sc = dyn;                                        // [C+1] scores, then e_j, then new acc
+  double *s_sc = dyn;                                        // [C+1] scores
   float *s_p = reinterpret_cast<float *>(dyn + (C + 1));     // [C+1] probabilities (fp32)
-  __shared__ double s_red[kWaves];
-  __shared__ Cand s_cand[kWaves];
-  __shared__ float s_o[kWaves][D];
+  __shared__ float s_o[RPB * D];                             // per row-group partial outputs
   __shared__ float s_psie[LESSDEC_MAX_RANK];
+  __shared__ double s_lscale;
+  __shared__ int s_eslot;
 
   const int u = blockIdx.x;
-  const int tid = threadIdx.x;
+  const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
   const int lr = tid % LPR, rb = tid / LPR;
   const int R = a.R;
-  const int n = a.n_seen[u];
-  const int m = n < C ? n : C;          // live slots are 0..m-1 (slots fill in order)
-  const int rows = m + 1;               // + the appended pair (K', V' of Eq. 3)
-  const bool full = (m == C);
 
   const T *kc = reinterpret_cast<const T *>(a.k_cache) + (size_t)u * C * D;
   const T *vc = reinterpret_cast<const T *>(a.v_cache) + (size_t)u * C * D;
@@ -159,124 +227,217 @@ __global__ __launch_bounds__(256) void step_kernel(const StepArgs a)
   const T *kn = reinterpret_cast<const T *>(a.k) + (size_t)u * D;
   const T *vn = reinterpret_cast<const T *>(a.v) + (size_t)u * D;
 
+  // ---- everything that does not depend on the step's decisions is requested first ------
+  const Vec qv = load_vec<T>(qn + lr * EPL);
+  const Vec knv = load_vec<T>(kn + lr * EPL);
+  const Vec vnv = load_vec<T>(vn + lr * EPL);
+  Vec kbuf[NBUF], vbuf[NBUF];
+  if constexpr (NIT > 0) {
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+      const int r = it * RPB + rb;
+      if (r < C) kbuf[it] = load_vec_nt<T>(kc + (size_t)r * D + lr * EPL);
+    }
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+      const int r = it * RPB + rb;
+      if (r < C) vbuf[it] = load_vec_nt<T>(vc + (size_t)r * D + lr * EPL);
+    }
+  }
+  // wave 0 also owns one row per lane in phase 2: its accumulated score and position
+  constexpr int NR2 = NIT > 0 ? (NIT * RPB + kWave - 1) / kWave : 1;
+  double acc_pre[NR2];
+  int pos_pre[NR2];
+  double fz = 0.0;                       // this lane's term of phi(q) z^T
+  if (wave == 0) {
+    if constexpr (NIT > 0) {
+#pragma unroll
+      for (int i = 0; i < NR2; ++i) {
+        const int j = lane + i * kWave;
+        acc_pre[i] = (j < C) ? a.acc[(size_t)u * C + j] : 0.0;
+        pos_pre[i] = (j < C) ? a.pos[(size_t)u * C + j] : -1;
+      }
+    }
+    for (int r = lane; r < R; r += kWave) fz = fma(a.f_phi[(size_t)u * R + r], a.z[(size_t)u * R + r], fz);
+  }
+  const int n = a.n_seen[u];
+  const int m = n < C ? n : C;          // live slots are 0..m-1 (slots fill in order)
+  const int rows = m + 1;               // + the appended pair (K', V' of Eq. 3)
+  const bool full = (m == C);
+
   // ---- phase 1: scores ---------------------------------------------------------------
   {
     double qd[EPL];
-    auto qv = load_vec<T>(qn + lr * EPL);
 #pragma unroll
     for (int i = 0; i < EPL; ++i) qd[i] = (double)Store<T>::get(qv, i);
     const double sqrt_d = sqrt((double)D);
-    for (int r = rb; r < rows; r += RPB) {
-      const T *src = (r < m) ? kc + (size_t)r * D : kn;
-      auto kv = load_vec<T>(src + lr * EPL);
+    auto score_row = [&](int r, const Vec &kv) {
       double part = 0.0;
 #pragma unroll
       for (int i = 0; i < EPL; ++i) part = fma(qd[i], (double)Store<T>::get(kv, i), part);
+      part = row_sum<LPR>(part);
+      if (lr == 0 && r < rows) s_sc[r] = part / sqrt_d;
+    };
+    if constexpr (NIT > 0) {
 #pragma unroll
-      for (int o = LPR / 2; o > 0; o >>= 1) part += __shfl_xor(part, o);
-      if (lr == 0) s_sc[r] = part / sqrt_d;
+      for (int it = 0; it < NIT; ++it) {
+        const int r = it * RPB + rb;
+        score_row(r, r < m ? kbuf[it] : knv);     // r > m: computed on the new key, not stored
+        __builtin_amdgcn_sched_barrier(0);        // one row at a time: keeps the fp64 temporaries few
+      }
+    } else {
+      for (int r0 = 0; r0 < rows; r0 += RPB) {
+        const int r = r0 + rb;
+        Vec kv = knv;
+        if (r < m) kv = load_vec_nt<T>(kc + (size_t)r * D + lr * EPL);
+        score_row(r, kv);
+      }
+    }
+  }
+  // the key registers are free now: fetch this thread's column of H for phase 4
+  float hreg[16];
+  if (tid < D && R <= 16) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) hreg[r] = (r < R) ? a.H[((size_t)u * R + r) * D + tid] : 0.f;
+  }
+  __syncthreads();
+
+  // ---- phase 2 (wave 0): softmax pieces, H2O accumulation, eviction choice --------------
+  if (wave == 0) {
+    double M = -__builtin_inf();
+    for (int j = lane; j < rows; j += kWave) M = fmax(M, s_sc[j]);
+    M = wave_max(M);
+    double S = 0.0;
+    for (int j = lane; j < rows; j += kWave) {
+      const double e = exp(s_sc[j] - M);
+      s_sc[j] = e;
+      S += e;
+    }
+    S = wave_sum(S);                                      // sparse part of the denominator, shifted
+    fz = wave_sum(fz);                                    // phi(q) z^T
+    // den = phi(q) z^T + sum_j e^{s_j}, in whichever scaling cannot overflow:
+    //   M > 0 (or no low-rank term): everything times e^{-M};  M <= 0: unscaled, e^{M} <= 1
+    double pscale, lscale;
+    if (fz > 0.0 && M <= 0.0) {
+      const double w = exp(M);
+      const double den = fz + w * S;
+      pscale = w / den;
+      lscale = 1.0 / den;
+    } else {
+      const double eM = (fz > 0.0) ? exp(-M) : 0.0;
+      const double den = fz * eM + S;
+      pscale = 1.0 / den;
+      lscale = eM / den;
+    }
+    const double ascale = (a.flags & LESSDEC_FLAG_SPARSE_DENOM) ? 1.0 / S : pscale;
+
+    Cand best = cand_none();
+    for (int j = lane, i = 0; j < rows; j += kWave, ++i) {
+      const double e = s_sc[j];
+      s_p[j] = (float)(e * pscale);
+      double na = e * ascale;
+      int pj = n;
+      if (j < m) {
+        if constexpr (NIT > 0) {
+          na += acc_pre[i];
+          pj = pos_pre[i];
+        } else {
+          na += a.acc[(size_t)u * C + j];
+          pj = a.pos[(size_t)u * C + j];
+        }
+      }
+      s_sc[j] = na;
+      if (full) {
+        const bool is_cand = (j < m) ? (pj <= n - a.Nr) : (a.Nr == 0);
+        const Cand cnd{na, pj, j};
+        if (is_cand && cand_less(cnd, best)) best = cnd;
+      }
+    }
+    const Cand ev = wave_argmin(best);
+    const int eslot = full ? ev.slot : -1;                 // m means: the new pair itself
+    const bool evict = full && eslot >= 0;
+    const int ins_slot = full ? ((eslot >= 0 && eslot < m) ? eslot : -1) : m;
+    // accumulated scores and positions (each lane reads back only what it wrote to s_sc)
+    for (int j = lane; j < rows; j += kWave) {
+      if (j < m) {
+        if (j != ins_slot) a.acc[(size_t)u * C + j] = s_sc[j];
+      } else if (ins_slot >= 0) {
+        a.acc[(size_t)u * C + ins_slot] = s_sc[m];
+        a.pos[(size_t)u * C + ins_slot] = n;
+      }
+    }
+    if (evict && lane < R)
+      s_psie[lane] = (eslot < m) ? a.psi[((size_t)u * C + eslot) * R + lane] : a.psi_new[(size_t)u * R + lane];
+    if (lane == 0) {
+      s_lscale = lscale;
+      s_eslot = eslot;
+      if (a.evicted_pos) a.evicted_pos[u] = evict ? ev.pos : -1;
+      a.n_seen[u] = n + 1;
     }
   }
   __syncthreads();
 
-  // ---- phase 2: softmax pieces, H2O accumulation, eviction choice ----------------------
-  double lmax = -__builtin_inf();
-  for (int j = tid; j < rows; j += kThreads) lmax = fmax(lmax, s_sc[j]);
-  const double M = block_max<kWaves>(lmax, s_red);
-
-  double lsum = 0.0;
-  for (int j = tid; j < rows; j += kThreads) {
-    double e = exp(s_sc[j] - M);
-    s_sc[j] = e;
-    lsum += e;
-  }
-  const double S = block_sum<kWaves>(lsum, s_red);       // sparse part of the denominator, shifted
-
-  double fz = 0.0;                                        // phi(q) z^T
-  for (int r = 0; r < R; ++r) fz = fma(a.f_phi[(size_t)u * R + r], a.z[(size_t)u * R + r], fz);
-
-  // den = phi(q) z^T + sum_j e^{s_j}; evaluated in whichever scaling cannot overflow:
-  //   M > 0 (or no low-rank term): everything times e^{-M}
-  //   M <= 0 with a low-rank term: unscaled, e^{M} <= 1
-  double pscale, lscale;
-  if (fz > 0.0 && M <= 0.0) {
-    const double w = exp(M);
-    const double den = fz + w * S;
-    pscale = w / den;
-    lscale = 1.0 / den;
-  } else {
-    const double eM = (fz > 0.0) ? exp(-M) : 0.0;
-    const double den = fz * eM + S;
-    pscale = 1.0 / den;
-    lscale = eM / den;
-  }
-  const double ascale = (a.flags & LESSDEC_FLAG_SPARSE_DENOM) ? 1.0 / S : pscale;
-
-  Cand best = cand_none();
-  for (int j = tid; j < rows; j += kThreads) {
-    const double e = s_sc[j];
-    s_p[j] = (float)(e * pscale);
-    double na = e * ascale;
-    int pj = n;
-    if (j < m) {
-      na += a.acc[(size_t)u * C + j];
-      pj = a.pos[(size_t)u * C + j];
-    }
-    s_sc[j] = na;
-    if (full) {
-      const bool is_cand = (j < m) ? (pj <= n - a.Nr) : (a.Nr == 0);
-      Cand c{na, pj, j};
-      if (is_cand && cand_less(c, best)) best = c;
-    }
-  }
-  const Cand ev = block_argmin<kWaves>(best, s_cand);      // its barriers also publish s_sc / s_p
-  const int eslot = full ? ev.slot : -1;                   // m means: the new pair itself
-  const bool evict = full && eslot >= 0;
-  const int ins_slot = full ? ((eslot >= 0 && eslot < m) ? eslot : -1) : m;
-
-  // ---- phase 3: p . V, and staging of the discarded pair's psi --------------------------
-  if (evict && tid < R)
-    s_psie[tid] = (eslot < m) ? a.psi[((size_t)u * C + eslot) * R + tid] : a.psi_new[(size_t)u * R + tid];
+  // ---- phase 3: p . V -----------------------------------------------------------------------
   {
     float o[EPL];
 #pragma unroll
     for (int i = 0; i < EPL; ++i) o[i] = 0.f;
-    for (int r = rb; r < rows; r += RPB) {
-      const T *src = (r < m) ? vc + (size_t)r * D : vn;
-      auto vv = load_vec<T>(src + lr * EPL);
-      const float p = s_p[r];
+    auto pv_row = [&](int r, const Vec &vv) {
+      const float p = (r < rows) ? s_p[r] : 0.f;
 #pragma unroll
       for (int i = 0; i < EPL; ++i) o[i] = fmaf(p, Store<T>::get(vv, i), o[i]);
-    }
-    // rows of one wave: lanes lr, lr + LPR, ... hold the same columns
+    };
+    if constexpr (NIT > 0) {
 #pragma unroll
-    for (int i = 0; i < EPL; ++i) {
-#pragma unroll
-      for (int off = LPR; off < kWave; off <<= 1) o[i] += __shfl_xor(o[i], off);
+      for (int it = 0; it < NIT; ++it) {
+        const int r = it * RPB + rb;
+        pv_row(r, r < m ? vbuf[it] : vnv);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    } else {
+      for (int r0 = 0; r0 < rows; r0 += RPB) {
+        const int r = r0 + rb;
+        Vec vv = vnv;
+        if (r < m) vv = load_vec_nt<T>(vc + (size_t)r * D + lr * EPL);
+        pv_row(r, vv);
+      }
     }
-    if ((tid & (kWave - 1)) < LPR) {
 #pragma unroll
-      for (int i = 0; i < EPL; ++i) s_o[tid / kWave][lr * EPL + i] = o[i];
-    }
+    for (int i = 0; i < EPL; ++i) s_o[rb * D + lr * EPL + i] = o[i];
   }
   __syncthreads();
 
   // ---- phase 4: output, state update, in-place insert -----------------------------------
   if (tid < D) {
     const int c = tid;
+    const int eslot = s_eslot;
+    const bool evict = full && eslot >= 0;
+    const int ins_slot = full ? ((eslot >= 0 && eslot < m) ? eslot : -1) : m;
     float pv = 0.f;
 #pragma unroll
-    for (int w = 0; w < kWaves; ++w) pv += s_o[w][c];
+    for (int gidx = 0; gidx < RPB; ++gidx) pv += s_o[gidx * D + c];
     float *Hu = a.H + (size_t)u * R * D;
     float fh = 0.f;
-    for (int r = 0; r < R; ++r) fh = fmaf((float)a.f_phi[(size_t)u * R + r], Hu[(size_t)r * D + c], fh);
-    const double o = (double)pv + lscale * (double)fh;
+    if (R <= 16) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        if (r < R) fh = fmaf((float)a.f_phi[(size_t)u * R + r], hreg[r], fh);
+    } else {
+      for (int r = 0; r < R; ++r) fh = fmaf((float)a.f_phi[(size_t)u * R + r], Hu[(size_t)r * D + c], fh);
+    }
+    const double o = (double)pv + s_lscale * (double)fh;
     reinterpret_cast<T *>(a.out)[(size_t)u * D + c] = Store<T>::from_float((float)o);
 
     if (evict) {
       const float ve = (eslot < m) ? Store<T>::to_float(vc[(size_t)eslot * D + c])
                                    : Store<T>::to_float(vn[c]);
-      for (int r = 0; r < R; ++r) Hu[(size_t)r * D + c] = fmaf(s_psie[r], ve, Hu[(size_t)r * D + c]);
+      if (R <= 16) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          if (r < R) Hu[(size_t)r * D + c] = fmaf(s_psie[r], ve, hreg[r]);
+      } else {
+        for (int r = 0; r < R; ++r) Hu[(size_t)r * D + c] = fmaf(s_psie[r], ve, Hu[(size_t)r * D + c]);
+      }
       if (c < R) a.z[(size_t)u * R + c] += (double)s_psie[c];
     }
     if (ins_slot >= 0) {
@@ -287,28 +448,19 @@ __global__ __launch_bounds__(256) void step_kernel(const StepArgs a)
       if (c < R) a.psi[((size_t)u * C + ins_slot) * R + c] = a.psi_new[(size_t)u * R + c];
     }
   }
-  // accumulated scores and positions
-  for (int j = tid; j < rows; j += kThreads) {
-    if (j < m) {
-      if (j != ins_slot) a.acc[(size_t)u * C + j] = s_sc[j];
-    } else {
-      int old = -1;
-      if (evict) old = (eslot < m) ? a.pos[(size_t)u * C + eslot] : n;
-      if (ins_slot >= 0) {
-        a.acc[(size_t)u * C + ins_slot] = s_sc[m];
-        a.pos[(size_t)u * C + ins_slot] = n;
-      }
-      if (a.evicted_pos) a.evicted_pos[u] = old;
-      a.n_seen[u] = n + 1;
-    }
-  }
 }
 
 template <typename T, int D>
 static hipError_t launch_step_t(const StepArgs &a, int units, hipStream_t st)
 {
-  size_t lds = (size_t)(a.C + 1) * (sizeof(double) + sizeof(float));
-  step_kernel<T, D><<<units, 256, lds, st>>>(a);
+  constexpr int RPB = 256 / (D / Store<T>::kPerVec);
+  const size_t lds = (size_t)(a.C + 1) * (sizeof(double) + sizeof(float));
+  const int need = (a.C + 1 + RPB - 1) / RPB;            // row iterations to cover C + 1 rows
+  if (need <= 2) step_unit_kernel<T, D, 2><<<units, 256, lds, st>>>(a);
+  else if (need <= 7) step_unit_kernel<T, D, 7><<<units, 256, lds, st>>>(a);
+  else if (need <= 11) step_unit_kernel<T, D, 11><<<units, 256, lds, st>>>(a);
+  else if (need <= 21) step_unit_kernel<T, D, 21><<<units, 256, lds, st>>>(a);
+  else step_unit_kernel<T, D, 0><<<units, 256, lds, st>>>(a);
   return hipGetLastError();
 }
 
@@ -318,33 +470,6 @@ hipError_t launch_step(const StepArgs &a, int units, int dtype, int D, hipStream
     return D == 128 ? launch_step_t<__half, 128>(a, units, st) : launch_step_t<__half, 64>(a, units, st);
   }
   return D == 128 ? launch_step_t<float, 128>(a, units, st) : launch_step_t<float, 64>(a, units, st);
-}
-
-// =====================================================================================
-// Reset: H = 0, z = 0, acc = 0, psi = 0, pos = -1, n_seen = 0 (fill kernels, so the call
-// can be recorded into a HIP graph).
-// =====================================================================================
-__global__ void reset_kernel(float *H, size_t nH, double *z, size_t nz, double *acc, size_t nacc,
-                             int32_t *pos, size_t npos, float *psi, size_t npsi, int32_t *n_seen,
-                             size_t nn)
-{
-  const size_t stride = (size_t)gridDim.x * blockDim.x;
-  const size_t t0 = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-  for (size_t i = t0; i < nH; i += stride) H[i] = 0.f;
-  for (size_t i = t0; i < nz; i += stride) z[i] = 0.0;
-  for (size_t i = t0; i < nacc; i += stride) acc[i] = 0.0;
-  for (size_t i = t0; i < npos; i += stride) pos[i] = -1;
-  for (size_t i = t0; i < npsi; i += stride) psi[i] = 0.f;
-  for (size_t i = t0; i < nn; i += stride) n_seen[i] = 0;
-}
-
-hipError_t launch_reset(const lessdec_desc *d, hipStream_t st)
-{
-  const size_t U = (size_t)d->batch * d->heads, C = (size_t)d->n_heavy + d->n_recent;
-  const size_t R = d->rank, D = d->head_dim;
-  reset_kernel<<<1024, 256, 0, st>>>(d->H, U * R * D, d->z, U * R, d->acc, U * C, d->pos, U * C,
-                                     d->psi, U * C * R, d->n_seen, U);
-  return hipGetLastError();
 }
 
 }  // namespace lessdec

@@ -74,9 +74,8 @@ def make_oracle(w, units, flags=0):
 
 
 def make_gpu(w, flags=0, max_prompt=None, device="cuda:0"):
-    import torch
-    from paper_2402_09398_amd import LessDec
-    W = {k: torch.from_numpy(v).to(device) for k, v in wl.head_weights(w).items()}
+    from paper_2402_09398_amd import LessDec, pack_weights
+    W = pack_weights(wl.head_weights(w), device)
     return LessDec(w.batch, w.heads, w.head_dim, w.n_heavy, w.n_recent, w.rank, w.hidden,
                    w.dtype, W, flags=flags, max_prompt=w.prompt if max_prompt is None else max_prompt,
                    device=device)
