@@ -109,9 +109,8 @@ def main():
     prefill_ms = e0.elapsed_time(e1)
     log(f"[bench] lessdec_prefill P={w.prompt}: {prefill_ms:.1f} ms")
     del Q, K, V
-    names = ("k_cache", "v_cache", "acc", "pos", "psi", "H", "z", "n_seen")
     for lay in layers[1:]:
-        for n in names:
+        for n in lay.STATE:
             getattr(lay, n).copy_(getattr(layers[0], n))
     q, k, v = (torch.from_numpy(inp[n]).to(dev) for n in ("q", "k", "v"))      # [T,U,D]
     del inp

@@ -11,8 +11,8 @@
  *    by the caller (the descriptor itself is a host struct).  The library allocates
  *    nothing, keeps no state between calls and never synchronises: all work is enqueued
  *    on the given HIP stream (`hip_stream` is a hipStream_t; NULL = the default stream).
- *  - All state of the method lives in the descriptor's buffers, so a checkpoint is a copy
- *    of them.  Calls on one descriptor must be stream-ordered; calls on different
+ *  - All state of the method lives in the descriptor's buffers (k_cache .. pend_psi), so a
+ *    checkpoint is a copy of them.  Calls on one descriptor must be stream-ordered; calls on different
  *    descriptors (different buffers) are independent.
  *  - Entry points return 0 on success and a negative LESSDEC_E* code otherwise.  Argument
  *    errors are detected on the host before anything is launched.  No C++ exception
@@ -69,6 +69,12 @@ typedef struct lessdec_desc {
   float *H;                       /* [B,Hh,R,D]                                            */
   double *z;                      /* [B,Hh,R]                                              */
   int32_t *n_seen;                /* [B,Hh] tokens seen so far by each unit                */
+  /* write-behind part of the state: lessdec_step leaves the fold of the pair it discarded
+     (Eq. 4, Eq. 5) to the head of the next step, where it costs no latency.  Until then the
+     pair is parked here; lessdec_state_sync folds it on request.                          */
+  int32_t *pend_slot;             /* [B,Hh] -1: nothing pending                            */
+  void *pend_v;                   /* [B,Hh,D] dtype, value row of the pending pair         */
+  float *pend_psi;                /* [B,Hh,R] psi of the last step's key                   */
   /* feature-map weights, per head (Eq. 1, Eq. 2), dtype, stored output-major like a linear
      layer's weight: row i of W?1 holds the D input weights of hidden unit i, i.e. each
      array is the transpose of the matrix of the same name in the equations.  16-byte
@@ -88,9 +94,17 @@ size_t lessdec_workspace_bytes(const lessdec_desc *desc, int32_t max_prompt);
 
 /*
  * Empty state: H_0 = 0, z_0 = 0 (Sec. 2.2), every slot empty (pos = -1, acc = 0, psi = 0),
- * n_seen = 0.  Must be called once before the first step on fresh buffers.
+ * n_seen = 0, nothing pending.  Must be called once before the first step on fresh buffers.
  */
 int lessdec_state_reset(const lessdec_desc *desc, void *hip_stream);
+
+/*
+ * Folds the pair that the last lessdec_step discarded into H and z (Eq. 4, Eq. 5) and puts
+ * the last key's psi into its slot, so that H, z and psi can be read as the state of
+ * Algorithm 1 after that step.  Optional: the next lessdec_step does the same fold itself,
+ * and its output is the same either way.  Nothing to do after reset or prefill.
+ */
+int lessdec_state_sync(const lessdec_desc *desc, void *hip_stream);
 
 /*
  * Prompt phase (remark after Eq. 3: with H_0 = z_0 = 0 it is regular attention).
@@ -117,8 +131,10 @@ int lessdec_prefill(const lessdec_desc *desc, const void *Q, const void *K, cons
  * phi(q) H and phi(q) z^T; adds each pair's probability to its accumulated score (the new
  * pair starts with its own); if the cache is full, discards the pair with the smallest
  * accumulated score among those not within the n_recent most recent tokens (the new one
- * counts as recent; ties discard the older), folds it into H, z and writes the new pair
- * into its slot; advances n_seen.
+ * counts as recent; ties discard the older), writes the new pair into its slot and leaves
+ * the discarded pair pending (see pend_slot); advances n_seen.  The fold of a pending pair
+ * from the previous step into H, z happens first, so Eq. 3 always sees the state Algorithm 1
+ * prescribes.
  */
 int lessdec_step(const lessdec_desc *desc, const void *q, const void *k, const void *v,
                  void *out, int32_t *evicted_pos, void *hip_stream);

@@ -17,7 +17,7 @@ DTYPE_F32, DTYPE_F16 = 0, 1
 FLAG_SPARSE_DENOM = 1
 OK, EINVAL, EWORKSPACE, EHIP = 0, -1, -2, -3
 
-EXPORTS = ("lessdec_workspace_bytes", "lessdec_state_reset", "lessdec_prefill", "lessdec_step",
+EXPORTS = ("lessdec_workspace_bytes", "lessdec_state_reset", "lessdec_state_sync", "lessdec_prefill", "lessdec_step",
            "lessdec_strerror", "lessdec_budget_tokens")
 
 
@@ -35,6 +35,7 @@ class Desc(C.Structure):
         ("k_cache", C.c_void_p), ("v_cache", C.c_void_p),
         ("acc", C.c_void_p), ("pos", C.c_void_p), ("psi", C.c_void_p),
         ("H", C.c_void_p), ("z", C.c_void_p), ("n_seen", C.c_void_p),
+        ("pend_slot", C.c_void_p), ("pend_v", C.c_void_p), ("pend_psi", C.c_void_p),
         ("Wq1", C.c_void_p), ("Wq2", C.c_void_p),
         ("Wk1", C.c_void_p), ("Wk2", C.c_void_p), ("Wk3", C.c_void_p),
         ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t),
@@ -56,6 +57,8 @@ def lib():
         L.lessdec_workspace_bytes.argtypes = [C.POINTER(Desc), C.c_int32]
         L.lessdec_state_reset.restype = C.c_int
         L.lessdec_state_reset.argtypes = [C.POINTER(Desc), C.c_void_p]
+        L.lessdec_state_sync.restype = C.c_int
+        L.lessdec_state_sync.argtypes = [C.POINTER(Desc), C.c_void_p]
         L.lessdec_prefill.restype = C.c_int
         L.lessdec_prefill.argtypes = [C.POINTER(Desc)] + [C.c_void_p] * 3 + [C.c_int32] + [C.c_void_p] * 2
         L.lessdec_step.restype = C.c_int
@@ -95,6 +98,10 @@ def lessdec_state_reset(desc: Desc, stream=None):
     _check(lib().lessdec_state_reset(C.byref(desc), _stream(stream)), "lessdec_state_reset")
 
 
+def lessdec_state_sync(desc: Desc, stream=None):
+    _check(lib().lessdec_state_sync(C.byref(desc), _stream(stream)), "lessdec_state_sync")
+
+
 def lessdec_prefill(desc: Desc, Q, K, V, P: int, out=None, stream=None):
     _check(lib().lessdec_prefill(C.byref(desc), _p(Q), _p(K), _p(V), int(P), _p(out),
                                  _stream(stream)), "lessdec_prefill")
@@ -123,6 +130,10 @@ class LessDec:
     (see pack_weights).
     """
 
+    # every buffer that makes up the state of the method (a checkpoint copies these)
+    STATE = ("k_cache", "v_cache", "acc", "pos", "psi", "H", "z", "n_seen",
+             "pend_slot", "pend_v", "pend_psi")
+
     def __init__(self, batch, heads, head_dim, n_heavy, n_recent, rank, hidden, dtype, weights,
                  flags=0, max_prompt=0, device="cuda:0"):
         import torch
@@ -145,6 +156,9 @@ class LessDec:
         self.H = torch.zeros((U, R, D), dtype=torch.float32, device=dev)
         self.z = torch.zeros((U, R), dtype=torch.float64, device=dev)
         self.n_seen = torch.zeros((U,), dtype=torch.int32, device=dev)
+        self.pend_slot = torch.full((U,), -1, dtype=torch.int32, device=dev)
+        self.pend_v = torch.zeros((U, D), dtype=self.tdtype, device=dev)
+        self.pend_psi = torch.zeros((U, R), dtype=torch.float32, device=dev)
         self.W = {}
         for name, shape in (("Wq1", (heads, hidden, D)), ("Wq2", (heads, R, hidden)),
                             ("Wk1", (heads, hidden, D)), ("Wk2", (heads, R, hidden)),
@@ -158,7 +172,7 @@ class LessDec:
         d.n_heavy, d.n_recent, d.rank, d.hidden = n_heavy, n_recent, rank, hidden
         d.dtype = DTYPE_F16 if self.tdtype == torch.float16 else DTYPE_F32
         d.flags = flags
-        for name in ("k_cache", "v_cache", "acc", "pos", "psi", "H", "z", "n_seen"):
+        for name in self.STATE:
             setattr(d, name, getattr(self, name).data_ptr())
         for name in self.W:
             setattr(d, name, self.W[name].data_ptr())
@@ -173,6 +187,9 @@ class LessDec:
 
     def state_reset(self, stream=None):
         lessdec_state_reset(self.desc, stream)
+
+    def state_sync(self, stream=None):
+        lessdec_state_sync(self.desc, stream)
 
     def prefill(self, Q, K, V, out=None, stream=None):
         """Q, K, V: [B*Hh, P, D] (or [B,Hh,P,D]) contiguous device tensors of the storage dtype."""

@@ -60,12 +60,14 @@ Workspace carve(const Shape &s, size_t P)
 int check_desc(const lessdec_desc *d, Shape *s, size_t P)
 {
   if (!shape_ok(d, s)) return LESSDEC_EINVAL;
-  if (!d->k_cache || !d->v_cache || !d->acc || !d->pos || !d->psi || !d->H || !d->z || !d->n_seen)
+  if (!d->k_cache || !d->v_cache || !d->acc || !d->pos || !d->psi || !d->H || !d->z || !d->n_seen ||
+      !d->pend_slot || !d->pend_v || !d->pend_psi)
     return LESSDEC_EINVAL;
   if (!d->Wq1 || !d->Wq2 || !d->Wk1 || !d->Wk2 || !d->Wk3) return LESSDEC_EINVAL;
   if (!aligned(d->k_cache, 16) || !aligned(d->v_cache, 16) || !aligned(d->acc, 8) ||
       !aligned(d->z, 8) || !aligned(d->H, 16) || !aligned(d->psi, 16) || !aligned(d->pos, 4) ||
-      !aligned(d->n_seen, 4))
+      !aligned(d->n_seen, 4) || !aligned(d->pend_slot, 4) || !aligned(d->pend_v, 16) ||
+      !aligned(d->pend_psi, 4))
     return LESSDEC_EINVAL;
   if (!aligned(d->Wq1, 16) || !aligned(d->Wq2, 16) || !aligned(d->Wk1, 16) ||
       !aligned(d->Wk2, 16) || !aligned(d->Wk3, 4))
@@ -73,6 +75,19 @@ int check_desc(const lessdec_desc *d, Shape *s, size_t P)
   if (!d->workspace || !aligned(d->workspace, 256)) return LESSDEC_EWORKSPACE;
   if (d->workspace_bytes < carve(*s, P).total) return LESSDEC_EWORKSPACE;
   return LESSDEC_OK;
+}
+
+StepArgs state_args(const lessdec_desc *desc, const Shape &s)
+{
+  StepArgs a;
+  a.C = (int)s.C; a.Nh = desc->n_heavy; a.Nr = desc->n_recent; a.R = desc->rank;
+  a.flags = desc->flags;
+  a.k_cache = desc->k_cache; a.v_cache = desc->v_cache; a.acc = desc->acc; a.pos = desc->pos;
+  a.psi = desc->psi; a.H = desc->H; a.z = desc->z; a.n_seen = desc->n_seen;
+  a.pend_slot = desc->pend_slot; a.pend_v = desc->pend_v; a.pend_psi = desc->pend_psi;
+  a.q = a.k = a.v = nullptr; a.out = nullptr; a.evicted_pos = nullptr;
+  a.f_phi = nullptr; a.psi_new = nullptr;
+  return a;
 }
 
 }  // namespace
@@ -92,6 +107,16 @@ int lessdec_state_reset(const lessdec_desc *desc, void *hip_stream)
   int rc = check_desc(desc, &s, 0);
   if (rc) return rc;
   return launch_reset(desc, (hipStream_t)hip_stream) == hipSuccess ? LESSDEC_OK : LESSDEC_EHIP;
+}
+
+int lessdec_state_sync(const lessdec_desc *desc, void *hip_stream)
+{
+  Shape s;
+  int rc = check_desc(desc, &s, 0);
+  if (rc) return rc;
+  const StepArgs a = state_args(desc, s);
+  return launch_state_sync(a, (int)s.U, desc->dtype, desc->head_dim, (hipStream_t)hip_stream) == hipSuccess
+             ? LESSDEC_OK : LESSDEC_EHIP;
 }
 
 int lessdec_step(const lessdec_desc *desc, const void *q, const void *k, const void *v, void *out,
@@ -128,11 +153,7 @@ int lessdec_step(const lessdec_desc *desc, const void *q, const void *k, const v
     if (launch_featmap_generic(fa, desc->dtype, st) != hipSuccess) return LESSDEC_EHIP;
   }
 
-  StepArgs a;
-  a.C = (int)s.C; a.Nh = desc->n_heavy; a.Nr = desc->n_recent; a.R = desc->rank;
-  a.flags = desc->flags;
-  a.k_cache = desc->k_cache; a.v_cache = desc->v_cache; a.acc = desc->acc; a.pos = desc->pos;
-  a.psi = desc->psi; a.H = desc->H; a.z = desc->z; a.n_seen = desc->n_seen;
+  StepArgs a = state_args(desc, s);
   a.q = q; a.k = k; a.v = v; a.out = out; a.evicted_pos = evicted_pos;
   a.f_phi = f_phi; a.psi_new = psi_new;
   if (launch_step(a, (int)s.U, desc->dtype, desc->head_dim, st) != hipSuccess) return LESSDEC_EHIP;

@@ -115,12 +115,12 @@ hipError_t launch_featmap_generic(const FeatmapArgs &a, int dtype, hipStream_t s
 }
 
 // =====================================================================================
-// Reset: H = 0, z = 0, acc = 0, psi = 0, pos = -1, n_seen = 0 (fill kernels, so the call
+// Reset: H = 0, z = 0, acc = 0, psi = 0, pos = -1, n_seen = 0, nothing pending (fill kernels, so the call
 // can be recorded into a HIP graph).
 // =====================================================================================
 __global__ void reset_kernel(float *H, size_t nH, double *z, size_t nz, double *acc, size_t nacc,
                              int32_t *pos, size_t npos, float *psi, size_t npsi, int32_t *n_seen,
-                             size_t nn)
+                             int32_t *pend_slot, size_t nn)
 {
   const size_t stride = (size_t)gridDim.x * blockDim.x;
   const size_t t0 = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -129,7 +129,10 @@ __global__ void reset_kernel(float *H, size_t nH, double *z, size_t nz, double *
   for (size_t i = t0; i < nacc; i += stride) acc[i] = 0.0;
   for (size_t i = t0; i < npos; i += stride) pos[i] = -1;
   for (size_t i = t0; i < npsi; i += stride) psi[i] = 0.f;
-  for (size_t i = t0; i < nn; i += stride) n_seen[i] = 0;
+  for (size_t i = t0; i < nn; i += stride) {
+    n_seen[i] = 0;
+    pend_slot[i] = -1;
+  }
 }
 
 hipError_t launch_reset(const lessdec_desc *d, hipStream_t st)
@@ -137,7 +140,7 @@ hipError_t launch_reset(const lessdec_desc *d, hipStream_t st)
   const size_t U = (size_t)d->batch * d->heads, C = (size_t)d->n_heavy + d->n_recent;
   const size_t R = d->rank, D = d->head_dim;
   reset_kernel<<<1024, 256, 0, st>>>(d->H, U * R * D, d->z, U * R, d->acc, U * C, d->pos, U * C,
-                                     d->psi, U * C * R, d->n_seen, U);
+                                     d->psi, U * C * R, d->n_seen, d->pend_slot, U);
   return hipGetLastError();
 }
 

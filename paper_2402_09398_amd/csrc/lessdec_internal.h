@@ -46,6 +46,9 @@ struct StepArgs {
   float *H;
   double *z;
   int32_t *n_seen;
+  int32_t *pend_slot;    // [U] fold left pending by the last step (see step_unit_kernel)
+  void *pend_v;          // [U,D] value row of the pending discarded pair
+  float *pend_psi;       // [U,R] psi of the last step's key while its slot write is pending
   const void *q, *k, *v;
   void *out;
   int32_t *evicted_pos;
@@ -53,6 +56,7 @@ struct StepArgs {
   const float *psi_new;  // [U,R] psi(k) of this step
 };
 hipError_t launch_step(const StepArgs &a, int units, int dtype, int D, hipStream_t st);
+hipError_t launch_state_sync(const StepArgs &a, int units, int dtype, int D, hipStream_t st);
 
 hipError_t launch_reset(const lessdec_desc *d, hipStream_t st);
 

@@ -261,7 +261,7 @@ __global__ __launch_bounds__(256) void prefill_finalize_kernel(
     const int32_t *__restrict__ slot_of, const float *__restrict__ psi_all, int C, int R,
     T *__restrict__ k_cache, T *__restrict__ v_cache, double *__restrict__ acc,
     int32_t *__restrict__ pos, float *__restrict__ psi, float *__restrict__ H,
-    double *__restrict__ z, int32_t *__restrict__ n_seen)
+    double *__restrict__ z, int32_t *__restrict__ n_seen, int32_t *__restrict__ pend_slot)
 {
   const size_t u = blockIdx.x;
   const int tid = threadIdx.x;
@@ -314,7 +314,10 @@ __global__ __launch_bounds__(256) void prefill_finalize_kernel(
       if (so[j] < 0) a += (double)pa[(size_t)j * R + r];
     z[u * R + r] = a;
   }
-  if (tid == 0) n_seen[u] = P;
+  if (tid == 0) {
+    n_seen[u] = P;
+    pend_slot[u] = -1;
+  }
 }
 
 template <typename T, int D>
@@ -349,7 +352,7 @@ static hipError_t launch_prefill_t(const PrefillArgs &a, hipStream_t st)
   }
   prefill_finalize_kernel<T, D><<<U, 256, 0, st>>>(
       (const T *)a.K, (const T *)a.V, P, a.colsum, a.slot_of, a.psi_all, C, d->rank, (T *)d->k_cache,
-      (T *)d->v_cache, d->acc, d->pos, d->psi, d->H, d->z, d->n_seen);
+      (T *)d->v_cache, d->acc, d->pos, d->psi, d->H, d->z, d->n_seen, d->pend_slot);
   return hipGetLastError();
 }
 

@@ -138,44 +138,74 @@ hipError_t launch_featmap_mfma(FeatmapMfmaArgs a, int n_maps, hipStream_t st)
 // Fused step kernel: one block of 256 threads per unit.
 //
 // A cache row is D * sizeof(T) bytes = LPR lanes of 16 bytes; the block covers RPB =
-// 256 / LPR rows per iteration with fully coalesced 16-byte loads.  With NIT > 0 every K
-// and V row of the unit is requested at kernel entry (NIT loads of each per thread,
-// non-temporal: a row is not touched again before the same layer's next token), so the
-// memory system sees the whole unit at once; NIT = 0 is the looped form for any capacity.
+// 256 / LPR rows (4096 bytes) per iteration with fully coalesced 16-byte loads.  With
+// NIT > 0 every K and V row of the unit is requested at kernel entry (NIT buffer loads of
+// each per thread, sharing one offset register; rows past the capacity read as zero;
+// non-temporal, since a row is not touched again before the same layer's next token), so
+// the memory system sees the whole unit at once and nothing after that waits on a load
+// whose address depends on the step's decisions.  NIT = 0 is the looped form for any
+// capacity.
 //
+// Head     while K and V are in flight: fold the pair discarded by the previous step into
+//          H, z (Eq. 4, Eq. 5) and put the previous key's psi into its slot.  That fold is
+//          written behind by one step because its inputs (psi of the discarded slot) are
+//          only addressable once the eviction is known; doing it here keeps every such
+//          dependent load off the tail of the kernel.  Eq. 3 of this step sees the folded
+//          H, z, exactly as if the fold had happened at the end of the previous step.
 // Phase 1  all waves: scores s_j = q . K_j / sqrt(D) of the live slots and of the appended
 //          key, fp64, reduced over the LPR lanes of a row.
 // Phase 2  wave 0, one lane per row: shift, exponentials, the denominator of Eq. 3 with
 //          phi(q) z^T, probabilities, H2O score accumulation, eviction argmin (Sec. 2.1),
-//          all by wave shuffles.
-// Phase 3  all waves: p . V in fp32 with the row mapping of phase 1.
-// Phase 4  one thread per column: out = p V + phi(q) H / den (Eq. 3), H += psi_e^T v_e,
-//          z += psi_e (Eq. 4, Eq. 5), the new pair written into the freed slot (Sec. 3.2).
+//          all by DPP / readlane reductions.
+// Phase 3  all waves: p . V in fp32 with the row mapping of phase 1; the discarded value
+//          row is picked out of the registers that already hold it.
+// Phase 4  one thread per column: out = p V + phi(q) H / den (Eq. 3); the new pair goes
+//          into the freed slot (Sec. 3.2); the discarded value row is left pending.
 // =====================================================================================
-// Adds to x the value of another lane of its 16-lane DPP row (both halves of the double).
-#define LESSDEC_DPP_ADD(x, ctrl)                                                         \
-  do {                                                                                   \
-    int lo_ = __double2loint(x), hi_ = __double2hiint(x);                                \
-    lo_ = __builtin_amdgcn_update_dpp(0, lo_, (ctrl), 0xf, 0xf, true);                   \
-    hi_ = __builtin_amdgcn_update_dpp(0, hi_, (ctrl), 0xf, 0xf, true);                   \
-    (x) += __hiloint2double(hi_, lo_);                                                   \
-  } while (0)
-
-__device__ inline double dpp_sum16(double v)
+template <int CTRL>
+__device__ inline int dpp_mov(int x)
 {
-  // sum over the 16 lanes of a DPP row; every lane ends with the total
-  LESSDEC_DPP_ADD(v, 0xB1);    // quad_perm [1,0,3,2]
-  LESSDEC_DPP_ADD(v, 0x4E);    // quad_perm [2,3,0,1]
-  LESSDEC_DPP_ADD(v, 0x124);   // row_ror 4: the quad four lanes over
-  LESSDEC_DPP_ADD(v, 0x128);   // row_ror 8: the pair of quads eight lanes over
+  return __builtin_amdgcn_update_dpp(0, x, CTRL, 0xf, 0xf, true);
+}
+template <int CTRL>
+__device__ inline double dpp_mov(double x)
+{
+  return __hiloint2double(dpp_mov<CTRL>(__double2hiint(x)), dpp_mov<CTRL>(__double2loint(x)));
+}
+// All-reduce over the 16 lanes of a DPP row: quad_perm [1,0,3,2], quad_perm [2,3,0,1],
+// row_ror 4, row_ror 8.  Every lane ends with the row's result.
+template <typename V, typename Op>
+__device__ inline V row16_allreduce(V v, Op op)
+{
+  v = op(v, dpp_mov<0xB1>(v));
+  v = op(v, dpp_mov<0x4E>(v));
+  v = op(v, dpp_mov<0x124>(v));
+  v = op(v, dpp_mov<0x128>(v));
   return v;
 }
+__device__ inline int readlane_v(int x, int l) { return __builtin_amdgcn_readlane(x, l); }
+__device__ inline double readlane_v(double x, int l)
+{
+  return __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(x), l),
+                          __builtin_amdgcn_readlane(__double2loint(x), l));
+}
+// All-reduce over the wave, combined in the fixed order ((row0, row1), row2), row3.
+template <typename V, typename Op>
+__device__ inline V wave_allreduce(V v, Op op)
+{
+  v = row16_allreduce(v, op);
+  return op(op(op(readlane_v(v, 0), readlane_v(v, 16)), readlane_v(v, 32)), readlane_v(v, 48));
+}
+struct OpAdd { __device__ double operator()(double a, double b) const { return a + b; } };
+struct OpMax { __device__ double operator()(double a, double b) const { return fmax(a, b); } };
+struct OpMin { __device__ double operator()(double a, double b) const { return fmin(a, b); } };
+struct OpMinI { __device__ int operator()(int a, int b) const { return a < b ? a : b; } };
 
 template <int LPR>
 __device__ inline double row_sum(double v)
 {
   if constexpr (LPR == 16) {
-    return dpp_sum16(v);
+    return row16_allreduce(v, OpAdd{});
   } else {
 #pragma unroll
     for (int o = LPR / 2; o > 0; o >>= 1) v += __shfl_xor(v, o);
@@ -191,10 +221,27 @@ __device__ inline typename Store<T>::Vec load_vec_nt(const T *p)
   __builtin_memcpy(&v.raw, &t, 16);
   return v;
 }
+template <typename T>
+__device__ inline typename Store<T>::Vec buffer_load_nt(__amdgpu_buffer_rsrc_t rsrc, int voffset, int soffset)
+{
+  typename Store<T>::Vec v;
+  const u4v t = __builtin_amdgcn_raw_buffer_load_b128(rsrc, voffset, soffset, 2 /* nt */);
+  __builtin_memcpy(&v.raw, &t, 16);
+  return v;
+}
 
-// Waves per SIMD the register allocation aims for: the K and V rows held in registers grow
-// with NIT (8 VGPRs per iteration), the rest of the kernel needs about 70.
-constexpr int step_waves_per_simd(int nit) { return nit == 0 ? 6 : nit <= 2 ? 5 : nit <= 7 ? 3 : nit <= 11 ? 2 : 1; }
+// pend_slot values: -1 nothing pending; s in [0, C): the pair that sat in slot s was
+// discarded (its psi is still in psi[s], its value row in pend_v) and psi[s] is to become
+// pend_psi; C: the last step's own pair was discarded (its psi is pend_psi).
+template <typename T>
+__device__ inline float pending_psi(const StepArgs &a, int u, int C, int R, int ps, int r)
+{
+  return ps < C ? a.psi[((size_t)u * C + ps) * R + r] : a.pend_psi[(size_t)u * R + r];
+}
+
+// Waves per SIMD the register allocation aims for (the K and V rows held in registers
+// take 8 VGPRs per iteration).
+constexpr int step_waves_per_simd(int nit) { return nit == 0 ? 6 : nit <= 2 ? 5 : nit <= 7 ? 4 : nit <= 11 ? 2 : 1; }
 
 template <typename T, int D, int NIT>
 __global__ __launch_bounds__(256, step_waves_per_simd(NIT)) void step_unit_kernel(const StepArgs a)
@@ -204,6 +251,7 @@ __global__ __launch_bounds__(256, step_waves_per_simd(NIT)) void step_unit_kerne
   constexpr int LPR = D / EPL;             // lanes per row
   constexpr int RPB = kThreads / LPR;      // rows per block iteration
   constexpr int NBUF = NIT > 0 ? NIT : 1;
+  constexpr int kIterBytes = kThreads * 16;
   static_assert(LPR >= 8 && LPR <= 32, "row must span 8..32 lanes");
   using Vec = typename Store<T>::Vec;
 
@@ -212,43 +260,46 @@ __global__ __launch_bounds__(256, step_waves_per_simd(NIT)) void step_unit_kerne
   double *s_sc = dyn;                                        // [C+1] scores
   float *s_p = reinterpret_cast<float *>(dyn + (C + 1));     // [C+1] probabilities (fp32)
   __shared__ float s_o[RPB * D];                             // per row-group partial outputs
-  __shared__ float s_psie[LESSDEC_MAX_RANK];
+  __shared__ float s_psie[LESSDEC_MAX_RANK];                 // psi of the pending discarded pair
+  __shared__ Vec s_ve[LPR];                                  // value row discarded by this step
   __shared__ double s_lscale;
   __shared__ int s_eslot;
 
   const int u = blockIdx.x;
   const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
   const int lr = tid % LPR, rb = tid / LPR;
+  const int col = tid - (kThreads - D);    // threads of the last D / 64 waves own one column each
   const int R = a.R;
 
-  const T *kc = reinterpret_cast<const T *>(a.k_cache) + (size_t)u * C * D;
-  const T *vc = reinterpret_cast<const T *>(a.v_cache) + (size_t)u * C * D;
+  T *kc = reinterpret_cast<T *>(a.k_cache) + (size_t)u * C * D;
+  T *vc = reinterpret_cast<T *>(a.v_cache) + (size_t)u * C * D;
   const T *qn = reinterpret_cast<const T *>(a.q) + (size_t)u * D;
   const T *kn = reinterpret_cast<const T *>(a.k) + (size_t)u * D;
   const T *vn = reinterpret_cast<const T *>(a.v) + (size_t)u * D;
 
-  // ---- everything that does not depend on the step's decisions is requested first ------
+  // ---- everything that does not depend on this step's decisions is requested first -----
   const Vec qv = load_vec<T>(qn + lr * EPL);
   const Vec knv = load_vec<T>(kn + lr * EPL);
   const Vec vnv = load_vec<T>(vn + lr * EPL);
   Vec kbuf[NBUF], vbuf[NBUF];
   if constexpr (NIT > 0) {
+    const int cache_bytes = C * D * (int)sizeof(T);
+    const __amdgpu_buffer_rsrc_t rk = __builtin_amdgcn_make_buffer_rsrc(kc, 0, cache_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rv = __builtin_amdgcn_make_buffer_rsrc(vc, 0, cache_bytes, 0x00020000);
 #pragma unroll
-    for (int it = 0; it < NIT; ++it) {
-      const int r = it * RPB + rb;
-      if (r < C) kbuf[it] = load_vec_nt<T>(kc + (size_t)r * D + lr * EPL);
-    }
+    for (int it = 0; it < NIT; ++it) kbuf[it] = buffer_load_nt<T>(rk, tid * 16, it * kIterBytes);
 #pragma unroll
-    for (int it = 0; it < NIT; ++it) {
-      const int r = it * RPB + rb;
-      if (r < C) vbuf[it] = load_vec_nt<T>(vc + (size_t)r * D + lr * EPL);
-    }
+    for (int it = 0; it < NIT; ++it) vbuf[it] = buffer_load_nt<T>(rv, tid * 16, it * kIterBytes);
   }
-  // wave 0 also owns one row per lane in phase 2: its accumulated score and position
+  const int n = a.n_seen[u];
+  const int ps = a.pend_slot[u];
+  const bool fold = ps >= 0;
+  // wave 0 owns one row per lane in phase 2: its accumulated score and position; and z
   constexpr int NR2 = NIT > 0 ? (NIT * RPB + kWave - 1) / kWave : 1;
   double acc_pre[NR2];
   int pos_pre[NR2];
-  double fz = 0.0;                       // this lane's term of phi(q) z^T
+  double f_lane = 0.0, z_lane = 0.0;
+  float ppsi_lane = 0.f;
   if (wave == 0) {
     if constexpr (NIT > 0) {
 #pragma unroll
@@ -258,9 +309,23 @@ __global__ __launch_bounds__(256, step_waves_per_simd(NIT)) void step_unit_kerne
         pos_pre[i] = (j < C) ? a.pos[(size_t)u * C + j] : -1;
       }
     }
-    for (int r = lane; r < R; r += kWave) fz = fma(a.f_phi[(size_t)u * R + r], a.z[(size_t)u * R + r], fz);
+    if (lane < R) {
+      f_lane = a.f_phi[(size_t)u * R + lane];
+      z_lane = a.z[(size_t)u * R + lane];
+      ppsi_lane = a.pend_psi[(size_t)u * R + lane];
+      if (fold) s_psie[lane] = pending_psi<T>(a, u, C, R, ps, lane);
+    }
   }
-  const int n = a.n_seen[u];
+  // column threads: their column of H and of the pending value row
+  float hreg[16];
+  float pend_v_c = 0.f;
+  if (col >= 0) {
+    if (R <= 16) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) hreg[r] = (r < R) ? a.H[((size_t)u * R + r) * D + col] : 0.f;
+    }
+    if (fold) pend_v_c = Store<T>::to_float(reinterpret_cast<const T *>(a.pend_v)[(size_t)u * D + col]);
+  }
   const int m = n < C ? n : C;          // live slots are 0..m-1 (slots fill in order)
   const int rows = m + 1;               // + the appended pair (K', V' of Eq. 3)
   const bool full = (m == C);
@@ -271,7 +336,7 @@ __global__ __launch_bounds__(256, step_waves_per_simd(NIT)) void step_unit_kerne
 #pragma unroll
     for (int i = 0; i < EPL; ++i) qd[i] = (double)Store<T>::get(qv, i);
     const double sqrt_d = sqrt((double)D);
-    auto score_row = [&](int r, const Vec &kv) {
+    auto score_row = [&](int r, const Vec kv) {
       double part = 0.0;
 #pragma unroll
       for (int i = 0; i < EPL; ++i) part = fma(qd[i], (double)Store<T>::get(kv, i), part);
@@ -282,7 +347,9 @@ __global__ __launch_bounds__(256, step_waves_per_simd(NIT)) void step_unit_kerne
 #pragma unroll
       for (int it = 0; it < NIT; ++it) {
         const int r = it * RPB + rb;
-        score_row(r, r < m ? kbuf[it] : knv);     // r > m: computed on the new key, not stored
+        Vec kv = kbuf[it];
+        if (r >= m) kv = knv;                     // r > m: computed on the new key, not stored
+        score_row(r, kv);
         __builtin_amdgcn_sched_barrier(0);        // one row at a time: keeps the fp64 temporaries few
       }
     } else {
@@ -294,27 +361,44 @@ __global__ __launch_bounds__(256, step_waves_per_simd(NIT)) void step_unit_kerne
       }
     }
   }
-  // the key registers are free now: fetch this thread's column of H for phase 4
-  float hreg[16];
-  if (tid < D && R <= 16) {
-#pragma unroll
-    for (int r = 0; r < 16; ++r) hreg[r] = (r < R) ? a.H[((size_t)u * R + r) * D + tid] : 0.f;
-  }
   __syncthreads();
+
+  // ---- head work of the column threads: fold the pending pair into H (Eq. 4) --------------
+  if (col >= 0 && fold) {
+    float *Hu = a.H + (size_t)u * R * D;
+    if (R <= 16) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        if (r < R) {
+          hreg[r] = fmaf(s_psie[r], pend_v_c, hreg[r]);
+          Hu[(size_t)r * D + col] = hreg[r];
+        }
+      }
+    } else {
+      for (int r = 0; r < R; ++r) Hu[(size_t)r * D + col] = fmaf(s_psie[r], pend_v_c, Hu[(size_t)r * D + col]);
+    }
+  }
 
   // ---- phase 2 (wave 0): softmax pieces, H2O accumulation, eviction choice --------------
   if (wave == 0) {
+    // pending fold of z (Eq. 5) and the slot write of the previous key's psi
+    if (fold && lane < R) {
+      z_lane += (double)s_psie[lane];
+      a.z[(size_t)u * R + lane] = z_lane;
+      if (ps < C) a.psi[((size_t)u * C + ps) * R + lane] = ppsi_lane;
+    }
+    const double fz = wave_allreduce(f_lane * z_lane, OpAdd{});      // phi(q) z^T
+
     double M = -__builtin_inf();
     for (int j = lane; j < rows; j += kWave) M = fmax(M, s_sc[j]);
-    M = wave_max(M);
+    M = wave_allreduce(M, OpMax{});
     double S = 0.0;
     for (int j = lane; j < rows; j += kWave) {
       const double e = exp(s_sc[j] - M);
       s_sc[j] = e;
       S += e;
     }
-    S = wave_sum(S);                                      // sparse part of the denominator, shifted
-    fz = wave_sum(fz);                                    // phi(q) z^T
+    S = wave_allreduce(S, OpAdd{});                       // sparse part of the denominator, shifted
     // den = phi(q) z^T + sum_j e^{s_j}, in whichever scaling cannot overflow:
     //   M > 0 (or no low-rank term): everything times e^{-M};  M <= 0: unscaled, e^{M} <= 1
     double pscale, lscale;
@@ -353,10 +437,19 @@ __global__ __launch_bounds__(256, step_waves_per_simd(NIT)) void step_unit_kerne
         if (is_cand && cand_less(cnd, best)) best = cnd;
       }
     }
-    const Cand ev = wave_argmin(best);
-    const int eslot = full ? ev.slot : -1;                 // m means: the new pair itself
-    const bool evict = full && eslot >= 0;
-    const int ins_slot = full ? ((eslot >= 0 && eslot < m) ? eslot : -1) : m;
+    // argmin over (score, position): smallest score, then the oldest among equals
+    int eslot = -1, epos = -1;
+    if (full) {
+      const double amin = wave_allreduce(best.acc, OpMin{});
+      const int pmin = wave_allreduce(best.acc == amin ? best.pos : INT_MAX, OpMinI{});
+      const unsigned long long win = __ballot(best.acc == amin && best.pos == pmin && best.slot >= 0);
+      if (win != 0ull) {
+        eslot = __builtin_amdgcn_readlane(best.slot, __ffsll((long long)win) - 1);
+        epos = pmin;
+      }
+    }
+    const bool evict = eslot >= 0;                         // eslot == m: the new pair itself
+    const int ins_slot = full ? ((evict && eslot < m) ? eslot : -1) : m;
     // accumulated scores and positions (each lane reads back only what it wrote to s_sc)
     for (int j = lane; j < rows; j += kWave) {
       if (j < m) {
@@ -366,12 +459,17 @@ __global__ __launch_bounds__(256, step_waves_per_simd(NIT)) void step_unit_kerne
         a.pos[(size_t)u * C + ins_slot] = n;
       }
     }
-    if (evict && lane < R)
-      s_psie[lane] = (eslot < m) ? a.psi[((size_t)u * C + eslot) * R + lane] : a.psi_new[(size_t)u * R + lane];
+    // psi of this step's key: straight into its slot while the cache fills, else pending
+    if (lane < R) {
+      const float pn = a.psi_new[(size_t)u * R + lane];
+      if (evict) a.pend_psi[(size_t)u * R + lane] = pn;
+      else a.psi[((size_t)u * C + m) * R + lane] = pn;
+    }
     if (lane == 0) {
       s_lscale = lscale;
       s_eslot = eslot;
-      if (a.evicted_pos) a.evicted_pos[u] = evict ? ev.pos : -1;
+      a.pend_slot[u] = evict ? (eslot < m ? eslot : C) : -1;
+      if (a.evicted_pos) a.evicted_pos[u] = evict ? epos : -1;
       a.n_seen[u] = n + 1;
     }
   }
@@ -379,19 +477,23 @@ __global__ __launch_bounds__(256, step_waves_per_simd(NIT)) void step_unit_kerne
 
   // ---- phase 3: p . V -----------------------------------------------------------------------
   {
+    const int eslot = s_eslot;
     float o[EPL];
 #pragma unroll
     for (int i = 0; i < EPL; ++i) o[i] = 0.f;
-    auto pv_row = [&](int r, const Vec &vv) {
+    auto pv_row = [&](int r, const Vec vv) {
       const float p = (r < rows) ? s_p[r] : 0.f;
 #pragma unroll
       for (int i = 0; i < EPL; ++i) o[i] = fmaf(p, Store<T>::get(vv, i), o[i]);
+      if (r == eslot) s_ve[lr] = vv;                     // the discarded pair's value row
     };
     if constexpr (NIT > 0) {
 #pragma unroll
       for (int it = 0; it < NIT; ++it) {
         const int r = it * RPB + rb;
-        pv_row(r, r < m ? vbuf[it] : vnv);
+        Vec vv = vbuf[it];
+        if (r >= m) vv = vnv;
+        pv_row(r, vv);
         __builtin_amdgcn_sched_barrier(0);
       }
     } else {
@@ -407,47 +509,56 @@ __global__ __launch_bounds__(256, step_waves_per_simd(NIT)) void step_unit_kerne
   }
   __syncthreads();
 
-  // ---- phase 4: output, state update, in-place insert -----------------------------------
-  if (tid < D) {
-    const int c = tid;
+  // ---- phase 4: output, in-place insert, pending value row -----------------------------------
+  if (col >= 0) {
     const int eslot = s_eslot;
-    const bool evict = full && eslot >= 0;
-    const int ins_slot = full ? ((eslot >= 0 && eslot < m) ? eslot : -1) : m;
+    const bool evict = eslot >= 0;
+    const int ins_slot = full ? ((evict && eslot < m) ? eslot : -1) : m;
     float pv = 0.f;
 #pragma unroll
-    for (int gidx = 0; gidx < RPB; ++gidx) pv += s_o[gidx * D + c];
-    float *Hu = a.H + (size_t)u * R * D;
+    for (int gidx = 0; gidx < RPB; ++gidx) pv += s_o[gidx * D + col];
     float fh = 0.f;
     if (R <= 16) {
 #pragma unroll
       for (int r = 0; r < 16; ++r)
         if (r < R) fh = fmaf((float)a.f_phi[(size_t)u * R + r], hreg[r], fh);
     } else {
-      for (int r = 0; r < R; ++r) fh = fmaf((float)a.f_phi[(size_t)u * R + r], Hu[(size_t)r * D + c], fh);
+      const float *Hu = a.H + (size_t)u * R * D;
+      for (int r = 0; r < R; ++r) fh = fmaf((float)a.f_phi[(size_t)u * R + r], Hu[(size_t)r * D + col], fh);
     }
     const double o = (double)pv + s_lscale * (double)fh;
-    reinterpret_cast<T *>(a.out)[(size_t)u * D + c] = Store<T>::from_float((float)o);
-
-    if (evict) {
-      const float ve = (eslot < m) ? Store<T>::to_float(vc[(size_t)eslot * D + c])
-                                   : Store<T>::to_float(vn[c]);
-      if (R <= 16) {
-#pragma unroll
-        for (int r = 0; r < 16; ++r)
-          if (r < R) Hu[(size_t)r * D + c] = fmaf(s_psie[r], ve, hreg[r]);
-      } else {
-        for (int r = 0; r < R; ++r) Hu[(size_t)r * D + c] = fmaf(s_psie[r], ve, Hu[(size_t)r * D + c]);
-      }
-      if (c < R) a.z[(size_t)u * R + c] += (double)s_psie[c];
-    }
+    reinterpret_cast<T *>(a.out)[(size_t)u * D + col] = Store<T>::from_float((float)o);
+    if (evict)
+      reinterpret_cast<T *>(a.pend_v)[(size_t)u * D + col] = reinterpret_cast<const T *>(s_ve)[col];
     if (ins_slot >= 0) {
-      T *kw = reinterpret_cast<T *>(a.k_cache) + ((size_t)u * C + ins_slot) * D;
-      T *vw = reinterpret_cast<T *>(a.v_cache) + ((size_t)u * C + ins_slot) * D;
-      kw[c] = kn[c];
-      vw[c] = vn[c];
-      if (c < R) a.psi[((size_t)u * C + ins_slot) * R + c] = a.psi_new[(size_t)u * R + c];
+      kc[(size_t)ins_slot * D + col] = kn[col];
+      vc[(size_t)ins_slot * D + col] = vn[col];
     }
   }
+}
+
+// Folds whatever the last step left pending, so that H, z and psi are current (Eq. 4, 5).
+template <typename T>
+__global__ __launch_bounds__(256) void state_sync_kernel(const StepArgs a, int D)
+{
+  const int u = blockIdx.x, tid = threadIdx.x, C = a.C, R = a.R;
+  __shared__ float s_psie[LESSDEC_MAX_RANK];
+  const int ps = a.pend_slot[u];
+  if (ps < 0) return;                                    // uniform per block
+  if (tid < R) s_psie[tid] = pending_psi<T>(a, u, C, R, ps, tid);
+  __syncthreads();
+  if (tid < D) {
+    const float v = Store<T>::to_float(reinterpret_cast<const T *>(a.pend_v)[(size_t)u * D + tid]);
+    for (int r = 0; r < R; ++r) {
+      float *h = a.H + ((size_t)u * R + r) * D + tid;
+      *h = fmaf(s_psie[r], v, *h);
+    }
+  }
+  if (tid < R) {
+    a.z[(size_t)u * R + tid] += (double)s_psie[tid];
+    if (ps < C) a.psi[((size_t)u * C + ps) * R + tid] = a.pend_psi[(size_t)u * R + tid];
+  }
+  if (tid == 0) a.pend_slot[u] = -1;
 }
 
 template <typename T, int D>
@@ -470,6 +581,13 @@ hipError_t launch_step(const StepArgs &a, int units, int dtype, int D, hipStream
     return D == 128 ? launch_step_t<__half, 128>(a, units, st) : launch_step_t<__half, 64>(a, units, st);
   }
   return D == 128 ? launch_step_t<float, 128>(a, units, st) : launch_step_t<float, 64>(a, units, st);
+}
+
+hipError_t launch_state_sync(const StepArgs &a, int units, int dtype, int D, hipStream_t st)
+{
+  if (dtype == LESSDEC_DTYPE_F16) state_sync_kernel<__half><<<units, 256, 0, st>>>(a, D);
+  else state_sync_kernel<float><<<units, 256, 0, st>>>(a, D);
+  return hipGetLastError();
 }
 
 }  // namespace lessdec

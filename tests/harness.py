@@ -93,6 +93,7 @@ def upload_oracle_state(gpu, st, units_all=True):
     gpu.H.copy_(torch.from_numpy(st.H.astype(np.float32)))
     gpu.z.copy_(torch.from_numpy(st.z))
     gpu.n_seen.copy_(torch.from_numpy(st.n.astype(np.int32)))
+    gpu.pend_slot.fill_(-1)
     psi = np.zeros((st.U, st.C, st.R), dtype=np.float32)
     for u in range(st.U):
         h = st.head[u]
@@ -116,6 +117,7 @@ def gpu_run(w, inp, flags=0, with_prefill=True, want_prefill_out=True, gpu=None,
     U, D = w.units, w.head_dim
 
     def snapshot():
+        gpu.state_sync()                      # fold what the last step left pending
         torch.cuda.synchronize(dev)
         return {k: getattr(gpu, k).cpu().numpy().copy()
                 for k in ("k_cache", "v_cache", "acc", "pos", "psi", "H", "z", "n_seen")}

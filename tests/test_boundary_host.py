@@ -27,8 +27,8 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_descriptor_layout_matches_header():
-    # 10 int32 fields, 13 pointers, 1 size_t on LP64
-    assert C.sizeof(binding.Desc) == 10 * 4 + 13 * 8 + 8 + 8
+    # 10 int32 fields, 17 pointers, 1 size_t on LP64
+    assert C.sizeof(binding.Desc) == 10 * 4 + 17 * 8 + 8
     assert binding.Desc.k_cache.offset == 40
 
 
@@ -67,11 +67,12 @@ def test_calls_reject_bad_descriptors_on_the_host():
     L = binding.lib()
     d = _desc()                                             # all pointers NULL
     assert L.lessdec_state_reset(C.byref(d), None) == binding.EINVAL
+    assert L.lessdec_state_sync(C.byref(d), None) == binding.EINVAL
     assert L.lessdec_step(C.byref(d), None, None, None, None, None, None) == binding.EINVAL
     assert L.lessdec_prefill(C.byref(d), None, None, None, 16, None, None) == binding.EINVAL
     # plausible pointers but no workspace -> workspace error; misaligned cache -> invalid
     for f in ("k_cache", "v_cache", "acc", "pos", "psi", "H", "z", "n_seen",
-              "Wq1", "Wq2", "Wk1", "Wk2", "Wk3"):
+              "pend_slot", "pend_v", "pend_psi", "Wq1", "Wq2", "Wk1", "Wk2", "Wk3"):
         setattr(d, f, 0x10000)
     assert L.lessdec_state_reset(C.byref(d), None) == binding.EWORKSPACE
     d.workspace = 0x20000; d.workspace_bytes = 16

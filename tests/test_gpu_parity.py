@@ -124,7 +124,7 @@ def test_checkpoint_restore_continues_bit_identically():
     first = {k: (v if k in "QKV" else v[:half]) for k, v in inp.items()}
     res = hz.gpu_run(w, first)
     gpu = res["gpu"]
-    names = ("k_cache", "v_cache", "acc", "pos", "psi", "H", "z", "n_seen")
+    names = gpu.STATE
     saved = {n: getattr(gpu, n).clone() for n in names}
     q, k, v = (torch.from_numpy(inp[n][half:]).cuda() for n in ("q", "k", "v"))
 
