@@ -10,7 +10,8 @@ HERE = Path(__file__).resolve().parent
 ROOT = HERE.parent
 CSRC = HERE / "csrc"
 LIB = HERE / "liblessdec.so"
-SOURCES = ["lessdec_api.hip", "lessdec_featmap.hip", "lessdec_step.hip", "lessdec_prefill.hip"]
+SOURCES = ["lessdec_api.hip", "lessdec_featmap.hip", "lessdec_mlp.hip", "lessdec_step.hip",
+           "lessdec_prefill.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

@@ -36,10 +36,12 @@ bool shape_ok(const lessdec_desc *d, Shape *s)
   return true;
 }
 
-// Workspace: [ f_phi U*R f64 | psi_new U*R f32 | prefill: rowmax, rowsum, colsum U*P f64 |
-//              slot_of U*P i32 | psi_all U*P*R f32 ], every part 256-byte aligned.
+// Workspace: [ f_phi U*R f64 | psi_new U*R f32 | part_phi (R'/128)*U*16 f32 |
+//              prefill: rowmax, rowsum, colsum U*P f64 | slot_of U*P i32 | psi_all U*P*R f32 ],
+// every part 256-byte aligned.
 struct Workspace {
-  size_t off_fphi, off_psinew, off_rowmax, off_rowsum, off_colsum, off_slot, off_psiall, total;
+  size_t off_fphi, off_psinew, off_partphi, off_rowmax, off_rowsum, off_colsum, off_slot,
+      off_psiall, total;
 };
 
 Workspace carve(const Shape &s, size_t P)
@@ -48,6 +50,8 @@ Workspace carve(const Shape &s, size_t P)
   size_t o = 0;
   w.off_fphi = o; o = align_up(o + s.U * s.R * sizeof(double), 256);
   w.off_psinew = o; o = align_up(o + s.U * s.R * sizeof(float), 256);
+  const size_t nparts = (s.Rp + kMlpPartHidden - 1) / kMlpPartHidden;
+  w.off_partphi = o; o = align_up(o + nparts * s.U * kMlpPartStride * sizeof(float), 256);
   w.off_rowmax = o; o = align_up(o + s.U * P * sizeof(double), 256);
   w.off_rowsum = o; o = align_up(o + s.U * P * sizeof(double), 256);
   w.off_colsum = o; o = align_up(o + s.U * P * sizeof(double), 256);
@@ -87,6 +91,8 @@ StepArgs state_args(const lessdec_desc *desc, const Shape &s)
   a.pend_slot = desc->pend_slot; a.pend_v = desc->pend_v; a.pend_psi = desc->pend_psi;
   a.q = a.k = a.v = nullptr; a.out = nullptr; a.evicted_pos = nullptr;
   a.f_phi = nullptr; a.psi_new = nullptr;
+  a.part_phi = nullptr; a.nparts = 0;
+  a.U = (int)s.U;
   return a;
 }
 
@@ -135,14 +141,18 @@ int lessdec_step(const lessdec_desc *desc, const void *q, const void *k, const v
   double *f_phi = reinterpret_cast<double *>(ws + w.off_fphi);
   float *psi_new = reinterpret_cast<float *>(ws + w.off_psinew);
 
-  if (featmap_mfma_supported(desc->dtype, desc->head_dim, desc->hidden, desc->rank)) {
-    FeatmapMfmaArgs fm;
+  float *part_phi = reinterpret_cast<float *>(ws + w.off_partphi);
+  int nparts = 0;
+  if (mlp_mfma_supported(desc->dtype, desc->head_dim, desc->hidden, desc->rank)) {
+    MlpArgs fm;
     fm.B = desc->batch; fm.Hh = desc->heads; fm.rpu = 1;
-    fm.D = desc->head_dim; fm.Rp = desc->hidden; fm.R = desc->rank; fm.nchunk = 0;
-    fm.map[0] = {(const __half *)q, (const __half *)desc->Wq1, (const __half *)desc->Wq2, nullptr, f_phi, 1};
+    fm.D = desc->head_dim; fm.Rp = desc->hidden; fm.R = desc->rank;
+    fm.nchunk = fm.nparts = fm.n_part_blocks = 0;
+    fm.map[0] = {(const __half *)q, (const __half *)desc->Wq1, (const __half *)desc->Wq2, nullptr, part_phi};
     fm.map[1] = {(const __half *)k, (const __half *)desc->Wk1, (const __half *)desc->Wk2,
-                 (const __half *)desc->Wk3, psi_new, 0};
-    if (launch_featmap_mfma(fm, 2, st) != hipSuccess) return LESSDEC_EHIP;
+                 (const __half *)desc->Wk3, psi_new};
+    if (launch_mlp(fm, true, true, st) != hipSuccess) return LESSDEC_EHIP;
+    nparts = desc->hidden / kMlpPartHidden;
   } else {
     FeatmapArgs fa;
     fa.B = desc->batch; fa.Hh = desc->heads; fa.rpu = 1;
@@ -156,6 +166,7 @@ int lessdec_step(const lessdec_desc *desc, const void *q, const void *k, const v
   StepArgs a = state_args(desc, s);
   a.q = q; a.k = k; a.v = v; a.out = out; a.evicted_pos = evicted_pos;
   a.f_phi = f_phi; a.psi_new = psi_new;
+  a.part_phi = part_phi; a.nparts = nparts;
   if (launch_step(a, (int)s.U, desc->dtype, desc->head_dim, st) != hipSuccess) return LESSDEC_EHIP;
   return LESSDEC_OK;
 }

@@ -21,20 +21,25 @@ struct FeatmapArgs {
 };
 hipError_t launch_featmap_generic(const FeatmapArgs &a, int dtype, hipStream_t st);
 
-// Matrix-core feature maps (fp16 storage): up to two maps (phi of q and psi of k) in one
-// launch, same row-to-unit convention as above.
-struct FeatmapMfmaArgs {
+// Matrix-core feature maps (fp16 storage, D in {64,128}, R' a multiple of 128, R <= 16).
+// Row convention as above.  Two kinds of blocks in one launch:
+//  - part blocks (map[0], phi): 16 rows x 128 hidden units each, writing the layer-2
+//    pre-activation partial sums out[(part * rows + row) * 16 + r] (fp32); the reader adds
+//    the R'/128 parts and applies the last activation of Eq. 1.
+//  - full blocks (map[1], psi): 16 rows x all hidden units, writing psi [rows, R] itself.
+constexpr int kMlpPartHidden = 128;
+constexpr int kMlpPartStride = 16;      // floats per row in a partial-sum buffer
+struct MlpArgs {
   struct Map {
-    const __half *x, *W1, *W2, *W3;   // W3 == NULL: Eq. 1, else Eq. 2
-    void *out;
-    int out_f64;
+    const __half *x, *W1, *W2, *W3;
+    float *out;                          // parts: partial sums; full: psi [rows, R]
   };
   Map map[2];
   int B, Hh, rpu, D, Rp, R;
-  int nchunk;                           // set by the launcher
+  int nchunk, nparts, n_part_blocks;     // set by the launcher
 };
-bool featmap_mfma_supported(int dtype, int D, int Rp, int R);
-hipError_t launch_featmap_mfma(FeatmapMfmaArgs a, int n_maps, hipStream_t st);
+bool mlp_mfma_supported(int dtype, int D, int Rp, int R);
+hipError_t launch_mlp(MlpArgs a, bool parts, bool fulls, hipStream_t st);
 
 struct StepArgs {
   int C, Nh, Nr, R;
@@ -52,8 +57,12 @@ struct StepArgs {
   const void *q, *k, *v;
   void *out;
   int32_t *evicted_pos;
-  const double *f_phi;   // [U,R] phi(q) of this step
-  const float *psi_new;  // [U,R] psi(k) of this step
+  // feature maps of this step's q and k: either final values (generic path) ...
+  const double *f_phi;   // [U,R] phi(q)
+  const float *psi_new;  // [U,R] psi(k)
+  // ... or layer-2 partial sums from the matrix-core path (nparts > 0)
+  const float *part_phi;              // [nparts, U, 16]
+  int nparts, U;
 };
 hipError_t launch_step(const StepArgs &a, int units, int dtype, int D, hipStream_t st);
 hipError_t launch_state_sync(const StepArgs &a, int units, int dtype, int D, hipStream_t st);

@@ -336,14 +336,14 @@ static hipError_t launch_prefill_t(const PrefillArgs &a, hipStream_t st)
   if ((e = hipGetLastError()) != hipSuccess) return e;
   prefill_select_kernel<<<U, 256, 0, st>>>(a.colsum, P, d->n_heavy, d->n_recent, a.slot_of);
   if ((e = hipGetLastError()) != hipSuccess) return e;
-  if (featmap_mfma_supported(d->dtype, d->head_dim, d->hidden, d->rank)) {
-    FeatmapMfmaArgs fm;
+  if (mlp_mfma_supported(d->dtype, d->head_dim, d->hidden, d->rank)) {
+    MlpArgs fm;
     fm.B = d->batch; fm.Hh = d->heads; fm.rpu = P; fm.D = d->head_dim; fm.Rp = d->hidden; fm.R = d->rank;
-    fm.nchunk = 0;
-    fm.map[0] = {(const __half *)a.K, (const __half *)d->Wk1, (const __half *)d->Wk2,
-                 (const __half *)d->Wk3, a.psi_all, 0};
-    fm.map[1] = fm.map[0];
-    if ((e = launch_featmap_mfma(fm, 1, st)) != hipSuccess) return e;
+    fm.nchunk = fm.nparts = fm.n_part_blocks = 0;
+    fm.map[1] = {(const __half *)a.K, (const __half *)d->Wk1, (const __half *)d->Wk2,
+                 (const __half *)d->Wk3, a.psi_all};
+    fm.map[0] = fm.map[1];
+    if ((e = launch_mlp(fm, false, true, st)) != hipSuccess) return e;
   } else {
     FeatmapArgs fa;
     fa.x = a.K; fa.W1 = d->Wk1; fa.W2 = d->Wk2; fa.W3 = d->Wk3; fa.out = a.psi_all; fa.out_f64 = 0;

@@ -1,138 +1,11 @@
-// Decode step (Algorithm 1): feature maps of the step's q and k on the matrix cores, and
-// the fused attention / score-accumulate / evict / state-update kernel (Eq. 3-5).
+// Decode step (Algorithm 1): the fused attention / score-accumulate / evict / state-update
+// kernel (Eq. 3-5) and the write-behind state fold.
 #include "lessdec_common.h"
 #include "lessdec_internal.h"
 
 namespace lessdec {
 
-typedef _Float16 v8h __attribute__((ext_vector_type(8)));
-typedef float v4f __attribute__((ext_vector_type(4)));
 typedef unsigned int u4v __attribute__((ext_vector_type(4)));
-
-// =====================================================================================
-// Feature maps on the matrix cores (fp16 storage only).
-//
-// One block of 4 waves evaluates 16 rows that share a head.  Layer 1 (the only real
-// contraction: 16 x D times D x R') runs on v_mfma_f32_16x16x32_f16 with M = hidden
-// units, N = rows: lane (kg, i) = (lane / 16, lane % 16) supplies 8 consecutive k of
-// matrix row i, result register w of lane (g, c) is element [4 g + w][c].  fp16 x fp16
-// products are exact in fp32, so only the fp32 accumulation rounds.  Wave w owns the
-// hidden units [w R'/4, (w+1) R'/4).  GELU is applied in registers and layer 2
-// (R' x R, R <= 16) is accumulated in fp64 straight from the MFMA result layout, so the
-// hidden activations never leave the registers; partial sums of the 4 waves meet in LDS.
-//
-// grid = n_maps * Hh * ceil(B * rpu / 16), head fastest (so that with Hh a multiple of 8
-// all blocks of a head land on one XCD and share its L2 copy of the weights); block 256.
-// =====================================================================================
-template <int D>
-__global__ __launch_bounds__(256) void featmap_mfma_kernel(const FeatmapMfmaArgs a)
-{
-  constexpr int KS = D / 32;                      // MFMA k-steps
-  __shared__ double s_red[4][16][16];             // [wave][row][r]
-  __shared__ double s_h2[16][16];
-  const int tid = threadIdx.x, wave = tid / 64, l = tid % 64, g = l / 16, c = l % 16;
-  const int Hh = a.Hh, Rp = a.Rp, R = a.R;
-  const int per_map = Hh * a.nchunk;
-  const int map = blockIdx.x / per_map;           // 0: first map in the args, 1: second
-  const int rem = blockIdx.x % per_map;
-  const int h = rem % Hh, chunk = rem / Hh;
-  const FeatmapMfmaArgs::Map mp = a.map[map];
-  const __half *W1 = mp.W1 + (size_t)h * Rp * D;
-  const __half *W2 = mp.W2 + (size_t)h * R * Rp;
-  const long rows_head = (long)a.B * a.rpu;
-  auto global_row = [&](long i) -> long {
-    long b = i / a.rpu, p = i % a.rpu;
-    return (b * Hh + h) * (long)a.rpu + p;
-  };
-
-  // B operand: this lane's row (c) of x, k = 32 ks + 8 g .. + 8
-  v8h bx[KS];
-  {
-    const long i = (long)chunk * 16 + c;
-    if (i < rows_head) {
-      const __half *xr = mp.x + global_row(i) * D;
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) bx[ks] = *reinterpret_cast<const v8h *>(xr + 32 * ks + 8 * g);
-    } else {
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) bx[ks] = v8h{0, 0, 0, 0, 0, 0, 0, 0};
-    }
-  }
-  double part[16];
-#pragma unroll
-  for (int r = 0; r < 16; ++r) part[r] = 0.0;
-
-  const int HW = Rp / 4;                          // hidden units of this wave (multiple of 16)
-  const int hid0 = wave * HW;
-  for (int mt = 0; mt < HW / 16; ++mt) {
-    const __half *w1r = W1 + (size_t)(hid0 + 16 * mt + c) * D + 8 * g;
-    v4f acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      const v8h av = *reinterpret_cast<const v8h *>(w1r + 32 * ks);
-      acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, bx[ks], acc, 0, 0, 0);
-    }
-    // acc[w] = pre-activation of hidden unit hid0 + 16 mt + 4 g + w for row c
-    double gl[4];
-#pragma unroll
-    for (int w = 0; w < 4; ++w) gl[w] = (double)gelu_f32(acc[w]);
-    const __half *w2p = W2 + hid0 + 16 * mt + 4 * g;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      if (r < R) {
-        const uint2 raw = *reinterpret_cast<const uint2 *>(w2p + (size_t)r * Rp);
-        const __half *wh = reinterpret_cast<const __half *>(&raw);
-#pragma unroll
-        for (int w = 0; w < 4; ++w) part[r] = fma(gl[w], (double)__half2float(wh[w]), part[r]);
-      }
-    }
-  }
-#pragma unroll
-  for (int r = 0; r < 16; ++r) {
-    part[r] += __shfl_xor(part[r], 16);
-    part[r] += __shfl_xor(part[r], 32);
-  }
-  if (g == 0) {
-#pragma unroll
-    for (int r = 0; r < 16; ++r) s_red[wave][c][r] = part[r];
-  }
-  __syncthreads();
-  // one thread per (row, r)
-  const int row = tid / 16, r = tid % 16;
-  const long i = (long)chunk * 16 + row;
-  double val = 0.0;
-  if (r < R) val = gelu_f64(((s_red[0][row][r] + s_red[1][row][r]) + s_red[2][row][r]) + s_red[3][row][r]);
-  if (mp.W3 != nullptr) {                          // psi: one more R x R matrix, no activation (Eq. 2)
-    s_h2[row][r] = val;
-    __syncthreads();
-    if (r < R) {
-      const __half *W3 = mp.W3 + ((size_t)h * R + r) * R;
-      double acc3 = 0.0;
-      for (int j = 0; j < R; ++j) acc3 = fma(s_h2[row][j], (double)__half2float(W3[j]), acc3);
-      val = acc3;
-    }
-  }
-  if (r < R && i < rows_head) {
-    const size_t o = (size_t)global_row(i) * R + r;
-    if (mp.out_f64) reinterpret_cast<double *>(mp.out)[o] = fabs(val);
-    else reinterpret_cast<float *>(mp.out)[o] = (float)fabs(val);
-  }
-}
-
-bool featmap_mfma_supported(int dtype, int D, int Rp, int R)
-{
-  return dtype == LESSDEC_DTYPE_F16 && (D == 64 || D == 128) && Rp % 64 == 0 && Rp >= 64 && R <= 16;
-}
-
-hipError_t launch_featmap_mfma(FeatmapMfmaArgs a, int n_maps, hipStream_t st)
-{
-  const long rows_head = (long)a.B * a.rpu;
-  a.nchunk = (int)((rows_head + 15) / 16);
-  const unsigned grid = (unsigned)((long)n_maps * a.Hh * a.nchunk);
-  if (a.D == 128) featmap_mfma_kernel<128><<<grid, 256, 0, st>>>(a);
-  else featmap_mfma_kernel<64><<<grid, 256, 0, st>>>(a);
-  return hipGetLastError();
-}
 
 // =====================================================================================
 // Fused step kernel: one block of 256 threads per unit.
@@ -241,11 +114,23 @@ __device__ inline float pending_psi(const StepArgs &a, int u, int C, int R, int 
 
 // Waves per SIMD the register allocation aims for (the K and V rows held in registers
 // take 8 VGPRs per iteration).
-constexpr int step_waves_per_simd(int nit) { return nit == 0 ? 6 : nit <= 2 ? 5 : nit <= 7 ? 4 : nit <= 11 ? 2 : 1; }
+constexpr int step_waves_per_simd(int nit) { return nit == 0 ? 6 : nit <= 2 ? 6 : nit <= 7 ? 5 : nit <= 11 ? 3 : 2; }
+
+#ifdef LESSDEC_TRACE
+__device__ unsigned long long *g_trace = nullptr;   // [blocks][8], set by the tracing harness
+#define LESSDEC_STAMP(i)                                                                  \
+  do {                                                                                    \
+    if (g_trace && (threadIdx.x & 63) == 0)                                               \
+      g_trace[(size_t)blockIdx.x * 8 + (i)] = __builtin_amdgcn_s_memrealtime();           \
+  } while (0)
+#else
+#define LESSDEC_STAMP(i) do { } while (0)
+#endif
 
 template <typename T, int D, int NIT>
 __global__ __launch_bounds__(256, step_waves_per_simd(NIT)) void step_unit_kernel(const StepArgs a)
 {
+  LESSDEC_STAMP(0);
   constexpr int kThreads = 256;
   constexpr int EPL = Store<T>::kPerVec;   // elements per lane
   constexpr int LPR = D / EPL;             // lanes per row
@@ -259,16 +144,21 @@ __global__ __launch_bounds__(256, step_waves_per_simd(NIT)) void step_unit_kerne
   const int C = a.C;
   double *s_sc = dyn;                                        // [C+1] scores
   float *s_p = reinterpret_cast<float *>(dyn + (C + 1));     // [C+1] probabilities (fp32)
-  __shared__ float s_o[RPB * D];                             // per row-group partial outputs
+  __shared__ __attribute__((aligned(16))) float s_o[RPB * D];   // per row-group partial outputs
   __shared__ float s_psie[LESSDEC_MAX_RANK];                 // psi of the pending discarded pair
+  __shared__ float s_f[LESSDEC_MAX_RANK];                    // phi(q) for the column threads
   __shared__ Vec s_ve[LPR];                                  // value row discarded by this step
   __shared__ double s_lscale;
   __shared__ int s_eslot;
 
   const int u = blockIdx.x;
-  const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+  const int tid = threadIdx.x, lane = tid % kWave;
   const int lr = tid % LPR, rb = tid / LPR;
-  const int col = tid - (kThreads - D);    // threads of the last D / 64 waves own one column each
+  // Roles rotate with the block index: the blocks that share a CU differ in blockIdx / 256
+  // (blocks go round-robin over 8 XCDs x 32 CUs), so their serial phase 2 lands on different
+  // SIMDs instead of queueing on one.  "wave" is the role index, not the hardware wave.
+  const int wave = (tid / kWave + (int)(blockIdx.x >> 8)) & 3;
+  const int col = wave * kWave + lane - (kThreads - D);   // role waves 4 - D/64 .. 3 own one column each
   const int R = a.R;
 
   T *kc = reinterpret_cast<T *>(a.k_cache) + (size_t)u * C * D;
@@ -277,27 +167,21 @@ __global__ __launch_bounds__(256, step_waves_per_simd(NIT)) void step_unit_kerne
   const T *kn = reinterpret_cast<const T *>(a.k) + (size_t)u * D;
   const T *vn = reinterpret_cast<const T *>(a.v) + (size_t)u * D;
 
-  // ---- everything that does not depend on this step's decisions is requested first -----
+  // ---- requests, small ones first -----------------------------------------------------------
+  // Loads return to a wave in issue order, so everything the head of the kernel works on
+  // while the keys are in flight (counters, feature-map partial sums, scores, H, the pending
+  // pair) is requested before the keys.
+  const int n = a.n_seen[u];
+  const int ps = a.pend_slot[u];
   const Vec qv = load_vec<T>(qn + lr * EPL);
   const Vec knv = load_vec<T>(kn + lr * EPL);
   const Vec vnv = load_vec<T>(vn + lr * EPL);
-  Vec kbuf[NBUF], vbuf[NBUF];
-  if constexpr (NIT > 0) {
-    const int cache_bytes = C * D * (int)sizeof(T);
-    const __amdgpu_buffer_rsrc_t rk = __builtin_amdgcn_make_buffer_rsrc(kc, 0, cache_bytes, 0x00020000);
-    const __amdgpu_buffer_rsrc_t rv = __builtin_amdgcn_make_buffer_rsrc(vc, 0, cache_bytes, 0x00020000);
-#pragma unroll
-    for (int it = 0; it < NIT; ++it) kbuf[it] = buffer_load_nt<T>(rk, tid * 16, it * kIterBytes);
-#pragma unroll
-    for (int it = 0; it < NIT; ++it) vbuf[it] = buffer_load_nt<T>(rv, tid * 16, it * kIterBytes);
-  }
-  const int n = a.n_seen[u];
-  const int ps = a.pend_slot[u];
-  const bool fold = ps >= 0;
   // wave 0 owns one row per lane in phase 2: its accumulated score and position; and z
   constexpr int NR2 = NIT > 0 ? (NIT * RPB + kWave - 1) / kWave : 1;
+  constexpr int kPre = 4;                 // feature-map parts fetched ahead (R' <= 512)
   double acc_pre[NR2];
   int pos_pre[NR2];
+  float pphi[kPre];
   double f_lane = 0.0, z_lane = 0.0;
   float ppsi_lane = 0.f;
   if (wave == 0) {
@@ -310,47 +194,96 @@ __global__ __launch_bounds__(256, step_waves_per_simd(NIT)) void step_unit_kerne
       }
     }
     if (lane < R) {
-      f_lane = a.f_phi[(size_t)u * R + lane];
       z_lane = a.z[(size_t)u * R + lane];
       ppsi_lane = a.pend_psi[(size_t)u * R + lane];
-      if (fold) s_psie[lane] = pending_psi<T>(a, u, C, R, ps, lane);
+      if (a.nparts > 0) {
+#pragma unroll
+        for (int p = 0; p < kPre; ++p)
+          pphi[p] = p < a.nparts ? a.part_phi[((size_t)p * a.U + u) * kMlpPartStride + lane] : 0.f;
+      } else {
+        f_lane = a.f_phi[(size_t)u * R + lane];
+      }
     }
   }
   // column threads: their column of H and of the pending value row
   float hreg[16];
-  float pend_v_c = 0.f;
+  float pend_v_c = 0.f, psin_c = 0.f;     // psin_c: psi of this step's key, threads col < R
   if (col >= 0) {
     if (R <= 16) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) hreg[r] = (r < R) ? a.H[((size_t)u * R + r) * D + col] : 0.f;
     }
-    if (fold) pend_v_c = Store<T>::to_float(reinterpret_cast<const T *>(a.pend_v)[(size_t)u * D + col]);
+    pend_v_c = Store<T>::to_float(reinterpret_cast<const T *>(a.pend_v)[(size_t)u * D + col]);
+    if (col < R) psin_c = a.psi_new[(size_t)u * R + col];
+  }
+  __builtin_amdgcn_sched_barrier(0);
+  Vec kbuf[NBUF], vbuf[NBUF];
+  if constexpr (NIT > 0) {
+    const int cache_bytes = C * D * (int)sizeof(T);
+    const __amdgpu_buffer_rsrc_t rk = __builtin_amdgcn_make_buffer_rsrc(kc, 0, cache_bytes, 0x00020000);
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) kbuf[it] = buffer_load_nt<T>(rk, tid * 16, it * kIterBytes);
+  }
+  __builtin_amdgcn_sched_barrier(0);
+  const bool fold = ps >= 0;
+
+  // ---- head work of wave 0 while the keys are in flight ---------------------------------------
+  if (wave == 0) {
+    if (a.nparts > 0) {
+      // matrix-core path: add the partial sums of layer 2, then the last activation of Eq. 1
+      double sp = 0.0;
+      if (lane < R) {
+#pragma unroll
+        for (int p = 0; p < kPre; ++p) sp += (double)pphi[p];
+        for (int p = kPre; p < a.nparts; ++p)
+          sp += (double)a.part_phi[((size_t)p * a.U + u) * kMlpPartStride + lane];
+      }
+      f_lane = lane < R ? fabs(gelu_f64(sp)) : 0.0;
+    }
+    if (lane < R) {
+      s_f[lane] = (float)f_lane;
+      if (fold) s_psie[lane] = pending_psi<T>(a, u, C, R, ps, lane);
+    }
   }
   const int m = n < C ? n : C;          // live slots are 0..m-1 (slots fill in order)
   const int rows = m + 1;               // + the appended pair (K', V' of Eq. 3)
   const bool full = (m == C);
+  if constexpr (NIT > 0) {
+    // row m of K', V' is the appended pair: it takes the place of the (empty or
+    // out-of-range) cache row in the registers of the threads that cover it
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+      if (it * RPB + rb == m) kbuf[it] = knv;
+    }
+  }
 
   // ---- phase 1: scores ---------------------------------------------------------------
   {
     double qd[EPL];
 #pragma unroll
     for (int i = 0; i < EPL; ++i) qd[i] = (double)Store<T>::get(qv, i);
-    const double sqrt_d = sqrt((double)D);
+    const double inv_sqrt_d = 1.0 / sqrt((double)D);      // folded at compile time
     auto score_row = [&](int r, const Vec kv) {
       double part = 0.0;
 #pragma unroll
       for (int i = 0; i < EPL; ++i) part = fma(qd[i], (double)Store<T>::get(kv, i), part);
       part = row_sum<LPR>(part);
-      if (lr == 0 && r < rows) s_sc[r] = part / sqrt_d;
+      if (lr == 0 && r < rows) s_sc[r] = part * inv_sqrt_d;
     };
     if constexpr (NIT > 0) {
+      // Each value row is requested as soon as the key row of the same iteration has been
+      // consumed, into the registers it leaves.  Requested at kernel entry the values would
+      // share the memory queues with every block's keys and delay all scores; requested
+      // here they keep the memory system busy while the scores are computed and are in
+      // flight while wave 0 works through phase 2.
+      const __amdgpu_buffer_rsrc_t rv =
+          __builtin_amdgcn_make_buffer_rsrc(vc, 0, C * D * (int)sizeof(T), 0x00020000);
 #pragma unroll
       for (int it = 0; it < NIT; ++it) {
-        const int r = it * RPB + rb;
-        Vec kv = kbuf[it];
-        if (r >= m) kv = knv;                     // r > m: computed on the new key, not stored
-        score_row(r, kv);
+        score_row(it * RPB + rb, kbuf[it]);       // rows past m are computed but not stored
         __builtin_amdgcn_sched_barrier(0);        // one row at a time: keeps the fp64 temporaries few
+        vbuf[it] = buffer_load_nt<T>(rv, tid * 16, it * kIterBytes);
+        __builtin_amdgcn_sched_barrier(0);
       }
     } else {
       for (int r0 = 0; r0 < rows; r0 += RPB) {
@@ -361,7 +294,10 @@ __global__ __launch_bounds__(256, step_waves_per_simd(NIT)) void step_unit_kerne
       }
     }
   }
+  LESSDEC_STAMP(1);
   __syncthreads();
+  LESSDEC_STAMP(2);
+
 
   // ---- head work of the column threads: fold the pending pair into H (Eq. 4) --------------
   if (col >= 0 && fold) {
@@ -404,16 +340,17 @@ __global__ __launch_bounds__(256, step_waves_per_simd(NIT)) void step_unit_kerne
     double pscale, lscale;
     if (fz > 0.0 && M <= 0.0) {
       const double w = exp(M);
-      const double den = fz + w * S;
-      pscale = w / den;
-      lscale = 1.0 / den;
+      const double inv = 1.0 / (fz + w * S);
+      pscale = w * inv;
+      lscale = inv;
     } else {
       const double eM = (fz > 0.0) ? exp(-M) : 0.0;
-      const double den = fz * eM + S;
-      pscale = 1.0 / den;
-      lscale = eM / den;
+      const double inv = 1.0 / (fz * eM + S);
+      pscale = inv;
+      lscale = eM * inv;
     }
-    const double ascale = (a.flags & LESSDEC_FLAG_SPARSE_DENOM) ? 1.0 / S : pscale;
+    double ascale = pscale;
+    if (a.flags & LESSDEC_FLAG_SPARSE_DENOM) ascale = 1.0 / S;
 
     Cand best = cand_none();
     for (int j = lane, i = 0; j < rows; j += kWave, ++i) {
@@ -459,12 +396,6 @@ __global__ __launch_bounds__(256, step_waves_per_simd(NIT)) void step_unit_kerne
         a.pos[(size_t)u * C + ins_slot] = n;
       }
     }
-    // psi of this step's key: straight into its slot while the cache fills, else pending
-    if (lane < R) {
-      const float pn = a.psi_new[(size_t)u * R + lane];
-      if (evict) a.pend_psi[(size_t)u * R + lane] = pn;
-      else a.psi[((size_t)u * C + m) * R + lane] = pn;
-    }
     if (lane == 0) {
       s_lscale = lscale;
       s_eslot = eslot;
@@ -472,8 +403,10 @@ __global__ __launch_bounds__(256, step_waves_per_simd(NIT)) void step_unit_kerne
       if (a.evicted_pos) a.evicted_pos[u] = evict ? epos : -1;
       a.n_seen[u] = n + 1;
     }
+    LESSDEC_STAMP(3);
   }
   __syncthreads();
+  LESSDEC_STAMP(4);
 
   // ---- phase 3: p . V -----------------------------------------------------------------------
   {
@@ -482,18 +415,19 @@ __global__ __launch_bounds__(256, step_waves_per_simd(NIT)) void step_unit_kerne
 #pragma unroll
     for (int i = 0; i < EPL; ++i) o[i] = 0.f;
     auto pv_row = [&](int r, const Vec vv) {
-      const float p = (r < rows) ? s_p[r] : 0.f;
+      if (r < rows) {                                    // rows past m may hold anything
+        const float p = s_p[r];
 #pragma unroll
-      for (int i = 0; i < EPL; ++i) o[i] = fmaf(p, Store<T>::get(vv, i), o[i]);
+        for (int i = 0; i < EPL; ++i) o[i] = fmaf(p, Store<T>::get(vv, i), o[i]);
+      }
       if (r == eslot) s_ve[lr] = vv;                     // the discarded pair's value row
     };
     if constexpr (NIT > 0) {
 #pragma unroll
       for (int it = 0; it < NIT; ++it) {
-        const int r = it * RPB + rb;
         Vec vv = vbuf[it];
-        if (r >= m) vv = vnv;
-        pv_row(r, vv);
+        if (it * RPB + rb == m) vv = vnv;         // the appended pair's value row
+        pv_row(it * RPB + rb, vv);
         __builtin_amdgcn_sched_barrier(0);
       }
     } else {
@@ -504,9 +438,11 @@ __global__ __launch_bounds__(256, step_waves_per_simd(NIT)) void step_unit_kerne
         pv_row(r, vv);
       }
     }
+    float4 *so4 = reinterpret_cast<float4 *>(s_o + rb * D + lr * EPL);
 #pragma unroll
-    for (int i = 0; i < EPL; ++i) s_o[rb * D + lr * EPL + i] = o[i];
+    for (int i = 0; i < EPL / 4; ++i) so4[i] = float4{o[4 * i], o[4 * i + 1], o[4 * i + 2], o[4 * i + 3]};
   }
+  LESSDEC_STAMP(5);
   __syncthreads();
 
   // ---- phase 4: output, in-place insert, pending value row -----------------------------------
@@ -521,10 +457,10 @@ __global__ __launch_bounds__(256, step_waves_per_simd(NIT)) void step_unit_kerne
     if (R <= 16) {
 #pragma unroll
       for (int r = 0; r < 16; ++r)
-        if (r < R) fh = fmaf((float)a.f_phi[(size_t)u * R + r], hreg[r], fh);
+        if (r < R) fh = fmaf(s_f[r], hreg[r], fh);
     } else {
       const float *Hu = a.H + (size_t)u * R * D;
-      for (int r = 0; r < R; ++r) fh = fmaf((float)a.f_phi[(size_t)u * R + r], Hu[(size_t)r * D + col], fh);
+      for (int r = 0; r < R; ++r) fh = fmaf(s_f[r], Hu[(size_t)r * D + col], fh);
     }
     const double o = (double)pv + s_lscale * (double)fh;
     reinterpret_cast<T *>(a.out)[(size_t)u * D + col] = Store<T>::from_float((float)o);
@@ -534,8 +470,30 @@ __global__ __launch_bounds__(256, step_waves_per_simd(NIT)) void step_unit_kerne
       kc[(size_t)ins_slot * D + col] = kn[col];
       vc[(size_t)ins_slot * D + col] = vn[col];
     }
+    // psi of this step's key: straight into its slot while the cache fills, else pending
+    if (col < R) {
+      if (evict) a.pend_psi[(size_t)u * R + col] = psin_c;
+      else a.psi[((size_t)u * C + m) * R + col] = psin_c;
+    }
   }
+  LESSDEC_STAMP(6);
+#ifdef LESSDEC_TRACE
+  if (g_trace && threadIdx.x == 0) {
+    unsigned hwid;
+    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hwid));
+    unsigned xcc;
+    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
+    g_trace[(size_t)blockIdx.x * 8 + 7] = ((unsigned long long)xcc << 32) | hwid;
+  }
+#endif
 }
+
+#ifdef LESSDEC_TRACE
+extern "C" int lessdec_trace_set(unsigned long long *buf)
+{
+  return (int)hipMemcpyToSymbol(HIP_SYMBOL(g_trace), &buf, sizeof(buf));
+}
+#endif
 
 // Folds whatever the last step left pending, so that H, z and psi are current (Eq. 4, 5).
 template <typename T>

@@ -22,7 +22,7 @@ BASE = wl.WORKLOADS[2]
 
 def small(name, **kw):
     d = dict(name=name, batch=2, heads=3, head_dim=128, prompt=48, steps=40, n_heavy=6,
-             n_recent=6, rank=8, hidden=64, dtype="f16")
+             n_recent=6, rank=8, hidden=128, dtype="f16")
     d.update(kw)
     return BASE.scaled(**d)
 
@@ -63,15 +63,18 @@ EDGE = [
     small("no-heavy-hitters", n_heavy=0, n_recent=5, prompt=20, steps=25),
     small("one-slot-recent", n_heavy=0, n_recent=1, prompt=9, steps=12),
     small("one-slot-heavy", n_heavy=1, n_recent=0, prompt=9, steps=12),
-    small("rank-64-hidden-48", rank=64, hidden=48),
-    small("rank-1", rank=1, hidden=33),
+    small("rank-64-hidden-48", rank=64, hidden=48),          # generic feature-map path
+    small("rank-1", rank=1, hidden=33),                      # generic feature-map path
+    small("rank-16-hidden-256", rank=16, hidden=256),        # matrix-core path at its largest rank
+    small("rank-3-hidden-384", rank=3, hidden=384, batch=20, heads=2),   # ragged row chunks
+    small("hidden-64-generic", hidden=64),
     small("hidden-2048", hidden=2048, batch=1, heads=2, steps=8),
     small("odd-batch-heads", batch=3, heads=5),
     small("d64-f16", head_dim=64),
     small("d128-f32", dtype="f32"),
     small("wide-cache", n_heavy=150, n_recent=150, prompt=400, steps=24, batch=1, heads=2),
     wl.WORKLOADS[4].scaled(name="heavy-tailed-keys", batch=1, heads=4, prompt=256, steps=64,
-                           n_heavy=10, n_recent=10, hidden=64),
+                           n_heavy=10, n_recent=10, hidden=128),
 ]
 
 
@@ -90,7 +93,7 @@ def test_sparse_denominator_reading():
 
 def test_maximum_capacity():
     w = small("max-capacity", batch=1, heads=2, n_heavy=2047, n_recent=2047, prompt=4200, steps=6,
-              rank=16, hidden=64)
+              rank=16, hidden=128)
     rep = hz.run_workload(w, range(w.units))
     report_ok(rep, min_decisions=w.units * w.steps)
 
