@@ -17,8 +17,8 @@
  *  - Entry points return 0 on success and a negative LESSDEC_E* code otherwise.  Argument
  *    errors are detected on the host before anything is launched.  No C++ exception
  *    crosses this boundary.
- *  - The per-unit counter n_seen is read and advanced on the device, so a sequence of
- *    steps can be recorded into a HIP graph.
+ *  - The per-unit counter n_seen is read and advanced on the device and no call clears
+ *    memory with a memset, so a sequence of steps can be recorded into a HIP graph.
  *
  * Arithmetic: everything that decides an eviction (scores, exponentials, the
  * denominator, accumulated probabilities, z, prompt column sums) is computed in fp64;
@@ -58,7 +58,6 @@ typedef struct lessdec_desc {
   int32_t rank, hidden;           /* R <= 64, R' <= 2048 (Eq. 1, Eq. 2)                    */
   int32_t dtype;                  /* LESSDEC_DTYPE_*                                       */
   uint32_t flags;                 /* LESSDEC_FLAG_*                                        */
-  int32_t reserved;
   /* sparse cache K_C, V_C (Sec. 3.1) as slots, replaced in place (Sec. 3.2)               */
   void *k_cache, *v_cache;        /* [B,Hh,C,D] dtype, 16-byte aligned                     */
   double *acc;                    /* [B,Hh,C] accumulated attention probability (H2O)      */
@@ -70,11 +69,13 @@ typedef struct lessdec_desc {
   double *z;                      /* [B,Hh,R]                                              */
   int32_t *n_seen;                /* [B,Hh] tokens seen so far by each unit                */
   /* write-behind part of the state: lessdec_step leaves the fold of the pair it discarded
-     (Eq. 4, Eq. 5) to the head of the next step, where it costs no latency.  Until then the
-     pair is parked here; lessdec_state_sync folds it on request.                          */
+     (Eq. 4, Eq. 5) to the head of the next step, where it costs no latency (the psi of the
+     discarded slot is only addressable once the eviction is known).  Until then the pair is
+     parked here; lessdec_state_sync folds it on request.                                  */
   int32_t *pend_slot;             /* [B,Hh] -1: nothing pending                            */
   void *pend_v;                   /* [B,Hh,D] dtype, value row of the pending pair         */
-  float *pend_psi;                /* [B,Hh,R] psi of the last step's key                   */
+  float *pend_psi;                /* [B,Hh,R] psi of the last step's key, which is written
+                                     into its slot together with the pending fold          */
   /* feature-map weights, per head (Eq. 1, Eq. 2), dtype, stored output-major like a linear
      layer's weight: row i of W?1 holds the D input weights of hidden unit i, i.e. each
      array is the transpose of the matrix of the same name in the equations.  16-byte

@@ -31,7 +31,7 @@ class Desc(C.Structure):
         ("batch", C.c_int32), ("heads", C.c_int32), ("head_dim", C.c_int32),
         ("n_heavy", C.c_int32), ("n_recent", C.c_int32),
         ("rank", C.c_int32), ("hidden", C.c_int32),
-        ("dtype", C.c_int32), ("flags", C.c_uint32), ("reserved", C.c_int32),
+        ("dtype", C.c_int32), ("flags", C.c_uint32),
         ("k_cache", C.c_void_p), ("v_cache", C.c_void_p),
         ("acc", C.c_void_p), ("pos", C.c_void_p), ("psi", C.c_void_p),
         ("H", C.c_void_p), ("z", C.c_void_p), ("n_seen", C.c_void_p),

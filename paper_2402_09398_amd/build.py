@@ -10,7 +10,7 @@ HERE = Path(__file__).resolve().parent
 ROOT = HERE.parent
 CSRC = HERE / "csrc"
 LIB = HERE / "liblessdec.so"
-SOURCES = ["lessdec_api.hip", "lessdec_featmap.hip", "lessdec_mlp.hip", "lessdec_step.hip",
+SOURCES = ["lessdec_api.hip", "lessdec_featmap.hip", "lessdec_mlp.hip", "lessdec_step.hip", "lessdec_wpu.hip",
            "lessdec_prefill.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

@@ -36,11 +36,11 @@ bool shape_ok(const lessdec_desc *d, Shape *s)
   return true;
 }
 
-// Workspace: [ f_phi U*R f64 | psi_new U*R f32 | part_phi (R'/128)*U*16 f32 |
+// Workspace: [ f_phi U*R f64 | f_psi U*R f32 |
 //              prefill: rowmax, rowsum, colsum U*P f64 | slot_of U*P i32 | psi_all U*P*R f32 ],
 // every part 256-byte aligned.
 struct Workspace {
-  size_t off_fphi, off_psinew, off_partphi, off_rowmax, off_rowsum, off_colsum, off_slot,
+  size_t off_fphi, off_fpsi, off_rowmax, off_rowsum, off_colsum, off_slot,
       off_psiall, total;
 };
 
@@ -49,9 +49,7 @@ Workspace carve(const Shape &s, size_t P)
   Workspace w;
   size_t o = 0;
   w.off_fphi = o; o = align_up(o + s.U * s.R * sizeof(double), 256);
-  w.off_psinew = o; o = align_up(o + s.U * s.R * sizeof(float), 256);
-  const size_t nparts = (s.Rp + kMlpPartHidden - 1) / kMlpPartHidden;
-  w.off_partphi = o; o = align_up(o + nparts * s.U * kMlpPartStride * sizeof(float), 256);
+  w.off_fpsi = o; o = align_up(o + s.U * s.R * sizeof(float), 256);
   w.off_rowmax = o; o = align_up(o + s.U * P * sizeof(double), 256);
   w.off_rowsum = o; o = align_up(o + s.U * P * sizeof(double), 256);
   w.off_colsum = o; o = align_up(o + s.U * P * sizeof(double), 256);
@@ -84,15 +82,15 @@ int check_desc(const lessdec_desc *d, Shape *s, size_t P)
 StepArgs state_args(const lessdec_desc *desc, const Shape &s)
 {
   StepArgs a;
-  a.C = (int)s.C; a.Nh = desc->n_heavy; a.Nr = desc->n_recent; a.R = desc->rank;
+  a.C = (int)s.C; a.Nh = desc->n_heavy; a.Nr = desc->n_recent; a.R = desc->rank; a.Rp = desc->hidden;
   a.flags = desc->flags;
   a.k_cache = desc->k_cache; a.v_cache = desc->v_cache; a.acc = desc->acc; a.pos = desc->pos;
   a.psi = desc->psi; a.H = desc->H; a.z = desc->z; a.n_seen = desc->n_seen;
   a.pend_slot = desc->pend_slot; a.pend_v = desc->pend_v; a.pend_psi = desc->pend_psi;
   a.q = a.k = a.v = nullptr; a.out = nullptr; a.evicted_pos = nullptr;
-  a.f_phi = nullptr; a.psi_new = nullptr;
-  a.part_phi = nullptr; a.nparts = 0;
-  a.U = (int)s.U;
+  a.U = (int)s.U; a.Hh = desc->heads; a.B = desc->batch;
+  a.f_phi = nullptr; a.f_psi = nullptr;
+  a.Wq1 = desc->Wq1; a.Wq2 = desc->Wq2; a.Wk1 = desc->Wk1; a.Wk2 = desc->Wk2; a.Wk3 = desc->Wk3;
   return a;
 }
 
@@ -121,7 +119,7 @@ int lessdec_state_sync(const lessdec_desc *desc, void *hip_stream)
   int rc = check_desc(desc, &s, 0);
   if (rc) return rc;
   const StepArgs a = state_args(desc, s);
-  return launch_state_sync(a, (int)s.U, desc->dtype, desc->head_dim, (hipStream_t)hip_stream) == hipSuccess
+  return launch_state_sync(a, desc->dtype, desc->head_dim, (hipStream_t)hip_stream) == hipSuccess
              ? LESSDEC_OK : LESSDEC_EHIP;
 }
 
@@ -136,38 +134,24 @@ int lessdec_step(const lessdec_desc *desc, const void *q, const void *k, const v
       !aligned(evicted_pos, 4))
     return LESSDEC_EINVAL;
   hipStream_t st = (hipStream_t)hip_stream;
+  StepArgs a = state_args(desc, s);
+  a.q = q; a.k = k; a.v = v; a.out = out; a.evicted_pos = evicted_pos;
+  if (wpu_supported(desc->dtype, desc->head_dim, (int)s.C, desc->hidden, desc->rank))
+    return launch_step_wpu(a, desc->head_dim, st) == hipSuccess ? LESSDEC_OK : LESSDEC_EHIP;
+  // general path: phi(q), psi(k) in fp64, then one block per unit
   const Workspace w = carve(s, 0);
   char *ws = static_cast<char *>(desc->workspace);
   double *f_phi = reinterpret_cast<double *>(ws + w.off_fphi);
-  float *psi_new = reinterpret_cast<float *>(ws + w.off_psinew);
-
-  float *part_phi = reinterpret_cast<float *>(ws + w.off_partphi);
-  int nparts = 0;
-  if (mlp_mfma_supported(desc->dtype, desc->head_dim, desc->hidden, desc->rank)) {
-    MlpArgs fm;
-    fm.B = desc->batch; fm.Hh = desc->heads; fm.rpu = 1;
-    fm.D = desc->head_dim; fm.Rp = desc->hidden; fm.R = desc->rank;
-    fm.nchunk = fm.nparts = fm.n_part_blocks = 0;
-    fm.map[0] = {(const __half *)q, (const __half *)desc->Wq1, (const __half *)desc->Wq2, nullptr, part_phi};
-    fm.map[1] = {(const __half *)k, (const __half *)desc->Wk1, (const __half *)desc->Wk2,
-                 (const __half *)desc->Wk3, psi_new};
-    if (launch_mlp(fm, true, true, st) != hipSuccess) return LESSDEC_EHIP;
-    nparts = desc->hidden / kMlpPartHidden;
-  } else {
-    FeatmapArgs fa;
-    fa.B = desc->batch; fa.Hh = desc->heads; fa.rpu = 1;
-    fa.D = desc->head_dim; fa.Rp = desc->hidden; fa.R = desc->rank;
-    fa.x = q; fa.W1 = desc->Wq1; fa.W2 = desc->Wq2; fa.W3 = nullptr; fa.out = f_phi; fa.out_f64 = 1;
-    if (launch_featmap_generic(fa, desc->dtype, st) != hipSuccess) return LESSDEC_EHIP;
-    fa.x = k; fa.W1 = desc->Wk1; fa.W2 = desc->Wk2; fa.W3 = desc->Wk3; fa.out = psi_new; fa.out_f64 = 0;
-    if (launch_featmap_generic(fa, desc->dtype, st) != hipSuccess) return LESSDEC_EHIP;
-  }
-
-  StepArgs a = state_args(desc, s);
-  a.q = q; a.k = k; a.v = v; a.out = out; a.evicted_pos = evicted_pos;
-  a.f_phi = f_phi; a.psi_new = psi_new;
-  a.part_phi = part_phi; a.nparts = nparts;
-  if (launch_step(a, (int)s.U, desc->dtype, desc->head_dim, st) != hipSuccess) return LESSDEC_EHIP;
+  float *f_psi = reinterpret_cast<float *>(ws + w.off_fpsi);
+  FeatmapArgs fa;
+  fa.B = desc->batch; fa.Hh = desc->heads; fa.rpu = 1;
+  fa.D = desc->head_dim; fa.Rp = desc->hidden; fa.R = desc->rank;
+  fa.x = q; fa.W1 = desc->Wq1; fa.W2 = desc->Wq2; fa.W3 = nullptr; fa.out = f_phi; fa.out_f64 = 1;
+  if (launch_featmap_generic(fa, desc->dtype, st) != hipSuccess) return LESSDEC_EHIP;
+  fa.x = k; fa.W1 = desc->Wk1; fa.W2 = desc->Wk2; fa.W3 = desc->Wk3; fa.out = f_psi; fa.out_f64 = 0;
+  if (launch_featmap_generic(fa, desc->dtype, st) != hipSuccess) return LESSDEC_EHIP;
+  a.f_phi = f_phi; a.f_psi = f_psi;
+  if (launch_step(a, desc->dtype, desc->head_dim, st) != hipSuccess) return LESSDEC_EHIP;
   return LESSDEC_OK;
 }
 

@@ -17,8 +17,8 @@ namespace lessdec {
 template <typename T, int TM>
 __global__ __launch_bounds__(256) void featmap_generic_kernel(
     const T *__restrict__ x, const T *__restrict__ W1, const T *__restrict__ W2,
-    const T *__restrict__ W3, void *__restrict__ out, int out_f64, int B, int Hh, int rpu, int D,
-    int Rp, int R)
+    const T *__restrict__ W3, void *__restrict__ out, int out_f64,
+    int B, int Hh, int rpu, int D, int Rp, int R)
 {
   extern __shared__ double sm[];
   double *xs = sm;                 // [TM][D]
@@ -80,7 +80,7 @@ __global__ __launch_bounds__(256) void featmap_generic_kernel(
         a = fma(h2[m * R + j], (double)Store<T>::to_float(W3h[(size_t)r * R + j]), a);
       g = fabs(a);
     }
-    size_t o = (size_t)global_row(i) * R + r;
+    const size_t o = (size_t)global_row(i) * R + r;
     if (out_f64) reinterpret_cast<double *>(out)[o] = g;
     else reinterpret_cast<float *>(out)[o] = (float)g;
   }
@@ -95,15 +95,15 @@ static hipError_t launch_featmap_generic_t(const FeatmapArgs &a, hipStream_t st)
     const unsigned grid = (unsigned)(a.Hh * ((rows_head + TM - 1) / TM));
     size_t lds = sizeof(double) * TM * (size_t)(a.D + a.Rp + a.R);
     featmap_generic_kernel<T, TM><<<grid, 256, lds, st>>>(
-        (const T *)a.x, (const T *)a.W1, (const T *)a.W2, (const T *)a.W3, a.out, a.out_f64, a.B,
-        a.Hh, a.rpu, a.D, a.Rp, a.R);
+        (const T *)a.x, (const T *)a.W1, (const T *)a.W2, (const T *)a.W3, a.out, a.out_f64,
+        a.B, a.Hh, a.rpu, a.D, a.Rp, a.R);
   } else {
     constexpr int TM = 2;
     const unsigned grid = (unsigned)(a.Hh * ((rows_head + TM - 1) / TM));
     size_t lds = sizeof(double) * TM * (size_t)(a.D + a.Rp + a.R);
     featmap_generic_kernel<T, TM><<<grid, 256, lds, st>>>(
-        (const T *)a.x, (const T *)a.W1, (const T *)a.W2, (const T *)a.W3, a.out, a.out_f64, a.B,
-        a.Hh, a.rpu, a.D, a.Rp, a.R);
+        (const T *)a.x, (const T *)a.W1, (const T *)a.W2, (const T *)a.W3, a.out, a.out_f64,
+        a.B, a.Hh, a.rpu, a.D, a.Rp, a.R);
   }
   return hipGetLastError();
 }
@@ -115,8 +115,8 @@ hipError_t launch_featmap_generic(const FeatmapArgs &a, int dtype, hipStream_t s
 }
 
 // =====================================================================================
-// Reset: H = 0, z = 0, acc = 0, psi = 0, pos = -1, n_seen = 0, nothing pending (fill kernels, so the call
-// can be recorded into a HIP graph).
+// Reset: H = 0, z = 0, acc = 0, psi = 0, pos = -1, n_seen = 0, nothing pending (a fill kernel,
+// so the call can be recorded into a HIP graph).
 // =====================================================================================
 __global__ void reset_kernel(float *H, size_t nH, double *z, size_t nz, double *acc, size_t nacc,
                              int32_t *pos, size_t npos, float *psi, size_t npsi, int32_t *n_seen,

@@ -21,28 +21,21 @@ struct FeatmapArgs {
 };
 hipError_t launch_featmap_generic(const FeatmapArgs &a, int dtype, hipStream_t st);
 
-// Matrix-core feature maps (fp16 storage, D in {64,128}, R' a multiple of 128, R <= 16).
-// Row convention as above.  Two kinds of blocks in one launch:
-//  - part blocks (map[0], phi): 16 rows x 128 hidden units each, writing the layer-2
-//    pre-activation partial sums out[(part * rows + row) * 16 + r] (fp32); the reader adds
-//    the R'/128 parts and applies the last activation of Eq. 1.
-//  - full blocks (map[1], psi): 16 rows x all hidden units, writing psi [rows, R] itself.
-constexpr int kMlpPartHidden = 128;
-constexpr int kMlpPartStride = 16;      // floats per row in a partial-sum buffer
+// Matrix-core psi (Eq. 2) for many rows: fp16 storage, D in {64,128}, R' a multiple of 32,
+// R <= 16.  Row convention as above; out is [rows, R] fp32.
 struct MlpArgs {
-  struct Map {
-    const __half *x, *W1, *W2, *W3;
-    float *out;                          // parts: partial sums; full: psi [rows, R]
-  };
-  Map map[2];
+  const __half *x, *W1, *W2, *W3;
+  float *out;
   int B, Hh, rpu, D, Rp, R;
-  int nchunk, nparts, n_part_blocks;     // set by the launcher
 };
 bool mlp_mfma_supported(int dtype, int D, int Rp, int R);
-hipError_t launch_mlp(MlpArgs a, bool parts, bool fulls, hipStream_t st);
+hipError_t launch_mlp(const MlpArgs &a, hipStream_t st);
+
+// pend_slot: -1 nothing; else slot index (C = the step's own pair) | kPendNoFold
+constexpr int kPendNoFold = 1 << 30;
 
 struct StepArgs {
-  int C, Nh, Nr, R;
+  int C, Nh, Nr, R, Rp;
   uint32_t flags;
   void *k_cache, *v_cache;
   double *acc;
@@ -51,21 +44,25 @@ struct StepArgs {
   float *H;
   double *z;
   int32_t *n_seen;
-  int32_t *pend_slot;    // [U] fold left pending by the last step (see step_unit_kernel)
+  int32_t *pend_slot;    // [U] work left pending by the last step (see lessdec_step.hip)
   void *pend_v;          // [U,D] value row of the pending discarded pair
-  float *pend_psi;       // [U,R] psi of the last step's key while its slot write is pending
+  float *pend_psi;       // [U,R] psi of the last step's key
   const void *q, *k, *v;
   void *out;
   int32_t *evicted_pos;
-  // feature maps of this step's q and k: either final values (generic path) ...
-  const double *f_phi;   // [U,R] phi(q)
-  const float *psi_new;  // [U,R] psi(k)
-  // ... or layer-2 partial sums from the matrix-core path (nparts > 0)
-  const float *part_phi;              // [nparts, U, 16]
-  int nparts, U;
+  int U, Hh, B;
+  // generic path: feature maps of this step's q and k from the launches before it
+  const double *f_phi;   // [U,R]
+  const float *f_psi;    // [U,R]
+  // wave-per-unit path: the weights, for the feature maps evaluated in the same launch
+  const void *Wq1, *Wq2, *Wk1, *Wk2, *Wk3;
 };
-hipError_t launch_step(const StepArgs &a, int units, int dtype, int D, hipStream_t st);
-hipError_t launch_state_sync(const StepArgs &a, int units, int dtype, int D, hipStream_t st);
+hipError_t launch_step(const StepArgs &a, int dtype, int D, hipStream_t st);
+hipError_t launch_state_sync(const StepArgs &a, int dtype, int D, hipStream_t st);
+
+// One launch per step, one wave per unit, feature maps included (lessdec_wpu.hip).
+bool wpu_supported(int dtype, int D, int C, int Rp, int R);
+hipError_t launch_step_wpu(const StepArgs &a, int D, hipStream_t st);
 
 hipError_t launch_reset(const lessdec_desc *d, hipStream_t st);
 

@@ -339,11 +339,9 @@ static hipError_t launch_prefill_t(const PrefillArgs &a, hipStream_t st)
   if (mlp_mfma_supported(d->dtype, d->head_dim, d->hidden, d->rank)) {
     MlpArgs fm;
     fm.B = d->batch; fm.Hh = d->heads; fm.rpu = P; fm.D = d->head_dim; fm.Rp = d->hidden; fm.R = d->rank;
-    fm.nchunk = fm.nparts = fm.n_part_blocks = 0;
-    fm.map[1] = {(const __half *)a.K, (const __half *)d->Wk1, (const __half *)d->Wk2,
-                 (const __half *)d->Wk3, a.psi_all};
-    fm.map[0] = fm.map[1];
-    if ((e = launch_mlp(fm, false, true, st)) != hipSuccess) return e;
+    fm.x = (const __half *)a.K; fm.W1 = (const __half *)d->Wk1; fm.W2 = (const __half *)d->Wk2;
+    fm.W3 = (const __half *)d->Wk3; fm.out = a.psi_all;
+    if ((e = launch_mlp(fm, st)) != hipSuccess) return e;
   } else {
     FeatmapArgs fa;
     fa.x = a.K; fa.W1 = d->Wk1; fa.W2 = d->Wk2; fa.W3 = d->Wk3; fa.out = a.psi_all; fa.out_f64 = 0;

@@ -1,0 +1,98 @@
+// Wave-level helpers shared by the decode-step kernels (gfx950, wave64): DPP reductions,
+// non-temporal 16-byte loads, and the encoding of the work a step leaves pending.
+#pragma once
+
+#include "lessdec_common.h"
+#include "lessdec_internal.h"
+
+namespace lessdec {
+
+typedef unsigned int u4v __attribute__((ext_vector_type(4)));
+
+// ---- cross-lane helpers (DPP within 16-lane rows, readlane across rows) -------------------
+template <int CTRL>
+__device__ inline int dpp_mov(int x)
+{
+  return __builtin_amdgcn_update_dpp(0, x, CTRL, 0xf, 0xf, true);
+}
+template <int CTRL>
+__device__ inline double dpp_mov(double x)
+{
+  return __hiloint2double(dpp_mov<CTRL>(__double2hiint(x)), dpp_mov<CTRL>(__double2loint(x)));
+}
+// All-reduce over the 16 lanes of a DPP row: quad_perm [1,0,3,2], quad_perm [2,3,0,1],
+// row_ror 4, row_ror 8.  Every lane ends with the row's result.
+template <typename V, typename Op>
+__device__ inline V row16_allreduce(V v, Op op)
+{
+  v = op(v, dpp_mov<0xB1>(v));
+  v = op(v, dpp_mov<0x4E>(v));
+  v = op(v, dpp_mov<0x124>(v));
+  v = op(v, dpp_mov<0x128>(v));
+  return v;
+}
+__device__ inline int readlane_v(int x, int l) { return __builtin_amdgcn_readlane(x, l); }
+__device__ inline double readlane_v(double x, int l)
+{
+  return __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(x), l),
+                          __builtin_amdgcn_readlane(__double2loint(x), l));
+}
+// All-reduce over the wave, combined in the fixed order ((row0, row1), row2), row3.
+template <typename V, typename Op>
+__device__ inline V wave_allreduce(V v, Op op)
+{
+  v = row16_allreduce(v, op);
+  return op(op(op(readlane_v(v, 0), readlane_v(v, 16)), readlane_v(v, 32)), readlane_v(v, 48));
+}
+struct OpAdd { __device__ double operator()(double a, double b) const { return a + b; } };
+struct OpMax { __device__ double operator()(double a, double b) const { return fmax(a, b); } };
+struct OpMin { __device__ double operator()(double a, double b) const { return fmin(a, b); } };
+struct OpMinI { __device__ int operator()(int a, int b) const { return a < b ? a : b; } };
+
+template <int LPR>
+__device__ inline double row_sum(double v)
+{
+  if constexpr (LPR == 16) {
+    return row16_allreduce(v, OpAdd{});
+  } else {
+#pragma unroll
+    for (int o = LPR / 2; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+  }
+}
+
+template <typename T>
+__device__ inline typename Store<T>::Vec load_vec_nt(const T *p)
+{
+  typename Store<T>::Vec v;
+  const u4v t = __builtin_nontemporal_load(reinterpret_cast<const u4v *>(p));
+  __builtin_memcpy(&v.raw, &t, 16);
+  return v;
+}
+template <typename T>
+__device__ inline typename Store<T>::Vec buffer_load_nt(__amdgpu_buffer_rsrc_t rsrc, int voffset, int soffset)
+{
+  typename Store<T>::Vec v;
+  const u4v t = __builtin_amdgcn_raw_buffer_load_b128(rsrc, voffset, soffset, 2 /* nt */);
+  __builtin_memcpy(&v.raw, &t, 16);
+  return v;
+}
+
+// The pending work a step leaves behind (pend_slot): -1 nothing; otherwise the low bits name
+// a slot.  Slot s < C: psi[s] is to become the psi of the key that now sits there (kept in
+// pend_psi) and, unless kPendNoFold is set, the pair that sat there before (psi still in
+// psi[s], value row in pend_v) is to be folded into H, z.  Slot C: the step's own pair was
+// discarded; its psi is the pend_psi entry itself.
+struct Pending {
+  int slot;
+  bool fold;
+};
+__device__ inline Pending decode_pending(int ps)
+{
+  Pending p;
+  p.slot = ps < 0 ? -1 : (ps & 0xffff);
+  p.fold = ps >= 0 && !(ps & kPendNoFold);
+  return p;
+}
+
+}  // namespace lessdec

@@ -1,0 +1,464 @@
+// Decode step (Algorithm 1), streaming form: one launch per step, one wave per unit, the
+// feature maps of the step (Eq. 1, Eq. 2) evaluated inside the same launch.
+#include "lessdec_mlp.h"
+#include "lessdec_wave.h"
+
+namespace lessdec {
+
+constexpr int kWpuUnits = 8;        // units (waves) per block
+constexpr int kWpuMaxRows = 512;    // C + 1 at most
+
+// =====================================================================================
+// A block is 8 waves = 8 units that share a head: batch rows 8 * chunk .. 8 * chunk + 7 of
+// head h (head fastest in blockIdx, so with Hh a multiple of 8 all blocks of a head run on
+// one XCD and share its L2 copy of the head's weights).
+//
+// Feature maps, whole block, on the matrix cores: the 8 rows of the block's units (padded to
+// the 16 of an MFMA tile) are the shared operand; wave w takes the groups of 32 hidden units
+// w, w + 8, ..; the layer-2 sums of the waves meet in the LDS behind a barrier and each
+// wave finishes the map of its own unit in fp64.  phi(q) is evaluated in the prologue: its
+// weight tiles are requested first, the head of the key stream right behind them, so the
+// HBM stream runs while the matrix cores work.  psi(k), which nothing needs before the next
+// step, is evaluated in the epilogue: its weight tiles are requested behind the last keys
+// and wait in registers until the value stream has drained.
+//
+// In between every wave is on its own, with no barrier and nothing shared:
+//
+// A cache row is LPR = D / 8 lanes of 16 bytes, one load instruction covers RPI = 64 / LPR
+// rows.  The rows of K and then of V pass through a ring of DEPTH registers per lane: each
+// load is consumed in issue order and its register re-used for the load DEPTH places
+// ahead, so the number of bytes in flight is constant (DEPTH KiB per wave) from the first
+// key row to the last value row; the value stream starts while the last keys are scored
+// and keeps coming during the softmax.  The K part of the stream is padded to a multiple
+// of DEPTH so that ring positions are compile-time constants; loads past the live rows are
+// requested out of the buffer's range, which returns zeros and moves no data.
+//
+// Phase 1  scores s_j = q . K_j / sqrt(D) of the live slots and the appended key as they
+//          arrive: fp64, reduced over the LPR lanes of a row by DPP, parked in the LDS.
+// Phase 2  lane j owns rows j, j + 64, ..: shift, exponentials, denominator of Eq. 3 with
+//          phi(q) z^T, probabilities, H2O score accumulation, eviction argmin (Sec. 2.1);
+//          fold of the pair the previous step discarded into H, z (Eq. 4, Eq. 5), which
+//          Eq. 3 of this step must already see.
+// Phase 3  p . V in fp32 as the value rows arrive; the value row of the discarded slot is
+//          written to pend_v by the lanes that hold it; the RPI partial rows are combined
+//          by a reduce-scatter that leaves each lane with the 8 / RPI output columns it
+//          also holds of H.
+// Phase 4  out = (p V + phi(q) H / den) (Eq. 3); the new pair goes into the freed slot
+//          (Sec. 3.2); the discarded pair is left pending for the next step.
+// =====================================================================================
+template <int D, int NR2, int RM, int DEPTH>
+__global__ __launch_bounds__(kWpuUnits * kWave) void wpu_step_kernel(const StepArgs a)
+{
+  using T = __half;
+  constexpr int EPL = 8;                   // elements per lane
+  constexpr int LPR = D / EPL;             // lanes per row
+  constexpr int RPI = kWave / LPR;         // rows per load instruction
+  constexpr int CPL = EPL / RPI;           // output columns per lane after the reduce-scatter
+  constexpr int KS = D / 32;
+  using Vec = typename Store<T>::Vec;
+
+  extern __shared__ double dyn[];
+  __shared__ float s_red[2][kWpuUnits][16][16];              // [map][wave][r][unit]
+  __shared__ float s_w3[16][17];                             // W3 of the head, [r'][r]
+
+  const int C = a.C, R = a.R, Rp = a.Rp, Hh = a.Hh;
+  const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  const int lr = lane % LPR, rb = lane / LPR;
+  const int g = lane >> 4, c = lane & 15;
+  const int h = (int)blockIdx.x % Hh, chunk = (int)blockIdx.x / Hh;
+  const int bb = chunk * kWpuUnits + wave;
+  const bool valid = bb < a.B;                               // wave-uniform
+  const int u = (valid ? bb : a.B - 1) * Hh + h;
+  const int rows_cap = (C + 2) & ~1;
+  double *s_sc = dyn + (size_t)wave * rows_cap;                                    // [C+1] scores
+  float *s_p = reinterpret_cast<float *>(dyn + (size_t)kWpuUnits * rows_cap) + (size_t)wave * rows_cap;
+
+  T *kc = reinterpret_cast<T *>(a.k_cache) + (size_t)u * C * D;
+  T *vc = reinterpret_cast<T *>(a.v_cache) + (size_t)u * C * D;
+  const T *qn = reinterpret_cast<const T *>(a.q) + (size_t)u * D;
+  const T *kn = reinterpret_cast<const T *>(a.k) + (size_t)u * D;
+  const T *vn = reinterpret_cast<const T *>(a.v) + (size_t)u * D;
+
+  // ---- requests: unit state and step inputs ---------------------------------------------------
+  const int n = a.n_seen[u];
+  const Pending pend = decode_pending(a.pend_slot[u]);
+  const int m = n < C ? n : C;          // live slots are 0..m-1 (slots fill in order)
+  const int rows = m + 1;               // + the appended pair (K', V' of Eq. 3)
+  const bool full = (m == C);
+  const Vec qv = load_vec<T>(qn + lr * EPL);
+  const Vec knv = load_vec<T>(kn + lr * EPL);
+  const Vec vnv = load_vec<T>(vn + lr * EPL);
+  double acc_pre[NR2];
+  int pos_pre[NR2];
+#pragma unroll
+  for (int i = 0; i < NR2; ++i) {
+    const int j = lane + i * kWave;
+    acc_pre[i] = (j < m) ? a.acc[(size_t)u * C + j] : 0.0;
+    pos_pre[i] = (j < m) ? a.pos[(size_t)u * C + j] : -1;
+  }
+  double z_lane = 0.0;                   // lane r < R
+  float ppsi_lane = 0.f, psie_lane = 0.f;
+  if (lane < R) {
+    z_lane = a.z[(size_t)u * R + lane];
+    ppsi_lane = a.pend_psi[(size_t)u * R + lane];
+    if (pend.fold && pend.slot < C) psie_lane = a.psi[((size_t)u * C + pend.slot) * R + lane];
+  }
+  const int col0 = lr * EPL + ((lane & 32) ? 4 : 0) + ((lane & 16) ? 2 : 0) + ((RPI == 8 && (lane & 8)) ? 1 : 0);
+  float hreg[RM][CPL];                   // this lane's columns of H (R <= RM)
+  float pend_v_c[CPL];
+#pragma unroll
+  for (int r = 0; r < RM; ++r) {
+#pragma unroll
+    for (int j = 0; j < CPL; ++j) hreg[r][j] = (r < R) ? a.H[((size_t)u * R + r) * D + col0 + j] : 0.f;
+  }
+  if ((int)threadIdx.x < R * R)
+    s_w3[threadIdx.x / R][threadIdx.x % R] =
+        __half2float(reinterpret_cast<const __half *>(a.Wk3)[(size_t)h * R * R + threadIdx.x]);
+#pragma unroll
+  for (int j = 0; j < CPL; ++j)
+    pend_v_c[j] = __half2float(reinterpret_cast<const T *>(a.pend_v)[(size_t)u * D + col0 + j]);
+
+  // ---- requests: operands of phi -----------------------------------------------------------------
+  const int bbc = chunk * kWpuUnits + c;                     // MFMA row c is the block's unit c
+  const bool rowv = c < kWpuUnits && bbc < a.B;
+  const size_t uc = (size_t)(rowv ? bbc : 0) * Hh + h;
+  const int ngrp = Rp / 32;
+  const bool g0 = wave < ngrp, g1 = wave + kWpuUnits < ngrp;
+  v8h bxq[KS];
+  MlpTiles<D> tq0, tq1;
+  {
+    const __half *Wq1 = reinterpret_cast<const __half *>(a.Wq1) + (size_t)h * Rp * D;
+    const __half *Wq2 = reinterpret_cast<const __half *>(a.Wq2) + (size_t)h * R * Rp;
+    mlp_load_row<D>(reinterpret_cast<const __half *>(a.q) + uc * D, rowv, g, bxq);
+    if (g0) tq0 = mlp_load_tiles<D>(Wq1, Wq2, Rp, R, 32 * wave, g, c);
+    if (g1) tq1 = mlp_load_tiles<D>(Wq1, Wq2, Rp, R, 32 * (wave + kWpuUnits), g, c);
+  }
+
+  // ---- requests: head of the key stream --------------------------------------------------------
+  const int nit = valid ? (rows + RPI - 1) / RPI : 0;        // load instructions per stream
+  const int nitp = (nit + DEPTH - 1) / DEPTH * DEPTH;        // K part of the stream, padded
+  const int live_bytes = valid ? m * D * (int)sizeof(T) : 0;
+  auto issue = [&](int s) -> u4v {                           // s is wave-uniform
+    const bool isk = s < nitp;
+    const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(isk ? kc : vc, 0, live_bytes, 0x00020000);
+    return __builtin_amdgcn_raw_buffer_load_b128(rs, lane * 16, (isk ? s : s - nitp) * (kWave * 16), 2 /* nt */);
+  };
+  u4v buf[DEPTH];
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int j = 0; j < DEPTH; ++j) buf[j] = issue(j);
+  __builtin_amdgcn_sched_barrier(0);
+
+  // ---- phi(q) (Eq. 1) --------------------------------------------------------------------------------
+  {
+    v4f cq = {0.f, 0.f, 0.f, 0.f};
+    if (g0) mlp_apply_tiles<D>(tq0, bxq, cq);
+    if (g1) mlp_apply_tiles<D>(tq1, bxq, cq);
+    if (ngrp > 2 * kWpuUnits) {                              // hidden widths above 512
+      const __half *Wq1 = reinterpret_cast<const __half *>(a.Wq1) + (size_t)h * Rp * D;
+      const __half *Wq2 = reinterpret_cast<const __half *>(a.Wq2) + (size_t)h * R * Rp;
+      for (int grp = wave + 2 * kWpuUnits; grp < ngrp; grp += kWpuUnits) {
+        const MlpTiles<D> t = mlp_load_tiles<D>(Wq1, Wq2, Rp, R, 32 * grp, g, c);
+        mlp_apply_tiles<D>(t, bxq, cq);
+      }
+    }
+#pragma unroll
+    for (int w = 0; w < 4; ++w) s_red[0][wave][4 * g + w][c] = cq[w];
+  }
+  __syncthreads();
+  double f_lane = 0.0;                   // phi(q), lane r < R
+  if (lane < R) {
+    double sq = 0.0;
+#pragma unroll
+    for (int w = 0; w < kWpuUnits; ++w) sq += (double)s_red[0][w][lane][wave];
+    f_lane = fabs(gelu_poly_f64(sq));                        // last activation of Eq. 1
+  }
+  if (pend.fold && pend.slot >= C) psie_lane = ppsi_lane;    // the previous step discarded its own pair
+
+  // ---- phase 1: scores as the key rows arrive -------------------------------------------------
+  if (valid) {
+    double qd[EPL];
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) qd[i] = (double)Store<T>::get(qv, i);
+    const double inv_sqrt_d = 1.0 / sqrt((double)D);      // folded at compile time
+    for (int base = 0; base < nitp; base += DEPTH) {
+#pragma unroll
+      for (int j = 0; j < DEPTH; ++j) {
+        const int s = base + j;
+        if (s < nit) {
+          const int r = s * RPI + rb;
+          Vec kv;
+          __builtin_memcpy(&kv.raw, &buf[j], 16);
+          if (r == m) kv = knv;                           // the appended key
+          double part = 0.0;
+#pragma unroll
+          for (int i = 0; i < EPL; ++i) part = fma(qd[i], (double)Store<T>::get(kv, i), part);
+          part = row_sum<LPR>(part);
+          if (lr == 0 && r < rows) s_sc[r] = part * inv_sqrt_d;
+        }
+        buf[j] = issue(s + DEPTH);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+  }
+
+  // ---- requests: operands of psi, behind the keys ---------------------------------------------------
+  v8h bxk[KS];
+  MlpTiles<D> tk0, tk1;
+  {
+    const __half *Wk1 = reinterpret_cast<const __half *>(a.Wk1) + (size_t)h * Rp * D;
+    const __half *Wk2 = reinterpret_cast<const __half *>(a.Wk2) + (size_t)h * R * Rp;
+    mlp_load_row<D>(reinterpret_cast<const __half *>(a.k) + uc * D, rowv, g, bxk);
+    if (g0) tk0 = mlp_load_tiles<D>(Wk1, Wk2, Rp, R, 32 * wave, g, c);
+    if (g1) tk1 = mlp_load_tiles<D>(Wk1, Wk2, Rp, R, 32 * (wave + kWpuUnits), g, c);
+  }
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+  if (valid) {
+    // ---- phase 2: softmax with the low-rank term, H2O bookkeeping, eviction choice -------------
+    int eslot = -1, ins_slot;
+    double lscale;
+    {
+      double sc[NR2];
+      double M = -__builtin_inf();
+#pragma unroll
+      for (int i = 0; i < NR2; ++i) {
+        const int j = lane + i * kWave;
+        sc[i] = j < rows ? s_sc[j] : -__builtin_inf();
+        M = fmax(M, sc[i]);
+      }
+      M = wave_allreduce(M, OpMax{});
+      double S = 0.0;
+#pragma unroll
+      for (int i = 0; i < NR2; ++i) {
+        const int j = lane + i * kWave;
+        sc[i] = j < rows ? exp(sc[i] - M) : 0.0;
+        S += sc[i];
+      }
+      S = wave_allreduce(S, OpAdd{});                       // sparse part of the denominator, shifted
+      // pending fold of z (Eq. 5), then phi(q) z^T
+      if (lane < R) {
+        if (pend.fold) {
+          z_lane += (double)psie_lane;
+          a.z[(size_t)u * R + lane] = z_lane;
+        }
+        if (pend.slot >= 0 && pend.slot < C) a.psi[((size_t)u * C + pend.slot) * R + lane] = ppsi_lane;
+      }
+      const double fz = wave_allreduce(f_lane * z_lane, OpAdd{});
+      // den = phi(q) z^T + sum_j e^{s_j}, in whichever scaling cannot overflow:
+      //   M > 0 (or no low-rank term): everything times e^{-M};  M <= 0: unscaled, e^{M} <= 1
+      double pscale;
+      if (fz > 0.0 && M <= 0.0) {
+        const double w = exp(M);
+        const double inv = 1.0 / (fz + w * S);
+        pscale = w * inv;
+        lscale = inv;
+      } else {
+        const double eM = (fz > 0.0) ? exp(-M) : 0.0;
+        const double inv = 1.0 / (fz * eM + S);
+        pscale = inv;
+        lscale = eM * inv;
+      }
+      double ascale = pscale;
+      if (a.flags & LESSDEC_FLAG_SPARSE_DENOM) ascale = 1.0 / S;
+
+      Cand best = cand_none();
+#pragma unroll
+      for (int i = 0; i < NR2; ++i) {
+        const int j = lane + i * kWave;
+        if (j < rows) {
+          const double e = sc[i];
+          s_p[j] = (float)(e * pscale);
+          double na = e * ascale;
+          int pj = n;
+          if (j < m) {
+            na += acc_pre[i];
+            pj = pos_pre[i];
+          }
+          sc[i] = na;
+          if (full) {
+            const bool is_cand = (j < m) ? (pj <= n - a.Nr) : (a.Nr == 0);
+            const Cand cnd{na, pj, j};
+            if (is_cand && cand_less(cnd, best)) best = cnd;
+          }
+        }
+      }
+      // argmin over (score, position): smallest score, then the oldest among equals
+      int epos = -1;
+      if (full) {
+        const double amin = wave_allreduce(best.acc, OpMin{});
+        const int pmin = wave_allreduce(best.acc == amin ? best.pos : INT_MAX, OpMinI{});
+        const unsigned long long win = __ballot(best.acc == amin && best.pos == pmin && best.slot >= 0);
+        if (win != 0ull) {
+          eslot = __builtin_amdgcn_readlane(best.slot, __ffsll((long long)win) - 1);
+          epos = pmin;
+        }
+      }
+      const bool evict = eslot >= 0;                         // eslot == m: the new pair itself
+      ins_slot = full ? ((evict && eslot < m) ? eslot : -1) : m;
+#pragma unroll
+      for (int i = 0; i < NR2; ++i) {
+        const int j = lane + i * kWave;
+        if (j < m) {
+          if (j != ins_slot) a.acc[(size_t)u * C + j] = sc[i];
+        } else if (j == m && ins_slot >= 0) {
+          a.acc[(size_t)u * C + ins_slot] = sc[i];
+          a.pos[(size_t)u * C + ins_slot] = n;
+        }
+      }
+      if (lane == 0) {
+        // what the next step has to finish: fold of the discarded pair and / or the slot write
+        a.pend_slot[u] = evict ? (eslot < m ? eslot : C) : (m | kPendNoFold);
+        if (a.evicted_pos) a.evicted_pos[u] = evict ? epos : -1;
+        a.n_seen[u] = n + 1;
+      }
+    }
+    // fold of the pending pair into H (Eq. 4), then phi(q) H for this lane's columns
+    float fh[CPL];
+#pragma unroll
+    for (int j = 0; j < CPL; ++j) fh[j] = 0.f;
+    {
+      const float f32 = (float)f_lane;
+      float *Hu = a.H + (size_t)u * R * D;
+#pragma unroll
+      for (int r = 0; r < RM; ++r) {
+        if (r < R) {
+          const float fr = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(f32), r));
+          const float pe = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(psie_lane), r));
+#pragma unroll
+          for (int j = 0; j < CPL; ++j) {
+            if (pend.fold) {
+              hreg[r][j] = fmaf(pe, pend_v_c[j], hreg[r][j]);
+              Hu[(size_t)r * D + col0 + j] = hreg[r][j];
+            }
+            fh[j] = fmaf(fr, hreg[r][j], fh[j]);
+          }
+        }
+      }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+    // ---- phase 3: p . V as the value rows arrive ------------------------------------------------
+    float o[EPL];
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) o[i] = 0.f;
+    for (int base = 0; base < nit; base += DEPTH) {
+#pragma unroll
+      for (int j = 0; j < DEPTH; ++j) {
+        const int s = base + j;
+        if (s < nit) {
+          const int r = s * RPI + rb;
+          Vec vv;
+          __builtin_memcpy(&vv.raw, &buf[j], 16);
+          if (r == m) vv = vnv;                              // the appended pair's value row
+          if (r < rows) {
+            const float p = s_p[r];
+#pragma unroll
+            for (int i = 0; i < EPL; ++i) o[i] = fmaf(p, Store<T>::get(vv, i), o[i]);
+          }
+          if (r == eslot)                                    // the discarded pair's value row
+            *reinterpret_cast<uint4 *>(reinterpret_cast<T *>(a.pend_v) + (size_t)u * D + lr * EPL) = vv.raw;
+        }
+        buf[j] = issue(nitp + s + DEPTH);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+    // reduce-scatter over the RPI row groups: after the stage with partner distance x, a lane
+    // keeps the half of its columns selected by its bit x
+    {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const bool hi = lane & 32;
+        const float send = hi ? o[i] : o[i + 4], keep = hi ? o[i + 4] : o[i];
+        o[i] = keep + __shfl_xor(send, 32);
+      }
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        const bool hi = lane & 16;
+        const float send = hi ? o[i] : o[i + 2], keep = hi ? o[i + 2] : o[i];
+        o[i] = keep + __shfl_xor(send, 16);
+      }
+      if constexpr (RPI == 8) {
+        const bool hi = lane & 8;
+        const float send = hi ? o[0] : o[1], keep = hi ? o[1] : o[0];
+        o[0] = keep + __shfl_xor(send, 8);
+      }
+    }
+
+    // ---- phase 4: output, in-place insert ---------------------------------------------------------
+    T res[CPL];
+#pragma unroll
+    for (int j = 0; j < CPL; ++j) res[j] = __float2half_rn((float)((double)o[j] + lscale * (double)fh[j]));
+    T *dst = reinterpret_cast<T *>(a.out) + (size_t)u * D + col0;
+    if constexpr (CPL == 2) *reinterpret_cast<__half2 *>(dst) = __half2{res[0], res[1]};
+    else dst[0] = res[0];
+    if (ins_slot >= 0 && rb == 0) {
+      *reinterpret_cast<uint4 *>(kc + (size_t)ins_slot * D + lr * EPL) = knv.raw;
+      *reinterpret_cast<uint4 *>(vc + (size_t)ins_slot * D + lr * EPL) = vnv.raw;
+    }
+  }
+
+  // ---- psi(k) (Eq. 2), for the next step ---------------------------------------------------------------
+  {
+    v4f ck = {0.f, 0.f, 0.f, 0.f};
+    if (g0) mlp_apply_tiles<D>(tk0, bxk, ck);
+    if (g1) mlp_apply_tiles<D>(tk1, bxk, ck);
+    if (ngrp > 2 * kWpuUnits) {
+      const __half *Wk1 = reinterpret_cast<const __half *>(a.Wk1) + (size_t)h * Rp * D;
+      const __half *Wk2 = reinterpret_cast<const __half *>(a.Wk2) + (size_t)h * R * Rp;
+      for (int grp = wave + 2 * kWpuUnits; grp < ngrp; grp += kWpuUnits) {
+        const MlpTiles<D> t = mlp_load_tiles<D>(Wk1, Wk2, Rp, R, 32 * grp, g, c);
+        mlp_apply_tiles<D>(t, bxk, ck);
+      }
+    }
+#pragma unroll
+    for (int w = 0; w < 4; ++w) s_red[1][wave][4 * g + w][c] = ck[w];
+  }
+  __syncthreads();
+  {
+    double sk = 0.0;
+    if (lane < R) {
+#pragma unroll
+      for (int w = 0; w < kWpuUnits; ++w) sk += (double)s_red[1][w][lane][wave];
+    }
+    const double h2 = lane < R ? gelu_poly_f64(sk) : 0.0;
+    double acc3 = 0.0;
+#pragma unroll
+    for (int j = 0; j < RM; ++j)
+      if (j < R) acc3 = fma(readlane_v(h2, j), (double)s_w3[lane & 15][j], acc3);
+    if (valid && lane < R) a.pend_psi[(size_t)u * R + lane] = (float)fabs(acc3);
+  }
+}
+
+bool wpu_supported(int dtype, int D, int C, int Rp, int R)
+{
+  return dtype == LESSDEC_DTYPE_F16 && (D == 64 || D == 128) && R <= 16 && Rp % 32 == 0 && Rp >= 32 &&
+         C + 1 <= kWpuMaxRows;
+}
+
+template <int D, int RM>
+static hipError_t launch_step_wpu_t(const StepArgs &a, hipStream_t st)
+{
+  constexpr int kDepth = 8;
+  const int rows_cap = (a.C + 2) & ~1;
+  const size_t lds = (size_t)kWpuUnits * rows_cap * (sizeof(double) + sizeof(float));
+  const unsigned grid = (unsigned)(a.Hh * ((a.B + kWpuUnits - 1) / kWpuUnits));
+  const int rows = a.C + 1;
+  if (rows <= 2 * kWave) wpu_step_kernel<D, 2, RM, kDepth><<<grid, kWpuUnits * kWave, lds, st>>>(a);
+  else if (rows <= 4 * kWave) wpu_step_kernel<D, 4, RM, kDepth><<<grid, kWpuUnits * kWave, lds, st>>>(a);
+  else wpu_step_kernel<D, kWpuMaxRows / kWave, RM, kDepth><<<grid, kWpuUnits * kWave, lds, st>>>(a);
+  return hipGetLastError();
+}
+
+hipError_t launch_step_wpu(const StepArgs &a, int D, hipStream_t st)
+{
+  if (D == 64) return launch_step_wpu_t<64, 16>(a, st);
+  return a.R <= 8 ? launch_step_wpu_t<128, 8>(a, st) : launch_step_wpu_t<128, 16>(a, st);
+}
+
+}  // namespace lessdec

@@ -20,8 +20,10 @@ from paper_2402_09398_amd import workloads as wl
 
 OUT_TOL = 2e-3        # attention outputs, relative to the row's largest magnitude
 STATE_TOL = 1e-4      # H and z, same norm
-SCORE_TOL = 2e-7      # accumulated scores: fp64 sums on both sides, but psi (hence z and the
-                      # denominator) carries the GPU's fp32 rounding of 6e-8 per feature
+SCORE_TOL = 5e-7      # accumulated scores, relative: fp64 sums on both sides, but phi(q) z^T enters the
+                      # denominator with the GPU's fp32 feature maps (a few tens of roundings of
+                      # 6e-8 each, up to 1e-6 on a feature) weighted by the low-rank share of the
+                      # denominator (0.1 .. 0.3 here); half the eviction exemption gap
 TIE_GAP = 1e-6        # exemption for the eviction choice
 
 

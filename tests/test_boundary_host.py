@@ -27,8 +27,8 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_descriptor_layout_matches_header():
-    # 10 int32 fields, 17 pointers, 1 size_t on LP64
-    assert C.sizeof(binding.Desc) == 10 * 4 + 17 * 8 + 8
+    # 9 int32 fields (padded to 8 bytes), 17 pointers, 1 size_t on LP64
+    assert C.sizeof(binding.Desc) == 9 * 4 + 4 + 17 * 8 + 8
     assert binding.Desc.k_cache.offset == 40
 
 
