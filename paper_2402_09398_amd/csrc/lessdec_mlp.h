@@ -27,7 +27,7 @@ typedef float v4f __attribute__((ext_vector_type(4)));
 template <int D>
 struct MlpTiles {
   v8h a0[D / 32], a1[D / 32];   // layer 1: hidden units hid + c and hid + 16 + c, all of D
-  v8h a2;                       // layer 2: row r = c of W2, the 8 hidden units of lane group g
+  v8h a2;                       // layer 2: row r = c of W2 (c < R), the 8 hidden units of lane group g
 };
 
 template <int D>
@@ -42,13 +42,12 @@ __device__ inline MlpTiles<D> mlp_load_tiles(const __half *__restrict__ W1, cons
     t.a0[ks] = *reinterpret_cast<const v8h *>(w1a + 32 * ks);
     t.a1[ks] = *reinterpret_cast<const v8h *>(w1b + 32 * ks);
   }
-  t.a2 = v8h{0, 0, 0, 0, 0, 0, 0, 0};
-  if (c < R) {
-    const __half *w2 = W2 + (size_t)c * Rp + hid + 4 * g;
-    const v4h lo = *reinterpret_cast<const v4h *>(w2);
-    const v4h hi = *reinterpret_cast<const v4h *>(w2 + 16);
-    t.a2 = v8h{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-  }
+  // rows c >= R of the layer-2 operand repeat row 0 (loaded unconditionally, so that nothing
+  // here waits for a load): their outputs are never looked at
+  const __half *w2 = W2 + (size_t)(c < R ? c : 0) * Rp + hid + 4 * g;
+  const v4h lo = *reinterpret_cast<const v4h *>(w2);
+  const v4h hi = *reinterpret_cast<const v4h *>(w2 + 16);
+  t.a2 = v8h{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
   return t;
 }
 
@@ -79,13 +78,14 @@ __device__ inline void mlp_apply_tiles(const MlpTiles<D> &t, const v8h (&bx)[D /
   c2 = __builtin_amdgcn_mfma_f32_16x16x32_f16(t.a2, blo, c2, 0, 0, 0);
 }
 
-// Row c of x (or zeros) in operand order.
+// Row c of x in operand order.  The loads are unconditional (a select on validity would
+// make the caller wait for them on the spot): for a padding row pass any readable row, its
+// outputs are never looked at.
 template <int D>
-__device__ inline void mlp_load_row(const __half *xr, bool valid, int g, v8h (&bx)[D / 32])
+__device__ inline void mlp_load_row(const __half *xr, int g, v8h (&bx)[D / 32])
 {
 #pragma unroll
-  for (int ks = 0; ks < D / 32; ++ks)
-    bx[ks] = valid ? *reinterpret_cast<const v8h *>(xr + 32 * ks + 8 * g) : v8h{0, 0, 0, 0, 0, 0, 0, 0};
+  for (int ks = 0; ks < D / 32; ++ks) bx[ks] = *reinterpret_cast<const v8h *>(xr + 32 * ks + 8 * g);
 }
 
 }  // namespace lessdec

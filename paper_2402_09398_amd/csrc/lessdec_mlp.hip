@@ -26,8 +26,7 @@ __global__ __launch_bounds__(256) void mlp_psi_kernel(const MlpArgs a)
   v8h bx[D / 32];
   {
     const long i = (long)chunk * 16 + c;
-    const bool valid = i < rows_head;
-    mlp_load_row<D>(a.x + (valid ? global_row(i) : 0) * D, valid, g, bx);
+    mlp_load_row<D>(a.x + (i < rows_head ? global_row(i) : 0) * D, g, bx);    // padding: any row
   }
   v4f c2 = {0.f, 0.f, 0.f, 0.f};
   for (int grp = wave; grp < Rp / 32; grp += 4) {

@@ -80,49 +80,23 @@ __global__ __launch_bounds__(kWpuUnits * kWave) void wpu_step_kernel(const StepA
   const T *kn = reinterpret_cast<const T *>(a.k) + (size_t)u * D;
   const T *vn = reinterpret_cast<const T *>(a.v) + (size_t)u * D;
 
-  // ---- requests: unit state and step inputs ---------------------------------------------------
-  const int n = a.n_seen[u];
-  const Pending pend = decode_pending(a.pend_slot[u]);
-  const int m = n < C ? n : C;          // live slots are 0..m-1 (slots fill in order)
-  const int rows = m + 1;               // + the appended pair (K', V' of Eq. 3)
-  const bool full = (m == C);
+  // ---- requests, in the order they are wanted back ------------------------------------------------
+  // 1. the step's rows and the head of the key stream (bounded by the capacity: the number of
+  //    live rows is not known yet; rows past them are fetched only while the cache fills)
   const Vec qv = load_vec<T>(qn + lr * EPL);
   const Vec knv = load_vec<T>(kn + lr * EPL);
-  const Vec vnv = load_vec<T>(vn + lr * EPL);
-  double acc_pre[NR2];
-  int pos_pre[NR2];
+  const int cap_bytes = valid ? C * D * (int)sizeof(T) : 0;
+  u4v buf[DEPTH];
+  {
+    const __amdgpu_buffer_rsrc_t rk = __builtin_amdgcn_make_buffer_rsrc(kc, 0, cap_bytes, 0x00020000);
 #pragma unroll
-  for (int i = 0; i < NR2; ++i) {
-    const int j = lane + i * kWave;
-    acc_pre[i] = (j < m) ? a.acc[(size_t)u * C + j] : 0.0;
-    pos_pre[i] = (j < m) ? a.pos[(size_t)u * C + j] : -1;
+    for (int j = 0; j < DEPTH; ++j)
+      buf[j] = __builtin_amdgcn_raw_buffer_load_b128(rk, lane * 16, j * (kWave * 16), 2 /* nt */);
   }
-  double z_lane = 0.0;                   // lane r < R
-  float ppsi_lane = 0.f, psie_lane = 0.f;
-  if (lane < R) {
-    z_lane = a.z[(size_t)u * R + lane];
-    ppsi_lane = a.pend_psi[(size_t)u * R + lane];
-    if (pend.fold && pend.slot < C) psie_lane = a.psi[((size_t)u * C + pend.slot) * R + lane];
-  }
-  const int col0 = lr * EPL + ((lane & 32) ? 4 : 0) + ((lane & 16) ? 2 : 0) + ((RPI == 8 && (lane & 8)) ? 1 : 0);
-  float hreg[RM][CPL];                   // this lane's columns of H (R <= RM)
-  float pend_v_c[CPL];
-#pragma unroll
-  for (int r = 0; r < RM; ++r) {
-#pragma unroll
-    for (int j = 0; j < CPL; ++j) hreg[r][j] = (r < R) ? a.H[((size_t)u * R + r) * D + col0 + j] : 0.f;
-  }
-  if ((int)threadIdx.x < R * R)
-    s_w3[threadIdx.x / R][threadIdx.x % R] =
-        __half2float(reinterpret_cast<const __half *>(a.Wk3)[(size_t)h * R * R + threadIdx.x]);
-#pragma unroll
-  for (int j = 0; j < CPL; ++j)
-    pend_v_c[j] = __half2float(reinterpret_cast<const T *>(a.pend_v)[(size_t)u * D + col0 + j]);
-
-  // ---- requests: operands of phi -----------------------------------------------------------------
+  __builtin_amdgcn_sched_barrier(0);
+  // 2. operands of phi
   const int bbc = chunk * kWpuUnits + c;                     // MFMA row c is the block's unit c
-  const bool rowv = c < kWpuUnits && bbc < a.B;
-  const size_t uc = (size_t)(rowv ? bbc : 0) * Hh + h;
+  const size_t uc = (size_t)((c < kWpuUnits && bbc < a.B) ? bbc : chunk * kWpuUnits) * Hh + h;
   const int ngrp = Rp / 32;
   const bool g0 = wave < ngrp, g1 = wave + kWpuUnits < ngrp;
   v8h bxq[KS];
@@ -130,59 +104,51 @@ __global__ __launch_bounds__(kWpuUnits * kWave) void wpu_step_kernel(const StepA
   {
     const __half *Wq1 = reinterpret_cast<const __half *>(a.Wq1) + (size_t)h * Rp * D;
     const __half *Wq2 = reinterpret_cast<const __half *>(a.Wq2) + (size_t)h * R * Rp;
-    mlp_load_row<D>(reinterpret_cast<const __half *>(a.q) + uc * D, rowv, g, bxq);
+    mlp_load_row<D>(reinterpret_cast<const __half *>(a.q) + uc * D, g, bxq);
     if (g0) tq0 = mlp_load_tiles<D>(Wq1, Wq2, Rp, R, 32 * wave, g, c);
     if (g1) tq1 = mlp_load_tiles<D>(Wq1, Wq2, Rp, R, 32 * (wave + kWpuUnits), g, c);
   }
+  __builtin_amdgcn_sched_barrier(0);
+  // 3. unit state and the rest of the step's inputs (wanted from phase 2 on)
+  const int n = a.n_seen[u];
+  const Pending pend = decode_pending(a.pend_slot[u]);
+  const int m = n < C ? n : C;          // live slots are 0..m-1 (slots fill in order)
+  const int rows = m + 1;               // + the appended pair (K', V' of Eq. 3)
+  const bool full = (m == C);
+  // (every load below is unconditional, from a clamped address where the wanted one may not
+  // exist: a load under a condition would make the first use of anything requested before
+  // it wait for it as well)
+  double acc_pre[NR2];
+  int pos_pre[NR2];
+#pragma unroll
+  for (int i = 0; i < NR2; ++i) {
+    const int j = lane + i * kWave;
+    const size_t idx = (size_t)u * C + (j < C ? j : C - 1);
+    acc_pre[i] = a.acc[idx];
+    pos_pre[i] = a.pos[idx];
+  }
+  const int rl = lane < R ? lane : R - 1;
+  double z_lane = a.z[(size_t)u * R + rl];                   // lane r < R
+  const float ppsi_lane = a.pend_psi[(size_t)u * R + rl];
+  float psie_lane = a.psi[((size_t)u * C + (pend.slot >= 0 && pend.slot < C ? pend.slot : 0)) * R + rl];
+  __builtin_amdgcn_sched_barrier(0);
 
-  // ---- requests: head of the key stream --------------------------------------------------------
+  // The stream: position s < nitp is load s of K, position nitp + t is load t of V.
   const int nit = valid ? (rows + RPI - 1) / RPI : 0;        // load instructions per stream
-  const int nitp = (nit + DEPTH - 1) / DEPTH * DEPTH;        // K part of the stream, padded
+  const int nitp = nit > 0 ? (nit + DEPTH - 1) / DEPTH * DEPTH : DEPTH;   // K part of the stream, padded
   const int live_bytes = valid ? m * D * (int)sizeof(T) : 0;
   auto issue = [&](int s) -> u4v {                           // s is wave-uniform
     const bool isk = s < nitp;
     const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(isk ? kc : vc, 0, live_bytes, 0x00020000);
     return __builtin_amdgcn_raw_buffer_load_b128(rs, lane * 16, (isk ? s : s - nitp) * (kWave * 16), 2 /* nt */);
   };
-  u4v buf[DEPTH];
-  __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-  for (int j = 0; j < DEPTH; ++j) buf[j] = issue(j);
-  __builtin_amdgcn_sched_barrier(0);
 
-  // ---- phi(q) (Eq. 1) --------------------------------------------------------------------------------
-  {
-    v4f cq = {0.f, 0.f, 0.f, 0.f};
-    if (g0) mlp_apply_tiles<D>(tq0, bxq, cq);
-    if (g1) mlp_apply_tiles<D>(tq1, bxq, cq);
-    if (ngrp > 2 * kWpuUnits) {                              // hidden widths above 512
-      const __half *Wq1 = reinterpret_cast<const __half *>(a.Wq1) + (size_t)h * Rp * D;
-      const __half *Wq2 = reinterpret_cast<const __half *>(a.Wq2) + (size_t)h * R * Rp;
-      for (int grp = wave + 2 * kWpuUnits; grp < ngrp; grp += kWpuUnits) {
-        const MlpTiles<D> t = mlp_load_tiles<D>(Wq1, Wq2, Rp, R, 32 * grp, g, c);
-        mlp_apply_tiles<D>(t, bxq, cq);
-      }
-    }
-#pragma unroll
-    for (int w = 0; w < 4; ++w) s_red[0][wave][4 * g + w][c] = cq[w];
-  }
-  __syncthreads();
+  // ---- phase 1: scores as the key rows arrive; phi(q) (Eq. 1) after the first pass --------------
   double f_lane = 0.0;                   // phi(q), lane r < R
-  if (lane < R) {
-    double sq = 0.0;
-#pragma unroll
-    for (int w = 0; w < kWpuUnits; ++w) sq += (double)s_red[0][w][lane][wave];
-    f_lane = fabs(gelu_poly_f64(sq));                        // last activation of Eq. 1
-  }
-  if (pend.fold && pend.slot >= C) psie_lane = ppsi_lane;    // the previous step discarded its own pair
-
-  // ---- phase 1: scores as the key rows arrive -------------------------------------------------
-  if (valid) {
-    double qd[EPL];
-#pragma unroll
-    for (int i = 0; i < EPL; ++i) qd[i] = (double)Store<T>::get(qv, i);
+  {
     const double inv_sqrt_d = 1.0 / sqrt((double)D);      // folded at compile time
-    for (int base = 0; base < nitp; base += DEPTH) {
+    int base = 0;
+    do {                                                   // nitp >= DEPTH, also for an idle wave
 #pragma unroll
       for (int j = 0; j < DEPTH; ++j) {
         const int s = base + j;
@@ -193,34 +159,75 @@ __global__ __launch_bounds__(kWpuUnits * kWave) void wpu_step_kernel(const StepA
           if (r == m) kv = knv;                           // the appended key
           double part = 0.0;
 #pragma unroll
-          for (int i = 0; i < EPL; ++i) part = fma(qd[i], (double)Store<T>::get(kv, i), part);
+          for (int i = 0; i < EPL; ++i)             // q is converted again every time: registers are dearer
+            part = fma((double)Store<T>::get(qv, i), (double)Store<T>::get(kv, i), part);
           part = row_sum<LPR>(part);
           if (lr == 0 && r < rows) s_sc[r] = part * inv_sqrt_d;
         }
         buf[j] = issue(s + DEPTH);
         __builtin_amdgcn_sched_barrier(0);
       }
-    }
+      if (base == 0) {
+        // The weight tiles have been back for a while (they were requested before the loads
+        // this pass re-issued), and the ring is full again: the stream goes on while the
+        // matrix cores work and the block meets at its barrier.
+        v4f cq = {0.f, 0.f, 0.f, 0.f};
+        if (g0) mlp_apply_tiles<D>(tq0, bxq, cq);
+        if (g1) mlp_apply_tiles<D>(tq1, bxq, cq);
+        if (ngrp > 2 * kWpuUnits) {                          // hidden widths above 512
+          const __half *Wq1 = reinterpret_cast<const __half *>(a.Wq1) + (size_t)h * Rp * D;
+          const __half *Wq2 = reinterpret_cast<const __half *>(a.Wq2) + (size_t)h * R * Rp;
+          for (int grp = wave + 2 * kWpuUnits; grp < ngrp; grp += kWpuUnits) {
+            const MlpTiles<D> t = mlp_load_tiles<D>(Wq1, Wq2, Rp, R, 32 * grp, g, c);
+            mlp_apply_tiles<D>(t, bxq, cq);
+          }
+        }
+#pragma unroll
+        for (int w = 0; w < 4; ++w) s_red[0][wave][4 * g + w][c] = cq[w];
+        __syncthreads();
+        if (lane < R) {
+          double sq = 0.0;
+#pragma unroll
+          for (int w = 0; w < kWpuUnits; ++w) sq += (double)s_red[0][w][lane][wave];
+          f_lane = fabs(gelu_poly_f64(sq));                  // last activation of Eq. 1
+        }
+      }
+    } while ((base += DEPTH) < nitp);
   }
 
   // ---- requests: operands of psi, behind the keys ---------------------------------------------------
   v8h bxk[KS];
   MlpTiles<D> tk0, tk1;
+  const int w3i = (int)threadIdx.x < R * R ? (int)threadIdx.x : 0;
+  const __half w3v = reinterpret_cast<const __half *>(a.Wk3)[(size_t)h * R * R + w3i];   // W3 of the head
   {
     const __half *Wk1 = reinterpret_cast<const __half *>(a.Wk1) + (size_t)h * Rp * D;
     const __half *Wk2 = reinterpret_cast<const __half *>(a.Wk2) + (size_t)h * R * Rp;
-    mlp_load_row<D>(reinterpret_cast<const __half *>(a.k) + uc * D, rowv, g, bxk);
+    mlp_load_row<D>(reinterpret_cast<const __half *>(a.k) + uc * D, g, bxk);
     if (g0) tk0 = mlp_load_tiles<D>(Wk1, Wk2, Rp, R, 32 * wave, g, c);
     if (g1) tk1 = mlp_load_tiles<D>(Wk1, Wk2, Rp, R, 32 * (wave + kWpuUnits), g, c);
   }
+  const Vec vnv = load_vec<T>(vn + lr * EPL);
+  // this lane's columns of H and of the pending value row: wanted after the value stream
+  const int col0 = lr * EPL + ((lane & 32) ? 4 : 0) + ((lane & 16) ? 2 : 0) + ((RPI == 8 && (lane & 8)) ? 1 : 0);
+  float hreg[RM][CPL];                   // (R <= RM)
+#pragma unroll
+  for (int r = 0; r < RM; ++r) {
+    const float *hp = a.H + ((size_t)u * R + (r < R ? r : R - 1)) * D + col0;
+#pragma unroll
+    for (int j = 0; j < CPL; ++j) hreg[r][j] = hp[j];
+  }
+  T pend_v_h[CPL];
+#pragma unroll
+  for (int j = 0; j < CPL; ++j) pend_v_h[j] = reinterpret_cast<const T *>(a.pend_v)[(size_t)u * D + col0 + j];
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
   __builtin_amdgcn_wave_barrier();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
+  int eslot = -1, ins_slot = -1;
+  double lscale = 0.0;
   if (valid) {
     // ---- phase 2: softmax with the low-rank term, H2O bookkeeping, eviction choice -------------
-    int eslot = -1, ins_slot;
-    double lscale;
     {
       double sc[NR2];
       double M = -__builtin_inf();
@@ -240,6 +247,9 @@ __global__ __launch_bounds__(kWpuUnits * kWave) void wpu_step_kernel(const StepA
       }
       S = wave_allreduce(S, OpAdd{});                       // sparse part of the denominator, shifted
       // pending fold of z (Eq. 5), then phi(q) z^T
+      if (lane >= R) z_lane = 0.0;
+      if (!pend.fold) psie_lane = 0.f;
+      else if (pend.slot >= C) psie_lane = ppsi_lane;        // the previous step discarded its own pair
       if (lane < R) {
         if (pend.fold) {
           z_lane += (double)psie_lane;
@@ -316,38 +326,18 @@ __global__ __launch_bounds__(kWpuUnits * kWave) void wpu_step_kernel(const StepA
         a.n_seen[u] = n + 1;
       }
     }
-    // fold of the pending pair into H (Eq. 4), then phi(q) H for this lane's columns
-    float fh[CPL];
-#pragma unroll
-    for (int j = 0; j < CPL; ++j) fh[j] = 0.f;
-    {
-      const float f32 = (float)f_lane;
-      float *Hu = a.H + (size_t)u * R * D;
-#pragma unroll
-      for (int r = 0; r < RM; ++r) {
-        if (r < R) {
-          const float fr = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(f32), r));
-          const float pe = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(psie_lane), r));
-#pragma unroll
-          for (int j = 0; j < CPL; ++j) {
-            if (pend.fold) {
-              hreg[r][j] = fmaf(pe, pend_v_c[j], hreg[r][j]);
-              Hu[(size_t)r * D + col0 + j] = hreg[r][j];
-            }
-            fh[j] = fmaf(fr, hreg[r][j], fh[j]);
-          }
-        }
-      }
-    }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  }
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
-    // ---- phase 3: p . V as the value rows arrive ------------------------------------------------
-    float o[EPL];
+  // ---- phase 3: p . V as the value rows arrive; psi(k) (Eq. 2) after the first pass -----------------
+  float o[EPL];
 #pragma unroll
-    for (int i = 0; i < EPL; ++i) o[i] = 0.f;
-    for (int base = 0; base < nit; base += DEPTH) {
+  for (int i = 0; i < EPL; ++i) o[i] = 0.f;
+  {
+    int base = 0;
+    do {                                                     // one pass at least, also for an idle wave
 #pragma unroll
       for (int j = 0; j < DEPTH; ++j) {
         const int s = base + j;
@@ -366,6 +356,63 @@ __global__ __launch_bounds__(kWpuUnits * kWave) void wpu_step_kernel(const StepA
         }
         buf[j] = issue(nitp + s + DEPTH);
         __builtin_amdgcn_sched_barrier(0);
+      }
+      if (base == 0) {
+        // psi of this step's key, which the next step will want: same scheme as phi above
+        v4f ck = {0.f, 0.f, 0.f, 0.f};
+        if (g0) mlp_apply_tiles<D>(tk0, bxk, ck);
+        if (g1) mlp_apply_tiles<D>(tk1, bxk, ck);
+        if (ngrp > 2 * kWpuUnits) {
+          const __half *Wk1 = reinterpret_cast<const __half *>(a.Wk1) + (size_t)h * Rp * D;
+          const __half *Wk2 = reinterpret_cast<const __half *>(a.Wk2) + (size_t)h * R * Rp;
+          for (int grp = wave + 2 * kWpuUnits; grp < ngrp; grp += kWpuUnits) {
+            const MlpTiles<D> t = mlp_load_tiles<D>(Wk1, Wk2, Rp, R, 32 * grp, g, c);
+            mlp_apply_tiles<D>(t, bxk, ck);
+          }
+        }
+#pragma unroll
+        for (int w = 0; w < 4; ++w) s_red[1][wave][4 * g + w][c] = ck[w];
+        if ((int)threadIdx.x < R * R) s_w3[threadIdx.x / R][threadIdx.x % R] = __half2float(w3v);
+        __syncthreads();
+        double sk = 0.0;
+        if (lane < R) {
+#pragma unroll
+          for (int w = 0; w < kWpuUnits; ++w) sk += (double)s_red[1][w][lane][wave];
+        }
+        const double h2 = lane < R ? gelu_poly_f64(sk) : 0.0;
+        double acc3 = 0.0;
+#pragma unroll
+        for (int j = 0; j < RM; ++j)
+          if (j < R) acc3 = fma(readlane_v(h2, j), (double)s_w3[lane & 15][j], acc3);
+        if (valid && lane < R) a.pend_psi[(size_t)u * R + lane] = (float)fabs(acc3);
+      }
+    } while ((base += DEPTH) < nit);
+  }
+  if (valid) {
+    // fold of the pending pair into H (Eq. 4), then phi(q) H for this lane's columns
+    float fh[CPL];
+#pragma unroll
+    for (int j = 0; j < CPL; ++j) fh[j] = 0.f;
+    {
+      const float f32 = (float)f_lane;
+      float pend_v_c[CPL];
+#pragma unroll
+      for (int j = 0; j < CPL; ++j) pend_v_c[j] = __half2float(pend_v_h[j]);
+      float *Hu = a.H + (size_t)u * R * D;
+#pragma unroll
+      for (int r = 0; r < RM; ++r) {
+        if (r < R) {
+          const float fr = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(f32), r));
+          const float pe = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(psie_lane), r));
+#pragma unroll
+          for (int j = 0; j < CPL; ++j) {
+            if (pend.fold) {
+              hreg[r][j] = fmaf(pe, pend_v_c[j], hreg[r][j]);
+              Hu[(size_t)r * D + col0 + j] = hreg[r][j];
+            }
+            fh[j] = fmaf(fr, hreg[r][j], fh[j]);
+          }
+        }
       }
     }
     // reduce-scatter over the RPI row groups: after the stage with partner distance x, a lane
@@ -403,36 +450,6 @@ __global__ __launch_bounds__(kWpuUnits * kWave) void wpu_step_kernel(const StepA
     }
   }
 
-  // ---- psi(k) (Eq. 2), for the next step ---------------------------------------------------------------
-  {
-    v4f ck = {0.f, 0.f, 0.f, 0.f};
-    if (g0) mlp_apply_tiles<D>(tk0, bxk, ck);
-    if (g1) mlp_apply_tiles<D>(tk1, bxk, ck);
-    if (ngrp > 2 * kWpuUnits) {
-      const __half *Wk1 = reinterpret_cast<const __half *>(a.Wk1) + (size_t)h * Rp * D;
-      const __half *Wk2 = reinterpret_cast<const __half *>(a.Wk2) + (size_t)h * R * Rp;
-      for (int grp = wave + 2 * kWpuUnits; grp < ngrp; grp += kWpuUnits) {
-        const MlpTiles<D> t = mlp_load_tiles<D>(Wk1, Wk2, Rp, R, 32 * grp, g, c);
-        mlp_apply_tiles<D>(t, bxk, ck);
-      }
-    }
-#pragma unroll
-    for (int w = 0; w < 4; ++w) s_red[1][wave][4 * g + w][c] = ck[w];
-  }
-  __syncthreads();
-  {
-    double sk = 0.0;
-    if (lane < R) {
-#pragma unroll
-      for (int w = 0; w < kWpuUnits; ++w) sk += (double)s_red[1][w][lane][wave];
-    }
-    const double h2 = lane < R ? gelu_poly_f64(sk) : 0.0;
-    double acc3 = 0.0;
-#pragma unroll
-    for (int j = 0; j < RM; ++j)
-      if (j < R) acc3 = fma(readlane_v(h2, j), (double)s_w3[lane & 15][j], acc3);
-    if (valid && lane < R) a.pend_psi[(size_t)u * R + lane] = (float)fabs(acc3);
-  }
 }
 
 bool wpu_supported(int dtype, int D, int C, int Rp, int R)
