@@ -36,11 +36,11 @@ bool shape_ok(const lessdec_desc *d, Shape *s)
   return true;
 }
 
-// Workspace: [ f_phi U*R f64 | f_psi U*R f32 |
+// Workspace: [ f_phi U*R f64 | f_psi U*R f32 | mlp_parts 2*ceil(R'/64)*U*16 f32 |
 //              prefill: rowmax, rowsum, colsum U*P f64 | slot_of U*P i32 | psi_all U*P*R f32 ],
 // every part 256-byte aligned.
 struct Workspace {
-  size_t off_fphi, off_fpsi, off_rowmax, off_rowsum, off_colsum, off_slot,
+  size_t off_fphi, off_fpsi, off_parts, off_rowmax, off_rowsum, off_colsum, off_slot,
       off_psiall, total;
 };
 
@@ -50,6 +50,7 @@ Workspace carve(const Shape &s, size_t P)
   size_t o = 0;
   w.off_fphi = o; o = align_up(o + s.U * s.R * sizeof(double), 256);
   w.off_fpsi = o; o = align_up(o + s.U * s.R * sizeof(float), 256);
+  w.off_parts = o; o = align_up(o + 2 * (size_t)mlp_nparts((int)s.Rp) * s.U * 16 * sizeof(float), 256);
   w.off_rowmax = o; o = align_up(o + s.U * P * sizeof(double), 256);
   w.off_rowsum = o; o = align_up(o + s.U * P * sizeof(double), 256);
   w.off_colsum = o; o = align_up(o + s.U * P * sizeof(double), 256);
@@ -89,8 +90,8 @@ StepArgs state_args(const lessdec_desc *desc, const Shape &s)
   a.pend_slot = desc->pend_slot; a.pend_v = desc->pend_v; a.pend_psi = desc->pend_psi;
   a.q = a.k = a.v = nullptr; a.out = nullptr; a.evicted_pos = nullptr;
   a.U = (int)s.U; a.Hh = desc->heads; a.B = desc->batch;
-  a.f_phi = nullptr; a.f_psi = nullptr;
-  a.Wq1 = desc->Wq1; a.Wq2 = desc->Wq2; a.Wk1 = desc->Wk1; a.Wk2 = desc->Wk2; a.Wk3 = desc->Wk3;
+  a.f_phi = nullptr; a.f_psi = nullptr; a.mlp_parts = nullptr;
+  a.Wk3 = desc->Wk3;
   return a;
 }
 
@@ -136,11 +137,21 @@ int lessdec_step(const lessdec_desc *desc, const void *q, const void *k, const v
   hipStream_t st = (hipStream_t)hip_stream;
   StepArgs a = state_args(desc, s);
   a.q = q; a.k = k; a.v = v; a.out = out; a.evicted_pos = evicted_pos;
-  if (wpu_supported(desc->dtype, desc->head_dim, (int)s.C, desc->hidden, desc->rank))
-    return launch_step_wpu(a, desc->head_dim, st) == hipSuccess ? LESSDEC_OK : LESSDEC_EHIP;
-  // general path: phi(q), psi(k) in fp64, then one block per unit
   const Workspace w = carve(s, 0);
   char *ws = static_cast<char *>(desc->workspace);
+  if (wpu_supported(desc->dtype, desc->head_dim, (int)s.C, desc->hidden, desc->rank)) {
+    // matrix-core feature maps up to the layer-2 sums, then one wave per unit
+    MlpPartsArgs fm;
+    fm.q = (const __half *)q; fm.k = (const __half *)k;
+    fm.Wq1 = (const __half *)desc->Wq1; fm.Wq2 = (const __half *)desc->Wq2;
+    fm.Wk1 = (const __half *)desc->Wk1; fm.Wk2 = (const __half *)desc->Wk2;
+    fm.out = reinterpret_cast<float *>(ws + w.off_parts);
+    fm.B = desc->batch; fm.Hh = desc->heads; fm.D = desc->head_dim; fm.Rp = desc->hidden; fm.R = desc->rank;
+    if (launch_mlp_parts(fm, st) != hipSuccess) return LESSDEC_EHIP;
+    a.mlp_parts = fm.out;
+    return launch_step_wpu(a, desc->head_dim, st) == hipSuccess ? LESSDEC_OK : LESSDEC_EHIP;
+  }
+  // general path: phi(q), psi(k) in fp64, then one block per unit
   double *f_phi = reinterpret_cast<double *>(ws + w.off_fphi);
   float *f_psi = reinterpret_cast<float *>(ws + w.off_fpsi);
   FeatmapArgs fa;

@@ -31,6 +31,19 @@ struct MlpArgs {
 bool mlp_mfma_supported(int dtype, int D, int Rp, int R);
 hipError_t launch_mlp(const MlpArgs &a, hipStream_t st);
 
+// Both feature maps of one decode step, up to the layer-2 sums: phi of q and psi of k for
+// every unit, the hidden units split into parts of kMlpPartHidden.  out[((map * nparts +
+// part) * U + u) * 16 + r] is part's share of the layer-2 pre-activation r of unit u (map 0:
+// q with Wq, map 1: k with Wk); the reader adds the parts and finishes Eq. 1 / Eq. 2.
+constexpr int kMlpPartHidden = 64;
+struct MlpPartsArgs {
+  const __half *q, *k, *Wq1, *Wq2, *Wk1, *Wk2;
+  float *out;
+  int B, Hh, D, Rp, R;
+};
+__host__ __device__ inline int mlp_nparts(int Rp) { return (Rp + kMlpPartHidden - 1) / kMlpPartHidden; }
+hipError_t launch_mlp_parts(const MlpPartsArgs &a, hipStream_t st);
+
 // pend_slot: -1 nothing; else slot index (C = the step's own pair) | kPendNoFold
 constexpr int kPendNoFold = 1 << 30;
 
@@ -54,13 +67,14 @@ struct StepArgs {
   // generic path: feature maps of this step's q and k from the launches before it
   const double *f_phi;   // [U,R]
   const float *f_psi;    // [U,R]
-  // wave-per-unit path: the weights, for the feature maps evaluated in the same launch
-  const void *Wq1, *Wq2, *Wk1, *Wk2, *Wk3;
+  // wave-per-unit path: layer-2 sums of both feature maps by parts (launch_mlp_parts), and W3
+  const float *mlp_parts;
+  const void *Wk3;
 };
 hipError_t launch_step(const StepArgs &a, int dtype, int D, hipStream_t st);
 hipError_t launch_state_sync(const StepArgs &a, int dtype, int D, hipStream_t st);
 
-// One launch per step, one wave per unit, feature maps included (lessdec_wpu.hip).
+// One wave per unit, K and V streamed through a register ring (lessdec_wpu.hip).
 bool wpu_supported(int dtype, int D, int C, int Rp, int R);
 hipError_t launch_step_wpu(const StepArgs &a, int D, hipStream_t st);
 

@@ -49,6 +49,44 @@ __global__ __launch_bounds__(256) void mlp_psi_kernel(const MlpArgs a)
   }
 }
 
+// Decode step: both maps for every unit, by parts of 64 hidden units.  One block = one
+// (head, map, part, chunk of 64 batch rows); its four waves take 16 rows each and the same
+// two groups of 32 hidden units, so the head's weights are read once per 64 rows.  Head
+// fastest in blockIdx: with Hh a multiple of 8 a head's blocks, and later its readers, share
+// an XCD and its L2.
+template <int D>
+__global__ __launch_bounds__(256) void mlp_parts_kernel(const MlpPartsArgs a)
+{
+  const int wave = threadIdx.x / 64, l = threadIdx.x % 64, g = l / 16, c = l % 16;
+  const int Hh = a.Hh, Rp = a.Rp, R = a.R, nparts = mlp_nparts(Rp);
+  int b = blockIdx.x;
+  const int h = b % Hh; b /= Hh;
+  const int map = b % 2; b /= 2;
+  const int part = b % nparts;
+  const int chunk = b / nparts;
+  const __half *x = map ? a.k : a.q;
+  const __half *W1 = (map ? a.Wk1 : a.Wq1) + (size_t)h * Rp * D;
+  const __half *W2 = (map ? a.Wk2 : a.Wq2) + (size_t)h * R * Rp;
+  const int row = chunk * 64 + wave * 16 + c;              // batch row of MFMA column c
+  const bool rowv = row < a.B;
+  const size_t u = (size_t)(rowv ? row : 0) * Hh + h;
+  v8h bx[D / 32];
+  mlp_load_row<D>(x + u * D, g, bx);                       // padding: any row
+  const int hid = part * kMlpPartHidden;
+  const bool two = hid + 32 < Rp;                          // the last part may hold one group
+  const MlpTiles<D> t0 = mlp_load_tiles<D>(W1, W2, Rp, R, hid, g, c);
+  const MlpTiles<D> t1 = mlp_load_tiles<D>(W1, W2, Rp, R, two ? hid + 32 : hid, g, c);
+  v4f c2 = {0.f, 0.f, 0.f, 0.f};
+  mlp_apply_tiles<D>(t0, bx, c2);
+  if (two) mlp_apply_tiles<D>(t1, bx, c2);
+  // c2[w]: output r = 4 g + w of row c
+  if (rowv) {
+    const size_t U = (size_t)a.B * Hh;
+    float *dst = a.out + (((size_t)map * nparts + part) * U + u) * 16 + 4 * g;
+    *reinterpret_cast<float4 *>(dst) = float4{c2[0], c2[1], c2[2], c2[3]};
+  }
+}
+
 bool mlp_mfma_supported(int dtype, int D, int Rp, int R)
 {
   return dtype == LESSDEC_DTYPE_F16 && (D == 64 || D == 128) && Rp % 32 == 0 && Rp >= 32 && R <= 16;
@@ -60,6 +98,14 @@ hipError_t launch_mlp(const MlpArgs &a, hipStream_t st)
   const unsigned grid = (unsigned)(((rows_head + 15) / 16) * a.Hh);
   if (a.D == 128) mlp_psi_kernel<128><<<grid, 256, 0, st>>>(a);
   else mlp_psi_kernel<64><<<grid, 256, 0, st>>>(a);
+  return hipGetLastError();
+}
+
+hipError_t launch_mlp_parts(const MlpPartsArgs &a, hipStream_t st)
+{
+  const unsigned grid = (unsigned)(a.Hh * 2 * mlp_nparts(a.Rp) * ((a.B + 63) / 64));
+  if (a.D == 128) mlp_parts_kernel<128><<<grid, 256, 0, st>>>(a);
+  else mlp_parts_kernel<64><<<grid, 256, 0, st>>>(a);
   return hipGetLastError();
 }
 

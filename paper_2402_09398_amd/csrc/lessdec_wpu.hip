@@ -1,6 +1,5 @@
-// Decode step (Algorithm 1), streaming form: one launch per step, one wave per unit, the
-// feature maps of the step (Eq. 1, Eq. 2) evaluated inside the same launch.
-#include "lessdec_mlp.h"
+// Decode step (Algorithm 1), streaming form: one wave per unit.  The layer-2 sums of the step's
+// feature maps come from the matrix-core launch before it (lessdec_mlp.hip).
 #include "lessdec_wave.h"
 
 namespace lessdec {
@@ -10,19 +9,9 @@ constexpr int kWpuMaxRows = 512;    // C + 1 at most
 
 // =====================================================================================
 // A block is 8 waves = 8 units that share a head: batch rows 8 * chunk .. 8 * chunk + 7 of
-// head h (head fastest in blockIdx, so with Hh a multiple of 8 all blocks of a head run on
-// one XCD and share its L2 copy of the head's weights).
-//
-// Feature maps, whole block, on the matrix cores: the 8 rows of the block's units (padded to
-// the 16 of an MFMA tile) are the shared operand; wave w takes the groups of 32 hidden units
-// w, w + 8, ..; the layer-2 sums of the waves meet in the LDS behind a barrier and each
-// wave finishes the map of its own unit in fp64.  phi(q) is evaluated in the prologue: its
-// weight tiles are requested first, the head of the key stream right behind them, so the
-// HBM stream runs while the matrix cores work.  psi(k), which nothing needs before the next
-// step, is evaluated in the epilogue: its weight tiles are requested behind the last keys
-// and wait in registers until the value stream has drained.
-//
-// In between every wave is on its own, with no barrier and nothing shared:
+// head h (head fastest in blockIdx, so with Hh a multiple of 8 the units of a head run on
+// the XCD whose L2 holds the feature-map sums written for them).  The waves of a block share
+// nothing and never meet at a barrier; each is on its own from the first instruction:
 //
 // A cache row is LPR = D / 8 lanes of 16 bytes, one load instruction covers RPI = 64 / LPR
 // rows.  The rows of K and then of V pass through a ring of DEPTH registers per lane: each
@@ -35,16 +24,19 @@ constexpr int kWpuMaxRows = 512;    // C + 1 at most
 //
 // Phase 1  scores s_j = q . K_j / sqrt(D) of the live slots and the appended key as they
 //          arrive: fp64, reduced over the LPR lanes of a row by DPP, parked in the LDS.
+//          After the first pass over the ring, phi(q) and psi(k) are finished from their
+//          layer-2 sums (last activations of Eq. 1 and Eq. 2, W3) in fp64.
 // Phase 2  lane j owns rows j, j + 64, ..: shift, exponentials, denominator of Eq. 3 with
 //          phi(q) z^T, probabilities, H2O score accumulation, eviction argmin (Sec. 2.1);
-//          fold of the pair the previous step discarded into H, z (Eq. 4, Eq. 5), which
-//          Eq. 3 of this step must already see.
+//          fold of the pair the previous step discarded into z (Eq. 5), which Eq. 3 of this
+//          step must already see.
 // Phase 3  p . V in fp32 as the value rows arrive; the value row of the discarded slot is
 //          written to pend_v by the lanes that hold it; the RPI partial rows are combined
 //          by a reduce-scatter that leaves each lane with the 8 / RPI output columns it
 //          also holds of H.
-// Phase 4  out = (p V + phi(q) H / den) (Eq. 3); the new pair goes into the freed slot
-//          (Sec. 3.2); the discarded pair is left pending for the next step.
+// Phase 4  fold of the pending pair into H (Eq. 4); out = p V + phi(q) H / den (Eq. 3); the
+//          new pair goes into the freed slot (Sec. 3.2); the discarded pair is left pending
+//          for the next step.
 // =====================================================================================
 template <int D, int NR2, int RM, int DEPTH>
 __global__ __launch_bounds__(kWpuUnits * kWave) void wpu_step_kernel(const StepArgs a)
@@ -54,22 +46,19 @@ __global__ __launch_bounds__(kWpuUnits * kWave) void wpu_step_kernel(const StepA
   constexpr int LPR = D / EPL;             // lanes per row
   constexpr int RPI = kWave / LPR;         // rows per load instruction
   constexpr int CPL = EPL / RPI;           // output columns per lane after the reduce-scatter
-  constexpr int KS = D / 32;
+  constexpr int NP = 8;                    // feature-map parts requested up front (R' <= 512)
   using Vec = typename Store<T>::Vec;
 
   extern __shared__ double dyn[];
-  __shared__ float s_red[2][kWpuUnits][16][16];              // [map][wave][r][unit]
-  __shared__ float s_w3[16][17];                             // W3 of the head, [r'][r]
 
-  const int C = a.C, R = a.R, Rp = a.Rp, Hh = a.Hh;
+  const int C = a.C, R = a.R, Hh = a.Hh;
   const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
   const int lr = lane % LPR, rb = lane / LPR;
-  const int g = lane >> 4, c = lane & 15;
   const int h = (int)blockIdx.x % Hh, chunk = (int)blockIdx.x / Hh;
   const int bb = chunk * kWpuUnits + wave;
-  const bool valid = bb < a.B;                               // wave-uniform
-  const int u = (valid ? bb : a.B - 1) * Hh + h;
+  if (bb >= a.B) return;                                     // wave-uniform; the waves share nothing
+  const int u = bb * Hh + h;
   const int rows_cap = (C + 2) & ~1;
   double *s_sc = dyn + (size_t)wave * rows_cap;                                    // [C+1] scores
   float *s_p = reinterpret_cast<float *>(dyn + (size_t)kWpuUnits * rows_cap) + (size_t)wave * rows_cap;
@@ -81,43 +70,43 @@ __global__ __launch_bounds__(kWpuUnits * kWave) void wpu_step_kernel(const StepA
   const T *vn = reinterpret_cast<const T *>(a.v) + (size_t)u * D;
 
   // ---- requests, in the order they are wanted back ------------------------------------------------
+  // Every load here is unconditional, from a clamped address where the wanted one may not
+  // exist: a load under a condition makes the first use of anything requested before it
+  // wait for it as well, and a wait in mid-stream drains the ring.
   // 1. the step's rows and the head of the key stream (bounded by the capacity: the number of
   //    live rows is not known yet; rows past them are fetched only while the cache fills)
   const Vec qv = load_vec<T>(qn + lr * EPL);
   const Vec knv = load_vec<T>(kn + lr * EPL);
-  const int cap_bytes = valid ? C * D * (int)sizeof(T) : 0;
   u4v buf[DEPTH];
   {
-    const __amdgpu_buffer_rsrc_t rk = __builtin_amdgcn_make_buffer_rsrc(kc, 0, cap_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rk =
+        __builtin_amdgcn_make_buffer_rsrc(kc, 0, C * D * (int)sizeof(T), 0x00020000);
 #pragma unroll
     for (int j = 0; j < DEPTH; ++j)
       buf[j] = __builtin_amdgcn_raw_buffer_load_b128(rk, lane * 16, j * (kWave * 16), 2 /* nt */);
   }
   __builtin_amdgcn_sched_barrier(0);
-  // 2. operands of phi
-  const int bbc = chunk * kWpuUnits + c;                     // MFMA row c is the block's unit c
-  const size_t uc = (size_t)((c < kWpuUnits && bbc < a.B) ? bbc : chunk * kWpuUnits) * Hh + h;
-  const int ngrp = Rp / 32;
-  const bool g0 = wave < ngrp, g1 = wave + kWpuUnits < ngrp;
-  v8h bxq[KS];
-  MlpTiles<D> tq0, tq1;
-  {
-    const __half *Wq1 = reinterpret_cast<const __half *>(a.Wq1) + (size_t)h * Rp * D;
-    const __half *Wq2 = reinterpret_cast<const __half *>(a.Wq2) + (size_t)h * R * Rp;
-    mlp_load_row<D>(reinterpret_cast<const __half *>(a.q) + uc * D, g, bxq);
-    if (g0) tq0 = mlp_load_tiles<D>(Wq1, Wq2, Rp, R, 32 * wave, g, c);
-    if (g1) tq1 = mlp_load_tiles<D>(Wq1, Wq2, Rp, R, 32 * (wave + kWpuUnits), g, c);
+  // 2. layer-2 sums of the two feature maps by parts (lane r + 16 i reads what lane r reads),
+  //    row r of W3
+  const int nparts = mlp_nparts(a.Rp);
+  const int rl = (lane & 15) < R ? (lane & 15) : R - 1;
+  float pq[NP], pk[NP];
+#pragma unroll
+  for (int p = 0; p < NP; ++p) {
+    const int pc = p < nparts ? p : nparts - 1;
+    pq[p] = a.mlp_parts[((size_t)pc * a.U + u) * 16 + rl];
+    pk[p] = a.mlp_parts[((size_t)(nparts + pc) * a.U + u) * 16 + rl];
   }
-  __builtin_amdgcn_sched_barrier(0);
-  // 3. unit state and the rest of the step's inputs (wanted from phase 2 on)
+  __half w3[RM];
+#pragma unroll
+  for (int j = 0; j < RM; ++j)
+    w3[j] = reinterpret_cast<const __half *>(a.Wk3)[((size_t)h * R + rl) * R + (j < R ? j : R - 1)];
+  // 3. unit state (wanted from phase 2 on)
   const int n = a.n_seen[u];
   const Pending pend = decode_pending(a.pend_slot[u]);
   const int m = n < C ? n : C;          // live slots are 0..m-1 (slots fill in order)
   const int rows = m + 1;               // + the appended pair (K', V' of Eq. 3)
   const bool full = (m == C);
-  // (every load below is unconditional, from a clamped address where the wanted one may not
-  // exist: a load under a condition would make the first use of anything requested before
-  // it wait for it as well)
   double acc_pre[NR2];
   int pos_pre[NR2];
 #pragma unroll
@@ -127,28 +116,28 @@ __global__ __launch_bounds__(kWpuUnits * kWave) void wpu_step_kernel(const StepA
     acc_pre[i] = a.acc[idx];
     pos_pre[i] = a.pos[idx];
   }
-  const int rl = lane < R ? lane : R - 1;
   double z_lane = a.z[(size_t)u * R + rl];                   // lane r < R
   const float ppsi_lane = a.pend_psi[(size_t)u * R + rl];
   float psie_lane = a.psi[((size_t)u * C + (pend.slot >= 0 && pend.slot < C ? pend.slot : 0)) * R + rl];
   __builtin_amdgcn_sched_barrier(0);
 
   // The stream: position s < nitp is load s of K, position nitp + t is load t of V.
-  const int nit = valid ? (rows + RPI - 1) / RPI : 0;        // load instructions per stream
-  const int nitp = nit > 0 ? (nit + DEPTH - 1) / DEPTH * DEPTH : DEPTH;   // K part of the stream, padded
-  const int live_bytes = valid ? m * D * (int)sizeof(T) : 0;
+  const int nit = (rows + RPI - 1) / RPI;                    // load instructions per stream
+  const int nitp = (nit + DEPTH - 1) / DEPTH * DEPTH;        // K part of the stream, padded
+  const int live_bytes = m * D * (int)sizeof(T);
   auto issue = [&](int s) -> u4v {                           // s is wave-uniform
     const bool isk = s < nitp;
     const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(isk ? kc : vc, 0, live_bytes, 0x00020000);
     return __builtin_amdgcn_raw_buffer_load_b128(rs, lane * 16, (isk ? s : s - nitp) * (kWave * 16), 2 /* nt */);
   };
 
-  // ---- phase 1: scores as the key rows arrive; phi(q) (Eq. 1) after the first pass --------------
+  // ---- phase 1: scores as the key rows arrive; the feature maps after the first pass ------------
   double f_lane = 0.0;                   // phi(q), lane r < R
+  float npsi_lane = 0.f;                 // psi(k) of this step's key, lane r < R
   {
     const double inv_sqrt_d = 1.0 / sqrt((double)D);      // folded at compile time
     int base = 0;
-    do {                                                   // nitp >= DEPTH, also for an idle wave
+    do {                                                   // nitp >= DEPTH
 #pragma unroll
       for (int j = 0; j < DEPTH; ++j) {
         const int s = base + j;
@@ -168,45 +157,32 @@ __global__ __launch_bounds__(kWpuUnits * kWave) void wpu_step_kernel(const StepA
         __builtin_amdgcn_sched_barrier(0);
       }
       if (base == 0) {
-        // The weight tiles have been back for a while (they were requested before the loads
-        // this pass re-issued), and the ring is full again: the stream goes on while the
-        // matrix cores work and the block meets at its barrier.
-        v4f cq = {0.f, 0.f, 0.f, 0.f};
-        if (g0) mlp_apply_tiles<D>(tq0, bxq, cq);
-        if (g1) mlp_apply_tiles<D>(tq1, bxq, cq);
-        if (ngrp > 2 * kWpuUnits) {                          // hidden widths above 512
-          const __half *Wq1 = reinterpret_cast<const __half *>(a.Wq1) + (size_t)h * Rp * D;
-          const __half *Wq2 = reinterpret_cast<const __half *>(a.Wq2) + (size_t)h * R * Rp;
-          for (int grp = wave + 2 * kWpuUnits; grp < ngrp; grp += kWpuUnits) {
-            const MlpTiles<D> t = mlp_load_tiles<D>(Wq1, Wq2, Rp, R, 32 * grp, g, c);
-            mlp_apply_tiles<D>(t, bxq, cq);
+        // The parts have been back for a while (they were requested before the loads this pass
+        // re-issued): finish both feature maps here, where nothing is waiting for anything.
+        double sq = 0.0, sk = 0.0;
+#pragma unroll
+        for (int p = 0; p < NP; ++p) {
+          if (p < nparts) {
+            sq += (double)pq[p];
+            sk += (double)pk[p];
           }
         }
-#pragma unroll
-        for (int w = 0; w < 4; ++w) s_red[0][wave][4 * g + w][c] = cq[w];
-        __syncthreads();
-        if (lane < R) {
-          double sq = 0.0;
-#pragma unroll
-          for (int w = 0; w < kWpuUnits; ++w) sq += (double)s_red[0][w][lane][wave];
-          f_lane = fabs(gelu_poly_f64(sq));                  // last activation of Eq. 1
+        for (int p = NP; p < nparts; ++p) {                  // hidden widths above 512
+          sq += (double)a.mlp_parts[((size_t)p * a.U + u) * 16 + rl];
+          sk += (double)a.mlp_parts[((size_t)(nparts + p) * a.U + u) * 16 + rl];
         }
+        f_lane = lane < R ? fabs(gelu_poly_f64(sq)) : 0.0;   // last activation of Eq. 1
+        const double h2 = gelu_poly_f64(sk);                 // lane r < R; Eq. 2: |W3 gelu(.)|
+        double acc3 = 0.0;
+#pragma unroll
+        for (int j = 0; j < RM; ++j)
+          if (j < R) acc3 = fma(readlane_v(h2, j), (double)__half2float(w3[j]), acc3);
+        npsi_lane = (float)fabs(acc3);
       }
     } while ((base += DEPTH) < nitp);
   }
 
-  // ---- requests: operands of psi, behind the keys ---------------------------------------------------
-  v8h bxk[KS];
-  MlpTiles<D> tk0, tk1;
-  const int w3i = (int)threadIdx.x < R * R ? (int)threadIdx.x : 0;
-  const __half w3v = reinterpret_cast<const __half *>(a.Wk3)[(size_t)h * R * R + w3i];   // W3 of the head
-  {
-    const __half *Wk1 = reinterpret_cast<const __half *>(a.Wk1) + (size_t)h * Rp * D;
-    const __half *Wk2 = reinterpret_cast<const __half *>(a.Wk2) + (size_t)h * R * Rp;
-    mlp_load_row<D>(reinterpret_cast<const __half *>(a.k) + uc * D, g, bxk);
-    if (g0) tk0 = mlp_load_tiles<D>(Wk1, Wk2, Rp, R, 32 * wave, g, c);
-    if (g1) tk1 = mlp_load_tiles<D>(Wk1, Wk2, Rp, R, 32 * (wave + kWpuUnits), g, c);
-  }
+  // ---- requests behind the keys: what the value stream and the output want --------------------------
   const Vec vnv = load_vec<T>(vn + lr * EPL);
   // this lane's columns of H and of the pending value row: wanted after the value stream
   const int col0 = lr * EPL + ((lane & 32) ? 4 : 0) + ((lane & 16) ? 2 : 0) + ((RPI == 8 && (lane & 8)) ? 1 : 0);
@@ -226,7 +202,7 @@ __global__ __launch_bounds__(kWpuUnits * kWave) void wpu_step_kernel(const StepA
 
   int eslot = -1, ins_slot = -1;
   double lscale = 0.0;
-  if (valid) {
+  {
     // ---- phase 2: softmax with the low-rank term, H2O bookkeeping, eviction choice -------------
     {
       double sc[NR2];
@@ -256,6 +232,7 @@ __global__ __launch_bounds__(kWpuUnits * kWave) void wpu_step_kernel(const StepA
           a.z[(size_t)u * R + lane] = z_lane;
         }
         if (pend.slot >= 0 && pend.slot < C) a.psi[((size_t)u * C + pend.slot) * R + lane] = ppsi_lane;
+        a.pend_psi[(size_t)u * R + lane] = npsi_lane;
       }
       const double fz = wave_allreduce(f_lane * z_lane, OpAdd{});
       // den = phi(q) z^T + sum_j e^{s_j}, in whichever scaling cannot overflow:
@@ -331,13 +308,13 @@ __global__ __launch_bounds__(kWpuUnits * kWave) void wpu_step_kernel(const StepA
   __builtin_amdgcn_wave_barrier();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
-  // ---- phase 3: p . V as the value rows arrive; psi(k) (Eq. 2) after the first pass -----------------
+  // ---- phase 3: p . V as the value rows arrive ------------------------------------------------------
   float o[EPL];
 #pragma unroll
   for (int i = 0; i < EPL; ++i) o[i] = 0.f;
   {
     int base = 0;
-    do {                                                     // one pass at least, also for an idle wave
+    do {                                                     // nit >= 1
 #pragma unroll
       for (int j = 0; j < DEPTH; ++j) {
         const int s = base + j;
@@ -357,38 +334,9 @@ __global__ __launch_bounds__(kWpuUnits * kWave) void wpu_step_kernel(const StepA
         buf[j] = issue(nitp + s + DEPTH);
         __builtin_amdgcn_sched_barrier(0);
       }
-      if (base == 0) {
-        // psi of this step's key, which the next step will want: same scheme as phi above
-        v4f ck = {0.f, 0.f, 0.f, 0.f};
-        if (g0) mlp_apply_tiles<D>(tk0, bxk, ck);
-        if (g1) mlp_apply_tiles<D>(tk1, bxk, ck);
-        if (ngrp > 2 * kWpuUnits) {
-          const __half *Wk1 = reinterpret_cast<const __half *>(a.Wk1) + (size_t)h * Rp * D;
-          const __half *Wk2 = reinterpret_cast<const __half *>(a.Wk2) + (size_t)h * R * Rp;
-          for (int grp = wave + 2 * kWpuUnits; grp < ngrp; grp += kWpuUnits) {
-            const MlpTiles<D> t = mlp_load_tiles<D>(Wk1, Wk2, Rp, R, 32 * grp, g, c);
-            mlp_apply_tiles<D>(t, bxk, ck);
-          }
-        }
-#pragma unroll
-        for (int w = 0; w < 4; ++w) s_red[1][wave][4 * g + w][c] = ck[w];
-        if ((int)threadIdx.x < R * R) s_w3[threadIdx.x / R][threadIdx.x % R] = __half2float(w3v);
-        __syncthreads();
-        double sk = 0.0;
-        if (lane < R) {
-#pragma unroll
-          for (int w = 0; w < kWpuUnits; ++w) sk += (double)s_red[1][w][lane][wave];
-        }
-        const double h2 = lane < R ? gelu_poly_f64(sk) : 0.0;
-        double acc3 = 0.0;
-#pragma unroll
-        for (int j = 0; j < RM; ++j)
-          if (j < R) acc3 = fma(readlane_v(h2, j), (double)s_w3[lane & 15][j], acc3);
-        if (valid && lane < R) a.pend_psi[(size_t)u * R + lane] = (float)fabs(acc3);
-      }
     } while ((base += DEPTH) < nit);
   }
-  if (valid) {
+  {
     // fold of the pending pair into H (Eq. 4), then phi(q) H for this lane's columns
     float fh[CPL];
 #pragma unroll
