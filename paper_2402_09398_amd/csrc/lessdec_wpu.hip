@@ -32,8 +32,8 @@ constexpr int kWpuMaxRows = 512;    // C + 1 at most
 //          step must already see.
 // Phase 3  p . V in fp32 as the value rows arrive; the value row of the discarded slot is
 //          written to pend_v by the lanes that hold it; the RPI partial rows are combined
-//          by a reduce-scatter that leaves each lane with the 8 / RPI output columns it
-//          also holds of H.
+//          by a reduce-scatter that leaves each lane with the four output columns it also
+//          holds of H.
 // Phase 4  fold of the pending pair into H (Eq. 4); out = p V + phi(q) H / den (Eq. 3); the
 //          new pair goes into the freed slot (Sec. 3.2); the discarded pair is left pending
 //          for the next step.
@@ -45,7 +45,6 @@ __global__ __launch_bounds__(kWpuUnits * kWave) void wpu_step_kernel(const StepA
   constexpr int EPL = 8;                   // elements per lane
   constexpr int LPR = D / EPL;             // lanes per row
   constexpr int RPI = kWave / LPR;         // rows per load instruction
-  constexpr int CPL = EPL / RPI;           // output columns per lane after the reduce-scatter
   constexpr int NP = 8;                    // feature-map parts requested up front (R' <= 512)
   using Vec = typename Store<T>::Vec;
 
@@ -184,18 +183,19 @@ __global__ __launch_bounds__(kWpuUnits * kWave) void wpu_step_kernel(const StepA
 
   // ---- requests behind the keys: what the value stream and the output want --------------------------
   const Vec vnv = load_vec<T>(vn + lr * EPL);
-  // this lane's columns of H and of the pending value row: wanted after the value stream
-  const int col0 = lr * EPL + ((lane & 32) ? 4 : 0) + ((lane & 16) ? 2 : 0) + ((RPI == 8 && (lane & 8)) ? 1 : 0);
-  float hreg[RM][CPL];                   // (R <= RM)
+  // This lane's share of H and of the pending value row, wanted after the value stream: four
+  // consecutive columns (those the reduce-scatter of phase 3 leaves it with) of every NHB-th
+  // row, so that one 16-byte load per lane covers NHB whole rows of H per instruction.
+  constexpr int NHB = RPI / 2, HR = RM / NHB;
+  const int col0 = lr * EPL + ((lane & LPR) ? 4 : 0);
+  const int hb = lane / (2 * LPR);                           // which rows: r = NHB * i + hb
+  float4 hreg[HR];
 #pragma unroll
-  for (int r = 0; r < RM; ++r) {
-    const float *hp = a.H + ((size_t)u * R + (r < R ? r : R - 1)) * D + col0;
-#pragma unroll
-    for (int j = 0; j < CPL; ++j) hreg[r][j] = hp[j];
+  for (int i = 0; i < HR; ++i) {
+    const int r = NHB * i + hb;
+    hreg[i] = *reinterpret_cast<const float4 *>(a.H + ((size_t)u * R + (r < R ? r : R - 1)) * D + col0);
   }
-  T pend_v_h[CPL];
-#pragma unroll
-  for (int j = 0; j < CPL; ++j) pend_v_h[j] = reinterpret_cast<const T *>(a.pend_v)[(size_t)u * D + col0 + j];
+  const uint2 pend_v_h = *reinterpret_cast<const uint2 *>(reinterpret_cast<const T *>(a.pend_v) + (size_t)u * D + col0);
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
   __builtin_amdgcn_wave_barrier();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
@@ -337,61 +337,59 @@ __global__ __launch_bounds__(kWpuUnits * kWave) void wpu_step_kernel(const StepA
     } while ((base += DEPTH) < nit);
   }
   {
-    // fold of the pending pair into H (Eq. 4), then phi(q) H for this lane's columns
-    float fh[CPL];
-#pragma unroll
-    for (int j = 0; j < CPL; ++j) fh[j] = 0.f;
+    // fold of the pending pair into H (Eq. 4), then phi(q) H for this lane's columns and rows
+    float fh[4] = {0.f, 0.f, 0.f, 0.f};
     {
       const float f32 = (float)f_lane;
-      float pend_v_c[CPL];
-#pragma unroll
-      for (int j = 0; j < CPL; ++j) pend_v_c[j] = __half2float(pend_v_h[j]);
+      const __half2 *pvh = reinterpret_cast<const __half2 *>(&pend_v_h);
+      const float2 pv01 = __half22float2(pvh[0]), pv23 = __half22float2(pvh[1]);
       float *Hu = a.H + (size_t)u * R * D;
 #pragma unroll
-      for (int r = 0; r < RM; ++r) {
-        if (r < R) {
-          const float fr = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(f32), r));
-          const float pe = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(psie_lane), r));
-#pragma unroll
-          for (int j = 0; j < CPL; ++j) {
-            if (pend.fold) {
-              hreg[r][j] = fmaf(pe, pend_v_c[j], hreg[r][j]);
-              Hu[(size_t)r * D + col0 + j] = hreg[r][j];
-            }
-            fh[j] = fmaf(fr, hreg[r][j], fh[j]);
-          }
+      for (int i = 0; i < HR; ++i) {
+        const int r = NHB * i + hb;                          // differs between the halves of the wave
+        const int rc = r < R ? r : R - 1;
+        const float fr = r < R ? __shfl(f32, rc) : 0.f;
+        const float pe = __shfl(psie_lane, rc);
+        if (pend.fold) {
+          hreg[i].x = fmaf(pe, pv01.x, hreg[i].x);
+          hreg[i].y = fmaf(pe, pv01.y, hreg[i].y);
+          hreg[i].z = fmaf(pe, pv23.x, hreg[i].z);
+          hreg[i].w = fmaf(pe, pv23.y, hreg[i].w);
+          if (r < R) *reinterpret_cast<float4 *>(Hu + (size_t)r * D + col0) = hreg[i];
         }
+        fh[0] = fmaf(fr, hreg[i].x, fh[0]);
+        fh[1] = fmaf(fr, hreg[i].y, fh[1]);
+        fh[2] = fmaf(fr, hreg[i].z, fh[2]);
+        fh[3] = fmaf(fr, hreg[i].w, fh[3]);
       }
     }
-    // reduce-scatter over the RPI row groups: after the stage with partner distance x, a lane
-    // keeps the half of its columns selected by its bit x
+    // The RPI row groups hold partial sums of the same 8 columns.  First stage (partner at
+    // distance LPR): reduce-scatter, a lane keeps the four columns selected by its bit LPR;
+    // remaining stages: all-reduce, together with the partial phi(q) H of the row subsets.
     {
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        const bool hi = lane & 32;
+        const bool hi = lane & LPR;
         const float send = hi ? o[i] : o[i + 4], keep = hi ? o[i + 4] : o[i];
-        o[i] = keep + __shfl_xor(send, 32);
+        o[i] = keep + __shfl_xor(send, LPR);
       }
 #pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        const bool hi = lane & 16;
-        const float send = hi ? o[i] : o[i + 2], keep = hi ? o[i + 2] : o[i];
-        o[i] = keep + __shfl_xor(send, 16);
-      }
-      if constexpr (RPI == 8) {
-        const bool hi = lane & 8;
-        const float send = hi ? o[0] : o[1], keep = hi ? o[1] : o[0];
-        o[0] = keep + __shfl_xor(send, 8);
+      for (int x = 2 * LPR; x < kWave; x *= 2) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          o[i] += __shfl_xor(o[i], x);
+          fh[i] += __shfl_xor(fh[i], x);
+        }
       }
     }
 
     // ---- phase 4: output, in-place insert ---------------------------------------------------------
-    T res[CPL];
-#pragma unroll
-    for (int j = 0; j < CPL; ++j) res[j] = __float2half_rn((float)((double)o[j] + lscale * (double)fh[j]));
-    T *dst = reinterpret_cast<T *>(a.out) + (size_t)u * D + col0;
-    if constexpr (CPL == 2) *reinterpret_cast<__half2 *>(dst) = __half2{res[0], res[1]};
-    else dst[0] = res[0];
+    if (hb == 0) {
+      __half2 res[2];
+      res[0] = __floats2half2_rn((float)((double)o[0] + lscale * (double)fh[0]), (float)((double)o[1] + lscale * (double)fh[1]));
+      res[1] = __floats2half2_rn((float)((double)o[2] + lscale * (double)fh[2]), (float)((double)o[3] + lscale * (double)fh[3]));
+      *reinterpret_cast<uint2 *>(reinterpret_cast<T *>(a.out) + (size_t)u * D + col0) = *reinterpret_cast<const uint2 *>(res);
+    }
     if (ins_slot >= 0 && rb == 0) {
       *reinterpret_cast<uint4 *>(kc + (size_t)ins_slot * D + lr * EPL) = knv.raw;
       *reinterpret_cast<uint4 *>(vc + (size_t)ins_slot * D + lr * EPL) = vnv.raw;
@@ -409,7 +407,7 @@ bool wpu_supported(int dtype, int D, int C, int Rp, int R)
 template <int D, int RM>
 static hipError_t launch_step_wpu_t(const StepArgs &a, hipStream_t st)
 {
-  constexpr int kDepth = 8;
+  constexpr int kDepth = 7;
   const int rows_cap = (a.C + 2) & ~1;
   const size_t lds = (size_t)kWpuUnits * rows_cap * (sizeof(double) + sizeof(float));
   const unsigned grid = (unsigned)(a.Hh * ((a.B + kWpuUnits - 1) / kWpuUnits));
