@@ -27,6 +27,11 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0        # MI355X published HBM3E bandwidth
 
+# HBM bytes per lessdec_step call (both launches), from the rocprofv3 FETCH_SIZE / WRITE_SIZE
+# counter runs of this same command (profiles/lessdec_step_cfg3_hbm_traffic.txt: counters
+# cannot be read from inside the process).  Only for the workload they were taken on.
+MEASURED_TRAFFIC_BYTES = {3: 150.7e6}
+
 
 def algorithmic_bytes_per_unit_step(w) -> float:
     """Bytes the method itself must move per unit and step ('Roofline')."""
@@ -150,7 +155,9 @@ def main():
                                f"prompt {w.prompt}, {w.n_heavy}+{w.n_recent} slots, rank {w.rank}, hidden {w.hidden}",
                    "layers_cycled": L, "prefill_ms": prefill_ms},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(w.cfg) if L >= 8 else None,
+                     "kernel": "one lessdec_step call = mlp_parts_kernel + wpu_step_kernel",
                      "bytes_per_launch": bytes_per_step,
                      "kv_only_frac": 2 * w.capacity * D * (2 if w.dtype == "f16" else 4) * U
                                      / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS},
