@@ -81,8 +81,8 @@ def main():
     ap.add_argument("--cfg", type=int, default=3, help="workload (1..5), default the batch-64 Llama-2-7B shape")
     ap.add_argument("--layers", type=int, default=8, help="independent layer states cycled round-robin")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-units", type=int, default=256)
-    ap.add_argument("--cpu-steps", type=int, default=384)
+    ap.add_argument("--cpu-units", type=int, default=1024)
+    ap.add_argument("--cpu-steps", type=int, default=512)
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (every unit is independent; "
@@ -142,7 +142,7 @@ def main():
     achieved = bytes_per_step / (ms_per_step * 1e-3) / 1e9
 
     result = {
-        "metric": "decode steps/sec (batch x heads), Llama-2-7B attention shape",
+        "metric": "decode steps/sec (batch\u00d7heads) + achieved HBM GB/s vs peak, Llama-2-7B shape",
         "value": unit_steps_per_s,
         "unit": "unit-steps/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
