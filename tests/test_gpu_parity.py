@@ -147,6 +147,52 @@ def test_checkpoint_restore_continues_bit_identically():
         assert torch.equal(a[2][n], b[2][n]), n
 
 
+@pytest.mark.parametrize("kind", ["streaming", "general"])
+def test_steps_replayed_from_a_hip_graph_match_eager_steps(kind):
+    """The step reads and advances its counters on the device and clears nothing with a memset,
+    so one captured step can be replayed for a whole sequence.  Every replay is checked against
+    the eager run, with eager work and synchronisation between replays."""
+    import torch
+    w = small("graph", steps=12) if kind == "streaming" else small("graph-general", steps=12, rank=20)
+    inp = wl.all_inputs(w)
+    res = hz.gpu_run(w, {k: (v if k in "QKV" else v[:0]) for k, v in inp.items()})      # prompt phase only
+    gpu = res["gpu"]
+    names = gpu.STATE
+    saved = {n: getattr(gpu, n).clone() for n in names}
+    q, k, v = (torch.from_numpy(inp[n]).cuda() for n in ("q", "k", "v"))
+    T = q.shape[0]
+    eager_out = torch.empty_like(q); eager_ev = torch.empty((T, w.units), dtype=torch.int32, device="cuda")
+    for t in range(T):
+        gpu.step(q[t], k[t], v[t], eager_out[t], eager_ev[t])
+    torch.cuda.synchronize()
+    eager_state = {n: getattr(gpu, n).clone() for n in names}
+    for n in names:
+        getattr(gpu, n).copy_(saved[n])
+    qi, ki, vi = q[0].clone(), k[0].clone(), v[0].clone()
+    out = torch.empty_like(qi); ev = torch.empty((w.units,), dtype=torch.int32, device="cuda")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        gpu.step(qi, ki, vi, out, ev)                    # warm-up on the capture stream
+        for n in names:
+            getattr(gpu, n).copy_(saved[n])
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            gpu.step(qi, ki, vi, out, ev)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    for t in range(T):
+        qi.copy_(q[t]); ki.copy_(k[t]); vi.copy_(v[t])
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager_out[t]), f"replay {t}: outputs differ"
+        assert torch.equal(ev, eager_ev[t]), f"replay {t}: evictions differ"
+    for n in names:
+        assert torch.equal(getattr(gpu, n), eager_state[n]), n
+
+
 # ------------------------------------------------------------------ the five configurations
 def sample_units(w, count, seed=0):
     rng = np.random.default_rng(seed)
