@@ -290,7 +290,7 @@ __global__ __launch_bounds__(kWpuUnits * kWave) void wpu_step_kernel(const StepA
       for (int i = 0; i < NR2; ++i) {
         const int j = lane + i * kWave;
         if (j < m) {
-          if (j != ins_slot) a.acc[(size_t)u * C + j] = sc[i];
+          if (j != ins_slot) __builtin_nontemporal_store(sc[i], a.acc + (size_t)u * C + j);
         } else if (j == m && ins_slot >= 0) {
           a.acc[(size_t)u * C + ins_slot] = sc[i];
           a.pos[(size_t)u * C + ins_slot] = n;
@@ -355,7 +355,7 @@ __global__ __launch_bounds__(kWpuUnits * kWave) void wpu_step_kernel(const StepA
           hreg[i].y = fmaf(pe, pv01.y, hreg[i].y);
           hreg[i].z = fmaf(pe, pv23.x, hreg[i].z);
           hreg[i].w = fmaf(pe, pv23.y, hreg[i].w);
-          if (r < R) *reinterpret_cast<float4 *>(Hu + (size_t)r * D + col0) = hreg[i];
+          if (r < R) store_nt(Hu + (size_t)r * D + col0, hreg[i]);
         }
         fh[0] = fmaf(fr, hreg[i].x, fh[0]);
         fh[1] = fmaf(fr, hreg[i].y, fh[1]);
@@ -391,8 +391,8 @@ __global__ __launch_bounds__(kWpuUnits * kWave) void wpu_step_kernel(const StepA
       *reinterpret_cast<uint2 *>(reinterpret_cast<T *>(a.out) + (size_t)u * D + col0) = *reinterpret_cast<const uint2 *>(res);
     }
     if (ins_slot >= 0 && rb == 0) {
-      *reinterpret_cast<uint4 *>(kc + (size_t)ins_slot * D + lr * EPL) = knv.raw;
-      *reinterpret_cast<uint4 *>(vc + (size_t)ins_slot * D + lr * EPL) = vnv.raw;
+      store_nt(kc + (size_t)ins_slot * D + lr * EPL, knv.raw);
+      store_nt(vc + (size_t)ins_slot * D + lr * EPL, vnv.raw);
     }
   }
 
