@@ -39,46 +39,6 @@ __device__ inline typename Store<T>::Vec load_vec(const T *p)
   return v;
 }
 
-// ---- wave / block reductions (fixed order, so results do not depend on timing) --------
-__device__ inline double wave_sum(double v)
-{
-#pragma unroll
-  for (int o = kWave / 2; o > 0; o >>= 1) v += __shfl_xor(v, o);
-  return v;
-}
-__device__ inline double wave_max(double v)
-{
-#pragma unroll
-  for (int o = kWave / 2; o > 0; o >>= 1) v = fmax(v, __shfl_xor(v, o));
-  return v;
-}
-
-// All threads of the block must call these. `red` has room for one double per wave.
-template <int kWaves>
-__device__ inline double block_sum(double v, double *red)
-{
-  v = wave_sum(v);
-  if ((threadIdx.x & (kWave - 1)) == 0) red[threadIdx.x / kWave] = v;
-  __syncthreads();
-  double r = red[0];
-#pragma unroll
-  for (int w = 1; w < kWaves; ++w) r += red[w];
-  __syncthreads();
-  return r;
-}
-template <int kWaves>
-__device__ inline double block_max(double v, double *red)
-{
-  v = wave_max(v);
-  if ((threadIdx.x & (kWave - 1)) == 0) red[threadIdx.x / kWave] = v;
-  __syncthreads();
-  double r = red[0];
-#pragma unroll
-  for (int w = 1; w < kWaves; ++w) r = fmax(r, red[w]);
-  __syncthreads();
-  return r;
-}
-
 // Eviction candidate: smaller accumulated score first, then the older token.
 struct Cand {
   double acc;
@@ -90,35 +50,9 @@ __device__ inline bool cand_less(const Cand &a, const Cand &b)
   return a.acc < b.acc || (a.acc == b.acc && a.pos < b.pos);
 }
 __device__ inline Cand cand_none() { return Cand{__builtin_inf(), INT_MAX, -1}; }
-__device__ inline Cand wave_argmin(Cand c)
-{
-#pragma unroll
-  for (int o = kWave / 2; o > 0; o >>= 1) {
-    Cand d;
-    d.acc = __shfl_xor(c.acc, o);
-    d.pos = __shfl_xor(c.pos, o);
-    d.slot = __shfl_xor(c.slot, o);
-    if (cand_less(d, c)) c = d;
-  }
-  return c;
-}
-template <int kWaves>
-__device__ inline Cand block_argmin(Cand c, Cand *red)
-{
-  c = wave_argmin(c);
-  if ((threadIdx.x & (kWave - 1)) == 0) red[threadIdx.x / kWave] = c;
-  __syncthreads();
-  Cand r = red[0];
-#pragma unroll
-  for (int w = 1; w < kWaves; ++w)
-    if (cand_less(red[w], r)) r = red[w];
-  __syncthreads();
-  return r;
-}
 
 // GELU, x * Phi(x) (Sec. 3.2 names GELU as the activation of both feature maps).
 __device__ inline double gelu_f64(double x) { return 0.5 * x * erfc(-x * 0.70710678118654752440); }
-__device__ inline float gelu_f32(float x) { return 0.5f * x * erfcf(-x * 0.70710678118654752440f); }
 
 // Branch-free fp32 GELU for the matrix-core feature maps.  With t = |x| the upper normal
 // tail is Q(t) = exp(-t^2/2) * (c1 u + ... + c7 u^7), u = 1 / (1 + 0.24 t) (polynomial error
