@@ -11,7 +11,10 @@ Infinity Cache, as in a real 32-layer decode.  Inputs are synthetic and resident
 before the timed region; the state of every layer comes from lessdec_prefill on a
 synthetic prompt.
 
-Prints one JSON line (see the design doc for the fields).  One GPU only.
+Prints one JSON line: value = unit-steps per second (units x steps / time), ms_per_step,
+roofline = algorithmic HBM bytes of a step divided by its measured time against the 8 TB/s
+peak (traffic = HBM bytes per step measured with rocprofv3 counters), cpu_baseline = the fp64
+oracle timed on the host cores on a sample of the same workload.  One GPU only.
 """
 from __future__ import annotations
 
@@ -34,7 +37,9 @@ MEASURED_TRAFFIC_BYTES = {3: 150.7e6}
 
 
 def algorithmic_bytes_per_unit_step(w) -> float:
-    """Bytes the method itself must move per unit and step ('Roofline')."""
+    """Bytes the method itself must move per unit and step: every retained key and value once,
+    the step's rows in and out, the H2O scores and positions, the low-rank state read and
+    written, and the per-head feature-map weights shared by the batch rows."""
     e = 2 if w.dtype == "f16" else 4
     C, D, R, Rp, B = w.capacity, w.head_dim, w.rank, w.hidden, w.batch
     kv = 2 * C * D * e                       # every retained key and value once
@@ -86,7 +91,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (every unit is independent; "
-                 "see DESIGN.md for how it would shard). Use --gpus 1.")
+                 "sharding would put whole units on each GPU, with no collective). Use --gpus 1.")
 
     import numpy as np
     import torch

@@ -36,7 +36,7 @@ def test_budget_helper_matches_table1_and_workloads():
     for pct, L_, tok in [(2, 4096, 80), (5, 4096, 204), (10, 4096, 408),
                          (2, 2048, 40), (5, 2048, 102), (10, 2048, 204)]:
         assert binding.lessdec_budget_tokens(pct, L_) == tok
-    # slot counts of the workloads (percentages of the prompt length)
+    # slot counts of the workloads (their percentages are taken of the prompt length)
     for cfg, pct in [(2, 10), (3, 10), (4, 8), (5, 4)]:
         w = wl.WORKLOADS[cfg]
         assert binding.lessdec_budget_tokens(pct, w.prompt) == w.capacity
