@@ -12,8 +12,9 @@ before the timed region; the state of every layer comes from lessdec_prefill on 
 synthetic prompt.
 
 Prints one JSON line: value = unit-steps per second (units x steps / time), ms_per_step,
-roofline = algorithmic HBM bytes of a step divided by its measured time against the 8 TB/s
-peak (traffic = HBM bytes per step measured with rocprofv3 counters), cpu_baseline = the fp64
+roofline = algorithmic HBM bytes of the attention launch (the dominant kernel) divided by its
+measured time against the 8 TB/s peak, with the same figure for the whole step beside it
+(traffic = HBM bytes per launch measured with rocprofv3 counters), cpu_baseline = the fp64
 oracle timed on the host cores on a sample of the same workload.  One GPU only.
 """
 from __future__ import annotations
@@ -30,10 +31,10 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0        # MI355X published HBM3E bandwidth
 
-# HBM bytes per lessdec_step call (both launches), from the rocprofv3 FETCH_SIZE / WRITE_SIZE
+# HBM bytes per launch of the attention kernel, from the rocprofv3 FETCH_SIZE / WRITE_SIZE
 # counter runs of this same command (profiles/lessdec_step_cfg3_hbm_traffic.txt: counters
 # cannot be read from inside the process).  Only for the workload they were taken on.
-MEASURED_TRAFFIC_BYTES = {3: 150.7e6}
+MEASURED_TRAFFIC_BYTES = {3: 138.6e6}        # the attention launch; the feature-map launch adds 12.1e6
 
 
 def algorithmic_bytes_per_unit_step(w) -> float:
@@ -49,6 +50,14 @@ def algorithmic_bytes_per_unit_step(w) -> float:
     psi = 2 * R * 4                          # psi of the discarded pair read, of the new pair written
     weights = (2 * (D * Rp + Rp * R) + R * R) * e / B   # per-head weights shared by the batch rows
     return kv + io + scores + state + psi + weights
+
+
+def attend_bytes_per_unit_step(w) -> float:
+    """The same figure for the attention launch alone: everything except the weights, which
+    only the feature-map launch reads."""
+    e = 2 if w.dtype == "f16" else 4
+    D, R, Rp, B = w.head_dim, w.rank, w.hidden, w.batch
+    return algorithmic_bytes_per_unit_step(w) - (2 * (D * Rp + Rp * R) + R * R) * e / B
 
 
 def log(*a):
@@ -142,6 +151,30 @@ def main():
     torch.cuda.synchronize()
     ms = e0.elapsed_time(e1)
     ms_per_step = ms / args.steps
+
+    # The two launches of a step, timed one kind at a time on the same stream, same inputs and
+    # same layer rotation (the attention launch then reads feature maps of an earlier query,
+    # which changes values but not work).
+    def run_half(first, count, attend):
+        for i in range(first, first + count):
+            lay = i % L
+            t = ((i // L) + 37 * lay) % T
+            if attend:
+                layers[lay].step_attend(q[t], k[t], v[t], outs[lay])
+            else:
+                layers[lay].step_features(q[t], k[t])
+
+    half_ms = {}
+    for attend in (False, True):
+        run_half(0, args.warmup, attend)
+        torch.cuda.synchronize()
+        e0.record(stream)
+        run_half(args.warmup, args.steps, attend)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        half_ms[attend] = e0.elapsed_time(e1) / args.steps
+    attend_bytes = attend_bytes_per_unit_step(w) * U
+    attend_achieved = attend_bytes / (half_ms[True] * 1e-3) / 1e9
     unit_steps_per_s = U * args.steps / (ms * 1e-3)
     bytes_per_step = algorithmic_bytes_per_unit_step(w) * U
     achieved = bytes_per_step / (ms_per_step * 1e-3) / 1e9
@@ -159,11 +192,15 @@ def main():
         "config": {"workload": f"cfg{w.cfg} {w.name}: batch {w.batch} x heads {w.heads} x head_dim {D}, "
                                f"prompt {w.prompt}, {w.n_heavy}+{w.n_recent} slots, rank {w.rank}, hidden {w.hidden}",
                    "layers_cycled": L, "prefill_ms": prefill_ms},
-        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS,
+        # the dominant kernel: the attention launch (lessdec_step_attend), timed by itself
+        "roofline": {"bound": "hbm", "achieved": attend_achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": attend_achieved / HBM_PEAK_GBS,
                      "traffic": MEASURED_TRAFFIC_BYTES.get(w.cfg) if L >= 8 else None,
-                     "kernel": "one lessdec_step call = mlp_parts_kernel + wpu_step_kernel",
-                     "bytes_per_launch": bytes_per_step,
+                     "kernel": "wpu_step_kernel (lessdec_step_attend)",
+                     "bytes_per_launch": attend_bytes, "ms_per_launch": half_ms[True],
+                     "features_ms_per_launch": half_ms[False],
+                     "whole_step": {"achieved": achieved, "frac": achieved / HBM_PEAK_GBS,
+                                    "bytes_per_step": bytes_per_step},
                      "kv_only_frac": 2 * w.capacity * D * (2 if w.dtype == "f16" else 4) * U
                                      / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS},
     }

@@ -140,6 +140,20 @@ int lessdec_prefill(const lessdec_desc *desc, const void *Q, const void *K, cons
 int lessdec_step(const lessdec_desc *desc, const void *q, const void *k, const void *v,
                  void *out, int32_t *evicted_pos, void *hip_stream);
 
+/*
+ * The two halves of lessdec_step, for a caller that has q and k before it wants the
+ * attention output (or that times them separately).  lessdec_step is exactly the first
+ * followed by the second.
+ *  lessdec_step_features: evaluates phi(q) (Eq. 1) and psi(k) (Eq. 2) of the step for every
+ *    unit into the workspace.  Touches no state.
+ *  lessdec_step_attend: everything else of the step, reading the feature maps that the last
+ *    lessdec_step_features on this descriptor left in the workspace; q and k must be the same
+ *    arrays.  The workspace must not be used by another call in between.
+ */
+int lessdec_step_features(const lessdec_desc *desc, const void *q, const void *k, void *hip_stream);
+int lessdec_step_attend(const lessdec_desc *desc, const void *q, const void *k, const void *v,
+                        void *out, int32_t *evicted_pos, void *hip_stream);
+
 /* Static message for a return code. */
 const char *lessdec_strerror(int code);
 

@@ -17,7 +17,7 @@ DTYPE_F32, DTYPE_F16 = 0, 1
 FLAG_SPARSE_DENOM = 1
 OK, EINVAL, EWORKSPACE, EHIP = 0, -1, -2, -3
 
-EXPORTS = ("lessdec_workspace_bytes", "lessdec_state_reset", "lessdec_state_sync", "lessdec_prefill", "lessdec_step",
+EXPORTS = ("lessdec_workspace_bytes", "lessdec_state_reset", "lessdec_state_sync", "lessdec_prefill", "lessdec_step", "lessdec_step_features", "lessdec_step_attend",
            "lessdec_strerror", "lessdec_budget_tokens")
 
 
@@ -63,6 +63,10 @@ def lib():
         L.lessdec_prefill.argtypes = [C.POINTER(Desc)] + [C.c_void_p] * 3 + [C.c_int32] + [C.c_void_p] * 2
         L.lessdec_step.restype = C.c_int
         L.lessdec_step.argtypes = [C.POINTER(Desc)] + [C.c_void_p] * 6
+        L.lessdec_step_features.restype = C.c_int
+        L.lessdec_step_features.argtypes = [C.POINTER(Desc)] + [C.c_void_p] * 3
+        L.lessdec_step_attend.restype = C.c_int
+        L.lessdec_step_attend.argtypes = [C.POINTER(Desc)] + [C.c_void_p] * 6
         L.lessdec_strerror.restype = C.c_char_p
         L.lessdec_strerror.argtypes = [C.c_int]
         L.lessdec_budget_tokens.restype = C.c_int32
@@ -105,6 +109,15 @@ def lessdec_state_sync(desc: Desc, stream=None):
 def lessdec_prefill(desc: Desc, Q, K, V, P: int, out=None, stream=None):
     _check(lib().lessdec_prefill(C.byref(desc), _p(Q), _p(K), _p(V), int(P), _p(out),
                                  _stream(stream)), "lessdec_prefill")
+
+
+def lessdec_step_features(desc: Desc, q, k, stream=None):
+    _check(lib().lessdec_step_features(C.byref(desc), _p(q), _p(k), _stream(stream)), "lessdec_step_features")
+
+
+def lessdec_step_attend(desc: Desc, q, k, v, out, evicted_pos=None, stream=None):
+    _check(lib().lessdec_step_attend(C.byref(desc), _p(q), _p(k), _p(v), _p(out), _p(evicted_pos),
+                                     _stream(stream)), "lessdec_step_attend")
 
 
 def lessdec_step(desc: Desc, q, k, v, out, evicted_pos=None, stream=None):
@@ -210,3 +223,20 @@ class LessDec:
                                         evicted_pos.numel() != self.B * self.Hh):
             raise LessdecError("step: evicted_pos must be int32 [B,Hh]")
         lessdec_step(self.desc, q, k, v, out, evicted_pos, stream)
+
+    def step_features(self, q, k, stream=None):
+        """First half of step(): phi(q), psi(k) of the step into the workspace."""
+        for t in (q, k):
+            if t.dtype != self.tdtype or not t.is_contiguous() or t.numel() != self.B * self.Hh * self.D:
+                raise LessdecError("step_features: tensors must be contiguous [B,Hh,D] of the storage dtype")
+        lessdec_step_features(self.desc, q, k, stream)
+
+    def step_attend(self, q, k, v, out, evicted_pos=None, stream=None):
+        """Second half of step(), after step_features(q, k) on the same tensors."""
+        for t in (q, k, v, out):
+            if t.dtype != self.tdtype or not t.is_contiguous() or t.numel() != self.B * self.Hh * self.D:
+                raise LessdecError("step_attend: tensors must be contiguous [B,Hh,D] of the storage dtype")
+        if evicted_pos is not None and (evicted_pos.dtype != self.torch.int32 or
+                                        evicted_pos.numel() != self.B * self.Hh):
+            raise LessdecError("step_attend: evicted_pos must be int32 [B,Hh]")
+        lessdec_step_attend(self.desc, q, k, v, out, evicted_pos, stream)

@@ -124,8 +124,40 @@ int lessdec_state_sync(const lessdec_desc *desc, void *hip_stream)
              ? LESSDEC_OK : LESSDEC_EHIP;
 }
 
-int lessdec_step(const lessdec_desc *desc, const void *q, const void *k, const void *v, void *out,
-                 int32_t *evicted_pos, void *hip_stream)
+int lessdec_step_features(const lessdec_desc *desc, const void *q, const void *k, void *hip_stream)
+{
+  Shape s;
+  int rc = check_desc(desc, &s, 0);
+  if (rc) return rc;
+  if (!q || !k || !aligned(q, 16) || !aligned(k, 16)) return LESSDEC_EINVAL;
+  hipStream_t st = (hipStream_t)hip_stream;
+  const Workspace w = carve(s, 0);
+  char *ws = static_cast<char *>(desc->workspace);
+  if (wpu_supported(desc->dtype, desc->head_dim, (int)s.C, desc->hidden, desc->rank)) {
+    // matrix-core feature maps up to the layer-2 sums
+    MlpPartsArgs fm;
+    fm.q = (const __half *)q; fm.k = (const __half *)k;
+    fm.Wq1 = (const __half *)desc->Wq1; fm.Wq2 = (const __half *)desc->Wq2;
+    fm.Wk1 = (const __half *)desc->Wk1; fm.Wk2 = (const __half *)desc->Wk2;
+    fm.out = reinterpret_cast<float *>(ws + w.off_parts);
+    fm.B = desc->batch; fm.Hh = desc->heads; fm.D = desc->head_dim; fm.Rp = desc->hidden; fm.R = desc->rank;
+    return launch_mlp_parts(fm, st) == hipSuccess ? LESSDEC_OK : LESSDEC_EHIP;
+  }
+  // general path: phi(q), psi(k) in fp64
+  FeatmapArgs fa;
+  fa.B = desc->batch; fa.Hh = desc->heads; fa.rpu = 1;
+  fa.D = desc->head_dim; fa.Rp = desc->hidden; fa.R = desc->rank;
+  fa.x = q; fa.W1 = desc->Wq1; fa.W2 = desc->Wq2; fa.W3 = nullptr;
+  fa.out = reinterpret_cast<double *>(ws + w.off_fphi); fa.out_f64 = 1;
+  if (launch_featmap_generic(fa, desc->dtype, st) != hipSuccess) return LESSDEC_EHIP;
+  fa.x = k; fa.W1 = desc->Wk1; fa.W2 = desc->Wk2; fa.W3 = desc->Wk3;
+  fa.out = reinterpret_cast<float *>(ws + w.off_fpsi); fa.out_f64 = 0;
+  if (launch_featmap_generic(fa, desc->dtype, st) != hipSuccess) return LESSDEC_EHIP;
+  return LESSDEC_OK;
+}
+
+int lessdec_step_attend(const lessdec_desc *desc, const void *q, const void *k, const void *v, void *out,
+                        int32_t *evicted_pos, void *hip_stream)
 {
   Shape s;
   int rc = check_desc(desc, &s, 0);
@@ -140,30 +172,28 @@ int lessdec_step(const lessdec_desc *desc, const void *q, const void *k, const v
   const Workspace w = carve(s, 0);
   char *ws = static_cast<char *>(desc->workspace);
   if (wpu_supported(desc->dtype, desc->head_dim, (int)s.C, desc->hidden, desc->rank)) {
-    // matrix-core feature maps up to the layer-2 sums, then one wave per unit
-    MlpPartsArgs fm;
-    fm.q = (const __half *)q; fm.k = (const __half *)k;
-    fm.Wq1 = (const __half *)desc->Wq1; fm.Wq2 = (const __half *)desc->Wq2;
-    fm.Wk1 = (const __half *)desc->Wk1; fm.Wk2 = (const __half *)desc->Wk2;
-    fm.out = reinterpret_cast<float *>(ws + w.off_parts);
-    fm.B = desc->batch; fm.Hh = desc->heads; fm.D = desc->head_dim; fm.Rp = desc->hidden; fm.R = desc->rank;
-    if (launch_mlp_parts(fm, st) != hipSuccess) return LESSDEC_EHIP;
-    a.mlp_parts = fm.out;
+    a.mlp_parts = reinterpret_cast<float *>(ws + w.off_parts);     // one wave per unit
     return launch_step_wpu(a, desc->head_dim, st) == hipSuccess ? LESSDEC_OK : LESSDEC_EHIP;
   }
-  // general path: phi(q), psi(k) in fp64, then one block per unit
-  double *f_phi = reinterpret_cast<double *>(ws + w.off_fphi);
-  float *f_psi = reinterpret_cast<float *>(ws + w.off_fpsi);
-  FeatmapArgs fa;
-  fa.B = desc->batch; fa.Hh = desc->heads; fa.rpu = 1;
-  fa.D = desc->head_dim; fa.Rp = desc->hidden; fa.R = desc->rank;
-  fa.x = q; fa.W1 = desc->Wq1; fa.W2 = desc->Wq2; fa.W3 = nullptr; fa.out = f_phi; fa.out_f64 = 1;
-  if (launch_featmap_generic(fa, desc->dtype, st) != hipSuccess) return LESSDEC_EHIP;
-  fa.x = k; fa.W1 = desc->Wk1; fa.W2 = desc->Wk2; fa.W3 = desc->Wk3; fa.out = f_psi; fa.out_f64 = 0;
-  if (launch_featmap_generic(fa, desc->dtype, st) != hipSuccess) return LESSDEC_EHIP;
-  a.f_phi = f_phi; a.f_psi = f_psi;
-  if (launch_step(a, desc->dtype, desc->head_dim, st) != hipSuccess) return LESSDEC_EHIP;
-  return LESSDEC_OK;
+  a.f_phi = reinterpret_cast<double *>(ws + w.off_fphi);           // one block per unit
+  a.f_psi = reinterpret_cast<float *>(ws + w.off_fpsi);
+  return launch_step(a, desc->dtype, desc->head_dim, st) == hipSuccess ? LESSDEC_OK : LESSDEC_EHIP;
+}
+
+int lessdec_step(const lessdec_desc *desc, const void *q, const void *k, const void *v, void *out,
+                 int32_t *evicted_pos, void *hip_stream)
+{
+  // argument checks of both halves first, so that nothing is launched on an error
+  Shape s;
+  int rc = check_desc(desc, &s, 0);
+  if (rc) return rc;
+  if (!q || !k || !v || !out) return LESSDEC_EINVAL;
+  if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(out, 16) ||
+      !aligned(evicted_pos, 4))
+    return LESSDEC_EINVAL;
+  rc = lessdec_step_features(desc, q, k, hip_stream);
+  if (rc) return rc;
+  return lessdec_step_attend(desc, q, k, v, out, evicted_pos, hip_stream);
 }
 
 int lessdec_prefill(const lessdec_desc *desc, const void *Q, const void *K, const void *V,

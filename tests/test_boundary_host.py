@@ -69,6 +69,8 @@ def test_calls_reject_bad_descriptors_on_the_host():
     assert L.lessdec_state_reset(C.byref(d), None) == binding.EINVAL
     assert L.lessdec_state_sync(C.byref(d), None) == binding.EINVAL
     assert L.lessdec_step(C.byref(d), None, None, None, None, None, None) == binding.EINVAL
+    assert L.lessdec_step_features(C.byref(d), None, None, None) == binding.EINVAL
+    assert L.lessdec_step_attend(C.byref(d), None, None, None, None, None, None) == binding.EINVAL
     assert L.lessdec_prefill(C.byref(d), None, None, None, 16, None, None) == binding.EINVAL
     # plausible pointers but no workspace -> workspace error; misaligned cache -> invalid
     for f in ("k_cache", "v_cache", "acc", "pos", "psi", "H", "z", "n_seen",
@@ -83,6 +85,8 @@ def test_calls_reject_bad_descriptors_on_the_host():
     d.k_cache = 0x10000
     assert L.lessdec_prefill(C.byref(d), 0x30000, 0x30000, 0x30000, 0, None, None) == binding.EINVAL
     assert L.lessdec_step(C.byref(d), 0x30000, 0x30000, 0x30004, 0x30000, None, None) == binding.EINVAL
+    assert L.lessdec_step_features(C.byref(d), 0x30000, 0x30008, None) == binding.EINVAL
+    assert L.lessdec_step_attend(C.byref(d), 0x30000, 0x30000, 0x30000, None, None, None) == binding.EINVAL
     assert b"workspace" in L.lessdec_strerror(binding.EWORKSPACE)
     assert L.lessdec_strerror(12345) is not None
 

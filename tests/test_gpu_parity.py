@@ -148,6 +148,36 @@ def test_checkpoint_restore_continues_bit_identically():
 
 
 @pytest.mark.parametrize("kind", ["streaming", "general"])
+def test_step_equals_its_two_halves(kind):
+    """lessdec_step is lessdec_step_features followed by lessdec_step_attend."""
+    import torch
+    w = small("halves", steps=20) if kind == "streaming" else small("halves-general", steps=20, rank=20)
+    inp = wl.all_inputs(w)
+    res = hz.gpu_run(w, {k: (v if k in "QKV" else v[:0]) for k, v in inp.items()})      # prompt phase only
+    gpu = res["gpu"]
+    names = gpu.STATE
+    saved = {n: getattr(gpu, n).clone() for n in names}
+    q, k, v = (torch.from_numpy(inp[n]).cuda() for n in ("q", "k", "v"))
+    T = q.shape[0]
+    got = []
+    for split in (False, True):
+        for n in names:
+            getattr(gpu, n).copy_(saved[n])
+        outs = torch.empty_like(q); ev = torch.empty((T, w.units), dtype=torch.int32, device="cuda")
+        for t in range(T):
+            if split:
+                gpu.step_features(q[t], k[t])
+                gpu.step_attend(q[t], k[t], v[t], outs[t], ev[t])
+            else:
+                gpu.step(q[t], k[t], v[t], outs[t], ev[t])
+        torch.cuda.synchronize()
+        got.append((outs.cpu(), ev.cpu(), {n: getattr(gpu, n).cpu().clone() for n in names}))
+    assert torch.equal(got[0][0], got[1][0]) and torch.equal(got[0][1], got[1][1])
+    for n in names:
+        assert torch.equal(got[0][2][n], got[1][2][n]), n
+
+
+@pytest.mark.parametrize("kind", ["streaming", "general"])
 def test_steps_replayed_from_a_hip_graph_match_eager_steps(kind):
     """The step reads and advances its counters on the device and clears nothing with a memset,
     so one captured step can be replayed for a whole sequence.  Every replay is checked against
