@@ -39,8 +39,12 @@ constexpr int kWpuMaxRows = 512;    // C + 1 at most
 //          for the next step.
 // =====================================================================================
 template <int D, int NR2, int RM, int DEPTH>
-__global__ __launch_bounds__(kWpuUnits * kWave) void wpu_step_kernel(const StepArgs a)
+__global__ __launch_bounds__(kWpuUnits * kWave) void wpu_step_kernel(void *k_cache_, const void *q_, const void *k_,
+                                                                    int C_, int Hh_, int B_, const StepArgs a)
 {
+  // The first arguments repeat what the head of the kernel needs to request the first rows:
+  // scalar arguments can be preloaded into registers by the launch (the compile flag asks for
+  // it), the struct has to be fetched.
   using T = __half;
   constexpr int EPL = 8;                   // elements per lane
   constexpr int LPR = D / EPL;             // lanes per row
@@ -50,22 +54,22 @@ __global__ __launch_bounds__(kWpuUnits * kWave) void wpu_step_kernel(const StepA
 
   extern __shared__ double dyn[];
 
-  const int C = a.C, R = a.R, Hh = a.Hh;
+  const int C = C_, R = a.R, Hh = Hh_;
   const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
   const int lr = lane % LPR, rb = lane / LPR;
   const int h = (int)blockIdx.x % Hh, chunk = (int)blockIdx.x / Hh;
   const int bb = chunk * kWpuUnits + wave;
-  if (bb >= a.B) return;                                     // wave-uniform; the waves share nothing
+  if (bb >= B_) return;                                      // wave-uniform; the waves share nothing
   const int u = bb * Hh + h;
   const int rows_cap = (C + 2) & ~1;
   double *s_sc = dyn + (size_t)wave * rows_cap;                                    // [C+1] scores
   float *s_p = reinterpret_cast<float *>(dyn + (size_t)kWpuUnits * rows_cap) + (size_t)wave * rows_cap;
 
-  T *kc = reinterpret_cast<T *>(a.k_cache) + (size_t)u * C * D;
+  T *kc = reinterpret_cast<T *>(k_cache_) + (size_t)u * C * D;
   T *vc = reinterpret_cast<T *>(a.v_cache) + (size_t)u * C * D;
-  const T *qn = reinterpret_cast<const T *>(a.q) + (size_t)u * D;
-  const T *kn = reinterpret_cast<const T *>(a.k) + (size_t)u * D;
+  const T *qn = reinterpret_cast<const T *>(q_) + (size_t)u * D;
+  const T *kn = reinterpret_cast<const T *>(k_) + (size_t)u * D;
   const T *vn = reinterpret_cast<const T *>(a.v) + (size_t)u * D;
 
   // ---- requests, in the order they are wanted back ------------------------------------------------
@@ -412,9 +416,9 @@ static hipError_t launch_step_wpu_t(const StepArgs &a, hipStream_t st)
   const size_t lds = (size_t)kWpuUnits * rows_cap * (sizeof(double) + sizeof(float));
   const unsigned grid = (unsigned)(a.Hh * ((a.B + kWpuUnits - 1) / kWpuUnits));
   const int rows = a.C + 1;
-  if (rows <= 2 * kWave) wpu_step_kernel<D, 2, RM, kDepth><<<grid, kWpuUnits * kWave, lds, st>>>(a);
-  else if (rows <= 4 * kWave) wpu_step_kernel<D, 4, RM, kDepth><<<grid, kWpuUnits * kWave, lds, st>>>(a);
-  else wpu_step_kernel<D, kWpuMaxRows / kWave, RM, kDepth><<<grid, kWpuUnits * kWave, lds, st>>>(a);
+  if (rows <= 2 * kWave) wpu_step_kernel<D, 2, RM, kDepth><<<grid, kWpuUnits * kWave, lds, st>>>(a.k_cache, a.q, a.k, a.C, a.Hh, a.B, a);
+  else if (rows <= 4 * kWave) wpu_step_kernel<D, 4, RM, kDepth><<<grid, kWpuUnits * kWave, lds, st>>>(a.k_cache, a.q, a.k, a.C, a.Hh, a.B, a);
+  else wpu_step_kernel<D, kWpuMaxRows / kWave, RM, kDepth><<<grid, kWpuUnits * kWave, lds, st>>>(a.k_cache, a.q, a.k, a.C, a.Hh, a.B, a);
   return hipGetLastError();
 }
 
