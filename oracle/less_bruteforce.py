@@ -1,4 +1,4 @@
-"""Set-based brute-force simulator of H2O + LESS for tiny inputs.
+"""Set-based brute-force simulator of H2O (or Lambda-masking) + LESS for tiny inputs.
 
 TEST INFRASTRUCTURE ONLY.  A second, deliberately different statement of the
 same semantics as oracle/less_oracle.c, used to pin it:
@@ -33,7 +33,9 @@ def psi(k, Wk1, Wk2, Wk3):
 
 
 class BruteForceUnit:
-    def __init__(self, head_dim, n_heavy, n_recent, W, sparse_denominator=False):
+    def __init__(self, head_dim, n_heavy, n_recent, W, sparse_denominator=False, policy="h2o"):
+        assert policy in ("h2o", "lambda")
+        self.policy = policy
         self.D, self.Nh, self.Nr = head_dim, n_heavy, n_recent
         self.W = {k: np.asarray(v, dtype=np.float64) for k, v in W.items()}
         self.sparse_denominator = sparse_denominator
@@ -66,8 +68,11 @@ class BruteForceUnit:
         else:
             recent = set(range(P - self.Nr, P))
             rest = [p for p in range(P) if p not in recent]
-            rest.sort(key=lambda p: (col[p], p))
-            heavy = set(rest[len(rest) - self.Nh:]) if self.Nh else set()
+            if self.policy == "lambda":
+                heavy = set(range(self.Nh))          # the first tokens of the sequence
+            else:
+                rest.sort(key=lambda p: (col[p], p))
+                heavy = set(rest[len(rest) - self.Nh:]) if self.Nh else set()
             self.alive = recent | heavy
             self.discarded = sorted(set(rest) - heavy)
         self.score = {p: col[p] for p in self.alive}
@@ -93,7 +98,10 @@ class BruteForceUnit:
         if len(self.alive) > self.Nh + self.Nr:
             newest = sorted(self.alive)[len(self.alive) - self.Nr:] if self.Nr else []
             cand = [p for p in self.alive if p not in newest]
-            evicted = min(cand, key=lambda p: (self.score[p], p))
+            if self.policy == "lambda":
+                evicted = min(p for p in cand if p >= self.Nh or p == n)
+            else:
+                evicted = min(cand, key=lambda p: (self.score[p], p))
             self.alive.remove(evicted); del self.score[evicted]
             self.discarded.append(evicted)
         return out, evicted

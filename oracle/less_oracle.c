@@ -24,6 +24,13 @@
  *                                        are accumulated per cached token; the
  *                                        budget is split into heavy hitters and
  *                                        most recent tokens (Sec. 4)
+ *   second sparse policy ............... Lambda-masking (Sec. 4, "Setup"): the
+ *                                        cache holds the first tokens of the
+ *                                        sequence and the most recent ones, so
+ *                                        the pair that leaves is always the
+ *                                        oldest one that is not among the first
+ *                                        (flag bit 1; n_heavy then counts the
+ *                                        kept first tokens, 4 in the paper)
  *   - in-place replacement ............. Sec. 3.2, "Efficient Generation"
  *   - prompt phase ..................... regular attention (remark after Eq. 3)
  *   Readings where the paper is silent (listed in the design notes as well):
@@ -44,6 +51,8 @@
 #include <string.h>
 
 #define LESS_FLAG_SPARSE_DENOM 1u /* accumulate e^s / (sparse-only denominator) */
+#define LESS_FLAG_LAMBDA 2u       /* Lambda-masking instead of H2O: keep the first n_heavy
+                                     tokens and the n_recent most recent ones              */
 
 typedef struct less_oracle_state {
   int32_t U, heads, D, n_heavy, n_recent, R, Rp;
@@ -172,7 +181,9 @@ static void fold_into_state(unit_view *s, const double *k, const double *v)
  *   out        [D]  : a-hat_t (Eq. 3)
  *   evicted    [1]  : original position of the pair folded into H, z; -1 none
  *   dec        [4]  : smallest and second smallest candidate (score, position);
- *                     position -1 where there is no such candidate
+ *                     position -1 where there is no such candidate.  Under
+ *                     Lambda-masking the policy's key is the position alone and
+ *                     "score" repeats it.
  *   share      [1]  : low-rank share of the denominator, phi(q) z^T / den
  * returns 0, or -1 if force_pos names no eviction candidate.
  */
@@ -254,6 +265,7 @@ static int step_unit(unit_view *s, const double *q, const double *k, const doubl
     s->acc[slot] = acc_new; s->pos[slot] = n;
   } else {
     /* recent = the Nr largest positions, the new token (position n) included */
+    const int lambda = (s->flags & LESS_FLAG_LAMBDA) != 0;
     int best = -2, second = -2;                          /* -1 denotes the new token */
     double bacc = INFINITY, sacc = INFINITY; int64_t bpos = -1, spos = -1;
     int forced = -2;
@@ -261,6 +273,11 @@ static int step_unit(unit_view *s, const double *q, const double *k, const doubl
       double a; int64_t p;
       if (j < 0) { if (s->Nr != 0) continue; a = acc_new; p = n; }
       else { if (s->pos[j] > n - s->Nr) continue; a = s->acc[j]; p = s->pos[j]; }
+      if (lambda) {
+        /* the first Nh tokens of the sequence stay for good; of the others the oldest leaves */
+        if (j >= 0 && p < s->Nh) continue;
+        a = (double)p;
+      }
       if (p == force_pos) forced = j;
       if (a < bacc || (a == bacc && p < bpos)) {
         second = best; sacc = bacc; spos = bpos;
@@ -305,7 +322,9 @@ static int cmp_scored(const void *x, const void *y)
  * Prompt phase of one unit: regular causal attention (H_0 = z_0 = 0), then the
  * cache is cut to the budget in one shot: the last Nr tokens are kept as
  * recent, the Nh tokens with the largest column sums of the attention matrix
- * as heavy hitters, and every other token is folded into H, z (Eq. 6).
+ * as heavy hitters (under Lambda-masking: the first Nh tokens instead), and
+ * every other token is folded into H, z (Eq. 6).  The column sums become the
+ * kept tokens' accumulated scores under either policy.
  *   out     [P,D] or NULL
  *   colsum  [P]   or NULL : accumulated attention probability of every token
  *   kept    [P]   or NULL : 1 kept, 0 discarded
@@ -345,6 +364,8 @@ static void prefill_unit(unit_view *s, const double *Q, const double *K, const d
   dec[0] = dec[2] = INFINITY; dec[1] = dec[3] = -1.0;
   if (P <= C) {
     for (int64_t j = 0; j < P; ++j) kept[j] = 1;
+  } else if (s->flags & LESS_FLAG_LAMBDA) {
+    for (int64_t j = 0; j < P; ++j) kept[j] = (j < s->Nh || j >= P - s->Nr) ? 1 : 0;
   } else {
     int64_t ncand = P - s->Nr;                            /* positions < P - Nr */
     scored *c = (scored *)malloc(sizeof(scored) * (size_t)(ncand > 0 ? ncand : 1));

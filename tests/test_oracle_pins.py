@@ -187,6 +187,9 @@ def test_zero_feature_maps_is_pure_h2o():
 @pytest.mark.parametrize("Nh,Nr,P,T,flags,seed", [
     (3, 3, 17, 25, 0, 0), (3, 3, 17, 25, 1, 1), (4, 0, 9, 14, 0, 2), (0, 5, 12, 14, 0, 3),
     (2, 6, 0, 30, 0, 4), (5, 2, 4, 20, 1, 5), (1, 1, 30, 10, 0, 6), (8, 8, 64, 24, 0, 7),
+    # Lambda-masking (flag bit 1), alone and with the sparse-denominator reading
+    (4, 6, 21, 25, 2, 8), (4, 6, 0, 30, 2, 9), (3, 0, 9, 12, 2, 10), (0, 5, 12, 14, 2, 11),
+    (2, 3, 4, 20, 3, 12),
 ])
 def test_against_set_based_twin(Nh, Nr, P, T, flags, seed):
     """Outputs, eviction log, kept set and state equal the brute-force simulator's."""
@@ -196,7 +199,8 @@ def test_against_set_based_twin(Nh, Nr, P, T, flags, seed):
     st = lo.OracleState(U, heads, D, Nh, Nr, R, Rp, W, flags=flags)
     Q, K, V = (rng.standard_normal((U, P, D)) for _ in range(3))
     q, k, v = (rng.standard_normal((T, U, D)) for _ in range(3))
-    twins = [BruteForceUnit(D, Nh, Nr, head_w(W, u % heads), sparse_denominator=bool(flags))
+    twins = [BruteForceUnit(D, Nh, Nr, head_w(W, u % heads), sparse_denominator=bool(flags & 1),
+                            policy="lambda" if flags & 2 else "h2o")
              for u in range(U)]
     if P:
         pre = st.prefill(Q, K, V)
@@ -217,6 +221,51 @@ def test_against_set_based_twin(Nh, Nr, P, T, flags, seed):
             np.testing.assert_allclose(st.z[u], zc, rtol=1e-10, atol=1e-13)
             for j in np.flatnonzero(st.pos[u] >= 0):
                 assert st.acc[u, j] == pytest.approx(tw.score[int(st.pos[u, j])], rel=1e-10)
+
+
+@pytest.mark.parametrize("P", [0, 5, 40])
+def test_lambda_masking_keeps_the_first_and_the_latest_tokens(P):
+    """Sec. 4, "Setup": under Lambda-masking the cache is the first tokens plus the most
+    recent ones.  That fixes everything about the policy in closed form: after n tokens the
+    cache is {0..Nh-1} and {n-Nr..n-1}, token n-Nr leaves when token n arrives, and H, z
+    are Eq. 6 over positions Nh..n-Nr-1; the output is Eq. 3 written out over those sets."""
+    rng = np.random.default_rng(21 + P)
+    U, heads, D, Rp, R, Nh, Nr, T = 2, 2, 6, 10, 3, 4, 7, 30
+    W = make_weights(rng, heads, D, Rp, R)
+    st = lo.OracleState(U, heads, D, Nh, Nr, R, Rp, W, flags=2)
+    Q, K, V = (rng.standard_normal((U, P, D)) for _ in range(3))
+    q, k, v = (rng.standard_normal((T, U, D)) for _ in range(3))
+    if P:
+        pre = st.prefill(Q, K, V)
+        want = np.zeros(P, bool); want[:Nh] = True; want[max(P - Nr, 0):] = True
+        if P <= Nh + Nr:
+            want[:] = True
+        assert (pre["kept"] == want).all()
+    else:
+        st.reset()
+    keys = [[K[u, i] for i in range(P)] for u in range(U)]
+    vals = [[V[u, i] for i in range(P)] for u in range(U)]
+    for t in range(T):
+        n = P + t
+        r = st.step(q[t], k[t], v[t])
+        for u in range(U):
+            Wh = head_w(W, u % heads)
+            cached = sorted(set(range(min(Nh, n))) | set(range(max(n - Nr, 0), n)))
+            if n <= Nh + Nr:
+                cached = list(range(n))
+            gone = [p for p in range(n) if p not in cached]
+            keys[u].append(k[t, u]); vals[u].append(v[t, u])
+            g = [bf_psi(keys[u][p], Wh["Wk1"], Wh["Wk2"], Wh["Wk3"]) for p in gone]
+            H = sum((np.outer(gp, vals[u][p]) for gp, p in zip(g, gone)), np.zeros((R, D)))
+            z = sum(g, np.zeros(R))
+            f = bf_phi(q[t, u], Wh["Wq1"], Wh["Wq2"])
+            w = np.array([np.exp(q[t, u] @ keys[u][p] / np.sqrt(D)) for p in cached + [n]])
+            num = f @ H + w @ np.array([vals[u][p] for p in cached + [n]])
+            np.testing.assert_allclose(r["out"][u], num / (f @ z + w.sum()), rtol=1e-9, atol=1e-12)
+            assert r["evicted"][u] == (n - Nr if n >= Nh + Nr else -1)
+    n = P + T
+    for u in range(U):
+        assert sorted(st.pos[u]) == list(range(Nh)) + list(range(n - Nr, n))
 
 
 def test_policy_invariants_and_convexity():
