@@ -41,6 +41,12 @@ extern "C" {
 /* flags */
 #define LESSDEC_FLAG_SPARSE_DENOM 1u /* H2O accumulates e^s over the sparse-only denominator
                                         instead of the full denominator of Eq. 3            */
+#define LESSDEC_FLAG_LAMBDA 2u       /* sparse policy: Lambda-masking instead of H2O (Sec. 4,
+                                        "Setup"): the cache keeps the first n_heavy tokens of
+                                        the sequence (4 in the paper) and the n_recent most
+                                        recent ones, so the oldest token that is not one of
+                                        the first leaves.  Scores are still accumulated in
+                                        acc but decide nothing                              */
 
 #define LESSDEC_OK 0
 #define LESSDEC_EINVAL (-1)    /* bad shape, NULL or misaligned pointer, unsupported size */

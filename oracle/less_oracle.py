@@ -21,6 +21,7 @@ _LIB = _HERE / "libless_oracle.so"
 _lib = None
 
 FLAG_SPARSE_DENOM = 1
+FLAG_LAMBDA = 2          # Lambda-masking instead of H2O (Sec. 4, setup)
 
 
 def build(force: bool = False) -> Path:

@@ -26,7 +26,7 @@ bool shape_ok(const lessdec_desc *d, Shape *s)
   if (d->rank < 1 || d->rank > LESSDEC_MAX_RANK) return false;
   if (d->hidden < 1 || d->hidden > LESSDEC_MAX_HIDDEN) return false;
   if (d->dtype != LESSDEC_DTYPE_F32 && d->dtype != LESSDEC_DTYPE_F16) return false;
-  if (d->flags & ~LESSDEC_FLAG_SPARSE_DENOM) return false;
+  if (d->flags & ~(LESSDEC_FLAG_SPARSE_DENOM | LESSDEC_FLAG_LAMBDA)) return false;
   if ((long)d->batch * d->heads > (1L << 30)) return false;
   s->U = (size_t)d->batch * d->heads;
   s->C = (size_t)C;

@@ -205,11 +205,13 @@ __global__ __launch_bounds__(64) void prefill_colpass_kernel(
 // -------------------------------------------------------------------------------------
 // Selection: the last Nr tokens are recent; among the others the Nh largest (column sum,
 // position) pairs are heavy hitters; everything else is discarded.  Exact rank counting,
-// no sort: token j is heavy iff fewer than Nh candidates are larger.  Kept tokens get
-// slots in ascending position.  grid = U, block = 256.
+// no sort: token j is heavy iff fewer than Nh candidates are larger.  Under Lambda-masking
+// (Sec. 4, "Setup") the first Nh tokens take the place of the heavy hitters.  Kept tokens
+// get slots in ascending position.  grid = U, block = 256.
 // -------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void prefill_select_kernel(const double *__restrict__ colsum, int P,
-                                                             int Nh, int Nr, int32_t *__restrict__ slot_of)
+                                                             int Nh, int Nr, int lambda,
+                                                             int32_t *__restrict__ slot_of)
 {
   __shared__ int s_cnt[256];
   const size_t u = blockIdx.x;
@@ -221,7 +223,9 @@ __global__ __launch_bounds__(256) void prefill_select_kernel(const double *__res
   // 1) kept flag (1 / 0) into slot_of
   for (int j = tid; j < P; j += 256) {
     int keep = 1;
-    if (P > C && j < ncand) {
+    if (P > C && lambda) {
+      keep = (j < Nh || j >= ncand) ? 1 : 0;
+    } else if (P > C && j < ncand) {
       const double a = cs[j];
       int larger = 0;
       for (int i = 0; i < ncand; ++i) {
@@ -334,7 +338,8 @@ static hipError_t launch_prefill_t(const PrefillArgs &a, hipStream_t st)
   prefill_colpass_kernel<T, D><<<grid, 64, 0, st>>>((const T *)a.Q, (const T *)a.K, P, a.rowmax,
                                                     a.rowsum, a.colsum);
   if ((e = hipGetLastError()) != hipSuccess) return e;
-  prefill_select_kernel<<<U, 256, 0, st>>>(a.colsum, P, d->n_heavy, d->n_recent, a.slot_of);
+  prefill_select_kernel<<<U, 256, 0, st>>>(a.colsum, P, d->n_heavy, d->n_recent,
+                                           (d->flags & LESSDEC_FLAG_LAMBDA) ? 1 : 0, a.slot_of);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   if (mlp_mfma_supported(d->dtype, d->head_dim, d->hidden, d->rank)) {
     MlpArgs fm;

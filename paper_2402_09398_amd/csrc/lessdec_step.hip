@@ -242,6 +242,7 @@ __global__ __launch_bounds__(256, step_waves_per_simd(NIT)) void step_kernel(con
     double ascale = pscale;
     if (a.flags & LESSDEC_FLAG_SPARSE_DENOM) ascale = 1.0 / S;
 
+    const bool lambda = (a.flags & LESSDEC_FLAG_LAMBDA) != 0;
     Cand best = cand_none();
     for (int j = lane, i = 0; j < rows; j += kWave, ++i) {
       const double e = s_sc[j];
@@ -259,8 +260,10 @@ __global__ __launch_bounds__(256, step_waves_per_simd(NIT)) void step_kernel(con
       }
       s_sc[j] = na;
       if (full) {
-        const bool is_cand = (j < m) ? (pj <= n - a.Nr) : (a.Nr == 0);
-        const Cand cnd{na, pj, j};
+        // H2O: every pair that is not among the Nr most recent competes on its score;
+        // Lambda-masking: the first Nh tokens never leave and the oldest of the others does
+        const bool is_cand = (j < m) ? (pj <= n - a.Nr && (!lambda || pj >= a.Nh)) : (a.Nr == 0);
+        const Cand cnd{lambda ? 0.0 : na, pj, j};
         if (is_cand && cand_less(cnd, best)) best = cnd;
       }
     }

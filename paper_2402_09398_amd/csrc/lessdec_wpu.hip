@@ -256,6 +256,7 @@ __global__ __launch_bounds__(kWpuUnits * kWave) void wpu_step_kernel(void *k_cac
       double ascale = pscale;
       if (a.flags & LESSDEC_FLAG_SPARSE_DENOM) ascale = 1.0 / S;
 
+      const bool lambda = (a.flags & LESSDEC_FLAG_LAMBDA) != 0;
       Cand best = cand_none();
 #pragma unroll
       for (int i = 0; i < NR2; ++i) {
@@ -271,8 +272,10 @@ __global__ __launch_bounds__(kWpuUnits * kWave) void wpu_step_kernel(void *k_cac
           }
           sc[i] = na;
           if (full) {
-            const bool is_cand = (j < m) ? (pj <= n - a.Nr) : (a.Nr == 0);
-            const Cand cnd{na, pj, j};
+            // H2O: every pair that is not among the Nr most recent competes on its score;
+            // Lambda-masking: the first Nh tokens never leave and the oldest of the others does
+            const bool is_cand = (j < m) ? (pj <= n - a.Nr && (!lambda || pj >= a.Nh)) : (a.Nr == 0);
+            const Cand cnd{lambda ? 0.0 : na, pj, j};
             if (is_cand && cand_less(cnd, best)) best = cnd;
           }
         }

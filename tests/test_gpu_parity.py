@@ -27,6 +27,11 @@ def small(name, **kw):
     return BASE.scaled(**d)
 
 
+def sample_units(w, count, seed=0):
+    rng = np.random.default_rng(seed)
+    return sorted(int(u) for u in rng.choice(w.units, size=min(count, w.units), replace=False))
+
+
 def report_ok(rep, min_decisions=0):
     print("\n" + rep.summary(), flush=True)
     assert rep.ok(), rep.failures[:10]
@@ -89,6 +94,37 @@ def test_sparse_denominator_reading():
     w = small("sparse-denominator")
     rep = hz.run_workload(w, range(w.units), flags=1)
     report_ok(rep, min_decisions=w.units * w.steps)
+
+
+# Lambda-masking (Sec. 4, "Setup": the first 4 tokens and the most recent ones) on both decode
+# paths; positions are distinct, so no eviction is ever within the tie exemption
+LAMBDA = [
+    small("lambda-streaming", n_heavy=4, n_recent=8),
+    small("lambda-general-f32", n_heavy=4, n_recent=8, dtype="f32", head_dim=64, rank=4),
+    small("lambda-no-prompt", n_heavy=4, n_recent=5, prompt=0, steps=30),
+    small("lambda-prompt-fits", n_heavy=4, n_recent=12, prompt=7, steps=30),
+    small("lambda-window-only", n_heavy=0, n_recent=9),
+    small("lambda-no-window", n_heavy=5, n_recent=0, prompt=20, steps=12),
+    small("lambda-sparse-denominator", n_heavy=4, n_recent=8),
+]
+
+
+@pytest.mark.parametrize("w", LAMBDA, ids=lambda w: w.name)
+def test_lambda_masking_policy(w):
+    flags = 3 if w.name.endswith("sparse-denominator") else 2
+    rep = hz.run_workload(w, range(w.units), flags=flags)
+    report_ok(rep, min_decisions=w.units * max(0, min(w.steps, w.prompt + w.steps - w.capacity)))
+    assert rep.exempt == 0
+
+
+def test_lambda_masking_at_the_benchmark_shape():
+    """Config 3's shape and budget with the paper's split for this policy: 4 first tokens,
+    the rest of the 102 slots recent."""
+    w = wl.WORKLOADS[3].scaled(name="cfg3-lambda", n_heavy=4, n_recent=98)
+    units = sample_units(w, 8, seed=33)
+    rep = hz.run_workload(w, units, flags=2, want_prefill_out=False)
+    report_ok(rep, min_decisions=len(units) * w.steps)
+    assert rep.exempt == 0 and 0.0 < rep.mean_share < 1.0
 
 
 def test_maximum_capacity():
@@ -224,11 +260,6 @@ def test_steps_replayed_from_a_hip_graph_match_eager_steps(kind):
 
 
 # ------------------------------------------------------------------ the five configurations
-def sample_units(w, count, seed=0):
-    rng = np.random.default_rng(seed)
-    return sorted(int(u) for u in rng.choice(w.units, size=min(count, w.units), replace=False))
-
-
 @pytest.mark.parametrize("cfg,count", [(1, 2), (2, 24), (3, 16), (4, 10), (5, 6)])
 def test_configuration_full_size(cfg, count):
     w = wl.WORKLOADS[cfg]
