@@ -37,10 +37,10 @@ bool shape_ok(const lessdec_desc *d, Shape *s)
 }
 
 // Workspace: [ f_phi U*R f64 | f_psi U*R f32 | mlp_parts 2*ceil(R'/64)*U*16 f32 |
-//              prefill: rowmax, rowsum, colsum U*P f64 | slot_of U*P i32 | psi_all U*P*R f32 ],
+//              prefill: lse, colsum U*P f64 | slot_of U*P i32 | psi_all U*P*R f32 ],
 // every part 256-byte aligned.
 struct Workspace {
-  size_t off_fphi, off_fpsi, off_parts, off_rowmax, off_rowsum, off_colsum, off_slot,
+  size_t off_fphi, off_fpsi, off_parts, off_lse, off_colsum, off_slot,
       off_psiall, total;
 };
 
@@ -51,8 +51,7 @@ Workspace carve(const Shape &s, size_t P)
   w.off_fphi = o; o = align_up(o + s.U * s.R * sizeof(double), 256);
   w.off_fpsi = o; o = align_up(o + s.U * s.R * sizeof(float), 256);
   w.off_parts = o; o = align_up(o + 2 * (size_t)mlp_nparts((int)s.Rp) * s.U * 16 * sizeof(float), 256);
-  w.off_rowmax = o; o = align_up(o + s.U * P * sizeof(double), 256);
-  w.off_rowsum = o; o = align_up(o + s.U * P * sizeof(double), 256);
+  w.off_lse = o; o = align_up(o + s.U * P * sizeof(double), 256);
   w.off_colsum = o; o = align_up(o + s.U * P * sizeof(double), 256);
   w.off_slot = o; o = align_up(o + s.U * P * sizeof(int32_t), 256);
   w.off_psiall = o; o = align_up(o + s.U * P * s.R * sizeof(float), 256);
@@ -210,8 +209,7 @@ int lessdec_prefill(const lessdec_desc *desc, const void *Q, const void *K, cons
   char *ws = static_cast<char *>(desc->workspace);
   PrefillArgs a;
   a.d = desc; a.Q = Q; a.K = K; a.V = V; a.P = P; a.out = out;
-  a.rowmax = reinterpret_cast<double *>(ws + w.off_rowmax);
-  a.rowsum = reinterpret_cast<double *>(ws + w.off_rowsum);
+  a.lse = reinterpret_cast<double *>(ws + w.off_lse);
   a.colsum = reinterpret_cast<double *>(ws + w.off_colsum);
   a.slot_of = reinterpret_cast<int32_t *>(ws + w.off_slot);
   a.psi_all = reinterpret_cast<float *>(ws + w.off_psiall);

@@ -86,7 +86,7 @@ struct PrefillArgs {
   int P;
   void *out;
   // workspace carve-up
-  double *rowmax, *rowsum;  // [U,P]
+  double *lse;              // [U,P] ln sum_j e^{s_ij} of every causal row
   double *colsum;           // [U,P]
   int32_t *slot_of;         // [U,P] slot index of a kept token, -1 if discarded
   float *psi_all;           // [U,P,R]

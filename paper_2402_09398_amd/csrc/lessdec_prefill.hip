@@ -16,6 +16,7 @@ namespace lessdec {
 
 typedef double v4d __attribute__((ext_vector_type(4)));
 typedef float v4f __attribute__((ext_vector_type(4)));
+typedef _Float16 v4h __attribute__((ext_vector_type(4)));
 
 template <typename T, int D>
 struct Chunk {
@@ -52,27 +53,130 @@ __device__ inline v4d tile_kq(const double (&kd)[D / 4], const Chunk<T, D> &qraw
   return acc;
 }
 
+constexpr int kPrefillWaves = 4;   // independent waves (16 queries or 16 keys each) per block
+constexpr int kXcds = 8;           // workgroups go to the chip's 8 dies round-robin by index
+
+// Workgroup -> (unit, group of kPrefillWaves tiles).  Causal sweeps have very different
+// lengths, so every die gets the same sequence of groups: die x works through units x, x + 8,
+// ..., each unit's groups in order.  The dies stay balanced and a unit's rows stay in one L2.
+// grid = ceil(U / 8) * 8 * ngrp.
+struct PrefillBlock { unsigned u; int grp; };
+__device__ inline PrefillBlock prefill_block(unsigned b, int ngrp)
+{
+  const unsigned xcd = b % kXcds, r = b / kXcds;
+  return PrefillBlock{(r / (unsigned)ngrp) * kXcds + xcd, (int)(r % (unsigned)ngrp)};
+}
+
+// p V^T for one tile of 16 keys, fp32 storage: v_mfma_f32_16x16x4_f32, one key group per
+// instruction (result register w of lane (g, c) holds D[4 g + w][c]); O[b][w] is output
+// element d = 16 b + 4 g + w of query c.
+template <int D>
+__device__ inline void tile_pv(const float *Vu, int P, int j0, int g, int c, const double (&e)[4],
+                               v4f (&O)[D / 16])
+{
+#pragma unroll
+  for (int v = 0; v < 4; ++v) {
+    const int kj = j0 + g + 4 * v;
+    const float *vrow = Vu + (size_t)(kj < P ? kj : P - 1) * D;
+    const float pf = (float)e[v];
+#pragma unroll
+    for (int b = 0; b < D / 16; ++b)
+      O[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(vrow[b * 16 + c], pf, O[b], 0, 0, 0);
+  }
+}
+template <int D>
+__device__ inline void store_out(float *orow, int g, const v4f (&O)[D / 16], float inv)
+{
+#pragma unroll
+  for (int b = 0; b < D / 16; ++b)
+#pragma unroll
+    for (int w = 0; w < 4; ++w) orow[b * 16 + 4 * g + w] = O[b][w] * inv;
+}
+
+// The same for fp16 storage on v_mfma_f32_16x16x16_f16: all 16 keys in one instruction.
+// Lane (g, c) supplies k index 4 g + w, which stands for key g + 4 w (the keys whose
+// probabilities the lane holds), and row i = c of the V^T operand stands for output element
+// d = (D / 16) c + b in block b, so that a lane's operand values for all blocks are one
+// contiguous run of each key row.  The probabilities go in as an fp16 pair hi + lo (22
+// bits), accumulation is fp32.  O[b][w] is output element d = (D / 16)(4 g + w) + b.
+template <int D>
+struct VTile {
+  static constexpr int NB = D / 16;                      // blocks = halves per lane per key row
+  _Float16 h[4][NB];
+  __device__ inline void load(const __half *Vu, int P, int j0, int g, int c)
+  {
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const int kj = j0 + g + 4 * w;
+      const __half *src = Vu + (size_t)(kj < P ? kj : P - 1) * D + NB * c;
+      if constexpr (NB == 8) {
+        *reinterpret_cast<uint4 *>(h[w]) = *reinterpret_cast<const uint4 *>(src);
+      } else {
+        *reinterpret_cast<uint2 *>(h[w]) = *reinterpret_cast<const uint2 *>(src);
+      }
+    }
+  }
+};
+template <int D>
+__device__ inline void tile_pv(const VTile<D> &vt, const double (&e)[4], v4f (&O)[D / 16])
+{
+  v4h ph, pl;
+#pragma unroll
+  for (int v = 0; v < 4; ++v) {
+    const float ef = (float)e[v];
+    const _Float16 hi = (_Float16)ef;
+    ph[v] = hi;
+    pl[v] = (_Float16)(ef - (float)hi);
+  }
+#pragma unroll
+  for (int b = 0; b < D / 16; ++b) {
+    const v4h a = {vt.h[0][b], vt.h[1][b], vt.h[2][b], vt.h[3][b]};
+    O[b] = __builtin_amdgcn_mfma_f32_16x16x16f16(a, ph, O[b], 0, 0, 0);
+    O[b] = __builtin_amdgcn_mfma_f32_16x16x16f16(a, pl, O[b], 0, 0, 0);
+  }
+}
+template <int D>
+__device__ inline void store_out(__half *orow, int g, const v4f (&O)[D / 16], float inv)
+{
+  constexpr int NB = D / 16;
+  // the lane owns elements NB (4 g + w) + b: one contiguous run of 4 NB halves
+  __half run[4 * NB];
+#pragma unroll
+  for (int w = 0; w < 4; ++w)
+#pragma unroll
+    for (int b = 0; b < NB; ++b) run[NB * w + b] = __float2half_rn(O[b][w] * inv);
+#pragma unroll
+  for (int i = 0; i < 4 * NB / 8; ++i)
+    *reinterpret_cast<uint4 *>(orow + 4 * NB * g + 8 * i) = *reinterpret_cast<const uint4 *>(run + 8 * i);
+}
+
 // -------------------------------------------------------------------------------------
-// Row pass: one wave per block of 16 queries.  Sweeps the key tiles up to the diagonal,
-// keeps the running row maximum m_i and sum L_i = sum_j e^{s_ij - m_i} (fp64), and, if an
-// output is wanted, the flash-style running numerator in fp32 on v_mfma_f32_16x16x4_f32
-// (result register w of lane (g, c) holds D[4 g + w][c]).
-// grid = U * ceil(P/16), block = 64.
+// Row pass: one wave per block of 16 queries, kPrefillWaves independent waves per
+// workgroup.  Sweeps the key tiles up to the diagonal, keeps the running row maximum m_i
+// and sum L_i = sum_j e^{s_ij - m_i} (fp64) and, if an output is wanted, the flash-style
+// running numerator in fp32; the numerator is rescaled only in tiles where some row's
+// maximum moved.  The next key tile is requested before the current one is multiplied.
+// Leaves lse_i = m_i + ln L_i.
 // -------------------------------------------------------------------------------------
 template <typename T, int D>
-__global__ __launch_bounds__(64) void prefill_rowpass_kernel(
-    const T *__restrict__ Q, const T *__restrict__ K, const T *__restrict__ V, int P,
-    double *__restrict__ rowmax, double *__restrict__ rowsum, T *__restrict__ out)
+__global__ __launch_bounds__(64 * kPrefillWaves) void prefill_rowpass_kernel(
+    const T *__restrict__ Q, const T *__restrict__ K, const T *__restrict__ V, unsigned U, int P,
+    double *__restrict__ lse, T *__restrict__ out)
 {
   constexpr int CH = D / 4, DB = D / 16;
+  constexpr bool kHalf = sizeof(T) == 2;
   const int nblk = (P + 15) / 16;
-  const int it = nblk - 1 - (int)(blockIdx.x % nblk);     // long rows first
-  const size_t u = blockIdx.x / nblk;
-  const int l = threadIdx.x, g = l / 16, c = l % 16;
+  const int ngrp = (nblk + kPrefillWaves - 1) / kPrefillWaves;
+  const PrefillBlock pb = prefill_block(blockIdx.x, ngrp);
+  const int grp = ngrp - 1 - pb.grp;                      // long rows first
+  const size_t u = pb.u;
+  const int l = threadIdx.x % 64, g = l / 16, c = l % 16;
+  const int it = grp * kPrefillWaves + (int)(threadIdx.x / 64);
+  if (it >= nblk || pb.u >= U) return;                    // wave-uniform; the waves share nothing
   const int qi = it * 16 + c;
   const int qrow = qi < P ? qi : P - 1;
   const T *Qu = Q + u * (size_t)P * D, *Ku = K + u * (size_t)P * D, *Vu = V + u * (size_t)P * D;
-  const double sqrt_d = sqrt((double)D);
+  const double scale = 1.0 / sqrt((double)D);
 
   double qd[CH];
   {
@@ -86,89 +190,85 @@ __global__ __launch_bounds__(64) void prefill_rowpass_kernel(
 #pragma unroll
   for (int b = 0; b < DB; ++b) O[b] = v4f{0.f, 0.f, 0.f, 0.f};
 
+  Chunk<T, D> kraw;
+  kraw.load(Ku + (size_t)(c < P ? c : P - 1) * D, g);
   for (int jt = 0; jt <= it; ++jt) {
     const int j0 = jt * 16;
-    Chunk<T, D> kraw;
-    {
-      const int kr = j0 + c;
-      kraw.load(Ku + (size_t)(kr < P ? kr : P - 1) * D, g);
+    VTile<D> vt;
+    if constexpr (kHalf) {
+      if (out != nullptr) vt.load(reinterpret_cast<const __half *>(Vu), P, j0, g, c);
     }
     const v4d acc = tile_kq<T, D>(kraw, qd);
+    {
+      const int kr = (jt < it ? j0 + 16 : j0) + c;
+      kraw.load(Ku + (size_t)(kr < P ? kr : P - 1) * D, g);
+    }
     double s[4], tmax = -__builtin_inf();
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
       const int kj = j0 + g + 4 * v;
-      s[v] = (kj <= qi && kj < P) ? acc[v] / sqrt_d : -__builtin_inf();
+      s[v] = (kj <= qi && kj < P) ? acc[v] * scale : -__builtin_inf();
       tmax = fmax(tmax, s[v]);
     }
     tmax = fmax(tmax, __shfl_xor(tmax, 16));
     tmax = fmax(tmax, __shfl_xor(tmax, 32));
     // key j0 <= qi always holds for jt <= it, so tmax is finite for every query with qi >= j0;
     // queries past the prompt end (qi >= P) still see key j0 < P.
-    const double m_new = fmax(m_run, tmax);
-    const double alpha = exp(m_run - m_new);
+    if (__any(tmax > m_run)) {
+      const double m_new = fmax(m_run, tmax);
+      const double alpha = exp(m_run - m_new);            // 1 where the maximum stayed
+      L *= alpha;
+      m_run = m_new;
+      if (out != nullptr) {
+        const float af = (float)alpha;
+#pragma unroll
+        for (int b = 0; b < DB; ++b) O[b] *= af;
+      }
+    }
     double e[4], esum = 0.0;
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
-      e[v] = exp(s[v] - m_new);
+      e[v] = exp(s[v] - m_run);
       esum += e[v];
     }
-    L = L * alpha + esum;
-    m_run = m_new;
+    L += esum;
     if (out != nullptr) {
-      const float af = (float)alpha;
-#pragma unroll
-      for (int b = 0; b < DB; ++b) O[b] *= af;
-#pragma unroll
-      for (int v = 0; v < 4; ++v) {
-        const int kj = j0 + g + 4 * v;
-        const T *vrow = Vu + (size_t)(kj < P ? kj : P - 1) * D;
-        const float pf = (float)e[v];
-#pragma unroll
-        for (int b = 0; b < DB; ++b)
-          O[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(Store<T>::to_float(vrow[b * 16 + c]), pf, O[b],
-                                                      0, 0, 0);
-      }
+      if constexpr (kHalf) tile_pv<D>(vt, e, O);
+      else tile_pv<D>(reinterpret_cast<const float *>(Vu), P, j0, g, c, e, O);
     }
   }
   L += __shfl_xor(L, 16);
   L += __shfl_xor(L, 32);
   if (qi < P) {
-    if (g == 0) {
-      rowmax[u * (size_t)P + qi] = m_run;
-      rowsum[u * (size_t)P + qi] = L;
-    }
-    if (out != nullptr) {
-      const float inv = (float)(1.0 / L);
-      T *orow = out + (u * (size_t)P + qi) * D;
-#pragma unroll
-      for (int b = 0; b < DB; ++b)
-#pragma unroll
-        for (int w = 0; w < 4; ++w) orow[b * 16 + 4 * g + w] = Store<T>::from_float(O[b][w] * inv);
-    }
+    if (g == 0) lse[u * (size_t)P + qi] = m_run + log(L);
+    if (out != nullptr) store_out<D>(out + (u * (size_t)P + qi) * D, g, O, (float)(1.0 / L));
   }
 }
 
 // -------------------------------------------------------------------------------------
 // Column pass: one wave per block of 16 keys.  Sweeps the query tiles from the diagonal
-// down and sums a_ij = e^{s_ij - m_i} / L_i over the queries: the accumulated attention
+// down and sums a_ij = e^{s_ij - lse_i} over the queries: the accumulated attention
 // probability of each prompt token (H2O's score, Sec. 2.1).  No atomics: every column is
 // owned by one wave and reduced in a fixed order.
-// grid = U * ceil(P/16), block = 64.
 // -------------------------------------------------------------------------------------
 template <typename T, int D>
-__global__ __launch_bounds__(64) void prefill_colpass_kernel(
-    const T *__restrict__ Q, const T *__restrict__ K, int P, const double *__restrict__ rowmax,
-    const double *__restrict__ rowsum, double *__restrict__ colsum)
+__global__ __launch_bounds__(64 * kPrefillWaves) void prefill_colpass_kernel(
+    const T *__restrict__ Q, const T *__restrict__ K, unsigned U, int P,
+    const double *__restrict__ lse, double *__restrict__ colsum)
 {
   constexpr int CH = D / 4;
   const int nblk = (P + 15) / 16;
-  const int jt = blockIdx.x % nblk;              // early columns have the longest sweeps
-  const size_t u = blockIdx.x / nblk;
-  const int l = threadIdx.x, g = l / 16, c = l % 16;
+  const int ngrp = (nblk + kPrefillWaves - 1) / kPrefillWaves;
+  const PrefillBlock pb = prefill_block(blockIdx.x, ngrp);
+  const int grp = pb.grp;                                 // early columns have the longest sweeps
+  const size_t u = pb.u;
+  const int l = threadIdx.x % 64, g = l / 16, c = l % 16;
+  const int jt = grp * kPrefillWaves + (int)(threadIdx.x / 64);
+  if (jt >= nblk || pb.u >= U) return;                    // wave-uniform; the waves share nothing
   const int j0 = jt * 16;
   const T *Qu = Q + u * (size_t)P * D, *Ku = K + u * (size_t)P * D;
-  const double sqrt_d = sqrt((double)D);
+  const double *lse_u = lse + u * (size_t)P;
+  const double scale = 1.0 / sqrt((double)D);
 
   double kd[CH];
   {
@@ -179,19 +279,32 @@ __global__ __launch_bounds__(64) void prefill_colpass_kernel(
     for (int s = 0; s < CH; ++s) kd[s] = kraw.get(s);
   }
   double cs[4] = {0.0, 0.0, 0.0, 0.0};
+  Chunk<T, D> qraw;
+  double lq;
+  {
+    const int qr = j0 + c < P ? j0 + c : P - 1;
+    qraw.load(Qu + (size_t)qr * D, g);
+    lq = lse_u[qr];
+  }
   for (int it = jt; it < nblk; ++it) {
     const int qi = it * 16 + c;
-    const int qrow = qi < P ? qi : P - 1;
-    Chunk<T, D> qraw;
-    qraw.load(Qu + (size_t)qrow * D, g);
-    const double m = rowmax[u * (size_t)P + qrow];
-    const double Lr = rowsum[u * (size_t)P + qrow];
+    Chunk<T, D> qnext;
+    double lnext;
+    {
+      const int qn = (it + 1 < nblk ? qi + 16 : qi);
+      const int qr = qn < P ? qn : P - 1;
+      qnext.load(Qu + (size_t)qr * D, g);
+      lnext = lse_u[qr];
+    }
     const v4d acc = tile_kq<T, D>(kd, qraw);
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
       const int kj = j0 + g + 4 * v;
-      if (qi < P && kj <= qi) cs[v] += exp(acc[v] / sqrt_d - m) / Lr;
+      const double a = exp(fma(acc[v], scale, -lq));
+      cs[v] += (qi < P && kj <= qi) ? a : 0.0;
     }
+    qraw = qnext;
+    lq = lnext;
   }
 #pragma unroll
   for (int v = 0; v < 4; ++v) {
@@ -330,13 +443,14 @@ static hipError_t launch_prefill_t(const PrefillArgs &a, hipStream_t st)
   const lessdec_desc *d = a.d;
   const int P = a.P, C = d->n_heavy + d->n_recent;
   const unsigned U = (unsigned)d->batch * d->heads;
-  const unsigned grid = U * (unsigned)((P + 15) / 16);
-  prefill_rowpass_kernel<T, D><<<grid, 64, 0, st>>>((const T *)a.Q, (const T *)a.K, (const T *)a.V, P,
-                                                    a.rowmax, a.rowsum, (T *)a.out);
+  const unsigned grid = (U + kXcds - 1) / kXcds * kXcds *
+                        (unsigned)(((P + 15) / 16 + kPrefillWaves - 1) / kPrefillWaves);
+  prefill_rowpass_kernel<T, D><<<grid, 64 * kPrefillWaves, 0, st>>>((const T *)a.Q, (const T *)a.K,
+                                                                   (const T *)a.V, U, P, a.lse, (T *)a.out);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  prefill_colpass_kernel<T, D><<<grid, 64, 0, st>>>((const T *)a.Q, (const T *)a.K, P, a.rowmax,
-                                                    a.rowsum, a.colsum);
+  prefill_colpass_kernel<T, D><<<grid, 64 * kPrefillWaves, 0, st>>>((const T *)a.Q, (const T *)a.K, U, P,
+                                                                   a.lse, a.colsum);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   prefill_select_kernel<<<U, 256, 0, st>>>(a.colsum, P, d->n_heavy, d->n_recent,
                                            (d->flags & LESSDEC_FLAG_LAMBDA) ? 1 : 0, a.slot_of);
