@@ -319,117 +319,142 @@ __global__ __launch_bounds__(64 * kPrefillWaves) void prefill_colpass_kernel(
 // Selection: the last Nr tokens are recent; among the others the Nh largest (column sum,
 // position) pairs are heavy hitters; everything else is discarded.  Exact rank counting,
 // no sort: token j is heavy iff fewer than Nh candidates are larger.  Under Lambda-masking
-// (Sec. 4, "Setup") the first Nh tokens take the place of the heavy hitters.  Kept tokens
-// get slots in ascending position.  grid = U, block = 256.
+// (Sec. 4, "Setup") the first Nh tokens take the place of the heavy hitters.
+// One thread per token: keep[j] = 1 / 0.   grid = U * ceil(P / 256), block = 256.
 // -------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void prefill_select_kernel(const double *__restrict__ colsum, int P,
-                                                             int Nh, int Nr, int lambda,
-                                                             int32_t *__restrict__ slot_of)
+__global__ __launch_bounds__(256) void prefill_rank_kernel(const double *__restrict__ colsum, int P,
+                                                           int Nh, int Nr, int lambda,
+                                                           int32_t *__restrict__ keep_of)
 {
-  __shared__ int s_cnt[256];
-  const size_t u = blockIdx.x;
-  const int tid = threadIdx.x;
+  const int nb = (P + 255) / 256;
+  const size_t u = blockIdx.x / nb;
+  const int j = (int)(blockIdx.x % nb) * 256 + (int)threadIdx.x;
+  if (j >= P) return;
   const double *cs = colsum + u * (size_t)P;
-  int32_t *so = slot_of + u * (size_t)P;
   const int C = Nh + Nr;
   const int ncand = P - Nr;                     // positions < P - Nr compete for the heavy slots
-  // 1) kept flag (1 / 0) into slot_of
-  for (int j = tid; j < P; j += 256) {
-    int keep = 1;
-    if (P > C && lambda) {
-      keep = (j < Nh || j >= ncand) ? 1 : 0;
-    } else if (P > C && j < ncand) {
-      const double a = cs[j];
-      int larger = 0;
-      for (int i = 0; i < ncand; ++i) {
-        const double b = cs[i];
-        larger += (b > a || (b == a && i > j)) ? 1 : 0;
-      }
-      keep = larger < Nh ? 1 : 0;
+  int keep = 1;
+  if (P > C && lambda) {
+    keep = (j < Nh || j >= ncand) ? 1 : 0;
+  } else if (P > C && j < ncand) {
+    const double a = cs[j];
+    int larger = 0;
+    for (int i = 0; i < ncand; ++i) {
+      const double b = cs[i];
+      larger += (b > a || (b == a && i > j)) ? 1 : 0;
     }
-    so[j] = keep;
+    keep = larger < Nh ? 1 : 0;
   }
-  __syncthreads();
-  // 2) slot = number of kept tokens before j: per-thread contiguous chunk + scan of 256 counts
-  const int chunk = (P + 255) / 256;
-  const int lo = tid * chunk, hi = (lo + chunk < P) ? lo + chunk : P;
-  int cnt = 0;
-  for (int j = lo; j < hi; ++j) cnt += so[j];
-  s_cnt[tid] = cnt;
-  __syncthreads();
-  int base = 0;
-  for (int t = 0; t < tid; ++t) base += s_cnt[t];
-  for (int j = lo; j < hi; ++j) {
-    const int keep = so[j];
-    so[j] = keep ? base : -1;
-    base += keep;
-  }
+  keep_of[u * (size_t)P + j] = keep;
 }
 
 // -------------------------------------------------------------------------------------
-// Finalize: gather the kept pairs into their slots (acc = column sum, pos, psi), clear the
-// unused slots, and build H = sum psi(k)^T v, z = sum psi(k) over the discarded pairs
-// (Eq. 6).  grid = U, block = 256 (threads < D own a column of H; threads D..D+R-1 own an
-// entry of z).
+// Finalize, one workgroup per unit: kept tokens get slots in ascending position; their
+// rows are gathered into the cache (acc = column sum, pos, psi), unused slots cleared; the
+// discarded pairs build H = sum psi(k)^T v, z = sum psi(k) (Eq. 6) in fp64.
+// For the state, wave w owns D / 4 columns of H, two per lane, and its lanes split the
+// tokens between them (interleaved parts, combined by lane exchange at the end), R in
+// chunks of RC rows.  slot_of: in 1 / 0 (kept / discarded), out slot index / -1.
+// grid = U, block = 256, dynamic LDS = C ints.
 // -------------------------------------------------------------------------------------
-template <typename T, int D>
+template <typename T, int D, int RC>
 __global__ __launch_bounds__(256) void prefill_finalize_kernel(
     const T *__restrict__ K, const T *__restrict__ V, int P, const double *__restrict__ colsum,
-    const int32_t *__restrict__ slot_of, const float *__restrict__ psi_all, int C, int R,
+    int32_t *__restrict__ slot_of, const float *__restrict__ psi_all, int C, int R,
     T *__restrict__ k_cache, T *__restrict__ v_cache, double *__restrict__ acc,
     int32_t *__restrict__ pos, float *__restrict__ psi, float *__restrict__ H,
     double *__restrict__ z, int32_t *__restrict__ n_seen, int32_t *__restrict__ pend_slot)
 {
+  extern __shared__ int s_tok[];                           // [C] token held by each slot
+  __shared__ int s_cnt[256];
   const size_t u = blockIdx.x;
-  const int tid = threadIdx.x;
+  const int tid = threadIdx.x, wave = tid / 64, lane = tid % 64;
   const T *Ku = K + u * (size_t)P * D, *Vu = V + u * (size_t)P * D;
-  const int32_t *so = slot_of + u * (size_t)P;
+  int32_t *so = slot_of + u * (size_t)P;
   const float *pa = psi_all + u * (size_t)P * R;
   const int kept = P < C ? P : C;
 
-  // gather: one (token, column) element per thread iteration
-  for (size_t idx = tid; idx < (size_t)P * D; idx += 256) {
-    const int j = (int)(idx / D), c = (int)(idx % D);
-    const int s = so[j];
-    if (s >= 0) {
-      k_cache[(u * C + s) * D + c] = Ku[idx];
-      v_cache[(u * C + s) * D + c] = Vu[idx];
+  // 1) slot = number of kept tokens before j: per-thread contiguous chunk + the 256 counts
+  {
+    const int chunk = (P + 255) / 256;
+    const int lo = tid * chunk < P ? tid * chunk : P, hi = (lo + chunk < P) ? lo + chunk : P;
+    int cnt = 0;
+    for (int j = lo; j < hi; ++j) cnt += so[j];
+    s_cnt[tid] = cnt;
+    __syncthreads();
+    int base = 0;
+    for (int t = 0; t < tid; ++t) base += s_cnt[t];
+    for (int j = lo; j < hi; ++j) {
+      const int keep = so[j];
+      so[j] = keep ? base : -1;
+      if (keep && base < C) s_tok[base] = j;
+      base += keep;
     }
   }
-  for (int j = tid; j < P; j += 256) {
-    const int s = so[j];
-    if (s >= 0) {
-      acc[u * C + s] = colsum[u * (size_t)P + j];
-      pos[u * C + s] = j;
-      for (int r = 0; r < R; ++r) psi[(u * C + s) * R + r] = pa[(size_t)j * R + r];
+  __syncthreads();
+
+  // 2) gather: rows moved as 16-byte vectors, 64 / kVecs slots per wave at a time
+  constexpr int kVecs = D * (int)sizeof(T) / 16;           // per row: 8, 16 or 32
+  constexpr int kSlotsPerWave = 64 / kVecs;
+  for (int s = wave * kSlotsPerWave + lane / kVecs; s < C; s += 4 * kSlotsPerWave) {
+    const size_t slot = u * C + s;
+    const int i = lane % kVecs;
+    if (s < kept) {
+      const int j = s_tok[s];
+      reinterpret_cast<uint4 *>(k_cache + slot * D)[i] = reinterpret_cast<const uint4 *>(Ku + (size_t)j * D)[i];
+      reinterpret_cast<uint4 *>(v_cache + slot * D)[i] = reinterpret_cast<const uint4 *>(Vu + (size_t)j * D)[i];
+      if (i == 0) {
+        acc[slot] = colsum[u * (size_t)P + j];
+        pos[slot] = j;
+      }
+      for (int r = i; r < R; r += kVecs) psi[slot * R + r] = pa[(size_t)j * R + r];
+    } else {
+      if (i == 0) {
+        acc[slot] = 0.0;
+        pos[slot] = -1;
+      }
+      for (int r = i; r < R; r += kVecs) psi[slot * R + r] = 0.f;
     }
   }
-  for (int s = kept + tid; s < C; s += 256) {
-    acc[u * C + s] = 0.0;
-    pos[u * C + s] = -1;
-    for (int r = 0; r < R; ++r) psi[(u * C + s) * R + r] = 0.f;
-  }
-  // state of the discarded pairs
-  if (tid < D) {
-    double h[LESSDEC_MAX_RANK];
+
+  // 3) state of the discarded pairs.  Kept tokens go through the same arithmetic with a zero
+  // weight, so that nothing in the loop depends on a load and iterations overlap.
+  constexpr int LW = D / 8, PARTS = 64 / LW;               // lanes per token (2 columns each), parts
+  const int col = wave * (D / 4) + 2 * (lane % LW), part = lane / LW;
+  for (int r0 = 0; r0 < R; r0 += RC) {
+    const int rn = R - r0 < RC ? R - r0 : RC;
+    double h0[RC], h1[RC], zs[RC];
 #pragma unroll
-    for (int r = 0; r < LESSDEC_MAX_RANK; ++r) h[r] = 0.0;
-    for (int j = 0; j < P; ++j) {
-      if (so[j] >= 0) continue;
-      const double v = (double)Store<T>::to_float(Vu[(size_t)j * D + tid]);
+    for (int r = 0; r < RC; ++r) h0[r] = h1[r] = zs[r] = 0.0;
+#pragma unroll 4
+    for (int j = part; j < P; j += PARTS) {
+      const double w = so[j] < 0 ? 1.0 : 0.0;
+      const T *vp = Vu + (size_t)j * D + col;
+      const double v0 = w * (double)Store<T>::to_float(vp[0]);
+      const double v1 = w * (double)Store<T>::to_float(vp[1]);
+      const float *pj = pa + (size_t)j * R + r0;
 #pragma unroll
-      for (int r = 0; r < LESSDEC_MAX_RANK; ++r)
-        if (r < R) h[r] = fma((double)pa[(size_t)j * R + r], v, h[r]);
+      for (int r = 0; r < RC; ++r) {
+        const double g = (double)pj[r < rn ? r : 0];       // rows past R: repeated, never stored
+        h0[r] = fma(g, v0, h0[r]);
+        h1[r] = fma(g, v1, h1[r]);
+        zs[r] = fma(g, w, zs[r]);
+      }
     }
 #pragma unroll
-    for (int r = 0; r < LESSDEC_MAX_RANK; ++r)
-      if (r < R) H[(u * R + r) * D + tid] = (float)h[r];
-  } else if (tid < D + R) {
-    const int r = tid - D;
-    double a = 0.0;
-    for (int j = 0; j < P; ++j)
-      if (so[j] < 0) a += (double)pa[(size_t)j * R + r];
-    z[u * R + r] = a;
+    for (int r = 0; r < RC; ++r) {
+#pragma unroll
+      for (int o = LW; o < 64; o <<= 1) {
+        h0[r] += __shfl_xor(h0[r], o);
+        h1[r] += __shfl_xor(h1[r], o);
+        zs[r] += __shfl_xor(zs[r], o);
+      }
+      if (r < rn && part == 0) {
+        H[(u * R + r0 + r) * D + col] = (float)h0[r];
+        H[(u * R + r0 + r) * D + col + 1] = (float)h1[r];
+      }
+      if (r < rn && tid == 0) z[u * R + r0 + r] = zs[r];
+    }
   }
   if (tid == 0) {
     n_seen[u] = P;
@@ -452,8 +477,8 @@ static hipError_t launch_prefill_t(const PrefillArgs &a, hipStream_t st)
   prefill_colpass_kernel<T, D><<<grid, 64 * kPrefillWaves, 0, st>>>((const T *)a.Q, (const T *)a.K, U, P,
                                                                    a.lse, a.colsum);
   if ((e = hipGetLastError()) != hipSuccess) return e;
-  prefill_select_kernel<<<U, 256, 0, st>>>(a.colsum, P, d->n_heavy, d->n_recent,
-                                           (d->flags & LESSDEC_FLAG_LAMBDA) ? 1 : 0, a.slot_of);
+  prefill_rank_kernel<<<U * (unsigned)((P + 255) / 256), 256, 0, st>>>(
+      a.colsum, P, d->n_heavy, d->n_recent, (d->flags & LESSDEC_FLAG_LAMBDA) ? 1 : 0, a.slot_of);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   if (mlp_mfma_supported(d->dtype, d->head_dim, d->hidden, d->rank)) {
     MlpArgs fm;
@@ -467,7 +492,17 @@ static hipError_t launch_prefill_t(const PrefillArgs &a, hipStream_t st)
     fa.B = d->batch; fa.Hh = d->heads; fa.rpu = P; fa.D = d->head_dim; fa.Rp = d->hidden; fa.R = d->rank;
     if ((e = launch_featmap_generic(fa, d->dtype, st)) != hipSuccess) return e;
   }
-  prefill_finalize_kernel<T, D><<<U, 256, 0, st>>>(
+  const size_t lds = (size_t)C * sizeof(int);
+  if (d->rank <= 4)
+    prefill_finalize_kernel<T, D, 4><<<U, 256, lds, st>>>(
+      (const T *)a.K, (const T *)a.V, P, a.colsum, a.slot_of, a.psi_all, C, d->rank, (T *)d->k_cache,
+      (T *)d->v_cache, d->acc, d->pos, d->psi, d->H, d->z, d->n_seen, d->pend_slot);
+  else if (d->rank <= 8)
+    prefill_finalize_kernel<T, D, 8><<<U, 256, lds, st>>>(
+      (const T *)a.K, (const T *)a.V, P, a.colsum, a.slot_of, a.psi_all, C, d->rank, (T *)d->k_cache,
+      (T *)d->v_cache, d->acc, d->pos, d->psi, d->H, d->z, d->n_seen, d->pend_slot);
+  else
+    prefill_finalize_kernel<T, D, 16><<<U, 256, lds, st>>>(
       (const T *)a.K, (const T *)a.V, P, a.colsum, a.slot_of, a.psi_all, C, d->rank, (T *)d->k_cache,
       (T *)d->v_cache, d->acc, d->pos, d->psi, d->H, d->z, d->n_seen, d->pend_slot);
   return hipGetLastError();
