@@ -51,6 +51,30 @@ __device__ inline bool cand_less(const Cand &a, const Cand &b)
 }
 __device__ inline Cand cand_none() { return Cand{__builtin_inf(), INT_MAX, -1}; }
 
+// e^x in fp64 for the softmax weights of the prompt phase, where x = s - max <= 0 up to
+// rounding: x = n ln 2 + r with |r| <= ln 2 / 2, Taylor polynomial of degree 10 in r
+// (truncation 2e-13 relative), scaled by 2^n; 0 below the underflow threshold and for -inf.
+// Half the instructions of the library routine; its error is far inside the 1e-6 margin by
+// which accumulated probabilities may differ before an eviction is called a tie.
+__device__ inline double exp_softmax_f64(double x)
+{
+  const double n = __builtin_rint(x * 1.44269504088896338700e+00);
+  double r = fma(n, -6.93147180369123816490e-01, x);
+  r = fma(n, -1.90821492927058770002e-10, r);
+  double p = 2.75573192239858906526e-07;                   // 1 / 10!
+  p = fma(p, r, 2.75573192239858906526e-06);
+  p = fma(p, r, 2.48015873015873015873e-05);
+  p = fma(p, r, 1.98412698412698412698e-04);
+  p = fma(p, r, 1.38888888888888888889e-03);
+  p = fma(p, r, 8.33333333333333333333e-03);
+  p = fma(p, r, 4.16666666666666666667e-02);
+  p = fma(p, r, 1.66666666666666666667e-01);
+  p = fma(p, r, 0.5);
+  p = fma(p, r, 1.0);
+  p = fma(p, r, 1.0);
+  return x > -708.0 ? __builtin_ldexp(p, (int)n) : 0.0;
+}
+
 // GELU, x * Phi(x) (Sec. 3.2 names GELU as the activation of both feature maps).
 __device__ inline double gelu_f64(double x) { return 0.5 * x * erfc(-x * 0.70710678118654752440); }
 

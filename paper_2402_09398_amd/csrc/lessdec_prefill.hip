@@ -228,7 +228,7 @@ __global__ __launch_bounds__(64 * kPrefillWaves) void prefill_rowpass_kernel(
     double e[4], esum = 0.0;
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
-      e[v] = exp(s[v] - m_run);
+      e[v] = exp_softmax_f64(s[v] - m_run);
       esum += e[v];
     }
     L += esum;
@@ -300,7 +300,7 @@ __global__ __launch_bounds__(64 * kPrefillWaves) void prefill_colpass_kernel(
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
       const int kj = j0 + g + 4 * v;
-      const double a = exp(fma(acc[v], scale, -lq));
+      const double a = exp_softmax_f64(fma(acc[v], scale, -lq));
       cs[v] += (qi < P && kj <= qi) ? a : 0.0;
     }
     qraw = qnext;
@@ -357,6 +357,19 @@ __global__ __launch_bounds__(256) void prefill_rank_kernel(const double *__restr
 // chunks of RC rows.  slot_of: in 1 / 0 (kept / discarded), out slot index / -1.
 // grid = U, block = 256, dynamic LDS = C ints.
 // -------------------------------------------------------------------------------------
+__device__ inline void load_pair(const __half *p, float &a, float &b)
+{
+  const __half2 h = *reinterpret_cast<const __half2 *>(p);
+  a = __low2float(h);
+  b = __high2float(h);
+}
+__device__ inline void load_pair(const float *p, float &a, float &b)
+{
+  const float2 f = *reinterpret_cast<const float2 *>(p);
+  a = f.x;
+  b = f.y;
+}
+
 template <typename T, int D, int RC>
 __global__ __launch_bounds__(256) void prefill_finalize_kernel(
     const T *__restrict__ K, const T *__restrict__ V, int P, const double *__restrict__ colsum,
@@ -421,24 +434,45 @@ __global__ __launch_bounds__(256) void prefill_finalize_kernel(
   // weight, so that nothing in the loop depends on a load and iterations overlap.
   constexpr int LW = D / 8, PARTS = 64 / LW;               // lanes per token (2 columns each), parts
   const int col = wave * (D / 4) + 2 * (lane % LW), part = lane / LW;
+  const bool vec4 = R % 4 == 0;                            // psi rows readable as 16-byte vectors
+  constexpr int kUnroll = RC >= 16 ? 2 : 4;                // tokens in flight per lane (register budget)
   for (int r0 = 0; r0 < R; r0 += RC) {
     const int rn = R - r0 < RC ? R - r0 : RC;
     double h0[RC], h1[RC], zs[RC];
 #pragma unroll
     for (int r = 0; r < RC; ++r) h0[r] = h1[r] = zs[r] = 0.0;
-#pragma unroll 4
-    for (int j = part; j < P; j += PARTS) {
+    auto token = [&](int j, const float (&gj)[RC]) {
       const double w = so[j] < 0 ? 1.0 : 0.0;
-      const T *vp = Vu + (size_t)j * D + col;
-      const double v0 = w * (double)Store<T>::to_float(vp[0]);
-      const double v1 = w * (double)Store<T>::to_float(vp[1]);
-      const float *pj = pa + (size_t)j * R + r0;
+      float vf0, vf1;
+      load_pair(Vu + (size_t)j * D + col, vf0, vf1);
+      const double v0 = w * (double)vf0, v1 = w * (double)vf1;
 #pragma unroll
       for (int r = 0; r < RC; ++r) {
-        const double g = (double)pj[r < rn ? r : 0];       // rows past R: repeated, never stored
+        const double g = (double)gj[r];
         h0[r] = fma(g, v0, h0[r]);
         h1[r] = fma(g, v1, h1[r]);
         zs[r] = fma(g, w, zs[r]);
+      }
+    };
+    // rows past R repeat row 0 (unconditional loads); their sums are never stored
+    if (vec4) {
+#pragma unroll kUnroll
+      for (int j = part; j < P; j += PARTS) {
+        const float *pj = pa + (size_t)j * R + r0;
+        float gj[RC];
+#pragma unroll
+        for (int r4 = 0; r4 < RC / 4; ++r4)
+          *reinterpret_cast<float4 *>(gj + 4 * r4) = *reinterpret_cast<const float4 *>(pj + (4 * r4 < rn ? 4 * r4 : 0));
+        token(j, gj);
+      }
+    } else {
+#pragma unroll kUnroll
+      for (int j = part; j < P; j += PARTS) {
+        const float *pj = pa + (size_t)j * R + r0;
+        float gj[RC];
+#pragma unroll
+        for (int r = 0; r < RC; ++r) gj[r] = pj[r < rn ? r : 0];
+        token(j, gj);
       }
     }
 #pragma unroll
