@@ -4,7 +4,7 @@
 
 namespace lessdec {
 
-constexpr int kWpuUnits = 8;        // units (waves) per block
+constexpr int kWpuUnits = 8;        // units (waves) per block, at most
 constexpr int kWpuMaxRows = 512;    // C + 1 at most
 
 // =====================================================================================
@@ -59,12 +59,13 @@ __global__ __launch_bounds__(kWpuUnits * kWave) void wpu_step_kernel(void *k_cac
   const int lane = threadIdx.x & 63;
   const int lr = lane % LPR, rb = lane / LPR;
   const int h = (int)blockIdx.x % Hh, chunk = (int)blockIdx.x / Hh;
-  const int bb = chunk * kWpuUnits + wave;
+  const int upb = (int)blockDim.x >> 6;                      // units (waves) in this block
+  const int bb = chunk * upb + wave;
   if (bb >= B_) return;                                      // wave-uniform; the waves share nothing
   const int u = bb * Hh + h;
   const int rows_cap = (C + 2) & ~1;
   double *s_sc = dyn + (size_t)wave * rows_cap;                                    // [C+1] scores
-  float *s_p = reinterpret_cast<float *>(dyn + (size_t)kWpuUnits * rows_cap) + (size_t)wave * rows_cap;
+  float *s_p = reinterpret_cast<float *>(dyn + (size_t)upb * rows_cap) + (size_t)wave * rows_cap;
 
   T *kc = reinterpret_cast<T *>(k_cache_) + (size_t)u * C * D;
   T *vc = reinterpret_cast<T *>(a.v_cache) + (size_t)u * C * D;
@@ -319,6 +320,7 @@ __global__ __launch_bounds__(kWpuUnits * kWave) void wpu_step_kernel(void *k_cac
   float o[EPL];
 #pragma unroll
   for (int i = 0; i < EPL; ++i) o[i] = 0.f;
+  float fh[4] = {0.f, 0.f, 0.f, 0.f};                        // phi(q) H, this lane's columns and rows
   {
     int base = 0;
     do {                                                     // nit >= 1
@@ -341,35 +343,36 @@ __global__ __launch_bounds__(kWpuUnits * kWave) void wpu_step_kernel(void *k_cac
         buf[j] = issue(nitp + s + DEPTH);
         __builtin_amdgcn_sched_barrier(0);
       }
+      if (base == 0) {
+        // H and the pending value row were requested before the loads this pass re-issued, so
+        // they are back: fold the pending pair into H (Eq. 4) and send H on its way while the
+        // value rows still stream, then phi(q) H for this lane's columns and rows.
+        const float f32 = (float)f_lane;
+        const __half2 *pvh = reinterpret_cast<const __half2 *>(&pend_v_h);
+        const float2 pv01 = __half22float2(pvh[0]), pv23 = __half22float2(pvh[1]);
+        float *Hu = a.H + (size_t)u * R * D;
+#pragma unroll
+        for (int i = 0; i < HR; ++i) {
+          const int r = NHB * i + hb;                        // differs between the halves of the wave
+          const int rc = r < R ? r : R - 1;
+          const float fr = r < R ? __shfl(f32, rc) : 0.f;
+          const float pe = __shfl(psie_lane, rc);
+          if (pend.fold) {
+            hreg[i].x = fmaf(pe, pv01.x, hreg[i].x);
+            hreg[i].y = fmaf(pe, pv01.y, hreg[i].y);
+            hreg[i].z = fmaf(pe, pv23.x, hreg[i].z);
+            hreg[i].w = fmaf(pe, pv23.y, hreg[i].w);
+            if (r < R) store_nt(Hu + (size_t)r * D + col0, hreg[i]);
+          }
+          fh[0] = fmaf(fr, hreg[i].x, fh[0]);
+          fh[1] = fmaf(fr, hreg[i].y, fh[1]);
+          fh[2] = fmaf(fr, hreg[i].z, fh[2]);
+          fh[3] = fmaf(fr, hreg[i].w, fh[3]);
+        }
+      }
     } while ((base += DEPTH) < nit);
   }
   {
-    // fold of the pending pair into H (Eq. 4), then phi(q) H for this lane's columns and rows
-    float fh[4] = {0.f, 0.f, 0.f, 0.f};
-    {
-      const float f32 = (float)f_lane;
-      const __half2 *pvh = reinterpret_cast<const __half2 *>(&pend_v_h);
-      const float2 pv01 = __half22float2(pvh[0]), pv23 = __half22float2(pvh[1]);
-      float *Hu = a.H + (size_t)u * R * D;
-#pragma unroll
-      for (int i = 0; i < HR; ++i) {
-        const int r = NHB * i + hb;                          // differs between the halves of the wave
-        const int rc = r < R ? r : R - 1;
-        const float fr = r < R ? __shfl(f32, rc) : 0.f;
-        const float pe = __shfl(psie_lane, rc);
-        if (pend.fold) {
-          hreg[i].x = fmaf(pe, pv01.x, hreg[i].x);
-          hreg[i].y = fmaf(pe, pv01.y, hreg[i].y);
-          hreg[i].z = fmaf(pe, pv23.x, hreg[i].z);
-          hreg[i].w = fmaf(pe, pv23.y, hreg[i].w);
-          if (r < R) store_nt(Hu + (size_t)r * D + col0, hreg[i]);
-        }
-        fh[0] = fmaf(fr, hreg[i].x, fh[0]);
-        fh[1] = fmaf(fr, hreg[i].y, fh[1]);
-        fh[2] = fmaf(fr, hreg[i].z, fh[2]);
-        fh[3] = fmaf(fr, hreg[i].w, fh[3]);
-      }
-    }
     // The RPI row groups hold partial sums of the same 8 columns.  First stage (partner at
     // distance LPR): reduce-scatter, a lane keeps the four columns selected by its bit LPR;
     // remaining stages: all-reduce, together with the partial phi(q) H of the row subsets.
@@ -416,12 +419,17 @@ static hipError_t launch_step_wpu_t(const StepArgs &a, hipStream_t st)
 {
   constexpr int kDepth = 7;
   const int rows_cap = (a.C + 2) & ~1;
-  const size_t lds = (size_t)kWpuUnits * rows_cap * (sizeof(double) + sizeof(float));
-  const unsigned grid = (unsigned)(a.Hh * ((a.B + kWpuUnits - 1) / kWpuUnits));
+  // Units per block: 8 when that still gives every compute unit a block, fewer for small
+  // batches, so that the units spread over the chip instead of sharing a few compute units.
+  int upb = kWpuUnits;
+  while (upb > 1 && a.Hh * ((a.B + upb - 1) / upb) < 256) upb >>= 1;
+  const size_t lds = (size_t)upb * rows_cap * (sizeof(double) + sizeof(float));
+  const unsigned grid = (unsigned)(a.Hh * ((a.B + upb - 1) / upb));
+  const unsigned block = (unsigned)(upb * kWave);
   const int rows = a.C + 1;
-  if (rows <= 2 * kWave) wpu_step_kernel<D, 2, RM, kDepth><<<grid, kWpuUnits * kWave, lds, st>>>(a.k_cache, a.q, a.k, a.C, a.Hh, a.B, a);
-  else if (rows <= 4 * kWave) wpu_step_kernel<D, 4, RM, kDepth><<<grid, kWpuUnits * kWave, lds, st>>>(a.k_cache, a.q, a.k, a.C, a.Hh, a.B, a);
-  else wpu_step_kernel<D, kWpuMaxRows / kWave, RM, kDepth><<<grid, kWpuUnits * kWave, lds, st>>>(a.k_cache, a.q, a.k, a.C, a.Hh, a.B, a);
+  if (rows <= 2 * kWave) wpu_step_kernel<D, 2, RM, kDepth><<<grid, block, lds, st>>>(a.k_cache, a.q, a.k, a.C, a.Hh, a.B, a);
+  else if (rows <= 4 * kWave) wpu_step_kernel<D, 4, RM, kDepth><<<grid, block, lds, st>>>(a.k_cache, a.q, a.k, a.C, a.Hh, a.B, a);
+  else wpu_step_kernel<D, kWpuMaxRows / kWave, RM, kDepth><<<grid, block, lds, st>>>(a.k_cache, a.q, a.k, a.C, a.Hh, a.B, a);
   return hipGetLastError();
 }
 
