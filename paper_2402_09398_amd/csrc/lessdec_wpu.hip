@@ -6,12 +6,17 @@ namespace lessdec {
 
 constexpr int kWpuUnits = 8;        // units (waves) per block, at most
 constexpr int kWpuMaxRows = 512;    // C + 1 at most
+constexpr int kWpuSplitWaves = 3072; // a unit's rows are split over more waves while the launch stays below this many
 
 // =====================================================================================
 // A block is 8 waves = 8 units that share a head: batch rows 8 * chunk .. 8 * chunk + 7 of
 // head h (head fastest in blockIdx, so with Hh a multiple of 8 the units of a head run on
 // the XCD whose L2 holds the feature-map sums written for them).  The waves of a block share
-// nothing and never meet at a barrier; each is on its own from the first instruction:
+// nothing and never meet at a barrier; each is on its own from the first instruction.
+// (SPLIT, for launches with few units: the block is one unit and its waves take every nw-th
+// load of each stream.  They meet twice: when the scores are complete, after which each wave
+// works out phase 2 for itself and only the lead wave stores; and when the partial outputs
+// are complete, which the lead wave adds in wave order and finishes.)
 //
 // A cache row is LPR = D / 8 lanes of 16 bytes, one load instruction covers RPI = 64 / LPR
 // rows.  The rows of K and then of V pass through a ring of DEPTH registers per lane: each
@@ -38,7 +43,7 @@ constexpr int kWpuMaxRows = 512;    // C + 1 at most
 //          new pair goes into the freed slot (Sec. 3.2); the discarded pair is left pending
 //          for the next step.
 // =====================================================================================
-template <int D, int NR2, int RM, int DEPTH>
+template <int D, int NR2, int RM, int DEPTH, bool SPLIT>
 __global__ __launch_bounds__(kWpuUnits * kWave) void wpu_step_kernel(void *k_cache_, const void *q_, const void *k_,
                                                                     int C_, int Hh_, int B_, const StepArgs a)
 {
@@ -59,13 +64,18 @@ __global__ __launch_bounds__(kWpuUnits * kWave) void wpu_step_kernel(void *k_cac
   const int lane = threadIdx.x & 63;
   const int lr = lane % LPR, rb = lane / LPR;
   const int h = (int)blockIdx.x % Hh, chunk = (int)blockIdx.x / Hh;
-  const int upb = (int)blockDim.x >> 6;                      // units (waves) in this block
-  const int bb = chunk * upb + wave;
-  if (bb >= B_) return;                                      // wave-uniform; the waves share nothing
+  const int upb = (int)blockDim.x >> 6;                      // waves in this block
+  // SPLIT: the waves of the block share one unit, wave w taking every nw-th load of each
+  // stream; otherwise a wave is a unit.
+  const int nw = SPLIT ? upb : 1, wv = SPLIT ? wave : 0;
+  const bool lead = !SPLIT || wave == 0;                     // the wave that writes the unit's state
+  const int bb = SPLIT ? chunk : chunk * upb + wave;
+  if (bb >= B_) return;                                      // uniform over the unit's waves
   const int u = bb * Hh + h;
   const int rows_cap = (C + 2) & ~1;
-  double *s_sc = dyn + (size_t)wave * rows_cap;                                    // [C+1] scores
-  float *s_p = reinterpret_cast<float *>(dyn + (size_t)upb * rows_cap) + (size_t)wave * rows_cap;
+  double *s_sc = dyn + (SPLIT ? 0 : (size_t)wave * rows_cap);                      // [C+1] scores
+  float *s_p = reinterpret_cast<float *>(dyn + (SPLIT ? 1 : (size_t)upb) * rows_cap) + (size_t)wave * rows_cap;
+  float *s_o = reinterpret_cast<float *>(dyn + rows_cap) + (size_t)upb * rows_cap;  // SPLIT: [nw][D] partial outputs
 
   T *kc = reinterpret_cast<T *>(k_cache_) + (size_t)u * C * D;
   T *vc = reinterpret_cast<T *>(a.v_cache) + (size_t)u * C * D;
@@ -87,7 +97,7 @@ __global__ __launch_bounds__(kWpuUnits * kWave) void wpu_step_kernel(void *k_cac
         __builtin_amdgcn_make_buffer_rsrc(kc, 0, C * D * (int)sizeof(T), 0x00020000);
 #pragma unroll
     for (int j = 0; j < DEPTH; ++j)
-      buf[j] = __builtin_amdgcn_raw_buffer_load_b128(rk, lane * 16, j * (kWave * 16), 2 /* nt */);
+      buf[j] = __builtin_amdgcn_raw_buffer_load_b128(rk, lane * 16, (j * nw + wv) * (kWave * 16), 2 /* nt */);
   }
   __builtin_amdgcn_sched_barrier(0);
   // 2. layer-2 sums of the two feature maps by parts (lane r + 16 i reads what lane r reads),
@@ -126,13 +136,14 @@ __global__ __launch_bounds__(kWpuUnits * kWave) void wpu_step_kernel(void *k_cac
   __builtin_amdgcn_sched_barrier(0);
 
   // The stream: position s < nitp is load s of K, position nitp + t is load t of V.
-  const int nit = (rows + RPI - 1) / RPI;                    // load instructions per stream
+  const int nl = (rows + RPI - 1) / RPI;                     // load instructions per stream
+  const int nit = SPLIT ? (nl > wv ? (nl - wv + nw - 1) / nw : 1) : nl;   // this wave's share (>= 1)
   const int nitp = (nit + DEPTH - 1) / DEPTH * DEPTH;        // K part of the stream, padded
   const int live_bytes = m * D * (int)sizeof(T);
   auto issue = [&](int s) -> u4v {                           // s is wave-uniform
     const bool isk = s < nitp;
     const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(isk ? kc : vc, 0, live_bytes, 0x00020000);
-    return __builtin_amdgcn_raw_buffer_load_b128(rs, lane * 16, (isk ? s : s - nitp) * (kWave * 16), 2 /* nt */);
+    return __builtin_amdgcn_raw_buffer_load_b128(rs, lane * 16, ((isk ? s : s - nitp) * nw + wv) * (kWave * 16), 2 /* nt */);
   };
 
   // ---- phase 1: scores as the key rows arrive; the feature maps after the first pass ------------
@@ -146,7 +157,7 @@ __global__ __launch_bounds__(kWpuUnits * kWave) void wpu_step_kernel(void *k_cac
       for (int j = 0; j < DEPTH; ++j) {
         const int s = base + j;
         if (s < nit) {
-          const int r = s * RPI + rb;
+          const int r = (s * nw + wv) * RPI + rb;
           Vec kv;
           __builtin_memcpy(&kv.raw, &buf[j], 16);
           if (r == m) kv = knv;                           // the appended key
@@ -201,9 +212,22 @@ __global__ __launch_bounds__(kWpuUnits * kWave) void wpu_step_kernel(void *k_cac
     hreg[i] = *reinterpret_cast<const float4 *>(a.H + ((size_t)u * R + (r < R ? r : R - 1)) * D + col0);
   }
   const uint2 pend_v_h = *reinterpret_cast<const uint2 *>(reinterpret_cast<const T *>(a.pend_v) + (size_t)u * D + col0);
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-  __builtin_amdgcn_wave_barrier();
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  if constexpr (SPLIT) {
+    // Every wave works out phase 2 for itself from the shared scores; only the lead wave
+    // stores.  Its stores must not overtake another wave's loads of the same state: have
+    // those loads back before the waves meet (the value rows requested after them stay in
+    // flight), then meet with the scores visible.
+#pragma unroll
+    for (int i = 0; i < NR2; ++i) asm volatile("" ::"v"(acc_pre[i]), "v"(pos_pre[i]));
+    asm volatile("" ::"v"(z_lane), "v"(ppsi_lane), "v"(psie_lane));
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+  } else {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  }
 
   int eslot = -1, ins_slot = -1;
   double lscale = 0.0;
@@ -234,10 +258,12 @@ __global__ __launch_bounds__(kWpuUnits * kWave) void wpu_step_kernel(void *k_cac
       if (lane < R) {
         if (pend.fold) {
           z_lane += (double)psie_lane;
-          a.z[(size_t)u * R + lane] = z_lane;
+          if (lead) a.z[(size_t)u * R + lane] = z_lane;
         }
-        if (pend.slot >= 0 && pend.slot < C) a.psi[((size_t)u * C + pend.slot) * R + lane] = ppsi_lane;
-        a.pend_psi[(size_t)u * R + lane] = npsi_lane;
+        if (lead) {
+          if (pend.slot >= 0 && pend.slot < C) a.psi[((size_t)u * C + pend.slot) * R + lane] = ppsi_lane;
+          a.pend_psi[(size_t)u * R + lane] = npsi_lane;
+        }
       }
       const double fz = wave_allreduce(f_lane * z_lane, OpAdd{});
       // den = phi(q) z^T + sum_j e^{s_j}, in whichever scaling cannot overflow:
@@ -297,14 +323,15 @@ __global__ __launch_bounds__(kWpuUnits * kWave) void wpu_step_kernel(void *k_cac
 #pragma unroll
       for (int i = 0; i < NR2; ++i) {
         const int j = lane + i * kWave;
-        if (j < m) {
+        if (!lead) {
+        } else if (j < m) {
           if (j != ins_slot) __builtin_nontemporal_store(sc[i], a.acc + (size_t)u * C + j);
         } else if (j == m && ins_slot >= 0) {
           a.acc[(size_t)u * C + ins_slot] = sc[i];
           a.pos[(size_t)u * C + ins_slot] = n;
         }
       }
-      if (lane == 0) {
+      if (lane == 0 && lead) {
         // what the next step has to finish: fold of the discarded pair and / or the slot write
         a.pend_slot[u] = evict ? (eslot < m ? eslot : C) : (m | kPendNoFold);
         if (a.evicted_pos) a.evicted_pos[u] = evict ? epos : -1;
@@ -321,6 +348,8 @@ __global__ __launch_bounds__(kWpuUnits * kWave) void wpu_step_kernel(void *k_cac
 #pragma unroll
   for (int i = 0; i < EPL; ++i) o[i] = 0.f;
   float fh[4] = {0.f, 0.f, 0.f, 0.f};                        // phi(q) H, this lane's columns and rows
+  uint4 pv_keep = {0u, 0u, 0u, 0u};
+  bool pv_have = false;
   {
     int base = 0;
     do {                                                     // nit >= 1
@@ -328,7 +357,7 @@ __global__ __launch_bounds__(kWpuUnits * kWave) void wpu_step_kernel(void *k_cac
       for (int j = 0; j < DEPTH; ++j) {
         const int s = base + j;
         if (s < nit) {
-          const int r = s * RPI + rb;
+          const int r = (s * nw + wv) * RPI + rb;
           Vec vv;
           __builtin_memcpy(&vv.raw, &buf[j], 16);
           if (r == m) vv = vnv;                              // the appended pair's value row
@@ -337,8 +366,14 @@ __global__ __launch_bounds__(kWpuUnits * kWave) void wpu_step_kernel(void *k_cac
 #pragma unroll
             for (int i = 0; i < EPL; ++i) o[i] = fmaf(p, Store<T>::get(vv, i), o[i]);
           }
-          if (r == eslot)                                    // the discarded pair's value row
-            *reinterpret_cast<uint4 *>(reinterpret_cast<T *>(a.pend_v) + (size_t)u * D + lr * EPL) = vv.raw;
+          if (r == eslot) {                                  // the discarded pair's value row
+            if constexpr (SPLIT) {
+              pv_keep = vv.raw;                              // stored once the lead wave has read the old one
+              pv_have = true;
+            } else {
+              *reinterpret_cast<uint4 *>(reinterpret_cast<T *>(a.pend_v) + (size_t)u * D + lr * EPL) = vv.raw;
+            }
+          }
         }
         buf[j] = issue(nitp + s + DEPTH);
         __builtin_amdgcn_sched_barrier(0);
@@ -362,7 +397,7 @@ __global__ __launch_bounds__(kWpuUnits * kWave) void wpu_step_kernel(void *k_cac
             hreg[i].y = fmaf(pe, pv01.y, hreg[i].y);
             hreg[i].z = fmaf(pe, pv23.x, hreg[i].z);
             hreg[i].w = fmaf(pe, pv23.y, hreg[i].w);
-            if (r < R) store_nt(Hu + (size_t)r * D + col0, hreg[i]);
+            if (r < R && lead) store_nt(Hu + (size_t)r * D + col0, hreg[i]);
           }
           fh[0] = fmaf(fr, hreg[i].x, fh[0]);
           fh[1] = fmaf(fr, hreg[i].y, fh[1]);
@@ -393,6 +428,22 @@ __global__ __launch_bounds__(kWpuUnits * kWave) void wpu_step_kernel(void *k_cac
       }
     }
 
+    if constexpr (SPLIT) {
+      // the waves' partial p . V meet in the LDS and the lead wave adds them in wave order
+      if (hb == 0) *reinterpret_cast<float4 *>(s_o + (size_t)wave * D + col0) = float4{o[0], o[1], o[2], o[3]};
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+      __builtin_amdgcn_s_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+      if (pv_have) *reinterpret_cast<uint4 *>(reinterpret_cast<T *>(a.pend_v) + (size_t)u * D + lr * EPL) = pv_keep;
+      if (!lead) return;
+      const float4 first = *reinterpret_cast<const float4 *>(s_o + col0);
+      o[0] = first.x; o[1] = first.y; o[2] = first.z; o[3] = first.w;
+      for (int w = 1; w < nw; ++w) {
+        const float4 part = *reinterpret_cast<const float4 *>(s_o + (size_t)w * D + col0);
+        o[0] += part.x; o[1] += part.y; o[2] += part.z; o[3] += part.w;
+      }
+    }
+
     // ---- phase 4: output, in-place insert ---------------------------------------------------------
     if (hb == 0) {
       __half2 res[2];
@@ -414,23 +465,43 @@ bool wpu_supported(int dtype, int D, int C, int Rp, int R)
          C + 1 <= kWpuMaxRows;
 }
 
-template <int D, int RM>
-static hipError_t launch_step_wpu_t(const StepArgs &a, hipStream_t st)
+template <int D, int RM, bool SPLIT>
+static hipError_t launch_step_wpu_s(const StepArgs &a, int upb, hipStream_t st)
 {
   constexpr int kDepth = 7;
   const int rows_cap = (a.C + 2) & ~1;
-  // Units per block: 8 when that still gives every compute unit a block, fewer for small
-  // batches, so that the units spread over the chip instead of sharing a few compute units.
-  int upb = kWpuUnits;
-  while (upb > 1 && a.Hh * ((a.B + upb - 1) / upb) < 256) upb >>= 1;
-  const size_t lds = (size_t)upb * rows_cap * (sizeof(double) + sizeof(float));
-  const unsigned grid = (unsigned)(a.Hh * ((a.B + upb - 1) / upb));
+  size_t lds = (size_t)(SPLIT ? 1 : upb) * rows_cap * sizeof(double) + (size_t)upb * rows_cap * sizeof(float);
+  if (SPLIT) lds += (size_t)upb * D * sizeof(float);
+  const unsigned grid = (unsigned)(a.Hh * (SPLIT ? a.B : (a.B + upb - 1) / upb));
   const unsigned block = (unsigned)(upb * kWave);
   const int rows = a.C + 1;
-  if (rows <= 2 * kWave) wpu_step_kernel<D, 2, RM, kDepth><<<grid, block, lds, st>>>(a.k_cache, a.q, a.k, a.C, a.Hh, a.B, a);
-  else if (rows <= 4 * kWave) wpu_step_kernel<D, 4, RM, kDepth><<<grid, block, lds, st>>>(a.k_cache, a.q, a.k, a.C, a.Hh, a.B, a);
-  else wpu_step_kernel<D, kWpuMaxRows / kWave, RM, kDepth><<<grid, block, lds, st>>>(a.k_cache, a.q, a.k, a.C, a.Hh, a.B, a);
+  if (rows <= 2 * kWave)
+    wpu_step_kernel<D, 2, RM, kDepth, SPLIT><<<grid, block, lds, st>>>(a.k_cache, a.q, a.k, a.C, a.Hh, a.B, a);
+  else if (rows <= 4 * kWave)
+    wpu_step_kernel<D, 4, RM, kDepth, SPLIT><<<grid, block, lds, st>>>(a.k_cache, a.q, a.k, a.C, a.Hh, a.B, a);
+  else
+    wpu_step_kernel<D, kWpuMaxRows / kWave, RM, kDepth, SPLIT><<<grid, block, lds, st>>>(a.k_cache, a.q, a.k, a.C, a.Hh,
+                                                                                      a.B, a);
   return hipGetLastError();
+}
+
+// Launch shape.  With thousands of units a wave per unit saturates the memory system; with
+// few, a step is bounded by how fast one wave can work through its rows, so the rows of a
+// unit are split over 2, 4 or 8 waves, while each keeps at least four loads per stream and
+// the launch stays below kWpuSplitWaves waves (measured: 1280 units gain from two waves
+// each, 2048 units lose).  Without a split, 8 units share a block when that still gives
+// every compute unit a block, fewer for small batches.
+template <int D, int RM>
+static hipError_t launch_step_wpu_t(const StepArgs &a, hipStream_t st)
+{
+  const long units = (long)a.B * a.Hh;
+  const int nl = (a.C + 1 + (kWave / (D / 8)) - 1) / (kWave / (D / 8));   // loads per stream
+  int nw = 1;
+  while (nw < kWpuUnits && units * nw * 2 <= kWpuSplitWaves && nl >= 8 * nw) nw *= 2;
+  if (nw > 1) return launch_step_wpu_s<D, RM, true>(a, nw, st);
+  int upb = kWpuUnits;
+  while (upb > 1 && a.Hh * ((a.B + upb - 1) / upb) < 256) upb >>= 1;
+  return launch_step_wpu_s<D, RM, false>(a, upb, st);
 }
 
 hipError_t launch_step_wpu(const StepArgs &a, int D, hipStream_t st)

@@ -78,6 +78,11 @@ EDGE = [
     small("d64-f16", head_dim=64),
     small("d128-f32", dtype="f32"),
     small("wide-cache", n_heavy=150, n_recent=150, prompt=400, steps=24, batch=1, heads=2),
+    # few units: the rows of a unit are split over 2, 4, 8 waves (32, 64, 128+ rows)
+    small("split-2-waves", n_heavy=20, n_recent=20, prompt=100, steps=30),
+    small("split-4-waves", n_heavy=35, n_recent=35, prompt=100, steps=30, head_dim=64, rank=16),
+    small("split-8-waves-filling", n_heavy=70, n_recent=70, prompt=0, steps=150, batch=1, heads=2),
+    small("split-8-waves-no-recent", n_heavy=130, n_recent=0, prompt=200, steps=20, batch=1, heads=2),
     wl.WORKLOADS[4].scaled(name="heavy-tailed-keys", batch=1, heads=4, prompt=256, steps=64,
                            n_heavy=10, n_recent=10, hidden=128),
 ]
