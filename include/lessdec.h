@@ -121,6 +121,7 @@ int lessdec_state_sync(const lessdec_desc *desc, void *hip_stream);
  * the largest column sums of the causal attention matrix (their H2O scores; ties keep the
  * later token), in ascending token order, with acc = column sum; every other prompt pair
  * is folded into H, z (Eq. 6); n_seen = P.  If P <= C every token is kept.
+ * With LESSDEC_FLAG_LAMBDA the first n_heavy tokens are kept in place of the heavy hitters.
  * Overwrites any previous state of the descriptor (no reset needed before it).
  * P >= 1.  Needs the workspace sized for max_prompt >= P.
  */
@@ -141,7 +142,8 @@ int lessdec_prefill(const lessdec_desc *desc, const void *Q, const void *K, cons
  * counts as recent; ties discard the older), writes the new pair into its slot and leaves
  * the discarded pair pending (see pend_slot); advances n_seen.  The fold of a pending pair
  * from the previous step into H, z happens first, so Eq. 3 always sees the state Algorithm 1
- * prescribes.
+ * prescribes.  With LESSDEC_FLAG_LAMBDA the discarded pair is instead the oldest one that is
+ * neither among the first n_heavy tokens of the sequence nor among the n_recent most recent.
  */
 int lessdec_step(const lessdec_desc *desc, const void *q, const void *k, const void *v,
                  void *out, int32_t *evicted_pos, void *hip_stream);
