@@ -53,6 +53,10 @@
 #define LESS_FLAG_SPARSE_DENOM 1u /* accumulate e^s / (sparse-only denominator) */
 #define LESS_FLAG_LAMBDA 2u       /* Lambda-masking instead of H2O: keep the first n_heavy
                                      tokens and the n_recent most recent ones              */
+#define LESS_FLAG_PROMPT_STEPWISE 4u /* the sparse policy runs from the first prompt token
+                                     (the evaluation setting of Sec. 4.1, where the policy
+                                     masks query-key pairs throughout the sequence) instead
+                                     of once at the end of the prompt                      */
 
 typedef struct less_oracle_state {
   int32_t U, heads, D, n_heavy, n_recent, R, Rp;
@@ -422,11 +426,39 @@ int less_oracle_step(less_oracle_state *S, const double *q, const double *k, con
   return bad;
 }
 
-/* Q,K,V [U,P,D]; out [U,P,D] or NULL; colsum [U,P] or NULL; kept [U,P] or NULL; dec [U,4] */
+/*
+ * Prompt phase with the policy active from the first token: token t of the prompt is one
+ * generation step (Algorithm 1) with its own query, key and value, exactly as if the prompt
+ * were generated.  out [P,D] or NULL: Eq. 3's output at every token.
+ */
+static void prefill_unit_stepwise(unit_view *s, const double *Q, const double *K, const double *V,
+                                  int64_t P, double *out)
+{
+  double *o = (double *)malloc(sizeof(double) * (size_t)s->D);
+  double dec[4];
+  int64_t ev;
+  reset_unit(s);
+  for (int64_t t = 0; t < P; ++t) {
+    step_unit(s, Q + t * s->D, K + t * s->D, V + t * s->D, -1, o, &ev, dec, NULL);
+    if (out) memcpy(out + t * s->D, o, sizeof(double) * (size_t)s->D);
+  }
+  free(o);
+}
+
+/* Q,K,V [U,P,D]; out [U,P,D] or NULL; colsum [U,P] or NULL; kept [U,P] or NULL; dec [U,4]
+   (colsum, kept and dec are left untouched in the stepwise setting) */
 void less_oracle_prefill(less_oracle_state *S, const double *Q, const double *K, const double *V,
                          int64_t P, double *out, double *colsum, int8_t *kept, double *dec)
 {
   const size_t PD = (size_t)P * S->D;
+  if (S->flags & LESS_FLAG_PROMPT_STEPWISE) {
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int u = 0; u < S->U; ++u) {
+      unit_view s = view_of(S, u);
+      prefill_unit_stepwise(&s, Q + u * PD, K + u * PD, V + u * PD, P, out ? out + u * PD : NULL);
+    }
+    return;
+  }
 #pragma omp parallel for schedule(dynamic, 1)
   for (int u = 0; u < S->U; ++u) {
     unit_view s = view_of(S, u);

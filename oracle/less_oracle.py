@@ -22,6 +22,7 @@ _lib = None
 
 FLAG_SPARSE_DENOM = 1
 FLAG_LAMBDA = 2          # Lambda-masking instead of H2O (Sec. 4, setup)
+FLAG_PROMPT_STEPWISE = 4 # the policy runs from the first prompt token (Sec. 4.1 setting)
 
 
 def build(force: bool = False) -> Path:
@@ -186,8 +187,8 @@ class OracleState:
         assert Q.shape == K.shape == V.shape and Q.shape[0] == self.U and Q.shape[2] == self.D
         P = Q.shape[1]
         out = np.empty((self.U, P, self.D)) if want_out else None
-        colsum = np.empty((self.U, P)); kept = np.empty((self.U, P), dtype=np.int8)
-        dec = np.empty((self.U, 4))
+        colsum = np.zeros((self.U, P)); kept = np.ones((self.U, P), dtype=np.int8)
+        dec = np.full((self.U, 4), np.inf); dec[:, 1::2] = -1
         lib().less_oracle_prefill(C.byref(self._struct()), _ptr(Q), _ptr(K), _ptr(V), P,
                                   _ptr(out), _ptr(colsum), _ptr(kept), _ptr(dec))
         return {"out": out, "colsum": colsum, "kept": kept.astype(bool), "dec": dec}

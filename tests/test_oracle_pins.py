@@ -268,6 +268,36 @@ def test_lambda_masking_keeps_the_first_and_the_latest_tokens(P):
         assert sorted(st.pos[u]) == list(range(Nh)) + list(range(n - Nr, n))
 
 
+@pytest.mark.parametrize("flags", [4, 6])
+def test_stepwise_prompt_is_the_generation_loop(flags):
+    """Sec. 4.1's setting: the sparse policy acts from the first token on.  The prompt phase
+    is then nothing but Algorithm 1 applied to every prompt token: same outputs, evictions and
+    state as the set-based twin stepping through the prompt from an empty cache."""
+    rng = np.random.default_rng(31 + flags)
+    U, heads, D, Rp, R, Nh, Nr, P, T = 3, 2, 6, 9, 3, 3, 4, 25, 6
+    W = make_weights(rng, heads, D, Rp, R)
+    st = lo.OracleState(U, heads, D, Nh, Nr, R, Rp, W, flags=flags)
+    Q, K, V = (rng.standard_normal((U, P, D)) for _ in range(3))
+    q, k, v = (rng.standard_normal((T, U, D)) for _ in range(3))
+    pre = st.prefill(Q, K, V)
+    twins = [BruteForceUnit(D, Nh, Nr, head_w(W, u % heads), policy="lambda" if flags & 2 else "h2o")
+             for u in range(U)]
+    for u, tw in enumerate(twins):
+        for t in range(P):
+            o, _ = tw.step(Q[u, t], K[u, t], V[u, t])
+            np.testing.assert_allclose(pre["out"][u, t], o, rtol=1e-9, atol=1e-12)
+        assert set(st.pos[u][st.pos[u] >= 0]) == tw.alive and st.n[u] == P
+        Hc, zc = tw.state()
+        np.testing.assert_allclose(st.H[u], Hc, rtol=1e-10, atol=1e-13)
+        np.testing.assert_allclose(st.z[u], zc, rtol=1e-10, atol=1e-13)
+    for t in range(T):                                    # and generation carries on from there
+        r = st.step(q[t], k[t], v[t])
+        for u, tw in enumerate(twins):
+            o, ev = tw.step(q[t, u], k[t, u], v[t, u])
+            assert r["evicted"][u] == ev
+            np.testing.assert_allclose(r["out"][u], o, rtol=1e-9, atol=1e-12)
+
+
 def test_policy_invariants_and_convexity():
     rng = np.random.default_rng(11)
     U, heads, D, Rp, R, Nh, Nr, P, T = 4, 2, 8, 16, 4, 4, 4, 30, 40
