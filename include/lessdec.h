@@ -48,6 +48,11 @@ extern "C" {
                                         the first leaves.  Scores are still accumulated in
                                         acc but decide nothing                              */
 
+#define LESSDEC_FLAG_PROMPT_STEPWISE 4u /* lessdec_prefill runs the sparse policy from the first
+                                        prompt token (the evaluation setting of Sec. 4.1, where
+                                        the policy masks query-key pairs throughout the sequence)
+                                        instead of pruning once at the end of the prompt     */
+
 #define LESSDEC_OK 0
 #define LESSDEC_EINVAL (-1)    /* bad shape, NULL or misaligned pointer, unsupported size */
 #define LESSDEC_EWORKSPACE (-2)/* workspace missing or too small                          */
@@ -122,6 +127,10 @@ int lessdec_state_sync(const lessdec_desc *desc, void *hip_stream);
  * later token), in ascending token order, with acc = column sum; every other prompt pair
  * is folded into H, z (Eq. 6); n_seen = P.  If P <= C every token is kept.
  * With LESSDEC_FLAG_LAMBDA the first n_heavy tokens are kept in place of the heavy hitters.
+ * With LESSDEC_FLAG_PROMPT_STEPWISE the call is lessdec_state_reset followed by one
+ * lessdec_step per prompt token t with rows Q[.,.,t,.], K[.,.,t,.], V[.,.,t,.] (2 P launches
+ * plus row staging; not the fast way through a prompt): out[.,.,t,.] is then Eq. 3's output
+ * at token t, and the state afterwards is the state after P steps (a fold may be pending).
  * Overwrites any previous state of the descriptor (no reset needed before it).
  * P >= 1.  Needs the workspace sized for max_prompt >= P.
  */

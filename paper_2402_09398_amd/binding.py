@@ -16,6 +16,7 @@ LIB_PATH = _HERE / "liblessdec.so"
 DTYPE_F32, DTYPE_F16 = 0, 1
 FLAG_SPARSE_DENOM = 1
 FLAG_LAMBDA = 2
+FLAG_PROMPT_STEPWISE = 4
 OK, EINVAL, EWORKSPACE, EHIP = 0, -1, -2, -3
 
 EXPORTS = ("lessdec_workspace_bytes", "lessdec_state_reset", "lessdec_state_sync", "lessdec_prefill", "lessdec_step", "lessdec_step_features", "lessdec_step_attend",

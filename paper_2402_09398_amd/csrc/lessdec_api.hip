@@ -26,7 +26,7 @@ bool shape_ok(const lessdec_desc *d, Shape *s)
   if (d->rank < 1 || d->rank > LESSDEC_MAX_RANK) return false;
   if (d->hidden < 1 || d->hidden > LESSDEC_MAX_HIDDEN) return false;
   if (d->dtype != LESSDEC_DTYPE_F32 && d->dtype != LESSDEC_DTYPE_F16) return false;
-  if (d->flags & ~(LESSDEC_FLAG_SPARSE_DENOM | LESSDEC_FLAG_LAMBDA)) return false;
+  if (d->flags & ~(LESSDEC_FLAG_SPARSE_DENOM | LESSDEC_FLAG_LAMBDA | LESSDEC_FLAG_PROMPT_STEPWISE)) return false;
   if ((long)d->batch * d->heads > (1L << 30)) return false;
   s->U = (size_t)d->batch * d->heads;
   s->C = (size_t)C;
@@ -37,10 +37,10 @@ bool shape_ok(const lessdec_desc *d, Shape *s)
 }
 
 // Workspace: [ f_phi U*R f64 | f_psi U*R f32 | mlp_parts 2*ceil(R'/64)*U*16 f32 |
-//              prefill: lse, colsum U*P f64 | slot_of U*P i32 | psi_all U*P*R f32 ],
+//              prefill: 4 staged rows U*D (4 bytes each) | lse, colsum U*P f64 | slot_of U*P i32 | psi_all U*P*R f32 ],
 // every part 256-byte aligned.
 struct Workspace {
-  size_t off_fphi, off_fpsi, off_parts, off_lse, off_colsum, off_slot,
+  size_t off_fphi, off_fpsi, off_parts, off_stage, off_lse, off_colsum, off_slot,
       off_psiall, total;
 };
 
@@ -51,6 +51,7 @@ Workspace carve(const Shape &s, size_t P)
   w.off_fphi = o; o = align_up(o + s.U * s.R * sizeof(double), 256);
   w.off_fpsi = o; o = align_up(o + s.U * s.R * sizeof(float), 256);
   w.off_parts = o; o = align_up(o + 2 * (size_t)mlp_nparts((int)s.Rp) * s.U * 16 * sizeof(float), 256);
+  w.off_stage = o; o = align_up(o + (P ? 4 * s.U * s.D * sizeof(float) : 0), 256);
   w.off_lse = o; o = align_up(o + s.U * P * sizeof(double), 256);
   w.off_colsum = o; o = align_up(o + s.U * P * sizeof(double), 256);
   w.off_slot = o; o = align_up(o + s.U * P * sizeof(int32_t), 256);
@@ -207,6 +208,25 @@ int lessdec_prefill(const lessdec_desc *desc, const void *Q, const void *K, cons
     return LESSDEC_EINVAL;
   const Workspace w = carve(s, (size_t)P);
   char *ws = static_cast<char *>(desc->workspace);
+  if (desc->flags & LESSDEC_FLAG_PROMPT_STEPWISE) {
+    // the generation loop over the prompt: token t's rows are staged as one step's q, k, v
+    hipStream_t st = (hipStream_t)hip_stream;
+    PromptRowsArgs r;
+    r.Q = Q; r.K = K; r.V = V; r.out = out; r.P = P; r.U = (unsigned)s.U; r.D = desc->head_dim;
+    r.dtype = desc->dtype;
+    r.qs = ws + w.off_stage;
+    r.ks = ws + w.off_stage + 1 * s.U * s.D * sizeof(float);
+    r.vs = ws + w.off_stage + 2 * s.U * s.D * sizeof(float);
+    r.outs = ws + w.off_stage + 3 * s.U * s.D * sizeof(float);
+    if (launch_reset(desc, st) != hipSuccess) return LESSDEC_EHIP;
+    for (int32_t t = 0; t < P; ++t) {
+      if (launch_prompt_rows(r, t, (out && t > 0) ? t - 1 : -1, st) != hipSuccess) return LESSDEC_EHIP;
+      if ((rc = lessdec_step_features(desc, r.qs, r.ks, hip_stream)) != LESSDEC_OK) return rc;
+      if ((rc = lessdec_step_attend(desc, r.qs, r.ks, r.vs, r.outs, nullptr, hip_stream)) != LESSDEC_OK) return rc;
+    }
+    if (out && launch_prompt_rows(r, -1, P - 1, st) != hipSuccess) return LESSDEC_EHIP;
+    return LESSDEC_OK;
+  }
   PrefillArgs a;
   a.d = desc; a.Q = Q; a.K = K; a.V = V; a.P = P; a.out = out;
   a.lse = reinterpret_cast<double *>(ws + w.off_lse);

@@ -93,4 +93,16 @@ struct PrefillArgs {
 };
 hipError_t launch_prefill(const PrefillArgs &a, hipStream_t st);
 
+// Row staging for the prompt phase taken token by token: rows [U,P,D] <-> one step's [U,D].
+struct PromptRowsArgs {
+  const void *Q, *K, *V;   // [U,P,D] dtype
+  void *out;               // [U,P,D] dtype or NULL
+  void *qs, *ks, *vs;      // [U,D] dtype: token `gather`'s rows
+  void *outs;              // [U,D] dtype: the output of token `scatter`
+  int P, D, dtype;
+  unsigned U;
+};
+// gather < 0: nothing staged; scatter < 0: nothing written back
+hipError_t launch_prompt_rows(const PromptRowsArgs &a, int gather, int scatter, hipStream_t st);
+
 }  // namespace lessdec

@@ -542,6 +542,37 @@ static hipError_t launch_prefill_t(const PrefillArgs &a, hipStream_t st)
   return hipGetLastError();
 }
 
+// -------------------------------------------------------------------------------------
+// Row staging for the prompt taken token by token: one 16-byte vector per thread.
+// -------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void prompt_rows_kernel(const uint4 *__restrict__ Q, const uint4 *__restrict__ K,
+                                                          const uint4 *__restrict__ V, uint4 *__restrict__ out,
+                                                          uint4 *__restrict__ qs, uint4 *__restrict__ ks,
+                                                          uint4 *__restrict__ vs, const uint4 *__restrict__ outs,
+                                                          unsigned U, int P, int vecs, int gather, int scatter)
+{
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;   // vector index in [U, vecs]
+  if (i >= (size_t)U * vecs) return;
+  const size_t u = i / vecs, c = i % vecs;
+  if (scatter >= 0) out[(u * P + scatter) * vecs + c] = outs[i];
+  if (gather >= 0) {
+    const size_t src = (u * P + gather) * vecs + c;
+    qs[i] = Q[src];
+    ks[i] = K[src];
+    vs[i] = V[src];
+  }
+}
+
+hipError_t launch_prompt_rows(const PromptRowsArgs &a, int gather, int scatter, hipStream_t st)
+{
+  const int vecs = a.D * (a.dtype == LESSDEC_DTYPE_F16 ? 2 : 4) / 16;
+  const size_t n = (size_t)a.U * vecs;
+  prompt_rows_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(
+      (const uint4 *)a.Q, (const uint4 *)a.K, (const uint4 *)a.V, (uint4 *)a.out, (uint4 *)a.qs, (uint4 *)a.ks,
+      (uint4 *)a.vs, (const uint4 *)a.outs, a.U, a.P, vecs, gather, scatter);
+  return hipGetLastError();
+}
+
 hipError_t launch_prefill(const PrefillArgs &a, hipStream_t st)
 {
   const int D = a.d->head_dim;

@@ -132,6 +132,48 @@ def test_lambda_masking_at_the_benchmark_shape():
     assert rep.exempt == 0 and 0.0 < rep.mean_share < 1.0
 
 
+# The sparse policy active from the first prompt token (Sec. 4.1's evaluation setting)
+STEPWISE = [
+    small("stepwise-streaming", prompt=40, steps=20),
+    small("stepwise-general-f32", dtype="f32", head_dim=64, rank=4, prompt=40, steps=20),
+    small("stepwise-lambda", n_heavy=4, n_recent=8, prompt=40, steps=10),
+    small("stepwise-split-waves", n_heavy=20, n_recent=20, prompt=100, steps=10),
+    small("stepwise-prompt-fits", n_heavy=30, n_recent=30, prompt=25, steps=50),
+]
+
+
+@pytest.mark.parametrize("w", STEPWISE, ids=lambda w: w.name)
+def test_policy_from_the_first_prompt_token(w):
+    flags = 4 | (2 if "lambda" in w.name else 0)
+    rep = hz.run_workload(w, range(w.units), flags=flags)
+    report_ok(rep, min_decisions=w.units * max(0, min(w.steps, w.prompt + w.steps - w.capacity)))
+
+
+@pytest.mark.parametrize("kind", ["streaming", "general"])
+def test_stepwise_prompt_is_the_generation_loop(kind):
+    """lessdec_prefill with LESSDEC_FLAG_PROMPT_STEPWISE = reset + one lessdec_step per prompt token."""
+    import torch
+    w = small("stepwise-loop", prompt=30, steps=0) if kind == "streaming" else \
+        small("stepwise-loop-general", prompt=30, steps=0, rank=20)
+    inp = wl.all_inputs(w)
+    Q, K, V = (torch.from_numpy(inp[n]).cuda() for n in ("Q", "K", "V"))
+    a = hz.make_gpu(w, flags=4)
+    out_a = torch.empty_like(Q)
+    a.prefill(Q, K, V, out=out_a)
+    b = hz.make_gpu(w, flags=0)
+    b.state_reset()
+    out_b = torch.empty_like(Q)
+    Qt, Kt, Vt = (x.reshape(w.units, w.prompt, w.head_dim).transpose(0, 1).contiguous() for x in (Q, K, V))
+    step_out = torch.empty_like(Qt[0])
+    for t in range(w.prompt):
+        b.step(Qt[t], Kt[t], Vt[t], step_out)
+        out_b.reshape(w.units, w.prompt, w.head_dim)[:, t].copy_(step_out)
+    torch.cuda.synchronize()
+    assert torch.equal(out_a, out_b)
+    for n in a.STATE:
+        assert torch.equal(getattr(a, n), getattr(b, n)), n
+
+
 def test_maximum_capacity():
     w = small("max-capacity", batch=1, heads=2, n_heavy=2047, n_recent=2047, prompt=4200, steps=6,
               rank=16, hidden=128)
