@@ -37,10 +37,10 @@ bool shape_ok(const lessdec_desc *d, Shape *s)
 }
 
 // Workspace: [ f_phi U*R f64 | f_psi U*R f32 | mlp_parts 2*ceil(R'/64)*U*16 f32 |
-//              prefill: 4 staged rows U*D (4 bytes each) | lse, colsum U*P f64 | slot_of U*P i32 | psi_all U*P*R f32 ],
+//              prefill: 4 staged rows U*D (4 bytes each) | lse, colsum U*P f64 | approx U*P f32, list U*P i32, count U i32 | slot_of U*P i32 | psi_all U*P*R f32 ],
 // every part 256-byte aligned.
 struct Workspace {
-  size_t off_fphi, off_fpsi, off_parts, off_stage, off_lse, off_colsum, off_slot,
+  size_t off_fphi, off_fpsi, off_parts, off_stage, off_lse, off_colsum, off_approx, off_list, off_count, off_slot,
       off_psiall, total;
 };
 
@@ -54,6 +54,9 @@ Workspace carve(const Shape &s, size_t P)
   w.off_stage = o; o = align_up(o + (P ? 4 * s.U * s.D * sizeof(float) : 0), 256);
   w.off_lse = o; o = align_up(o + s.U * P * sizeof(double), 256);
   w.off_colsum = o; o = align_up(o + s.U * P * sizeof(double), 256);
+  w.off_approx = o; o = align_up(o + s.U * P * sizeof(float), 256);
+  w.off_list = o; o = align_up(o + s.U * P * sizeof(int32_t), 256);
+  w.off_count = o; o = align_up(o + (P ? s.U * sizeof(int32_t) : 0), 256);
   w.off_slot = o; o = align_up(o + s.U * P * sizeof(int32_t), 256);
   w.off_psiall = o; o = align_up(o + s.U * P * s.R * sizeof(float), 256);
   w.total = o;
@@ -232,6 +235,9 @@ int lessdec_prefill(const lessdec_desc *desc, const void *Q, const void *K, cons
   a.lse = reinterpret_cast<double *>(ws + w.off_lse);
   a.colsum = reinterpret_cast<double *>(ws + w.off_colsum);
   a.slot_of = reinterpret_cast<int32_t *>(ws + w.off_slot);
+  a.approx = reinterpret_cast<float *>(ws + w.off_approx);
+  a.list = reinterpret_cast<int32_t *>(ws + w.off_list);
+  a.count = reinterpret_cast<int32_t *>(ws + w.off_count);
   a.psi_all = reinterpret_cast<float *>(ws + w.off_psiall);
   return launch_prefill(a, (hipStream_t)hip_stream) == hipSuccess ? LESSDEC_OK : LESSDEC_EHIP;
 }

@@ -89,6 +89,9 @@ struct PrefillArgs {
   double *lse;              // [U,P] ln sum_j e^{s_ij} of every causal row
   double *colsum;           // [U,P]
   int32_t *slot_of;         // [U,P] slot index of a kept token, -1 if discarded
+  float *approx;            // [U,P] cheap column sums (selection band only)
+  int32_t *list;            // [U,P] tokens whose exact column sum is wanted; later keep flags
+  int32_t *count;           // [U] length of each unit's list
   float *psi_all;           // [U,P,R]
 };
 hipError_t launch_prefill(const PrefillArgs &a, hipStream_t st);

@@ -286,25 +286,26 @@ __global__ __launch_bounds__(64 * kPrefillWaves) void prefill_colpass_kernel(
     qraw.load(Qu + (size_t)qr * D, g);
     lq = lse_u[qr];
   }
-  for (int it = jt; it < nblk; ++it) {
+  auto tile = [&](int it, const Chunk<T, D> &cur, double lcur, Chunk<T, D> &nxt, double &lnxt) {
     const int qi = it * 16 + c;
-    Chunk<T, D> qnext;
-    double lnext;
     {
       const int qn = (it + 1 < nblk ? qi + 16 : qi);
       const int qr = qn < P ? qn : P - 1;
-      qnext.load(Qu + (size_t)qr * D, g);
-      lnext = lse_u[qr];
+      nxt.load(Qu + (size_t)qr * D, g);
+      lnxt = lse_u[qr];
     }
-    const v4d acc = tile_kq<T, D>(kd, qraw);
+    const v4d acc = tile_kq<T, D>(kd, cur);
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
-      const int kj = j0 + g + 4 * v;
-      const double a = exp_softmax_f64(fma(acc[v], scale, -lq));
-      cs[v] += (qi < P && kj <= qi) ? a : 0.0;
+      const double a = exp_softmax_f64(fma(acc[v], scale, -lcur));
+      cs[v] += (qi < P && (j0 + g + 4 * v) <= qi) ? a : 0.0;
     }
-    qraw = qnext;
-    lq = lnext;
+  };
+  Chunk<T, D> qother;
+  double lother;
+  for (int it = jt; it < nblk; it += 2) {
+    tile(it, qraw, lq, qother, lother);
+    if (it + 1 < nblk) tile(it + 1, qother, lother, qraw, lq);
   }
 #pragma unroll
   for (int v = 0; v < 4; ++v) {
@@ -312,6 +313,293 @@ __global__ __launch_bounds__(64 * kPrefillWaves) void prefill_colpass_kernel(
     for (int o = 8; o > 0; o >>= 1) cs[v] += __shfl_xor(cs[v], o);
     const int kj = j0 + g + 4 * v;
     if (c == 0 && kj < P) colsum[u * (size_t)P + kj] = cs[v];
+  }
+}
+
+// -------------------------------------------------------------------------------------
+// Cheap column sums, fp16 storage only: the same sweep as the column pass on
+// v_mfma_f32_16x16x32_f16 with fp32 accumulation and the fast fp32 exponential.  Their only
+// use is to tell which tokens can possibly matter for the selection (prefill_band_kernel);
+// every value that decides or is stored comes from the exact pass over those tokens.
+// Lane (g, c) supplies elements 32 ks + 8 g .. + 7 of key row c (A) and of query row c (B);
+// result register w holds S^T[key 4 g + w][query c].
+// -------------------------------------------------------------------------------------
+typedef _Float16 v8h __attribute__((ext_vector_type(8)));
+constexpr int kApproxTiles = 4;    // key tiles (of 16) per wave: a query tile is loaded once for all of them
+template <int D>
+__global__ __launch_bounds__(64 * kPrefillWaves) void prefill_colapprox_kernel(
+    const __half *__restrict__ Q, const __half *__restrict__ K, unsigned U, int P,
+    const double *__restrict__ lse, float *__restrict__ approx)
+{
+  constexpr int KS = D / 32, KT = kApproxTiles;
+  const int nblk = (P + 15) / 16;
+  const int nkb = (nblk + KT - 1) / KT;                   // groups of KT key tiles
+  const int ngrp = (nkb + kPrefillWaves - 1) / kPrefillWaves;
+  const PrefillBlock pb = prefill_block(blockIdx.x, ngrp);
+  const size_t u = pb.u;
+  const int l = threadIdx.x % 64, g = l / 16, c = l % 16;
+  const int kb = pb.grp * kPrefillWaves + (int)(threadIdx.x / 64);
+  if (kb >= nkb || pb.u >= U) return;                     // wave-uniform; the waves share nothing
+  const int jt0 = kb * KT, j0 = jt0 * 16;
+  const __half *Qu = Q + u * (size_t)P * D, *Ku = K + u * (size_t)P * D;
+  const double *lse_u = lse + u * (size_t)P;
+  const float scale = (float)(1.0 / sqrt((double)D));
+  auto load_row = [&](const __half *row, v8h (&dst)[KS]) {
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) dst[ks] = *reinterpret_cast<const v8h *>(row + 32 * ks + 8 * g);
+  };
+  v8h ka[KT][KS], qa[KS];
+#pragma unroll
+  for (int t = 0; t < KT; ++t) {
+    const int kr = j0 + 16 * t + c;
+    load_row(Ku + (size_t)(kr < P ? kr : P - 1) * D, ka[t]);
+  }
+  float lq;
+  {
+    const int qr = j0 + c < P ? j0 + c : P - 1;
+    load_row(Qu + (size_t)qr * D, qa);
+    lq = (float)lse_u[qr];
+  }
+  float cs[KT][4];
+#pragma unroll
+  for (int t = 0; t < KT; ++t)
+#pragma unroll
+    for (int w = 0; w < 4; ++w) cs[t][w] = 0.f;
+  // one query tile: request the tile after it into `nxt`, then multiply `cur` (two buffers
+  // that swap roles, so that no register copy has to wait for the request just made)
+  auto tile = [&](int it, const v8h (&cur)[KS], float lcur, v8h (&nxt)[KS], float &lnxt) {
+    const int qi = it * 16 + c;
+    {
+      const int qx = (it + 1 < nblk ? qi + 16 : qi);
+      const int qr = qx < P ? qx : P - 1;
+      load_row(Qu + (size_t)qr * D, nxt);
+      lnxt = (float)lse_u[qr];
+    }
+#pragma unroll
+    for (int t = 0; t < KT; ++t) {
+      if (jt0 + t > it) continue;                         // key tile wholly after these queries (uniform)
+      v4f acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka[t][ks], cur[ks], acc, 0, 0, 0);
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        const int kj = j0 + 16 * t + 4 * g + w;
+        const float a = __expf(fmaf(acc[w], scale, -lcur));
+        cs[t][w] += (qi < P && kj <= qi) ? a : 0.f;
+      }
+    }
+  };
+  v8h qb[KS];
+  float lb;
+  for (int it = jt0; it < nblk; it += 2) {
+    tile(it, qa, lq, qb, lb);
+    if (it + 1 < nblk) tile(it + 1, qb, lb, qa, lq);
+  }
+#pragma unroll
+  for (int t = 0; t < KT; ++t)
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+#pragma unroll
+      for (int o = 8; o > 0; o >>= 1) cs[t][w] += __shfl_xor(cs[t][w], o);
+      const int kj = j0 + 16 * t + 4 * g + w;
+      if (c == 0 && kj < P) approx[u * (size_t)P + kj] = cs[t][w];
+    }
+}
+
+// -------------------------------------------------------------------------------------
+// Which tokens can matter, from the cheap column sums.  With every cheap value within a
+// relative kBand of the exact one (worst-case error of the fp32 path is about a quarter of
+// that), a token is surely a heavy hitter if fewer than Nh others could possibly be larger,
+// surely discarded if at least Nh others are surely larger, and in doubt otherwise.
+// flag[j] = 1 kept for sure (heavy or recent), 0 discarded for sure, 2 in doubt.
+// One thread per token.   grid = U * ceil(P / 256), block = 256.
+// -------------------------------------------------------------------------------------
+constexpr float kBand = 1.0f / 256.0f;
+__global__ __launch_bounds__(256) void prefill_band_kernel(const float *__restrict__ approx, int P, int Nh,
+                                                           int Nr, int32_t *__restrict__ flag)
+{
+  const int nb = (P + 255) / 256;
+  const size_t u = blockIdx.x / nb;
+  const int j = (int)(blockIdx.x % nb) * 256 + (int)threadIdx.x;
+  if (j >= P) return;
+  const float *a = approx + u * (size_t)P;
+  const int ncand = P - Nr;
+  int f = 1;                                    // recent
+  if (j < ncand) {
+    const float lo = a[j] * (1.f - kBand), hi = a[j] * (1.f + kBand);
+    int maybe_larger = 0, surely_larger = 0;
+    for (int i = 0; i < ncand; ++i) {
+      const float b = a[i];
+      maybe_larger += (b * (1.f + kBand) >= lo) ? 1 : 0;   // counts j itself
+      surely_larger += (b * (1.f - kBand) > hi) ? 1 : 0;
+    }
+    f = (maybe_larger - 1 < Nh) ? 1 : (surely_larger >= Nh ? 0 : 2);
+  }
+  flag[u * (size_t)P + j] = f;
+}
+
+// -------------------------------------------------------------------------------------
+// List of the tokens whose exact column sum is wanted (flag != 0), ascending, per unit.
+// grid = U, block = 256.
+// -------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void prefill_compact_kernel(const int32_t *__restrict__ flag, int P,
+                                                              int32_t *__restrict__ list,
+                                                              int32_t *__restrict__ count)
+{
+  __shared__ int s_cnt[256];
+  const size_t u = blockIdx.x;
+  const int tid = threadIdx.x;
+  const int32_t *f = flag + u * (size_t)P;
+  int32_t *out = list + u * (size_t)P;
+  const int chunk = (P + 255) / 256;
+  const int lo = tid * chunk < P ? tid * chunk : P, hi = (lo + chunk < P) ? lo + chunk : P;
+  int cnt = 0;
+  for (int j = lo; j < hi; ++j) cnt += f[j] != 0 ? 1 : 0;
+  s_cnt[tid] = cnt;
+  __syncthreads();
+  int base = 0;
+  for (int t = 0; t < tid; ++t) base += s_cnt[t];
+  for (int j = lo; j < hi; ++j)
+    if (f[j] != 0) out[base++] = j;
+  if (tid == 255) count[u] = base;
+}
+
+// -------------------------------------------------------------------------------------
+// Exact column sums of listed tokens only: the column pass with 16 listed keys per wave in
+// place of 16 consecutive ones.  The sweep starts at the query tile of the wave's earliest
+// key; a key takes part from its own position on.  The length of the list is only known on
+// the device: a unit gets enough blocks for a list a little longer than the budget, and its
+// waves loop should the list be longer.   grid = ceil(U / 8) * 8 * blocks_per_unit.
+// -------------------------------------------------------------------------------------
+template <typename T, int D>
+__global__ __launch_bounds__(64 * kPrefillWaves) void prefill_colexact_kernel(
+    const T *__restrict__ Q, const T *__restrict__ K, unsigned U, int P, const double *__restrict__ lse,
+    const int32_t *__restrict__ list, const int32_t *__restrict__ count, int blocks_per_unit,
+    double *__restrict__ colsum)
+{
+  constexpr int CH = D / 4;
+  const int nblk = (P + 15) / 16;
+  const PrefillBlock pb = prefill_block(blockIdx.x, blocks_per_unit);
+  const size_t u = pb.u;
+  const int l = threadIdx.x % 64, g = l / 16, c = l % 16;
+  if (pb.u >= U) return;
+  const int n = count[u];
+  const T *Qu = Q + u * (size_t)P * D, *Ku = K + u * (size_t)P * D;
+  const double *lse_u = lse + u * (size_t)P;
+  const double scale = 1.0 / sqrt((double)D);
+  // tiles of 16 listed keys, dealt to the unit's waves in turn (the list is ascending, so
+  // the long sweeps come first); wave-uniform, the waves share nothing
+  for (int lt = pb.grp * kPrefillWaves + (int)(threadIdx.x / 64); lt * 16 < n;
+       lt += blocks_per_unit * kPrefillWaves) {
+    const int32_t *li = list + u * (size_t)P + lt * 16;
+    const int nk = n - lt * 16 < 16 ? n - lt * 16 : 16;   // listed keys of this tile
+    double kd[CH];
+    {
+      Chunk<T, D> kraw;
+      kraw.load(Ku + (size_t)li[c < nk ? c : 0] * D, g);
+#pragma unroll
+      for (int s = 0; s < CH; ++s) kd[s] = kraw.get(s);
+    }
+    int kjv[4];                                           // positions of the lane's four keys
+#pragma unroll
+    for (int v = 0; v < 4; ++v) kjv[v] = g + 4 * v < nk ? li[g + 4 * v] : INT_MAX;
+    const int it0 = li[0] / 16;
+    double cs[4] = {0.0, 0.0, 0.0, 0.0};
+    Chunk<T, D> qraw;
+    double lq;
+    {
+      const int qr = it0 * 16 + c < P ? it0 * 16 + c : P - 1;
+      qraw.load(Qu + (size_t)qr * D, g);
+      lq = lse_u[qr];
+    }
+    auto tile = [&](int it, const Chunk<T, D> &cur, double lcur, Chunk<T, D> &nxt, double &lnxt) {
+      const int qi = it * 16 + c;
+      {
+        const int qn = (it + 1 < nblk ? qi + 16 : qi);
+        const int qr = qn < P ? qn : P - 1;
+        nxt.load(Qu + (size_t)qr * D, g);
+        lnxt = lse_u[qr];
+      }
+      const v4d acc = tile_kq<T, D>(kd, cur);
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const double a = exp_softmax_f64(fma(acc[v], scale, -lcur));
+        cs[v] += (qi < P && kjv[v] <= qi) ? a : 0.0;
+      }
+    };
+    Chunk<T, D> qother;
+    double lother;
+    for (int it = it0; it < nblk; it += 2) {
+      tile(it, qraw, lq, qother, lother);
+      if (it + 1 < nblk) tile(it + 1, qother, lother, qraw, lq);
+    }
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+#pragma unroll
+      for (int o = 8; o > 0; o >>= 1) cs[v] += __shfl_xor(cs[v], o);
+      if (c == 0 && kjv[v] != INT_MAX) colsum[u * (size_t)P + kjv[v]] = cs[v];
+    }
+  }
+}
+
+// -------------------------------------------------------------------------------------
+// Settles the tokens in doubt with their exact column sums: the heavy set is the tokens kept
+// for sure plus the best of those in doubt, by (column sum, position) as in the rank kernel.
+// keep[j] = 1 / 0.   grid = U, block = 256.
+// -------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void prefill_refine_kernel(const double *__restrict__ colsum,
+                                                             const int32_t *__restrict__ flag, int P, int Nh,
+                                                             int Nr, int32_t *__restrict__ keep)
+{
+  constexpr int kCap = 1024;                    // tokens in doubt held in the LDS (a handful in practice)
+  __shared__ int s_sure, s_nd;
+  __shared__ int s_idx[kCap];
+  __shared__ double s_val[kCap];
+  const size_t u = blockIdx.x;
+  const int tid = threadIdx.x;
+  const double *cs = colsum + u * (size_t)P;
+  const int32_t *f = flag + u * (size_t)P;
+  int32_t *out = keep + u * (size_t)P;
+  const int ncand = P - Nr;
+  if (tid == 0) s_sure = s_nd = 0;
+  __syncthreads();
+  int mine = 0;
+  for (int j = tid; j < P; j += 256) {
+    const int fj = f[j];
+    mine += (fj == 1 && j < ncand) ? 1 : 0;
+    if (fj == 2) {
+      const int k = atomicAdd(&s_nd, 1);
+      if (k < kCap) {
+        s_idx[k] = j;
+        s_val[k] = cs[j];
+      }
+    }
+    out[j] = fj == 1 ? 1 : 0;
+  }
+  if (mine) atomicAdd(&s_sure, mine);
+  __syncthreads();
+  const int need = Nh - s_sure;                 // heavy slots left for the tokens in doubt
+  const int nd = s_nd;
+  if (nd <= kCap) {
+    for (int k = tid; k < nd; k += 256) {
+      const double a = s_val[k];
+      const int j = s_idx[k];
+      int larger = 0;
+      for (int i = 0; i < nd; ++i) larger += (s_val[i] > a || (s_val[i] == a && s_idx[i] > j)) ? 1 : 0;
+      out[j] = larger < need ? 1 : 0;
+    }
+  } else {
+    for (int j = tid; j < ncand; j += 256) {
+      if (f[j] != 2) continue;
+      const double a = cs[j];
+      int larger = 0;
+      for (int i = 0; i < ncand; ++i) {
+        if (f[i] != 2) continue;
+        const double b = cs[i];
+        larger += (b > a || (b == a && i > j)) ? 1 : 0;
+      }
+      out[j] = larger < need ? 1 : 0;
+    }
   }
 }
 
@@ -508,11 +796,45 @@ static hipError_t launch_prefill_t(const PrefillArgs &a, hipStream_t st)
                                                                    (const T *)a.V, U, P, a.lse, (T *)a.out);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  prefill_colpass_kernel<T, D><<<grid, 64 * kPrefillWaves, 0, st>>>((const T *)a.Q, (const T *)a.K, U, P,
-                                                                   a.lse, a.colsum);
-  if ((e = hipGetLastError()) != hipSuccess) return e;
-  prefill_rank_kernel<<<U * (unsigned)((P + 255) / 256), 256, 0, st>>>(
-      a.colsum, P, d->n_heavy, d->n_recent, (d->flags & LESSDEC_FLAG_LAMBDA) ? 1 : 0, a.slot_of);
+  // Column sums and selection.  Exact sums are needed of the kept tokens (they become the
+  // accumulated scores) and of those whose rank is in doubt; with fp16 storage the cheap pass
+  // tells which those are, with Lambda-masking the kept set is known beforehand.  Otherwise
+  // (fp32 storage, or a prompt inside the budget) every column is summed exactly.
+  const bool lambda = (d->flags & LESSDEC_FLAG_LAMBDA) != 0;
+  const unsigned rank_grid = U * (unsigned)((P + 255) / 256);
+  int32_t *keep = a.slot_of;
+  if (P > C && (lambda || sizeof(T) == 2)) {
+    if (lambda) {
+      prefill_rank_kernel<<<rank_grid, 256, 0, st>>>(a.colsum, P, d->n_heavy, d->n_recent, 1, a.slot_of);
+    } else {
+      if constexpr (sizeof(T) == 2) {
+        const unsigned agrid = (U + kXcds - 1) / kXcds * kXcds *
+                               (unsigned)((((P + 15) / 16 + kApproxTiles - 1) / kApproxTiles + kPrefillWaves - 1) /
+                                          kPrefillWaves);
+        prefill_colapprox_kernel<D><<<agrid, 64 * kPrefillWaves, 0, st>>>((const __half *)a.Q, (const __half *)a.K, U,
+                                                                         P, a.lse, a.approx);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+      }
+      prefill_band_kernel<<<rank_grid, 256, 0, st>>>(a.approx, P, d->n_heavy, d->n_recent, a.slot_of);
+    }
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    prefill_compact_kernel<<<U, 256, 0, st>>>(a.slot_of, P, a.list, a.count);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    const int bpu = (C + 32 + 16 * kPrefillWaves - 1) / (16 * kPrefillWaves);
+    prefill_colexact_kernel<T, D><<<(U + kXcds - 1) / kXcds * kXcds * (unsigned)bpu, 64 * kPrefillWaves, 0, st>>>(
+        (const T *)a.Q, (const T *)a.K, U, P, a.lse, a.list, a.count, bpu, a.colsum);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    if (!lambda) {
+      prefill_refine_kernel<<<U, 256, 0, st>>>(a.colsum, a.slot_of, P, d->n_heavy, d->n_recent, a.list);
+      keep = a.list;
+    }
+  } else {
+    prefill_colpass_kernel<T, D><<<grid, 64 * kPrefillWaves, 0, st>>>((const T *)a.Q, (const T *)a.K, U, P,
+                                                                     a.lse, a.colsum);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    prefill_rank_kernel<<<rank_grid, 256, 0, st>>>(a.colsum, P, d->n_heavy, d->n_recent, lambda ? 1 : 0,
+                                                   a.slot_of);
+  }
   if ((e = hipGetLastError()) != hipSuccess) return e;
   if (mlp_mfma_supported(d->dtype, d->head_dim, d->hidden, d->rank)) {
     MlpArgs fm;
@@ -529,15 +851,15 @@ static hipError_t launch_prefill_t(const PrefillArgs &a, hipStream_t st)
   const size_t lds = (size_t)C * sizeof(int);
   if (d->rank <= 4)
     prefill_finalize_kernel<T, D, 4><<<U, 256, lds, st>>>(
-      (const T *)a.K, (const T *)a.V, P, a.colsum, a.slot_of, a.psi_all, C, d->rank, (T *)d->k_cache,
+      (const T *)a.K, (const T *)a.V, P, a.colsum, keep, a.psi_all, C, d->rank, (T *)d->k_cache,
       (T *)d->v_cache, d->acc, d->pos, d->psi, d->H, d->z, d->n_seen, d->pend_slot);
   else if (d->rank <= 8)
     prefill_finalize_kernel<T, D, 8><<<U, 256, lds, st>>>(
-      (const T *)a.K, (const T *)a.V, P, a.colsum, a.slot_of, a.psi_all, C, d->rank, (T *)d->k_cache,
+      (const T *)a.K, (const T *)a.V, P, a.colsum, keep, a.psi_all, C, d->rank, (T *)d->k_cache,
       (T *)d->v_cache, d->acc, d->pos, d->psi, d->H, d->z, d->n_seen, d->pend_slot);
   else
     prefill_finalize_kernel<T, D, 16><<<U, 256, lds, st>>>(
-      (const T *)a.K, (const T *)a.V, P, a.colsum, a.slot_of, a.psi_all, C, d->rank, (T *)d->k_cache,
+      (const T *)a.K, (const T *)a.V, P, a.colsum, keep, a.psi_all, C, d->rank, (T *)d->k_cache,
       (T *)d->v_cache, d->acc, d->pos, d->psi, d->H, d->z, d->n_seen, d->pend_slot);
   return hipGetLastError();
 }
