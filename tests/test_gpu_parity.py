@@ -85,6 +85,12 @@ EDGE = [
     small("split-8-waves-no-recent", n_heavy=130, n_recent=0, prompt=200, steps=20, batch=1, heads=2),
     wl.WORKLOADS[4].scaled(name="heavy-tailed-keys", batch=1, heads=4, prompt=256, steps=64,
                            n_heavy=10, n_recent=10, hidden=128),
+    # near-uniform attention in fp16 storage: column sums of the prompt lie close together, so
+    # the cheap selection pass leaves many tokens in doubt for the exact pass to settle
+    wl.WORKLOADS[1].scaled(name="close-column-sums-f16", dtype="f16", head_dim=128, batch=2, heads=3,
+                           prompt=900, steps=12, n_heavy=300, n_recent=20, rank=8, hidden=128),
+    wl.WORKLOADS[1].scaled(name="close-column-sums-f16-d64", dtype="f16", head_dim=64, batch=1, heads=2,
+                           prompt=333, steps=12, n_heavy=40, n_recent=7, rank=4, hidden=64),
 ]
 
 
