@@ -247,7 +247,7 @@ __global__ __launch_bounds__(kWpuUnits * kWave) void wpu_step_kernel(void *k_cac
 #pragma unroll
       for (int i = 0; i < NR2; ++i) {
         const int j = lane + i * kWave;
-        sc[i] = j < rows ? exp(sc[i] - M) : 0.0;
+        sc[i] = j < rows ? exp_softmax_f64(sc[i] - M) : 0.0;
         S += sc[i];
       }
       S = wave_allreduce(S, OpAdd{});                       // sparse part of the denominator, shifted
@@ -270,12 +270,12 @@ __global__ __launch_bounds__(kWpuUnits * kWave) void wpu_step_kernel(void *k_cac
       //   M > 0 (or no low-rank term): everything times e^{-M};  M <= 0: unscaled, e^{M} <= 1
       double pscale;
       if (fz > 0.0 && M <= 0.0) {
-        const double w = exp(M);
+        const double w = exp_softmax_f64(M);
         const double inv = 1.0 / (fz + w * S);
         pscale = w * inv;
         lscale = inv;
       } else {
-        const double eM = (fz > 0.0) ? exp(-M) : 0.0;
+        const double eM = (fz > 0.0) ? exp_softmax_f64(-M) : 0.0;
         const double inv = 1.0 / (fz * eM + S);
         pscale = inv;
         lscale = eM * inv;
