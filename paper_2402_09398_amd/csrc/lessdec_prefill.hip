@@ -151,12 +151,16 @@ __device__ inline void store_out(__half *orow, int g, const v4f (&O)[D / 16], fl
 }
 
 // -------------------------------------------------------------------------------------
-// Row pass: one wave per block of 16 queries, kPrefillWaves independent waves per
-// workgroup.  Sweeps the key tiles up to the diagonal, keeps the running row maximum m_i
-// and sum L_i = sum_j e^{s_ij - m_i} (fp64) and, if an output is wanted, the flash-style
-// running numerator in fp32; the numerator is rescaled only in tiles where some row's
-// maximum moved.  The next key tile is requested before the current one is multiplied.
-// Leaves lse_i = m_i + ln L_i.
+// Row pass: one wave per block of 16 queries, kPrefillWaves consecutive query blocks per
+// workgroup.  The workgroup sweeps the key tiles up to its last diagonal; every key tile is
+// fetched and widened to fp64 once, by all 256 threads, into the LDS (two buffers, one
+// barrier per tile) in the order the matrix instruction wants its operand, and each wave
+// whose diagonal is not yet passed multiplies it with its own queries (kept in registers).
+// A wave keeps the running row maximum m_i and sum L_i = sum_j e^{s_ij - m_i} (fp64) and, if
+// an output is wanted, the flash-style running numerator in fp32, rescaled only in tiles
+// where some row's maximum moved.  Leaves lse_i = m_i + ln L_i.
+// LDS layout of a tile: lane (g, c) reads its operand values s = 2 i, 2 i + 1 (key row c,
+// element g D/4 + s) as one 16-byte piece at index (4 i + g) 16 + c: conflict-free.
 // -------------------------------------------------------------------------------------
 template <typename T, int D>
 __global__ __launch_bounds__(64 * kPrefillWaves) void prefill_rowpass_kernel(
@@ -165,14 +169,19 @@ __global__ __launch_bounds__(64 * kPrefillWaves) void prefill_rowpass_kernel(
 {
   constexpr int CH = D / 4, DB = D / 16;
   constexpr bool kHalf = sizeof(T) == 2;
+  constexpr int EPT = 16 * D / (64 * kPrefillWaves);      // tile elements widened per thread
+  static_assert(EPT % 2 == 0 && CH % EPT == 0, "a thread's elements stay within one lane group");
+  __shared__ double2 s_k[2][16 * D / 2];
   const int nblk = (P + 15) / 16;
   const int ngrp = (nblk + kPrefillWaves - 1) / kPrefillWaves;
   const PrefillBlock pb = prefill_block(blockIdx.x, ngrp);
+  if (pb.u >= U) return;                                  // uniform over the workgroup
   const int grp = ngrp - 1 - pb.grp;                      // long rows first
   const size_t u = pb.u;
   const int l = threadIdx.x % 64, g = l / 16, c = l % 16;
   const int it = grp * kPrefillWaves + (int)(threadIdx.x / 64);
-  if (it >= nblk || pb.u >= U) return;                    // wave-uniform; the waves share nothing
+  const bool active = it < nblk;                          // wave-uniform
+  const int it_last = (grp + 1) * kPrefillWaves - 1 < nblk - 1 ? (grp + 1) * kPrefillWaves - 1 : nblk - 1;
   const int qi = it * 16 + c;
   const int qrow = qi < P ? qi : P - 1;
   const T *Qu = Q + u * (size_t)P * D, *Ku = K + u * (size_t)P * D, *Vu = V + u * (size_t)P * D;
@@ -190,18 +199,46 @@ __global__ __launch_bounds__(64 * kPrefillWaves) void prefill_rowpass_kernel(
 #pragma unroll
   for (int b = 0; b < DB; ++b) O[b] = v4f{0.f, 0.f, 0.f, 0.f};
 
-  Chunk<T, D> kraw;
-  kraw.load(Ku + (size_t)(c < P ? c : P - 1) * D, g);
-  for (int jt = 0; jt <= it; ++jt) {
+  // this thread's share of a key tile: EPT consecutive elements of row wc
+  const int wc = threadIdx.x % 16, we = EPT * (int)(threadIdx.x / 16);
+  const int wg = we / CH, wi = (we % CH) / 2;             // lane group and first piece of those elements
+  T raw[EPT];
+  auto fetch = [&](int jt) {
+    const int kr = jt * 16 + wc;
+    const T *src = Ku + (size_t)(kr < P ? kr : P - 1) * D + we;
+    if constexpr (EPT * sizeof(T) == 32) {
+      reinterpret_cast<uint4 *>(raw)[0] = reinterpret_cast<const uint4 *>(src)[0];
+      reinterpret_cast<uint4 *>(raw)[1] = reinterpret_cast<const uint4 *>(src)[1];
+    } else if constexpr (EPT * sizeof(T) == 16) {
+      reinterpret_cast<uint4 *>(raw)[0] = reinterpret_cast<const uint4 *>(src)[0];
+    } else {
+      reinterpret_cast<uint2 *>(raw)[0] = reinterpret_cast<const uint2 *>(src)[0];
+    }
+  };
+  fetch(0);
+  for (int jt = 0; jt <= it_last; ++jt) {
     const int j0 = jt * 16;
+    double2 *buf = s_k[jt & 1];
+#pragma unroll
+    for (int p = 0; p < EPT / 2; ++p)
+      buf[((wi + p) * 4 + wg) * 16 + wc] =
+          double2{(double)Store<T>::to_float(raw[2 * p]), (double)Store<T>::to_float(raw[2 * p + 1])};
+    fetch(jt < it_last ? jt + 1 : jt);
     VTile<D> vt;
     if constexpr (kHalf) {
       if (out != nullptr) vt.load(reinterpret_cast<const __half *>(Vu), P, j0, g, c);
     }
-    const v4d acc = tile_kq<T, D>(kraw, qd);
-    {
-      const int kr = (jt < it ? j0 + 16 : j0) + c;
-      kraw.load(Ku + (size_t)(kr < P ? kr : P - 1) * D, g);
+    // tile jt is complete, and nobody still reads the buffer that tile jt + 1 will go into
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+    if (!active || jt > it) continue;                     // wave-uniform
+    v4d acc = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+    for (int i = 0; i < CH / 2; ++i) {
+      const double2 kk = buf[(i * 4 + g) * 16 + c];
+      acc = __builtin_amdgcn_mfma_f64_16x16x4f64(kk.x, qd[2 * i], acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f64_16x16x4f64(kk.y, qd[2 * i + 1], acc, 0, 0, 0);
     }
     double s[4], tmax = -__builtin_inf();
 #pragma unroll
@@ -239,7 +276,7 @@ __global__ __launch_bounds__(64 * kPrefillWaves) void prefill_rowpass_kernel(
   }
   L += __shfl_xor(L, 16);
   L += __shfl_xor(L, 32);
-  if (qi < P) {
+  if (active && qi < P) {
     if (g == 0) lse[u * (size_t)P + qi] = m_run + log(L);
     if (out != nullptr) store_out<D>(out + (u * (size_t)P + qi) * D, g, O, (float)(1.0 / L));
   }
