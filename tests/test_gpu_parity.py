@@ -236,11 +236,21 @@ def test_checkpoint_restore_continues_bit_identically():
         assert torch.equal(a[2][n], b[2][n]), n
 
 
-@pytest.mark.parametrize("kind", ["streaming", "general"])
+def _kind_workload(name, kind, steps):
+    """The decode path a small workload takes: one wave per unit, a unit's rows split over
+    several waves (enough slots for that), or the any-shape kernels (rank above 16)."""
+    if kind == "streaming":
+        return small(name, steps=steps)
+    if kind == "split":
+        return small(name + "-split", steps=steps, n_heavy=35, n_recent=35, prompt=90)
+    return small(name + "-general", steps=steps, rank=20)
+
+
+@pytest.mark.parametrize("kind", ["streaming", "split", "general"])
 def test_step_equals_its_two_halves(kind):
     """lessdec_step is lessdec_step_features followed by lessdec_step_attend."""
     import torch
-    w = small("halves", steps=20) if kind == "streaming" else small("halves-general", steps=20, rank=20)
+    w = _kind_workload("halves", kind, 20)
     inp = wl.all_inputs(w)
     res = hz.gpu_run(w, {k: (v if k in "QKV" else v[:0]) for k, v in inp.items()})      # prompt phase only
     gpu = res["gpu"]
@@ -266,13 +276,13 @@ def test_step_equals_its_two_halves(kind):
         assert torch.equal(got[0][2][n], got[1][2][n]), n
 
 
-@pytest.mark.parametrize("kind", ["streaming", "general"])
+@pytest.mark.parametrize("kind", ["streaming", "split", "general"])
 def test_steps_replayed_from_a_hip_graph_match_eager_steps(kind):
     """The step reads and advances its counters on the device and clears nothing with a memset,
     so one captured step can be replayed for a whole sequence.  Every replay is checked against
     the eager run, with eager work and synchronisation between replays."""
     import torch
-    w = small("graph", steps=12) if kind == "streaming" else small("graph-general", steps=12, rank=20)
+    w = _kind_workload("graph", kind, 12)
     inp = wl.all_inputs(w)
     res = hz.gpu_run(w, {k: (v if k in "QKV" else v[:0]) for k, v in inp.items()})      # prompt phase only
     gpu = res["gpu"]
