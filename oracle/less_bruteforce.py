@@ -33,9 +33,14 @@ def psi(k, Wk1, Wk2, Wk3):
 
 
 class BruteForceUnit:
-    def __init__(self, head_dim, n_heavy, n_recent, W, sparse_denominator=False, policy="h2o"):
+    def __init__(self, head_dim, n_heavy, n_recent, W, sparse_denominator=False, policy="h2o",
+                 q_per_kv=1):
+        """q_per_kv = G > 1: the unit has G query heads sharing keys, values, cache and state;
+        then W["Wq1"], W["Wq2"] carry a leading axis G, step() takes q [G,D] and prefill() Q
+        [G,P,D], and outputs have the same leading axis."""
         assert policy in ("h2o", "lambda")
         self.policy = policy
+        self.G = q_per_kv
         self.D, self.Nh, self.Nr = head_dim, n_heavy, n_recent
         self.W = {k: np.asarray(v, dtype=np.float64) for k, v in W.items()}
         self.sparse_denominator = sparse_denominator
@@ -46,7 +51,7 @@ class BruteForceUnit:
 
     # Eq. 6: the state is the sum over everything discarded so far
     def state(self):
-        R = self.W["Wq2"].shape[1]
+        R = self.W["Wk3"].shape[0]
         H = np.zeros((R, self.D)); z = np.zeros(R)
         for p in self.discarded:
             g = psi(self.keys[p], self.W["Wk1"], self.W["Wk2"], self.W["Wk3"])
@@ -55,13 +60,17 @@ class BruteForceUnit:
 
     def prefill(self, Q, K, V):
         Q, K, V = (np.asarray(a, dtype=np.float64) for a in (Q, K, V))
-        P = Q.shape[0]
-        S = Q @ K.T / np.sqrt(self.D)
-        S[np.triu_indices(P, 1)] = -np.inf
-        A = np.exp(S - S.max(axis=1, keepdims=True))
-        A /= A.sum(axis=1, keepdims=True)
+        P = K.shape[0]
+        Qs = Q[None] if self.G == 1 else Q
+        col = np.zeros(P); outs = []
+        for Qg in Qs:                                           # every query head of the unit
+            S = Qg @ K.T / np.sqrt(self.D)
+            S[np.triu_indices(P, 1)] = -np.inf
+            A = np.exp(S - S.max(axis=1, keepdims=True))
+            A /= A.sum(axis=1, keepdims=True)
+            col += A.sum(axis=0)                                # attention mass from all heads
+            outs.append(A @ V)
         self.keys = [K[i] for i in range(P)]; self.values = [V[i] for i in range(P)]
-        col = A.sum(axis=0)
         C = self.Nh + self.Nr
         if P <= C:
             self.alive = set(range(P))
@@ -76,23 +85,28 @@ class BruteForceUnit:
             self.alive = recent | heavy
             self.discarded = sorted(set(rest) - heavy)
         self.score = {p: col[p] for p in self.alive}
-        return A @ V
+        return outs[0] if self.G == 1 else np.stack(outs)
 
     def step(self, q, k, v):
         q, k, v = (np.asarray(a, dtype=np.float64) for a in (q, k, v))
         n = len(self.keys)
         H, z = self.state()
-        f = phi(q, self.W["Wq1"], self.W["Wq2"])
         self.keys.append(k); self.values.append(v)
         members = sorted(self.alive) + [n]                      # K', V' of Eq. 3
-        w = {p: np.exp(q @ self.keys[p] / np.sqrt(self.D)) for p in members}
-        num = f @ H + sum(w[p] * self.values[p] for p in members)
-        den_sparse = sum(w[p] for p in members)
-        den = f @ z + den_sparse
-        out = num / den
-        d = den_sparse if self.sparse_denominator else den
-        for p in members:
-            self.score[p] = self.score.get(p, 0.0) + w[p] / d
+        outs = []
+        for g in range(self.G):                                 # every query head of the unit
+            qg = q if self.G == 1 else q[g]
+            Wq1, Wq2 = (self.W["Wq1"], self.W["Wq2"]) if self.G == 1 else (self.W["Wq1"][g], self.W["Wq2"][g])
+            f = phi(qg, Wq1, Wq2)
+            w = {p: np.exp(qg @ self.keys[p] / np.sqrt(self.D)) for p in members}
+            num = f @ H + sum(w[p] * self.values[p] for p in members)
+            den_sparse = sum(w[p] for p in members)
+            den = f @ z + den_sparse
+            outs.append(num / den)
+            d = den_sparse if self.sparse_denominator else den
+            for p in members:
+                self.score[p] = self.score.get(p, 0.0) + w[p] / d
+        out = outs[0] if self.G == 1 else np.stack(outs)
         self.alive.add(n)
         evicted = -1
         if len(self.alive) > self.Nh + self.Nr:

@@ -33,6 +33,12 @@
  *                                        kept first tokens, 4 in the paper)
  *   - in-place replacement ............. Sec. 3.2, "Efficient Generation"
  *   - prompt phase ..................... regular attention (remark after Eq. 3)
+ *   several query heads per KV head ..... multi-query / grouped-query attention (Sec. 3.2,
+ *                                        "Inexpensive Training"): the G query heads that
+ *                                        share a key/value head share its sparse cache and
+ *                                        its state H, z (psi acts on keys), each has its own
+ *                                        phi and its own Eq. 3, and H2O accumulates the
+ *                                        attention probabilities of all of them per token
  *   Readings where the paper is silent (listed in the design notes as well):
  *     which denominator the accumulated probabilities use (flag bit 0),
  *     a new token's own probability starts its score, recency is decided by
@@ -61,8 +67,10 @@
 typedef struct less_oracle_state {
   int32_t U, heads, D, n_heavy, n_recent, R, Rp;
   uint32_t flags;
+  int32_t G;                                     /* query heads per unit (KV head); >= 1   */
   const int32_t *head;                           /* [U] head index of each unit            */
-  const double *Wq1, *Wq2, *Wk1, *Wk2, *Wk3;     /* [heads,D,Rp] [heads,Rp,R] .. [heads,R,R] */
+  const double *Wq1, *Wq2;                       /* phi, per query head: [heads*G,D,Rp] [heads*G,Rp,R] */
+  const double *Wk1, *Wk2, *Wk3;                 /* psi, per KV head: [heads,D,Rp] [heads,Rp,R] [heads,R,R] */
   double *Kc, *Vc;                               /* [U,C,D]                                */
   double *acc;                                   /* [U,C]                                  */
   int64_t *pos;                                  /* [U,C], -1 = empty                      */
@@ -127,7 +135,7 @@ void less_oracle_psi(const double *k, const double *W1, const double *W2, const 
 
 /* ---- per-unit views -------------------------------------------------------- */
 typedef struct {
-  int D, C, Nh, Nr, R, Rp;
+  int D, C, Nh, Nr, R, Rp, G;
   uint32_t flags;
   const double *Wq1, *Wq2, *Wk1, *Wk2, *Wk3;
   double *Kc, *Vc, *acc, *H, *z;
@@ -139,9 +147,9 @@ static unit_view view_of(const less_oracle_state *S, int u)
   unit_view v;
   int h = S->head[u];
   v.D = S->D; v.Nh = S->n_heavy; v.Nr = S->n_recent; v.C = v.Nh + v.Nr;
-  v.R = S->R; v.Rp = S->Rp; v.flags = S->flags;
-  v.Wq1 = S->Wq1 + (size_t)h * v.D * v.Rp;
-  v.Wq2 = S->Wq2 + (size_t)h * v.Rp * v.R;
+  v.R = S->R; v.Rp = S->Rp; v.flags = S->flags; v.G = S->G < 1 ? 1 : S->G;
+  v.Wq1 = S->Wq1 + (size_t)h * v.G * v.D * v.Rp;          /* query head h G + g follows at g */
+  v.Wq2 = S->Wq2 + (size_t)h * v.G * v.Rp * v.R;
   v.Wk1 = S->Wk1 + (size_t)h * v.D * v.Rp;
   v.Wk2 = S->Wk2 + (size_t)h * v.Rp * v.R;
   v.Wk3 = S->Wk3 + (size_t)h * v.R * v.R;
@@ -182,7 +190,7 @@ static void fold_into_state(unit_view *s, const double *k, const double *v)
  *   force_pos  >= 0 : evict the cached token with this original position
  *                     instead of the policy's own choice (used by the parity
  *                     protocol after an exempt near-tie); < 0: policy decides.
- *   out        [D]  : a-hat_t (Eq. 3)
+ *   q, out   [G,D]  : the unit's G query heads and their a-hat_t (Eq. 3)
  *   evicted    [1]  : original position of the pair folded into H, z; -1 none
  *   dec        [4]  : smallest and second smallest candidate (score, position);
  *                     position -1 where there is no such candidate.  Under
@@ -195,68 +203,81 @@ static int step_unit(unit_view *s, const double *q, const double *k, const doubl
                      int64_t force_pos, double *out, int64_t *evicted, double *dec,
                      double *share)
 {
-  const int D = s->D, C = s->C, R = s->R;
+  const int D = s->D, C = s->C, R = s->R, G = s->G;
   const int64_t n = *s->n;
   double f[64];
   double *sc = (double *)malloc(sizeof(double) * (size_t)(C + 1));
   double *e = (double *)malloc(sizeof(double) * (size_t)(C + 1));
+  double *inc = (double *)calloc((size_t)(C + 1), sizeof(double));   /* this step's probabilities per pair */
   const double sqrtD = sqrt((double)D);
   int rc = 0;
-
-  less_oracle_phi(q, s->Wq1, s->Wq2, D, s->Rp, R, f);                 /* Eq. 1 */
-
-  /* scores against the cached keys and the appended key (K' of Eq. 3) */
   int live = 0;
-  for (int j = 0; j < C; ++j) {
-    if (s->pos[j] < 0) { sc[j] = -INFINITY; continue; }
-    double a = 0.0;
-    for (int d = 0; d < D; ++d) a += q[d] * s->Kc[(size_t)j * D + d];
-    sc[j] = a / sqrtD;
-    ++live;
-  }
-  {
-    double a = 0.0;
-    for (int d = 0; d < D; ++d) a += q[d] * k[d];
-    sc[C] = a / sqrtD;
-  }
+  for (int j = 0; j < C; ++j) if (s->pos[j] >= 0) ++live;
+  double share_sum = 0.0;
 
-  /* phi(q) z^T and the common shift m* = max(scores, ln(phi(q) z^T)) */
-  double fz = 0.0;
-  for (int r = 0; r < R; ++r) fz += f[r] * s->z[r];
-  double mstar = sc[C];
-  for (int j = 0; j < C; ++j) if (s->pos[j] >= 0 && sc[j] > mstar) mstar = sc[j];
-  double lfz = (fz > 0.0) ? log(fz) : -INFINITY;
-  if (lfz > mstar) mstar = lfz;
+  /* every query head of the unit attends over the same cache and state with its own phi */
+  for (int g = 0; g < G; ++g) {
+    const double *qg = q + (size_t)g * D;
+    double *og = out + (size_t)g * D;
+    less_oracle_phi(qg, s->Wq1 + (size_t)g * D * s->Rp, s->Wq2 + (size_t)g * s->Rp * R, D, s->Rp, R, f);   /* Eq. 1 */
 
-  /* Eq. 3, numerator and denominator both multiplied by e^{-m*} */
-  double wl = (fz > 0.0) ? exp(lfz - mstar) : 0.0;       /* phi(q) z^T e^{-m*} */
-  double den = wl;
-  for (int d = 0; d < D; ++d) out[d] = 0.0;
-  if (fz > 0.0) {
-    double sh = exp(-mstar);
-    for (int d = 0; d < D; ++d) {
+    /* scores against the cached keys and the appended key (K' of Eq. 3) */
+    for (int j = 0; j < C; ++j) {
+      if (s->pos[j] < 0) { sc[j] = -INFINITY; continue; }
       double a = 0.0;
-      for (int r = 0; r < R; ++r) a += f[r] * s->H[(size_t)r * D + d];
-      out[d] = a * sh;                                   /* phi(q) H e^{-m*} */
+      for (int d = 0; d < D; ++d) a += qg[d] * s->Kc[(size_t)j * D + d];
+      sc[j] = a / sqrtD;
     }
+    {
+      double a = 0.0;
+      for (int d = 0; d < D; ++d) a += qg[d] * k[d];
+      sc[C] = a / sqrtD;
+    }
+
+    /* phi(q) z^T and the common shift m* = max(scores, ln(phi(q) z^T)) */
+    double fz = 0.0;
+    for (int r = 0; r < R; ++r) fz += f[r] * s->z[r];
+    double mstar = sc[C];
+    for (int j = 0; j < C; ++j) if (s->pos[j] >= 0 && sc[j] > mstar) mstar = sc[j];
+    double lfz = (fz > 0.0) ? log(fz) : -INFINITY;
+    if (lfz > mstar) mstar = lfz;
+
+    /* Eq. 3, numerator and denominator both multiplied by e^{-m*} */
+    double wl = (fz > 0.0) ? exp(lfz - mstar) : 0.0;       /* phi(q) z^T e^{-m*} */
+    double den = wl;
+    for (int d = 0; d < D; ++d) og[d] = 0.0;
+    if (fz > 0.0) {
+      double sh = exp(-mstar);
+      for (int d = 0; d < D; ++d) {
+        double a = 0.0;
+        for (int r = 0; r < R; ++r) a += f[r] * s->H[(size_t)r * D + d];
+        og[d] = a * sh;                                    /* phi(q) H e^{-m*} */
+      }
+    }
+    for (int j = 0; j < C; ++j) {
+      if (s->pos[j] < 0) { e[j] = 0.0; continue; }
+      e[j] = exp(sc[j] - mstar);
+      den += e[j];
+      for (int d = 0; d < D; ++d) og[d] += e[j] * s->Vc[(size_t)j * D + d];
+    }
+    e[C] = exp(sc[C] - mstar);
+    den += e[C];
+    for (int d = 0; d < D; ++d) og[d] += e[C] * v[d];
+    for (int d = 0; d < D; ++d) og[d] /= den;
+    share_sum += wl / den;
+
+    /* H2O: this head's attention probabilities, added up over the heads of the unit */
+    double dacc = (s->flags & LESS_FLAG_SPARSE_DENOM) ? (den - wl) : den;
+    for (int j = 0; j < C; ++j)
+      if (s->pos[j] >= 0) inc[j] += e[j] / dacc;
+    inc[C] += e[C] / dacc;
   }
-  for (int j = 0; j < C; ++j) {
-    if (s->pos[j] < 0) { e[j] = 0.0; continue; }
-    e[j] = exp(sc[j] - mstar);
-    den += e[j];
-    for (int d = 0; d < D; ++d) out[d] += e[j] * s->Vc[(size_t)j * D + d];
-  }
-  e[C] = exp(sc[C] - mstar);
-  den += e[C];
-  for (int d = 0; d < D; ++d) out[d] += e[C] * v[d];
-  for (int d = 0; d < D; ++d) out[d] /= den;
-  if (share) *share = wl / den;
+  if (share) *share = share_sum / G;
 
   /* H2O: accumulate this step's attention probabilities per cached token */
-  double dacc = (s->flags & LESS_FLAG_SPARSE_DENOM) ? (den - wl) : den;
   for (int j = 0; j < C; ++j)
-    if (s->pos[j] >= 0) s->acc[j] += e[j] / dacc;
-  double acc_new = e[C] / dacc;
+    if (s->pos[j] >= 0) s->acc[j] += inc[j];
+  double acc_new = inc[C];
 
   /* cache update: append, and if over capacity evict one pair into H, z */
   dec[0] = dec[2] = INFINITY; dec[1] = dec[3] = -1.0;
@@ -308,7 +329,7 @@ static int step_unit(unit_view *s, const double *q, const double *k, const doubl
     }
   }
   *s->n = n + 1;
-  free(sc); free(e);
+  free(sc); free(e); free(inc);
   return rc;
 }
 
@@ -345,22 +366,27 @@ static void prefill_unit(unit_view *s, const double *Q, const double *K, const d
   reset_unit(s);
   double *colsum = (double *)calloc((size_t)(P > 0 ? P : 1), sizeof(double));
   double *row = (double *)malloc(sizeof(double) * (size_t)(P > 0 ? P : 1));
-  for (int64_t i = 0; i < P; ++i) {
-    double m = -INFINITY;
-    for (int64_t j = 0; j <= i; ++j) {
-      double a = 0.0;
-      for (int d = 0; d < D; ++d) a += Q[i * D + d] * K[j * D + d];
-      row[j] = a / sqrtD;
-      if (row[j] > m) m = row[j];
-    }
-    double L = 0.0;
-    for (int64_t j = 0; j <= i; ++j) { row[j] = exp(row[j] - m); L += row[j]; }
-    for (int64_t j = 0; j <= i; ++j) { row[j] /= L; colsum[j] += row[j]; }
-    if (out) {
-      for (int d = 0; d < D; ++d) {
+  /* Q and out are [G,P,D]: every query head of the unit attends over the same keys and
+     values, and a token's score is the attention mass it receives from all of them */
+  for (int g = 0; g < s->G; ++g) {
+    const double *Qg = Q + (size_t)g * P * D;
+    for (int64_t i = 0; i < P; ++i) {
+      double m = -INFINITY;
+      for (int64_t j = 0; j <= i; ++j) {
         double a = 0.0;
-        for (int64_t j = 0; j <= i; ++j) a += row[j] * V[j * D + d];
-        out[i * D + d] = a;
+        for (int d = 0; d < D; ++d) a += Qg[i * D + d] * K[j * D + d];
+        row[j] = a / sqrtD;
+        if (row[j] > m) m = row[j];
+      }
+      double L = 0.0;
+      for (int64_t j = 0; j <= i; ++j) { row[j] = exp(row[j] - m); L += row[j]; }
+      for (int64_t j = 0; j <= i; ++j) { row[j] /= L; colsum[j] += row[j]; }
+      if (out) {
+        for (int d = 0; d < D; ++d) {
+          double a = 0.0;
+          for (int64_t j = 0; j <= i; ++j) a += row[j] * V[j * D + d];
+          out[((size_t)g * P + i) * D + d] = a;
+        }
       }
     }
   }
@@ -407,19 +433,19 @@ void less_oracle_reset(less_oracle_state *S)
   for (int u = 0; u < S->U; ++u) { unit_view v = view_of(S, u); reset_unit(&v); }
 }
 
-/* q,k,v [U,D]; force [U] or NULL; out [U,D]; evicted [U]; dec [U,4]; share [U] or NULL.
+/* q [U,G,D]; k,v [U,D]; force [U] or NULL; out [U,G,D]; evicted [U]; dec [U,4]; share [U] or NULL.
    returns the number of units whose forced position was not a candidate. */
 int less_oracle_step(less_oracle_state *S, const double *q, const double *k, const double *v,
                      const int64_t *force, double *out, int64_t *evicted, double *dec,
                      double *share)
 {
   int bad = 0;
-  const int D = S->D;
+  const int D = S->D, G = S->G < 1 ? 1 : S->G;
 #pragma omp parallel for schedule(static) reduction(+ : bad)
   for (int u = 0; u < S->U; ++u) {
     unit_view s = view_of(S, u);
-    int rc = step_unit(&s, q + (size_t)u * D, k + (size_t)u * D, v + (size_t)u * D,
-                       force ? force[u] : -1, out + (size_t)u * D, evicted + u,
+    int rc = step_unit(&s, q + (size_t)u * G * D, k + (size_t)u * D, v + (size_t)u * D,
+                       force ? force[u] : -1, out + (size_t)u * G * D, evicted + u,
                        dec + (size_t)u * 4, share ? share + u : NULL);
     if (rc) ++bad;
   }
@@ -434,35 +460,39 @@ int less_oracle_step(less_oracle_state *S, const double *q, const double *k, con
 static void prefill_unit_stepwise(unit_view *s, const double *Q, const double *K, const double *V,
                                   int64_t P, double *out)
 {
-  double *o = (double *)malloc(sizeof(double) * (size_t)s->D);
+  const int D = s->D, G = s->G;
+  double *o = (double *)malloc(sizeof(double) * (size_t)G * D);
+  double *qt = (double *)malloc(sizeof(double) * (size_t)G * D);      /* token t's G queries */
   double dec[4];
   int64_t ev;
   reset_unit(s);
   for (int64_t t = 0; t < P; ++t) {
-    step_unit(s, Q + t * s->D, K + t * s->D, V + t * s->D, -1, o, &ev, dec, NULL);
-    if (out) memcpy(out + t * s->D, o, sizeof(double) * (size_t)s->D);
+    for (int g = 0; g < G; ++g) memcpy(qt + (size_t)g * D, Q + ((size_t)g * P + t) * D, sizeof(double) * (size_t)D);
+    step_unit(s, qt, K + t * D, V + t * D, -1, o, &ev, dec, NULL);
+    if (out)
+      for (int g = 0; g < G; ++g) memcpy(out + ((size_t)g * P + t) * D, o + (size_t)g * D, sizeof(double) * (size_t)D);
   }
-  free(o);
+  free(o); free(qt);
 }
 
-/* Q,K,V [U,P,D]; out [U,P,D] or NULL; colsum [U,P] or NULL; kept [U,P] or NULL; dec [U,4]
+/* Q [U,G,P,D]; K,V [U,P,D]; out [U,G,P,D] or NULL; colsum [U,P] or NULL; kept [U,P] or NULL; dec [U,4]
    (colsum, kept and dec are left untouched in the stepwise setting) */
 void less_oracle_prefill(less_oracle_state *S, const double *Q, const double *K, const double *V,
                          int64_t P, double *out, double *colsum, int8_t *kept, double *dec)
 {
-  const size_t PD = (size_t)P * S->D;
+  const size_t PD = (size_t)P * S->D, GPD = PD * (size_t)(S->G < 1 ? 1 : S->G);
   if (S->flags & LESS_FLAG_PROMPT_STEPWISE) {
 #pragma omp parallel for schedule(dynamic, 1)
     for (int u = 0; u < S->U; ++u) {
       unit_view s = view_of(S, u);
-      prefill_unit_stepwise(&s, Q + u * PD, K + u * PD, V + u * PD, P, out ? out + u * PD : NULL);
+      prefill_unit_stepwise(&s, Q + u * GPD, K + u * PD, V + u * PD, P, out ? out + u * GPD : NULL);
     }
     return;
   }
 #pragma omp parallel for schedule(dynamic, 1)
   for (int u = 0; u < S->U; ++u) {
     unit_view s = view_of(S, u);
-    prefill_unit(&s, Q + u * PD, K + u * PD, V + u * PD, P, out ? out + u * PD : NULL,
+    prefill_unit(&s, Q + u * GPD, K + u * PD, V + u * PD, P, out ? out + u * GPD : NULL,
                  colsum ? colsum + (size_t)u * P : NULL, kept ? kept + (size_t)u * P : NULL,
                  dec + (size_t)u * 4);
   }

@@ -40,7 +40,7 @@ class _State(C.Structure):
     _fields_ = [
         ("U", C.c_int32), ("heads", C.c_int32), ("D", C.c_int32),
         ("n_heavy", C.c_int32), ("n_recent", C.c_int32), ("R", C.c_int32), ("Rp", C.c_int32),
-        ("flags", C.c_uint32),
+        ("flags", C.c_uint32), ("G", C.c_int32),
         ("head", C.c_void_p),
         ("Wq1", C.c_void_p), ("Wq2", C.c_void_p),
         ("Wk1", C.c_void_p), ("Wk2", C.c_void_p), ("Wk3", C.c_void_p),
@@ -117,13 +117,19 @@ def psi(k, W1, W2, W3):
 class OracleState:
     """State of U independent (batch, head) units, all fp64 on the host.
 
-    weights: dict Wq1 [Hh,D,R'], Wq2 [Hh,R',R], Wk1, Wk2, Wk3 [Hh,R,R] (any float dtype;
-    the values are taken exactly and widened to fp64).
-    head_of_unit: head index of every unit (default u % heads).
+    weights: dict Wq1 [Hh*G,D,R'], Wq2 [Hh*G,R',R] (per query head, head h's G query heads in
+    a row), Wk1 [Hh,D,R'], Wk2 [Hh,R',R], Wk3 [Hh,R,R] (any float dtype; the values are taken
+    exactly and widened to fp64).
+    head_of_unit: (KV) head index of every unit (default u % heads).
+    q_per_kv: G, query heads that share a unit's keys, values, cache and state (multi-query /
+    grouped-query attention); with G > 1 queries and outputs carry an extra axis: q [U,G,D],
+    Q [U,G,P,D].
     """
 
     def __init__(self, units, heads, head_dim, n_heavy, n_recent, rank, hidden, weights,
-                 flags=0, head_of_unit=None):
+                 flags=0, head_of_unit=None, q_per_kv=1):
+        self.G = int(q_per_kv)
+        assert self.G >= 1
         self.U, self.heads, self.D = int(units), int(heads), int(head_dim)
         self.Nh, self.Nr = int(n_heavy), int(n_recent)
         self.C = self.Nh + self.Nr
@@ -135,8 +141,8 @@ class OracleState:
             dtype=np.int32)
         assert self.head.shape == (self.U,) and self.head.max(initial=0) < self.heads
         self.W = {k: _f64(weights[k]) for k in ("Wq1", "Wq2", "Wk1", "Wk2", "Wk3")}
-        assert self.W["Wq1"].shape == (self.heads, self.D, self.Rp)
-        assert self.W["Wq2"].shape == (self.heads, self.Rp, self.R)
+        assert self.W["Wq1"].shape == (self.heads * self.G, self.D, self.Rp)
+        assert self.W["Wq2"].shape == (self.heads * self.G, self.Rp, self.R)
         assert self.W["Wk1"].shape == (self.heads, self.D, self.Rp)
         assert self.W["Wk2"].shape == (self.heads, self.Rp, self.R)
         assert self.W["Wk3"].shape == (self.heads, self.R, self.R)
@@ -150,6 +156,7 @@ class OracleState:
         s = _State()
         s.U, s.heads, s.D = self.U, self.heads, self.D
         s.n_heavy, s.n_recent, s.R, s.Rp, s.flags = self.Nh, self.Nr, self.R, self.Rp, self.flags
+        s.G = self.G
         s.head = self.head.ctypes.data
         for k in ("Wq1", "Wq2", "Wk1", "Wk2", "Wk3"):
             setattr(s, k, self.W[k].ctypes.data)
@@ -168,8 +175,9 @@ class OracleState:
         force: None or int array [U]; entries >= 0 override the policy's choice.
         """
         q = _f64(q); k = _f64(k); v = _f64(v)
-        assert q.shape == k.shape == v.shape == (self.U, self.D)
-        out = np.empty((self.U, self.D)); ev = np.empty(self.U, dtype=np.int64)
+        qshape = (self.U, self.D) if self.G == 1 else (self.U, self.G, self.D)
+        assert q.shape == qshape and k.shape == v.shape == (self.U, self.D)
+        out = np.empty(qshape); ev = np.empty(self.U, dtype=np.int64)
         dec = np.empty((self.U, 4)); share = np.empty(self.U)
         fo = None if force is None else np.ascontiguousarray(force, dtype=np.int64)
         bad = lib().less_oracle_step(C.byref(self._struct()), _ptr(q), _ptr(k), _ptr(v),
@@ -184,9 +192,10 @@ class OracleState:
         Returns dict(out [U,P,D] or None, colsum [U,P], kept [U,P] bool, dec [U,4]).
         """
         Q = _f64(Q); K = _f64(K); V = _f64(V)
-        assert Q.shape == K.shape == V.shape and Q.shape[0] == self.U and Q.shape[2] == self.D
-        P = Q.shape[1]
-        out = np.empty((self.U, P, self.D)) if want_out else None
+        assert K.shape == V.shape and K.shape[0] == self.U and K.shape[2] == self.D
+        P = K.shape[1]
+        assert Q.shape == (K.shape if self.G == 1 else (self.U, self.G, P, self.D))
+        out = np.empty(Q.shape) if want_out else None
         colsum = np.zeros((self.U, P)); kept = np.ones((self.U, P), dtype=np.int8)
         dec = np.full((self.U, 4), np.inf); dec[:, 1::2] = -1
         lib().less_oracle_prefill(C.byref(self._struct()), _ptr(Q), _ptr(K), _ptr(V), P,

@@ -17,9 +17,9 @@ SRC = (lo._HERE / "less_oracle.c").read_text()
 
 # (name, text in the oracle, what a mistaken author might have written)
 MUTANTS = [
-    ("denominator-without-low-rank-term", "  double den = wl;", "  double den = 0.0;"),
-    ("numerator-without-low-rank-term", "      out[d] = a * sh;", "      out[d] = 0.0 * a * sh;"),
-    ("score-sign", "    sc[j] = a / sqrtD;", "    sc[j] = -a / sqrtD;"),
+    ("denominator-without-low-rank-term", "    double den = wl;", "    double den = 0.0;"),
+    ("numerator-without-low-rank-term", "        og[d] = a * sh;", "        og[d] = 0.0 * a * sh;"),
+    ("score-sign", "      sc[j] = a / sqrtD;", "      sc[j] = -a / sqrtD;"),
     ("score-scale-D-instead-of-sqrt-D", "  const double sqrtD = sqrt((double)D);\n  int rc = 0;",
      "  const double sqrtD = (double)D;\n  int rc = 0;"),
     ("phi-first-matrix-transposed", "    for (int d = 0; d < D; ++d) a += q[d] * W1[(size_t)d * Rp + i];",
@@ -29,9 +29,17 @@ MUTANTS = [
     ("psi-without-absolute-value", "    g[r] = fabs(a);", "    g[r] = a;"),
     ("phi-without-absolute-value", "    f[r] = fabs(less_oracle_gelu(a));", "    f[r] = less_oracle_gelu(a);"),
     ("gelu-argument-scale", "return 0.5 * x * erfc(-x / sqrt(2.0));", "return 0.5 * x * erfc(-x);"),
-    ("new-token-starts-with-zero-score", "  double acc_new = e[C] / dacc;", "  double acc_new = 0.0 * e[C] / dacc;"),
-    ("scores-not-accumulated", "    if (s->pos[j] >= 0) s->acc[j] += e[j] / dacc;",
-     "    if (s->pos[j] >= 0) s->acc[j] = e[j] / dacc;"),
+    ("new-token-starts-with-zero-score", "  double acc_new = inc[C];", "  double acc_new = 0.0 * inc[C];"),
+    ("scores-not-accumulated", "    if (s->pos[j] >= 0) s->acc[j] += inc[j];",
+     "    if (s->pos[j] >= 0) s->acc[j] = inc[j];"),
+    ("only-the-first-query-head-scores", "      if (s->pos[j] >= 0) inc[j] += e[j] / dacc;",
+     "      if (s->pos[j] >= 0 && g == 0) inc[j] += e[j] / dacc;"),
+    ("query-heads-share-the-first-phi",
+     "    less_oracle_phi(qg, s->Wq1 + (size_t)g * D * s->Rp, s->Wq2 + (size_t)g * s->Rp * R, D, s->Rp, R, f);   /* Eq. 1 */",
+     "    less_oracle_phi(qg, s->Wq1, s->Wq2, D, s->Rp, R, f);"),
+    ("prompt-scores-from-the-last-query-head-only",
+     "      for (int64_t j = 0; j <= i; ++j) { row[j] /= L; colsum[j] += row[j]; }",
+     "      for (int64_t j = 0; j <= i; ++j) { row[j] /= L; if (g == s->G - 1) colsum[j] += row[j]; }"),
     ("recent-window-off-by-one", "      else { if (s->pos[j] > n - s->Nr) continue;",
      "      else { if (s->pos[j] >= n - s->Nr) continue;"),
     ("evicts-the-largest-score", "      if (a < bacc || (a == bacc && p < bpos)) {",
@@ -43,15 +51,15 @@ MUTANTS = [
      "    for (int d = 0; d < s->D; ++d) s->H[(size_t)r * s->D + d] += g[r] * v[d];",
      "    for (int d = 0; d < s->D; ++d) s->H[(size_t)r * s->D + d] += g[r] * k[d];"),
     ("state-folded-before-the-output",      # Algorithm 1 uses H_t, z_t from before this step's eviction
-     "  less_oracle_phi(q, s->Wq1, s->Wq2, D, s->Rp, R, f);                 /* Eq. 1 */",
-     "  less_oracle_phi(q, s->Wq1, s->Wq2, D, s->Rp, R, f);\n"
+     "  double share_sum = 0.0;\n",
+     "  double share_sum = 0.0;\n"
      "  if (n >= C && C > 0 && s->Nr > 0) { int jm = 0; for (int j = 1; j < C; ++j) if (s->pos[j] < s->pos[jm]) jm = j;\n"
      "    double gg[64]; less_oracle_psi(s->Kc + (size_t)jm * D, s->Wk1, s->Wk2, s->Wk3, D, s->Rp, R, gg);\n"
      "    for (int r = 0; r < R; ++r) s->z[r] += 1e-3 * gg[r]; }"),
     ("prompt-keeps-the-smallest-column-sums", "  if (a->a < b->a) return -1;\n  if (a->a > b->a) return 1;",
      "  if (a->a < b->a) return 1;\n  if (a->a > b->a) return -1;"),
-    ("prompt-column-sums-unnormalised", "    for (int64_t j = 0; j <= i; ++j) { row[j] /= L; colsum[j] += row[j]; }",
-     "    for (int64_t j = 0; j <= i; ++j) { colsum[j] += row[j]; row[j] /= L; }"),
+    ("prompt-column-sums-unnormalised", "      for (int64_t j = 0; j <= i; ++j) { row[j] /= L; colsum[j] += row[j]; }",
+     "      for (int64_t j = 0; j <= i; ++j) { colsum[j] += row[j]; row[j] /= L; }"),
     ("prompt-recent-window-off-by-one", "    int64_t ncand = P - s->Nr;                            /* positions < P - Nr */",
      "    int64_t ncand = P - s->Nr + 1;"),
     ("prompt-discarded-pairs-not-folded", "      fold_into_state(s, K + j * D, V + j * D);           /* Eq. 6 */",

@@ -298,6 +298,104 @@ def test_stepwise_prompt_is_the_generation_loop(flags):
             np.testing.assert_allclose(r["out"][u], o, rtol=1e-9, atol=1e-12)
 
 
+# ---------------------------------------------------------------- several query heads per KV head
+def make_weights_gqa(rng, heads, G, D, Rp, R):
+    W = make_weights(rng, heads, D, Rp, R)
+    Wq = make_weights(rng, heads * G, D, Rp, R)
+    W["Wq1"], W["Wq2"] = Wq["Wq1"], Wq["Wq2"]
+    return W
+
+
+@pytest.mark.parametrize("G,Nh,Nr,P,T,flags,seed", [
+    (2, 3, 3, 17, 20, 0, 0), (3, 4, 0, 9, 14, 1, 1), (4, 2, 5, 0, 25, 0, 2), (2, 4, 6, 21, 12, 2, 3),
+    (3, 3, 4, 19, 8, 4, 4),
+])
+def test_query_groups_against_set_based_twin(G, Nh, Nr, P, T, flags, seed):
+    """Sec. 3.2: with several query heads per key/value head the sparse policy sees the attention
+    mass of all of them.  Outputs per query head, evictions and state equal the twin's."""
+    rng = np.random.default_rng(300 + seed)
+    U, heads, D, Rp, R = 3, 2, 6, 9, 3
+    W = make_weights_gqa(rng, heads, G, D, Rp, R)
+    st = lo.OracleState(U, heads, D, Nh, Nr, R, Rp, W, flags=flags, q_per_kv=G)
+    Q = rng.standard_normal((U, G, P, D)); K, V = (rng.standard_normal((U, P, D)) for _ in range(2))
+    q = rng.standard_normal((T, U, G, D)); k, v = (rng.standard_normal((T, U, D)) for _ in range(2))
+    def twin_w(u):
+        h = u % heads
+        w = head_w(W, h)
+        w["Wq1"], w["Wq2"] = W["Wq1"][h * G:(h + 1) * G], W["Wq2"][h * G:(h + 1) * G]
+        return w
+    twins = [BruteForceUnit(D, Nh, Nr, twin_w(u), sparse_denominator=bool(flags & 1),
+                            policy="lambda" if flags & 2 else "h2o", q_per_kv=G) for u in range(U)]
+    if P:
+        pre = st.prefill(Q, K, V)
+        for u, tw in enumerate(twins):
+            if flags & 4:                                    # the policy runs through the prompt
+                for t in range(P):
+                    o, _ = tw.step(Q[u, :, t], K[u, t], V[u, t])
+                    np.testing.assert_allclose(pre["out"][u, :, t], o, rtol=1e-9, atol=1e-12)
+            else:
+                np.testing.assert_allclose(pre["out"][u], tw.prefill(Q[u], K[u], V[u]), rtol=1e-10)
+            assert set(st.pos[u][st.pos[u] >= 0]) == tw.alive
+    else:
+        st.reset()
+    for t in range(T):
+        r = st.step(q[t], k[t], v[t])
+        for u, tw in enumerate(twins):
+            o, ev = tw.step(q[t, u], k[t, u], v[t, u])
+            assert r["evicted"][u] == ev, (t, u)
+            np.testing.assert_allclose(r["out"][u], o, rtol=1e-9, atol=1e-12)
+            Hc, zc = tw.state()
+            np.testing.assert_allclose(st.H[u], Hc, rtol=1e-10, atol=1e-13)
+            np.testing.assert_allclose(st.z[u], zc, rtol=1e-10, atol=1e-13)
+            for j in np.flatnonzero(st.pos[u] >= 0):
+                assert st.acc[u, j] == pytest.approx(tw.score[int(st.pos[u, j])], rel=1e-10)
+
+
+def test_identical_query_heads_behave_as_one():
+    """Two query heads with the same query and the same phi see the same probabilities, so
+    every accumulated score is twice the single-head one: same outputs, same evictions,
+    same state as the single-head run."""
+    rng = np.random.default_rng(41)
+    U, heads, D, Rp, R, Nh, Nr, P, T = 2, 2, 6, 8, 3, 3, 3, 15, 20
+    W1 = make_weights(rng, heads, D, Rp, R)
+    W2 = dict(W1); W2["Wq1"] = np.repeat(W1["Wq1"], 2, axis=0); W2["Wq2"] = np.repeat(W1["Wq2"], 2, axis=0)
+    one = lo.OracleState(U, heads, D, Nh, Nr, R, Rp, W1)
+    two = lo.OracleState(U, heads, D, Nh, Nr, R, Rp, W2, q_per_kv=2)
+    Q, K, V = (rng.standard_normal((U, P, D)) for _ in range(3))
+    q, k, v = (rng.standard_normal((T, U, D)) for _ in range(3))
+    p1 = one.prefill(Q, K, V); p2 = two.prefill(np.stack([Q, Q], axis=1), K, V)
+    assert (p1["kept"] == p2["kept"]).all()
+    np.testing.assert_array_equal(p2["out"][:, 0], p1["out"]); np.testing.assert_array_equal(p2["out"][:, 1], p1["out"])
+    for t in range(T):
+        r1 = one.step(q[t], k[t], v[t]); r2 = two.step(np.stack([q[t], q[t]], axis=1), k[t], v[t])
+        assert (r1["evicted"] == r2["evicted"]).all()
+        np.testing.assert_array_equal(r2["out"][:, 0], r1["out"]); np.testing.assert_array_equal(r2["out"][:, 1], r1["out"])
+        np.testing.assert_allclose(two.acc, 2.0 * one.acc, rtol=1e-14)
+        np.testing.assert_array_equal(two.H, one.H); np.testing.assert_array_equal(two.z, one.z)
+
+
+def test_query_groups_with_unbounded_budget_are_full_attention_per_head():
+    rng = np.random.default_rng(42)
+    U, heads, G, D, Rp, R, P, T = 2, 1, 3, 8, 8, 2, 9, 5
+    W = make_weights_gqa(rng, heads, G, D, Rp, R)
+    st = lo.OracleState(U, heads, D, 40, 40, R, Rp, W, q_per_kv=G)
+    Q = rng.standard_normal((U, G, P, D)); K, V = (rng.standard_normal((U, P, D)) for _ in range(2))
+    q = rng.standard_normal((T, U, G, D)); k, v = (rng.standard_normal((T, U, D)) for _ in range(2))
+    pre = st.prefill(Q, K, V)
+    for u in range(U):
+        for g in range(G):
+            for i in range(P):
+                np.testing.assert_allclose(pre["out"][u, g, i], sdpa_last_row(Q[u, g, i], K[u, :i + 1], V[u, :i + 1]),
+                                           rtol=1e-11)
+    Ks, Vs = K.copy(), V.copy()
+    for t in range(T):
+        r = st.step(q[t], k[t], v[t])
+        Ks = np.concatenate([Ks, k[t][:, None]], axis=1); Vs = np.concatenate([Vs, v[t][:, None]], axis=1)
+        for u in range(U):
+            for g in range(G):
+                np.testing.assert_allclose(r["out"][u, g], sdpa_last_row(q[t, u, g], Ks[u], Vs[u]), rtol=1e-11)
+
+
 def test_policy_invariants_and_convexity():
     rng = np.random.default_rng(11)
     U, heads, D, Rp, R, Nh, Nr, P, T = 4, 2, 8, 16, 4, 4, 4, 30, 40
