@@ -61,6 +61,7 @@ extern "C" {
 #define LESSDEC_MAX_RANK 64
 #define LESSDEC_MAX_CAPACITY 4094
 #define LESSDEC_MAX_HIDDEN 2048
+#define LESSDEC_MAX_Q_PER_KV 128
 
 typedef struct lessdec_desc {
   int32_t batch, heads, head_dim; /* B, Hh, D; D is 64 or 128                              */
@@ -69,6 +70,14 @@ typedef struct lessdec_desc {
   int32_t rank, hidden;           /* R <= 64, R' <= 2048 (Eq. 1, Eq. 2)                    */
   int32_t dtype;                  /* LESSDEC_DTYPE_*                                       */
   uint32_t flags;                 /* LESSDEC_FLAG_*                                        */
+  int32_t q_per_kv;               /* G: query heads per key/value head (multi-query and
+                                     grouped-query attention; Sec. 3.2 extends H2O to the
+                                     scores of all query heads).  0 or 1: one.  With G > 1
+                                     `heads` counts key/value heads; a unit's G query heads
+                                     share its cache and state, each has its own phi, and a
+                                     pair's accumulated score grows by its probability under
+                                     every one of them.  q, out and Wq1, Wq2 then carry the
+                                     extra axis G (see below); C <= 2047                   */
   /* sparse cache K_C, V_C (Sec. 3.1) as slots, replaced in place (Sec. 3.2)               */
   void *k_cache, *v_cache;        /* [B,Hh,C,D] dtype, 16-byte aligned                     */
   double *acc;                    /* [B,Hh,C] accumulated attention probability (H2O)      */
@@ -91,7 +100,8 @@ typedef struct lessdec_desc {
      layer's weight: row i of W?1 holds the D input weights of hidden unit i, i.e. each
      array is the transpose of the matrix of the same name in the equations.  16-byte
      aligned.                                                                              */
-  const void *Wq1, *Wq2;          /* phi: [Hh,R',D], [Hh,R,R']                             */
+  const void *Wq1, *Wq2;          /* phi: [Hh,R',D], [Hh,R,R']; with G > 1 per query head:
+                                     [Hh*G,R',D], [Hh*G,R,R'], head h's G in a row          */
   const void *Wk1, *Wk2, *Wk3;    /* psi: [Hh,R',D], [Hh,R,R'], [Hh,R,R]                   */
   void *workspace;                /* >= lessdec_workspace_bytes(), 256-byte aligned        */
   size_t workspace_bytes;
@@ -127,6 +137,8 @@ int lessdec_state_sync(const lessdec_desc *desc, void *hip_stream);
  * later token), in ascending token order, with acc = column sum; every other prompt pair
  * is folded into H, z (Eq. 6); n_seen = P.  If P <= C every token is kept.
  * With LESSDEC_FLAG_LAMBDA the first n_heavy tokens are kept in place of the heavy hitters.
+ * With q_per_kv = G > 1: Q and out are [B,Hh,G,P,D]; only the LESSDEC_FLAG_PROMPT_STEPWISE
+ * form of the call is available (LESSDEC_EINVAL otherwise).
  * With LESSDEC_FLAG_PROMPT_STEPWISE the call is lessdec_state_reset followed by one
  * lessdec_step per prompt token t with rows Q[.,.,t,.], K[.,.,t,.], V[.,.,t,.] (2 P launches
  * plus row staging; not the fast way through a prompt): out[.,.,t,.] is then Eq. 3's output
@@ -153,6 +165,8 @@ int lessdec_prefill(const lessdec_desc *desc, const void *Q, const void *K, cons
  * from the previous step into H, z happens first, so Eq. 3 always sees the state Algorithm 1
  * prescribes.  With LESSDEC_FLAG_LAMBDA the discarded pair is instead the oldest one that is
  * neither among the first n_heavy tokens of the sequence nor among the n_recent most recent.
+ * With q_per_kv = G > 1: q and out are [B,Hh,G,D] (k, v stay [B,Hh,D]); the step runs on a
+ * plain kernel that folds the discarded pair at once (nothing is left pending).
  */
 int lessdec_step(const lessdec_desc *desc, const void *q, const void *k, const void *v,
                  void *out, int32_t *evicted_pos, void *hip_stream);

@@ -33,7 +33,7 @@ class Desc(C.Structure):
         ("batch", C.c_int32), ("heads", C.c_int32), ("head_dim", C.c_int32),
         ("n_heavy", C.c_int32), ("n_recent", C.c_int32),
         ("rank", C.c_int32), ("hidden", C.c_int32),
-        ("dtype", C.c_int32), ("flags", C.c_uint32),
+        ("dtype", C.c_int32), ("flags", C.c_uint32), ("q_per_kv", C.c_int32),
         ("k_cache", C.c_void_p), ("v_cache", C.c_void_p),
         ("acc", C.c_void_p), ("pos", C.c_void_p), ("psi", C.c_void_p),
         ("H", C.c_void_p), ("z", C.c_void_p), ("n_seen", C.c_void_p),
@@ -150,7 +150,7 @@ class LessDec:
              "pend_slot", "pend_v", "pend_psi")
 
     def __init__(self, batch, heads, head_dim, n_heavy, n_recent, rank, hidden, dtype, weights,
-                 flags=0, max_prompt=0, device="cuda:0"):
+                 flags=0, max_prompt=0, device="cuda:0", q_per_kv=1):
         import torch
         if not torch.cuda.is_available():
             raise LessdecError("no GPU visible: lessdec has no CPU path")
@@ -161,6 +161,7 @@ class LessDec:
         self.B, self.Hh, self.D = batch, heads, head_dim
         self.Nh, self.Nr, self.C = n_heavy, n_recent, n_heavy + n_recent
         self.R, self.Rp = rank, hidden
+        self.G = G = int(q_per_kv)            # query heads per unit; q, out and Wq1, Wq2 carry this axis
         U, Cc, D, R = batch * heads, self.C, head_dim, rank
         dev = self.device
         self.k_cache = torch.zeros((U, Cc, D), dtype=self.tdtype, device=dev)
@@ -175,7 +176,7 @@ class LessDec:
         self.pend_v = torch.zeros((U, D), dtype=self.tdtype, device=dev)
         self.pend_psi = torch.zeros((U, R), dtype=torch.float32, device=dev)
         self.W = {}
-        for name, shape in (("Wq1", (heads, hidden, D)), ("Wq2", (heads, R, hidden)),
+        for name, shape in (("Wq1", (heads * G, hidden, D)), ("Wq2", (heads * G, R, hidden)),
                             ("Wk1", (heads, hidden, D)), ("Wk2", (heads, R, hidden)),
                             ("Wk3", (heads, R, R))):
             w = weights[name]
@@ -187,6 +188,7 @@ class LessDec:
         d.n_heavy, d.n_recent, d.rank, d.hidden = n_heavy, n_recent, rank, hidden
         d.dtype = DTYPE_F16 if self.tdtype == torch.float16 else DTYPE_F32
         d.flags = flags
+        d.q_per_kv = G
         for name in self.STATE:
             setattr(d, name, getattr(self, name).data_ptr())
         for name in self.W:
@@ -207,20 +209,21 @@ class LessDec:
         lessdec_state_sync(self.desc, stream)
 
     def prefill(self, Q, K, V, out=None, stream=None):
-        """Q, K, V: [B*Hh, P, D] (or [B,Hh,P,D]) contiguous device tensors of the storage dtype."""
-        P = Q.shape[-2]
-        for t in (Q, K, V) + ((out,) if out is not None else ()):
-            if t.dtype != self.tdtype or not t.is_contiguous() or t.numel() != self.B * self.Hh * P * self.D:
-                raise LessdecError("prefill: tensors must be contiguous [B,Hh,P,D] of the storage dtype")
+        """K, V: [B*Hh, P, D] (or [B,Hh,P,D]), Q, out: the same with an axis G before P if
+        q_per_kv > 1; contiguous device tensors of the storage dtype."""
+        P = K.shape[-2]
+        for t, g in ((Q, self.G), (K, 1), (V, 1)) + (((out, self.G),) if out is not None else ()):
+            if t.dtype != self.tdtype or not t.is_contiguous() or t.numel() != self.B * self.Hh * g * P * self.D:
+                raise LessdecError("prefill: tensors must be contiguous [B,Hh,(G,)P,D] of the storage dtype")
         if P > self.max_prompt:
             raise LessdecError(f"prefill: P={P} exceeds max_prompt={self.max_prompt} the workspace was sized for")
         lessdec_prefill(self.desc, Q, K, V, P, out, stream)
 
     def step(self, q, k, v, out, evicted_pos=None, stream=None):
         """q, k, v, out: [B*Hh, D] contiguous device tensors; evicted_pos: int32 [B*Hh] or None."""
-        for t in (q, k, v, out):
-            if t.dtype != self.tdtype or not t.is_contiguous() or t.numel() != self.B * self.Hh * self.D:
-                raise LessdecError("step: tensors must be contiguous [B,Hh,D] of the storage dtype")
+        for t, g in ((q, self.G), (k, 1), (v, 1), (out, self.G)):
+            if t.dtype != self.tdtype or not t.is_contiguous() or t.numel() != self.B * self.Hh * g * self.D:
+                raise LessdecError("step: tensors must be contiguous [B,Hh,(G,)D] of the storage dtype")
         if evicted_pos is not None and (evicted_pos.dtype != self.torch.int32 or
                                         evicted_pos.numel() != self.B * self.Hh):
             raise LessdecError("step: evicted_pos must be int32 [B,Hh]")
@@ -228,16 +231,16 @@ class LessDec:
 
     def step_features(self, q, k, stream=None):
         """First half of step(): phi(q), psi(k) of the step into the workspace."""
-        for t in (q, k):
-            if t.dtype != self.tdtype or not t.is_contiguous() or t.numel() != self.B * self.Hh * self.D:
-                raise LessdecError("step_features: tensors must be contiguous [B,Hh,D] of the storage dtype")
+        for t, g in ((q, self.G), (k, 1)):
+            if t.dtype != self.tdtype or not t.is_contiguous() or t.numel() != self.B * self.Hh * g * self.D:
+                raise LessdecError("step_features: tensors must be contiguous [B,Hh,(G,)D] of the storage dtype")
         lessdec_step_features(self.desc, q, k, stream)
 
     def step_attend(self, q, k, v, out, evicted_pos=None, stream=None):
         """Second half of step(), after step_features(q, k) on the same tensors."""
-        for t in (q, k, v, out):
-            if t.dtype != self.tdtype or not t.is_contiguous() or t.numel() != self.B * self.Hh * self.D:
-                raise LessdecError("step_attend: tensors must be contiguous [B,Hh,D] of the storage dtype")
+        for t, g in ((q, self.G), (k, 1), (v, 1), (out, self.G)):
+            if t.dtype != self.tdtype or not t.is_contiguous() or t.numel() != self.B * self.Hh * g * self.D:
+                raise LessdecError("step_attend: tensors must be contiguous [B,Hh,(G,)D] of the storage dtype")
         if evicted_pos is not None and (evicted_pos.dtype != self.torch.int32 or
                                         evicted_pos.numel() != self.B * self.Hh):
             raise LessdecError("step_attend: evicted_pos must be int32 [B,Hh]")

@@ -12,7 +12,7 @@ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
 struct Shape {
-  size_t U, C, D, R, Rp;
+  size_t U, C, D, R, Rp, G;
 };
 
 bool shape_ok(const lessdec_desc *d, Shape *s)
@@ -28,11 +28,14 @@ bool shape_ok(const lessdec_desc *d, Shape *s)
   if (d->dtype != LESSDEC_DTYPE_F32 && d->dtype != LESSDEC_DTYPE_F16) return false;
   if (d->flags & ~(LESSDEC_FLAG_SPARSE_DENOM | LESSDEC_FLAG_LAMBDA | LESSDEC_FLAG_PROMPT_STEPWISE)) return false;
   if ((long)d->batch * d->heads > (1L << 30)) return false;
+  if (d->q_per_kv < 0 || d->q_per_kv > LESSDEC_MAX_Q_PER_KV) return false;
+  if (d->q_per_kv > 1 && C > 2047) return false;
   s->U = (size_t)d->batch * d->heads;
   s->C = (size_t)C;
   s->D = (size_t)d->head_dim;
   s->R = (size_t)d->rank;
   s->Rp = (size_t)d->hidden;
+  s->G = d->q_per_kv > 1 ? (size_t)d->q_per_kv : 1;
   return true;
 }
 
@@ -48,10 +51,10 @@ Workspace carve(const Shape &s, size_t P)
 {
   Workspace w;
   size_t o = 0;
-  w.off_fphi = o; o = align_up(o + s.U * s.R * sizeof(double), 256);
+  w.off_fphi = o; o = align_up(o + s.U * s.G * s.R * sizeof(double), 256);
   w.off_fpsi = o; o = align_up(o + s.U * s.R * sizeof(float), 256);
   w.off_parts = o; o = align_up(o + 2 * (size_t)mlp_nparts((int)s.Rp) * s.U * 16 * sizeof(float), 256);
-  w.off_stage = o; o = align_up(o + (P ? 4 * s.U * s.D * sizeof(float) : 0), 256);
+  w.off_stage = o; o = align_up(o + (P ? 4 * s.U * s.G * s.D * sizeof(float) : 0), 256);
   w.off_lse = o; o = align_up(o + s.U * P * sizeof(double), 256);
   w.off_colsum = o; o = align_up(o + s.U * P * sizeof(double), 256);
   w.off_approx = o; o = align_up(o + s.U * P * sizeof(float), 256);
@@ -136,7 +139,7 @@ int lessdec_step_features(const lessdec_desc *desc, const void *q, const void *k
   hipStream_t st = (hipStream_t)hip_stream;
   const Workspace w = carve(s, 0);
   char *ws = static_cast<char *>(desc->workspace);
-  if (wpu_supported(desc->dtype, desc->head_dim, (int)s.C, desc->hidden, desc->rank)) {
+  if (s.G == 1 && wpu_supported(desc->dtype, desc->head_dim, (int)s.C, desc->hidden, desc->rank)) {
     // matrix-core feature maps up to the layer-2 sums
     MlpPartsArgs fm;
     fm.q = (const __half *)q; fm.k = (const __half *)k;
@@ -148,11 +151,12 @@ int lessdec_step_features(const lessdec_desc *desc, const void *q, const void *k
   }
   // general path: phi(q), psi(k) in fp64
   FeatmapArgs fa;
-  fa.B = desc->batch; fa.Hh = desc->heads; fa.rpu = 1;
+  fa.B = desc->batch; fa.Hh = desc->heads * (int)s.G; fa.rpu = 1;   // q rows [B,Hh,G]: query head h G + g
   fa.D = desc->head_dim; fa.Rp = desc->hidden; fa.R = desc->rank;
   fa.x = q; fa.W1 = desc->Wq1; fa.W2 = desc->Wq2; fa.W3 = nullptr;
   fa.out = reinterpret_cast<double *>(ws + w.off_fphi); fa.out_f64 = 1;
   if (launch_featmap_generic(fa, desc->dtype, st) != hipSuccess) return LESSDEC_EHIP;
+  fa.Hh = desc->heads;
   fa.x = k; fa.W1 = desc->Wk1; fa.W2 = desc->Wk2; fa.W3 = desc->Wk3;
   fa.out = reinterpret_cast<float *>(ws + w.off_fpsi); fa.out_f64 = 0;
   if (launch_featmap_generic(fa, desc->dtype, st) != hipSuccess) return LESSDEC_EHIP;
@@ -174,6 +178,11 @@ int lessdec_step_attend(const lessdec_desc *desc, const void *q, const void *k, 
   a.q = q; a.k = k; a.v = v; a.out = out; a.evicted_pos = evicted_pos;
   const Workspace w = carve(s, 0);
   char *ws = static_cast<char *>(desc->workspace);
+  if (s.G > 1) {
+    a.f_phi = reinterpret_cast<double *>(ws + w.off_fphi);
+    a.f_psi = reinterpret_cast<float *>(ws + w.off_fpsi);
+    return launch_step_gqa(a, (int)s.G, desc->dtype, desc->head_dim, st) == hipSuccess ? LESSDEC_OK : LESSDEC_EHIP;
+  }
   if (wpu_supported(desc->dtype, desc->head_dim, (int)s.C, desc->hidden, desc->rank)) {
     a.mlp_parts = reinterpret_cast<float *>(ws + w.off_parts);     // one wave per unit
     return launch_step_wpu(a, desc->head_dim, st) == hipSuccess ? LESSDEC_OK : LESSDEC_EHIP;
@@ -216,11 +225,12 @@ int lessdec_prefill(const lessdec_desc *desc, const void *Q, const void *K, cons
     hipStream_t st = (hipStream_t)hip_stream;
     PromptRowsArgs r;
     r.Q = Q; r.K = K; r.V = V; r.out = out; r.P = P; r.U = (unsigned)s.U; r.D = desc->head_dim;
-    r.dtype = desc->dtype;
+    r.dtype = desc->dtype; r.G = (int)s.G;
+    const size_t part = s.U * s.G * s.D * sizeof(float);
     r.qs = ws + w.off_stage;
-    r.ks = ws + w.off_stage + 1 * s.U * s.D * sizeof(float);
-    r.vs = ws + w.off_stage + 2 * s.U * s.D * sizeof(float);
-    r.outs = ws + w.off_stage + 3 * s.U * s.D * sizeof(float);
+    r.ks = ws + w.off_stage + 1 * part;
+    r.vs = ws + w.off_stage + 2 * part;
+    r.outs = ws + w.off_stage + 3 * part;
     if (launch_reset(desc, st) != hipSuccess) return LESSDEC_EHIP;
     for (int32_t t = 0; t < P; ++t) {
       if (launch_prompt_rows(r, t, (out && t > 0) ? t - 1 : -1, st) != hipSuccess) return LESSDEC_EHIP;
@@ -230,6 +240,7 @@ int lessdec_prefill(const lessdec_desc *desc, const void *Q, const void *K, cons
     if (out && launch_prompt_rows(r, -1, P - 1, st) != hipSuccess) return LESSDEC_EHIP;
     return LESSDEC_OK;
   }
+  if (s.G > 1) return LESSDEC_EINVAL;     // several query heads per unit: only the stepwise form
   PrefillArgs a;
   a.d = desc; a.Q = Q; a.K = K; a.V = V; a.P = P; a.out = out;
   a.lse = reinterpret_cast<double *>(ws + w.off_lse);

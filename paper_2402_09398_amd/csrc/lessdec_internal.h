@@ -72,6 +72,8 @@ struct StepArgs {
   const void *Wk3;
 };
 hipError_t launch_step(const StepArgs &a, int dtype, int D, hipStream_t st);
+// several query heads per unit: q, out [U,G,D], f_phi [U,G,R]
+hipError_t launch_step_gqa(const StepArgs &a, int G, int dtype, int D, hipStream_t st);
 hipError_t launch_state_sync(const StepArgs &a, int dtype, int D, hipStream_t st);
 
 // One wave per unit, K and V streamed through a register ring (lessdec_wpu.hip).
@@ -100,9 +102,9 @@ hipError_t launch_prefill(const PrefillArgs &a, hipStream_t st);
 struct PromptRowsArgs {
   const void *Q, *K, *V;   // [U,P,D] dtype
   void *out;               // [U,P,D] dtype or NULL
-  void *qs, *ks, *vs;      // [U,D] dtype: token `gather`'s rows
-  void *outs;              // [U,D] dtype: the output of token `scatter`
-  int P, D, dtype;
+  void *qs, *ks, *vs;      // [U,G,D], [U,D], [U,D] dtype: token `gather`'s rows
+  void *outs;              // [U,G,D] dtype: the output of token `scatter`
+  int P, D, dtype, G;      // Q and out are [U,G,P,D]
   unsigned U;
 };
 // gather < 0: nothing staged; scatter < 0: nothing written back

@@ -908,27 +908,30 @@ __global__ __launch_bounds__(256) void prompt_rows_kernel(const uint4 *__restric
                                                           const uint4 *__restrict__ V, uint4 *__restrict__ out,
                                                           uint4 *__restrict__ qs, uint4 *__restrict__ ks,
                                                           uint4 *__restrict__ vs, const uint4 *__restrict__ outs,
-                                                          unsigned U, int P, int vecs, int gather, int scatter)
+                                                          unsigned U, int G, int P, int vecs, int gather,
+                                                          int scatter)
 {
-  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;   // vector index in [U, vecs]
-  if (i >= (size_t)U * vecs) return;
-  const size_t u = i / vecs, c = i % vecs;
-  if (scatter >= 0) out[(u * P + scatter) * vecs + c] = outs[i];
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;   // vector index in [U * G, vecs]
+  if (i >= (size_t)U * G * vecs) return;
+  const size_t ug = i / vecs, c = i % vecs;                  // query row (unit, head)
+  if (scatter >= 0) out[(ug * P + scatter) * vecs + c] = outs[i];
   if (gather >= 0) {
-    const size_t src = (u * P + gather) * vecs + c;
-    qs[i] = Q[src];
-    ks[i] = K[src];
-    vs[i] = V[src];
+    qs[i] = Q[(ug * P + gather) * vecs + c];
+    if (ug % G == 0) {                                       // the unit's key and value rows, once
+      const size_t u = ug / G;
+      ks[u * vecs + c] = K[(u * P + gather) * vecs + c];
+      vs[u * vecs + c] = V[(u * P + gather) * vecs + c];
+    }
   }
 }
 
 hipError_t launch_prompt_rows(const PromptRowsArgs &a, int gather, int scatter, hipStream_t st)
 {
   const int vecs = a.D * (a.dtype == LESSDEC_DTYPE_F16 ? 2 : 4) / 16;
-  const size_t n = (size_t)a.U * vecs;
+  const size_t n = (size_t)a.U * a.G * vecs;
   prompt_rows_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(
       (const uint4 *)a.Q, (const uint4 *)a.K, (const uint4 *)a.V, (uint4 *)a.out, (uint4 *)a.qs, (uint4 *)a.ks,
-      (uint4 *)a.vs, (const uint4 *)a.outs, a.U, a.P, vecs, gather, scatter);
+      (uint4 *)a.vs, (const uint4 *)a.outs, a.U, a.G, a.P, vecs, gather, scatter);
   return hipGetLastError();
 }
 

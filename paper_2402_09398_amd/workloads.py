@@ -50,6 +50,7 @@ class Workload:
     hidden: int
     dtype: str            # "f32" or "f16": storage type of q/k/v, the cache, the weights, out
     outlier_channels: int = 0
+    q_per_kv: int = 1     # query heads per key/value head; > 1: q, Q and Wq1, Wq2 get an axis G
 
     @property
     def units(self) -> int:
@@ -100,18 +101,26 @@ def head_params(w: Workload, h: int) -> dict:
         m = g.standard_normal((rows, cols)) / np.sqrt(rows)
         return m.astype(np.float32).astype(w.np_dtype)
 
-    return {
+    p = {
         "sigma": sigma,
         "outlier_channels": outl,
         "Wq1": mat(D, Rp), "Wq2": mat(Rp, R),
         "Wk1": mat(D, Rp), "Wk2": mat(Rp, R), "Wk3": mat(R, R),
     }
+    if w.q_per_kv > 1:          # the head's further query heads, drawn after everything else
+        p["Wq1"] = np.stack([p["Wq1"]] + [mat(D, Rp) for _ in range(w.q_per_kv - 1)])
+        p["Wq2"] = np.stack([p["Wq2"]] + [mat(Rp, R) for _ in range(w.q_per_kv - 1)])
+    return p
 
 
 def head_weights(w: Workload) -> dict:
     """All heads' weights stacked: Wq1 [Hh,D,R'], Wq2 [Hh,R',R], Wk1, Wk2, Wk3 [Hh,R,R]."""
     hp = [head_params(w, h) for h in range(w.heads)]
-    return {k: np.stack([p[k] for p in hp]) for k in ("Wq1", "Wq2", "Wk1", "Wk2", "Wk3")}
+    W = {k: np.stack([p[k] for p in hp]) for k in ("Wq1", "Wq2", "Wk1", "Wk2", "Wk3")}
+    if w.q_per_kv > 1:          # [Hh,G,..] -> [Hh*G,..]: head h's query heads in a row
+        W["Wq1"] = W["Wq1"].reshape((-1,) + W["Wq1"].shape[2:])
+        W["Wq2"] = W["Wq2"].reshape((-1,) + W["Wq2"].shape[2:])
+    return W
 
 
 def unit_inputs(w: Workload, u: int, prompt: int | None = None, steps: int | None = None) -> dict:
@@ -151,11 +160,15 @@ def unit_inputs(w: Workload, u: int, prompt: int | None = None, steps: int | Non
 
     Q = store(draw_qk(P, False)); K = store(draw_qk(P, True)); V = store(draw_v(P))
     q = store(draw_qk(T, False)); k = store(draw_qk(T, True)); v = store(draw_v(T))
+    if w.q_per_kv > 1:          # further query heads, drawn after everything else: Q [G,P,D], q [T,G,D]
+        Q = np.stack([Q] + [store(draw_qk(P, False)) for _ in range(w.q_per_kv - 1)])
+        q = np.stack([q] + [store(draw_qk(T, False)) for _ in range(w.q_per_kv - 1)], axis=1)
     return {"Q": Q, "K": K, "V": V, "q": q, "k": k, "v": v}
 
 
 def all_inputs(w: Workload, units=None, workers: int = 8) -> dict:
-    """Stacked inputs for the given units (default: all): Q,K,V [U,P,D]; q,k,v [T,U,D]."""
+    """Stacked inputs for the given units (default: all): Q,K,V [U,P,D]; q,k,v [T,U,D]
+    (Q [U,G,P,D] and q [T,U,G,D] with several query heads per unit)."""
     units = list(range(w.units)) if units is None else list(units)
     with ThreadPoolExecutor(max_workers=workers) as ex:
         per = list(ex.map(lambda u: unit_inputs(w, u), units))

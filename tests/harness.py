@@ -72,7 +72,8 @@ class Report:
 def make_oracle(w, units, flags=0):
     W = wl.head_weights(w)
     return lo.OracleState(len(units), w.heads, w.head_dim, w.n_heavy, w.n_recent, w.rank,
-                          w.hidden, W, flags=flags, head_of_unit=[u % w.heads for u in units])
+                          w.hidden, W, flags=flags, head_of_unit=[u % w.heads for u in units],
+                          q_per_kv=w.q_per_kv)
 
 
 def make_gpu(w, flags=0, max_prompt=None, device="cuda:0"):
@@ -80,7 +81,7 @@ def make_gpu(w, flags=0, max_prompt=None, device="cuda:0"):
     W = pack_weights(wl.head_weights(w), device)
     return LessDec(w.batch, w.heads, w.head_dim, w.n_heavy, w.n_recent, w.rank, w.hidden,
                    w.dtype, W, flags=flags, max_prompt=w.prompt if max_prompt is None else max_prompt,
-                   device=device)
+                   device=device, q_per_kv=w.q_per_kv)
 
 
 def upload_oracle_state(gpu, st, units_all=True):
@@ -138,14 +139,15 @@ def gpu_run(w, inp, flags=0, with_prefill=True, want_prefill_out=True, gpu=None,
     T = inp["q"].shape[0]
     if T:
         q, k, v = (torch.from_numpy(inp[n]).to(dev) for n in ("q", "k", "v"))
-        outs = torch.empty((T, U, D), dtype=gpu.tdtype, device=dev)
+        outs = torch.empty(q.shape, dtype=gpu.tdtype, device=dev)
         ev = torch.full((T, U), -7, dtype=torch.int32, device=dev)
         for t in range(T):
             gpu.step(q[t], k[t], v[t], outs[t], ev[t])
         torch.cuda.synchronize(dev)
         res["outs"] = outs.cpu().numpy(); res["evicted"] = ev.cpu().numpy()
     else:
-        res["outs"] = np.zeros((0, U, D), dtype=w.np_dtype); res["evicted"] = np.zeros((0, U), dtype=np.int32)
+        res["outs"] = np.zeros((0,) + inp["q"].shape[1:], dtype=w.np_dtype)
+        res["evicted"] = np.zeros((0, U), dtype=np.int32)
     res["final"] = snapshot()
     return res
 
@@ -223,7 +225,7 @@ def check_against_oracle(w, inp_units, units, res, flags=0, with_prefill=True, o
         force = np.where(active, gev, -1)
         r = st.step(inp_units["q"][t], inp_units["k"][t], inp_units["v"][t], force=force)
         shares.append(r["share"])
-        err = rel_inf(res["outs"][t][units], r["out"])
+        err = rel_inf(res["outs"][t][units], r["out"]).reshape(len(units), -1).max(axis=1)   # over query heads
         for i, u in enumerate(units):
             if not active[i]:
                 continue

@@ -28,7 +28,7 @@ def test_library_exports_every_declared_symbol():
 
 def test_descriptor_layout_matches_header():
     # 9 int32 fields (padded to 8 bytes), 17 pointers, 1 size_t on LP64
-    assert C.sizeof(binding.Desc) == 9 * 4 + 4 + 17 * 8 + 8
+    assert C.sizeof(binding.Desc) == 10 * 4 + 17 * 8 + 8
     assert binding.Desc.k_cache.offset == 40
 
 
@@ -59,7 +59,8 @@ def test_workspace_bytes_and_shape_validation():
     assert binding.lessdec_workspace_bytes(_desc(), 512) > binding.lessdec_workspace_bytes(_desc(), 0)
     for bad in (dict(head_dim=96), dict(rank=0), dict(rank=65), dict(hidden=0), dict(hidden=4096),
                 dict(n_heavy=0, n_recent=0), dict(n_heavy=4000, n_recent=4000), dict(dtype=7),
-                dict(batch=0), dict(flags=8), dict(n_heavy=-1)):
+                dict(batch=0), dict(flags=8), dict(n_heavy=-1), dict(q_per_kv=-1), dict(q_per_kv=129),
+                dict(q_per_kv=2, n_heavy=1024, n_recent=1024)):
         assert binding.lessdec_workspace_bytes(_desc(**bad), 0) == 0, bad
 
 
@@ -87,6 +88,10 @@ def test_calls_reject_bad_descriptors_on_the_host():
     assert L.lessdec_step(C.byref(d), 0x30000, 0x30000, 0x30004, 0x30000, None, None) == binding.EINVAL
     assert L.lessdec_step_features(C.byref(d), 0x30000, 0x30008, None) == binding.EINVAL
     assert L.lessdec_step_attend(C.byref(d), 0x30000, 0x30000, 0x30000, None, None, None) == binding.EINVAL
+    # several query heads per unit: the one-shot prompt phase is not available, the stepwise one is
+    d.q_per_kv = 2
+    assert L.lessdec_prefill(C.byref(d), 0x30000, 0x30000, 0x30000, 8, None, None) == binding.EINVAL
+    d.q_per_kv = 0
     assert b"workspace" in L.lessdec_strerror(binding.EWORKSPACE)
     assert L.lessdec_strerror(12345) is not None
 
@@ -122,3 +127,14 @@ def test_workload_generator_shapes_and_determinism():
     assert np.array_equal(full["k"][:, 1], wl.unit_inputs(w, 2)["k"])
     w1 = wl.WORKLOADS[1]
     assert wl.unit_inputs(w1, 0)["Q"].dtype == np.float32
+    # several query heads per unit: an extra axis on the queries and on phi's weights only;
+    # the first query head and everything else are the single-head draws
+    wg = w.scaled(q_per_kv=3)
+    g = wl.unit_inputs(wg, 1)
+    assert g["Q"].shape == (3, 40, 128) and g["q"].shape == (5, 3, 128) and g["K"].shape == (40, 128)
+    assert np.array_equal(g["Q"][0], a["Q"]) and np.array_equal(g["q"][:, 0], a["q"]) and np.array_equal(g["v"], a["v"])
+    gw = wl.head_weights(wg)
+    assert gw["Wq1"].shape == (9, 128, 512) and gw["Wk1"].shape == (3, 128, 512)
+    assert np.array_equal(gw["Wq1"][3], allw["Wq1"][1]) and np.array_equal(gw["Wk2"], allw["Wk2"])
+    fullg = wl.all_inputs(wg, units=[0, 2])
+    assert fullg["Q"].shape == (2, 3, 40, 128) and fullg["q"].shape == (5, 2, 3, 128)

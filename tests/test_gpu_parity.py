@@ -180,6 +180,26 @@ def test_stepwise_prompt_is_the_generation_loop(kind):
         assert torch.equal(getattr(a, n), getattr(b, n)), n
 
 
+# Several query heads per key/value head (multi-query / grouped-query attention, Sec. 3.2): the
+# prompt is taken token by token (the one-shot prompt phase is not available for this form)
+GROUPS = [
+    (small("mqa-4-heads", q_per_kv=4, prompt=30, steps=25), 4),
+    (small("gqa-2-heads-f32-d64", q_per_kv=2, dtype="f32", head_dim=64, rank=4, prompt=30, steps=25), 4),
+    (small("gqa-3-heads-lambda", q_per_kv=3, n_heavy=4, n_recent=8, prompt=30, steps=20), 6),
+    (small("mqa-8-heads-no-prompt", q_per_kv=8, prompt=0, steps=40, n_heavy=5, n_recent=5), 4),
+    (small("gqa-2-heads-no-recent-window", q_per_kv=2, n_heavy=6, n_recent=0, prompt=20, steps=20), 4),
+    (small("gqa-2-heads-sparse-denominator", q_per_kv=2, prompt=20, steps=20), 5),
+    (small("gqa-5-heads-wide-cache", q_per_kv=5, n_heavy=100, n_recent=60, prompt=200, steps=10, batch=1,
+           heads=2, rank=16, hidden=96), 4),
+]
+
+
+@pytest.mark.parametrize("w,flags", GROUPS, ids=lambda x: x.name if hasattr(x, "name") else str(x))
+def test_query_groups_sharing_a_cache(w, flags):
+    rep = hz.run_workload(w, range(w.units), flags=flags)
+    report_ok(rep, min_decisions=w.units * max(0, min(w.steps, w.prompt + w.steps - w.capacity)))
+
+
 def test_maximum_capacity():
     w = small("max-capacity", batch=1, heads=2, n_heavy=2047, n_recent=2047, prompt=4200, steps=6,
               rank=16, hidden=128)
