@@ -96,7 +96,7 @@ StepArgs state_args(const lessdec_desc *desc, const Shape &s)
   a.pend_slot = desc->pend_slot; a.pend_v = desc->pend_v; a.pend_psi = desc->pend_psi;
   a.q = a.k = a.v = nullptr; a.out = nullptr; a.evicted_pos = nullptr;
   a.U = (int)s.U; a.Hh = desc->heads; a.B = desc->batch;
-  a.f_phi = nullptr; a.f_psi = nullptr; a.mlp_parts = nullptr;
+  a.f_phi = nullptr; a.f_phi32 = nullptr; a.f_psi = nullptr; a.mlp_parts = nullptr;
   a.Wk3 = desc->Wk3;
   return a;
 }
@@ -149,6 +149,19 @@ int lessdec_step_features(const lessdec_desc *desc, const void *q, const void *k
     fm.B = desc->batch; fm.Hh = desc->heads; fm.D = desc->head_dim; fm.Rp = desc->hidden; fm.R = desc->rank;
     return launch_mlp_parts(fm, st) == hipSuccess ? LESSDEC_OK : LESSDEC_EHIP;
   }
+  if (s.G > 1 && mlp_mfma_supported(desc->dtype, desc->head_dim, desc->hidden, desc->rank)) {
+    // several query heads per unit: both maps complete on the matrix cores, fp32 results
+    MlpArgs fm;
+    fm.B = desc->batch; fm.rpu = 1; fm.D = desc->head_dim; fm.Rp = desc->hidden; fm.R = desc->rank;
+    fm.Hh = desc->heads * (int)s.G;                     // q rows [B,Hh,G]: query head h G + g
+    fm.x = (const __half *)q; fm.W1 = (const __half *)desc->Wq1; fm.W2 = (const __half *)desc->Wq2;
+    fm.W3 = nullptr; fm.out = reinterpret_cast<float *>(ws + w.off_fphi);
+    if (launch_mlp(fm, st) != hipSuccess) return LESSDEC_EHIP;
+    fm.Hh = desc->heads;
+    fm.x = (const __half *)k; fm.W1 = (const __half *)desc->Wk1; fm.W2 = (const __half *)desc->Wk2;
+    fm.W3 = (const __half *)desc->Wk3; fm.out = reinterpret_cast<float *>(ws + w.off_fpsi);
+    return launch_mlp(fm, st) == hipSuccess ? LESSDEC_OK : LESSDEC_EHIP;
+  }
   // general path: phi(q), psi(k) in fp64
   FeatmapArgs fa;
   fa.B = desc->batch; fa.Hh = desc->heads * (int)s.G; fa.rpu = 1;   // q rows [B,Hh,G]: query head h G + g
@@ -179,7 +192,10 @@ int lessdec_step_attend(const lessdec_desc *desc, const void *q, const void *k, 
   const Workspace w = carve(s, 0);
   char *ws = static_cast<char *>(desc->workspace);
   if (s.G > 1) {
-    a.f_phi = reinterpret_cast<double *>(ws + w.off_fphi);
+    if (mlp_mfma_supported(desc->dtype, desc->head_dim, desc->hidden, desc->rank))
+      a.f_phi32 = reinterpret_cast<float *>(ws + w.off_fphi);
+    else
+      a.f_phi = reinterpret_cast<double *>(ws + w.off_fphi);
     a.f_psi = reinterpret_cast<float *>(ws + w.off_fpsi);
     return launch_step_gqa(a, (int)s.G, desc->dtype, desc->head_dim, st) == hipSuccess ? LESSDEC_OK : LESSDEC_EHIP;
   }

@@ -7,55 +7,52 @@
 // First form of this path: one block of 256 threads per unit, the heads one after the other,
 // all arithmetic fp64 in the order of the equations, cache rows read straight from memory.
 // It folds the discarded pair into H, z within the step (nothing is left pending).
-#include "lessdec_common.h"
-#include "lessdec_internal.h"
+#include "lessdec_wave.h"
 
 namespace lessdec {
 
 namespace {
 
-__device__ inline double block_max(double v, double *s_red, int tid)
+// all-reduce over the block's four waves: within a wave by lane exchange, across waves through
+// four LDS words, combined in wave order
+template <typename Op>
+__device__ inline double block_allreduce(double v, double *s_red, int tid, Op op)
 {
-  s_red[tid] = v;
+  v = wave_allreduce(v, op);
+  if (tid % kWave == 0) s_red[tid / kWave] = v;
   __syncthreads();
-  for (int o = 128; o > 0; o >>= 1) {
-    if (tid < o) s_red[tid] = fmax(s_red[tid], s_red[tid + o]);
-    __syncthreads();
-  }
-  const double r = s_red[0];
-  __syncthreads();
-  return r;
-}
-__device__ inline double block_sum(double v, double *s_red, int tid)
-{
-  s_red[tid] = v;
-  __syncthreads();
-  for (int o = 128; o > 0; o >>= 1) {
-    if (tid < o) s_red[tid] += s_red[tid + o];
-    __syncthreads();
-  }
-  const double r = s_red[0];
+  const double r = op(op(op(s_red[0], s_red[1]), s_red[2]), s_red[3]);
   __syncthreads();
   return r;
 }
 
 }  // namespace
 
-// q, out: [U,G,D]; k, v: [U,D]; f_phi: [U,G,R] fp64; f_psi: [U,R] fp32.
-// grid = U, block = 256, dynamic LDS = (2 (C + 2) + D + 64) doubles.
-template <typename T, int D>
+// q, out: [U,G,D]; k, v: [U,D]; f_phi [U,G,R] fp64 or f_phi32 in fp32; f_psi: [U,R] fp32.
+// grid = U, block = 256, dynamic LDS: see launch_step_gqa_t.
+// STAGE: the unit's key and value rows (and H, z) are copied into the LDS once and every head
+// works from there; without it each head reads them from memory again (any capacity).
+template <typename T, int D, bool STAGE>
 __global__ __launch_bounds__(256) void gqa_step_kernel(const StepArgs a, int G)
 {
   extern __shared__ double dyn[];
-  __shared__ double s_red[256];
+  __shared__ double s_red[4];
   __shared__ Cand s_cand[256];
+  __shared__ double s_num[256];
+  constexpr int EPL = Store<T>::kPerVec, LPR = D / EPL, RPB = 256 / LPR;   // lanes per row, rows per pass
+  using Vec = typename Store<T>::Vec;
   const int u = (int)blockIdx.x, tid = threadIdx.x;
+  const int lr = tid % LPR, rb = tid / LPR;
   const int C = a.C, R = a.R;
   const int rows_cap = C + 2;
   double *s_e = dyn;                       // [C+1] scores, then e^{s - m*}, then the new accumulated scores
   double *s_inc = dyn + rows_cap;          // [C+1] this step's probabilities per pair, summed over the heads
   double *s_q = s_inc + rows_cap;          // [D] the head's query
   double *s_f = s_q + D;                   // [R] the head's phi(q)
+  double *s_z = s_f + 64;                  // [R] z
+  float *s_H = reinterpret_cast<float *>(s_z + 64);                    // STAGE: [R,D]
+  T *s_k = reinterpret_cast<T *>(s_H + (STAGE ? R * D : 0));          // STAGE: [C+1,D] keys, the appended one last
+  T *s_v = s_k + (STAGE ? (size_t)(C + 1) * D : 0);                    // STAGE: [C+1,D] values
 
   const int n = a.n_seen[u];
   const int m = n < C ? n : C;             // live slots are 0..m-1 (slots fill in order)
@@ -70,27 +67,69 @@ __global__ __launch_bounds__(256) void gqa_step_kernel(const StepArgs a, int G)
   const double sqrt_d = sqrt((double)D);
 
   for (int r = tid; r < rows; r += 256) s_inc[r] = 0.0;
-
-  for (int g = 0; g < G; ++g) {
-    const T *qg = reinterpret_cast<const T *>(a.q) + ((size_t)u * G + g) * D;
-    __syncthreads();
-    if (tid < D) s_q[tid] = (double)Store<T>::to_float(qg[tid]);
-    if (tid < R) s_f[tid] = a.f_phi[((size_t)u * G + g) * R + tid];
-    __syncthreads();
-    // scores against the cached keys and the appended key
-    double mx = -__builtin_inf();
-    for (int r = tid; r < rows; r += 256) {
-      const T *row = r < m ? kc + (size_t)r * D : kn;
-      double acc = 0.0;
-      for (int d = 0; d < D; ++d) acc = fma(s_q[d], (double)Store<T>::to_float(row[d]), acc);
-      const double s = acc / sqrt_d;
-      s_e[r] = s;
-      mx = fmax(mx, s);
+  if (tid < R) s_z[tid] = zu[tid];
+  if constexpr (STAGE) {
+    constexpr int VPR = D / EPL;                             // 16-byte vectors per row
+    for (int i = tid; i < rows * VPR; i += 256) {
+      const int r = i / VPR, c = i % VPR;
+      reinterpret_cast<Vec *>(s_k)[i] = load_vec<T>((r < m ? kc + (size_t)r * D : kn) + c * EPL);
+      reinterpret_cast<Vec *>(s_v)[i] = load_vec<T>((r < m ? vc + (size_t)r * D : vn) + c * EPL);
     }
-    mx = block_max(mx, s_red, tid);
+    for (int i = tid; i < R * D; i += 256) s_H[i] = Hu[i];
+  }
+
+  // a head's query element and phi entry of this thread, requested one head ahead
+  auto fetch_q = [&](int g) -> double {
+    return tid < D ? (double)Store<T>::to_float(reinterpret_cast<const T *>(a.q)[((size_t)u * G + g) * D + tid]) : 0.0;
+  };
+  auto fetch_f = [&](int g) -> double {
+    if (tid >= R) return 0.0;
+    const size_t i = ((size_t)u * G + g) * R + tid;
+    return a.f_phi32 ? (double)a.f_phi32[i] : a.f_phi[i];
+  };
+  double q_next = fetch_q(0), f_next = fetch_f(0);
+  const double inv_sqrt_d = 1.0 / sqrt_d;
+  for (int g = 0; g < G; ++g) {
+    __syncthreads();
+    if (tid < D) s_q[tid] = q_next;
+    if (tid < R) s_f[tid] = f_next;
+    if (g + 1 < G) {
+      q_next = fetch_q(g + 1);
+      f_next = fetch_f(g + 1);
+    }
+    __syncthreads();
+    double qreg[EPL];                                        // this lane's share of the query
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) qreg[i] = s_q[lr * EPL + i];
+    // scores against the cached keys and the appended key: LPR lanes of 16 bytes per row; the
+    // rows of the first NP passes are requested together, further passes one at a time
+    double mx = -__builtin_inf();
+    auto row_ptr = [&](int r) -> const T * {
+      const int rc = r < rows ? r : rows - 1;
+      if constexpr (STAGE) return s_k + (size_t)rc * D + lr * EPL;
+      return (rc < m ? kc + (size_t)rc * D : kn) + lr * EPL;
+    };
+    auto score = [&](int r, const Vec &kv) {
+      double acc = 0.0;
+#pragma unroll
+      for (int i = 0; i < EPL; ++i) acc = fma(qreg[i], (double)Store<T>::get(kv, i), acc);
+      acc = row_sum<LPR>(acc);
+      const double s = acc * inv_sqrt_d;
+      if (lr == 0 && r < rows) s_e[r] = s;
+      if (r < rows) mx = fmax(mx, s);
+    };
+    constexpr int NP = 8;
+    Vec kvs[NP];
+#pragma unroll
+    for (int p = 0; p < NP; ++p) kvs[p] = load_vec<T>(row_ptr(p * RPB + rb));   // clamped: always in range
+#pragma unroll
+    for (int p = 0; p < NP; ++p)
+      if (p * RPB < rows) score(p * RPB + rb, kvs[p]);
+    for (int r0 = NP * RPB; r0 < rows; r0 += RPB) score(r0 + rb, load_vec<T>(row_ptr(r0 + rb)));
+    mx = block_allreduce(mx, s_red, tid, OpMax{});
     // phi(q) z^T and the common shift m* = max(scores, ln(phi(q) z^T)) (Eq. 3 times e^{-m*})
     double fz = 0.0;
-    for (int r = 0; r < R; ++r) fz = fma(s_f[r], zu[r], fz);
+    for (int r = 0; r < R; ++r) fz = fma(s_f[r], s_z[r], fz);
     const double lfz = fz > 0.0 ? log(fz) : -__builtin_inf();
     const double mstar = fmax(mx, lfz);
     const double wl = fz > 0.0 ? exp(lfz - mstar) : 0.0;
@@ -100,18 +139,33 @@ __global__ __launch_bounds__(256) void gqa_step_kernel(const StepArgs a, int G)
       s_e[r] = e;
       part += e;
     }
-    const double den = wl + block_sum(part, s_red, tid);   // the barriers inside publish s_e
-    // output column d: (phi(q) H e^{-m*} + sum_j e_j V_j) / den
-    if (tid < D) {
+    const double den = wl + block_allreduce(part, s_red, tid, OpAdd{});   // the barriers inside publish s_e
+    // output column d: (phi(q) H e^{-m*} + sum_j e_j V_j) / den; the 256 / D thread groups
+    // take the rows in turn and meet in the LDS
+    {
+      constexpr int NG = 256 / D;
+      const int d = tid % D, grp = tid / D;
       double num = 0.0;
-      if (fz > 0.0) {
+      if (grp == 0 && fz > 0.0) {
         double fh = 0.0;
-        for (int r = 0; r < R; ++r) fh = fma(s_f[r], (double)Hu[(size_t)r * D + tid], fh);
+        for (int r = 0; r < R; ++r) fh = fma(s_f[r], (double)(STAGE ? s_H[r * D + d] : Hu[(size_t)r * D + d]), fh);
         num = fh * exp(-mstar);
       }
-      for (int r = 0; r < m; ++r) num = fma(s_e[r], (double)Store<T>::to_float(vc[(size_t)r * D + tid]), num);
-      num = fma(s_e[m], (double)Store<T>::to_float(vn[tid]), num);
-      reinterpret_cast<T *>(a.out)[((size_t)u * G + g) * D + tid] = Store<T>::from_float((float)(num / den));
+      if constexpr (STAGE) {
+#pragma unroll 8
+        for (int r = grp; r < rows; r += NG) num = fma(s_e[r], (double)Store<T>::to_float(s_v[(size_t)r * D + d]), num);
+      } else {
+#pragma unroll 8
+        for (int r = grp; r < m; r += NG) num = fma(s_e[r], (double)Store<T>::to_float(vc[(size_t)r * D + d]), num);
+        if (grp == m % NG) num = fma(s_e[m], (double)Store<T>::to_float(vn[d]), num);
+      }
+      s_num[tid] = num;
+      __syncthreads();
+      if (tid < D) {
+#pragma unroll
+        for (int k = 1; k < NG; ++k) num += s_num[k * D + tid];
+        reinterpret_cast<T *>(a.out)[((size_t)u * G + g) * D + tid] = Store<T>::from_float((float)(num / den));
+      }
     }
     // this head's probabilities (H2O accumulates those of every head)
     const double dacc = (a.flags & LESSDEC_FLAG_SPARSE_DENOM) ? den - wl : den;
@@ -180,17 +234,23 @@ __global__ __launch_bounds__(256) void gqa_step_kernel(const StepArgs a, int G)
   }
 }
 
+template <typename T, int D>
+static hipError_t launch_step_gqa_t(const StepArgs &a, int G, hipStream_t st)
+{
+  const size_t base = (size_t)(2 * (a.C + 2) + D + 64 + 64) * sizeof(double);
+  const size_t staged = base + (size_t)a.R * D * sizeof(float) + 2 * (size_t)(a.C + 1) * D * sizeof(T);
+  if (staged <= 64 * 1024)
+    gqa_step_kernel<T, D, true><<<a.U, 256, staged, st>>>(a, G);
+  else
+    gqa_step_kernel<T, D, false><<<a.U, 256, base, st>>>(a, G);
+  return hipGetLastError();
+}
+
 hipError_t launch_step_gqa(const StepArgs &a, int G, int dtype, int D, hipStream_t st)
 {
-  const size_t lds = (size_t)(2 * (a.C + 2) + D + 64) * sizeof(double);
-  if (dtype == LESSDEC_DTYPE_F16) {
-    if (D == 128) gqa_step_kernel<__half, 128><<<a.U, 256, lds, st>>>(a, G);
-    else gqa_step_kernel<__half, 64><<<a.U, 256, lds, st>>>(a, G);
-  } else {
-    if (D == 128) gqa_step_kernel<float, 128><<<a.U, 256, lds, st>>>(a, G);
-    else gqa_step_kernel<float, 64><<<a.U, 256, lds, st>>>(a, G);
-  }
-  return hipGetLastError();
+  if (dtype == LESSDEC_DTYPE_F16)
+    return D == 128 ? launch_step_gqa_t<__half, 128>(a, G, st) : launch_step_gqa_t<__half, 64>(a, G, st);
+  return D == 128 ? launch_step_gqa_t<float, 128>(a, G, st) : launch_step_gqa_t<float, 64>(a, G, st);
 }
 
 }  // namespace lessdec

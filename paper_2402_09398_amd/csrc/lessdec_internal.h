@@ -65,7 +65,8 @@ struct StepArgs {
   int32_t *evicted_pos;
   int U, Hh, B;
   // generic path: feature maps of this step's q and k from the launches before it
-  const double *f_phi;   // [U,R]
+  const double *f_phi;   // [U,R] ([U,G,R] with several query heads per unit)
+  const float *f_phi32;  // the same in fp32 from the matrix-core feature maps, or NULL
   const float *f_psi;    // [U,R]
   // wave-per-unit path: layer-2 sums of both feature maps by parts (launch_mlp_parts), and W3
   const float *mlp_parts;

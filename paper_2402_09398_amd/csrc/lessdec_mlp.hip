@@ -1,4 +1,5 @@
-// psi (Eq. 2) of many rows on the matrix cores: used by the prompt phase for every prompt key.
+// psi (Eq. 2), or phi (Eq. 1) when no third matrix is given, of many rows on the matrix cores:
+// used by the prompt phase for every prompt key and by the multi-head decode step.
 #include "lessdec_internal.h"
 #include "lessdec_mlp.h"
 
@@ -50,12 +51,17 @@ __global__ __launch_bounds__(256) void mlp_psi_kernel(const MlpArgs a)
     s_h2[row][r] = (r < R) ? gelu_poly_f64((double)sum) : 0.0;
   }
   __syncthreads();
-  const __half *W3 = a.W3 + ((size_t)h * R + (r < R ? r : 0)) * R;
+  // W3 == nullptr: the map has no third matrix (phi, Eq. 1)
+  const __half *W3 = a.W3 ? a.W3 + ((size_t)h * R + (r < R ? r : 0)) * R : nullptr;
   for (int row = tid / 16; row < 16 * kPsiTiles; row += 16) {
     const long i = (long)chunk * (16 * kPsiTiles) + row;
     if (r < R && i < rows_head) {
       double acc3 = 0.0;
-      for (int j = 0; j < R; ++j) acc3 = fma(s_h2[row][j], (double)__half2float(W3[j]), acc3);
+      if (W3 != nullptr) {
+        for (int j = 0; j < R; ++j) acc3 = fma(s_h2[row][j], (double)__half2float(W3[j]), acc3);
+      } else {
+        acc3 = s_h2[row][r];
+      }
       a.out[(size_t)global_row(i) * R + r] = (float)fabs(acc3);
     }
   }
