@@ -137,8 +137,8 @@ int lessdec_state_sync(const lessdec_desc *desc, void *hip_stream);
  * later token), in ascending token order, with acc = column sum; every other prompt pair
  * is folded into H, z (Eq. 6); n_seen = P.  If P <= C every token is kept.
  * With LESSDEC_FLAG_LAMBDA the first n_heavy tokens are kept in place of the heavy hitters.
- * With q_per_kv = G > 1: Q and out are [B,Hh,G,P,D]; only the LESSDEC_FLAG_PROMPT_STEPWISE
- * form of the call is available (LESSDEC_EINVAL otherwise).
+ * With q_per_kv = G > 1: Q and out are [B,Hh,G,P,D], and a token's score is the column sum
+ * of all G causal attention matrices of its unit.
  * With LESSDEC_FLAG_PROMPT_STEPWISE the call is lessdec_state_reset followed by one
  * lessdec_step per prompt token t with rows Q[.,.,t,.], K[.,.,t,.], V[.,.,t,.] (2 P launches
  * plus row staging; not the fast way through a prompt): out[.,.,t,.] is then Eq. 3's output

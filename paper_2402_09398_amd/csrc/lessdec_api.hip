@@ -40,7 +40,7 @@ bool shape_ok(const lessdec_desc *d, Shape *s)
 }
 
 // Workspace: [ f_phi U*R f64 | f_psi U*R f32 | mlp_parts 2*ceil(R'/64)*U*16 f32 |
-//              prefill: 4 staged rows U*D (4 bytes each) | lse, colsum U*P f64 | approx U*P f32, list U*P i32, count U i32 | slot_of U*P i32 | psi_all U*P*R f32 ],
+//              prefill: 4 staged rows U*D (4 bytes each) | lse U*G*P f64, colsum U*P f64 | approx U*P f32, list U*P i32, count U i32 | slot_of U*P i32 | psi_all U*P*R f32 ],
 // every part 256-byte aligned.
 struct Workspace {
   size_t off_fphi, off_fpsi, off_parts, off_stage, off_lse, off_colsum, off_approx, off_list, off_count, off_slot,
@@ -55,7 +55,7 @@ Workspace carve(const Shape &s, size_t P)
   w.off_fpsi = o; o = align_up(o + s.U * s.R * sizeof(float), 256);
   w.off_parts = o; o = align_up(o + 2 * (size_t)mlp_nparts((int)s.Rp) * s.U * 16 * sizeof(float), 256);
   w.off_stage = o; o = align_up(o + (P ? 4 * s.U * s.G * s.D * sizeof(float) : 0), 256);
-  w.off_lse = o; o = align_up(o + s.U * P * sizeof(double), 256);
+  w.off_lse = o; o = align_up(o + s.U * s.G * P * sizeof(double), 256);
   w.off_colsum = o; o = align_up(o + s.U * P * sizeof(double), 256);
   w.off_approx = o; o = align_up(o + s.U * P * sizeof(float), 256);
   w.off_list = o; o = align_up(o + s.U * P * sizeof(int32_t), 256);
@@ -256,7 +256,6 @@ int lessdec_prefill(const lessdec_desc *desc, const void *Q, const void *K, cons
     if (out && launch_prompt_rows(r, -1, P - 1, st) != hipSuccess) return LESSDEC_EHIP;
     return LESSDEC_OK;
   }
-  if (s.G > 1) return LESSDEC_EINVAL;     // several query heads per unit: only the stepwise form
   PrefillArgs a;
   a.d = desc; a.Q = Q; a.K = K; a.V = V; a.P = P; a.out = out;
   a.lse = reinterpret_cast<double *>(ws + w.off_lse);

@@ -164,9 +164,11 @@ __device__ inline void store_out(__half *orow, int g, const v4f (&O)[D / 16], fl
 // -------------------------------------------------------------------------------------
 template <typename T, int D>
 __global__ __launch_bounds__(64 * kPrefillWaves) void prefill_rowpass_kernel(
-    const T *__restrict__ Q, const T *__restrict__ K, const T *__restrict__ V, unsigned U, int P,
+    const T *__restrict__ Q, const T *__restrict__ K, const T *__restrict__ V, unsigned U, int G, int P,
     double *__restrict__ lse, T *__restrict__ out)
 {
+  // U counts query rows here: unit u's G query heads are rows u G .. u G + G - 1 of Q, out and
+  // lse, and attend over unit u's keys and values
   constexpr int CH = D / 4, DB = D / 16;
   constexpr bool kHalf = sizeof(T) == 2;
   constexpr int EPT = 16 * D / (64 * kPrefillWaves);      // tile elements widened per thread
@@ -184,7 +186,8 @@ __global__ __launch_bounds__(64 * kPrefillWaves) void prefill_rowpass_kernel(
   const int it_last = (grp + 1) * kPrefillWaves - 1 < nblk - 1 ? (grp + 1) * kPrefillWaves - 1 : nblk - 1;
   const int qi = it * 16 + c;
   const int qrow = qi < P ? qi : P - 1;
-  const T *Qu = Q + u * (size_t)P * D, *Ku = K + u * (size_t)P * D, *Vu = V + u * (size_t)P * D;
+  const size_t ukv = u / (unsigned)G;
+  const T *Qu = Q + u * (size_t)P * D, *Ku = K + ukv * (size_t)P * D, *Vu = V + ukv * (size_t)P * D;
   const double scale = 1.0 / sqrt((double)D);
 
   double qd[CH];
@@ -291,7 +294,7 @@ __global__ __launch_bounds__(64 * kPrefillWaves) void prefill_rowpass_kernel(
 template <typename T, int D>
 __global__ __launch_bounds__(64 * kPrefillWaves) void prefill_colpass_kernel(
     const T *__restrict__ Q, const T *__restrict__ K, unsigned U, int P,
-    const double *__restrict__ lse, double *__restrict__ colsum)
+    const double *__restrict__ lse, int G, double *__restrict__ colsum)
 {
   constexpr int CH = D / 4;
   const int nblk = (P + 15) / 16;
@@ -303,8 +306,7 @@ __global__ __launch_bounds__(64 * kPrefillWaves) void prefill_colpass_kernel(
   const int jt = grp * kPrefillWaves + (int)(threadIdx.x / 64);
   if (jt >= nblk || pb.u >= U) return;                    // wave-uniform; the waves share nothing
   const int j0 = jt * 16;
-  const T *Qu = Q + u * (size_t)P * D, *Ku = K + u * (size_t)P * D;
-  const double *lse_u = lse + u * (size_t)P;
+  const T *Ku = K + u * (size_t)P * D;
   const double scale = 1.0 / sqrt((double)D);
 
   double kd[CH];
@@ -316,6 +318,9 @@ __global__ __launch_bounds__(64 * kPrefillWaves) void prefill_colpass_kernel(
     for (int s = 0; s < CH; ++s) kd[s] = kraw.get(s);
   }
   double cs[4] = {0.0, 0.0, 0.0, 0.0};
+  for (int h = 0; h < G; ++h) {                           // the unit's query heads, one sweep each
+  const T *Qu = Q + (u * G + h) * (size_t)P * D;
+  const double *lse_u = lse + (u * G + h) * (size_t)P;
   Chunk<T, D> qraw;
   double lq;
   {
@@ -344,6 +349,7 @@ __global__ __launch_bounds__(64 * kPrefillWaves) void prefill_colpass_kernel(
     tile(it, qraw, lq, qother, lother);
     if (it + 1 < nblk) tile(it + 1, qother, lother, qraw, lq);
   }
+  }
 #pragma unroll
   for (int v = 0; v < 4; ++v) {
 #pragma unroll
@@ -366,7 +372,7 @@ constexpr int kApproxTiles = 4;    // key tiles (of 16) per wave: a query tile i
 template <int D>
 __global__ __launch_bounds__(64 * kPrefillWaves) void prefill_colapprox_kernel(
     const __half *__restrict__ Q, const __half *__restrict__ K, unsigned U, int P,
-    const double *__restrict__ lse, float *__restrict__ approx)
+    const double *__restrict__ lse, int G, float *__restrict__ approx)
 {
   constexpr int KS = D / 32, KT = kApproxTiles;
   const int nblk = (P + 15) / 16;
@@ -378,8 +384,7 @@ __global__ __launch_bounds__(64 * kPrefillWaves) void prefill_colapprox_kernel(
   const int kb = pb.grp * kPrefillWaves + (int)(threadIdx.x / 64);
   if (kb >= nkb || pb.u >= U) return;                     // wave-uniform; the waves share nothing
   const int jt0 = kb * KT, j0 = jt0 * 16;
-  const __half *Qu = Q + u * (size_t)P * D, *Ku = K + u * (size_t)P * D;
-  const double *lse_u = lse + u * (size_t)P;
+  const __half *Ku = K + u * (size_t)P * D;
   const float scale = (float)(1.0 / sqrt((double)D));
   auto load_row = [&](const __half *row, v8h (&dst)[KS]) {
 #pragma unroll
@@ -391,17 +396,20 @@ __global__ __launch_bounds__(64 * kPrefillWaves) void prefill_colapprox_kernel(
     const int kr = j0 + 16 * t + c;
     load_row(Ku + (size_t)(kr < P ? kr : P - 1) * D, ka[t]);
   }
+  float cs[KT][4];
+#pragma unroll
+  for (int t = 0; t < KT; ++t)
+#pragma unroll
+    for (int w = 0; w < 4; ++w) cs[t][w] = 0.f;
+  for (int h = 0; h < G; ++h) {                           // the unit's query heads, one sweep each
+  const __half *Qu = Q + (u * G + h) * (size_t)P * D;
+  const double *lse_u = lse + (u * G + h) * (size_t)P;
   float lq;
   {
     const int qr = j0 + c < P ? j0 + c : P - 1;
     load_row(Qu + (size_t)qr * D, qa);
     lq = (float)lse_u[qr];
   }
-  float cs[KT][4];
-#pragma unroll
-  for (int t = 0; t < KT; ++t)
-#pragma unroll
-    for (int w = 0; w < 4; ++w) cs[t][w] = 0.f;
   // one query tile: request the tile after it into `nxt`, then multiply `cur` (two buffers
   // that swap roles, so that no register copy has to wait for the request just made)
   auto tile = [&](int it, const v8h (&cur)[KS], float lcur, v8h (&nxt)[KS], float &lnxt) {
@@ -431,6 +439,7 @@ __global__ __launch_bounds__(64 * kPrefillWaves) void prefill_colapprox_kernel(
   for (int it = jt0; it < nblk; it += 2) {
     tile(it, qa, lq, qb, lb);
     if (it + 1 < nblk) tile(it + 1, qb, lb, qa, lq);
+  }
   }
 #pragma unroll
   for (int t = 0; t < KT; ++t)
@@ -511,7 +520,7 @@ __global__ __launch_bounds__(256) void prefill_compact_kernel(const int32_t *__r
 template <typename T, int D>
 __global__ __launch_bounds__(64 * kPrefillWaves) void prefill_colexact_kernel(
     const T *__restrict__ Q, const T *__restrict__ K, unsigned U, int P, const double *__restrict__ lse,
-    const int32_t *__restrict__ list, const int32_t *__restrict__ count, int blocks_per_unit,
+    const int32_t *__restrict__ list, const int32_t *__restrict__ count, int blocks_per_unit, int G,
     double *__restrict__ colsum)
 {
   constexpr int CH = D / 4;
@@ -521,8 +530,7 @@ __global__ __launch_bounds__(64 * kPrefillWaves) void prefill_colexact_kernel(
   const int l = threadIdx.x % 64, g = l / 16, c = l % 16;
   if (pb.u >= U) return;
   const int n = count[u];
-  const T *Qu = Q + u * (size_t)P * D, *Ku = K + u * (size_t)P * D;
-  const double *lse_u = lse + u * (size_t)P;
+  const T *Ku = K + u * (size_t)P * D;
   const double scale = 1.0 / sqrt((double)D);
   // tiles of 16 listed keys, dealt to the unit's waves in turn (the list is ascending, so
   // the long sweeps come first); wave-uniform, the waves share nothing
@@ -542,6 +550,9 @@ __global__ __launch_bounds__(64 * kPrefillWaves) void prefill_colexact_kernel(
     for (int v = 0; v < 4; ++v) kjv[v] = g + 4 * v < nk ? li[g + 4 * v] : INT_MAX;
     const int it0 = li[0] / 16;
     double cs[4] = {0.0, 0.0, 0.0, 0.0};
+    for (int h = 0; h < G; ++h) {                         // the unit's query heads, one sweep each
+    const T *Qu = Q + (u * G + h) * (size_t)P * D;
+    const double *lse_u = lse + (u * G + h) * (size_t)P;
     Chunk<T, D> qraw;
     double lq;
     {
@@ -569,6 +580,7 @@ __global__ __launch_bounds__(64 * kPrefillWaves) void prefill_colexact_kernel(
     for (int it = it0; it < nblk; it += 2) {
       tile(it, qraw, lq, qother, lother);
       if (it + 1 < nblk) tile(it + 1, qother, lother, qraw, lq);
+    }
     }
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
@@ -827,10 +839,11 @@ static hipError_t launch_prefill_t(const PrefillArgs &a, hipStream_t st)
   const lessdec_desc *d = a.d;
   const int P = a.P, C = d->n_heavy + d->n_recent;
   const unsigned U = (unsigned)d->batch * d->heads;
-  const unsigned grid = (U + kXcds - 1) / kXcds * kXcds *
-                        (unsigned)(((P + 15) / 16 + kPrefillWaves - 1) / kPrefillWaves);
-  prefill_rowpass_kernel<T, D><<<grid, 64 * kPrefillWaves, 0, st>>>((const T *)a.Q, (const T *)a.K,
-                                                                   (const T *)a.V, U, P, a.lse, (T *)a.out);
+  const int G = d->q_per_kv > 1 ? d->q_per_kv : 1;          // query heads per unit
+  const unsigned tiles = (unsigned)(((P + 15) / 16 + kPrefillWaves - 1) / kPrefillWaves);
+  const unsigned grid = (U + kXcds - 1) / kXcds * kXcds * tiles;
+  prefill_rowpass_kernel<T, D><<<(U * G + kXcds - 1) / kXcds * kXcds * tiles, 64 * kPrefillWaves, 0, st>>>(
+      (const T *)a.Q, (const T *)a.K, (const T *)a.V, U * G, G, P, a.lse, (T *)a.out);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   // Column sums and selection.  Exact sums are needed of the kept tokens (they become the
@@ -849,7 +862,7 @@ static hipError_t launch_prefill_t(const PrefillArgs &a, hipStream_t st)
                                (unsigned)((((P + 15) / 16 + kApproxTiles - 1) / kApproxTiles + kPrefillWaves - 1) /
                                           kPrefillWaves);
         prefill_colapprox_kernel<D><<<agrid, 64 * kPrefillWaves, 0, st>>>((const __half *)a.Q, (const __half *)a.K, U,
-                                                                         P, a.lse, a.approx);
+                                                                         P, a.lse, G, a.approx);
         if ((e = hipGetLastError()) != hipSuccess) return e;
       }
       prefill_band_kernel<<<rank_grid, 256, 0, st>>>(a.approx, P, d->n_heavy, d->n_recent, a.slot_of);
@@ -859,7 +872,7 @@ static hipError_t launch_prefill_t(const PrefillArgs &a, hipStream_t st)
     if ((e = hipGetLastError()) != hipSuccess) return e;
     const int bpu = (C + 32 + 16 * kPrefillWaves - 1) / (16 * kPrefillWaves);
     prefill_colexact_kernel<T, D><<<(U + kXcds - 1) / kXcds * kXcds * (unsigned)bpu, 64 * kPrefillWaves, 0, st>>>(
-        (const T *)a.Q, (const T *)a.K, U, P, a.lse, a.list, a.count, bpu, a.colsum);
+        (const T *)a.Q, (const T *)a.K, U, P, a.lse, a.list, a.count, bpu, G, a.colsum);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     if (!lambda) {
       prefill_refine_kernel<<<U, 256, 0, st>>>(a.colsum, a.slot_of, P, d->n_heavy, d->n_recent, a.list);
@@ -867,7 +880,7 @@ static hipError_t launch_prefill_t(const PrefillArgs &a, hipStream_t st)
     }
   } else {
     prefill_colpass_kernel<T, D><<<grid, 64 * kPrefillWaves, 0, st>>>((const T *)a.Q, (const T *)a.K, U, P,
-                                                                     a.lse, a.colsum);
+                                                                     a.lse, G, a.colsum);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     prefill_rank_kernel<<<rank_grid, 256, 0, st>>>(a.colsum, P, d->n_heavy, d->n_recent, lambda ? 1 : 0,
                                                    a.slot_of);

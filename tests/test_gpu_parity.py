@@ -180,9 +180,15 @@ def test_stepwise_prompt_is_the_generation_loop(kind):
         assert torch.equal(getattr(a, n), getattr(b, n)), n
 
 
-# Several query heads per key/value head (multi-query / grouped-query attention, Sec. 3.2): the
-# prompt is taken token by token (the one-shot prompt phase is not available for this form)
+# Several query heads per key/value head (multi-query / grouped-query attention, Sec. 3.2), with
+# the prompt taken token by token (flag 4) and in one shot
 GROUPS = [
+    (small("gqa-4-heads-one-shot-prompt", q_per_kv=4, prompt=70, steps=25), 0),
+    (small("gqa-2-heads-one-shot-prompt-f32", q_per_kv=2, dtype="f32", head_dim=64, rank=4, prompt=41, steps=20), 0),
+    (small("gqa-3-heads-one-shot-prompt-lambda", q_per_kv=3, n_heavy=4, n_recent=8, prompt=50, steps=15), 2),
+    (small("gqa-2-heads-one-shot-prompt-fits", q_per_kv=2, n_heavy=20, n_recent=20, prompt=25, steps=30), 0),
+    (small("gqa-8-heads-one-shot-long-prompt", q_per_kv=8, n_heavy=30, n_recent=30, prompt=300, steps=10, batch=1,
+           heads=2), 0),
     (small("mqa-4-heads", q_per_kv=4, prompt=30, steps=25), 4),
     (small("gqa-2-heads-f32-d64", q_per_kv=2, dtype="f32", head_dim=64, rank=4, prompt=30, steps=25), 4),
     (small("gqa-3-heads-lambda", q_per_kv=3, n_heavy=4, n_recent=8, prompt=30, steps=20), 6),
