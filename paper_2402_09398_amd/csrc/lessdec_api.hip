@@ -43,7 +43,7 @@ bool shape_ok(const lessdec_desc *d, Shape *s)
 //              prefill: 4 staged rows U*D (4 bytes each) | lse U*G*P f64, colsum U*P f64 | approx U*P f32, list U*P i32, count U i32 | slot_of U*P i32 | psi_all U*P*R f32 ],
 // every part 256-byte aligned.
 struct Workspace {
-  size_t off_fphi, off_fpsi, off_parts, off_stage, off_lse, off_colsum, off_approx, off_list, off_count, off_slot,
+  size_t off_fphi, off_fpsi, off_parts, off_gqa, off_stage, off_lse, off_colsum, off_approx, off_list, off_count, off_slot,
       off_psiall, total;
 };
 
@@ -54,6 +54,7 @@ Workspace carve(const Shape &s, size_t P)
   w.off_fphi = o; o = align_up(o + s.U * s.G * s.R * sizeof(double), 256);
   w.off_fpsi = o; o = align_up(o + s.U * s.R * sizeof(float), 256);
   w.off_parts = o; o = align_up(o + 2 * (size_t)mlp_nparts((int)s.Rp) * s.U * 16 * sizeof(float), 256);
+  w.off_gqa = o; o = align_up(o + (s.G > 1 ? s.U * gqa_head_blocks((long)s.U, (int)s.G) * (s.C + 2) * sizeof(double) : 0), 256);
   w.off_stage = o; o = align_up(o + (P ? 4 * s.U * s.G * s.D * sizeof(float) : 0), 256);
   w.off_lse = o; o = align_up(o + s.U * s.G * P * sizeof(double), 256);
   w.off_colsum = o; o = align_up(o + s.U * P * sizeof(double), 256);
@@ -96,7 +97,7 @@ StepArgs state_args(const lessdec_desc *desc, const Shape &s)
   a.pend_slot = desc->pend_slot; a.pend_v = desc->pend_v; a.pend_psi = desc->pend_psi;
   a.q = a.k = a.v = nullptr; a.out = nullptr; a.evicted_pos = nullptr;
   a.U = (int)s.U; a.Hh = desc->heads; a.B = desc->batch;
-  a.f_phi = nullptr; a.f_phi32 = nullptr; a.f_psi = nullptr; a.mlp_parts = nullptr;
+  a.f_phi = nullptr; a.f_phi32 = nullptr; a.f_psi = nullptr; a.mlp_parts = nullptr; a.gqa_parts = nullptr;
   a.Wk3 = desc->Wk3;
   return a;
 }
@@ -197,6 +198,7 @@ int lessdec_step_attend(const lessdec_desc *desc, const void *q, const void *k, 
     else
       a.f_phi = reinterpret_cast<double *>(ws + w.off_fphi);
     a.f_psi = reinterpret_cast<float *>(ws + w.off_fpsi);
+    a.gqa_parts = reinterpret_cast<double *>(ws + w.off_gqa);
     return launch_step_gqa(a, (int)s.G, desc->dtype, desc->head_dim, st) == hipSuccess ? LESSDEC_OK : LESSDEC_EHIP;
   }
   if (wpu_supported(desc->dtype, desc->head_dim, (int)s.C, desc->hidden, desc->rank)) {

@@ -30,10 +30,89 @@ __device__ inline double block_allreduce(double v, double *s_red, int tid, Op op
 
 // q, out: [U,G,D]; k, v: [U,D]; f_phi [U,G,R] fp64 or f_phi32 in fp32; f_psi: [U,R] fp32.
 // grid = U, block = 256, dynamic LDS: see launch_step_gqa_t.
+// After the last head: accumulated scores, eviction choice, fold of the discarded pair into
+// H, z (Eq. 4, Eq. 5), in-place insert of the new pair (Sec. 3.2).  s_inc holds the step's
+// probabilities per pair summed over the heads; s_e is scratch of the same size.
+template <typename T, int D>
+__device__ inline void gqa_finish_unit(const StepArgs &a, int u, int tid, double *s_e, const double *s_inc,
+                                       Cand *s_cand)
+{
+  const int C = a.C, R = a.R;
+  const int n = a.n_seen[u];
+  const int m = n < C ? n : C;
+  const int rows = m + 1;
+  const bool full = (m == C);
+  T *kc = reinterpret_cast<T *>(a.k_cache) + (size_t)u * C * D;
+  T *vc = reinterpret_cast<T *>(a.v_cache) + (size_t)u * C * D;
+  const T *kn = reinterpret_cast<const T *>(a.k) + (size_t)u * D;
+  const T *vn = reinterpret_cast<const T *>(a.v) + (size_t)u * D;
+  float *Hu = a.H + (size_t)u * R * D;
+  double *zu = a.z + (size_t)u * R;
+  // accumulated scores; eviction candidate of this thread's rows
+  const bool lambda = (a.flags & LESSDEC_FLAG_LAMBDA) != 0;
+  Cand best = cand_none();
+  for (int r = tid; r < rows; r += 256) {
+    double na = s_inc[r];
+    int pj = n;
+    if (r < m) {
+      na += a.acc[(size_t)u * C + r];
+      pj = a.pos[(size_t)u * C + r];
+    }
+    s_e[r] = na;
+    if (full) {
+      const bool is_cand = (r < m) ? (pj <= n - a.Nr && (!lambda || pj >= a.Nh)) : (a.Nr == 0);
+      const Cand cnd{lambda ? 0.0 : na, pj, r};
+      if (is_cand && cand_less(cnd, best)) best = cnd;
+    }
+  }
+  s_cand[tid] = best;
+  __syncthreads();
+  for (int o = 128; o > 0; o >>= 1) {
+    if (tid < o && cand_less(s_cand[tid + o], s_cand[tid])) s_cand[tid] = s_cand[tid + o];
+    __syncthreads();
+  }
+  const Cand win = s_cand[0];
+  const int eslot = full ? win.slot : -1;                    // eslot == m: the new pair itself
+  const bool evict = eslot >= 0;
+  const int ins_slot = full ? ((evict && eslot < m) ? eslot : -1) : m;
+
+  // fold of the discarded pair into H, z (Eq. 4, Eq. 5), before its row is overwritten
+  if (evict) {
+    const float *pe = eslot < m ? a.psi + ((size_t)u * C + eslot) * R : a.f_psi + (size_t)u * R;
+    if (tid < D) {
+      const double ve = (double)Store<T>::to_float(eslot < m ? vc[(size_t)eslot * D + tid] : vn[tid]);
+      for (int r = 0; r < R; ++r)
+        Hu[(size_t)r * D + tid] = (float)fma((double)pe[r], ve, (double)Hu[(size_t)r * D + tid]);
+    } else if (tid - D < R) {
+      zu[tid - D] += (double)pe[tid - D];
+    }
+  }
+  __syncthreads();
+  // scores of the pairs that stay, and the new pair into its slot (Sec. 3.2: in place)
+  for (int r = tid; r < m; r += 256)
+    if (r != ins_slot) a.acc[(size_t)u * C + r] = s_e[r];
+  if (ins_slot >= 0) {
+    if (tid < D) {
+      kc[(size_t)ins_slot * D + tid] = kn[tid];
+      vc[(size_t)ins_slot * D + tid] = vn[tid];
+    }
+    if (tid < R) a.psi[((size_t)u * C + ins_slot) * R + tid] = a.f_psi[(size_t)u * R + tid];
+    if (tid == 0) {
+      a.acc[(size_t)u * C + ins_slot] = s_e[m];
+      a.pos[(size_t)u * C + ins_slot] = n;
+    }
+  }
+  if (tid == 0) {
+    a.n_seen[u] = n + 1;
+    a.pend_slot[u] = -1;
+    if (a.evicted_pos) a.evicted_pos[u] = evict ? win.pos : -1;
+  }
+}
+
 // STAGE: the unit's key and value rows (and H, z) are copied into the LDS once and every head
 // works from there; without it each head reads them from memory again (any capacity).
 template <typename T, int D, bool STAGE>
-__global__ __launch_bounds__(256) void gqa_step_kernel(const StepArgs a, int G)
+__global__ __launch_bounds__(256) void gqa_step_kernel(const StepArgs a, int G, int nhb)
 {
   extern __shared__ double dyn[];
   __shared__ double s_red[4];
@@ -41,7 +120,9 @@ __global__ __launch_bounds__(256) void gqa_step_kernel(const StepArgs a, int G)
   __shared__ double s_num[256];
   constexpr int EPL = Store<T>::kPerVec, LPR = D / EPL, RPB = 256 / LPR;   // lanes per row, rows per pass
   using Vec = typename Store<T>::Vec;
-  const int u = (int)blockIdx.x, tid = threadIdx.x;
+  // nhb blocks per unit, each with a contiguous share of the unit's heads
+  const int u = (int)blockIdx.x / nhb, hb = (int)blockIdx.x % nhb, tid = threadIdx.x;
+  const int g_begin = (int)((long)G * hb / nhb), g_end = (int)((long)G * (hb + 1) / nhb);
   const int lr = tid % LPR, rb = tid / LPR;
   const int C = a.C, R = a.R;
   const int rows_cap = C + 2;
@@ -57,7 +138,6 @@ __global__ __launch_bounds__(256) void gqa_step_kernel(const StepArgs a, int G)
   const int n = a.n_seen[u];
   const int m = n < C ? n : C;             // live slots are 0..m-1 (slots fill in order)
   const int rows = m + 1;                  // + the appended pair (K', V' of Eq. 3)
-  const bool full = (m == C);
   T *kc = reinterpret_cast<T *>(a.k_cache) + (size_t)u * C * D;
   T *vc = reinterpret_cast<T *>(a.v_cache) + (size_t)u * C * D;
   const T *kn = reinterpret_cast<const T *>(a.k) + (size_t)u * D;
@@ -87,13 +167,13 @@ __global__ __launch_bounds__(256) void gqa_step_kernel(const StepArgs a, int G)
     const size_t i = ((size_t)u * G + g) * R + tid;
     return a.f_phi32 ? (double)a.f_phi32[i] : a.f_phi[i];
   };
-  double q_next = fetch_q(0), f_next = fetch_f(0);
+  double q_next = fetch_q(g_begin), f_next = fetch_f(g_begin);
   const double inv_sqrt_d = 1.0 / sqrt_d;
-  for (int g = 0; g < G; ++g) {
+  for (int g = g_begin; g < g_end; ++g) {
     __syncthreads();
     if (tid < D) s_q[tid] = q_next;
     if (tid < R) s_f[tid] = f_next;
-    if (g + 1 < G) {
+    if (g + 1 < g_end) {
       q_next = fetch_q(g + 1);
       f_next = fetch_f(g + 1);
     }
@@ -173,76 +253,57 @@ __global__ __launch_bounds__(256) void gqa_step_kernel(const StepArgs a, int G)
   }
   __syncthreads();
 
-  // accumulated scores; eviction candidate of this thread's rows
-  const bool lambda = (a.flags & LESSDEC_FLAG_LAMBDA) != 0;
-  Cand best = cand_none();
-  for (int r = tid; r < rows; r += 256) {
-    double na = s_inc[r];
-    int pj = n;
-    if (r < m) {
-      na += a.acc[(size_t)u * C + r];
-      pj = a.pos[(size_t)u * C + r];
-    }
-    s_e[r] = na;
-    if (full) {
-      const bool is_cand = (r < m) ? (pj <= n - a.Nr && (!lambda || pj >= a.Nh)) : (a.Nr == 0);
-      const Cand cnd{lambda ? 0.0 : na, pj, r};
-      if (is_cand && cand_less(cnd, best)) best = cnd;
-    }
+  if (nhb > 1) {
+    // the unit's heads are spread over nhb blocks: leave this block's sums for the finishing launch
+    double *part = a.gqa_parts + ((size_t)u * nhb + hb) * rows_cap;
+    for (int r = tid; r < rows; r += 256) part[r] = s_inc[r];
+    return;
   }
-  s_cand[tid] = best;
-  __syncthreads();
-  for (int o = 128; o > 0; o >>= 1) {
-    if (tid < o && cand_less(s_cand[tid + o], s_cand[tid])) s_cand[tid] = s_cand[tid + o];
-    __syncthreads();
-  }
-  const Cand win = s_cand[0];
-  const int eslot = full ? win.slot : -1;                    // eslot == m: the new pair itself
-  const bool evict = eslot >= 0;
-  const int ins_slot = full ? ((evict && eslot < m) ? eslot : -1) : m;
+  gqa_finish_unit<T, D>(a, u, tid, s_e, s_inc, s_cand);
+}
 
-  // fold of the discarded pair into H, z (Eq. 4, Eq. 5), before its row is overwritten
-  if (evict) {
-    const float *pe = eslot < m ? a.psi + ((size_t)u * C + eslot) * R : a.f_psi + (size_t)u * R;
-    if (tid < D) {
-      const double ve = (double)Store<T>::to_float(eslot < m ? vc[(size_t)eslot * D + tid] : vn[tid]);
-      for (int r = 0; r < R; ++r)
-        Hu[(size_t)r * D + tid] = (float)fma((double)pe[r], ve, (double)Hu[(size_t)r * D + tid]);
-    } else if (tid - D < R) {
-      zu[tid - D] += (double)pe[tid - D];
-    }
+// Finishing launch when a unit's heads were spread over several blocks: adds their sums in
+// block order and finishes the unit.   grid = U, block = 256, dynamic LDS = 2 (C + 2) doubles.
+template <typename T, int D>
+__global__ __launch_bounds__(256) void gqa_finish_kernel(const StepArgs a, int nhb)
+{
+  extern __shared__ double dyn[];
+  __shared__ Cand s_cand[256];
+  const int u = (int)blockIdx.x, tid = threadIdx.x;
+  const int rows_cap = a.C + 2;
+  double *s_e = dyn, *s_inc = dyn + rows_cap;
+  const int n = a.n_seen[u];
+  const int rows = (n < a.C ? n : a.C) + 1;
+  for (int r = tid; r < rows; r += 256) {
+    double v = 0.0;
+    for (int hb = 0; hb < nhb; ++hb) v += a.gqa_parts[((size_t)u * nhb + hb) * rows_cap + r];
+    s_inc[r] = v;
   }
   __syncthreads();
-  // scores of the pairs that stay, and the new pair into its slot (Sec. 3.2: in place)
-  for (int r = tid; r < m; r += 256)
-    if (r != ins_slot) a.acc[(size_t)u * C + r] = s_e[r];
-  if (ins_slot >= 0) {
-    if (tid < D) {
-      kc[(size_t)ins_slot * D + tid] = kn[tid];
-      vc[(size_t)ins_slot * D + tid] = vn[tid];
-    }
-    if (tid < R) a.psi[((size_t)u * C + ins_slot) * R + tid] = a.f_psi[(size_t)u * R + tid];
-    if (tid == 0) {
-      a.acc[(size_t)u * C + ins_slot] = s_e[m];
-      a.pos[(size_t)u * C + ins_slot] = n;
-    }
-  }
-  if (tid == 0) {
-    a.n_seen[u] = n + 1;
-    a.pend_slot[u] = -1;
-    if (a.evicted_pos) a.evicted_pos[u] = evict ? win.pos : -1;
-  }
+  gqa_finish_unit<T, D>(a, u, tid, s_e, s_inc, s_cand);
+}
+
+// Blocks per unit: one when the units alone fill the chip, else the heads are spread over up
+// to kGqaMaxHeadBlocks blocks (the cache rows are then staged once per block).
+int gqa_head_blocks(long units, int G)
+{
+  int nhb = (int)((512 + units - 1) / units);          // measured: 512 units x 8 heads lose with a split
+  if (nhb > kGqaMaxHeadBlocks) nhb = kGqaMaxHeadBlocks;
+  if (nhb > G) nhb = G;
+  return nhb < 1 ? 1 : nhb;
 }
 
 template <typename T, int D>
 static hipError_t launch_step_gqa_t(const StepArgs &a, int G, hipStream_t st)
 {
+  const int nhb = gqa_head_blocks(a.U, G);
   const size_t base = (size_t)(2 * (a.C + 2) + D + 64 + 64) * sizeof(double);
   const size_t staged = base + (size_t)a.R * D * sizeof(float) + 2 * (size_t)(a.C + 1) * D * sizeof(T);
   if (staged <= 64 * 1024)
-    gqa_step_kernel<T, D, true><<<a.U, 256, staged, st>>>(a, G);
+    gqa_step_kernel<T, D, true><<<a.U * nhb, 256, staged, st>>>(a, G, nhb);
   else
-    gqa_step_kernel<T, D, false><<<a.U, 256, base, st>>>(a, G);
+    gqa_step_kernel<T, D, false><<<a.U * nhb, 256, base, st>>>(a, G, nhb);
+  if (nhb > 1) gqa_finish_kernel<T, D><<<a.U, 256, (size_t)2 * (a.C + 2) * sizeof(double), st>>>(a, nhb);
   return hipGetLastError();
 }
 

@@ -67,6 +67,7 @@ struct StepArgs {
   // generic path: feature maps of this step's q and k from the launches before it
   const double *f_phi;   // [U,R] ([U,G,R] with several query heads per unit)
   const float *f_phi32;  // the same in fp32 from the matrix-core feature maps, or NULL
+  double *gqa_parts;     // [U, head blocks, C+2] a step's probability sums per block of heads
   const float *f_psi;    // [U,R]
   // wave-per-unit path: layer-2 sums of both feature maps by parts (launch_mlp_parts), and W3
   const float *mlp_parts;
@@ -75,6 +76,8 @@ struct StepArgs {
 hipError_t launch_step(const StepArgs &a, int dtype, int D, hipStream_t st);
 // several query heads per unit: q, out [U,G,D], f_phi [U,G,R]
 hipError_t launch_step_gqa(const StepArgs &a, int G, int dtype, int D, hipStream_t st);
+constexpr int kGqaMaxHeadBlocks = 8;
+int gqa_head_blocks(long units, int G);
 hipError_t launch_state_sync(const StepArgs &a, int dtype, int D, hipStream_t st);
 
 // One wave per unit, K and V streamed through a register ring (lessdec_wpu.hip).

@@ -189,6 +189,8 @@ GROUPS = [
     (small("gqa-2-heads-one-shot-prompt-fits", q_per_kv=2, n_heavy=20, n_recent=20, prompt=25, steps=30), 0),
     (small("gqa-8-heads-one-shot-long-prompt", q_per_kv=8, n_heavy=30, n_recent=30, prompt=300, steps=10, batch=1,
            heads=2), 0),
+    # 512 units: every unit's heads in one block (fewer units spread them over several blocks)
+    (small("gqa-2-heads-many-units", q_per_kv=2, batch=32, heads=16, prompt=20, steps=10, hidden=64), 0),
     (small("mqa-4-heads", q_per_kv=4, prompt=30, steps=25), 4),
     (small("gqa-2-heads-f32-d64", q_per_kv=2, dtype="f32", head_dim=64, rank=4, prompt=30, steps=25), 4),
     (small("gqa-3-heads-lambda", q_per_kv=3, n_heavy=4, n_recent=8, prompt=30, steps=20), 6),
