@@ -157,11 +157,11 @@ int lessdec_step_features(const lessdec_desc *desc, const void *q, const void *k
     fm.Hh = desc->heads * (int)s.G;                     // q rows [B,Hh,G]: query head h G + g
     fm.x = (const __half *)q; fm.W1 = (const __half *)desc->Wq1; fm.W2 = (const __half *)desc->Wq2;
     fm.W3 = nullptr; fm.out = reinterpret_cast<float *>(ws + w.off_fphi);
-    if (launch_mlp(fm, st) != hipSuccess) return LESSDEC_EHIP;
-    fm.Hh = desc->heads;
-    fm.x = (const __half *)k; fm.W1 = (const __half *)desc->Wk1; fm.W2 = (const __half *)desc->Wk2;
-    fm.W3 = (const __half *)desc->Wk3; fm.out = reinterpret_cast<float *>(ws + w.off_fpsi);
-    return launch_mlp(fm, st) == hipSuccess ? LESSDEC_OK : LESSDEC_EHIP;
+    MlpArgs fk = fm;
+    fk.Hh = desc->heads;
+    fk.x = (const __half *)k; fk.W1 = (const __half *)desc->Wk1; fk.W2 = (const __half *)desc->Wk2;
+    fk.W3 = (const __half *)desc->Wk3; fk.out = reinterpret_cast<float *>(ws + w.off_fpsi);
+    return launch_mlp_pair(fm, fk, st) == hipSuccess ? LESSDEC_OK : LESSDEC_EHIP;
   }
   // general path: phi(q), psi(k) in fp64
   FeatmapArgs fa;

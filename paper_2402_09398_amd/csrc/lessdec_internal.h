@@ -30,6 +30,7 @@ struct MlpArgs {
 };
 bool mlp_mfma_supported(int dtype, int D, int Rp, int R);
 hipError_t launch_mlp(const MlpArgs &a, hipStream_t st);
+hipError_t launch_mlp_pair(const MlpArgs &a, const MlpArgs &b, hipStream_t st);   // both in one launch (same D, R', R)
 
 // Both feature maps of one decode step, up to the layer-2 sums: phi of q and psi of k for
 // every unit, the hidden units split into parts of kMlpPartHidden.  out[((map * nparts +

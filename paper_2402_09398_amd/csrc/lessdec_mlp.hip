@@ -12,13 +12,13 @@ namespace lessdec {
 // the 64 x 16 outputs (activation, W3, absolute value) in fp64.
 constexpr int kPsiTiles = 4;
 template <int D>
-__global__ __launch_bounds__(256) void mlp_psi_kernel(const MlpArgs a)
+__device__ inline void mlp_psi_block(const MlpArgs &a, unsigned bid)
 {
   __shared__ float s_red[4][16][16 * kPsiTiles + 1];       // [wave][r][row]
   __shared__ double s_h2[16 * kPsiTiles][17];              // [row][r]
   const int tid = threadIdx.x, wave = tid / 64, l = tid % 64, g = l / 16, c = l % 16;
   const int Hh = a.Hh, Rp = a.Rp, R = a.R;
-  const int h = blockIdx.x % Hh, chunk = blockIdx.x / Hh;
+  const int h = bid % Hh, chunk = bid / Hh;
   const __half *W1 = a.W1 + (size_t)h * Rp * D;
   const __half *W2 = a.W2 + (size_t)h * R * Rp;
   const long rows_head = (long)a.B * a.rpu;
@@ -65,6 +65,20 @@ __global__ __launch_bounds__(256) void mlp_psi_kernel(const MlpArgs a)
       a.out[(size_t)global_row(i) * R + r] = (float)fabs(acc3);
     }
   }
+}
+
+template <int D>
+__global__ __launch_bounds__(256) void mlp_psi_kernel(const MlpArgs a)
+{
+  mlp_psi_block<D>(a, blockIdx.x);
+}
+// two maps in one launch (phi of the queries and psi of the keys of a multi-head decode step):
+// the first na blocks work on a, the rest on b
+template <int D>
+__global__ __launch_bounds__(256) void mlp_pair_kernel(const MlpArgs a, const MlpArgs b, unsigned na)
+{
+  if (blockIdx.x < na) mlp_psi_block<D>(a, blockIdx.x);
+  else mlp_psi_block<D>(b, blockIdx.x - na);
 }
 
 // Decode step: both maps for every unit, by parts of 64 hidden units.  One block = one
@@ -121,6 +135,15 @@ hipError_t launch_mlp(const MlpArgs &a, hipStream_t st)
   const unsigned grid = (unsigned)(((rows_head + 16 * kPsiTiles - 1) / (16 * kPsiTiles)) * a.Hh);
   if (a.D == 128) mlp_psi_kernel<128><<<grid, 256, 0, st>>>(a);
   else mlp_psi_kernel<64><<<grid, 256, 0, st>>>(a);
+  return hipGetLastError();
+}
+
+hipError_t launch_mlp_pair(const MlpArgs &a, const MlpArgs &b, hipStream_t st)
+{
+  const unsigned na = (unsigned)((((long)a.B * a.rpu + 16 * kPsiTiles - 1) / (16 * kPsiTiles)) * a.Hh);
+  const unsigned nb = (unsigned)((((long)b.B * b.rpu + 16 * kPsiTiles - 1) / (16 * kPsiTiles)) * b.Hh);
+  if (a.D == 128) mlp_pair_kernel<128><<<na + nb, 256, 0, st>>>(a, b, na);
+  else mlp_pair_kernel<64><<<na + nb, 256, 0, st>>>(a, b, na);
   return hipGetLastError();
 }
 
