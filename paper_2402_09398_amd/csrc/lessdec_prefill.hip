@@ -102,7 +102,7 @@ __device__ inline void store_out(float *orow, int g, const v4f (&O)[D / 16], flo
 template <int D>
 struct VTile {
   static constexpr int NB = D / 16;                      // blocks = halves per lane per key row
-  _Float16 h[4][NB];
+  unsigned d[4][NB / 2];                                 // key row w: NB halves in NB / 2 dwords
   __device__ inline void load(const __half *Vu, int P, int j0, int g, int c)
   {
 #pragma unroll
@@ -110,11 +110,23 @@ struct VTile {
       const int kj = j0 + g + 4 * w;
       const __half *src = Vu + (size_t)(kj < P ? kj : P - 1) * D + NB * c;
       if constexpr (NB == 8) {
-        *reinterpret_cast<uint4 *>(h[w]) = *reinterpret_cast<const uint4 *>(src);
+        const uint4 t = *reinterpret_cast<const uint4 *>(src);
+        d[w][0] = t.x; d[w][1] = t.y; d[w][2] = t.z; d[w][3] = t.w;
       } else {
-        *reinterpret_cast<uint2 *>(h[w]) = *reinterpret_cast<const uint2 *>(src);
+        const uint2 t = *reinterpret_cast<const uint2 *>(src);
+        d[w][0] = t.x; d[w][1] = t.y;
       }
     }
+  }
+  // the operand of block b: element b of the four key rows, picked out of the dwords with byte
+  // permutes (an array indexed per element would make a round trip through scratch memory)
+  __device__ inline v4h operand(int b) const
+  {
+    typedef unsigned u2v __attribute__((ext_vector_type(2)));
+    const unsigned sel = (b & 1) ? 0x07060302u : 0x05040100u;
+    const u2v r = {__builtin_amdgcn_perm(d[1][b / 2], d[0][b / 2], sel),
+                   __builtin_amdgcn_perm(d[3][b / 2], d[2][b / 2], sel)};
+    return __builtin_bit_cast(v4h, r);
   }
 };
 template <int D>
@@ -130,7 +142,7 @@ __device__ inline void tile_pv(const VTile<D> &vt, const double (&e)[4], v4f (&O
   }
 #pragma unroll
   for (int b = 0; b < D / 16; ++b) {
-    const v4h a = {vt.h[0][b], vt.h[1][b], vt.h[2][b], vt.h[3][b]};
+    const v4h a = vt.operand(b);
     O[b] = __builtin_amdgcn_mfma_f32_16x16x16f16(a, ph, O[b], 0, 0, 0);
     O[b] = __builtin_amdgcn_mfma_f32_16x16x16f16(a, pl, O[b], 0, 0, 0);
   }
