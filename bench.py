@@ -42,22 +42,26 @@ def algorithmic_bytes_per_unit_step(w) -> float:
     the step's rows in and out, the H2O scores and positions, the low-rank state read and
     written, and the per-head feature-map weights shared by the batch rows."""
     e = 2 if w.dtype == "f16" else 4
-    C, D, R, Rp, B = w.capacity, w.head_dim, w.rank, w.hidden, w.batch
+    C, D, R, Rp, B, G = w.capacity, w.head_dim, w.rank, w.hidden, w.batch, w.q_per_kv
     kv = 2 * C * D * e                       # every retained key and value once
-    io = 3 * D * e + D * e + 2 * D * e       # q,k,v in; out; the inserted pair
+    io = (G + 2) * D * e + G * D * e + 2 * D * e   # q (G heads), k, v in; out (G heads); the inserted pair
     scores = 2 * 8 * C + 4 * C + 4           # acc (fp64) read+write, pos read, one pos write
     state = 2 * (R * D * 4 + R * 8)          # H (fp32) and z (fp64) read + write
     psi = 2 * R * 4                          # psi of the discarded pair read, of the new pair written
-    weights = (2 * (D * Rp + Rp * R) + R * R) * e / B   # per-head weights shared by the batch rows
-    return kv + io + scores + state + psi + weights
+    return kv + io + scores + state + psi + _weight_bytes_per_unit_step(w)
+
+
+def _weight_bytes_per_unit_step(w) -> float:
+    """Per-head feature-map weights (phi per query head, psi per key/value head), shared by the batch rows."""
+    e = 2 if w.dtype == "f16" else 4
+    D, R, Rp, B, G = w.head_dim, w.rank, w.hidden, w.batch, w.q_per_kv
+    return ((G + 1) * (D * Rp + Rp * R) + R * R) * e / B
 
 
 def attend_bytes_per_unit_step(w) -> float:
     """The same figure for the attention launch alone: everything except the weights, which
     only the feature-map launch reads."""
-    e = 2 if w.dtype == "f16" else 4
-    D, R, Rp, B = w.head_dim, w.rank, w.hidden, w.batch
-    return algorithmic_bytes_per_unit_step(w) - (2 * (D * Rp + Rp * R) + R * R) * e / B
+    return algorithmic_bytes_per_unit_step(w) - _weight_bytes_per_unit_step(w)
 
 
 def log(*a):
@@ -72,7 +76,7 @@ def cpu_baseline(w, n_units, n_steps):
     inp = wl.all_inputs(w.scaled(steps=n_steps), units, workers=16)
     W = wl.head_weights(w)
     st = lo.OracleState(n_units, w.heads, w.head_dim, w.n_heavy, w.n_recent, w.rank, w.hidden, W,
-                        head_of_unit=[u % w.heads for u in units])
+                        head_of_unit=[u % w.heads for u in units], q_per_kv=w.q_per_kv)
     t0 = time.perf_counter()
     st.prefill(inp["Q"], inp["K"], inp["V"], want_out=False)
     t_prefill = time.perf_counter() - t0
@@ -94,6 +98,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=128)
     ap.add_argument("--cfg", type=int, default=3, help="workload (1..5), default the batch-64 Llama-2-7B shape")
     ap.add_argument("--layers", type=int, default=8, help="independent layer states cycled round-robin")
+    ap.add_argument("--q-per-kv", type=int, default=1,
+                    help="G > 1: the workload's heads become heads/G key/value heads with G query heads each "
+                         "(multi-query / grouped-query attention); a different workload than the headline one")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-units", type=int, default=1024)
     ap.add_argument("--cpu-steps", type=int, default=512)
@@ -110,6 +117,10 @@ def main():
         sys.exit("bench.py: no GPU visible")
     dev = torch.device("cuda:0")
     w = wl.WORKLOADS[args.cfg]
+    if args.q_per_kv > 1:
+        if w.heads % args.q_per_kv:
+            sys.exit(f"bench.py: --q-per-kv must divide the workload's {w.heads} heads")
+        w = w.scaled(name=f"{w.name}-gqa{args.q_per_kv}", heads=w.heads // args.q_per_kv, q_per_kv=args.q_per_kv)
     L = args.layers
     U, D, T = w.units, w.head_dim, w.steps
 
@@ -118,7 +129,7 @@ def main():
     log(f"[bench] inputs for {U} units generated in {time.perf_counter() - t0:.1f} s")
     W = pack_weights(wl.head_weights(w), dev)
     layers = [LessDec(w.batch, w.heads, D, w.n_heavy, w.n_recent, w.rank, w.hidden, w.dtype, W,
-                      max_prompt=w.prompt if i == 0 else 0, device=dev) for i in range(L)]
+                      max_prompt=w.prompt if i == 0 else 0, device=dev, q_per_kv=w.q_per_kv) for i in range(L)]
     Q, K, V = (torch.from_numpy(inp[k]).to(dev) for k in ("Q", "K", "V"))
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -141,7 +152,7 @@ def main():
             getattr(lay, n).copy_(getattr(layers[0], n))
     q, k, v = (torch.from_numpy(inp[n]).to(dev) for n in ("q", "k", "v"))      # [T,U,D]
     del inp
-    outs = [torch.empty((U, D), dtype=layers[0].tdtype, device=dev) for _ in range(L)]
+    outs = [torch.empty(q.shape[1:], dtype=layers[0].tdtype, device=dev) for _ in range(L)]
     torch.cuda.synchronize()
 
     def run(first, count):
@@ -198,7 +209,8 @@ def main():
         "dtype": "f16 storage, f64 scores / f32 values",
         "data": "synthetic",
         "config": {"workload": f"cfg{w.cfg} {w.name}: batch {w.batch} x heads {w.heads} x head_dim {D}, "
-                               f"prompt {w.prompt}, {w.n_heavy}+{w.n_recent} slots, rank {w.rank}, hidden {w.hidden}",
+                               f"prompt {w.prompt}, {w.n_heavy}+{w.n_recent} slots, rank {w.rank}, hidden {w.hidden}"
+                               + (f", {w.q_per_kv} query heads per head" if w.q_per_kv > 1 else ""),
                    "layers_cycled": L, "prefill_ms": prefill_ms},
         # the prompt phase (secondary path), one warm call: algorithmic flops against the fp64 matrix peak
         "prefill": {"ms": prefill_ms, "prompt_tokens_per_s": U * w.prompt / (prefill_ms * 1e-3),
@@ -212,7 +224,7 @@ def main():
         "roofline": {"bound": "hbm", "achieved": attend_achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": attend_achieved / HBM_PEAK_GBS,
                      "traffic": MEASURED_TRAFFIC_BYTES.get(w.cfg) if L >= 8 else None,
-                     "kernel": "wpu_step_kernel (lessdec_step_attend)",
+                     "kernel": ("wpu_step_kernel" if w.q_per_kv == 1 else "gqa_step_kernel") + " (lessdec_step_attend)",
                      "bytes_per_launch": attend_bytes, "ms_per_launch": half_ms[True],
                      "features_ms_per_launch": half_ms[False],
                      "whole_step": {"achieved": achieved, "frac": achieved / HBM_PEAK_GBS,
