@@ -5,17 +5,18 @@
 
 namespace lessdec {
 
-// One block = 64 rows that share a head, as four tiles of 16 (head fastest in blockIdx: with
+// One block = 16 kTiles rows that share a head, as kTiles tiles of 16 (head fastest in blockIdx: with
 // Hh a multiple of 8 every block of a head lands on the same XCD and shares its L2 copy of the
 // weights).  The four waves split the groups of 32 hidden units and apply each loaded weight
-// tile to all four row tiles, add their layer-2 sums through the LDS, and 256 threads finish
-// the 64 x 16 outputs (activation, W3, absolute value) in fp64.
-constexpr int kPsiTiles = 4;
-template <int D>
+// tile to all the row tiles, add their layer-2 sums through the LDS, and 256 threads finish
+// the rows x 16 outputs (activation, W3, absolute value) in fp64.
+constexpr int kPsiTiles = 4;      // prompt phase: 64 rows per block
+constexpr int kPairTiles = 1;     // decode step: 16 rows per block, so that a batch of 64 fills more of the chip
+template <int D, int kTiles>
 __device__ inline void mlp_psi_block(const MlpArgs &a, unsigned bid)
 {
-  __shared__ float s_red[4][16][16 * kPsiTiles + 1];       // [wave][r][row]
-  __shared__ double s_h2[16 * kPsiTiles][17];              // [row][r]
+  __shared__ float s_red[4][16][16 * kTiles + 1];       // [wave][r][row]
+  __shared__ double s_h2[16 * kTiles][17];              // [row][r]
   const int tid = threadIdx.x, wave = tid / 64, l = tid % 64, g = l / 16, c = l % 16;
   const int Hh = a.Hh, Rp = a.Rp, R = a.R;
   const int h = bid % Hh, chunk = bid / Hh;
@@ -26,35 +27,35 @@ __device__ inline void mlp_psi_block(const MlpArgs &a, unsigned bid)
     const long bb = i / a.rpu, p = i % a.rpu;
     return (bb * Hh + h) * (long)a.rpu + p;
   };
-  v8h bx[kPsiTiles][D / 32];
+  v8h bx[kTiles][D / 32];
 #pragma unroll
-  for (int t = 0; t < kPsiTiles; ++t) {
-    const long i = ((long)chunk * kPsiTiles + t) * 16 + c;
+  for (int t = 0; t < kTiles; ++t) {
+    const long i = ((long)chunk * kTiles + t) * 16 + c;
     mlp_load_row<D>(a.x + (i < rows_head ? global_row(i) : 0) * D, g, bx[t]);   // padding: any row
   }
-  v4f c2[kPsiTiles];
+  v4f c2[kTiles];
 #pragma unroll
-  for (int t = 0; t < kPsiTiles; ++t) c2[t] = v4f{0.f, 0.f, 0.f, 0.f};
+  for (int t = 0; t < kTiles; ++t) c2[t] = v4f{0.f, 0.f, 0.f, 0.f};
   for (int grp = wave; grp < Rp / 32; grp += 4) {
     const MlpTiles<D> w = mlp_load_tiles<D>(W1, W2, Rp, R, 32 * grp, g, c);
 #pragma unroll
-    for (int t = 0; t < kPsiTiles; ++t) mlp_apply_tiles<D>(w, bx[t], c2[t]);
+    for (int t = 0; t < kTiles; ++t) mlp_apply_tiles<D>(w, bx[t], c2[t]);
   }
 #pragma unroll
-  for (int t = 0; t < kPsiTiles; ++t)
+  for (int t = 0; t < kTiles; ++t)
 #pragma unroll
     for (int w = 0; w < 4; ++w) s_red[wave][4 * g + w][16 * t + c] = c2[t][w];
   __syncthreads();
   const int r = tid % 16;
-  for (int row = tid / 16; row < 16 * kPsiTiles; row += 16) {
+  for (int row = tid / 16; row < 16 * kTiles; row += 16) {
     const float sum = ((s_red[0][r][row] + s_red[1][r][row]) + s_red[2][r][row]) + s_red[3][r][row];
     s_h2[row][r] = (r < R) ? gelu_poly_f64((double)sum) : 0.0;
   }
   __syncthreads();
   // W3 == nullptr: the map has no third matrix (phi, Eq. 1)
   const __half *W3 = a.W3 ? a.W3 + ((size_t)h * R + (r < R ? r : 0)) * R : nullptr;
-  for (int row = tid / 16; row < 16 * kPsiTiles; row += 16) {
-    const long i = (long)chunk * (16 * kPsiTiles) + row;
+  for (int row = tid / 16; row < 16 * kTiles; row += 16) {
+    const long i = (long)chunk * (16 * kTiles) + row;
     if (r < R && i < rows_head) {
       double acc3 = 0.0;
       if (W3 != nullptr) {
@@ -70,15 +71,15 @@ __device__ inline void mlp_psi_block(const MlpArgs &a, unsigned bid)
 template <int D>
 __global__ __launch_bounds__(256) void mlp_psi_kernel(const MlpArgs a)
 {
-  mlp_psi_block<D>(a, blockIdx.x);
+  mlp_psi_block<D, kPsiTiles>(a, blockIdx.x);
 }
 // two maps in one launch (phi of the queries and psi of the keys of a multi-head decode step):
 // the first na blocks work on a, the rest on b
 template <int D>
 __global__ __launch_bounds__(256) void mlp_pair_kernel(const MlpArgs a, const MlpArgs b, unsigned na)
 {
-  if (blockIdx.x < na) mlp_psi_block<D>(a, blockIdx.x);
-  else mlp_psi_block<D>(b, blockIdx.x - na);
+  if (blockIdx.x < na) mlp_psi_block<D, kPairTiles>(a, blockIdx.x);
+  else mlp_psi_block<D, kPairTiles>(b, blockIdx.x - na);
 }
 
 // Decode step: both maps for every unit, by parts of 64 hidden units.  One block = one
@@ -140,8 +141,8 @@ hipError_t launch_mlp(const MlpArgs &a, hipStream_t st)
 
 hipError_t launch_mlp_pair(const MlpArgs &a, const MlpArgs &b, hipStream_t st)
 {
-  const unsigned na = (unsigned)((((long)a.B * a.rpu + 16 * kPsiTiles - 1) / (16 * kPsiTiles)) * a.Hh);
-  const unsigned nb = (unsigned)((((long)b.B * b.rpu + 16 * kPsiTiles - 1) / (16 * kPsiTiles)) * b.Hh);
+  const unsigned na = (unsigned)((((long)a.B * a.rpu + 16 * kPairTiles - 1) / (16 * kPairTiles)) * a.Hh);
+  const unsigned nb = (unsigned)((((long)b.B * b.rpu + 16 * kPairTiles - 1) / (16 * kPairTiles)) * b.Hh);
   if (a.D == 128) mlp_pair_kernel<128><<<na + nb, 256, 0, st>>>(a, b, na);
   else mlp_pair_kernel<64><<<na + nb, 256, 0, st>>>(a, b, na);
   return hipGetLastError();
