@@ -40,14 +40,14 @@ bool shape_ok(const lessdec_desc *d, Shape *s)
 }
 
 // Workspace: [ f_phi U*R f64 | f_psi U*R f32 | mlp_parts 2*ceil(R'/64)*U*16 f32 |
-//              prefill: 4 staged rows U*D (4 bytes each) | lse U*G*P f64, colsum U*P f64 | approx U*P f32, list U*P i32, count U i32 | slot_of U*P i32 | psi_all U*P*R f32 ],
+//              prefill: 4 staged rows U*D (4 bytes each) | lse U*G*P f64, colsum U*P f64 | approx U*P f32, list U*P i32, count U i32 | slot_of U*P i32 | psi_all U*P*R f32 | phi_all U*G*P*R f32 (masked prompt only) ],
 // every part 256-byte aligned.
 struct Workspace {
   size_t off_fphi, off_fpsi, off_parts, off_gqa, off_stage, off_lse, off_colsum, off_approx, off_list, off_count, off_slot,
-      off_psiall, total;
+      off_psiall, off_phiall, total;
 };
 
-Workspace carve(const Shape &s, size_t P)
+Workspace carve(const Shape &s, size_t P, unsigned flags)
 {
   Workspace w;
   size_t o = 0;
@@ -63,6 +63,9 @@ Workspace carve(const Shape &s, size_t P)
   w.off_count = o; o = align_up(o + (P ? s.U * sizeof(int32_t) : 0), 256);
   w.off_slot = o; o = align_up(o + s.U * P * sizeof(int32_t), 256);
   w.off_psiall = o; o = align_up(o + s.U * P * s.R * sizeof(float), 256);
+  // phi of every prompt query: only for Lambda-masking taken through the prompt token by token
+  const bool masked = (flags & LESSDEC_FLAG_LAMBDA) && (flags & LESSDEC_FLAG_PROMPT_STEPWISE);
+  w.off_phiall = o; o = align_up(o + (masked ? s.U * s.G * P * s.R * sizeof(float) : 0), 256);
   w.total = o;
   return w;
 }
@@ -83,7 +86,7 @@ int check_desc(const lessdec_desc *d, Shape *s, size_t P)
       !aligned(d->Wk2, 16) || !aligned(d->Wk3, 4))
     return LESSDEC_EINVAL;
   if (!d->workspace || !aligned(d->workspace, 256)) return LESSDEC_EWORKSPACE;
-  if (d->workspace_bytes < carve(*s, P).total) return LESSDEC_EWORKSPACE;
+  if (d->workspace_bytes < carve(*s, P, d->flags).total) return LESSDEC_EWORKSPACE;
   return LESSDEC_OK;
 }
 
@@ -110,7 +113,7 @@ size_t lessdec_workspace_bytes(const lessdec_desc *desc, int32_t max_prompt)
 {
   Shape s;
   if (!shape_ok(desc, &s) || max_prompt < 0) return 0;
-  return carve(s, (size_t)max_prompt).total;
+  return carve(s, (size_t)max_prompt, desc->flags).total;
 }
 
 int lessdec_state_reset(const lessdec_desc *desc, void *hip_stream)
@@ -138,7 +141,7 @@ int lessdec_step_features(const lessdec_desc *desc, const void *q, const void *k
   if (rc) return rc;
   if (!q || !k || !aligned(q, 16) || !aligned(k, 16)) return LESSDEC_EINVAL;
   hipStream_t st = (hipStream_t)hip_stream;
-  const Workspace w = carve(s, 0);
+  const Workspace w = carve(s, 0, desc->flags);
   char *ws = static_cast<char *>(desc->workspace);
   if (s.G == 1 && wpu_supported(desc->dtype, desc->head_dim, (int)s.C, desc->hidden, desc->rank)) {
     // matrix-core feature maps up to the layer-2 sums
@@ -190,7 +193,7 @@ int lessdec_step_attend(const lessdec_desc *desc, const void *q, const void *k, 
   hipStream_t st = (hipStream_t)hip_stream;
   StepArgs a = state_args(desc, s);
   a.q = q; a.k = k; a.v = v; a.out = out; a.evicted_pos = evicted_pos;
-  const Workspace w = carve(s, 0);
+  const Workspace w = carve(s, 0, desc->flags);
   char *ws = static_cast<char *>(desc->workspace);
   if (s.G > 1) {
     if (mlp_mfma_supported(desc->dtype, desc->head_dim, desc->hidden, desc->rank))
@@ -236,9 +239,13 @@ int lessdec_prefill(const lessdec_desc *desc, const void *Q, const void *K, cons
   if (!Q || !K || !V) return LESSDEC_EINVAL;
   if (!aligned(Q, 16) || !aligned(K, 16) || !aligned(V, 16) || !aligned(out, 16))
     return LESSDEC_EINVAL;
-  const Workspace w = carve(s, (size_t)P);
+  const Workspace w = carve(s, (size_t)P, desc->flags);
   char *ws = static_cast<char *>(desc->workspace);
-  if (desc->flags & LESSDEC_FLAG_PROMPT_STEPWISE) {
+  // Lambda-masking taken through a prompt longer than the budget: the cache every token meets is
+  // known beforehand, so all rows are computed at once (same results as the loop below)
+  const bool masked = (desc->flags & LESSDEC_FLAG_PROMPT_STEPWISE) && (desc->flags & LESSDEC_FLAG_LAMBDA) &&
+                      (size_t)P > s.C;
+  if ((desc->flags & LESSDEC_FLAG_PROMPT_STEPWISE) && !masked) {
     // the generation loop over the prompt: token t's rows are staged as one step's q, k, v
     hipStream_t st = (hipStream_t)hip_stream;
     PromptRowsArgs r;
@@ -267,6 +274,8 @@ int lessdec_prefill(const lessdec_desc *desc, const void *Q, const void *K, cons
   a.list = reinterpret_cast<int32_t *>(ws + w.off_list);
   a.count = reinterpret_cast<int32_t *>(ws + w.off_count);
   a.psi_all = reinterpret_cast<float *>(ws + w.off_psiall);
+  a.phi_all = reinterpret_cast<float *>(ws + w.off_phiall);
+  a.masked = masked ? 1 : 0;
   return launch_prefill(a, (hipStream_t)hip_stream) == hipSuccess ? LESSDEC_OK : LESSDEC_EHIP;
 }
 

@@ -298,6 +298,232 @@ __global__ __launch_bounds__(64 * kPrefillWaves) void prefill_rowpass_kernel(
 }
 
 // -------------------------------------------------------------------------------------
+// Masked row pass: Lambda-masking taken through the prompt token by token (Sec. 4, "Setup";
+// Sec. 3.2 builds the same matrix for training), all rows at once.  Under that policy the cache
+// that token t meets is known beforehand: the first Nh tokens and the Nr tokens before it, the
+// pairs discarded by then are Nh .. t - Nr - 1.  Row t of the attention matrix therefore has
+// e^{q_t k_j / sqrt(D)} where pair j is cached (or is t itself) and phi(q_t) psi(k_j)^T where
+// it was discarded, and out_t = (row t) V / (row t) 1 is Eq. 3 with H, z of Eq. 6.
+// Same tiling as the row pass.  A workgroup first sweeps the key tiles that hold cached pairs
+// of any of its queries (the first ceil(Nh / 16) tiles and those from the window of its first
+// query on), staged through the LDS as there; then its waves sweep the tiles in between, which
+// are low-rank for every query of the workgroup, on their own: the 16 x 16 tile
+// psi(K) phi(Q)^T is R / 4 matrix instructions instead of D / 4, nothing is staged.
+// Online normalisation as in the row pass, the low-rank entries entering as w e^{-m}; m also
+// rises to ln(w) where that would exceed 1, so every weight handed to p V stays in [0, 1].
+// Leaves lse_t = m_t + ln(sum of the entries that H2O's scores are normalised by): all of them,
+// or with the sparse-denominator flag the exponentials only.
+// -------------------------------------------------------------------------------------
+template <typename T, int D>
+__global__ __launch_bounds__(64 * kPrefillWaves) void prefill_maskedrows_kernel(
+    const T *__restrict__ Q, const T *__restrict__ K, const T *__restrict__ V, unsigned U, int G, int P,
+    const float *__restrict__ phi, const float *__restrict__ psi, int R, int Nh, int Nr, int sparse_den,
+    double *__restrict__ lse, T *__restrict__ out)
+{
+  constexpr int CH = D / 4, DB = D / 16;
+  constexpr bool kHalf = sizeof(T) == 2;
+  constexpr int EPT = 16 * D / (64 * kPrefillWaves);
+  static_assert(EPT % 2 == 0 && CH % EPT == 0, "a thread's elements stay within one lane group");
+  __shared__ double2 s_k[2][16 * D / 2];
+  const int nblk = (P + 15) / 16;
+  const int ngrp = (nblk + kPrefillWaves - 1) / kPrefillWaves;
+  const PrefillBlock pb = prefill_block(blockIdx.x, ngrp);
+  if (pb.u >= U) return;                                  // uniform over the workgroup
+  const int grp = ngrp - 1 - pb.grp;                      // long rows first
+  const size_t u = pb.u;
+  const int l = threadIdx.x % 64, g = l / 16, c = l % 16;
+  const int it = grp * kPrefillWaves + (int)(threadIdx.x / 64);
+  const bool active = it < nblk;                          // wave-uniform
+  const int it_last = (grp + 1) * kPrefillWaves - 1 < nblk - 1 ? (grp + 1) * kPrefillWaves - 1 : nblk - 1;
+  const int qi = it * 16 + c;
+  const int qrow = qi < P ? qi : P - 1;
+  const size_t ukv = u / (unsigned)G;
+  const T *Qu = Q + u * (size_t)P * D, *Ku = K + ukv * (size_t)P * D, *Vu = V + ukv * (size_t)P * D;
+  const float *psi_u = psi + ukv * (size_t)P * R;
+  const float *phi_q = phi + (u * (size_t)P + qrow) * R;
+  const double scale = 1.0 / sqrt((double)D);
+
+  // key tiles [0, nfirst) and [band0, it_last] can hold cached pairs of the workgroup's queries
+  const int q0b = grp * kPrefillWaves * 16;
+  int nfirst = (Nh + 15) / 16;
+  if (nfirst > it_last + 1) nfirst = it_last + 1;
+  int band0 = q0b - Nr >= 0 ? (q0b - Nr) / 16 : 0;
+  if (band0 < nfirst) band0 = nfirst;
+  if (band0 > it_last + 1) band0 = it_last + 1;
+  const int ndense = nfirst + (it_last + 1 - band0);
+  auto tile_of = [&](int idx) { return idx < nfirst ? idx : band0 + (idx - nfirst); };
+
+  double qd[CH];
+  {
+    Chunk<T, D> qraw;
+    qraw.load(Qu + (size_t)qrow * D, g);
+#pragma unroll
+    for (int s = 0; s < CH; ++s) qd[s] = qraw.get(s);
+  }
+  // phi of the lane's query: feature 4 s + g is this lane's operand of step s
+  double fq[4];
+#pragma unroll
+  for (int s = 0; s < 4; ++s) fq[s] = 4 * s + g < R ? (double)phi_q[4 * s + g] : 0.0;
+
+  double m_run = -__builtin_inf(), em_run = 0.0, L = 0.0, Ls = 0.0;   // em_run = e^{-m_run} once m_run is finite
+  v4f O[DB];
+#pragma unroll
+  for (int b = 0; b < DB; ++b) O[b] = v4f{0.f, 0.f, 0.f, 0.f};
+
+  // low-rank tile: acc[v] = psi(k_{j0 + g + 4 v}) phi(q_c)^T
+  auto lowrank_tile = [&](int j0) -> v4d {
+    const int kr = j0 + c;
+    const float *prow = psi_u + (size_t)(kr < P ? kr : P - 1) * R;
+    v4d w = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      if (4 * s < R) {
+        const double a = 4 * s + g < R ? (double)prow[4 * s + g] : 0.0;
+        w = __builtin_amdgcn_mfma_f64_16x16x4f64(a, fq[s], w, 0, 0, 0);
+      }
+    }
+    for (int s = 4; 4 * s < R; ++s) {
+      const int r = 4 * s + g;
+      const double a = r < R ? (double)prow[r] : 0.0, b = r < R ? (double)phi_q[r] : 0.0;
+      w = __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, w, 0, 0, 0);
+    }
+    return w;
+  };
+  // one tile's entries into the running sums: sc[v] the scaled score of a cached pair or -inf,
+  // wv[v] the low-rank weight of a discarded pair or 0
+  auto consume = [&](const double (&sc)[4], const double (&wv)[4], double (&e)[4]) {
+    double tmax = -__builtin_inf(), wmax = 0.0;
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      tmax = fmax(tmax, sc[v]);
+      wmax = fmax(wmax, wv[v]);
+    }
+    tmax = fmax(tmax, __shfl_xor(tmax, 16));
+    tmax = fmax(tmax, __shfl_xor(tmax, 32));
+    wmax = fmax(wmax, __shfl_xor(wmax, 16));
+    wmax = fmax(wmax, __shfl_xor(wmax, 32));
+    const bool up = tmax > m_run || (wmax > 0.0 && (m_run == -__builtin_inf() || wmax * em_run > 1.0));
+    if (__any(up)) {
+      double m_new = fmax(m_run, tmax);
+      if (wmax > 0.0) m_new = fmax(m_new, log(wmax));
+      if (m_new > m_run) {
+        const double alpha = exp(m_run - m_new);          // 0 when nothing was summed before
+        L *= alpha;
+        Ls *= alpha;
+        m_run = m_new;
+        em_run = exp(-m_new);
+        if (out != nullptr) {
+          const float af = (float)alpha;
+#pragma unroll
+          for (int b = 0; b < DB; ++b) O[b] *= af;
+        }
+      }
+    }
+    double esum = 0.0, wsum = 0.0;
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      const double es = sc[v] > -__builtin_inf() ? exp_softmax_f64(sc[v] - m_run) : 0.0;
+      const double ew = wv[v] > 0.0 ? fmin(wv[v] * em_run, 1.0) : 0.0;
+      e[v] = es + ew;                                     // at most one of them is not 0
+      esum += es;
+      wsum += ew;
+    }
+    L += esum + wsum;
+    Ls += esum;
+  };
+
+  // this thread's share of a key tile: EPT consecutive elements of row wc
+  const int wc = threadIdx.x % 16, we = EPT * (int)(threadIdx.x / 16);
+  const int wg = we / CH, wi = (we % CH) / 2;
+  T raw[EPT];
+  auto fetch = [&](int jt) {
+    const int kr = jt * 16 + wc;
+    const T *src = Ku + (size_t)(kr < P ? kr : P - 1) * D + we;
+    if constexpr (EPT * sizeof(T) == 32) {
+      reinterpret_cast<uint4 *>(raw)[0] = reinterpret_cast<const uint4 *>(src)[0];
+      reinterpret_cast<uint4 *>(raw)[1] = reinterpret_cast<const uint4 *>(src)[1];
+    } else if constexpr (EPT * sizeof(T) == 16) {
+      reinterpret_cast<uint4 *>(raw)[0] = reinterpret_cast<const uint4 *>(src)[0];
+    } else {
+      reinterpret_cast<uint2 *>(raw)[0] = reinterpret_cast<const uint2 *>(src)[0];
+    }
+  };
+  if (ndense > 0) fetch(tile_of(0));
+  for (int idx = 0; idx < ndense; ++idx) {
+    const int jt = tile_of(idx), j0 = jt * 16;
+    double2 *buf = s_k[idx & 1];
+#pragma unroll
+    for (int p = 0; p < EPT / 2; ++p)
+      buf[((wi + p) * 4 + wg) * 16 + wc] =
+          double2{(double)Store<T>::to_float(raw[2 * p]), (double)Store<T>::to_float(raw[2 * p + 1])};
+    fetch(tile_of(idx + 1 < ndense ? idx + 1 : idx));
+    VTile<D> vt;
+    if constexpr (kHalf) {
+      if (out != nullptr) vt.load(reinterpret_cast<const __half *>(Vu), P, j0, g, c);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+    if (!active || jt > it) continue;                     // wave-uniform
+    v4d acc = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+    for (int i = 0; i < CH / 2; ++i) {
+      const double2 kk = buf[(i * 4 + g) * 16 + c];
+      acc = __builtin_amdgcn_mfma_f64_16x16x4f64(kk.x, qd[2 * i], acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f64_16x16x4f64(kk.y, qd[2 * i + 1], acc, 0, 0, 0);
+    }
+    // some pair of this tile discarded before some query of this wave? (wave-uniform)
+    const bool any_low = j0 + 15 >= Nh && j0 < it * 16 + 15 - Nr;
+    v4d wt = {0.0, 0.0, 0.0, 0.0};
+    if (any_low) wt = lowrank_tile(j0);
+    double sc[4], wv[4], e[4];
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      const int kj = j0 + g + 4 * v;
+      const bool causal = kj <= qi && kj < P;
+      const bool cached = causal && (kj < Nh || kj >= qi - Nr);
+      sc[v] = cached ? acc[v] * scale : -__builtin_inf();
+      wv[v] = (causal && !cached) ? wt[v] : 0.0;
+    }
+    consume(sc, wv, e);
+    if (out != nullptr) {
+      if constexpr (kHalf) tile_pv<D>(vt, e, O);
+      else tile_pv<D>(reinterpret_cast<const float *>(Vu), P, j0, g, c, e, O);
+    }
+  }
+  // the tiles in between: every pair discarded before every query of the workgroup
+  if (active) {
+    for (int jt = nfirst; jt < band0; ++jt) {
+      const int j0 = jt * 16;
+      VTile<D> vt;
+      if constexpr (kHalf) {
+        if (out != nullptr) vt.load(reinterpret_cast<const __half *>(Vu), P, j0, g, c);
+      }
+      const v4d wt = lowrank_tile(j0);
+      double sc[4], wv[4], e[4];
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        sc[v] = -__builtin_inf();
+        wv[v] = wt[v];
+      }
+      consume(sc, wv, e);
+      if (out != nullptr) {
+        if constexpr (kHalf) tile_pv<D>(vt, e, O);
+        else tile_pv<D>(reinterpret_cast<const float *>(Vu), P, j0, g, c, e, O);
+      }
+    }
+  }
+  L += __shfl_xor(L, 16);
+  L += __shfl_xor(L, 32);
+  Ls += __shfl_xor(Ls, 16);
+  Ls += __shfl_xor(Ls, 32);
+  if (active && qi < P) {
+    if (g == 0) lse[u * (size_t)P + qi] = m_run + log(sparse_den ? Ls : L);
+    if (out != nullptr) store_out<D>(out + (u * (size_t)P + qi) * D, g, O, (float)(1.0 / L));
+  }
+}
+
+// -------------------------------------------------------------------------------------
 // Column pass: one wave per block of 16 keys.  Sweeps the query tiles from the diagonal
 // down and sums a_ij = e^{s_ij - lse_i} over the queries: the accumulated attention
 // probability of each prompt token (H2O's score, Sec. 2.1).  No atomics: every column is
@@ -698,7 +924,9 @@ __global__ __launch_bounds__(256) void prefill_rank_kernel(const double *__restr
 }
 
 // -------------------------------------------------------------------------------------
-// Finalize, one workgroup per unit: kept tokens get slots in ascending position; their
+// Finalize, one workgroup per unit: kept tokens get slots in ascending position (or, for the
+// prompt taken token by token under Lambda-masking, the slots that in-place replacement would
+// have left them in); their
 // rows are gathered into the cache (acc = column sum, pos, psi), unused slots cleared; the
 // discarded pairs build H = sum psi(k)^T v, z = sum psi(k) (Eq. 6) in fp64.
 // For the state, wave w owns D / 4 columns of H, two per lane, and its lanes split the
@@ -725,7 +953,7 @@ __global__ __launch_bounds__(256) void prefill_finalize_kernel(
     int32_t *__restrict__ slot_of, const float *__restrict__ psi_all, int C, int R,
     T *__restrict__ k_cache, T *__restrict__ v_cache, double *__restrict__ acc,
     int32_t *__restrict__ pos, float *__restrict__ psi, float *__restrict__ H,
-    double *__restrict__ z, int32_t *__restrict__ n_seen, int32_t *__restrict__ pend_slot)
+    double *__restrict__ z, int32_t *__restrict__ n_seen, int32_t *__restrict__ pend_slot, int ring_nh)
 {
   extern __shared__ int s_tok[];                           // [C] token held by each slot
   __shared__ int s_cnt[256];
@@ -748,8 +976,11 @@ __global__ __launch_bounds__(256) void prefill_finalize_kernel(
     for (int t = 0; t < tid; ++t) base += s_cnt[t];
     for (int j = lo; j < hi; ++j) {
       const int keep = so[j];
-      so[j] = keep ? base : -1;
-      if (keep && base < C) s_tok[base] = j;
+      // ring_nh >= 0: the slots as in-place replacement leaves them when the first ring_nh tokens
+      // stay and the others pass through the remaining slots in turn (Sec. 3.2)
+      const int slot = (ring_nh < 0 || j < ring_nh || P <= C || C <= ring_nh) ? base : ring_nh + (j - ring_nh) % (C - ring_nh);
+      so[j] = keep ? slot : -1;
+      if (keep && slot < C) s_tok[slot] = j;
       base += keep;
     }
   }
@@ -854,15 +1085,54 @@ static hipError_t launch_prefill_t(const PrefillArgs &a, hipStream_t st)
   const int G = d->q_per_kv > 1 ? d->q_per_kv : 1;          // query heads per unit
   const unsigned tiles = (unsigned)(((P + 15) / 16 + kPrefillWaves - 1) / kPrefillWaves);
   const unsigned grid = (U + kXcds - 1) / kXcds * kXcds * tiles;
-  prefill_rowpass_kernel<T, D><<<(U * G + kXcds - 1) / kXcds * kXcds * tiles, 64 * kPrefillWaves, 0, st>>>(
-      (const T *)a.Q, (const T *)a.K, (const T *)a.V, U * G, G, P, a.lse, (T *)a.out);
-  hipError_t e = hipGetLastError();
+  const bool lambda = (d->flags & LESSDEC_FLAG_LAMBDA) != 0;
+  // the prompt taken token by token under Lambda-masking, all rows at once (needs P > C: inside
+  // the budget nothing is discarded and the regular rows are the same)
+  const bool masked = a.masked && lambda && P > C;
+  const int ring_nh = masked ? d->n_heavy : -1;
+  hipError_t e;
+  auto key_features = [&]() -> hipError_t {
+    if (mlp_mfma_supported(d->dtype, d->head_dim, d->hidden, d->rank)) {
+      MlpArgs fm;
+      fm.B = d->batch; fm.Hh = d->heads; fm.rpu = P; fm.D = d->head_dim; fm.Rp = d->hidden; fm.R = d->rank;
+      fm.x = (const __half *)a.K; fm.W1 = (const __half *)d->Wk1; fm.W2 = (const __half *)d->Wk2;
+      fm.W3 = (const __half *)d->Wk3; fm.out = a.psi_all;
+      return launch_mlp(fm, st);
+    }
+    FeatmapArgs fa;
+    fa.x = a.K; fa.W1 = d->Wk1; fa.W2 = d->Wk2; fa.W3 = d->Wk3; fa.out = a.psi_all; fa.out_f64 = 0;
+    fa.B = d->batch; fa.Hh = d->heads; fa.rpu = P; fa.D = d->head_dim; fa.Rp = d->hidden; fa.R = d->rank;
+    return launch_featmap_generic(fa, d->dtype, st);
+  };
+  if (masked) {
+    // psi of every prompt key, phi of every prompt query (Eq. 1, Eq. 2), then the masked rows
+    if ((e = key_features()) != hipSuccess) return e;
+    if (mlp_mfma_supported(d->dtype, d->head_dim, d->hidden, d->rank)) {
+      MlpArgs fm;
+      fm.B = d->batch; fm.Hh = d->heads * G; fm.rpu = P; fm.D = d->head_dim; fm.Rp = d->hidden; fm.R = d->rank;
+      fm.x = (const __half *)a.Q; fm.W1 = (const __half *)d->Wq1; fm.W2 = (const __half *)d->Wq2;
+      fm.W3 = nullptr; fm.out = a.phi_all;
+      e = launch_mlp(fm, st);
+    } else {
+      FeatmapArgs fa;
+      fa.x = a.Q; fa.W1 = d->Wq1; fa.W2 = d->Wq2; fa.W3 = nullptr; fa.out = a.phi_all; fa.out_f64 = 0;
+      fa.B = d->batch; fa.Hh = d->heads * G; fa.rpu = P; fa.D = d->head_dim; fa.Rp = d->hidden; fa.R = d->rank;
+      e = launch_featmap_generic(fa, d->dtype, st);
+    }
+    if (e != hipSuccess) return e;
+    prefill_maskedrows_kernel<T, D><<<(U * G + kXcds - 1) / kXcds * kXcds * tiles, 64 * kPrefillWaves, 0, st>>>(
+        (const T *)a.Q, (const T *)a.K, (const T *)a.V, U * G, G, P, a.phi_all, a.psi_all, d->rank, d->n_heavy,
+        d->n_recent, (d->flags & LESSDEC_FLAG_SPARSE_DENOM) ? 1 : 0, a.lse, (T *)a.out);
+  } else {
+    prefill_rowpass_kernel<T, D><<<(U * G + kXcds - 1) / kXcds * kXcds * tiles, 64 * kPrefillWaves, 0, st>>>(
+        (const T *)a.Q, (const T *)a.K, (const T *)a.V, U * G, G, P, a.lse, (T *)a.out);
+  }
+  e = hipGetLastError();
   if (e != hipSuccess) return e;
   // Column sums and selection.  Exact sums are needed of the kept tokens (they become the
   // accumulated scores) and of those whose rank is in doubt; with fp16 storage the cheap pass
   // tells which those are, with Lambda-masking the kept set is known beforehand.  Otherwise
   // (fp32 storage, or a prompt inside the budget) every column is summed exactly.
-  const bool lambda = (d->flags & LESSDEC_FLAG_LAMBDA) != 0;
   const unsigned rank_grid = U * (unsigned)((P + 255) / 256);
   int32_t *keep = a.slot_of;
   if (P > C && (lambda || sizeof(T) == 2)) {
@@ -898,31 +1168,20 @@ static hipError_t launch_prefill_t(const PrefillArgs &a, hipStream_t st)
                                                    a.slot_of);
   }
   if ((e = hipGetLastError()) != hipSuccess) return e;
-  if (mlp_mfma_supported(d->dtype, d->head_dim, d->hidden, d->rank)) {
-    MlpArgs fm;
-    fm.B = d->batch; fm.Hh = d->heads; fm.rpu = P; fm.D = d->head_dim; fm.Rp = d->hidden; fm.R = d->rank;
-    fm.x = (const __half *)a.K; fm.W1 = (const __half *)d->Wk1; fm.W2 = (const __half *)d->Wk2;
-    fm.W3 = (const __half *)d->Wk3; fm.out = a.psi_all;
-    if ((e = launch_mlp(fm, st)) != hipSuccess) return e;
-  } else {
-    FeatmapArgs fa;
-    fa.x = a.K; fa.W1 = d->Wk1; fa.W2 = d->Wk2; fa.W3 = d->Wk3; fa.out = a.psi_all; fa.out_f64 = 0;
-    fa.B = d->batch; fa.Hh = d->heads; fa.rpu = P; fa.D = d->head_dim; fa.Rp = d->hidden; fa.R = d->rank;
-    if ((e = launch_featmap_generic(fa, d->dtype, st)) != hipSuccess) return e;
-  }
+  if (!masked && (e = key_features()) != hipSuccess) return e;
   const size_t lds = (size_t)C * sizeof(int);
   if (d->rank <= 4)
     prefill_finalize_kernel<T, D, 4><<<U, 256, lds, st>>>(
       (const T *)a.K, (const T *)a.V, P, a.colsum, keep, a.psi_all, C, d->rank, (T *)d->k_cache,
-      (T *)d->v_cache, d->acc, d->pos, d->psi, d->H, d->z, d->n_seen, d->pend_slot);
+      (T *)d->v_cache, d->acc, d->pos, d->psi, d->H, d->z, d->n_seen, d->pend_slot, ring_nh);
   else if (d->rank <= 8)
     prefill_finalize_kernel<T, D, 8><<<U, 256, lds, st>>>(
       (const T *)a.K, (const T *)a.V, P, a.colsum, keep, a.psi_all, C, d->rank, (T *)d->k_cache,
-      (T *)d->v_cache, d->acc, d->pos, d->psi, d->H, d->z, d->n_seen, d->pend_slot);
+      (T *)d->v_cache, d->acc, d->pos, d->psi, d->H, d->z, d->n_seen, d->pend_slot, ring_nh);
   else
     prefill_finalize_kernel<T, D, 16><<<U, 256, lds, st>>>(
       (const T *)a.K, (const T *)a.V, P, a.colsum, keep, a.psi_all, C, d->rank, (T *)d->k_cache,
-      (T *)d->v_cache, d->acc, d->pos, d->psi, d->H, d->z, d->n_seen, d->pend_slot);
+      (T *)d->v_cache, d->acc, d->pos, d->psi, d->H, d->z, d->n_seen, d->pend_slot, ring_nh);
   return hipGetLastError();
 }
 

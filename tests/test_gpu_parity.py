@@ -180,6 +180,70 @@ def test_stepwise_prompt_is_the_generation_loop(kind):
         assert torch.equal(getattr(a, n), getattr(b, n)), n
 
 
+# Lambda-masking taken through a prompt longer than the budget: the library computes all prompt
+# rows at once (the cache each token meets is known beforehand); the oracle walks the prompt token
+# by token.  Shapes span several key tiles, a ragged last tile, first-token tiles and window
+# tiles that coincide or lie apart, and the degenerate splits.
+MASKED = [
+    (small("masked-prompt-f16", n_heavy=4, n_recent=28, prompt=200, steps=10), 6),
+    (small("masked-prompt-f32-d64", n_heavy=4, n_recent=12, prompt=100, steps=10, dtype="f32", head_dim=64, rank=4), 6),
+    (small("masked-prompt-window-only", n_heavy=0, n_recent=24, prompt=150, steps=10), 6),
+    (small("masked-prompt-no-window", n_heavy=5, n_recent=0, prompt=90, steps=10), 6),
+    (small("masked-prompt-sparse-denominator", n_heavy=4, n_recent=20, prompt=120, steps=10), 7),
+    (small("masked-prompt-two-first-tiles", n_heavy=20, n_recent=20, prompt=130, steps=10), 6),
+    (small("masked-prompt-rank-20", n_heavy=4, n_recent=16, prompt=110, steps=10, rank=20), 6),
+    (small("masked-prompt-rank-6-f32", n_heavy=3, n_recent=9, prompt=70, steps=10, rank=6, dtype="f32"), 6),
+    (small("masked-prompt-2-heads", n_heavy=4, n_recent=20, prompt=140, steps=10, q_per_kv=2), 6),
+    (small("masked-prompt-one-past-budget", n_heavy=4, n_recent=12, prompt=17, steps=10), 6),
+    (small("masked-prompt-long", n_heavy=4, n_recent=60, prompt=600, steps=5, batch=1, heads=2), 6),
+]
+
+
+@pytest.mark.parametrize("w,flags", MASKED, ids=lambda x: x.name if hasattr(x, "name") else str(x))
+def test_lambda_masking_through_the_prompt_all_rows_at_once(w, flags):
+    rep = hz.run_workload(w, range(w.units), flags=flags)
+    report_ok(rep, min_decisions=w.units * w.steps)
+    assert rep.exempt == 0
+
+
+def test_masked_prompt_at_the_benchmark_shape():
+    """Config 3's shape, 4 first tokens + 98 recent, the policy active through the 1024-token
+    prompt: every unit on the GPU, a sample of units through the oracle's token-by-token walk."""
+    w = wl.WORKLOADS[3].scaled(name="cfg3-lambda-through-prompt", n_heavy=4, n_recent=98, steps=16)
+    units = sample_units(w, 6, seed=34)
+    rep = hz.run_workload(w, units, flags=6)
+    report_ok(rep, min_decisions=len(units) * w.steps)
+    assert rep.exempt == 0
+
+
+def test_masked_prompt_agrees_with_the_generation_loop():
+    """The all-rows-at-once form against the library's own loop of decode steps (flag 2 only)."""
+    import torch
+    w = small("masked-vs-loop", n_heavy=4, n_recent=20, prompt=100, steps=0)
+    inp = wl.all_inputs(w)
+    Q, K, V = (torch.from_numpy(inp[n]).cuda() for n in ("Q", "K", "V"))
+    a = hz.make_gpu(w, flags=6)
+    out_a = torch.empty_like(Q)
+    a.prefill(Q, K, V, out=out_a)
+    b = hz.make_gpu(w, flags=2)
+    b.state_reset()
+    out_b = torch.empty_like(Q)
+    Qt, Kt, Vt = (x.reshape(w.units, w.prompt, w.head_dim).transpose(0, 1).contiguous() for x in (Q, K, V))
+    step_out = torch.empty_like(Qt[0])
+    for t in range(w.prompt):
+        b.step(Qt[t], Kt[t], Vt[t], step_out)
+        out_b.reshape(w.units, w.prompt, w.head_dim)[:, t].copy_(step_out)
+    b.state_sync()
+    torch.cuda.synchronize()
+    assert torch.equal(a.pos, b.pos) and torch.equal(a.n_seen, b.n_seen)
+    assert torch.equal(a.k_cache, b.k_cache) and torch.equal(a.v_cache, b.v_cache)
+    assert torch.allclose(out_a.float(), out_b.float(), rtol=0, atol=2e-3 * float(out_b.float().abs().max()))
+    assert torch.allclose(a.acc, b.acc, rtol=0, atol=5e-7)
+    assert torch.allclose(a.H, b.H, rtol=1e-4, atol=1e-4 * float(b.H.abs().max()))
+    assert torch.allclose(a.z, b.z, rtol=1e-4, atol=0)
+    assert torch.allclose(a.psi, b.psi, rtol=1e-5, atol=1e-6)
+
+
 # Several query heads per key/value head (multi-query / grouped-query attention, Sec. 3.2), with
 # the prompt taken token by token (flag 4) and in one shot
 GROUPS = [
