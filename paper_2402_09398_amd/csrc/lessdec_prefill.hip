@@ -304,11 +304,11 @@ __global__ __launch_bounds__(64 * kPrefillWaves) void prefill_rowpass_kernel(
 // pairs discarded by then are Nh .. t - Nr - 1.  Row t of the attention matrix therefore has
 // e^{q_t k_j / sqrt(D)} where pair j is cached (or is t itself) and phi(q_t) psi(k_j)^T where
 // it was discarded, and out_t = (row t) V / (row t) 1 is Eq. 3 with H, z of Eq. 6.
-// Same tiling as the row pass.  A workgroup first sweeps the key tiles that hold cached pairs
-// of any of its queries (the first ceil(Nh / 16) tiles and those from the window of its first
-// query on), staged through the LDS as there; then its waves sweep the tiles in between, which
-// are low-rank for every query of the workgroup, on their own: the 16 x 16 tile
-// psi(K) phi(Q)^T is R / 4 matrix instructions instead of D / 4, nothing is staged.
+// Same tiling as the row pass.  A workgroup first sweeps the key tiles that can hold cached
+// pairs of any of its queries (the first ceil(Nh / 16) tiles and those from the window of its
+// first query on), staged through the LDS as there, all other entries masked out.  Then every
+// wave sweeps, on its own, the tiles that hold pairs discarded before its queries: the 16 x 16
+// tile psi(K) phi(Q)^T is R / 4 matrix instructions instead of D / 4, nothing is staged.
 // Online normalisation as in the row pass, the low-rank entries entering as w e^{-m}; m also
 // rises to ln(w) where that would exceed 1, so every weight handed to p V stays in [0, 1].
 // Leaves lse_t = m_t + ln(sum of the entries that H2O's scores are normalised by): all of them,
@@ -360,77 +360,10 @@ __global__ __launch_bounds__(64 * kPrefillWaves) void prefill_maskedrows_kernel(
 #pragma unroll
     for (int s = 0; s < CH; ++s) qd[s] = qraw.get(s);
   }
-  // phi of the lane's query: feature 4 s + g is this lane's operand of step s
-  double fq[4];
-#pragma unroll
-  for (int s = 0; s < 4; ++s) fq[s] = 4 * s + g < R ? (double)phi_q[4 * s + g] : 0.0;
-
-  double m_run = -__builtin_inf(), em_run = 0.0, L = 0.0, Ls = 0.0;   // em_run = e^{-m_run} once m_run is finite
+  double m_run = -__builtin_inf(), L = 0.0;               // L: sum of the exponentials
   v4f O[DB];
 #pragma unroll
   for (int b = 0; b < DB; ++b) O[b] = v4f{0.f, 0.f, 0.f, 0.f};
-
-  // low-rank tile: acc[v] = psi(k_{j0 + g + 4 v}) phi(q_c)^T
-  auto lowrank_tile = [&](int j0) -> v4d {
-    const int kr = j0 + c;
-    const float *prow = psi_u + (size_t)(kr < P ? kr : P - 1) * R;
-    v4d w = {0.0, 0.0, 0.0, 0.0};
-#pragma unroll
-    for (int s = 0; s < 4; ++s) {
-      if (4 * s < R) {
-        const double a = 4 * s + g < R ? (double)prow[4 * s + g] : 0.0;
-        w = __builtin_amdgcn_mfma_f64_16x16x4f64(a, fq[s], w, 0, 0, 0);
-      }
-    }
-    for (int s = 4; 4 * s < R; ++s) {
-      const int r = 4 * s + g;
-      const double a = r < R ? (double)prow[r] : 0.0, b = r < R ? (double)phi_q[r] : 0.0;
-      w = __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, w, 0, 0, 0);
-    }
-    return w;
-  };
-  // one tile's entries into the running sums: sc[v] the scaled score of a cached pair or -inf,
-  // wv[v] the low-rank weight of a discarded pair or 0
-  auto consume = [&](const double (&sc)[4], const double (&wv)[4], double (&e)[4]) {
-    double tmax = -__builtin_inf(), wmax = 0.0;
-#pragma unroll
-    for (int v = 0; v < 4; ++v) {
-      tmax = fmax(tmax, sc[v]);
-      wmax = fmax(wmax, wv[v]);
-    }
-    tmax = fmax(tmax, __shfl_xor(tmax, 16));
-    tmax = fmax(tmax, __shfl_xor(tmax, 32));
-    wmax = fmax(wmax, __shfl_xor(wmax, 16));
-    wmax = fmax(wmax, __shfl_xor(wmax, 32));
-    const bool up = tmax > m_run || (wmax > 0.0 && (m_run == -__builtin_inf() || wmax * em_run > 1.0));
-    if (__any(up)) {
-      double m_new = fmax(m_run, tmax);
-      if (wmax > 0.0) m_new = fmax(m_new, log(wmax));
-      if (m_new > m_run) {
-        const double alpha = exp(m_run - m_new);          // 0 when nothing was summed before
-        L *= alpha;
-        Ls *= alpha;
-        m_run = m_new;
-        em_run = exp(-m_new);
-        if (out != nullptr) {
-          const float af = (float)alpha;
-#pragma unroll
-          for (int b = 0; b < DB; ++b) O[b] *= af;
-        }
-      }
-    }
-    double esum = 0.0, wsum = 0.0;
-#pragma unroll
-    for (int v = 0; v < 4; ++v) {
-      const double es = sc[v] > -__builtin_inf() ? exp_softmax_f64(sc[v] - m_run) : 0.0;
-      const double ew = wv[v] > 0.0 ? fmin(wv[v] * em_run, 1.0) : 0.0;
-      e[v] = es + ew;                                     // at most one of them is not 0
-      esum += es;
-      wsum += ew;
-    }
-    L += esum + wsum;
-    Ls += esum;
-  };
 
   // this thread's share of a key tile: EPT consecutive elements of row wc
   const int wc = threadIdx.x % 16, we = EPT * (int)(threadIdx.x / 16);
@@ -448,6 +381,7 @@ __global__ __launch_bounds__(64 * kPrefillWaves) void prefill_maskedrows_kernel(
       reinterpret_cast<uint2 *>(raw)[0] = reinterpret_cast<const uint2 *>(src)[0];
     }
   };
+  // 1) the cached pairs: the row pass over the tiles that can hold any, other entries masked out
   if (ndense > 0) fetch(tile_of(0));
   for (int idx = 0; idx < ndense; ++idx) {
     const int jt = tile_of(idx), j0 = jt * 16;
@@ -464,7 +398,8 @@ __global__ __launch_bounds__(64 * kPrefillWaves) void prefill_maskedrows_kernel(
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
-    if (!active || jt > it) continue;                     // wave-uniform
+    // no cached pair of this wave's queries in the tile? (wave-uniform)
+    if (!active || jt > it || (j0 >= Nh && j0 + 15 < it * 16 - Nr)) continue;
     v4d acc = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
     for (int i = 0; i < CH / 2; ++i) {
@@ -472,47 +407,130 @@ __global__ __launch_bounds__(64 * kPrefillWaves) void prefill_maskedrows_kernel(
       acc = __builtin_amdgcn_mfma_f64_16x16x4f64(kk.x, qd[2 * i], acc, 0, 0, 0);
       acc = __builtin_amdgcn_mfma_f64_16x16x4f64(kk.y, qd[2 * i + 1], acc, 0, 0, 0);
     }
-    // some pair of this tile discarded before some query of this wave? (wave-uniform)
-    const bool any_low = j0 + 15 >= Nh && j0 < it * 16 + 15 - Nr;
-    v4d wt = {0.0, 0.0, 0.0, 0.0};
-    if (any_low) wt = lowrank_tile(j0);
-    double sc[4], wv[4], e[4];
+    double sc[4], tmax = -__builtin_inf();
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
       const int kj = j0 + g + 4 * v;
-      const bool causal = kj <= qi && kj < P;
-      const bool cached = causal && (kj < Nh || kj >= qi - Nr);
+      const bool cached = kj <= qi && kj < P && (kj < Nh || kj >= qi - Nr);
       sc[v] = cached ? acc[v] * scale : -__builtin_inf();
-      wv[v] = (causal && !cached) ? wt[v] : 0.0;
+      tmax = fmax(tmax, sc[v]);
     }
-    consume(sc, wv, e);
+    tmax = fmax(tmax, __shfl_xor(tmax, 16));
+    tmax = fmax(tmax, __shfl_xor(tmax, 32));
+    if (__any(tmax > m_run)) {
+      const double m_new = fmax(m_run, tmax);
+      const double alpha = m_new > m_run ? exp(m_run - m_new) : 1.0;   // 0 when nothing was summed before
+      L *= alpha;
+      m_run = m_new;
+      if (out != nullptr) {
+        const float af = (float)alpha;
+#pragma unroll
+        for (int b = 0; b < DB; ++b) O[b] *= af;
+      }
+    }
+    double e[4], esum = 0.0;
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      e[v] = sc[v] > -__builtin_inf() ? exp_softmax_f64(sc[v] - m_run) : 0.0;
+      esum += e[v];
+    }
+    L += esum;
     if (out != nullptr) {
       if constexpr (kHalf) tile_pv<D>(vt, e, O);
       else tile_pv<D>(reinterpret_cast<const float *>(Vu), P, j0, g, c, e, O);
     }
   }
-  // the tiles in between: every pair discarded before every query of the workgroup
-  if (active) {
-    for (int jt = nfirst; jt < band0; ++jt) {
-      const int j0 = jt * 16;
-      VTile<D> vt;
-      if constexpr (kHalf) {
-        if (out != nullptr) vt.load(reinterpret_cast<const __half *>(Vu), P, j0, g, c);
+
+  // 2) the discarded pairs, every wave on its own: key tiles from Nh's tile to the last one that
+  // holds a pair older than the window of the wave's last query.  The tile psi(K) phi(Q)^T is
+  // R / 4 matrix instructions; entries of pairs that are cached for the lane's query are masked
+  // out.  The next tile's value rows and psi operands are requested before this tile's arithmetic.
+  double Lw = 0.0;                                         // sum of the low-rank entries, times e^{-m_run}
+  const int jt_lo = Nh / 16, jt_hi = (it * 16 + 14 - Nr) >= 0 ? (it * 16 + 14 - Nr) / 16 : -1;
+  if (active && jt_lo <= jt_hi) {
+    // m_run is finite for every query of the prompt: the diagonal tile held the query itself
+    double em_run = m_run > -__builtin_inf() ? exp(-m_run) : 0.0;
+    // phi of the lane's query: feature 4 s + g is this lane's operand of step s
+    double fq[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      const int r = 4 * s + g;
+      const float x = phi_q[r < R ? r : R - 1];
+      fq[s] = r < R ? (double)x : 0.0;
+    }
+    auto psi_operands = [&](int j0, float (&a)[4]) {
+      const int kr = j0 + c;                                  // a tile of the last, ragged query block can pass the prompt end
+      const float *prow = psi_u + (size_t)(kr < P ? kr : P - 1) * R;
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {                           // unconditional loads, features past R zeroed after
+        const int r = 4 * s + g;
+        const float x = prow[r < R ? r : R - 1];
+        a[s] = r < R ? x : 0.f;
       }
-      const v4d wt = lowrank_tile(j0);
-      double sc[4], wv[4], e[4];
+    };
+    VTile<D> vt_next;
+    float pa_next[4];
+    if constexpr (kHalf) vt_next.load(reinterpret_cast<const __half *>(Vu), P, jt_lo * 16, g, c);
+    psi_operands(jt_lo * 16, pa_next);
+    for (int jt = jt_lo; jt <= jt_hi; ++jt) {
+      const int j0 = jt * 16;
+      const VTile<D> vt = vt_next;
+      float pa[4];
+#pragma unroll
+      for (int s = 0; s < 4; ++s) pa[s] = pa_next[s];
+      const int jn = jt < jt_hi ? j0 + 16 : j0;
+      if constexpr (kHalf) vt_next.load(reinterpret_cast<const __half *>(Vu), P, jn, g, c);
+      psi_operands(jn, pa_next);
+      v4d wt = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+      for (int s = 0; s < 4; ++s)
+        if (4 * s < R) wt = __builtin_amdgcn_mfma_f64_16x16x4f64((double)pa[s], fq[s], wt, 0, 0, 0);
+      for (int s = 4; 4 * s < R; ++s) {
+        const int r = 4 * s + g;
+        const int kr = j0 + c < P ? j0 + c : P - 1;
+        const double a = r < R ? (double)psi_u[(size_t)kr * R + r] : 0.0, b = r < R ? (double)phi_q[r] : 0.0;
+        wt = __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, wt, 0, 0, 0);
+      }
+      double wv[4], wmax = 0.0;
 #pragma unroll
       for (int v = 0; v < 4; ++v) {
-        sc[v] = -__builtin_inf();
-        wv[v] = wt[v];
+        const int kj = j0 + g + 4 * v;
+        wv[v] = (kj >= Nh && kj < qi - Nr) ? wt[v] : 0.0;
+        wmax = fmax(wmax, wv[v]);
       }
-      consume(sc, wv, e);
+      wmax = fmax(wmax, __shfl_xor(wmax, 16));
+      wmax = fmax(wmax, __shfl_xor(wmax, 32));
+      // m also rises to ln(w) where w e^{-m} would exceed 1: every weight handed to p V stays in [0, 1]
+      if (__any(wmax * em_run > 1.0)) {
+        const double m_new = wmax > 0.0 ? fmax(m_run, log(wmax)) : m_run;
+        if (m_new > m_run) {
+          const double alpha = exp(m_run - m_new);
+          L *= alpha;
+          Lw *= alpha;
+          m_run = m_new;
+          em_run = exp(-m_new);
+          if (out != nullptr) {
+            const float af = (float)alpha;
+#pragma unroll
+            for (int b = 0; b < DB; ++b) O[b] *= af;
+          }
+        }
+      }
+      double e[4], wsum = 0.0;
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        e[v] = fmin(wv[v] * em_run, 1.0);
+        wsum += e[v];
+      }
+      Lw += wsum;
       if (out != nullptr) {
         if constexpr (kHalf) tile_pv<D>(vt, e, O);
         else tile_pv<D>(reinterpret_cast<const float *>(Vu), P, j0, g, c, e, O);
       }
     }
   }
+  double Ls = L;                                           // exponentials only
+  L += Lw;
   L += __shfl_xor(L, 16);
   L += __shfl_xor(L, 32);
   Ls += __shfl_xor(Ls, 16);
