@@ -68,7 +68,7 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def cpu_baseline(w, n_units, n_steps):
+def cpu_baseline(w, n_units, n_steps, flags=0):
     """The oracle as it stands, timed on the host cores on a bounded sample of the workload."""
     from oracle import less_oracle as lo
     from paper_2402_09398_amd import workloads as wl
@@ -76,7 +76,7 @@ def cpu_baseline(w, n_units, n_steps):
     inp = wl.all_inputs(w.scaled(steps=n_steps), units, workers=16)
     W = wl.head_weights(w)
     st = lo.OracleState(n_units, w.heads, w.head_dim, w.n_heavy, w.n_recent, w.rank, w.hidden, W,
-                        head_of_unit=[u % w.heads for u in units], q_per_kv=w.q_per_kv)
+                        flags=flags, head_of_unit=[u % w.heads for u in units], q_per_kv=w.q_per_kv)
     t0 = time.perf_counter()
     st.prefill(inp["Q"], inp["K"], inp["V"], want_out=False)
     t_prefill = time.perf_counter() - t0
@@ -101,6 +101,11 @@ def main():
     ap.add_argument("--q-per-kv", type=int, default=1,
                     help="G > 1: the workload's heads become heads/G key/value heads with G query heads each "
                          "(multi-query / grouped-query attention); a different workload than the headline one")
+    ap.add_argument("--policy", choices=("h2o", "lambda"), default="h2o",
+                    help="lambda: Lambda-masking with the paper's split (4 first tokens, the other slots recent); "
+                         "a different workload than the headline one")
+    ap.add_argument("--prompt-stepwise", action="store_true",
+                    help="the sparse policy active from the first prompt token (LESSDEC_FLAG_PROMPT_STEPWISE)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-units", type=int, default=1024)
     ap.add_argument("--cpu-steps", type=int, default=512)
@@ -121,6 +126,13 @@ def main():
         if w.heads % args.q_per_kv:
             sys.exit(f"bench.py: --q-per-kv must divide the workload's {w.heads} heads")
         w = w.scaled(name=f"{w.name}-gqa{args.q_per_kv}", heads=w.heads // args.q_per_kv, q_per_kv=args.q_per_kv)
+    flags = 0
+    if args.policy == "lambda":
+        w = w.scaled(name=f"{w.name}-lambda", n_heavy=4, n_recent=w.capacity - 4)
+        flags |= 2
+    if args.prompt_stepwise:
+        w = w.scaled(name=f"{w.name}-prompt-stepwise")
+        flags |= 4
     L = args.layers
     U, D, T = w.units, w.head_dim, w.steps
 
@@ -129,7 +141,8 @@ def main():
     log(f"[bench] inputs for {U} units generated in {time.perf_counter() - t0:.1f} s")
     W = pack_weights(wl.head_weights(w), dev)
     layers = [LessDec(w.batch, w.heads, D, w.n_heavy, w.n_recent, w.rank, w.hidden, w.dtype, W,
-                      max_prompt=w.prompt if i == 0 else 0, device=dev, q_per_kv=w.q_per_kv) for i in range(L)]
+                      max_prompt=w.prompt if i == 0 else 0, device=dev, q_per_kv=w.q_per_kv, flags=flags)
+              for i in range(L)]
     Q, K, V = (torch.from_numpy(inp[k]).to(dev) for k in ("Q", "K", "V"))
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -143,8 +156,19 @@ def main():
     # algorithmic flops of the prompt phase per unit: causal Q K^T twice and A V (3 P^2 D), psi of the
     # discarded keys, the state build; the score contractions decide the heavy set and run in fp64
     n_ev = max(w.prompt - w.capacity, 0)
-    prefill_flops = U * (3.0 * w.prompt ** 2 * D + 2.0 * n_ev * (D * w.hidden + w.hidden * w.rank + w.rank ** 2)
-                         + 2.0 * w.rank * n_ev * D)
+    state_flops = 2.0 * n_ev * (D * w.hidden + w.hidden * w.rank + w.rank ** 2) + 2.0 * w.rank * n_ev * D
+    Pn, Cn, G = float(w.prompt), float(w.capacity), float(w.q_per_kv)
+    if flags & 2 and flags & 4 and w.prompt > w.capacity:
+        # Lambda-masking through the prompt: scores of the cached pairs only, low-rank weights of the
+        # discarded ones (phi of every query as well), A V over everything, column sums of the kept tokens
+        score_flops = G * (2.0 * Pn * (Cn + 1) * D + Pn ** 2 * w.rank + Pn ** 2 * D + 2.0 * Cn * Pn * D
+                           + 2.0 * Pn * (D * w.hidden + w.hidden * w.rank))
+        state_flops = 2.0 * Pn * (D * w.hidden + w.hidden * w.rank + w.rank ** 2) + 2.0 * w.rank * n_ev * D
+    elif flags & 2:
+        score_flops = G * (2.0 * Pn ** 2 * D + 2.0 * Cn * Pn * D)     # the kept set is known: its column sums only
+    else:
+        score_flops = G * 3.0 * Pn ** 2 * D
+    prefill_flops = U * (score_flops + state_flops)
     log(f"[bench] lessdec_prefill P={w.prompt}: {prefill_ms:.1f} ms")
     del Q, K, V, pout
     for lay in layers[1:]:
@@ -210,20 +234,26 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"cfg{w.cfg} {w.name}: batch {w.batch} x heads {w.heads} x head_dim {D}, "
                                f"prompt {w.prompt}, {w.n_heavy}+{w.n_recent} slots, rank {w.rank}, hidden {w.hidden}"
-                               + (f", {w.q_per_kv} query heads per head" if w.q_per_kv > 1 else ""),
+                               + (f", {w.q_per_kv} query heads per head" if w.q_per_kv > 1 else "")
+                               + (", Lambda-masking" if flags & 2 else "")
+                               + (", policy active through the prompt" if flags & 4 else ""),
                    "layers_cycled": L, "prefill_ms": prefill_ms},
         # the prompt phase (secondary path), one warm call: algorithmic flops against the fp64 matrix peak
         "prefill": {"ms": prefill_ms, "prompt_tokens_per_s": U * w.prompt / (prefill_ms * 1e-3),
                     "bound": "mfma", "achieved": prefill_flops / (prefill_ms * 1e-3) / 1e12, "peak": 78.6,
                     "unit": "TFLOP/s", "frac": prefill_flops / (prefill_ms * 1e-3) / 1e12 / 78.6,
                     "flops": prefill_flops,
-                    "note": "algorithmic flops count Q K^T twice (row statistics, column sums) and A V; the "
-                            "column sums are computed exactly (fp64) only for tokens that can be kept, found by a "
-                            "cheap fp16 pass, and A V runs in fp16, so the figure can exceed the fp64 peak"},
+                    "note": ("algorithmic flops count Q K^T twice (row statistics, column sums) and A V; the "
+                             "column sums are computed exactly (fp64) only for tokens that can be kept, found by a "
+                             "cheap fp16 pass, and A V runs in fp16, so the figure can exceed the fp64 peak")
+                            if not flags & 2 else
+                            ("algorithmic flops of this policy: scores in fp64 (all causal pairs, or with the policy "
+                             "active through the prompt only the cached ones plus rank-R weights of the discarded "
+                             "ones), A V in fp16, column sums of the kept tokens only")},
         # the dominant kernel: the attention launch (lessdec_step_attend), timed by itself
         "roofline": {"bound": "hbm", "achieved": attend_achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": attend_achieved / HBM_PEAK_GBS,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(w.cfg) if L >= 8 and w.q_per_kv == 1 else None,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(w.cfg) if L >= 8 and w.q_per_kv == 1 and flags == 0 else None,
                      "kernel": ("wpu_step_kernel" if w.q_per_kv == 1 else "gqa_staged_kernel") + " (lessdec_step_attend)",
                      "bytes_per_launch": attend_bytes, "ms_per_launch": half_ms[True],
                      "features_ms_per_launch": half_ms[False],
@@ -233,7 +263,7 @@ def main():
                                      / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS},
     }
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(w, min(args.cpu_units, U), min(args.cpu_steps, T))
+        result["cpu_baseline"] = cpu_baseline(w, min(args.cpu_units, U), min(args.cpu_steps, T), flags)
     print(json.dumps(result), flush=True)
 
 

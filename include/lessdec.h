@@ -143,6 +143,10 @@ int lessdec_state_sync(const lessdec_desc *desc, void *hip_stream);
  * lessdec_step per prompt token t with rows Q[.,.,t,.], K[.,.,t,.], V[.,.,t,.] (2 P launches
  * plus row staging; not the fast way through a prompt): out[.,.,t,.] is then Eq. 3's output
  * at token t, and the state afterwards is the state after P steps (a fold may be pending).
+ * With LESSDEC_FLAG_LAMBDA as well and P > n_heavy + n_recent the same results (outputs, slot
+ * order and state, to rounding) are computed for all prompt tokens at once: under that policy
+ * the cache each token meets is known beforehand (Sec. 3.2 builds the same masked matrix for
+ * training); nothing is left pending then.
  * Overwrites any previous state of the descriptor (no reset needed before it).
  * P >= 1.  Needs the workspace sized for max_prompt >= P.
  */

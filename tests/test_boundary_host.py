@@ -57,6 +57,9 @@ def _desc(**kw):
 def test_workspace_bytes_and_shape_validation():
     assert binding.lessdec_workspace_bytes(_desc(), 0) > 0
     assert binding.lessdec_workspace_bytes(_desc(), 512) > binding.lessdec_workspace_bytes(_desc(), 0)
+    # Lambda-masking through the prompt also holds phi of every prompt query
+    assert binding.lessdec_workspace_bytes(_desc(flags=6), 512) > binding.lessdec_workspace_bytes(_desc(flags=2), 512)
+    assert binding.lessdec_workspace_bytes(_desc(flags=4), 512) == binding.lessdec_workspace_bytes(_desc(), 512)
     for bad in (dict(head_dim=96), dict(rank=0), dict(rank=65), dict(hidden=0), dict(hidden=4096),
                 dict(n_heavy=0, n_recent=0), dict(n_heavy=4000, n_recent=4000), dict(dtype=7),
                 dict(batch=0), dict(flags=8), dict(n_heavy=-1), dict(q_per_kv=-1), dict(q_per_kv=129),
