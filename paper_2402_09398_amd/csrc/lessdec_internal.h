@@ -101,6 +101,7 @@ struct PrefillArgs {
   int32_t *count;           // [U] length of each unit's list
   float *psi_all;           // [U,P,R]
   float *phi_all = nullptr; // [U*G,P,R], only for the masked form
+  float *psimax = nullptr;  // [U,R] feature-wise maximum of psi over the prompt, only for the masked form
   int masked = 0;           // Lambda-masking through the prompt token by token, all rows at once
 };
 hipError_t launch_prefill(const PrefillArgs &a, hipStream_t st);

@@ -298,6 +298,26 @@ __global__ __launch_bounds__(64 * kPrefillWaves) void prefill_rowpass_kernel(
 }
 
 // -------------------------------------------------------------------------------------
+// Feature-wise maximum of psi over a unit's prompt keys: psimax[u][r] = max_j psi_all[u][j][r].
+// The values are >= 0 (Eq. 2 ends in an absolute value), so they order like their bit patterns
+// and an integer LDS maximum does.   grid = U, block = 256.
+// -------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void prefill_psimax_kernel(const float *__restrict__ psi_all, int P, int R,
+                                                             float *__restrict__ psimax)
+{
+  __shared__ int s_max[LESSDEC_MAX_RANK];
+  const size_t u = blockIdx.x;
+  const int tid = threadIdx.x;
+  if (tid < R) s_max[tid] = 0;
+  __syncthreads();
+  const float *pa = psi_all + u * (size_t)P * R;
+  const int n = P * R;
+  for (int i = tid; i < n; i += 256) atomicMax(&s_max[i % R], __float_as_int(pa[i]));
+  __syncthreads();
+  if (tid < R) psimax[u * R + tid] = __int_as_float(s_max[tid]);
+}
+
+// -------------------------------------------------------------------------------------
 // Masked row pass: Lambda-masking taken through the prompt token by token (Sec. 4, "Setup";
 // Sec. 3.2 builds the same matrix for training), all rows at once.  Under that policy the cache
 // that token t meets is known beforehand: the first Nh tokens and the Nr tokens before it, the
@@ -309,16 +329,17 @@ __global__ __launch_bounds__(64 * kPrefillWaves) void prefill_rowpass_kernel(
 // first query on), staged through the LDS as there, all other entries masked out.  Then every
 // wave sweeps, on its own, the tiles that hold pairs discarded before its queries: the 16 x 16
 // tile psi(K) phi(Q)^T is R / 4 matrix instructions instead of D / 4, nothing is staged.
-// Online normalisation as in the row pass, the low-rank entries entering as w e^{-m}; m also
-// rises to ln(w) where that would exceed 1, so every weight handed to p V stays in [0, 1].
+// Online normalisation as in the row pass, the low-rank entries entering as w e^{-m}; before the
+// second sweep m rises to ln of an upper bound of the query's weights (phi(q) . max_j psi(k_j),
+// psimax [U, R] from prefill_psimax_kernel), so every weight handed to p V stays in [0, 1].
 // Leaves lse_t = m_t + ln(sum of the entries that H2O's scores are normalised by): all of them,
 // or with the sparse-denominator flag the exponentials only.
 // -------------------------------------------------------------------------------------
 template <typename T, int D>
 __global__ __launch_bounds__(64 * kPrefillWaves) void prefill_maskedrows_kernel(
     const T *__restrict__ Q, const T *__restrict__ K, const T *__restrict__ V, unsigned U, int G, int P,
-    const float *__restrict__ phi, const float *__restrict__ psi, int R, int Nh, int Nr, int sparse_den,
-    double *__restrict__ lse, T *__restrict__ out)
+    const float *__restrict__ phi, const float *__restrict__ psi, const float *__restrict__ psimax, int R, int Nh,
+    int Nr, int sparse_den, double *__restrict__ lse, T *__restrict__ out)
 {
   constexpr int CH = D / 4, DB = D / 16;
   constexpr bool kHalf = sizeof(T) == 2;
@@ -458,6 +479,33 @@ __global__ __launch_bounds__(64 * kPrefillWaves) void prefill_maskedrows_kernel(
       const float x = phi_q[r < R ? r : R - 1];
       fq[s] = r < R ? (double)x : 0.0;
     }
+    // No weight of this query can exceed wb = phi(q) . max_j psi(k_j) (all features are >= 0), so
+    // m rises to ln(wb) once, here, and every w e^{-m} handed to p V below stays in [0, 1]
+    // without the sweep tracking a maximum.
+    {
+      const float *pm = psimax + ukv * (size_t)R;
+      double wb = 0.0;
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        const int r = 4 * s + g;
+        wb = fma(fq[s], (double)pm[r < R ? r : R - 1], wb);  // fq is 0 past R
+      }
+      for (int r = 16 + g; r < R; r += 4) wb = fma((double)phi_q[r], (double)pm[r], wb);
+      wb += __shfl_xor(wb, 16);
+      wb += __shfl_xor(wb, 32);
+      const double m_new = wb > 0.0 ? fmax(m_run, log(wb)) : m_run;
+      if (m_new > m_run) {
+        const double alpha = exp(m_run - m_new);
+        L *= alpha;
+        m_run = m_new;
+        em_run = exp(-m_new);
+        if (out != nullptr) {
+          const float af = (float)alpha;
+#pragma unroll
+          for (int b = 0; b < DB; ++b) O[b] *= af;
+        }
+      }
+    }
     auto psi_operands = [&](int j0, float (&a)[4]) {
       const int kr = j0 + c;                                  // a tile of the last, ragged query block can pass the prompt end
       const float *prow = psi_u + (size_t)(kr < P ? kr : P - 1) * R;
@@ -491,35 +539,11 @@ __global__ __launch_bounds__(64 * kPrefillWaves) void prefill_maskedrows_kernel(
         const double a = r < R ? (double)psi_u[(size_t)kr * R + r] : 0.0, b = r < R ? (double)phi_q[r] : 0.0;
         wt = __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, wt, 0, 0, 0);
       }
-      double wv[4], wmax = 0.0;
-#pragma unroll
-      for (int v = 0; v < 4; ++v) {
-        const int kj = j0 + g + 4 * v;
-        wv[v] = (kj >= Nh && kj < qi - Nr) ? wt[v] : 0.0;
-        wmax = fmax(wmax, wv[v]);
-      }
-      wmax = fmax(wmax, __shfl_xor(wmax, 16));
-      wmax = fmax(wmax, __shfl_xor(wmax, 32));
-      // m also rises to ln(w) where w e^{-m} would exceed 1: every weight handed to p V stays in [0, 1]
-      if (__any(wmax * em_run > 1.0)) {
-        const double m_new = wmax > 0.0 ? fmax(m_run, log(wmax)) : m_run;
-        if (m_new > m_run) {
-          const double alpha = exp(m_run - m_new);
-          L *= alpha;
-          Lw *= alpha;
-          m_run = m_new;
-          em_run = exp(-m_new);
-          if (out != nullptr) {
-            const float af = (float)alpha;
-#pragma unroll
-            for (int b = 0; b < DB; ++b) O[b] *= af;
-          }
-        }
-      }
       double e[4], wsum = 0.0;
 #pragma unroll
       for (int v = 0; v < 4; ++v) {
-        e[v] = fmin(wv[v] * em_run, 1.0);
+        const int kj = j0 + g + 4 * v;
+        e[v] = (kj >= Nh && kj < qi - Nr) ? fmin(wt[v] * em_run, 1.0) : 0.0;
         wsum += e[v];
       }
       Lw += wsum;
@@ -1138,9 +1162,11 @@ static hipError_t launch_prefill_t(const PrefillArgs &a, hipStream_t st)
       e = launch_featmap_generic(fa, d->dtype, st);
     }
     if (e != hipSuccess) return e;
+    prefill_psimax_kernel<<<U, 256, 0, st>>>(a.psi_all, P, d->rank, a.psimax);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
     prefill_maskedrows_kernel<T, D><<<(U * G + kXcds - 1) / kXcds * kXcds * tiles, 64 * kPrefillWaves, 0, st>>>(
-        (const T *)a.Q, (const T *)a.K, (const T *)a.V, U * G, G, P, a.phi_all, a.psi_all, d->rank, d->n_heavy,
-        d->n_recent, (d->flags & LESSDEC_FLAG_SPARSE_DENOM) ? 1 : 0, a.lse, (T *)a.out);
+        (const T *)a.Q, (const T *)a.K, (const T *)a.V, U * G, G, P, a.phi_all, a.psi_all, a.psimax, d->rank,
+        d->n_heavy, d->n_recent, (d->flags & LESSDEC_FLAG_SPARSE_DENOM) ? 1 : 0, a.lse, (T *)a.out);
   } else {
     prefill_rowpass_kernel<T, D><<<(U * G + kXcds - 1) / kXcds * kXcds * tiles, 64 * kPrefillWaves, 0, st>>>(
         (const T *)a.Q, (const T *)a.K, (const T *)a.V, U * G, G, P, a.lse, (T *)a.out);
