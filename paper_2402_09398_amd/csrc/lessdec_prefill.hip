@@ -175,7 +175,7 @@ __device__ inline void store_out(__half *orow, int g, const v4f (&O)[D / 16], fl
 // element g D/4 + s) as one 16-byte piece at index (4 i + g) 16 + c: conflict-free.
 // -------------------------------------------------------------------------------------
 template <typename T, int D>
-__global__ __launch_bounds__(64 * kPrefillWaves) void prefill_rowpass_kernel(
+__global__ __launch_bounds__(64 * kPrefillWaves) __attribute__((amdgpu_waves_per_eu(2, 2))) void prefill_rowpass_kernel(
     const T *__restrict__ Q, const T *__restrict__ K, const T *__restrict__ V, unsigned U, int G, int P,
     double *__restrict__ lse, T *__restrict__ out)
 {
@@ -336,7 +336,7 @@ __global__ __launch_bounds__(256) void prefill_psimax_kernel(const float *__rest
 // or with the sparse-denominator flag the exponentials only.
 // -------------------------------------------------------------------------------------
 template <typename T, int D>
-__global__ __launch_bounds__(64 * kPrefillWaves) void prefill_maskedrows_kernel(
+__global__ __launch_bounds__(64 * kPrefillWaves) __attribute__((amdgpu_waves_per_eu(2, 2))) void prefill_maskedrows_kernel(
     const T *__restrict__ Q, const T *__restrict__ K, const T *__restrict__ V, unsigned U, int G, int P,
     const float *__restrict__ phi, const float *__restrict__ psi, const float *__restrict__ psimax, int R, int Nh,
     int Nr, int sparse_den, double *__restrict__ lse, T *__restrict__ out)
