@@ -82,6 +82,91 @@ __global__ __launch_bounds__(256) void mlp_pair_kernel(const MlpArgs a, const Ml
   else mlp_psi_block<D, kPairTiles>(b, blockIdx.x - na);
 }
 
+// Many rows per head (the prompt phase): a workgroup keeps its head's weights in registers and
+// streams rows through them.  Wave w holds the groups of 32 hidden units w, w + 4, ... (NGW of
+// them: R' = 128 NGW) for the whole kernel; per chunk of 16 kRowTiles rows it loads the rows,
+// applies its groups, and the block adds the four layer-2 sums through the LDS and finishes the
+// outputs as above (same arithmetic in the same order as mlp_psi_block: identical results).  The
+// next chunk's rows are requested before the current chunk's arithmetic.
+// grid = Hh * parts (head fastest), every block a contiguous share of the head's chunks.
+constexpr int kRowTiles = 1;
+template <int D, int NGW>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void mlp_rows_kernel(const MlpArgs a,
+                                                                                                  int parts)
+{
+  __shared__ float s_red[4][16][16 * kRowTiles + 1];       // [wave][r][row]
+  __shared__ double s_h2[16 * kRowTiles][17];              // [row][r]
+  const int tid = threadIdx.x, wave = tid / 64, l = tid % 64, g = l / 16, c = l % 16;
+  const int Hh = a.Hh, Rp = a.Rp, R = a.R;
+  const int h = (int)blockIdx.x % Hh, part = (int)blockIdx.x / Hh;
+  const __half *W1 = a.W1 + (size_t)h * Rp * D;
+  const __half *W2 = a.W2 + (size_t)h * R * Rp;
+  const long rows_head = (long)a.B * a.rpu;
+  const long nchunk = (rows_head + 16 * kRowTiles - 1) / (16 * kRowTiles);
+  const long ch0 = nchunk * part / parts, ch1 = nchunk * (part + 1) / parts;
+  auto global_row = [&](long i) -> long {
+    const long bb = i / a.rpu, p = i % a.rpu;
+    return (bb * Hh + h) * (long)a.rpu + p;
+  };
+  MlpTiles<D> w[NGW];
+#pragma unroll
+  for (int k = 0; k < NGW; ++k) w[k] = mlp_load_tiles<D>(W1, W2, Rp, R, 32 * (wave + 4 * k), g, c);
+  const int r = tid % 16;
+  __shared__ double s_w3[16][17];                          // W3 of the head, widened once; W3 == nullptr: phi (Eq. 1)
+  {
+    const int j = tid / 16;
+    s_w3[r][j] = (a.W3 != nullptr && r < R && j < R) ? (double)__half2float(a.W3[((size_t)h * R + r) * R + j]) : 0.0;
+  }
+
+  auto load_chunk = [&](long ch, v8h (&bx)[kRowTiles][D / 32]) {
+#pragma unroll
+    for (int t = 0; t < kRowTiles; ++t) {
+      const long i = (ch * kRowTiles + t) * 16 + c;
+      mlp_load_row<D>(a.x + (i < rows_head ? global_row(i) : 0) * D, g, bx[t]);   // padding: any row
+    }
+  };
+  v8h bx_next[kRowTiles][D / 32];
+  if (ch0 < ch1) load_chunk(ch0, bx_next);
+  for (long ch = ch0; ch < ch1; ++ch) {
+    v8h bx[kRowTiles][D / 32];
+#pragma unroll
+    for (int t = 0; t < kRowTiles; ++t)
+#pragma unroll
+      for (int ks = 0; ks < D / 32; ++ks) bx[t][ks] = bx_next[t][ks];
+    load_chunk(ch + 1 < ch1 ? ch + 1 : ch, bx_next);
+    v4f c2[kRowTiles];
+#pragma unroll
+    for (int t = 0; t < kRowTiles; ++t) c2[t] = v4f{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int k = 0; k < NGW; ++k)
+#pragma unroll
+      for (int t = 0; t < kRowTiles; ++t) mlp_apply_tiles<D>(w[k], bx[t], c2[t]);
+    __syncthreads();                                       // the previous chunk's readers are done
+#pragma unroll
+    for (int t = 0; t < kRowTiles; ++t)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) s_red[wave][4 * g + q][16 * t + c] = c2[t][q];
+    __syncthreads();
+    for (int row = tid / 16; row < 16 * kRowTiles; row += 16) {
+      const float sum = ((s_red[0][r][row] + s_red[1][r][row]) + s_red[2][r][row]) + s_red[3][r][row];
+      s_h2[row][r] = (r < R) ? gelu_poly_f64((double)sum) : 0.0;
+    }
+    __syncthreads();
+    for (int row = tid / 16; row < 16 * kRowTiles; row += 16) {
+      const long i = ch * (16 * kRowTiles) + row;
+      if (r < R && i < rows_head) {
+        double acc3 = 0.0;
+        if (a.W3 != nullptr) {
+          for (int j = 0; j < R; ++j) acc3 = fma(s_h2[row][j], s_w3[r][j], acc3);
+        } else {
+          acc3 = s_h2[row][r];
+        }
+        a.out[(size_t)global_row(i) * R + r] = (float)fabs(acc3);
+      }
+    }
+  }
+}
+
 // Decode step: both maps for every unit, by parts of 64 hidden units.  One block = one
 // (head, map, part, chunk of 64 batch rows); its four waves take 16 rows each and the same
 // two groups of 32 hidden units, so the head's weights are read once per 64 rows.  Head
@@ -133,6 +218,25 @@ bool mlp_mfma_supported(int dtype, int D, int Rp, int R)
 hipError_t launch_mlp(const MlpArgs &a, hipStream_t st)
 {
   const long rows_head = (long)a.B * a.rpu;
+  // many rows per head and R' = 128, 256, 384 or 512: weights stay in registers, rows stream through
+  const int ngw = a.Rp % 128 == 0 ? a.Rp / 128 : 0;
+  const long nchunk = (rows_head + 16 * kRowTiles - 1) / (16 * kRowTiles);
+  if (ngw >= 1 && ngw <= 4 && nchunk >= 64) {
+    long parts = 1024 / a.Hh;                              // about four workgroups per compute unit
+    if (parts < 1) parts = 1;
+    if (parts > nchunk / 8) parts = nchunk / 8;            // at least 8 chunks behind every weight load
+    const unsigned grid = (unsigned)(a.Hh * parts);
+#define LESSDEC_MLP_ROWS(DD, NG) mlp_rows_kernel<DD, NG><<<grid, 256, 0, st>>>(a, (int)parts)
+    if (a.D == 128) {
+      if (ngw == 1) LESSDEC_MLP_ROWS(128, 1); else if (ngw == 2) LESSDEC_MLP_ROWS(128, 2);
+      else if (ngw == 3) LESSDEC_MLP_ROWS(128, 3); else LESSDEC_MLP_ROWS(128, 4);
+    } else {
+      if (ngw == 1) LESSDEC_MLP_ROWS(64, 1); else if (ngw == 2) LESSDEC_MLP_ROWS(64, 2);
+      else if (ngw == 3) LESSDEC_MLP_ROWS(64, 3); else LESSDEC_MLP_ROWS(64, 4);
+    }
+#undef LESSDEC_MLP_ROWS
+    return hipGetLastError();
+  }
   const unsigned grid = (unsigned)(((rows_head + 16 * kPsiTiles - 1) / (16 * kPsiTiles)) * a.Hh);
   if (a.D == 128) mlp_psi_kernel<128><<<grid, 256, 0, st>>>(a);
   else mlp_psi_kernel<64><<<grid, 256, 0, st>>>(a);
