@@ -58,13 +58,11 @@ template <> __device__ inline void store_four<__half>(__half *p, const float (&v
 
 }  // namespace
 
-// q, out: [U,G,D]; k, v: [U,D]; f_phi [U,G,R] fp64 or f_phi32 in fp32; f_psi: [U,R] fp32.
-// grid = U, block = 256, dynamic LDS: see launch_step_gqa_t.
-// After the last head: accumulated scores, eviction choice, fold of the discarded pair into
-// H, z (Eq. 4, Eq. 5), in-place insert of the new pair (Sec. 3.2).  s_inc holds the step's
-// probabilities per pair summed over the heads; s_e is scratch of the same size.
-// A caller that holds LDS copies of the unit's rows passes them in LdsCopies (as they were before
-// the step: H before the fold); every null member is read from memory instead.
+// Layouts of this file's kernels: q, out [U,G,D]; k, v [U,D]; f_phi [U,G,R] fp64 or f_phi32 in
+// fp32; f_psi [U,R] fp32.
+
+// LDS copies of a unit's rows as they were before the step (H before the fold), for
+// gqa_finish_unit; every null member is read from memory instead.
 template <typename T>
 struct LdsCopies {
   const T *k = nullptr, *v = nullptr;      // [m+1, D] rows in slot order, the appended pair last
@@ -73,6 +71,10 @@ struct LdsCopies {
   const int *pos = nullptr;                // [m]
 };
 
+// After the unit's last head, by the whole block of 256 threads: accumulated scores, eviction
+// choice, fold of the discarded pair into H, z (Eq. 4, Eq. 5), in-place insert of the new pair
+// (Sec. 3.2).  s_inc holds the step's probabilities per pair summed over the heads; s_e is
+// scratch of the same size; s_cand 256 entries.
 template <typename T, int D>
 __device__ inline void gqa_finish_unit(const StepArgs &a, int u, int tid, double *s_e, const double *s_inc,
                                        Cand *s_cand, const LdsCopies<T> lds = LdsCopies<T>())
