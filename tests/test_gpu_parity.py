@@ -78,6 +78,9 @@ EDGE = [
     small("d64-f16", head_dim=64),
     small("d128-f32", dtype="f32"),
     small("wide-cache", n_heavy=150, n_recent=150, prompt=400, steps=24, batch=1, heads=2),
+    # 1024 prompt rows or more per head: psi of the prompt keys from the row-streaming kernel
+    small("psi-streaming-d64-hidden-256", head_dim=64, hidden=256, batch=4, heads=2, prompt=300, steps=6),
+    small("psi-streaming-hidden-384-ragged-rows", hidden=384, rank=5, batch=3, heads=2, prompt=347, steps=6),
     # few units: the rows of a unit are split over 2, 4, 8 waves (32, 64, 128+ rows)
     small("split-2-waves", n_heavy=20, n_recent=20, prompt=100, steps=30),
     small("split-4-waves", n_heavy=35, n_recent=35, prompt=100, steps=30, head_dim=64, rank=16),
