@@ -40,11 +40,11 @@ bool shape_ok(const lessdec_desc *d, Shape *s)
 }
 
 // Workspace: [ f_phi U*R f64 | f_psi U*R f32 | mlp_parts 2*ceil(R'/64)*U*16 f32 |
-//              prefill: 4 staged rows U*D (4 bytes each) | lse U*G*P f64, colsum U*P f64 | approx U*P f32, list U*P i32, count U i32 | slot_of U*P i32 | psi_all U*P*R f32 | phi_all U*G*P*R f32, psimax U*R f32 (masked prompt only) ],
+//              prefill: 4 staged rows U*D (4 bytes each) | lse U*G*P f64, colsum U*P f64 | approx U*P f32, list U*P i32, count U i32 | slot_of U*P i32 | psi_all U*P*R f32 | phi_all U*G*P*R f32, psimax U*R f32, hpre U*(P/64+1)*R*D f32, zpre U*(P/64+1)*R f32 (masked prompt only) ],
 // every part 256-byte aligned.
 struct Workspace {
   size_t off_fphi, off_fpsi, off_parts, off_gqa, off_stage, off_lse, off_colsum, off_approx, off_list, off_count, off_slot,
-      off_psiall, off_phiall, off_psimax, total;
+      off_psiall, off_phiall, off_psimax, off_hpre, off_zpre, total;
 };
 
 Workspace carve(const Shape &s, size_t P, unsigned flags)
@@ -67,6 +67,9 @@ Workspace carve(const Shape &s, size_t P, unsigned flags)
   const bool masked = (flags & LESSDEC_FLAG_LAMBDA) && (flags & LESSDEC_FLAG_PROMPT_STEPWISE);
   w.off_phiall = o; o = align_up(o + (masked ? s.U * s.G * P * s.R * sizeof(float) : 0), 256);
   w.off_psimax = o; o = align_up(o + (masked && P ? s.U * s.R * sizeof(float) : 0), 256);
+  const size_t nkb = P / 64 + 1;                            // prefix states of the masked prompt, one per 64 keys
+  w.off_hpre = o; o = align_up(o + (masked && P ? s.U * nkb * s.R * s.D * sizeof(float) : 0), 256);
+  w.off_zpre = o; o = align_up(o + (masked && P ? s.U * nkb * s.R * sizeof(float) : 0), 256);
   w.total = o;
   return w;
 }
@@ -277,6 +280,8 @@ int lessdec_prefill(const lessdec_desc *desc, const void *Q, const void *K, cons
   a.psi_all = reinterpret_cast<float *>(ws + w.off_psiall);
   a.phi_all = reinterpret_cast<float *>(ws + w.off_phiall);
   a.psimax = reinterpret_cast<float *>(ws + w.off_psimax);
+  a.hpre = reinterpret_cast<float *>(ws + w.off_hpre);
+  a.zpre = reinterpret_cast<float *>(ws + w.off_zpre);
   a.masked = masked ? 1 : 0;
   return launch_prefill(a, (hipStream_t)hip_stream) == hipSuccess ? LESSDEC_OK : LESSDEC_EHIP;
 }

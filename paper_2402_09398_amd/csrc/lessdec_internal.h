@@ -102,6 +102,8 @@ struct PrefillArgs {
   float *psi_all;           // [U,P,R]
   float *phi_all = nullptr; // [U*G,P,R], only for the masked form
   float *psimax = nullptr;  // [U,R] feature-wise maximum of psi over the prompt, only for the masked form
+  float *hpre = nullptr;    // [U, P/64+1, R, D] prefix sums of psi^T v, only for the masked form
+  float *zpre = nullptr;    // [U, P/64+1, R] prefix sums of psi, only for the masked form
   int masked = 0;           // Lambda-masking through the prompt token by token, all rows at once
 };
 hipError_t launch_prefill(const PrefillArgs &a, hipStream_t st);

@@ -318,6 +318,63 @@ __global__ __launch_bounds__(256) void prefill_psimax_kernel(const float *__rest
 }
 
 // -------------------------------------------------------------------------------------
+// Prefix states for the masked row pass: hpre[u][kb] = sum of psi(k_j)^T v_j and zpre[u][kb] =
+// sum of psi(k_j) over the pairs Nh <= j < 64 kb (Eq. 6 restricted to a prefix), kb = 0 ..
+// P / 64: what the low-rank part of Eq. 3 needs for a query whose discarded pairs reach at least
+// to 64 kb.  fp32 sums (they only enter attention outputs and their normalisation, never a
+// score; the state itself is built in fp64 by the finalize kernel).
+// One workgroup per unit walks the keys in order, 64 at a time through the LDS; thread (d, rg)
+// owns column d of rows rg, rg + 256 / D, ... of H, RC of them.   grid = U, block = 256.
+// -------------------------------------------------------------------------------------
+constexpr int kPrefixKeys = 64;
+template <typename T, int D, int RC>
+__global__ __launch_bounds__(256) void prefill_prefix_kernel(const T *__restrict__ V,
+                                                             const float *__restrict__ psi_all, int P, int R,
+                                                             int Nh, float *__restrict__ hpre,
+                                                             float *__restrict__ zpre)
+{
+  constexpr int NG = 256 / D;                               // row groups
+  __shared__ float s_psi[kPrefixKeys][LESSDEC_MAX_RANK + 1];
+  const size_t u = blockIdx.x;
+  const int tid = threadIdx.x, d = tid % D, rg = tid / D;
+  const int nkb = P / kPrefixKeys + 1;
+  const T *Vu = V + u * (size_t)P * D;
+  const float *pa = psi_all + u * (size_t)P * R;
+  float *hu = hpre + u * (size_t)nkb * R * D;
+  float *zu = zpre + u * (size_t)nkb * R;
+  float acc[RC];
+#pragma unroll
+  for (int i = 0; i < RC; ++i) acc[i] = 0.f;
+  float zacc = 0.f;                                         // thread r < R: z's entry r
+  for (int kb = 0; kb < nkb; ++kb) {
+    // the state before this block of keys
+#pragma unroll
+    for (int i = 0; i < RC; ++i) {
+      const int r = rg + NG * i;
+      if (r < R) hu[((size_t)kb * R + r) * D + d] = acc[i];
+    }
+    if (tid < R) zu[(size_t)kb * R + tid] = zacc;
+    const int j0 = kb * kPrefixKeys;
+    if (j0 >= P) break;                                     // uniform
+    const int nj = P - j0 < kPrefixKeys ? P - j0 : kPrefixKeys;
+    __syncthreads();                                        // the previous block's readers are done
+    for (int i = tid; i < nj * R; i += 256) {
+      const int jj = i / R, r = i % R;
+      s_psi[jj][r] = j0 + jj >= Nh ? pa[(size_t)j0 * R + i] : 0.f;   // the first Nh pairs are never discarded
+    }
+    __syncthreads();
+#pragma unroll 8
+    for (int jj = 0; jj < nj; ++jj) {
+      const float v = Store<T>::to_float(Vu[(size_t)(j0 + jj) * D + d]);
+#pragma unroll
+      for (int i = 0; i < RC; ++i) acc[i] = fmaf(s_psi[jj][(rg + NG * i) % (LESSDEC_MAX_RANK + 1)], v, acc[i]);
+    }
+    if (tid < R)
+      for (int jj = 0; jj < nj; ++jj) zacc += s_psi[jj][tid];
+  }
+}
+
+// -------------------------------------------------------------------------------------
 // Masked row pass: Lambda-masking taken through the prompt token by token (Sec. 4, "Setup";
 // Sec. 3.2 builds the same matrix for training), all rows at once.  Under that policy the cache
 // that token t meets is known beforehand: the first Nh tokens and the Nr tokens before it, the
@@ -338,8 +395,9 @@ __global__ __launch_bounds__(256) void prefill_psimax_kernel(const float *__rest
 template <typename T, int D>
 __global__ __launch_bounds__(64 * kPrefillWaves) __attribute__((amdgpu_waves_per_eu(2, 2))) void prefill_maskedrows_kernel(
     const T *__restrict__ Q, const T *__restrict__ K, const T *__restrict__ V, unsigned U, int G, int P,
-    const float *__restrict__ phi, const float *__restrict__ psi, const float *__restrict__ psimax, int R, int Nh,
-    int Nr, int sparse_den, double *__restrict__ lse, T *__restrict__ out)
+    const float *__restrict__ phi, const float *__restrict__ psi, const float *__restrict__ psimax,
+    const float *__restrict__ hpre, const float *__restrict__ zpre, int R, int Nh, int Nr, int sparse_den,
+    double *__restrict__ lse, T *__restrict__ out)
 {
   constexpr int CH = D / 4, DB = D / 16;
   constexpr bool kHalf = sizeof(T) == 2;
@@ -467,7 +525,8 @@ __global__ __launch_bounds__(64 * kPrefillWaves) __attribute__((amdgpu_waves_per
   // R / 4 matrix instructions; entries of pairs that are cached for the lane's query are masked
   // out.  The next tile's value rows and psi operands are requested before this tile's arithmetic.
   double Lw = 0.0;                                         // sum of the low-rank entries, times e^{-m_run}
-  const int jt_lo = Nh / 16, jt_hi = (it * 16 + 14 - Nr) >= 0 ? (it * 16 + 14 - Nr) / 16 : -1;
+  int jt_lo = Nh / 16;
+  const int jt_hi = (it * 16 + 14 - Nr) >= 0 ? (it * 16 + 14 - Nr) / 16 : -1;
   if (active && jt_lo <= jt_hi) {
     // m_run is finite for every query of the prompt: the diagonal tile held the query itself
     double em_run = m_run > -__builtin_inf() ? exp(-m_run) : 0.0;
@@ -505,6 +564,38 @@ __global__ __launch_bounds__(64 * kPrefillWaves) __attribute__((amdgpu_waves_per
           for (int b = 0; b < DB; ++b) O[b] *= af;
         }
       }
+    }
+    // Pairs before 64 kbq were discarded before every query of this wave (and the first Nh are
+    // left out of the prefix states): their share of Eq. 3 is phi(q) hpre[kbq] e^{-m} in the
+    // numerator, on fp32 matrix tiles in the output layout of p V, and phi(q) zpre[kbq] e^{-m} in
+    // the denominator.  Only the tiles from 64 kbq on are swept entry by entry.
+    const int kbq = it * 16 - Nr > 0 ? (it * 16 - Nr) / kPrefixKeys : 0;
+    if (kbq * kPrefixKeys > Nh) {
+      const int nkb = P / kPrefixKeys + 1;
+      const float *hk = hpre + (ukv * (size_t)nkb + kbq) * R * D;
+      const float *zk = zpre + (ukv * (size_t)nkb + kbq) * R;
+      double zsum = 0.0;
+      // one step = features 4 s + g: f the lane's phi entry (0 past R), rc its clamped row
+      auto prefix_step = [&](double f, int rc) {
+        zsum = fma(f, (double)zk[rc], zsum);
+        if (out != nullptr) {
+          const float bf = (float)(f * em_run);
+#pragma unroll
+          for (int b = 0; b < DB; ++b) {
+            const float a = hk[(size_t)rc * D + (kHalf ? DB * c + b : 16 * b + c)];
+            O[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, bf, O[b], 0, 0, 0);
+          }
+        }
+      };
+#pragma unroll
+      for (int s = 0; s < 4; ++s)
+        if (4 * s < R) prefix_step(fq[s], 4 * s + g < R ? 4 * s + g : R - 1);
+      for (int s = 4; 4 * s < R; ++s) {
+        const int r = 4 * s + g, rc = r < R ? r : R - 1;
+        prefix_step(r < R ? (double)phi_q[rc] : 0.0, rc);
+      }
+      Lw += zsum * em_run;                                    // this lane group's features; the groups are added at the end
+      if (jt_lo < kbq * (kPrefixKeys / 16)) jt_lo = kbq * (kPrefixKeys / 16);
     }
     auto psi_operands = [&](int j0, float (&a)[4]) {
       const int kr = j0 + c;                                  // a tile of the last, ragged query block can pass the prompt end
@@ -1164,8 +1255,17 @@ static hipError_t launch_prefill_t(const PrefillArgs &a, hipStream_t st)
     if (e != hipSuccess) return e;
     prefill_psimax_kernel<<<U, 256, 0, st>>>(a.psi_all, P, d->rank, a.psimax);
     if ((e = hipGetLastError()) != hipSuccess) return e;
+    {
+      const int rc = (d->rank + 256 / D - 1) / (256 / D);   // rows of H per thread
+#define LESSDEC_PREFIX(RC) prefill_prefix_kernel<T, D, RC><<<U, 256, 0, st>>>((const T *)a.V, a.psi_all, P, d->rank, \
+                                                                              d->n_heavy, a.hpre, a.zpre)
+      if (rc <= 4) LESSDEC_PREFIX(4); else if (rc <= 8) LESSDEC_PREFIX(8);
+      else if (rc <= 16) LESSDEC_PREFIX(16); else LESSDEC_PREFIX(32);
+#undef LESSDEC_PREFIX
+    }
+    if ((e = hipGetLastError()) != hipSuccess) return e;
     prefill_maskedrows_kernel<T, D><<<(U * G + kXcds - 1) / kXcds * kXcds * tiles, 64 * kPrefillWaves, 0, st>>>(
-        (const T *)a.Q, (const T *)a.K, (const T *)a.V, U * G, G, P, a.phi_all, a.psi_all, a.psimax, d->rank,
+        (const T *)a.Q, (const T *)a.K, (const T *)a.V, U * G, G, P, a.phi_all, a.psi_all, a.psimax, a.hpre, a.zpre, d->rank,
         d->n_heavy, d->n_recent, (d->flags & LESSDEC_FLAG_SPARSE_DENOM) ? 1 : 0, a.lse, (T *)a.out);
   } else {
     prefill_rowpass_kernel<T, D><<<(U * G + kXcds - 1) / kXcds * kXcds * tiles, 64 * kPrefillWaves, 0, st>>>(
