@@ -254,7 +254,7 @@ def main():
         "roofline": {"bound": "hbm", "achieved": attend_achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": attend_achieved / HBM_PEAK_GBS,
                      "traffic": MEASURED_TRAFFIC_BYTES.get(w.cfg) if L >= 8 and w.q_per_kv == 1 and flags == 0 else None,
-                     "kernel": ("wpu_step_kernel" if w.q_per_kv == 1 else "gqa_staged_kernel") + " (lessdec_step_attend)",
+                     "kernel": ("wpu_step_kernel" if w.q_per_kv == 1 else "gqa_chunk_kernel") + " (lessdec_step_attend)",
                      "bytes_per_launch": attend_bytes, "ms_per_launch": half_ms[True],
                      "features_ms_per_launch": half_ms[False],
                      "whole_step": {"achieved": achieved, "frac": achieved / HBM_PEAK_GBS,

@@ -5,28 +5,14 @@
 // grows by its probability under every head.
 //
 // One block of 256 threads per unit (or per share of a unit's heads), all arithmetic fp64 in the
-// order of the equations.  Two forms: the staged one copies the unit's cache rows, H and z into
-// the LDS once and takes the heads four at a time; the streaming one (any capacity) takes them
-// one at a time and reads the rows from memory.  Both fold the discarded pair into H, z within
-// the step (nothing is left pending).
+// order of the equations, the heads four at a time; a block that goes over its unit's rows more
+// than once (more than four heads) first copies them into the LDS when they fit.  The discarded
+// pair is folded into H, z within the step (nothing is left pending).
 #include "lessdec_wave.h"
 
 namespace lessdec {
 
 namespace {
-
-// all-reduce over the block's four waves: within a wave by lane exchange, across waves through
-// four LDS words, combined in wave order
-template <typename Op>
-__device__ inline double block_allreduce(double v, double *s_red, int tid, Op op)
-{
-  v = wave_allreduce(v, op);
-  if (tid % kWave == 0) s_red[tid / kWave] = v;
-  __syncthreads();
-  const double r = op(op(op(s_red[0], s_red[1]), s_red[2]), s_red[3]);
-  __syncthreads();
-  return r;
-}
 
 // four adjacent stored elements (8 or 16 bytes, aligned) as floats, and back
 template <typename T> __device__ inline void load_four(const T *p, float (&v)[4]);
@@ -164,150 +150,19 @@ __device__ inline void gqa_finish_unit(const StepArgs &a, int u, int tid, double
   }
 }
 
-// Any capacity: the heads one after the other, each reading the unit's cache rows from memory.
-template <typename T, int D>
-__global__ __launch_bounds__(256) void gqa_stream_kernel(const StepArgs a, int G, int nhb)
-{
-  extern __shared__ double dyn[];
-  __shared__ double s_red[4];
-  __shared__ Cand s_cand[256];
-  __shared__ double s_num[256];
-  constexpr int EPL = Store<T>::kPerVec, LPR = D / EPL, RPB = 256 / LPR;   // lanes per row, rows per pass
-  using Vec = typename Store<T>::Vec;
-  // nhb blocks per unit, each with a contiguous share of the unit's heads
-  const int u = (int)blockIdx.x / nhb, hb = (int)blockIdx.x % nhb, tid = threadIdx.x;
-  const int g_begin = (int)((long)G * hb / nhb), g_end = (int)((long)G * (hb + 1) / nhb);
-  const int lr = tid % LPR, rb = tid / LPR;
-  const int C = a.C, R = a.R;
-  const int rows_cap = C + 2;
-  double *s_e = dyn;                       // [C+1] scores, then e^{s - m*}, then the new accumulated scores
-  double *s_inc = dyn + rows_cap;          // [C+1] this step's probabilities per pair, summed over the heads
-  double *s_q = s_inc + rows_cap;          // [D] the head's query
-  double *s_f = s_q + D;                   // [R] the head's phi(q)
-  double *s_z = s_f + 64;                  // [R] z
-
-  const int n = a.n_seen[u];
-  const int m = n < C ? n : C;             // live slots are 0..m-1 (slots fill in order)
-  const int rows = m + 1;                  // + the appended pair (K', V' of Eq. 3)
-  T *kc = reinterpret_cast<T *>(a.k_cache) + (size_t)u * C * D;
-  T *vc = reinterpret_cast<T *>(a.v_cache) + (size_t)u * C * D;
-  const T *kn = reinterpret_cast<const T *>(a.k) + (size_t)u * D;
-  const T *vn = reinterpret_cast<const T *>(a.v) + (size_t)u * D;
-  float *Hu = a.H + (size_t)u * R * D;
-  double *zu = a.z + (size_t)u * R;
-  const double sqrt_d = sqrt((double)D);
-
-  for (int r = tid; r < rows; r += 256) s_inc[r] = 0.0;
-  if (tid < R) s_z[tid] = zu[tid];
-
-  // a head's query element and phi entry of this thread, requested one head ahead
-  auto fetch_q = [&](int g) -> double {
-    return tid < D ? (double)Store<T>::to_float(reinterpret_cast<const T *>(a.q)[((size_t)u * G + g) * D + tid]) : 0.0;
-  };
-  auto fetch_f = [&](int g) -> double {
-    if (tid >= R) return 0.0;
-    const size_t i = ((size_t)u * G + g) * R + tid;
-    return a.f_phi32 ? (double)a.f_phi32[i] : a.f_phi[i];
-  };
-  double q_next = fetch_q(g_begin), f_next = fetch_f(g_begin);
-  const double inv_sqrt_d = 1.0 / sqrt_d;
-  for (int g = g_begin; g < g_end; ++g) {
-    __syncthreads();
-    if (tid < D) s_q[tid] = q_next;
-    if (tid < R) s_f[tid] = f_next;
-    if (g + 1 < g_end) {
-      q_next = fetch_q(g + 1);
-      f_next = fetch_f(g + 1);
-    }
-    __syncthreads();
-    double qreg[EPL];                                        // this lane's share of the query
-#pragma unroll
-    for (int i = 0; i < EPL; ++i) qreg[i] = s_q[lr * EPL + i];
-    // scores against the cached keys and the appended key: LPR lanes of 16 bytes per row; the
-    // rows of the first NP passes are requested together, further passes one at a time
-    double mx = -__builtin_inf();
-    auto row_ptr = [&](int r) -> const T * {
-      const int rc = r < rows ? r : rows - 1;
-      return (rc < m ? kc + (size_t)rc * D : kn) + lr * EPL;
-    };
-    auto score = [&](int r, const Vec &kv) {
-      double acc = 0.0;
-#pragma unroll
-      for (int i = 0; i < EPL; ++i) acc = fma(qreg[i], (double)Store<T>::get(kv, i), acc);
-      acc = row_sum<LPR>(acc);
-      const double s = acc * inv_sqrt_d;
-      if (lr == 0 && r < rows) s_e[r] = s;
-      if (r < rows) mx = fmax(mx, s);
-    };
-    constexpr int NP = 8;
-    Vec kvs[NP];
-#pragma unroll
-    for (int p = 0; p < NP; ++p) kvs[p] = load_vec<T>(row_ptr(p * RPB + rb));   // clamped: always in range
-#pragma unroll
-    for (int p = 0; p < NP; ++p)
-      if (p * RPB < rows) score(p * RPB + rb, kvs[p]);
-    for (int r0 = NP * RPB; r0 < rows; r0 += RPB) score(r0 + rb, load_vec<T>(row_ptr(r0 + rb)));
-    mx = block_allreduce(mx, s_red, tid, OpMax{});
-    // phi(q) z^T and the common shift m* = max(scores, ln(phi(q) z^T)) (Eq. 3 times e^{-m*})
-    double fz = 0.0;
-    for (int r = 0; r < R; ++r) fz = fma(s_f[r], s_z[r], fz);
-    const double lfz = fz > 0.0 ? log(fz) : -__builtin_inf();
-    const double mstar = fmax(mx, lfz);
-    const double wl = fz > 0.0 ? exp(lfz - mstar) : 0.0;
-    double part = 0.0;
-    for (int r = tid; r < rows; r += 256) {
-      const double e = exp(s_e[r] - mstar);
-      s_e[r] = e;
-      part += e;
-    }
-    const double den = wl + block_allreduce(part, s_red, tid, OpAdd{});   // the barriers inside publish s_e
-    // output column d: (phi(q) H e^{-m*} + sum_j e_j V_j) / den; the 256 / D thread groups
-    // take the rows in turn and meet in the LDS
-    {
-      constexpr int NG = 256 / D;
-      const int d = tid % D, grp = tid / D;
-      double num = 0.0;
-      if (grp == 0 && fz > 0.0) {
-        double fh = 0.0;
-        for (int r = 0; r < R; ++r) fh = fma(s_f[r], (double)Hu[(size_t)r * D + d], fh);
-        num = fh * exp(-mstar);
-      }
-#pragma unroll 8
-      for (int r = grp; r < m; r += NG) num = fma(s_e[r], (double)Store<T>::to_float(vc[(size_t)r * D + d]), num);
-      if (grp == m % NG) num = fma(s_e[m], (double)Store<T>::to_float(vn[d]), num);
-      s_num[tid] = num;
-      __syncthreads();
-      if (tid < D) {
-#pragma unroll
-        for (int k = 1; k < NG; ++k) num += s_num[k * D + tid];
-        reinterpret_cast<T *>(a.out)[((size_t)u * G + g) * D + tid] = Store<T>::from_float((float)(num / den));
-      }
-    }
-    // this head's probabilities (H2O accumulates those of every head)
-    const double dacc = (a.flags & LESSDEC_FLAG_SPARSE_DENOM) ? den - wl : den;
-    for (int r = tid; r < rows; r += 256) s_inc[r] += s_e[r] / dacc;
-  }
-  __syncthreads();
-
-  if (nhb > 1) {
-    // the unit's heads are spread over nhb blocks: leave this block's sums for the finishing launch
-    double *part = a.gqa_parts + ((size_t)u * nhb + hb) * rows_cap;
-    for (int r = tid; r < rows; r += 256) part[r] = s_inc[r];
-    return;
-  }
-  gqa_finish_unit<T, D>(a, u, tid, s_e, s_inc, s_cand);
-}
-
-// Staged form: the unit's key and value rows, H and z are copied into the LDS once and the heads
-// are taken four at a time (kGqaChunk = the block's four waves).  Per chunk: every thread scores
-// its share of a key row against the four queries; wave w then does the softmax of head w by
-// itself (maximum, Eq. 3's low-rank denominator term, exponentials, their sum) with lane
-// exchanges only, and the head's output the same way.  Four barriers per chunk.
-// Dynamic LDS: see gqa_staged_lds.
+// The heads of a unit (or of a block's share of them) are taken four at a time (kGqaChunk = the
+// block's four waves).  Per chunk: every thread scores its 16-byte share of a key row against
+// the four queries; wave w then does the softmax of head w by itself (maximum, Eq. 3's low-rank
+// denominator term, exponentials, their sum) with lane exchanges only, and the head's output the
+// same way.  Four barriers per chunk.
+// STAGE: the unit's key and value rows, H, the scores and positions are copied into the LDS
+// once and every chunk works from there (pays from the second chunk on).  Without it the rows
+// are read from memory where they are used, the first passes of a sweep requested together.
+// Dynamic LDS: see gqa_chunk_lds.
 constexpr int kGqaChunk = 4;
 
-template <typename T, int D>
-__global__ __launch_bounds__(256) void gqa_staged_kernel(const StepArgs a, int G, int nhb)
+template <typename T, int D, bool STAGE>
+__global__ __launch_bounds__(256) void gqa_chunk_kernel(const StepArgs a, int G, int nhb)
 {
   extern __shared__ double dyn[];
   constexpr int GC = kGqaChunk;
@@ -363,11 +218,11 @@ __global__ __launch_bounds__(256) void gqa_staged_kernel(const StepArgs a, int G
 
   for (int r = tid; r < rows; r += 256) s_inc[r] = 0.0;
   if (tid < R) s_z[tid] = a.z[(size_t)u * R + tid];
-  for (int r = tid; r < m; r += 256) {
-    s_acc[r] = a.acc[(size_t)u * C + r];
-    s_pos[r] = a.pos[(size_t)u * C + r];
-  }
-  {
+  if constexpr (STAGE) {
+    for (int r = tid; r < m; r += 256) {
+      s_acc[r] = a.acc[(size_t)u * C + r];
+      s_pos[r] = a.pos[(size_t)u * C + r];
+    }
     // all requests of a batch first, then the LDS stores (the staged sizes fit one batch)
     constexpr int VPR = D / EPL, NB = 8;                     // 16-byte vectors per row; vectors per thread and batch
     const int nvec = rows * VPR;
@@ -426,9 +281,12 @@ __global__ __launch_bounds__(256) void gqa_staged_kernel(const StepArgs a, int G
       for (int g = 0; g < GC; ++g)
 #pragma unroll
         for (int i = 0; i < EPL; ++i) qreg[g][i] = s_q[g * D + lr * EPL + i];
-      for (int r0 = 0; r0 < rows; r0 += RPB) {
-        const int r = r0 + rb, rc = r < rows ? r : rows - 1;
-        const Vec kv = *reinterpret_cast<const Vec *>(s_k + (size_t)rc * D + lr * EPL);
+      auto row_vec = [&](int r) -> Vec {                     // this lane's 16 bytes of key row r (clamped: in range)
+        const int rc = r < rows ? r : rows - 1;
+        if constexpr (STAGE) return *reinterpret_cast<const Vec *>(s_k + (size_t)rc * D + lr * EPL);
+        return load_vec<T>((rc < m ? kc + (size_t)rc * D : kn) + lr * EPL);
+      };
+      auto score = [&](int r, const Vec &kv) {
         double kd[EPL];
 #pragma unroll
         for (int i = 0; i < EPL; ++i) kd[i] = (double)Store<T>::get(kv, i);
@@ -440,6 +298,19 @@ __global__ __launch_bounds__(256) void gqa_staged_kernel(const StepArgs a, int G
           acc = row_sum<LPR>(acc);
           if (lr == 0 && r < rows) s_e[g * ecap + r] = acc * inv_sqrt_d;
         }
+      };
+      if constexpr (STAGE) {
+        for (int r0 = 0; r0 < rows; r0 += RPB) score(r0 + rb, row_vec(r0 + rb));
+      } else {
+        // from memory: the rows of the first NP passes are requested together
+        constexpr int NP = 8;
+        Vec kvs[NP];
+#pragma unroll
+        for (int p = 0; p < NP; ++p) kvs[p] = row_vec(p * RPB + rb);
+#pragma unroll
+        for (int p = 0; p < NP; ++p)
+          if (p * RPB < rows) score(p * RPB + rb, kvs[p]);
+        for (int r0 = NP * RPB; r0 < rows; r0 += RPB) score(r0 + rb, row_vec(r0 + rb));
       }
     }
     __syncthreads();
@@ -479,8 +350,9 @@ __global__ __launch_bounds__(256) void gqa_staged_kernel(const StepArgs a, int G
       const double hs = s_hd[w * 4 + 0];
       double num[4] = {0.0, 0.0, 0.0, 0.0};
       if (rs == 0 && hs > 0.0) {
+#pragma unroll 8
         for (int r = 0; r < R; ++r) {
-          const float4 h4 = *reinterpret_cast<const float4 *>(s_H + r * D + 4 * dq);
+          const float4 h4 = *reinterpret_cast<const float4 *>((STAGE ? s_H : Hu) + r * D + 4 * dq);
           const double f = s_f[w * 64 + r];
           num[0] = fma(f, (double)h4.x, num[0]);
           num[1] = fma(f, (double)h4.y, num[1]);
@@ -490,11 +362,12 @@ __global__ __launch_bounds__(256) void gqa_staged_kernel(const StepArgs a, int G
 #pragma unroll
         for (int i = 0; i < 4; ++i) num[i] *= hs;
       }
-#pragma unroll 4
+#pragma unroll 8
       for (int r = rs; r < rows; r += NRS) {
         const double e = e_w[r];
         float v4[4];
-        load_four<T>(s_v + (size_t)r * D + 4 * dq, v4);
+        if constexpr (STAGE) load_four<T>(s_v + (size_t)r * D + 4 * dq, v4);
+        else load_four<T>((r < m ? vc + (size_t)r * D : vn) + 4 * dq, v4);
 #pragma unroll
         for (int i = 0; i < 4; ++i) num[i] = fma(e, (double)v4[i], num[i]);
       }
@@ -527,16 +400,20 @@ __global__ __launch_bounds__(256) void gqa_staged_kernel(const StepArgs a, int G
     return;
   }
   LdsCopies<T> lds;
-  lds.k = s_k; lds.v = s_v; lds.H = s_H; lds.acc = s_acc; lds.pos = s_pos;
+  if constexpr (STAGE) {
+    lds.k = s_k; lds.v = s_v; lds.H = s_H; lds.acc = s_acc; lds.pos = s_pos;
+  }
   gqa_finish_unit<T, D>(a, u, tid, s_e, s_inc, s_cand, lds);
 }
 
-// Dynamic LDS of the staged form, in bytes.
+// Dynamic LDS of gqa_chunk_kernel, in bytes.
 template <typename T, int D>
-static size_t gqa_staged_lds(int C, int R)
+static size_t gqa_chunk_lds(int C, int R, bool stage)
 {
-  return (size_t)((kGqaChunk + 1) * ((C + 3) & ~1) + kGqaChunk * (D + 64) + 64 + kGqaChunk * 4 + (C + 1) / 2 * 2) * sizeof(double) +
-         (size_t)((C + 3) / 4 * 4) * sizeof(int) + (size_t)R * D * sizeof(float) + 2 * (size_t)(C + 1) * D * sizeof(T);
+  const size_t work = (size_t)((kGqaChunk + 1) * ((C + 3) & ~1) + kGqaChunk * (D + 64) + 64 + kGqaChunk * 4) * sizeof(double);
+  if (!stage) return work;
+  return work + (size_t)((C + 1) / 2 * 2) * sizeof(double) + (size_t)((C + 3) / 4 * 4) * sizeof(int) +
+         (size_t)R * D * sizeof(float) + 2 * (size_t)(C + 1) * D * sizeof(T);
 }
 
 // Finishing launch when a unit's heads were spread over several blocks: adds their sums in
@@ -595,14 +472,16 @@ template <typename T, int D>
 static hipError_t launch_step_gqa_t(const StepArgs &a, int G, hipStream_t st)
 {
   int nhb = gqa_head_blocks(a.U, G);
-  const size_t base = (size_t)(2 * (a.C + 2) + D + 64 + 64) * sizeof(double);
-  const size_t staged = gqa_staged_lds<T, D>(a.C, a.R);
-  const bool stage = staged <= kGqaStagedLds && staged <= block_lds_limit();
-  if (stage && nhb > (G + kGqaChunk - 1) / kGqaChunk) nhb = (G + kGqaChunk - 1) / kGqaChunk;   // whole chunks per block
+  const int nchunk = (G + kGqaChunk - 1) / kGqaChunk;
+  if (nhb > nchunk) nhb = nchunk;                           // whole chunks per block
+  // staging the rows pays when a block goes over them more than once
+  const size_t staged = gqa_chunk_lds<T, D>(a.C, a.R, true), plain = gqa_chunk_lds<T, D>(a.C, a.R, false);
+  const bool stage = (G + nhb - 1) / nhb > kGqaChunk && staged <= kGqaStagedLds && staged <= block_lds_limit();
+  if (!stage && plain > block_lds_limit()) return hipErrorInvalidValue;
   if (stage)
-    gqa_staged_kernel<T, D><<<a.U * nhb, 256, staged, st>>>(a, G, nhb);
+    gqa_chunk_kernel<T, D, true><<<a.U * nhb, 256, staged, st>>>(a, G, nhb);
   else
-    gqa_stream_kernel<T, D><<<a.U * nhb, 256, base, st>>>(a, G, nhb);
+    gqa_chunk_kernel<T, D, false><<<a.U * nhb, 256, plain, st>>>(a, G, nhb);
   if (nhb > 1) gqa_finish_kernel<T, D><<<a.U, 256, (size_t)2 * (a.C + 2) * sizeof(double), st>>>(a, nhb);
   return hipGetLastError();
 }
