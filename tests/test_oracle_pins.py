@@ -298,6 +298,43 @@ def test_stepwise_prompt_is_the_generation_loop(flags):
             np.testing.assert_allclose(r["out"][u], o, rtol=1e-9, atol=1e-12)
 
 
+@pytest.mark.parametrize("Nh,Nr,flags", [(3, 4, 6), (0, 5, 6), (4, 0, 6), (2, 6, 7)])
+def test_lambda_masking_through_the_prompt_is_a_masked_attention_matrix(Nh, Nr, flags):
+    """Under Lambda-masking the cache token t meets is known beforehand (tokens 0..Nh-1 and
+    t-Nr..t-1), so the token-by-token walk equals one masked matrix (Sec. 3.2 builds it for
+    training): e^{q_t k_j / sqrt(D)} where pair j is cached or is t itself, phi(q_t) psi(k_j)^T
+    where it was discarded; out = row V / row 1.  Accumulated scores are the column sums of the
+    cached entries over the normalisation of the flags' reading; slots follow in-place replacement."""
+    rng = np.random.default_rng(77 + Nh + Nr)
+    U, heads, D, Rp, R, P = 2, 2, 6, 9, 3, 23
+    W = make_weights(rng, heads, D, Rp, R)
+    st = lo.OracleState(U, heads, D, Nh, Nr, R, Rp, W, flags=flags)
+    Q, K, V = (rng.standard_normal((U, P, D)) for _ in range(3))
+    pre = st.prefill(Q, K, V)
+    t_idx, j_idx = np.arange(P)[:, None], np.arange(P)[None, :]
+    causal = j_idx <= t_idx
+    cached = causal & ((j_idx < Nh) | (j_idx >= t_idx - Nr))
+    for u in range(U):
+        w = head_w(W, u % heads)
+        F = np.stack([bf_phi(Q[u, t], w["Wq1"], w["Wq2"]) for t in range(P)])
+        G = np.stack([bf_psi(K[u, j], w["Wk1"], w["Wk2"], w["Wk3"]) for j in range(P)])
+        E = np.where(cached, np.exp(Q[u] @ K[u].T / np.sqrt(D)), 0.0)
+        Lr = np.where(causal & ~cached, F @ G.T, 0.0)
+        A = E + Lr
+        np.testing.assert_allclose(pre["out"][u], (A @ V[u]) / A.sum(1, keepdims=True), rtol=1e-9, atol=1e-12)
+        den = E.sum(1) if flags & 1 else A.sum(1)
+        col = (E / den[:, None]).sum(0)
+        for s_ in np.flatnonzero(st.pos[u] >= 0):
+            j = int(st.pos[u, s_])
+            assert st.acc[u, s_] == pytest.approx(col[j], rel=1e-10)
+            assert s_ == (j if j < Nh else Nh + (j - Nh) % Nr)
+        kept = sorted(st.pos[u][st.pos[u] >= 0])
+        assert kept == list(range(Nh)) + list(range(P - Nr, P))
+        gone = [j for j in range(Nh, P - Nr)]
+        np.testing.assert_allclose(st.H[u], G[gone].T @ V[u][gone], rtol=1e-10, atol=1e-13)
+        np.testing.assert_allclose(st.z[u], G[gone].sum(0), rtol=1e-10, atol=1e-13)
+
+
 # ---------------------------------------------------------------- several query heads per KV head
 def make_weights_gqa(rng, heads, G, D, Rp, R):
     W = make_weights(rng, heads, D, Rp, R)
