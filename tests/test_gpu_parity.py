@@ -209,6 +209,32 @@ def test_lambda_masking_through_the_prompt_all_rows_at_once(w, flags):
     assert rep.exempt == 0
 
 
+def _random_masked_shapes(count, seed):
+    """Seeded draws over the splits, prompt lengths, ranks and storage types of the masked form."""
+    rng = np.random.default_rng(seed)
+    out = []
+    for i in range(count):
+        nh, nr = int(rng.integers(0, 21)), int(rng.integers(0, 41))
+        if nh + nr == 0:
+            nr = 3
+        f16 = bool(rng.integers(0, 2))
+        d = int(rng.choice([64, 128]))
+        rank = int(rng.choice([1, 3, 4, 8, 12, 16, 20])) if f16 else int(rng.choice([2, 4, 7]))
+        prompt = nh + nr + int(rng.integers(1, 330))
+        out.append((small(f"masked-random-{i}-nh{nh}-nr{nr}-p{prompt}-r{rank}-d{d}-{'f16' if f16 else 'f32'}",
+                          n_heavy=nh, n_recent=nr, prompt=prompt, steps=4, rank=rank, head_dim=d,
+                          dtype="f16" if f16 else "f32", batch=1, heads=2,
+                          q_per_kv=int(rng.choice([1, 1, 2]))), 6 | int(rng.integers(0, 2))))
+    return out
+
+
+@pytest.mark.parametrize("w,flags", _random_masked_shapes(10, seed=2024), ids=lambda x: x.name if hasattr(x, "name") else str(x))
+def test_masked_prompt_random_shapes(w, flags):
+    rep = hz.run_workload(w, range(w.units), flags=flags)
+    report_ok(rep, min_decisions=w.units * w.steps if w.capacity else 0)
+    assert rep.exempt == 0
+
+
 def test_masked_prompt_at_the_benchmark_shape():
     """Config 3's shape, 4 first tokens + 98 recent, the policy active through the 1024-token
     prompt: every unit on the GPU, a sample of units through the oracle's token-by-token walk."""
