@@ -137,3 +137,9 @@ def test_workload_generator_shapes_and_determinism():
     assert np.array_equal(gw["Wq1"][3], allw["Wq1"][1]) and np.array_equal(gw["Wk2"], allw["Wk2"])
     fullg = wl.all_inputs(wg, units=[0, 2])
     assert fullg["Q"].shape == (2, 3, 40, 128) and fullg["q"].shape == (5, 2, 3, 128)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess, sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0 and "one GPU" in r.stderr
