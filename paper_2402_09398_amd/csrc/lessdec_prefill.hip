@@ -135,7 +135,10 @@ __device__ inline void tile_pv(const VTile<D> &vt, const double (&e)[4], v4f (&O
   v4h ph, pl;
 #pragma unroll
   for (int v = 0; v < 4; ++v) {
-    const float ef = (float)e[v];
+    float ef = (float)e[v];
+    // keep the fp32 value: folded into one fp64 -> fp16 conversion this becomes a long software
+    // sequence (there is no such instruction)
+    asm volatile("" : "+v"(ef));
     const _Float16 hi = (_Float16)ef;
     ph[v] = hi;
     pl[v] = (_Float16)(ef - (float)hi);
