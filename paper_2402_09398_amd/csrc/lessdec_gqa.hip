@@ -379,7 +379,10 @@ __global__ __launch_bounds__(256) void gqa_chunk_kernel(const StepArgs a, int G,
         const double inv_den = s_hd[w * 4 + 1];
         float o4[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) o4[i] = (float)(num[i] * inv_den);
+        for (int i = 0; i < 4; ++i) {
+          o4[i] = (float)(num[i] * inv_den);
+          asm volatile("" : "+v"(o4[i]));                  // fp64 -> fp16 in one step would be a software sequence
+        }
         store_four<T>(reinterpret_cast<T *>(a.out) + ((size_t)u * G + g0 + w) * D + 4 * dq, o4);
       }
     }

@@ -354,7 +354,9 @@ __global__ __launch_bounds__(256, step_waves_per_simd(NIT)) void step_kernel(con
       for (int r = 0; r < R; ++r) fh = fmaf(s_f[r], Hu[(size_t)r * D + col], fh);
     }
     const double o = (double)pv + s_lscale * (double)fh;
-    reinterpret_cast<T *>(a.out)[(size_t)u * D + col] = Store<T>::from_float((float)o);
+    float of = (float)o;
+    asm volatile("" : "+v"(of));                             // fp64 -> fp16 in one step would be a software sequence
+    reinterpret_cast<T *>(a.out)[(size_t)u * D + col] = Store<T>::from_float(of);
     if (evict)
       reinterpret_cast<T *>(a.pend_v)[(size_t)u * D + col] = reinterpret_cast<const T *>(s_ve)[col];
     if (ins_slot >= 0) {
