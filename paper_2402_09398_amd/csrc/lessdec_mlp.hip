@@ -101,12 +101,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   const int h = (int)blockIdx.x % Hh, part = (int)blockIdx.x / Hh;
   const __half *W1 = a.W1 + (size_t)h * Rp * D;
   const __half *W2 = a.W2 + (size_t)h * R * Rp;
-  const long rows_head = (long)a.B * a.rpu;
-  const long nchunk = (rows_head + 16 * kRowTiles - 1) / (16 * kRowTiles);
-  const long ch0 = nchunk * part / parts, ch1 = nchunk * (part + 1) / parts;
-  auto global_row = [&](long i) -> long {
-    const long bb = i / a.rpu, p = i % a.rpu;
-    return (bb * Hh + h) * (long)a.rpu + p;
+  // 32-bit row arithmetic (the launcher checks that a head's rows fit): a 64-bit division per row
+  // would be a long instruction sequence
+  const unsigned rows_head = (unsigned)a.B * (unsigned)a.rpu, rpu = (unsigned)a.rpu;
+  const unsigned nchunk = (rows_head + 16 * kRowTiles - 1) / (16 * kRowTiles);
+  const unsigned ch0 = (unsigned)((unsigned long)nchunk * part / parts);
+  const unsigned ch1 = (unsigned)((unsigned long)nchunk * (part + 1) / parts);
+  auto global_row = [&](unsigned i) -> size_t {
+    const unsigned bb = i / rpu, p = i - bb * rpu;
+    return ((size_t)bb * Hh + h) * rpu + p;
   };
   MlpTiles<D> w[NGW];
 #pragma unroll
@@ -118,16 +121,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     s_w3[r][j] = (a.W3 != nullptr && r < R && j < R) ? (double)__half2float(a.W3[((size_t)h * R + r) * R + j]) : 0.0;
   }
 
-  auto load_chunk = [&](long ch, v8h (&bx)[kRowTiles][D / 32]) {
+  auto load_chunk = [&](unsigned ch, v8h (&bx)[kRowTiles][D / 32]) {
 #pragma unroll
     for (int t = 0; t < kRowTiles; ++t) {
-      const long i = (ch * kRowTiles + t) * 16 + c;
+      const unsigned i = (ch * kRowTiles + t) * 16 + c;
       mlp_load_row<D>(a.x + (i < rows_head ? global_row(i) : 0) * D, g, bx[t]);   // padding: any row
     }
   };
   v8h bx_next[kRowTiles][D / 32];
   if (ch0 < ch1) load_chunk(ch0, bx_next);
-  for (long ch = ch0; ch < ch1; ++ch) {
+  for (unsigned ch = ch0; ch < ch1; ++ch) {
     v8h bx[kRowTiles][D / 32];
 #pragma unroll
     for (int t = 0; t < kRowTiles; ++t)
@@ -153,7 +156,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     }
     __syncthreads();
     for (int row = tid / 16; row < 16 * kRowTiles; row += 16) {
-      const long i = ch * (16 * kRowTiles) + row;
+      const unsigned i = ch * (16 * kRowTiles) + row;
       if (r < R && i < rows_head) {
         double acc3 = 0.0;
         if (a.W3 != nullptr) {
@@ -221,7 +224,7 @@ hipError_t launch_mlp(const MlpArgs &a, hipStream_t st)
   // many rows per head and R' = 128, 256, 384 or 512: weights stay in registers, rows stream through
   const int ngw = a.Rp % 128 == 0 ? a.Rp / 128 : 0;
   const long nchunk = (rows_head + 16 * kRowTiles - 1) / (16 * kRowTiles);
-  if (ngw >= 1 && ngw <= 4 && nchunk >= 64) {
+  if (ngw >= 1 && ngw <= 4 && nchunk >= 64 && rows_head < (1L << 31) - 64) {
     long parts = 1024 / a.Hh;                              // about four workgroups per compute unit
     if (parts < 1) parts = 1;
     if (parts > nchunk / 8) parts = nchunk / 8;            // at least 8 chunks behind every weight load
