@@ -359,15 +359,23 @@ def test_checkpoint_restore_continues_bit_identically():
 
 def _kind_workload(name, kind, steps):
     """The decode path a small workload takes: one wave per unit, a unit's rows split over
-    several waves (enough slots for that), or the any-shape kernels (rank above 16)."""
+    several waves (enough slots for that), several query heads per unit, or the any-shape kernels
+    (rank above 16)."""
     if kind == "streaming":
         return small(name, steps=steps)
     if kind == "split":
         return small(name + "-split", steps=steps, n_heavy=35, n_recent=35, prompt=90)
+    if kind == "multi-head":                 # four query heads per unit: one block per unit
+        return small(name + "-multi-head", steps=steps, q_per_kv=4)
+    if kind == "multi-head-spread":          # eight: a unit's heads over two blocks and a finishing launch
+        return small(name + "-multi-head-spread", steps=steps, q_per_kv=8)
     return small(name + "-general", steps=steps, rank=20)
 
 
-@pytest.mark.parametrize("kind", ["streaming", "split", "general"])
+KINDS = ["streaming", "split", "general", "multi-head", "multi-head-spread"]
+
+
+@pytest.mark.parametrize("kind", KINDS)
 def test_step_equals_its_two_halves(kind):
     """lessdec_step is lessdec_step_features followed by lessdec_step_attend."""
     import torch
@@ -397,7 +405,7 @@ def test_step_equals_its_two_halves(kind):
         assert torch.equal(got[0][2][n], got[1][2][n]), n
 
 
-@pytest.mark.parametrize("kind", ["streaming", "split", "general"])
+@pytest.mark.parametrize("kind", KINDS)
 def test_steps_replayed_from_a_hip_graph_match_eager_steps(kind):
     """The step reads and advances its counters on the device and clears nothing with a memset,
     so one captured step can be replayed for a whole sequence.  Every replay is checked against
