@@ -209,6 +209,13 @@ def test_lambda_masking_through_the_prompt_all_rows_at_once(w, flags):
     assert rep.exempt == 0
 
 
+def test_masked_prompt_without_attention_outputs():
+    """lessdec_prefill with out = NULL: the state must come out the same."""
+    w = small("masked-prompt-no-outputs", n_heavy=4, n_recent=20, prompt=150, steps=10)
+    rep = hz.run_workload(w, range(w.units), flags=6, want_prefill_out=False)
+    report_ok(rep, min_decisions=w.units * w.steps)
+
+
 def _random_masked_shapes(count, seed):
     """Seeded draws over the splits, prompt lengths, ranks and storage types of the masked form."""
     rng = np.random.default_rng(seed)
