@@ -198,6 +198,7 @@ MASKED = [
     (small("masked-prompt-rank-6-f32", n_heavy=3, n_recent=9, prompt=70, steps=10, rank=6, dtype="f32"), 6),
     (small("masked-prompt-2-heads", n_heavy=4, n_recent=20, prompt=140, steps=10, q_per_kv=2), 6),
     (small("masked-prompt-one-past-budget", n_heavy=4, n_recent=12, prompt=17, steps=10), 6),
+    (small("masked-prompt-inside-budget", n_heavy=4, n_recent=12, prompt=11, steps=20), 6),   # the loop of steps
     (small("masked-prompt-long", n_heavy=4, n_recent=60, prompt=600, steps=5, batch=1, heads=2), 6),
 ]
 
@@ -205,7 +206,7 @@ MASKED = [
 @pytest.mark.parametrize("w,flags", MASKED, ids=lambda x: x.name if hasattr(x, "name") else str(x))
 def test_lambda_masking_through_the_prompt_all_rows_at_once(w, flags):
     rep = hz.run_workload(w, range(w.units), flags=flags)
-    report_ok(rep, min_decisions=w.units * w.steps)
+    report_ok(rep, min_decisions=w.units * max(0, min(w.steps, w.prompt + w.steps - w.capacity)))
     assert rep.exempt == 0
 
 
