@@ -365,6 +365,16 @@ def test_checkpoint_restore_continues_bit_identically():
         assert torch.equal(a[2][n], b[2][n]), n
 
 
+def test_query_groups_at_the_benchmark_shape():
+    """Config 3's shape regrouped as `bench.py --q-per-kv 4` runs it (512 units of 4 query heads,
+    1024-token prompt): every unit on the GPU, a sample of units through the oracle."""
+    w3 = wl.WORKLOADS[3]
+    w = w3.scaled(name="cfg3-gqa4", heads=w3.heads // 4, q_per_kv=4, steps=32)
+    units = sample_units(w, 4, seed=35)
+    rep = hz.run_workload(w, units)
+    report_ok(rep, min_decisions=len(units) * w.steps)
+
+
 def _kind_workload(name, kind, steps):
     """The decode path a small workload takes: one wave per unit, a unit's rows split over
     several waves (enough slots for that), several query heads per unit, or the any-shape kernels
