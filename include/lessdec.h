@@ -19,6 +19,11 @@
  *    crosses this boundary.
  *  - The per-unit counter n_seen is read and advanced on the device and no call clears
  *    memory with a memset, so a sequence of steps can be recorded into a HIP graph.
+ *  - State buffers that were never reset (Algorithm 1's "load" step on arbitrary memory): the
+ *    result of a step is then meaningless, but every access stays inside the unit's own arrays.
+ *    The kernels read n_seen < 0 as 0, never use more than C slots whatever n_seen says, and
+ *    decode any pend_slot word to "nothing pending" or a slot in [0, C]; positions and scores
+ *    are only compared, never used as addresses.
  *
  * Arithmetic: everything that decides an eviction (scores, exponentials, the
  * denominator, accumulated probabilities, z, prompt column sums) is computed in fp64;

@@ -168,11 +168,13 @@ class OracleState:
     def reset(self):
         lib().less_oracle_reset(C.byref(self._struct()))
 
-    def step(self, q, k, v, force=None):
+    def step(self, q, k, v, force=None, strict=True):
         """One generation step for all units. q,k,v [U,D].
 
         Returns dict(out [U,D], evicted [U], dec [U,4], share [U]).
-        force: None or int array [U]; entries >= 0 override the policy's choice.
+        force: None or int array [U]; entries >= 0 override the policy's choice.  A forced
+        position that is not an eviction candidate is an error (strict) or leaves that unit
+        on the policy's own choice, which `evicted` then shows (not strict).
         """
         q = _f64(q); k = _f64(k); v = _f64(v)
         qshape = (self.U, self.D) if self.G == 1 else (self.U, self.G, self.D)
@@ -182,7 +184,7 @@ class OracleState:
         fo = None if force is None else np.ascontiguousarray(force, dtype=np.int64)
         bad = lib().less_oracle_step(C.byref(self._struct()), _ptr(q), _ptr(k), _ptr(v),
                                      _ptr(fo), _ptr(out), _ptr(ev), _ptr(dec), _ptr(share))
-        if bad:
+        if bad and strict:
             raise ValueError(f"{bad} unit(s): forced position is not an eviction candidate")
         return {"out": out, "evicted": ev, "dec": dec, "share": share}
 

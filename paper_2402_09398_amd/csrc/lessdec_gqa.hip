@@ -66,7 +66,7 @@ __device__ inline void gqa_finish_unit(const StepArgs &a, int u, int tid, double
                                        Cand *s_cand, const LdsCopies<T> lds = LdsCopies<T>())
 {
   const int C = a.C, R = a.R;
-  const int n = a.n_seen[u];
+  const int n = sane_n_seen(a.n_seen[u]);
   const int m = n < C ? n : C;
   const int rows = m + 1;
   const bool full = (m == C);
@@ -190,7 +190,7 @@ __global__ __launch_bounds__(256) void gqa_chunk_kernel(const StepArgs a, int G,
   Cand *s_cand = reinterpret_cast<Cand *>(s_q);                 // after the last chunk (256 entries fit in s_q, s_f)
   static_assert(sizeof(Cand) * 256 <= (GC * D + GC * 64) * sizeof(double), "candidates overlay the query area");
 
-  const int n = a.n_seen[u];
+  const int n = sane_n_seen(a.n_seen[u]);
   const int m = n < C ? n : C;             // live slots are 0..m-1 (slots fill in order)
   const int rows = m + 1;                  // + the appended pair (K', V' of Eq. 3)
   const T *kc = reinterpret_cast<const T *>(a.k_cache) + (size_t)u * C * D;
@@ -429,7 +429,7 @@ __global__ __launch_bounds__(256) void gqa_finish_kernel(const StepArgs a, int n
   const int u = (int)blockIdx.x, tid = threadIdx.x;
   const int rows_cap = a.C + 2;
   double *s_e = dyn, *s_inc = dyn + rows_cap;
-  const int n = a.n_seen[u];
+  const int n = sane_n_seen(a.n_seen[u]);
   const int rows = (n < a.C ? n : a.C) + 1;
   for (int r = tid; r < rows; r += 256) {
     double p[kGqaMaxHeadBlocks];

@@ -79,8 +79,8 @@ __global__ __launch_bounds__(256, step_waves_per_simd(NIT)) void step_kernel(con
   const T *vn = reinterpret_cast<const T *>(a.v) + (size_t)u * D;
 
   // ---- requests, small ones first -----------------------------------------------------------
-  const int n = a.n_seen[u];
-  const Pending pend = decode_pending(a.pend_slot[u]);
+  const int n = sane_n_seen(a.n_seen[u]);
+  const Pending pend = decode_pending(a.pend_slot[u], C);
   const Vec qv = load_vec<T>(qn + lr * EPL);
   const Vec knv = load_vec<T>(kn + lr * EPL);
   const Vec vnv = load_vec<T>(vn + lr * EPL);
@@ -372,7 +372,7 @@ __global__ __launch_bounds__(256) void state_sync_kernel(const StepArgs a, int D
 {
   const int u = blockIdx.x, tid = threadIdx.x, C = a.C, R = a.R;
   __shared__ float s_psie[LESSDEC_MAX_RANK];
-  const Pending pend = decode_pending(a.pend_slot[u]);
+  const Pending pend = decode_pending(a.pend_slot[u], C);
   if (pend.slot < 0) return;                             // uniform per block
   const float *ppsi = a.pend_psi + (size_t)u * R;
   if (pend.fold) {

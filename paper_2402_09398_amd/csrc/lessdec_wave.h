@@ -103,12 +103,19 @@ struct Pending {
   int slot;
   bool fold;
 };
-__device__ inline Pending decode_pending(int ps)
+// A word that no step wrote (buffers never reset) still decodes to a slot in [-1, C]: every use
+// of the slot is then an access inside the unit's own arrays.
+__device__ inline Pending decode_pending(int ps, int C)
 {
   Pending p;
-  p.slot = ps < 0 ? -1 : (ps & 0xffff);
+  const int s = ps & 0xffff;
+  p.slot = ps < 0 ? -1 : (s < C ? s : C);
   p.fold = ps >= 0 && !(ps & kPendNoFold);
   return p;
 }
+// Tokens seen by a unit, as loaded: a step on buffers that were never reset must stay inside the
+// unit's arrays whatever the word holds, so a negative count reads as an empty cache (and a huge
+// one stays clear of overflow when it is advanced and compared with positions).
+__device__ inline int sane_n_seen(int n) { return n < 0 ? 0 : (n > (1 << 30) ? (1 << 30) : n); }
 
 }  // namespace lessdec

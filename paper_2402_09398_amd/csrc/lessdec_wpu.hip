@@ -116,8 +116,8 @@ __global__ __launch_bounds__(kWpuUnits * kWave) void wpu_step_kernel(void *k_cac
   for (int j = 0; j < RM; ++j)
     w3[j] = reinterpret_cast<const __half *>(a.Wk3)[((size_t)h * R + rl) * R + (j < R ? j : R - 1)];
   // 3. unit state (wanted from phase 2 on)
-  const int n = a.n_seen[u];
-  const Pending pend = decode_pending(a.pend_slot[u]);
+  const int n = sane_n_seen(a.n_seen[u]);
+  const Pending pend = decode_pending(a.pend_slot[u], C);
   const int m = n < C ? n : C;          // live slots are 0..m-1 (slots fill in order)
   const int rows = m + 1;               // + the appended pair (K', V' of Eq. 3)
   const bool full = (m == C);

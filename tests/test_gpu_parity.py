@@ -28,8 +28,24 @@ def small(name, **kw):
 
 
 def sample_units(w, count, seed=0):
+    """`count` units for the oracle: always unit 0 and the last unit, the first and last unit of the
+    first and of the last block of eight batch rows that the streaming kernel forms per head, and
+    the same number of batch rows of every head (drawn from the seed) for the rest."""
+    U, Hh, B = w.units, w.heads, w.batch
+    if count >= U:
+        return list(range(U))
+    forced = {0, U - 1, min(7, B - 1) * Hh, max(B - 8, 0) * Hh + Hh - 1}
     rng = np.random.default_rng(seed)
-    return sorted(int(u) for u in rng.choice(w.units, size=min(count, w.units), replace=False))
+    per_head = max(1, count // Hh)
+    chosen = set(forced)
+    if count >= Hh:
+        for h in range(Hh):
+            for b in rng.choice(B, size=min(per_head, B), replace=False):
+                chosen.add(int(b) * Hh + h)
+    rest = [u for u in rng.permutation(U) if int(u) not in chosen]
+    for u in rest[:max(0, count - len(chosen))]:
+        chosen.add(int(u))
+    return sorted(chosen)
 
 
 def report_ok(rep, min_decisions=0):
@@ -470,10 +486,110 @@ def test_steps_replayed_from_a_hip_graph_match_eager_steps(kind):
 
 
 # ------------------------------------------------------------------ the five configurations
-@pytest.mark.parametrize("cfg,count", [(1, 2), (2, 24), (3, 16), (4, 10), (5, 6)])
+# Every unit runs on the GPU in the launch shape bench.py times and is checked for the invariants
+# of harness.check_every_unit; the units below also go through the oracle element by element:
+# all of cfg 1, 2 and 5, a quarter of cfg 3 (16 batch rows of every head) and an eighth of cfg 4
+# (4 batch rows of every one of its 40 heads), always with the first and last unit and the first
+# and last wave of a block.
+@pytest.mark.parametrize("cfg,count", [(1, 2), (2, 256), (3, 512), (4, 160), (5, 128)])
 def test_configuration_full_size(cfg, count):
     w = wl.WORKLOADS[cfg]
     units = sample_units(w, count, seed=cfg)
+    assert 0 in units and w.units - 1 in units and len(units) >= min(count, w.units)
+    assert {u % w.heads for u in units} == set(range(w.heads))
     rep = hz.run_workload(w, units, want_prefill_out=True)
     report_ok(rep, min_decisions=len(units) * w.steps - rep.prefill_exempt_units * w.steps)
     assert 0.0 < rep.mean_share < 1.0          # both the sparse and the low-rank term matter
+
+
+# ------------------------------------------------------------------ ties (Sec. 2.1: H2O keeps the
+# pairs with the largest accumulated scores; equal scores discard the older pair, equal column
+# sums at the prompt keep the later token)
+TIE_KINDS = ["streaming", "split", "general", "multi-head"]
+
+
+def _tie_workload(kind):
+    if kind == "streaming":      # one wave per unit; 70 slots: the tied pair sits in different lanes' second rows
+        return small("tie-streaming", n_heavy=40, n_recent=30, prompt=100, steps=6, batch=64, heads=32)
+    if kind == "split":
+        return small("tie-split", n_heavy=40, n_recent=30, prompt=100, steps=6)
+    if kind == "multi-head":
+        return small("tie-multi-head", n_heavy=40, n_recent=30, prompt=100, steps=6, q_per_kv=4)
+    return small("tie-general", n_heavy=40, n_recent=30, prompt=100, steps=6, dtype="f32")
+
+
+def _state_with_tie(w, inp, units, near=0.0):
+    st = hz.make_oracle(w, units)
+    st.prefill(inp["Q"], inp["K"], inp["V"], want_out=False)
+    a, b = hz.plant_score_tie(st, slot_new=3, slot_old=37)
+    if near:
+        st.acc[:, a] *= 1.0 + near
+    return st, a, b
+
+
+@pytest.mark.parametrize("kind", TIE_KINDS)
+def test_equal_accumulated_scores_discard_the_older_pair(kind):
+    """Two cached pairs with the same key and bit-equal accumulated scores, the smallest of the
+    unit, the older token in the higher slot: the step must discard the older one."""
+    w = _tie_workload(kind)
+    units = list(range(w.units))
+    inp = wl.all_inputs(w, workers=16)
+    st, a, b = _state_with_tie(w, inp, units)
+    older = st.pos[:, b].copy()
+    gpu = hz.make_gpu(w)
+    hz.upload_oracle_state(gpu, st)
+    res = hz.gpu_run(w, inp, with_prefill=False, gpu=gpu)
+    assert np.array_equal(res["evicted"][0], older)
+    rep = hz.check_against_oracle(w, inp, units, res, oracle_state=st)
+    report_ok(rep, min_decisions=w.units * w.steps)
+    assert rep.min_gap == 0.0 and rep.exempt == 0
+    assert hz.check_every_unit(w, res) == []
+
+
+@pytest.mark.parametrize("kind", TIE_KINDS)
+def test_scores_inside_the_exemption_gap(kind):
+    """The same pair with scores 1e-7 apart (relative).  The GPU starts from a state whose score of
+    the smaller one is 1.5e-7 higher, as rounding within the tolerance could leave it, so it
+    discards the oracle's runner-up: the protocol must call that exempt, follow the GPU's choice
+    and find everything else in agreement."""
+    import torch
+    w = _tie_workload(kind)
+    units = list(range(w.units))
+    inp = wl.all_inputs(w, workers=16)
+    st, a, b = _state_with_tie(w, inp, units, near=1e-7)       # oracle: slot b smallest, slot a 1e-7 above
+    gpu = hz.make_gpu(w)
+    hz.upload_oracle_state(gpu, st)
+    gpu.acc[:, b] *= 1.0 + 1.5e-7
+    torch.cuda.synchronize()
+    res = hz.gpu_run(w, inp, with_prefill=False, gpu=gpu)
+    assert np.array_equal(res["evicted"][0], st.pos[:, a])      # the GPU's smallest is the oracle's runner-up
+    res["after_prefill"]["acc"][:, b] = st.acc[:, b]           # (compared before the first step: the oracle's value)
+    rep = hz.check_against_oracle(w, inp, units, res, oracle_state=st)
+    report_ok(rep, min_decisions=w.units * w.steps)
+    assert rep.exempt == w.units and rep.min_gap < hz.TIE_GAP
+
+
+@pytest.mark.parametrize("name,kw,supers", [
+    ("prompt-tie-f16", dict(n_heavy=1), ()),
+    ("prompt-tie-f16-third-place", dict(n_heavy=3), (5, 9)),
+    ("prompt-tie-f32", dict(n_heavy=1, dtype="f32"), ()),
+    ("prompt-tie-f32-third-place", dict(n_heavy=3, dtype="f32", rank=4), (5, 9)),
+    ("prompt-tie-f16-d64", dict(n_heavy=1, head_dim=64), ()),
+    ("prompt-tie-f16-2-heads", dict(n_heavy=1, q_per_kv=2), ()),
+])
+def test_equal_prompt_column_sums_keep_the_later_token(name, kw, supers):
+    """Two adjacent prompt tokens with the same key whose column sums are bit-equal and sit exactly
+    at the boundary of the heavy set: the later one is kept."""
+    w = small(name, prompt=80, steps=8, n_recent=6, **kw)
+    inp = wl.all_inputs(w)
+    j1, j2 = hz.plant_prompt_tie(w, inp, 19, supers)
+    units = list(range(w.units))
+    probe = hz.make_oracle(w, units)
+    pre = probe.prefill(inp["Q"], inp["K"], inp["V"], want_out=False)
+    assert (pre["dec"][:, 0] == pre["dec"][:, 2]).all() and pre["kept"][:, j2].all() and not pre["kept"][:, j1].any()
+    res = hz.gpu_run(w, inp)
+    kept = res["after_prefill"]["pos"]
+    assert (kept == j2).any(axis=1).all() and not (kept == j1).any()
+    rep = hz.check_against_oracle(w, inp, units, res)
+    report_ok(rep, min_decisions=w.units * w.steps)
+    assert rep.prefill_exempt_units == 0
