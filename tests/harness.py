@@ -20,11 +20,14 @@ from paper_2402_09398_amd import workloads as wl
 
 OUT_TOL = 2e-3        # attention outputs, relative to the row's largest magnitude
 STATE_TOL = 1e-4      # H and z, same norm
-SCORE_TOL = 2e-7      # accumulated scores, relative: fp64 sums on both sides; what differs is
+SCORE_TOL = 5e-7      # accumulated scores, relative: fp64 sums on both sides; what differs is
                       # phi(q) z^T in the denominator, which the GPU builds from fp32 feature maps
-                      # (some tens of roundings of 6e-8, mostly cancelling), weighted by the low-rank
-                      # share of the denominator (up to 0.8 on these workloads).  A fifth of the
-                      # eviction exemption gap; the largest error seen on any workload is 1.3e-7
+                      # (fp32 GELU good to 2.5e-7 absolute on each of R' hidden activations, fp32
+                      # accumulation: a few 1e-7 relative on a feature), weighted by the low-rank
+                      # share of the denominator.  Half the eviction exemption gap.  The run that
+                      # needs more than 2e-7: workload "one-slot-recent" (one slot, so a score is a
+                      # single probability and nothing averages out), unit 3, 2.36e-7 at a low-rank
+                      # share of 0.68; the five benchmark workloads stay below 1.3e-7
 TIE_GAP = 1e-6        # exemption for the eviction choice
 
 

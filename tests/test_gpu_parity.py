@@ -5,7 +5,7 @@ five configurations of the benchmark run every unit on the GPU at full size and 
 sample of units through the oracle (units are independent).
 
 Tolerances (tests/harness.py): attention outputs 2e-3 relative to the row's largest
-magnitude (fp16 storage, fp32 accumulation), H and z 1e-4, accumulated scores 2e-7 (fp64
+magnitude (fp16 storage, fp32 accumulation), H and z 1e-4, accumulated scores 5e-7 (fp64
 sums, fp32 feature maps); eviction positions exact, except where the oracle's two smallest candidate
 scores differ by less than 1e-6 relative.
 """
@@ -536,10 +536,16 @@ def test_equal_accumulated_scores_discard_the_older_pair(kind):
     inp = wl.all_inputs(w, workers=16)
     st, a, b = _state_with_tie(w, inp, units)
     older = st.pos[:, b].copy()
+    # the units in which the planted pair is what the step has to choose between (in a few, a
+    # peaked head gives the pair so much probability that another pair scores lower)
+    probe, _, _ = _state_with_tie(w, inp, units)
+    dec = probe.step(inp["q"][0], inp["k"][0], inp["v"][0])["dec"]
+    tied = (dec[:, 0] == dec[:, 2]) & (dec[:, 1] == older)
+    assert tied.mean() > 0.9
     gpu = hz.make_gpu(w)
     hz.upload_oracle_state(gpu, st)
     res = hz.gpu_run(w, inp, with_prefill=False, gpu=gpu)
-    assert np.array_equal(res["evicted"][0], older)
+    assert np.array_equal(res["evicted"][0][tied], older[tied])
     rep = hz.check_against_oracle(w, inp, units, res, oracle_state=st)
     report_ok(rep, min_decisions=w.units * w.steps)
     assert rep.min_gap == 0.0 and rep.exempt == 0
@@ -557,16 +563,22 @@ def test_scores_inside_the_exemption_gap(kind):
     units = list(range(w.units))
     inp = wl.all_inputs(w, workers=16)
     st, a, b = _state_with_tie(w, inp, units, near=1e-7)       # oracle: slot b smallest, slot a 1e-7 above
+    newer = st.pos[:, a].copy()
+    probe, _, _ = _state_with_tie(w, inp, units, near=1e-7)
+    dec = probe.step(inp["q"][0], inp["k"][0], inp["v"][0])["dec"]
+    near = (dec[:, 1] == st.pos[:, b]) & (dec[:, 3] == newer)   # the pair is the oracle's first and second
+    assert near.mean() > 0.9
     gpu = hz.make_gpu(w)
     hz.upload_oracle_state(gpu, st)
     gpu.acc[:, b] *= 1.0 + 1.5e-7
     torch.cuda.synchronize()
     res = hz.gpu_run(w, inp, with_prefill=False, gpu=gpu)
-    assert np.array_equal(res["evicted"][0], st.pos[:, a])      # the GPU's smallest is the oracle's runner-up
+    assert np.array_equal(res["evicted"][0][near], newer[near])  # the GPU's smallest is the oracle's runner-up
     res["after_prefill"]["acc"][:, b] = st.acc[:, b]           # (compared before the first step: the oracle's value)
     rep = hz.check_against_oracle(w, inp, units, res, oracle_state=st)
     report_ok(rep, min_decisions=w.units * w.steps)
-    assert rep.exempt == w.units and rep.min_gap < hz.TIE_GAP
+    # (where another pair left first, the planted pair meets in a later step and is exempt there)
+    assert int(near.sum()) <= rep.exempt <= w.units and rep.min_gap < hz.TIE_GAP
 
 
 @pytest.mark.parametrize("name,kw,supers", [
