@@ -62,11 +62,14 @@ extern "C" {
 #define LESSDEC_EINVAL (-1)    /* bad shape, NULL or misaligned pointer, unsupported size */
 #define LESSDEC_EWORKSPACE (-2)/* workspace missing or too small                          */
 #define LESSDEC_EHIP (-3)      /* a HIP launch or query failed                            */
+#define LESSDEC_ESCRATCH (-4)  /* lessdec_step_static: the shape needs more scratch than the
+                                  library's built-in LESSDEC_STATIC_SCRATCH_BYTES            */
 
 #define LESSDEC_MAX_RANK 64
 #define LESSDEC_MAX_CAPACITY 4094
 #define LESSDEC_MAX_HIDDEN 2048
 #define LESSDEC_MAX_Q_PER_KV 128
+#define LESSDEC_STATIC_SCRATCH_BYTES (4u << 20) /* built-in scratch of lessdec_step_static, per GPU */
 
 typedef struct lessdec_desc {
   int32_t batch, heads, head_dim; /* B, Hh, D; D is 64 or 128                              */
@@ -192,6 +195,23 @@ int lessdec_step(const lessdec_desc *desc, const void *q, const void *k, const v
  */
 int lessdec_step_features(const lessdec_desc *desc, const void *q, const void *k, void *hip_stream);
 int lessdec_step_attend(const lessdec_desc *desc, const void *q, const void *k, const void *v,
+                        void *out, int32_t *evicted_pos, void *hip_stream);
+
+/*
+ * lessdec_step for callers that cannot bring or allocate scratch memory: code under HIP graph
+ * capture, serving loops and harnesses that forbid allocation.  Same arguments, same kernels
+ * and bit-identical results; desc->workspace and desc->workspace_bytes are ignored (may be
+ * NULL / 0) and the per-step scratch (the feature maps of the step on their way to the
+ * attention kernel, the per-block probability sums of the multi-head path) lives in a buffer
+ * of LESSDEC_STATIC_SCRATCH_BYTES that is part of the library image on every GPU it runs on.
+ * Calls no allocating routine.  A shape whose lessdec_workspace_bytes(desc, 0) exceeds that
+ * size is refused with LESSDEC_ESCRATCH before anything is launched (batch 64 x 32 heads at
+ * hidden width 512 needs 2.2 MiB).  The first call on a device looks up the buffer's device
+ * address (make that call outside a graph capture).  All calls on one GPU share the buffer, in
+ * whatever descriptor or stream: calls that overlap in time on one GPU race; calls ordered by
+ * a stream do not, and nothing needs clearing between them.
+ */
+int lessdec_step_static(const lessdec_desc *desc, const void *q, const void *k, const void *v,
                         void *out, int32_t *evicted_pos, void *hip_stream);
 
 /* Static message for a return code. */

@@ -17,9 +17,10 @@ DTYPE_F32, DTYPE_F16 = 0, 1
 FLAG_SPARSE_DENOM = 1
 FLAG_LAMBDA = 2
 FLAG_PROMPT_STEPWISE = 4
-OK, EINVAL, EWORKSPACE, EHIP = 0, -1, -2, -3
+OK, EINVAL, EWORKSPACE, EHIP, ESCRATCH = 0, -1, -2, -3, -4
+STATIC_SCRATCH_BYTES = 4 << 20
 
-EXPORTS = ("lessdec_workspace_bytes", "lessdec_state_reset", "lessdec_state_sync", "lessdec_prefill", "lessdec_step", "lessdec_step_features", "lessdec_step_attend",
+EXPORTS = ("lessdec_workspace_bytes", "lessdec_state_reset", "lessdec_state_sync", "lessdec_prefill", "lessdec_step", "lessdec_step_features", "lessdec_step_attend", "lessdec_step_static",
            "lessdec_strerror", "lessdec_budget_tokens")
 
 
@@ -65,6 +66,8 @@ def lib():
         L.lessdec_prefill.argtypes = [C.POINTER(Desc)] + [C.c_void_p] * 3 + [C.c_int32] + [C.c_void_p] * 2
         L.lessdec_step.restype = C.c_int
         L.lessdec_step.argtypes = [C.POINTER(Desc)] + [C.c_void_p] * 6
+        L.lessdec_step_static.restype = C.c_int
+        L.lessdec_step_static.argtypes = [C.POINTER(Desc)] + [C.c_void_p] * 6
         L.lessdec_step_features.restype = C.c_int
         L.lessdec_step_features.argtypes = [C.POINTER(Desc)] + [C.c_void_p] * 3
         L.lessdec_step_attend.restype = C.c_int
@@ -125,6 +128,11 @@ def lessdec_step_attend(desc: Desc, q, k, v, out, evicted_pos=None, stream=None)
 def lessdec_step(desc: Desc, q, k, v, out, evicted_pos=None, stream=None):
     _check(lib().lessdec_step(C.byref(desc), _p(q), _p(k), _p(v), _p(out), _p(evicted_pos),
                               _stream(stream)), "lessdec_step")
+
+
+def lessdec_step_static(desc: Desc, q, k, v, out, evicted_pos=None, stream=None):
+    _check(lib().lessdec_step_static(C.byref(desc), _p(q), _p(k), _p(v), _p(out), _p(evicted_pos),
+                                     _stream(stream)), "lessdec_step_static")
 
 
 def pack_weights(weights, device="cuda:0"):

@@ -2,7 +2,17 @@
 // allocates, synchronises or keeps state between calls.
 #include <math.h>
 
+#include <mutex>
+
 #include "lessdec_internal.h"
+
+// Built-in scratch of lessdec_step_static: part of the code object, so every GPU the library
+// runs on holds its own copy at its own address for the life of the process.  In host code the
+// name is only a handle for hipGetSymbolAddress; kernels get the looked-up address as an argument.
+// (No `used` attribute here: the compiler gives a static device variable that host code refers to
+// a global symbol in the code object, which is what the runtime's lookup needs; marked `used` it
+// stays a local symbol and the lookup aborts the process.)
+static __device__ __align__(256) unsigned char scratch[LESSDEC_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -107,6 +117,25 @@ StepArgs state_args(const lessdec_desc *desc, const Shape &s)
   a.f_phi = nullptr; a.f_phi32 = nullptr; a.f_psi = nullptr; a.mlp_parts = nullptr; a.gqa_parts = nullptr;
   a.Wk3 = desc->Wk3;
   return a;
+}
+
+// Device address of `scratch` on the current device, looked up once per device.
+constexpr int kMaxDevices = 64;
+void *g_scratch_addr[kMaxDevices];
+std::mutex g_scratch_mutex;
+
+int static_scratch(void **addr)
+{
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return LESSDEC_EHIP;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_addr[dev]) {
+    void *p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return LESSDEC_EHIP;
+    g_scratch_addr[dev] = p;
+  }
+  *addr = g_scratch_addr[dev];
+  return LESSDEC_OK;
 }
 
 }  // namespace
@@ -233,6 +262,21 @@ int lessdec_step(const lessdec_desc *desc, const void *q, const void *k, const v
   return lessdec_step_attend(desc, q, k, v, out, evicted_pos, hip_stream);
 }
 
+int lessdec_step_static(const lessdec_desc *desc, const void *q, const void *k, const void *v, void *out,
+                        int32_t *evicted_pos, void *hip_stream)
+{
+  Shape s;
+  if (!shape_ok(desc, &s)) return LESSDEC_EINVAL;
+  if (carve(s, 0, desc->flags).total > (size_t)LESSDEC_STATIC_SCRATCH_BYTES) return LESSDEC_ESCRATCH;
+  lessdec_desc d = *desc;
+  void *addr = nullptr;
+  const int rc = static_scratch(&addr);
+  if (rc) return rc;
+  d.workspace = addr;
+  d.workspace_bytes = LESSDEC_STATIC_SCRATCH_BYTES;
+  return lessdec_step(&d, q, k, v, out, evicted_pos, hip_stream);
+}
+
 int lessdec_prefill(const lessdec_desc *desc, const void *Q, const void *K, const void *V,
                     int32_t P, void *out, void *hip_stream)
 {
@@ -293,6 +337,7 @@ const char *lessdec_strerror(int code)
     case LESSDEC_EINVAL: return "invalid argument (shape, NULL or misaligned pointer, unsupported size)";
     case LESSDEC_EWORKSPACE: return "workspace missing, misaligned or too small";
     case LESSDEC_EHIP: return "HIP launch failed";
+    case LESSDEC_ESCRATCH: return "shape needs more scratch than the built-in buffer of lessdec_step_static holds";
     default: return "unknown lessdec error";
   }
 }
