@@ -12,10 +12,13 @@ before the timed region; the state of every layer comes from lessdec_prefill on 
 synthetic prompt.
 
 Prints one JSON line: value = unit-steps per second (units x steps / time), ms_per_step,
-roofline = algorithmic HBM bytes of the attention launch (the dominant kernel) divided by its
-measured time against the 8 TB/s peak, with the same figure for the whole step beside it
-(traffic = HBM bytes per launch measured with rocprofv3 counters), cpu_baseline = the fp64
-oracle timed on the host cores on a sample of the same workload.  One GPU only.
+roofline = the method's algorithmic HBM bytes per step divided by the measured time of a step
+(one launch on the headline workload: the feature-map jobs run inside the attention launch)
+against the 8 TB/s peak, beside it the same against the read rate a probe kernel sustains on
+this chip, the step timed again as replays of a HIP graph (median and minimum), the bytes this
+implementation moves on top of the algorithmic ones, and traffic = HBM bytes per step measured
+with rocprofv3 counters; cpu_baseline = the fp64 oracle timed on the host cores on a sample of
+the same workload.  One GPU only.
 """
 from __future__ import annotations
 
@@ -31,37 +34,39 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0        # MI355X published HBM3E bandwidth
 
-# HBM bytes per launch of the attention kernel, from the rocprofv3 FETCH_SIZE / WRITE_SIZE
-# counter runs of this same command (profiles/lessdec_step_cfg3_hbm_traffic.txt: counters
-# cannot be read from inside the process).  Only for the workload they were taken on.
-MEASURED_TRAFFIC_BYTES = {3: 138.6e6}        # the attention launch; the feature-map launch adds 12.1e6
+# HBM bytes per step (both directions), from the rocprofv3 FETCH_SIZE / WRITE_SIZE counter runs of
+# this same command on this build (profiles/lessdec_step_cfg3_hbm_traffic.txt: counters cannot be
+# read from inside the process).  Only for the workload and launch shape they were taken on.
+MEASURED_TRAFFIC_BYTES = {3: 153.8e6}        # 134.9 MB read + 18.9 MB written by the one launch of a step
 
 
 def algorithmic_bytes_per_unit_step(w) -> float:
     """Bytes the method itself must move per unit and step: every retained key and value once,
-    the step's rows in and out, the H2O scores and positions, the low-rank state read and
-    written, and the per-head feature-map weights shared by the batch rows."""
+    the step's rows in and out, the inserted pair, the H2O scores (4-byte) read and written, the
+    positions, the low-rank state (4-byte) read and written, psi of the discarded and of the new
+    pair, and the per-head feature-map weights shared by the batch rows."""
     e = 2 if w.dtype == "f16" else 4
     C, D, R, Rp, B, G = w.capacity, w.head_dim, w.rank, w.hidden, w.batch, w.q_per_kv
     kv = 2 * C * D * e                       # every retained key and value once
     io = (G + 2) * D * e + G * D * e + 2 * D * e   # q (G heads), k, v in; out (G heads); the inserted pair
-    scores = 2 * 8 * C + 4 * C + 4           # acc (fp64) read+write, pos read, one pos write
-    state = 2 * (R * D * 4 + R * 8)          # H (fp32) and z (fp64) read + write
+    scores = 2 * 4 * C + 4 * C + 4           # acc read+write, pos read, one pos write
+    state = 2 * (R * D + R) * 4              # H and z read + write
     psi = 2 * R * 4                          # psi of the discarded pair read, of the new pair written
-    return kv + io + scores + state + psi + _weight_bytes_per_unit_step(w)
+    weights = ((G + 1) * (D * Rp + Rp * R) + R * R) * e / B
+    return kv + io + scores + state + psi + weights
 
 
-def _weight_bytes_per_unit_step(w) -> float:
-    """Per-head feature-map weights (phi per query head, psi per key/value head), shared by the batch rows."""
+def implementation_extra_bytes_per_unit_step(w) -> dict:
+    """What this implementation moves on top of that (streaming single-head path)."""
     e = 2 if w.dtype == "f16" else 4
-    D, R, Rp, B, G = w.head_dim, w.rank, w.hidden, w.batch, w.q_per_kv
-    return ((G + 1) * (D * Rp + Rp * R) + R * R) * e / B
-
-
-def attend_bytes_per_unit_step(w) -> float:
-    """The same figure for the attention launch alone: everything except the weights, which
-    only the feature-map launch reads."""
-    return algorithmic_bytes_per_unit_step(w) - _weight_bytes_per_unit_step(w)
+    C, D, R, Rp = w.capacity, w.head_dim, w.rank, w.hidden
+    nparts = (Rp + 63) // 64
+    return {"fp64 accumulated scores (8 instead of 4 bytes, read and written)": 2 * 4 * C,
+            "fp64 z (read and written)": 2 * 4 * R,
+            "feature-map exchange array (written, read, handed back empty)": 3 * 2 * nparts * 16 * 4,
+            "parked discarded pair: value row and psi (written, read next step), slot word": 2 * (D * e + 4 * R) + 8,
+            "q and k rows read by the feature-map jobs as well": 2 * D * e,
+            "token counter and eviction log": 12}
 
 
 def log(*a):
@@ -107,6 +112,7 @@ def main():
     ap.add_argument("--prompt-stepwise", action="store_true",
                     help="the sparse policy active from the first prompt token (LESSDEC_FLAG_PROMPT_STEPWISE)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--graph-reps", type=int, default=20, help="timed replays of the captured steps (at least 10)")
     ap.add_argument("--cpu-units", type=int, default=1024)
     ap.add_argument("--cpu-steps", type=int, default=512)
     args = ap.parse_args()
@@ -195,33 +201,58 @@ def main():
     ms = e0.elapsed_time(e1)
     ms_per_step = ms / args.steps
 
-    # The two launches of a step, timed one kind at a time on the same stream, same inputs and
-    # same layer rotation (the attention launch then reads feature maps of an earlier query,
-    # which changes values but not work).
-    def run_half(first, count, attend):
-        for i in range(first, first + count):
-            lay = i % L
-            t = ((i // L) + 37 * lay) % T
-            if attend:
-                layers[lay].step_attend(q[t], k[t], v[t], outs[lay])
-            else:
-                layers[lay].step_features(q[t], k[t])
-
-    half_ms = {}
-    for attend in (False, True):
-        run_half(0, args.warmup, attend)
-        torch.cuda.synchronize()
-        e0.record(stream)
-        run_half(args.warmup, args.steps, attend)
-        e1.record(stream)
-        torch.cuda.synchronize()
-        half_ms[attend] = e0.elapsed_time(e1) / args.steps
-    attend_bytes = attend_bytes_per_unit_step(w) * U
-    attend_achieved = attend_bytes / (half_ms[True] * 1e-3) / 1e9
     unit_steps_per_s = U * args.steps / (ms * 1e-3)
     bytes_per_step = algorithmic_bytes_per_unit_step(w) * U
     achieved = bytes_per_step / (ms_per_step * 1e-3) / 1e9
 
+    # The same steps as replays of a HIP graph (what a serving loop would run): one graph of
+    # `graph_steps` steps, replayed `graph_reps` times, each replay timed by itself.
+    graph_steps, graph_reps = 8 * L, max(10, args.graph_reps)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        run(0, L)                                          # first launches on the capture stream
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            run(0, graph_steps)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    for _ in range(3):
+        graph.replay()
+    torch.cuda.synchronize()
+    rep_ms = []
+    for _ in range(graph_reps):
+        e0.record(stream)
+        graph.replay()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        rep_ms.append(e0.elapsed_time(e1) / graph_steps)
+    rep_ms.sort()
+
+    # The read rate this chip sustains for a stream shaped like the step's: the probe kernel over
+    # a buffer as large as the cycled working set, one wave per region as in the step.
+    from paper_2402_09398_amd import lessdec_probe_stream_read
+    probe_bytes = 1 << 30
+    pbuf = torch.empty((probe_bytes,), dtype=torch.uint8, device=dev).fill_(1)
+    psink = torch.zeros((8192,), dtype=torch.int32, device=dev)
+    for _ in range(3):
+        lessdec_probe_stream_read(pbuf, probe_bytes, 8192, psink)
+    torch.cuda.synchronize()
+    e0.record(stream)
+    for _ in range(10):
+        lessdec_probe_stream_read(pbuf, probe_bytes, 8192, psink)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    probe_gbs = 10 * probe_bytes / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    del pbuf
+
+    from paper_2402_09398_amd.binding import lessdec_step_launches
+    launches = lessdec_step_launches(layers[0].desc)
+    one_launch = launches == 1
+    extras = implementation_extra_bytes_per_unit_step(w) if w.q_per_kv == 1 else {}
+    fp64_flops = U * G * (Pn ** 2 * D + 2.0 * min(Cn, Pn) * Pn * D * 0.5)    # row pass + exact columns of the kept/doubtful tokens (about)
+    fp16_flops = prefill_flops - U * G * Pn ** 2 * D                          # everything else: A V, cheap column sums, psi, state
     result = {
         "metric": "decode steps/sec (batch\u00d7heads) + achieved HBM GB/s vs peak, Llama-2-7B shape",
         "value": unit_steps_per_s,
@@ -238,29 +269,37 @@ def main():
                                + (", Lambda-masking" if flags & 2 else "")
                                + (", policy active through the prompt" if flags & 4 else ""),
                    "layers_cycled": L, "prefill_ms": prefill_ms},
-        # the prompt phase (secondary path), one warm call: algorithmic flops against the fp64 matrix peak
-        "prefill": {"ms": prefill_ms, "prompt_tokens_per_s": U * w.prompt / (prefill_ms * 1e-3),
-                    "bound": "mfma", "achieved": prefill_flops / (prefill_ms * 1e-3) / 1e12, "peak": 78.6,
-                    "unit": "TFLOP/s", "frac": prefill_flops / (prefill_ms * 1e-3) / 1e12 / 78.6,
-                    "flops": prefill_flops,
-                    "note": ("algorithmic flops count Q K^T twice (row statistics, column sums) and A V; the "
-                             "column sums are computed exactly (fp64) only for tokens that can be kept, found by a "
-                             "cheap fp16 pass, and A V runs in fp16, so the figure can exceed the fp64 peak")
-                            if not flags & 2 else
-                            ("algorithmic flops of this policy: scores in fp64 (all causal pairs, or with the policy "
-                             "active through the prompt only the cached ones plus rank-R weights of the discarded "
-                             "ones), A V in fp16, column sums of the kept tokens only")},
-        # the dominant kernel: the attention launch (lessdec_step_attend), timed by itself
-        "roofline": {"bound": "hbm", "achieved": attend_achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": attend_achieved / HBM_PEAK_GBS,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(w.cfg) if L >= 8 and w.q_per_kv == 1 and flags == 0 else None,
-                     "kernel": ("wpu_step_kernel" if w.q_per_kv == 1 else "gqa_chunk_kernel") + " (lessdec_step_attend)",
-                     "bytes_per_launch": attend_bytes, "ms_per_launch": half_ms[True],
-                     "features_ms_per_launch": half_ms[False],
-                     "whole_step": {"achieved": achieved, "frac": achieved / HBM_PEAK_GBS,
-                                    "bytes_per_step": bytes_per_step},
+        # the whole step: on the headline workload one launch (feature-map jobs + attention waves)
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(w.cfg) if L >= 8 and w.q_per_kv == 1 and flags == 0 and one_launch else None,
+                     "kernel": ("wpu_step_kernel" + (" (one launch per step: feature-map jobs and attention waves)"
+                                                     if one_launch else " + mlp_parts_kernel (two launches per step)")
+                                if w.q_per_kv == 1 else "gqa_chunk_kernel + mlp_pair_kernel (two launches per step)"),
+                     "launches_per_step": launches,
+                     "bytes_per_launch": bytes_per_step, "ms_per_launch": ms_per_step,
+                     "algorithmic_bytes_per_unit_step": algorithmic_bytes_per_unit_step(w),
+                     "implementation_extra_bytes_per_unit_step": extras,
+                     "frac_with_extras": (bytes_per_step + sum(extras.values()) * U) / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
                      "kv_only_frac": 2 * w.capacity * D * (2 if w.dtype == "f16" else 4) * U
-                                     / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS},
+                                     / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                     "stream_probe": {"GB/s": probe_gbs, "frac_of_probe": achieved / probe_gbs,
+                                      "what": "lessdec_probe_stream_read: 1 GiB read once by 8192 waves, 7 KiB in flight each"},
+                     "graph_replay": {"reps": graph_reps, "steps_per_replay": graph_steps,
+                                      "ms_per_step_median": rep_ms[len(rep_ms) // 2], "ms_per_step_min": rep_ms[0],
+                                      "frac_median": bytes_per_step / (rep_ms[len(rep_ms) // 2] * 1e-3) / 1e9 / HBM_PEAK_GBS}},
+        # the prompt phase (secondary path), one warm call.  No per-kernel times are available inside
+        # the process, so each class of matrix work is divided by the time of the WHOLE call: lower
+        # bounds of what its kernels reach (per-kernel figures: profiles/).
+        "prefill": {"ms": prefill_ms, "prompt_tokens_per_s": U * w.prompt / (prefill_ms * 1e-3),
+                    "bound": "mfma",
+                    "fp64_matrix": {"flops": fp64_flops, "achieved": fp64_flops / (prefill_ms * 1e-3) / 1e12, "peak": 78.6,
+                                    "unit": "TFLOP/s", "frac": fp64_flops / (prefill_ms * 1e-3) / 1e12 / 78.6,
+                                    "what": "Q K^T of the row pass and the exact column sums (they decide the heavy set)"},
+                    "fp16_matrix": {"flops": fp16_flops, "achieved": fp16_flops / (prefill_ms * 1e-3) / 1e12, "peak": 2500.0,
+                                    "unit": "TFLOP/s", "frac": fp16_flops / (prefill_ms * 1e-3) / 1e12 / 2500.0,
+                                    "what": "A V, the cheap column sums, psi of the prompt keys, the state build"},
+                    "note": "each class over the time of the whole call (a lower bound for its own kernels)"},
     }
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, min(args.cpu_units, U), min(args.cpu_steps, T), flags)

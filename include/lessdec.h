@@ -111,7 +111,15 @@ typedef struct lessdec_desc {
   const void *Wq1, *Wq2;          /* phi: [Hh,R',D], [Hh,R,R']; with G > 1 per query head:
                                      [Hh*G,R',D], [Hh*G,R,R'], head h's G in a row          */
   const void *Wk1, *Wk2, *Wk3;    /* psi: [Hh,R',D], [Hh,R,R'], [Hh,R,R]                   */
-  void *workspace;                /* >= lessdec_workspace_bytes(), 256-byte aligned        */
+  void *workspace;                /* >= lessdec_workspace_bytes(), 256-byte aligned.  Scratch,
+                                     with one condition: before the first lessdec_step with a
+                                     workspace it must either have been handed, in this
+                                     descriptor, to lessdec_state_reset or lessdec_prefill, or
+                                     be filled with 0xFF bytes (where lessdec_step runs as one
+                                     launch, the feature maps reach the attention waves through
+                                     an array in it whose unwritten entries must read as empty;
+                                     every step leaves it so).  A workspace serves descriptors
+                                     of one shape                                            */
   size_t workspace_bytes;
 } lessdec_desc;
 
@@ -185,8 +193,9 @@ int lessdec_step(const lessdec_desc *desc, const void *q, const void *k, const v
 
 /*
  * The two halves of lessdec_step, for a caller that has q and k before it wants the
- * attention output (or that times them separately).  lessdec_step is exactly the first
- * followed by the second.
+ * attention output.  lessdec_step gives exactly the results of the first followed by the
+ * second (on large shapes it runs both in one launch).  Every lessdec_step_features is to be
+ * followed by its lessdec_step_attend before the next step on that workspace.
  *  lessdec_step_features: evaluates phi(q) (Eq. 1) and psi(k) (Eq. 2) of the step for every
  *    unit into the workspace.  Touches no state.
  *  lessdec_step_attend: everything else of the step, reading the feature maps that the last
@@ -196,6 +205,12 @@ int lessdec_step(const lessdec_desc *desc, const void *q, const void *k, const v
 int lessdec_step_features(const lessdec_desc *desc, const void *q, const void *k, void *hip_stream);
 int lessdec_step_attend(const lessdec_desc *desc, const void *q, const void *k, const void *v,
                         void *out, int32_t *evicted_pos, void *hip_stream);
+
+/*
+ * Host only: the number of kernel launches one lessdec_step on this descriptor makes (1 where the
+ * feature-map jobs run inside the attention launch), 0 if the shape fields are invalid.
+ */
+int lessdec_step_launches(const lessdec_desc *desc);
 
 /*
  * lessdec_step for callers that cannot bring or allocate scratch memory: code under HIP graph
@@ -213,6 +228,16 @@ int lessdec_step_attend(const lessdec_desc *desc, const void *q, const void *k, 
  */
 int lessdec_step_static(const lessdec_desc *desc, const void *q, const void *k, const void *v,
                         void *out, int32_t *evicted_pos, void *hip_stream);
+
+/*
+ * Measurement aid (Sec. 4.5 times the method; this times the memory it runs on): reads
+ * `bytes` of device memory at `buf` (16-byte aligned) once, as `waves` (a multiple of 8)
+ * independent contiguous read streams shaped like those of lessdec_step, and discards the data.
+ * sink: [waves] device words, left untouched in practice.  Timing it gives the read rate this
+ * chip sustains for the access pattern of the decode step, to put beside the published peak.
+ */
+int lessdec_probe_stream_read(const void *buf, size_t bytes, int32_t waves, uint32_t *sink,
+                              void *hip_stream);
 
 /* Static message for a return code. */
 const char *lessdec_strerror(int code);

@@ -4,6 +4,6 @@
 inputs, `build` the in-tree build of liblessdec.so.
 """
 from . import binding, workloads  # noqa: F401
-from .binding import (LessDec, LessdecError, lessdec_budget_tokens, lessdec_prefill,  # noqa: F401
+from .binding import (LessDec, LessdecError, lessdec_budget_tokens, lessdec_prefill, lessdec_probe_stream_read,  # noqa: F401
                       lessdec_state_reset, lessdec_state_sync, lessdec_step, lessdec_step_attend,
                       lessdec_step_features, lessdec_step_static, lessdec_workspace_bytes, pack_weights)

@@ -21,6 +21,7 @@ OK, EINVAL, EWORKSPACE, EHIP, ESCRATCH = 0, -1, -2, -3, -4
 STATIC_SCRATCH_BYTES = 4 << 20
 
 EXPORTS = ("lessdec_workspace_bytes", "lessdec_state_reset", "lessdec_state_sync", "lessdec_prefill", "lessdec_step", "lessdec_step_features", "lessdec_step_attend", "lessdec_step_static",
+           "lessdec_probe_stream_read", "lessdec_step_launches",
            "lessdec_strerror", "lessdec_budget_tokens")
 
 
@@ -72,6 +73,10 @@ def lib():
         L.lessdec_step_features.argtypes = [C.POINTER(Desc)] + [C.c_void_p] * 3
         L.lessdec_step_attend.restype = C.c_int
         L.lessdec_step_attend.argtypes = [C.POINTER(Desc)] + [C.c_void_p] * 6
+        L.lessdec_probe_stream_read.restype = C.c_int
+        L.lessdec_probe_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_int32, C.c_void_p, C.c_void_p]
+        L.lessdec_step_launches.restype = C.c_int
+        L.lessdec_step_launches.argtypes = [C.POINTER(Desc)]
         L.lessdec_strerror.restype = C.c_char_p
         L.lessdec_strerror.argtypes = [C.c_int]
         L.lessdec_budget_tokens.restype = C.c_int32
@@ -133,6 +138,15 @@ def lessdec_step(desc: Desc, q, k, v, out, evicted_pos=None, stream=None):
 def lessdec_step_static(desc: Desc, q, k, v, out, evicted_pos=None, stream=None):
     _check(lib().lessdec_step_static(C.byref(desc), _p(q), _p(k), _p(v), _p(out), _p(evicted_pos),
                                      _stream(stream)), "lessdec_step_static")
+
+
+def lessdec_step_launches(desc: Desc) -> int:
+    return int(lib().lessdec_step_launches(C.byref(desc)))
+
+
+def lessdec_probe_stream_read(buf, nbytes: int, waves: int, sink, stream=None):
+    _check(lib().lessdec_probe_stream_read(_p(buf), int(nbytes), int(waves), _p(sink), _stream(stream)),
+           "lessdec_probe_stream_read")
 
 
 def pack_weights(weights, device="cuda:0"):
@@ -204,7 +218,8 @@ class LessDec:
         need = lessdec_workspace_bytes(d, max_prompt)
         if need == 0:
             raise LessdecError("lessdec_workspace_bytes: invalid shape")
-        self.workspace = torch.empty((need,), dtype=torch.uint8, device=dev)
+        # 0xFF bytes: the per-step exchange array of the one-launch step reads as empty (lessdec.h)
+        self.workspace = torch.full((need,), 255, dtype=torch.uint8, device=dev)
         d.workspace = self.workspace.data_ptr()
         d.workspace_bytes = need
         self.desc = d

@@ -114,9 +114,30 @@ StepArgs state_args(const lessdec_desc *desc, const Shape &s)
   a.pend_slot = desc->pend_slot; a.pend_v = desc->pend_v; a.pend_psi = desc->pend_psi;
   a.q = a.k = a.v = nullptr; a.out = nullptr; a.evicted_pos = nullptr;
   a.U = (int)s.U; a.Hh = desc->heads; a.B = desc->batch;
-  a.f_phi = nullptr; a.f_phi32 = nullptr; a.f_psi = nullptr; a.mlp_parts = nullptr; a.gqa_parts = nullptr;
-  a.Wk3 = desc->Wk3;
+  a.f_phi = nullptr; a.f_phi32 = nullptr; a.f_psi = nullptr; a.mlp_parts = nullptr; a.mlp_out = nullptr;
+  a.gqa_parts = nullptr;
+  a.Wk3 = desc->Wk3; a.Wk2 = desc->Wk2;
   return a;
+}
+
+MlpPartsArgs parts_args(const lessdec_desc *desc, const void *q, const void *k, float *out)
+{
+  MlpPartsArgs fm;
+  fm.q = (const __half *)q; fm.k = (const __half *)k;
+  fm.Wq1 = (const __half *)desc->Wq1; fm.Wq2 = (const __half *)desc->Wq2;
+  fm.Wk1 = (const __half *)desc->Wk1; fm.Wk2 = (const __half *)desc->Wk2;
+  fm.out = out;
+  fm.B = desc->batch; fm.Hh = desc->heads; fm.D = desc->head_dim; fm.Rp = desc->hidden; fm.R = desc->rank;
+  return fm;
+}
+
+// The per-step exchange array of the streaming path starts out empty (see wpu_step_kernel).
+hipError_t empty_exchange(const lessdec_desc *desc, const Shape &s, hipStream_t st)
+{
+  if (s.G != 1 || !wpu_supported(desc->dtype, desc->head_dim, (int)s.C, desc->hidden, desc->rank)) return hipSuccess;
+  const Workspace w = carve(s, 0, desc->flags);
+  return launch_fill_empty(reinterpret_cast<float *>(static_cast<char *>(desc->workspace) + w.off_parts),
+                           2 * (size_t)mlp_nparts((int)s.Rp) * s.U * 16, st);
 }
 
 // Device address of `scratch` on the current device, looked up once per device.
@@ -154,6 +175,7 @@ int lessdec_state_reset(const lessdec_desc *desc, void *hip_stream)
   Shape s;
   int rc = check_desc(desc, &s, 0);
   if (rc) return rc;
+  if (empty_exchange(desc, s, (hipStream_t)hip_stream) != hipSuccess) return LESSDEC_EHIP;
   return launch_reset(desc, (hipStream_t)hip_stream) == hipSuccess ? LESSDEC_OK : LESSDEC_EHIP;
 }
 
@@ -178,12 +200,7 @@ int lessdec_step_features(const lessdec_desc *desc, const void *q, const void *k
   char *ws = static_cast<char *>(desc->workspace);
   if (s.G == 1 && wpu_supported(desc->dtype, desc->head_dim, (int)s.C, desc->hidden, desc->rank)) {
     // matrix-core feature maps up to the layer-2 sums
-    MlpPartsArgs fm;
-    fm.q = (const __half *)q; fm.k = (const __half *)k;
-    fm.Wq1 = (const __half *)desc->Wq1; fm.Wq2 = (const __half *)desc->Wq2;
-    fm.Wk1 = (const __half *)desc->Wk1; fm.Wk2 = (const __half *)desc->Wk2;
-    fm.out = reinterpret_cast<float *>(ws + w.off_parts);
-    fm.B = desc->batch; fm.Hh = desc->heads; fm.D = desc->head_dim; fm.Rp = desc->hidden; fm.R = desc->rank;
+    const MlpPartsArgs fm = parts_args(desc, q, k, reinterpret_cast<float *>(ws + w.off_parts));
     return launch_mlp_parts(fm, st) == hipSuccess ? LESSDEC_OK : LESSDEC_EHIP;
   }
   if (s.G > 1 && mlp_mfma_supported(desc->dtype, desc->head_dim, desc->hidden, desc->rank)) {
@@ -238,7 +255,7 @@ int lessdec_step_attend(const lessdec_desc *desc, const void *q, const void *k, 
     return launch_step_gqa(a, (int)s.G, desc->dtype, desc->head_dim, st) == hipSuccess ? LESSDEC_OK : LESSDEC_EHIP;
   }
   if (wpu_supported(desc->dtype, desc->head_dim, (int)s.C, desc->hidden, desc->rank)) {
-    a.mlp_parts = reinterpret_cast<float *>(ws + w.off_parts);     // one wave per unit
+    a.mlp_parts = a.mlp_out = reinterpret_cast<float *>(ws + w.off_parts);     // one wave per unit
     return launch_step_wpu(a, desc->head_dim, st) == hipSuccess ? LESSDEC_OK : LESSDEC_EHIP;
   }
   a.f_phi = reinterpret_cast<double *>(ws + w.off_fphi);           // one block per unit
@@ -257,9 +274,30 @@ int lessdec_step(const lessdec_desc *desc, const void *q, const void *k, const v
   if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(out, 16) ||
       !aligned(evicted_pos, 4))
     return LESSDEC_EINVAL;
+  if (s.G == 1 && wpu_supported(desc->dtype, desc->head_dim, (int)s.C, desc->hidden, desc->rank) &&
+      wpu_fusable(desc->batch, desc->heads, desc->head_dim, (int)s.C, desc->hidden, desc->rank)) {
+    // feature maps and attention in one launch
+    StepArgs a = state_args(desc, s);
+    a.q = q; a.k = k; a.v = v; a.out = out; a.evicted_pos = evicted_pos;
+    const Workspace w = carve(s, 0, desc->flags);
+    float *parts = reinterpret_cast<float *>(static_cast<char *>(desc->workspace) + w.off_parts);
+    a.mlp_parts = a.mlp_out = parts;
+    const MlpPartsArgs fm = parts_args(desc, q, k, parts);
+    return launch_step_wpu(a, desc->head_dim, (hipStream_t)hip_stream, &fm) == hipSuccess ? LESSDEC_OK : LESSDEC_EHIP;
+  }
   rc = lessdec_step_features(desc, q, k, hip_stream);
   if (rc) return rc;
   return lessdec_step_attend(desc, q, k, v, out, evicted_pos, hip_stream);
+}
+
+int lessdec_step_launches(const lessdec_desc *desc)
+{
+  Shape s;
+  if (!shape_ok(desc, &s)) return 0;
+  if (s.G > 1) return gqa_head_blocks((long)s.U, (int)s.G) > 1 ? 3 : 2;   // feature maps, heads, (finishing launch)
+  if (wpu_supported(desc->dtype, desc->head_dim, (int)s.C, desc->hidden, desc->rank))
+    return wpu_fusable(desc->batch, desc->heads, desc->head_dim, (int)s.C, desc->hidden, desc->rank) ? 1 : 2;
+  return 3;                                                                 // phi, psi, step
 }
 
 int lessdec_step_static(const lessdec_desc *desc, const void *q, const void *k, const void *v, void *out,
@@ -274,7 +312,16 @@ int lessdec_step_static(const lessdec_desc *desc, const void *q, const void *k, 
   if (rc) return rc;
   d.workspace = addr;
   d.workspace_bytes = LESSDEC_STATIC_SCRATCH_BYTES;
-  return lessdec_step(&d, q, k, v, out, evicted_pos, hip_stream);
+  // always the two launches: the one-launch form of lessdec_step needs an exchange array that is
+  // empty when the step starts, which a buffer shared by descriptors of any shape cannot promise
+  if (!q || !k || !v || !out) return LESSDEC_EINVAL;
+  if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(out, 16) || !aligned(evicted_pos, 4))
+    return LESSDEC_EINVAL;
+  int rc2 = check_desc(&d, &s, 0);
+  if (rc2) return rc2;
+  rc2 = lessdec_step_features(&d, q, k, hip_stream);
+  if (rc2) return rc2;
+  return lessdec_step_attend(&d, q, k, v, out, evicted_pos, hip_stream);
 }
 
 int lessdec_prefill(const lessdec_desc *desc, const void *Q, const void *K, const void *V,
@@ -304,6 +351,7 @@ int lessdec_prefill(const lessdec_desc *desc, const void *Q, const void *K, cons
     r.ks = ws + w.off_stage + 1 * part;
     r.vs = ws + w.off_stage + 2 * part;
     r.outs = ws + w.off_stage + 3 * part;
+    if (empty_exchange(desc, s, st) != hipSuccess) return LESSDEC_EHIP;
     if (launch_reset(desc, st) != hipSuccess) return LESSDEC_EHIP;
     for (int32_t t = 0; t < P; ++t) {
       if (launch_prompt_rows(r, t, (out && t > 0) ? t - 1 : -1, st) != hipSuccess) return LESSDEC_EHIP;
@@ -327,6 +375,7 @@ int lessdec_prefill(const lessdec_desc *desc, const void *Q, const void *K, cons
   a.hpre = reinterpret_cast<float *>(ws + w.off_hpre);
   a.zpre = reinterpret_cast<float *>(ws + w.off_zpre);
   a.masked = masked ? 1 : 0;
+  if (empty_exchange(desc, s, (hipStream_t)hip_stream) != hipSuccess) return LESSDEC_EHIP;
   return launch_prefill(a, (hipStream_t)hip_stream) == hipSuccess ? LESSDEC_OK : LESSDEC_EHIP;
 }
 

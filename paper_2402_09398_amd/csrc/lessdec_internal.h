@@ -72,7 +72,9 @@ struct StepArgs {
   const float *f_psi;    // [U,R]
   // wave-per-unit path: layer-2 sums of both feature maps by parts (launch_mlp_parts), and W3
   const float *mlp_parts;
+  float *mlp_out;        // the same array, for handing entries back empty (and, fused, for writing them)
   const void *Wk3;
+  const void *Wk2;       // fused launch only (the other weight pointers are kernel arguments of their own)
 };
 hipError_t launch_step(const StepArgs &a, int dtype, int D, hipStream_t st);
 // several query heads per unit: q, out [U,G,D], f_phi [U,G,R]
@@ -83,7 +85,13 @@ hipError_t launch_state_sync(const StepArgs &a, int dtype, int D, hipStream_t st
 
 // One wave per unit, K and V streamed through a register ring (lessdec_wpu.hip).
 bool wpu_supported(int dtype, int D, int C, int Rp, int R);
-hipError_t launch_step_wpu(const StepArgs &a, int D, hipStream_t st);
+// fm == nullptr: the step's feature-map sums are in a.mlp_parts already (launch_mlp_parts ran
+// before).  fm != nullptr (only where wpu_fusable says so): one launch does both.
+hipError_t launch_step_wpu(const StepArgs &a, int D, hipStream_t st, const MlpPartsArgs *fm = nullptr);
+// Whether the whole step of this shape runs as one launch: the exchange array must then hold
+// kMlpEmpty everywhere when the step starts (launch_fill_empty; every step leaves it so).
+bool wpu_fusable(int B, int Hh, int D, int C, int Rp, int R);
+hipError_t launch_fill_empty(float *parts, size_t count, hipStream_t st);
 
 hipError_t launch_reset(const lessdec_desc *d, hipStream_t st);
 

@@ -16,8 +16,14 @@
 #pragma once
 
 #include "lessdec_common.h"
+#include "lessdec_internal.h"
 
 namespace lessdec {
+
+// An entry of the per-step exchange between the feature-map jobs and the attention waves that no
+// job has written yet: a NaN that no sum of finite products can be (all bits set; a caller clears
+// a workspace with a byte fill of 0xFF).
+constexpr unsigned kMlpEmpty = 0xffffffffu;
 
 typedef _Float16 v8h __attribute__((ext_vector_type(8)));
 typedef _Float16 v4h __attribute__((ext_vector_type(4)));
@@ -86,6 +92,103 @@ __device__ inline void mlp_load_row(const __half *xr, int g, v8h (&bx)[D / 32])
 {
 #pragma unroll
   for (int ks = 0; ks < D / 32; ++ks) bx[ks] = *reinterpret_cast<const v8h *>(xr + 32 * ks + 8 * g);
+}
+
+// One job of a decode step's feature maps: (head, map, part of kMlpPartHidden hidden units,
+// chunk of 64 batch rows), done by a block of four waves of 16 rows each that take the same two
+// groups of 32 hidden units, so the head's weights are read once per 64 rows.  job = ((chunk *
+// nparts + part) * 2 + map) * Hh + head: head fastest, so with Hh a multiple of 8 a head's jobs,
+// and later its readers, share an XCD and its L2.  wave: 0..3 within the job; every thread of the
+// block must call (one barrier inside).
+// The job's 64 rows of W1 are contiguous in memory: the block fetches them with whole-line loads
+// (a wave instruction = 1 KiB = four rows) into the LDS, once for its four waves, and the waves
+// pick their matrix operands out of the LDS.  Operand-shaped loads from memory (16 rows x 64
+// bytes per instruction, by each of the four waves) put nine times as many cache-line requests
+// on the compute unit's memory pipeline, which is what slows waves streaming the cache next to
+// it when this job runs inside the attention launch.  Rows are padded by 16 bytes in the LDS so
+// that the 16 lanes of an operand read (same 16-byte column, 16 rows) fall into different banks.
+// out[((map * nparts + part) * U + u) * 16 + r]: part's share of the layer-2 pre-activation r of
+// unit u.  COHERENT: the readers run in the same launch, possibly on another XCD whose L2 is not
+// coherent with this one's: the results go out as device-scope stores (written through).
+template <int D, bool COHERENT>
+__device__ inline void mlp_parts_job(const __half *q, const __half *k, const __half *Wq1, const __half *Wk1,
+                                     const __half *Wq2, const __half *Wk2, int Hh, int Rp, int R, int B,
+                                     float *out, int job, int wave, int l)
+{
+  constexpr int kRowBytes = D * 2, kStride = kRowBytes + 16, kChunks = kRowBytes / 16;
+  __shared__ __attribute__((aligned(16))) unsigned char s_w1[kMlpPartHidden * kStride];
+  const int g = l / 16, c = l % 16;
+  const int nparts = mlp_nparts(Rp);
+  int b = job;
+  const int h = b % Hh; b /= Hh;
+  const int map = b % 2; b /= 2;
+  const int part = b % nparts;
+  const int chunk = b / nparts;
+  const __half *x = map ? k : q;
+  const __half *W1 = (map ? Wk1 : Wq1) + (size_t)h * Rp * D;
+  const __half *W2 = (map ? Wk2 : Wq2) + (size_t)h * R * Rp;
+  const int row = chunk * 64 + wave * 16 + c;              // batch row of MFMA column c
+  const bool rowv = row < B;
+  const size_t u = (size_t)(rowv ? row : 0) * Hh + h;
+  v8h bx[D / 32];
+  mlp_load_row<D>(x + u * D, g, bx);                       // padding: any row
+  const int hid = part * kMlpPartHidden;
+  const bool two = hid + 32 < Rp;                          // the last part may hold one group
+  // the job's rows of W1, whole lines (rows past the last hidden unit repeat it: never used)
+  constexpr int kPerThread = kMlpPartHidden * kChunks / 256;
+  uint4 wreg[kPerThread];
+  const int tid = wave * 64 + l;
+#pragma unroll
+  for (int i = 0; i < kPerThread; ++i) {
+    const int idx = tid + 256 * i, wr = idx / kChunks, ch = idx % kChunks;
+    const int hr = hid + wr < Rp ? hid + wr : Rp - 1;
+    wreg[i] = *reinterpret_cast<const uint4 *>(W1 + (size_t)hr * D + ch * 8);
+  }
+  // layer 2: row r = c of W2 (c < R), the 8 hidden units of lane group g in each group of 32
+  v8h a2[2];
+#pragma unroll
+  for (int grp = 0; grp < 2; ++grp) {
+    const __half *w2 = W2 + (size_t)(c < R ? c : 0) * Rp + (grp == 0 || two ? hid + 32 * grp : hid) + 4 * g;
+    const v4h lo = *reinterpret_cast<const v4h *>(w2);
+    const v4h hi = *reinterpret_cast<const v4h *>(w2 + 16);
+    a2[grp] = v8h{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+  }
+#pragma unroll
+  for (int i = 0; i < kPerThread; ++i) {
+    const int idx = tid + 256 * i, wr = idx / kChunks, ch = idx % kChunks;
+    *reinterpret_cast<uint4 *>(s_w1 + wr * kStride + ch * 16) = wreg[i];
+  }
+  __syncthreads();
+  auto tiles = [&](int grp) {
+    MlpTiles<D> t;
+#pragma unroll
+    for (int ks = 0; ks < D / 32; ++ks) {
+      t.a0[ks] = *reinterpret_cast<const v8h *>(s_w1 + (32 * grp + c) * kStride + (32 * ks + 8 * g) * 2);
+      t.a1[ks] = *reinterpret_cast<const v8h *>(s_w1 + (32 * grp + 16 + c) * kStride + (32 * ks + 8 * g) * 2);
+    }
+    t.a2 = a2[grp];
+    return t;
+  };
+  const MlpTiles<D> t0 = tiles(0);
+  const MlpTiles<D> t1 = tiles(two ? 1 : 0);
+  v4f c2 = {0.f, 0.f, 0.f, 0.f};
+  mlp_apply_tiles<D>(t0, bx, c2);
+  if (two) mlp_apply_tiles<D>(t1, bx, c2);
+  // c2[w]: output r = 4 g + w of row c
+  if (rowv) {
+    const size_t U = (size_t)B * Hh;
+    float *dst = out + (((size_t)map * nparts + part) * U + u) * 16 + 4 * g;
+    if constexpr (COHERENT) {
+      unsigned long long lo, hi;
+      const float2 a = {c2[0], c2[1]}, bq = {c2[2], c2[3]};
+      __builtin_memcpy(&lo, &a, 8);
+      __builtin_memcpy(&hi, &bq, 8);
+      __hip_atomic_store(reinterpret_cast<unsigned long long *>(dst), lo, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_store(reinterpret_cast<unsigned long long *>(dst) + 1, hi, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    } else {
+      *reinterpret_cast<float4 *>(dst) = float4{c2[0], c2[1], c2[2], c2[3]};
+    }
+  }
 }
 
 }  // namespace lessdec

@@ -170,11 +170,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   }
 }
 
-// Decode step: both maps for every unit, by parts of 64 hidden units.  One block = one
-// (head, map, part, chunk of 64 batch rows); its four waves take 16 rows each and the same
-// two groups of 32 hidden units, so the head's weights are read once per 64 rows.  Head
-// fastest in blockIdx: with Hh a multiple of 8 a head's blocks, and later its readers, share
-// an XCD and its L2.
+// Decode step: both maps for every unit, by parts of 64 hidden units, one job of mlp_parts_job
+// per block.
 template <int D>
 __global__ __launch_bounds__(256) void mlp_parts_kernel(const __half *q, const __half *k, const __half *Wq1,
                                                         const __half *Wk1, const __half *Wq2, const __half *Wk2,
@@ -183,34 +180,8 @@ __global__ __launch_bounds__(256) void mlp_parts_kernel(const __half *q, const _
   // Plain scalar arguments, the ones the loads need first: the launch can preload the first
   // sixteen dwords into registers (the compile flag asks for it), which takes the argument
   // fetch out of a kernel that is one chain of latencies.
-  const int wave = threadIdx.x / 64, l = threadIdx.x % 64, g = l / 16, c = l % 16;
-  const int nparts = mlp_nparts(Rp);
-  int b = blockIdx.x;
-  const int h = b % Hh; b /= Hh;
-  const int map = b % 2; b /= 2;
-  const int part = b % nparts;
-  const int chunk = b / nparts;
-  const __half *x = map ? k : q;
-  const __half *W1 = (map ? Wk1 : Wq1) + (size_t)h * Rp * D;
-  const __half *W2 = (map ? Wk2 : Wq2) + (size_t)h * R * Rp;
-  const int row = chunk * 64 + wave * 16 + c;              // batch row of MFMA column c
-  const bool rowv = row < B;
-  const size_t u = (size_t)(rowv ? row : 0) * Hh + h;
-  v8h bx[D / 32];
-  mlp_load_row<D>(x + u * D, g, bx);                       // padding: any row
-  const int hid = part * kMlpPartHidden;
-  const bool two = hid + 32 < Rp;                          // the last part may hold one group
-  const MlpTiles<D> t0 = mlp_load_tiles<D>(W1, W2, Rp, R, hid, g, c);
-  const MlpTiles<D> t1 = mlp_load_tiles<D>(W1, W2, Rp, R, two ? hid + 32 : hid, g, c);
-  v4f c2 = {0.f, 0.f, 0.f, 0.f};
-  mlp_apply_tiles<D>(t0, bx, c2);
-  if (two) mlp_apply_tiles<D>(t1, bx, c2);
-  // c2[w]: output r = 4 g + w of row c
-  if (rowv) {
-    const size_t U = (size_t)B * Hh;
-    float *dst = out + (((size_t)map * nparts + part) * U + u) * 16 + 4 * g;
-    *reinterpret_cast<float4 *>(dst) = float4{c2[0], c2[1], c2[2], c2[3]};
-  }
+  mlp_parts_job<D, false>(q, k, Wq1, Wk1, Wq2, Wk2, Hh, Rp, R, B, out, (int)blockIdx.x, (int)threadIdx.x / 64,
+                          (int)threadIdx.x % 64);
 }
 
 bool mlp_mfma_supported(int dtype, int D, int Rp, int R)

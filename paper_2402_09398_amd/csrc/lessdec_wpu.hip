@@ -1,5 +1,6 @@
 // Decode step (Algorithm 1), streaming form: one wave per unit.  The layer-2 sums of the step's
 // feature maps come from the matrix-core launch before it (lessdec_mlp.hip).
+#include "lessdec_mlp.h"
 #include "lessdec_wave.h"
 
 namespace lessdec {
@@ -7,6 +8,8 @@ namespace lessdec {
 constexpr int kWpuUnits = 8;        // units (waves) per block, at most
 constexpr int kWpuMaxRows = 512;    // C + 1 at most
 constexpr int kWpuSplitWaves = 3072; // a unit's rows are split over more waves while the launch stays below this many
+constexpr int kWpuFusedUnits = 4;   // FUSED: units (waves) per block, the size of a feature-map job
+constexpr int kWpuSpinLimit = 1 << 14;   // FUSED: polls of the feature-map entries before a wave gives up
 
 // =====================================================================================
 // A block is 8 waves = 8 units that share a head: batch rows 8 * chunk .. 8 * chunk + 7 of
@@ -42,15 +45,31 @@ constexpr int kWpuSplitWaves = 3072; // a unit's rows are split over more waves 
 // Phase 4  fold of the pending pair into H (Eq. 4); out = p V + phi(q) H / den (Eq. 3); the
 //          new pair goes into the freed slot (Sec. 3.2); the discarded pair is left pending
 //          for the next step.
+//
+// FUSED: the whole step in one launch.  The first n_mlp blocks (four waves each) are the step's
+// feature-map jobs (mlp_parts_job), the blocks behind them the attention waves, four units per
+// block.  Workgroups are dispatched in index order, so every job is on a compute unit before any
+// attention wave that may wait for it, and the jobs wait for nothing: no cycle of waits exists.
+// The layer-2 sums travel through the exchange array as 32-bit entries, written through by the
+// jobs and read with device-scope loads.  An entry that no job has written yet holds kMlpEmpty:
+// an attention wave requests its entries behind the last-but-one pass of the key stream (by then
+// the jobs are normally long done), checks them after the last pass, asks again while any is still
+// empty, and puts kMlpEmpty back once it has them, so that the array is all empty again when the
+// step ends.  (The form that gets its entries from a launch before it, !FUSED, empties them as
+// well: either form can follow the other on one workspace.)  A wave that has polled
+// kWpuSpinLimit times gives up and computes with the empty entries, which are NaN: the outputs
+// of its unit then show it.
 // =====================================================================================
-template <int D, int NR2, int RM, int DEPTH, bool SPLIT>
-__global__ __launch_bounds__(kWpuUnits * kWave) void wpu_step_kernel(void *k_cache_, const void *q_, const void *k_,
-                                                                    int C_, int Hh_, int B_, const StepArgs a)
+template <int D, int NR2, int RM, int DEPTH, bool SPLIT, bool FUSED>
+__global__ __launch_bounds__((FUSED ? kWpuFusedUnits : kWpuUnits) * kWave, FUSED ? 4 : 1) void wpu_step_kernel(
+    void *k_cache_, const void *q_, const void *k_, int crp_, int Hh_, int B_, int n_mlp, const void *Wq1_,
+    const void *Wk1_, const void *Wq2_, const StepArgs a)
 {
   // The first arguments repeat what the head of the kernel needs to request the first rows:
   // scalar arguments can be preloaded into registers by the launch (the compile flag asks for
-  // it), the struct has to be fetched.
+  // it), the struct has to be fetched.  crp_ = C | R << 12 | R' << 19.
   using T = __half;
+  static_assert(!(SPLIT && FUSED), "the fused launch is one wave per unit");
   constexpr int EPL = 8;                   // elements per lane
   constexpr int LPR = D / EPL;             // lanes per row
   constexpr int RPI = kWave / LPR;         // rows per load instruction
@@ -59,11 +78,21 @@ __global__ __launch_bounds__(kWpuUnits * kWave) void wpu_step_kernel(void *k_cac
 
   extern __shared__ double dyn[];
 
-  const int C = C_, R = a.R, Hh = Hh_;
+  const int C = crp_ & 0xfff, R = (crp_ >> 12) & 0x7f, Rp = crp_ >> 19, Hh = Hh_;
   const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
+  if constexpr (FUSED) {
+    if ((int)blockIdx.x < n_mlp) {
+      mlp_parts_job<D, true>(reinterpret_cast<const __half *>(q_), reinterpret_cast<const __half *>(k_),
+                             reinterpret_cast<const __half *>(Wq1_), reinterpret_cast<const __half *>(Wk1_),
+                             reinterpret_cast<const __half *>(Wq2_), reinterpret_cast<const __half *>(a.Wk2), Hh, Rp, R,
+                             B_, a.mlp_out, (int)blockIdx.x, wave, lane);
+      return;
+    }
+  }
+  const int bid = FUSED ? (int)blockIdx.x - n_mlp : (int)blockIdx.x;
   const int lr = lane % LPR, rb = lane / LPR;
-  const int h = (int)blockIdx.x % Hh, chunk = (int)blockIdx.x / Hh;
+  const int h = bid % Hh, chunk = bid / Hh;
   const int upb = (int)blockDim.x >> 6;                      // waves in this block
   // SPLIT: the waves of the block share one unit, wave w taking every nw-th load of each
   // stream; otherwise a wave is a unit.
@@ -102,15 +131,26 @@ __global__ __launch_bounds__(kWpuUnits * kWave) void wpu_step_kernel(void *k_cac
   __builtin_amdgcn_sched_barrier(0);
   // 2. layer-2 sums of the two feature maps by parts (lane r + 16 i reads what lane r reads),
   //    row r of W3
-  const int nparts = mlp_nparts(a.Rp);
+  const int nparts = mlp_nparts(Rp);
   const int rl = (lane & 15) < R ? (lane & 15) : R - 1;
   float pq[NP], pk[NP];
+  // FUSED: device-scope loads, the entries may come from another XCD in this very launch
+  auto request_parts = [&]() {
 #pragma unroll
-  for (int p = 0; p < NP; ++p) {
-    const int pc = p < nparts ? p : nparts - 1;
-    pq[p] = a.mlp_parts[((size_t)pc * a.U + u) * 16 + rl];
-    pk[p] = a.mlp_parts[((size_t)(nparts + pc) * a.U + u) * 16 + rl];
-  }
+    for (int p = 0; p < NP; ++p) {
+      const int pc = p < nparts ? p : nparts - 1;
+      const float *eq = a.mlp_parts + ((size_t)pc * a.U + u) * 16 + rl;
+      const float *ek = a.mlp_parts + ((size_t)(nparts + pc) * a.U + u) * 16 + rl;
+      if constexpr (FUSED) {
+        pq[p] = __hip_atomic_load(eq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        pk[p] = __hip_atomic_load(ek, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      } else {
+        pq[p] = *eq;
+        pk[p] = *ek;
+      }
+    }
+  };
+  if constexpr (!FUSED) request_parts();
   __half w3[RM];
 #pragma unroll
   for (int j = 0; j < RM; ++j)
@@ -149,10 +189,8 @@ __global__ __launch_bounds__(kWpuUnits * kWave) void wpu_step_kernel(void *k_cac
   // ---- phase 1: scores as the key rows arrive; the feature maps after the first pass ------------
   double f_lane = 0.0;                   // phi(q), lane r < R
   float npsi_lane = 0.f;                 // psi(k) of this step's key, lane r < R
-  {
-    const double inv_sqrt_d = 1.0 / sqrt((double)D);      // folded at compile time
-    int base = 0;
-    do {                                                   // nitp >= DEPTH
+  const double inv_sqrt_d = 1.0 / sqrt((double)D);        // folded at compile time
+  auto key_pass = [&](int base) {
 #pragma unroll
       for (int j = 0; j < DEPTH; ++j) {
         const int s = base + j;
@@ -161,57 +199,86 @@ __global__ __launch_bounds__(kWpuUnits * kWave) void wpu_step_kernel(void *k_cac
           Vec kv;
           __builtin_memcpy(&kv.raw, &buf[j], 16);
           if (r == m) kv = knv;                           // the appended key
+          // a product of two halves is exact in fp32 (22 bits), so fp32 multiply, widen, fp64 add
+          // gives the bits of an fp64 multiply-add with two conversions fewer per element
           double part = 0.0;
 #pragma unroll
-          for (int i = 0; i < EPL; ++i)             // q is converted again every time: registers are dearer
-            part = fma((double)Store<T>::get(qv, i), (double)Store<T>::get(kv, i), part);
+          for (int i = 0; i < EPL; ++i) part += (double)(Store<T>::get(qv, i) * Store<T>::get(kv, i));
           part = row_sum<LPR>(part);
           if (lr == 0 && r < rows) s_sc[r] = part * inv_sqrt_d;
         }
         buf[j] = issue(s + DEPTH);
         __builtin_amdgcn_sched_barrier(0);
       }
-      if (base == 0) {
+    };
+    // Both feature maps from their layer-2 sums, and the entries handed back empty.
+    auto finish_maps = [&]() {
+      double sq = 0.0, sk = 0.0;
+#pragma unroll
+      for (int p = 0; p < NP; ++p) {
+        if (p < nparts) {
+          sq += (double)pq[p];
+          sk += (double)pk[p];
+        }
+      }
+      for (int p = NP; p < nparts; ++p) {                  // hidden widths above 512 (never FUSED)
+        sq += (double)a.mlp_parts[((size_t)p * a.U + u) * 16 + rl];
+        sk += (double)a.mlp_parts[((size_t)(nparts + p) * a.U + u) * 16 + rl];
+      }
+      f_lane = lane < R ? fabs(gelu_poly_f64(sq)) : 0.0;   // last activation of Eq. 1
+      const double h2 = gelu_poly_f64(sk);                 // lane r < R; Eq. 2: |W3 gelu(.)|
+      double acc3 = 0.0;
+#pragma unroll
+      for (int j = 0; j < RM; ++j)
+        if (j < R) acc3 = fma(readlane_v(h2, j), (double)__half2float(w3[j]), acc3);
+      npsi_lane = (float)fabs(acc3);
+      if constexpr (!SPLIT) {
+        // lane = (map * nparts + part) * 4 + quarter of the part's 16 entries
+        for (int e = lane; e < 2 * nparts * 4; e += kWave) {
+          const u4v empty = {kMlpEmpty, kMlpEmpty, kMlpEmpty, kMlpEmpty};
+          __builtin_nontemporal_store(empty, reinterpret_cast<u4v *>(a.mlp_out + ((size_t)(e >> 2) * a.U + u) * 16) + (e & 3));
+        }
+      }
+    };
+    if constexpr (FUSED) {
+      // The entries are requested before the last pass of the key stream and first looked at after
+      // the sparse part of phase 2: that hides their way from memory.  (Asking a pass earlier
+      // still keeps their sixteen registers live through two passes and makes the kernel spill.)
+      int base = 0;
+      for (; base + DEPTH < nitp; base += DEPTH) key_pass(base);
+      request_parts();
+      key_pass(base);
+    } else {
+      int base = 0;
+      do {                                                 // nitp >= DEPTH
+        key_pass(base);
         // The parts have been back for a while (they were requested before the loads this pass
         // re-issued): finish both feature maps here, where nothing is waiting for anything.
-        double sq = 0.0, sk = 0.0;
-#pragma unroll
-        for (int p = 0; p < NP; ++p) {
-          if (p < nparts) {
-            sq += (double)pq[p];
-            sk += (double)pk[p];
-          }
-        }
-        for (int p = NP; p < nparts; ++p) {                  // hidden widths above 512
-          sq += (double)a.mlp_parts[((size_t)p * a.U + u) * 16 + rl];
-          sk += (double)a.mlp_parts[((size_t)(nparts + p) * a.U + u) * 16 + rl];
-        }
-        f_lane = lane < R ? fabs(gelu_poly_f64(sq)) : 0.0;   // last activation of Eq. 1
-        const double h2 = gelu_poly_f64(sk);                 // lane r < R; Eq. 2: |W3 gelu(.)|
-        double acc3 = 0.0;
-#pragma unroll
-        for (int j = 0; j < RM; ++j)
-          if (j < R) acc3 = fma(readlane_v(h2, j), (double)__half2float(w3[j]), acc3);
-        npsi_lane = (float)fabs(acc3);
-      }
-    } while ((base += DEPTH) < nitp);
-  }
+        if (base == 0) finish_maps();
+      } while ((base += DEPTH) < nitp);
+    }
 
   // ---- requests behind the keys: what the value stream and the output want --------------------------
-  const Vec vnv = load_vec<T>(vn + lr * EPL);
   // This lane's share of H and of the pending value row, wanted after the value stream: four
   // consecutive columns (those the reduce-scatter of phase 3 leaves it with) of every NHB-th
   // row, so that one 16-byte load per lane covers NHB whole rows of H per instruction.
+  // (FUSED: requested inside phase 2, once the feature-map entries have given their registers back.)
   constexpr int NHB = RPI / 2, HR = RM / NHB;
   const int col0 = lr * EPL + ((lane & LPR) ? 4 : 0);
   const int hb = lane / (2 * LPR);                           // which rows: r = NHB * i + hb
+  Vec vnv;
   float4 hreg[HR];
+  uint2 pend_v_h;
+  auto request_tail = [&]() {
+    vnv = load_vec<T>(vn + lr * EPL);
 #pragma unroll
-  for (int i = 0; i < HR; ++i) {
-    const int r = NHB * i + hb;
-    hreg[i] = *reinterpret_cast<const float4 *>(a.H + ((size_t)u * R + (r < R ? r : R - 1)) * D + col0);
-  }
-  const uint2 pend_v_h = *reinterpret_cast<const uint2 *>(reinterpret_cast<const T *>(a.pend_v) + (size_t)u * D + col0);
+    for (int i = 0; i < HR; ++i) {
+      const int r = NHB * i + hb;
+      hreg[i] = *reinterpret_cast<const float4 *>(a.H + ((size_t)u * R + (r < R ? r : R - 1)) * D + col0);
+    }
+    pend_v_h = *reinterpret_cast<const uint2 *>(reinterpret_cast<const T *>(a.pend_v) + (size_t)u * D + col0);
+  };
+  if constexpr (!FUSED) request_tail();
   if constexpr (SPLIT) {
     // Every wave works out phase 2 for itself from the shared scores; only the lead wave
     // stores.  Its stores must not overtake another wave's loads of the same state: have
@@ -251,6 +318,22 @@ __global__ __launch_bounds__(kWpuUnits * kWave) void wpu_step_kernel(void *k_cac
         S += sc[i];
       }
       S = wave_allreduce(S, OpAdd{});                       // sparse part of the denominator, shifted
+      if constexpr (FUSED) {
+        // the feature-map entries, requested during the key stream: all there?
+        auto have_all = [&]() {
+          bool ok = true;
+#pragma unroll
+          for (int p = 0; p < NP; ++p)
+            ok = ok && __float_as_uint(pq[p]) != kMlpEmpty && __float_as_uint(pk[p]) != kMlpEmpty;
+          return __all(ok) != 0;
+        };
+        for (int spin = 0; !have_all() && spin < kWpuSpinLimit; ++spin) {
+          __builtin_amdgcn_s_sleep(32);
+          request_parts();
+        }
+        finish_maps();
+        request_tail();
+      }
       // pending fold of z (Eq. 5), then phi(q) z^T
       if (lane >= R) z_lane = 0.0;
       if (!pend.fold) psie_lane = 0.f;
@@ -465,24 +548,63 @@ bool wpu_supported(int dtype, int D, int C, int Rp, int R)
          C + 1 <= kWpuMaxRows;
 }
 
-template <int D, int RM, bool SPLIT>
-static hipError_t launch_step_wpu_s(const StepArgs &a, int upb, hipStream_t st)
+__global__ void fill_empty_kernel(unsigned *p, size_t count)
 {
-  constexpr int kDepth = 7;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += (size_t)gridDim.x * blockDim.x)
+    p[i] = kMlpEmpty;
+}
+
+hipError_t launch_fill_empty(float *parts, size_t count, hipStream_t st)
+{
+  if (count == 0) return hipSuccess;
+  const unsigned grid = (unsigned)((count + 255) / 256 < 2048 ? (count + 255) / 256 : 2048);
+  fill_empty_kernel<<<grid, 256, 0, st>>>(reinterpret_cast<unsigned *>(parts), count);
+  return hipGetLastError();
+}
+
+static inline int pack_crp(const StepArgs &a) { return a.C | (a.R << 12) | (a.Rp << 19); }
+
+template <int D, int RM, bool SPLIT, bool FUSED>
+static hipError_t launch_step_wpu_s(const StepArgs &a, int upb, hipStream_t st, const MlpPartsArgs *fm)
+{
+  constexpr int kDepth = FUSED ? 6 : 7;
   const int rows_cap = (a.C + 2) & ~1;
   size_t lds = (size_t)(SPLIT ? 1 : upb) * rows_cap * sizeof(double) + (size_t)upb * rows_cap * sizeof(float);
   if (SPLIT) lds += (size_t)upb * D * sizeof(float);
-  const unsigned grid = (unsigned)(a.Hh * (SPLIT ? a.B : (a.B + upb - 1) / upb));
+  const unsigned n_mlp = FUSED ? (unsigned)(a.Hh * 2 * mlp_nparts(a.Rp) * ((a.B + 63) / 64)) : 0u;
+  const unsigned grid = n_mlp + (unsigned)(a.Hh * (SPLIT ? a.B : (a.B + upb - 1) / upb));
   const unsigned block = (unsigned)(upb * kWave);
   const int rows = a.C + 1;
-  if (rows <= 2 * kWave)
-    wpu_step_kernel<D, 2, RM, kDepth, SPLIT><<<grid, block, lds, st>>>(a.k_cache, a.q, a.k, a.C, a.Hh, a.B, a);
-  else if (rows <= 4 * kWave)
-    wpu_step_kernel<D, 4, RM, kDepth, SPLIT><<<grid, block, lds, st>>>(a.k_cache, a.q, a.k, a.C, a.Hh, a.B, a);
-  else
-    wpu_step_kernel<D, kWpuMaxRows / kWave, RM, kDepth, SPLIT><<<grid, block, lds, st>>>(a.k_cache, a.q, a.k, a.C, a.Hh,
-                                                                                      a.B, a);
+  const int crp = pack_crp(a);
+  const void *wq1 = fm ? fm->Wq1 : nullptr, *wk1 = fm ? fm->Wk1 : nullptr, *wq2 = fm ? fm->Wq2 : nullptr;
+#define LESSDEC_WPU_LAUNCH(NR2)                                                                                  \
+  wpu_step_kernel<D, NR2, RM, kDepth, SPLIT, FUSED><<<grid, block, lds, st>>>(a.k_cache, a.q, a.k, crp, a.Hh, a.B, \
+                                                                              (int)n_mlp, wq1, wk1, wq2, a)
+  if (rows <= 2 * kWave) LESSDEC_WPU_LAUNCH(2);
+  else if (rows <= 4 * kWave) LESSDEC_WPU_LAUNCH(4);
+  else LESSDEC_WPU_LAUNCH(kWpuMaxRows / kWave);
+#undef LESSDEC_WPU_LAUNCH
   return hipGetLastError();
+}
+
+// Number of waves a unit's rows are split over (1: a wave per unit).
+static int wpu_split_waves(long units, int D, int C)
+{
+  const int nl = (C + 1 + (kWave / (D / 8)) - 1) / (kWave / (D / 8));   // loads per stream
+  int nw = 1;
+  while (nw < kWpuUnits && units * nw * 2 <= kWpuSplitWaves && nl >= 8 * nw) nw *= 2;
+  return nw;
+}
+
+// One launch for the whole step: a wave per unit (no split), enough units that the feature-map
+// jobs and the attention waves fill the chip together, parts that fit the registers kept for
+// them, and a shape whose kernel stays within the 128 registers that four waves per SIMD leave
+// each (at most 128 rows and rank 8: the larger forms spill).
+bool wpu_fusable(int B, int Hh, int D, int C, int Rp, int R)
+{
+  const long units = (long)B * Hh;
+  return wpu_split_waves(units, D, C) == 1 && units >= 1024 && mlp_nparts(Rp) <= 8 && C + 1 <= 2 * kWave && R <= 8 &&
+         Rp < 4096 && D == 128;
 }
 
 // Launch shape.  With thousands of units a wave per unit saturates the memory system; with
@@ -492,22 +614,25 @@ static hipError_t launch_step_wpu_s(const StepArgs &a, int upb, hipStream_t st)
 // each, 2048 units lose).  Without a split, 8 units share a block when that still gives
 // every compute unit a block, fewer for small batches.
 template <int D, int RM>
-static hipError_t launch_step_wpu_t(const StepArgs &a, hipStream_t st)
+static hipError_t launch_step_wpu_t(const StepArgs &a, hipStream_t st, const MlpPartsArgs *fm)
 {
   const long units = (long)a.B * a.Hh;
-  const int nl = (a.C + 1 + (kWave / (D / 8)) - 1) / (kWave / (D / 8));   // loads per stream
-  int nw = 1;
-  while (nw < kWpuUnits && units * nw * 2 <= kWpuSplitWaves && nl >= 8 * nw) nw *= 2;
-  if (nw > 1) return launch_step_wpu_s<D, RM, true>(a, nw, st);
+  if (fm) {
+    if constexpr (D == 128) return launch_step_wpu_s<D, RM, false, true>(a, kWpuFusedUnits, st, fm);
+    else return hipErrorInvalidValue;
+  }
+  const int nw = wpu_split_waves(units, D, a.C);
+  if (nw > 1) return launch_step_wpu_s<D, RM, true, false>(a, nw, st, nullptr);
   int upb = kWpuUnits;
   while (upb > 1 && a.Hh * ((a.B + upb - 1) / upb) < 256) upb >>= 1;
-  return launch_step_wpu_s<D, RM, false>(a, upb, st);
+  return launch_step_wpu_s<D, RM, false, false>(a, upb, st, nullptr);
 }
 
-hipError_t launch_step_wpu(const StepArgs &a, int D, hipStream_t st)
+hipError_t launch_step_wpu(const StepArgs &a, int D, hipStream_t st, const MlpPartsArgs *fm)
 {
-  if (D == 64) return launch_step_wpu_t<64, 16>(a, st);
-  return a.R <= 8 ? launch_step_wpu_t<128, 8>(a, st) : launch_step_wpu_t<128, 16>(a, st);
+  if (fm && !wpu_fusable(a.B, a.Hh, D, a.C, a.Rp, a.R)) return hipErrorInvalidValue;
+  if (D == 64) return launch_step_wpu_t<64, 16>(a, st, fm);
+  return a.R <= 8 ? launch_step_wpu_t<128, 8>(a, st, fm) : launch_step_wpu_t<128, 16>(a, st, fm);
 }
 
 }  // namespace lessdec

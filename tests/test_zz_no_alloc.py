@@ -49,7 +49,7 @@ def test_static_scratch_step_matches_step_twice_in_a_row(kind):
     kw = {"multi-head": dict(q_per_kv=4), "general": dict(rank=20), "streaming": {}}[kind]
     d = dict(head_dim=128, n_heavy=6, n_recent=6, rank=8, hidden=128, dtype="f16", prompt=40)
     d.update(kw)
-    big = BASE.scaled(name=f"static-{kind}-big", batch=48, heads=16, steps=12, **d)
+    big = BASE.scaled(name=f"static-{kind}-big", batch=64, heads=16, steps=12, **d)
     little = BASE.scaled(name=f"static-{kind}-small", batch=2, heads=3, steps=12, **d)
     _run_both(big, 12)
     _run_both(little, 12)
