@@ -50,10 +50,10 @@ bool shape_ok(const lessdec_desc *d, Shape *s)
 }
 
 // Workspace: [ f_phi U*R f64 | f_psi U*R f32 | mlp_parts 2*ceil(R'/64)*U*16 f32 |
-//              prefill: 4 staged rows U*D (4 bytes each) | lse U*G*P f64, colsum U*P f64 | approx U*P f32, list U*P i32, count U i32 | slot_of U*P i32 | psi_all U*P*R f32 | phi_all U*G*P*R f32, psimax U*R f32, hpre U*(P/64+1)*R*D f32, zpre U*(P/64+1)*R f32 (masked prompt only) ],
+//              prefill: 4 staged rows U*D (4 bytes each) | lse U*G*P f64, colsum U*P f64 | approx U*P f32, list U*P i32, count U i32, bound U f32 | slot_of U*P i32 | psi_all U*P*R f32 | phi_all U*G*P*R f32, psimax U*R f32, hpre U*(P/64+1)*R*D f32, zpre U*(P/64+1)*R f32 (masked prompt only) ],
 // every part 256-byte aligned.
 struct Workspace {
-  size_t off_fphi, off_fpsi, off_parts, off_gqa, off_stage, off_lse, off_colsum, off_approx, off_list, off_count, off_slot,
+  size_t off_fphi, off_fpsi, off_parts, off_gqa, off_stage, off_lse, off_colsum, off_approx, off_list, off_count, off_bound, off_slot,
       off_psiall, off_phiall, off_psimax, off_hpre, off_zpre, total;
 };
 
@@ -71,6 +71,7 @@ Workspace carve(const Shape &s, size_t P, unsigned flags)
   w.off_approx = o; o = align_up(o + s.U * P * sizeof(float), 256);
   w.off_list = o; o = align_up(o + s.U * P * sizeof(int32_t), 256);
   w.off_count = o; o = align_up(o + (P ? s.U * sizeof(int32_t) : 0), 256);
+  w.off_bound = o; o = align_up(o + (P ? s.U * sizeof(float) : 0), 256);
   w.off_slot = o; o = align_up(o + s.U * P * sizeof(int32_t), 256);
   w.off_psiall = o; o = align_up(o + s.U * P * s.R * sizeof(float), 256);
   // phi of every prompt query: only for Lambda-masking taken through the prompt token by token
@@ -369,6 +370,7 @@ int lessdec_prefill(const lessdec_desc *desc, const void *Q, const void *K, cons
   a.approx = reinterpret_cast<float *>(ws + w.off_approx);
   a.list = reinterpret_cast<int32_t *>(ws + w.off_list);
   a.count = reinterpret_cast<int32_t *>(ws + w.off_count);
+  a.bound = reinterpret_cast<float *>(ws + w.off_bound);
   a.psi_all = reinterpret_cast<float *>(ws + w.off_psiall);
   a.phi_all = reinterpret_cast<float *>(ws + w.off_phiall);
   a.psimax = reinterpret_cast<float *>(ws + w.off_psimax);

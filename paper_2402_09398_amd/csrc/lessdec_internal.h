@@ -107,6 +107,7 @@ struct PrefillArgs {
   float *approx;            // [U,P] cheap column sums (selection band only)
   int32_t *list;            // [U,P] tokens whose exact column sum is wanted; later keep flags
   int32_t *count;           // [U] length of each unit's list
+  float *bound;             // [U] largest score magnitude the unit's prompt can produce (selection band)
   float *psi_all;           // [U,P,R]
   float *phi_all = nullptr; // [U*G,P,R], only for the masked form
   float *psimax = nullptr;  // [U,R] feature-wise maximum of psi over the prompt, only for the masked form

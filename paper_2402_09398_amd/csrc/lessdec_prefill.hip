@@ -827,31 +827,96 @@ __global__ __launch_bounds__(64 * kPrefillWaves) void prefill_colapprox_kernel(
 }
 
 // -------------------------------------------------------------------------------------
-// Which tokens can matter, from the cheap column sums.  With every cheap value within a
-// relative kBand of the exact one (worst-case error of the fp32 path is about a quarter of
-// that), a token is surely a heavy hitter if fewer than Nh others could possibly be larger,
-// surely discarded if at least Nh others are surely larger, and in doubt otherwise.
+// The largest score magnitude a unit's prompt can produce: max_i |q_i| max_j |k_j| / sqrt(D)
+// over its tokens and query heads (>= |q_i . k_j| / sqrt(D) for every pair).  It bounds the rounding
+// error of the cheap column sums (below).  One block per unit, a row per D / 8 lanes.
+// -------------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(256) void prefill_scorebound_kernel(const __half *__restrict__ Q,
+                                                                 const __half *__restrict__ K, int P, int G,
+                                                                 float *__restrict__ bound)
+{
+  constexpr int LPR = D / 8, RPB = 256 / LPR;
+  __shared__ float s_max[2][256 / kWave];
+  const size_t u = blockIdx.x;
+  const int tid = threadIdx.x, lr = tid % LPR, rb = tid / LPR;
+  float mx[2] = {0.f, 0.f};                               // largest squared norm: queries, keys
+  for (int which = 0; which < 2; ++which) {
+    const __half *base = which ? K + u * (size_t)P * D : Q + u * (size_t)G * P * D;
+    const long rows = which ? P : (long)G * P;
+    for (long r = rb; r < rows; r += RPB) {
+      const uint4 raw = *reinterpret_cast<const uint4 *>(base + r * D + lr * 8);
+      const __half2 *h2 = reinterpret_cast<const __half2 *>(&raw);
+      float ss = 0.f;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float2 f = __half22float2(h2[i]);
+        ss = fmaf(f.x, f.x, fmaf(f.y, f.y, ss));
+      }
+#pragma unroll
+      for (int o = LPR / 2; o > 0; o >>= 1) ss += __shfl_xor(ss, o);
+      mx[which] = fmaxf(mx[which], ss);
+    }
+  }
+#pragma unroll
+  for (int which = 0; which < 2; ++which) {
+#pragma unroll
+    for (int o = kWave / 2; o > 0; o >>= 1) mx[which] = fmaxf(mx[which], __shfl_xor(mx[which], o));
+    if (tid % kWave == 0) s_max[which][tid / kWave] = mx[which];
+  }
+  __syncthreads();
+  if (tid == 0) {
+    float mq = 0.f, mk = 0.f;
+    for (int w = 0; w < 256 / kWave; ++w) {
+      mq = fmaxf(mq, s_max[0][w]);
+      mk = fmaxf(mk, s_max[1][w]);
+    }
+    // rounded up a little: the squared norms above carry fp32 rounding themselves
+    bound[u] = sqrtf(mq) * sqrtf(mk) * (float)(1.0 / sqrt((double)D)) * 1.001f;
+  }
+}
+
+// -------------------------------------------------------------------------------------
+// Which tokens can matter, from the cheap column sums.  A cheap sum a~ and the exact one a
+// satisfy |a~ - a| <= eps a + tau with
+//   eps = 2^-24 ((D + 6) M + 3 ln P + G P / 16 + 6),   M = the unit's score bound (above):
+// D M for the fp32 accumulation of the D exact fp16 products of a score, 5 M + 3 ln P for the
+// rounded 1 / sqrt(D), the row's log-sum rounded to fp32 (|lse| <= M + ln P), the fused
+// multiply-add and the scaling inside the fast exponential (|s - lse| <= 2 M + ln P each), 2
+// for the exponential itself, G P / 16 + 4 for a lane's running sum and the four lane exchanges;
+// tau = 2^-100 covers terms flushed to zero.  The band used is twice that, and at least kBand
+// (at the benchmark shapes eps is a tenth of kBand; the band only grows for prompts with far
+// larger queries and keys).  With every cheap value within the band of the exact one, a token
+// is surely a heavy hitter if fewer than Nh others could possibly be larger, surely discarded
+// if at least Nh others are surely larger, and in doubt otherwise.
 // flag[j] = 1 kept for sure (heavy or recent), 0 discarded for sure, 2 in doubt.
 // One thread per token.   grid = U * ceil(P / 256), block = 256.
 // -------------------------------------------------------------------------------------
 constexpr float kBand = 1.0f / 256.0f;
-__global__ __launch_bounds__(256) void prefill_band_kernel(const float *__restrict__ approx, int P, int Nh,
-                                                           int Nr, int32_t *__restrict__ flag)
+__host__ __device__ inline float colapprox_error_bound(float M, int D, int P, int G)
+{
+  return 5.9604645e-08f * ((float)(D + 6) * M + 3.f * logf((float)P) + (float)G * (float)P / 16.f + 6.f);
+}
+__global__ __launch_bounds__(256) void prefill_band_kernel(const float *__restrict__ approx,
+                                                           const float *__restrict__ bound, int D, int G, int P,
+                                                           int Nh, int Nr, int32_t *__restrict__ flag)
 {
   const int nb = (P + 255) / 256;
   const size_t u = blockIdx.x / nb;
   const int j = (int)(blockIdx.x % nb) * 256 + (int)threadIdx.x;
   if (j >= P) return;
   const float *a = approx + u * (size_t)P;
+  const float band = fmaxf(kBand, 2.f * colapprox_error_bound(bound[u], D, P, G));
+  const float tau = 7.8886091e-31f;                      // 2^-100
   const int ncand = P - Nr;
   int f = 1;                                    // recent
   if (j < ncand) {
-    const float lo = a[j] * (1.f - kBand), hi = a[j] * (1.f + kBand);
+    const float lo = a[j] * (1.f - band) - tau, hi = a[j] * (1.f + band) + tau;
     int maybe_larger = 0, surely_larger = 0;
     for (int i = 0; i < ncand; ++i) {
       const float b = a[i];
-      maybe_larger += (b * (1.f + kBand) >= lo) ? 1 : 0;   // counts j itself
-      surely_larger += (b * (1.f - kBand) > hi) ? 1 : 0;
+      maybe_larger += (b * (1.f + band) + tau >= lo) ? 1 : 0;   // counts j itself
+      surely_larger += (b * (1.f - band) - tau > hi) ? 1 : 0;
     }
     f = (maybe_larger - 1 < Nh) ? 1 : (surely_larger >= Nh ? 0 : 2);
   }
@@ -1293,8 +1358,10 @@ static hipError_t launch_prefill_t(const PrefillArgs &a, hipStream_t st)
         prefill_colapprox_kernel<D><<<agrid, 64 * kPrefillWaves, 0, st>>>((const __half *)a.Q, (const __half *)a.K, U,
                                                                          P, a.lse, G, a.approx);
         if ((e = hipGetLastError()) != hipSuccess) return e;
+        prefill_scorebound_kernel<D><<<U, 256, 0, st>>>((const __half *)a.Q, (const __half *)a.K, P, G, a.bound);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
       }
-      prefill_band_kernel<<<rank_grid, 256, 0, st>>>(a.approx, P, d->n_heavy, d->n_recent, a.slot_of);
+      prefill_band_kernel<<<rank_grid, 256, 0, st>>>(a.approx, a.bound, D, G, P, d->n_heavy, d->n_recent, a.slot_of);
     }
     if ((e = hipGetLastError()) != hipSuccess) return e;
     prefill_compact_kernel<<<U, 256, 0, st>>>(a.slot_of, P, a.list, a.count);
