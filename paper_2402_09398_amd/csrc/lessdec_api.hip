@@ -98,7 +98,7 @@ int check_desc(const lessdec_desc *d, Shape *s, size_t P)
       !aligned(d->pend_psi, 4))
     return LESSDEC_EINVAL;
   if (!aligned(d->Wq1, 16) || !aligned(d->Wq2, 16) || !aligned(d->Wk1, 16) ||
-      !aligned(d->Wk2, 16) || !aligned(d->Wk3, 4))
+      !aligned(d->Wk2, 16) || !aligned(d->Wk3, d->dtype == LESSDEC_DTYPE_F16 ? 16 : 4))
     return LESSDEC_EINVAL;
   if (!d->workspace || !aligned(d->workspace, 256)) return LESSDEC_EWORKSPACE;
   if (d->workspace_bytes < carve(*s, P, d->flags).total) return LESSDEC_EWORKSPACE;

@@ -152,9 +152,16 @@ __global__ __launch_bounds__((FUSED ? kWpuFusedUnits : kWpuUnits) * kWave, FUSED
   };
   if constexpr (!FUSED) request_parts();
   __half w3[RM];
+  {
+    const __half *w3row = reinterpret_cast<const __half *>(a.Wk3) + ((size_t)h * R + rl) * R;
+    if (RM == 8 && R == 8) {                                 // a row is one aligned 16-byte load
+      const uint4 raw = *reinterpret_cast<const uint4 *>(w3row);
+      __builtin_memcpy(w3, &raw, 16);
+    } else {
 #pragma unroll
-  for (int j = 0; j < RM; ++j)
-    w3[j] = reinterpret_cast<const __half *>(a.Wk3)[((size_t)h * R + rl) * R + (j < R ? j : R - 1)];
+      for (int j = 0; j < RM; ++j) w3[j] = w3row[j < R ? j : R - 1];
+    }
+  }
   // 3. unit state (wanted from phase 2 on)
   const int n = sane_n_seen(a.n_seen[u]);
   const Pending pend = decode_pending(a.pend_slot[u], C);

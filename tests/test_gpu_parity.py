@@ -108,6 +108,12 @@ EDGE = [
     small("one-launch-filling", batch=70, heads=16, prompt=0, steps=30),
     small("one-launch-rank-16-hidden-512", batch=64, heads=16, rank=16, hidden=512, prompt=40, steps=12),
     small("one-launch-hidden-96", batch=33, heads=32, hidden=96, rank=5, prompt=40, steps=12),
+    # five heads: a head's feature-map jobs and its attention waves land on different XCDs, so the
+    # entries cross between L2 caches that are not coherent with each other
+    small("one-launch-5-heads", batch=230, heads=5, prompt=30, steps=16),
+    # four times more workgroups than the chip holds at once: the attention waves of the later
+    # batch rows start only when earlier ones have finished, the jobs still come first
+    small("one-launch-8192-units", batch=256, heads=32, prompt=20, steps=10, hidden=64),
     wl.WORKLOADS[4].scaled(name="heavy-tailed-keys", batch=1, heads=4, prompt=256, steps=64,
                            n_heavy=10, n_recent=10, hidden=128),
     # near-uniform attention in fp16 storage: column sums of the prompt lie close together, so
