@@ -156,9 +156,11 @@ int lessdec_state_sync(const lessdec_desc *desc, void *hip_stream);
  * With q_per_kv = G > 1: Q and out are [B,Hh,G,P,D], and a token's score is the column sum
  * of all G causal attention matrices of its unit.
  * With LESSDEC_FLAG_PROMPT_STEPWISE the call is lessdec_state_reset followed by one
- * lessdec_step per prompt token t with rows Q[.,.,t,.], K[.,.,t,.], V[.,.,t,.] (2 P launches
- * plus row staging; not the fast way through a prompt): out[.,.,t,.] is then Eq. 3's output
- * at token t, and the state afterwards is the state after P steps (a fold may be pending).
+ * lessdec_step per prompt token t with rows Q[.,.,t,.], K[.,.,t,.], V[.,.,t,.] (bit for bit: on
+ * the streaming path the steps read and write the rows where they lie in the prompt arrays, one
+ * launch per token on large shapes; elsewhere rows are staged and a token takes three launches):
+ * out[.,.,t,.] is then Eq. 3's output at token t, and the state afterwards is the state after
+ * P steps (a fold may be pending).
  * With LESSDEC_FLAG_LAMBDA as well and P > n_heavy + n_recent the same results (outputs, slot
  * order and state, to rounding) are computed for all prompt tokens at once: under that policy
  * the cache each token meets is known beforehand (Sec. 3.2 builds the same masked matrix for

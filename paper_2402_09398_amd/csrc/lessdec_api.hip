@@ -113,12 +113,19 @@ StepArgs state_args(const lessdec_desc *desc, const Shape &s)
   a.k_cache = desc->k_cache; a.v_cache = desc->v_cache; a.acc = desc->acc; a.pos = desc->pos;
   a.psi = desc->psi; a.H = desc->H; a.z = desc->z; a.n_seen = desc->n_seen;
   a.pend_slot = desc->pend_slot; a.pend_v = desc->pend_v; a.pend_psi = desc->pend_psi;
-  a.q = a.k = a.v = nullptr; a.out = nullptr; a.evicted_pos = nullptr;
+  a.q = a.k = a.v = nullptr; a.out = nullptr; a.evicted_pos = nullptr; a.x_stride = desc->head_dim;
   a.U = (int)s.U; a.Hh = desc->heads; a.B = desc->batch;
   a.f_phi = nullptr; a.f_phi32 = nullptr; a.f_psi = nullptr; a.mlp_parts = nullptr; a.mlp_out = nullptr;
   a.gqa_parts = nullptr;
   a.Wk3 = desc->Wk3; a.Wk2 = desc->Wk2;
   return a;
+}
+
+// The streaming decode path (one wave per unit) serves this descriptor.
+bool use_wpu(const lessdec_desc *desc, const Shape &s)
+{
+  return s.G == 1 && desc->batch < 65536 && desc->heads < 65536 &&
+         wpu_supported(desc->dtype, desc->head_dim, (int)s.C, desc->hidden, desc->rank);
 }
 
 MlpPartsArgs parts_args(const lessdec_desc *desc, const void *q, const void *k, float *out)
@@ -135,7 +142,7 @@ MlpPartsArgs parts_args(const lessdec_desc *desc, const void *q, const void *k, 
 // The per-step exchange array of the streaming path starts out empty (see wpu_step_kernel).
 hipError_t empty_exchange(const lessdec_desc *desc, const Shape &s, hipStream_t st)
 {
-  if (s.G != 1 || !wpu_supported(desc->dtype, desc->head_dim, (int)s.C, desc->hidden, desc->rank)) return hipSuccess;
+  if (!use_wpu(desc, s)) return hipSuccess;
   const Workspace w = carve(s, 0, desc->flags);
   return launch_fill_empty(reinterpret_cast<float *>(static_cast<char *>(desc->workspace) + w.off_parts),
                            2 * (size_t)mlp_nparts((int)s.Rp) * s.U * 16, st);
@@ -190,7 +197,13 @@ int lessdec_state_sync(const lessdec_desc *desc, void *hip_stream)
              ? LESSDEC_OK : LESSDEC_EHIP;
 }
 
-int lessdec_step_features(const lessdec_desc *desc, const void *q, const void *k, void *hip_stream)
+}  // extern "C"
+
+namespace {
+
+// x_stride: elements between the rows of consecutive units in q, k, v, out (head_dim for the
+// packed [B,Hh,D] rows of the public calls; the streaming path alone takes other values).
+int step_features_impl(const lessdec_desc *desc, const void *q, const void *k, int x_stride, void *hip_stream)
 {
   Shape s;
   int rc = check_desc(desc, &s, 0);
@@ -199,11 +212,13 @@ int lessdec_step_features(const lessdec_desc *desc, const void *q, const void *k
   hipStream_t st = (hipStream_t)hip_stream;
   const Workspace w = carve(s, 0, desc->flags);
   char *ws = static_cast<char *>(desc->workspace);
-  if (s.G == 1 && wpu_supported(desc->dtype, desc->head_dim, (int)s.C, desc->hidden, desc->rank)) {
+  if (use_wpu(desc, s)) {
     // matrix-core feature maps up to the layer-2 sums
-    const MlpPartsArgs fm = parts_args(desc, q, k, reinterpret_cast<float *>(ws + w.off_parts));
+    MlpPartsArgs fm = parts_args(desc, q, k, reinterpret_cast<float *>(ws + w.off_parts));
+    fm.x_stride = x_stride;
     return launch_mlp_parts(fm, st) == hipSuccess ? LESSDEC_OK : LESSDEC_EHIP;
   }
+  if (x_stride != desc->head_dim) return LESSDEC_EINVAL;
   if (s.G > 1 && mlp_mfma_supported(desc->dtype, desc->head_dim, desc->hidden, desc->rank)) {
     // several query heads per unit: both maps complete on the matrix cores, fp32 results
     MlpArgs fm;
@@ -231,8 +246,8 @@ int lessdec_step_features(const lessdec_desc *desc, const void *q, const void *k
   return LESSDEC_OK;
 }
 
-int lessdec_step_attend(const lessdec_desc *desc, const void *q, const void *k, const void *v, void *out,
-                        int32_t *evicted_pos, void *hip_stream)
+int step_attend_impl(const lessdec_desc *desc, const void *q, const void *k, const void *v, void *out,
+                     int32_t *evicted_pos, int x_stride, void *hip_stream)
 {
   Shape s;
   int rc = check_desc(desc, &s, 0);
@@ -243,9 +258,10 @@ int lessdec_step_attend(const lessdec_desc *desc, const void *q, const void *k, 
     return LESSDEC_EINVAL;
   hipStream_t st = (hipStream_t)hip_stream;
   StepArgs a = state_args(desc, s);
-  a.q = q; a.k = k; a.v = v; a.out = out; a.evicted_pos = evicted_pos;
+  a.q = q; a.k = k; a.v = v; a.out = out; a.evicted_pos = evicted_pos; a.x_stride = x_stride;
   const Workspace w = carve(s, 0, desc->flags);
   char *ws = static_cast<char *>(desc->workspace);
+  if (x_stride != desc->head_dim && !use_wpu(desc, s)) return LESSDEC_EINVAL;
   if (s.G > 1) {
     if (mlp_mfma_supported(desc->dtype, desc->head_dim, desc->hidden, desc->rank))
       a.f_phi32 = reinterpret_cast<float *>(ws + w.off_fphi);
@@ -255,7 +271,7 @@ int lessdec_step_attend(const lessdec_desc *desc, const void *q, const void *k, 
     a.gqa_parts = reinterpret_cast<double *>(ws + w.off_gqa);
     return launch_step_gqa(a, (int)s.G, desc->dtype, desc->head_dim, st) == hipSuccess ? LESSDEC_OK : LESSDEC_EHIP;
   }
-  if (wpu_supported(desc->dtype, desc->head_dim, (int)s.C, desc->hidden, desc->rank)) {
+  if (use_wpu(desc, s)) {
     a.mlp_parts = a.mlp_out = reinterpret_cast<float *>(ws + w.off_parts);     // one wave per unit
     return launch_step_wpu(a, desc->head_dim, st) == hipSuccess ? LESSDEC_OK : LESSDEC_EHIP;
   }
@@ -264,8 +280,8 @@ int lessdec_step_attend(const lessdec_desc *desc, const void *q, const void *k, 
   return launch_step(a, desc->dtype, desc->head_dim, st) == hipSuccess ? LESSDEC_OK : LESSDEC_EHIP;
 }
 
-int lessdec_step(const lessdec_desc *desc, const void *q, const void *k, const void *v, void *out,
-                 int32_t *evicted_pos, void *hip_stream)
+int step_impl(const lessdec_desc *desc, const void *q, const void *k, const void *v, void *out,
+              int32_t *evicted_pos, int x_stride, void *hip_stream)
 {
   // argument checks of both halves first, so that nothing is launched on an error
   Shape s;
@@ -275,20 +291,41 @@ int lessdec_step(const lessdec_desc *desc, const void *q, const void *k, const v
   if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(out, 16) ||
       !aligned(evicted_pos, 4))
     return LESSDEC_EINVAL;
-  if (s.G == 1 && wpu_supported(desc->dtype, desc->head_dim, (int)s.C, desc->hidden, desc->rank) &&
-      wpu_fusable(desc->batch, desc->heads, desc->head_dim, (int)s.C, desc->hidden, desc->rank)) {
+  if (use_wpu(desc, s) && wpu_fusable(desc->batch, desc->heads, desc->head_dim, (int)s.C, desc->hidden, desc->rank)) {
     // feature maps and attention in one launch
     StepArgs a = state_args(desc, s);
-    a.q = q; a.k = k; a.v = v; a.out = out; a.evicted_pos = evicted_pos;
+    a.q = q; a.k = k; a.v = v; a.out = out; a.evicted_pos = evicted_pos; a.x_stride = x_stride;
     const Workspace w = carve(s, 0, desc->flags);
     float *parts = reinterpret_cast<float *>(static_cast<char *>(desc->workspace) + w.off_parts);
     a.mlp_parts = a.mlp_out = parts;
-    const MlpPartsArgs fm = parts_args(desc, q, k, parts);
+    MlpPartsArgs fm = parts_args(desc, q, k, parts);
+    fm.x_stride = x_stride;
     return launch_step_wpu(a, desc->head_dim, (hipStream_t)hip_stream, &fm) == hipSuccess ? LESSDEC_OK : LESSDEC_EHIP;
   }
-  rc = lessdec_step_features(desc, q, k, hip_stream);
+  rc = step_features_impl(desc, q, k, x_stride, hip_stream);
   if (rc) return rc;
-  return lessdec_step_attend(desc, q, k, v, out, evicted_pos, hip_stream);
+  return step_attend_impl(desc, q, k, v, out, evicted_pos, x_stride, hip_stream);
+}
+
+}  // namespace
+
+extern "C" {
+
+int lessdec_step_features(const lessdec_desc *desc, const void *q, const void *k, void *hip_stream)
+{
+  return desc ? step_features_impl(desc, q, k, desc->head_dim, hip_stream) : LESSDEC_EINVAL;
+}
+
+int lessdec_step_attend(const lessdec_desc *desc, const void *q, const void *k, const void *v, void *out,
+                        int32_t *evicted_pos, void *hip_stream)
+{
+  return desc ? step_attend_impl(desc, q, k, v, out, evicted_pos, desc->head_dim, hip_stream) : LESSDEC_EINVAL;
+}
+
+int lessdec_step(const lessdec_desc *desc, const void *q, const void *k, const void *v, void *out,
+                 int32_t *evicted_pos, void *hip_stream)
+{
+  return desc ? step_impl(desc, q, k, v, out, evicted_pos, desc->head_dim, hip_stream) : LESSDEC_EINVAL;
 }
 
 int lessdec_step_launches(const lessdec_desc *desc)
@@ -296,7 +333,7 @@ int lessdec_step_launches(const lessdec_desc *desc)
   Shape s;
   if (!shape_ok(desc, &s)) return 0;
   if (s.G > 1) return gqa_head_blocks((long)s.U, (int)s.G) > 1 ? 3 : 2;   // feature maps, heads, (finishing launch)
-  if (wpu_supported(desc->dtype, desc->head_dim, (int)s.C, desc->hidden, desc->rank))
+  if (use_wpu(desc, s))
     return wpu_fusable(desc->batch, desc->heads, desc->head_dim, (int)s.C, desc->hidden, desc->rank) ? 1 : 2;
   return 3;                                                                 // phi, psi, step
 }
@@ -354,6 +391,19 @@ int lessdec_prefill(const lessdec_desc *desc, const void *Q, const void *K, cons
     r.outs = ws + w.off_stage + 3 * part;
     if (empty_exchange(desc, s, st) != hipSuccess) return LESSDEC_EHIP;
     if (launch_reset(desc, st) != hipSuccess) return LESSDEC_EHIP;
+    if (use_wpu(desc, s) && out && (size_t)P * s.D < ((size_t)1 << 31)) {
+      // the streaming path reads token t's rows where they lie in the prompt arrays and writes its
+      // output row there: one step (one launch on large shapes) per token, nothing staged
+      const size_t e = desc->dtype == LESSDEC_DTYPE_F16 ? 2 : 4;
+      for (int32_t t = 0; t < P; ++t) {
+        const size_t off = (size_t)t * s.D * e;
+        rc = step_impl(desc, static_cast<const char *>(Q) + off, static_cast<const char *>(K) + off,
+                       static_cast<const char *>(V) + off, static_cast<char *>(out) + off, nullptr, (int)(P * s.D),
+                       hip_stream);
+        if (rc) return rc;
+      }
+      return LESSDEC_OK;
+    }
     for (int32_t t = 0; t < P; ++t) {
       if (launch_prompt_rows(r, t, (out && t > 0) ? t - 1 : -1, st) != hipSuccess) return LESSDEC_EHIP;
       if ((rc = lessdec_step_features(desc, r.qs, r.ks, hip_stream)) != LESSDEC_OK) return rc;

@@ -41,6 +41,7 @@ struct MlpPartsArgs {
   const __half *q, *k, *Wq1, *Wq2, *Wk1, *Wk2;
   float *out;
   int B, Hh, D, Rp, R;
+  int x_stride = 0;      // elements from a unit's q / k row to the next unit's (0: D, rows packed)
 };
 __host__ __device__ inline int mlp_nparts(int Rp) { return (Rp + kMlpPartHidden - 1) / kMlpPartHidden; }
 hipError_t launch_mlp_parts(const MlpPartsArgs &a, hipStream_t st);
@@ -64,6 +65,8 @@ struct StepArgs {
   const void *q, *k, *v;
   void *out;
   int32_t *evicted_pos;
+  int x_stride;          // wave-per-unit path: elements from a unit's q / k / v / out row to the next unit's
+                         // (D for packed rows; P D when the rows are token t of [U,P,D] prompt arrays)
   int U, Hh, B;
   // generic path: feature maps of this step's q and k from the launches before it
   const double *f_phi;   // [U,R] ([U,G,R] with several query heads per unit)

@@ -107,13 +107,14 @@ __device__ inline void mlp_load_row(const __half *xr, int g, v8h (&bx)[D / 32])
 // on the compute unit's memory pipeline, which is what slows waves streaming the cache next to
 // it when this job runs inside the attention launch.  Rows are padded by 16 bytes in the LDS so
 // that the 16 lanes of an operand read (same 16-byte column, 16 rows) fall into different banks.
+// x_stride: elements from unit u's row of q / k to unit u + 1's (D when the rows are packed).
 // out[((map * nparts + part) * U + u) * 16 + r]: part's share of the layer-2 pre-activation r of
 // unit u.  COHERENT: the readers run in the same launch, possibly on another XCD whose L2 is not
 // coherent with this one's: the results go out as device-scope stores (written through).
 template <int D, bool COHERENT>
 __device__ inline void mlp_parts_job(const __half *q, const __half *k, const __half *Wq1, const __half *Wk1,
                                      const __half *Wq2, const __half *Wk2, int Hh, int Rp, int R, int B,
-                                     float *out, int job, int wave, int l)
+                                     int x_stride, float *out, int job, int wave, int l)
 {
   constexpr int kRowBytes = D * 2, kStride = kRowBytes + 16, kChunks = kRowBytes / 16;
   __shared__ __attribute__((aligned(16))) unsigned char s_w1[kMlpPartHidden * kStride];
@@ -131,7 +132,7 @@ __device__ inline void mlp_parts_job(const __half *q, const __half *k, const __h
   const bool rowv = row < B;
   const size_t u = (size_t)(rowv ? row : 0) * Hh + h;
   v8h bx[D / 32];
-  mlp_load_row<D>(x + u * D, g, bx);                       // padding: any row
+  mlp_load_row<D>(x + u * (size_t)x_stride, g, bx);        // padding: any row
   const int hid = part * kMlpPartHidden;
   const bool two = hid + 32 < Rp;                          // the last part may hold one group
   // the job's rows of W1, whole lines (rows past the last hidden unit repeat it: never used)

@@ -175,13 +175,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 template <int D>
 __global__ __launch_bounds__(256) void mlp_parts_kernel(const __half *q, const __half *k, const __half *Wq1,
                                                         const __half *Wk1, const __half *Wq2, const __half *Wk2,
-                                                        int Hh, int Rp, int R, int B, float *out)
+                                                        int Hh, int rrp, int x_stride, int B, float *out)
 {
   // Plain scalar arguments, the ones the loads need first: the launch can preload the first
-  // sixteen dwords into registers (the compile flag asks for it), which takes the argument
-  // fetch out of a kernel that is one chain of latencies.
-  mlp_parts_job<D, false>(q, k, Wq1, Wk1, Wq2, Wk2, Hh, Rp, R, B, out, (int)blockIdx.x, (int)threadIdx.x / 64,
-                          (int)threadIdx.x % 64);
+  // sixteen dwords into registers (the compile flag asks for it),
+  // which takes the argument fetch out of a kernel that is one chain of latencies.  rrp = R | R' << 8.
+  mlp_parts_job<D, false>(q, k, Wq1, Wk1, Wq2, Wk2, Hh, rrp >> 8, rrp & 0xff, B, x_stride, out, (int)blockIdx.x,
+                          (int)threadIdx.x / 64, (int)threadIdx.x % 64);
 }
 
 bool mlp_mfma_supported(int dtype, int D, int Rp, int R)
@@ -229,10 +229,11 @@ hipError_t launch_mlp_pair(const MlpArgs &a, const MlpArgs &b, hipStream_t st)
 hipError_t launch_mlp_parts(const MlpPartsArgs &a, hipStream_t st)
 {
   const unsigned grid = (unsigned)(a.Hh * 2 * mlp_nparts(a.Rp) * ((a.B + 63) / 64));
+  const int rrp = a.R | (a.Rp << 8), xs = a.x_stride ? a.x_stride : a.D;
   if (a.D == 128)
-    mlp_parts_kernel<128><<<grid, 256, 0, st>>>(a.q, a.k, a.Wq1, a.Wk1, a.Wq2, a.Wk2, a.Hh, a.Rp, a.R, a.B, a.out);
+    mlp_parts_kernel<128><<<grid, 256, 0, st>>>(a.q, a.k, a.Wq1, a.Wk1, a.Wq2, a.Wk2, a.Hh, rrp, xs, a.B, a.out);
   else
-    mlp_parts_kernel<64><<<grid, 256, 0, st>>>(a.q, a.k, a.Wq1, a.Wk1, a.Wq2, a.Wk2, a.Hh, a.Rp, a.R, a.B, a.out);
+    mlp_parts_kernel<64><<<grid, 256, 0, st>>>(a.q, a.k, a.Wq1, a.Wk1, a.Wq2, a.Wk2, a.Hh, rrp, xs, a.B, a.out);
   return hipGetLastError();
 }
 

@@ -62,12 +62,13 @@ constexpr int kWpuSpinLimit = 1 << 14;   // FUSED: polls of the feature-map entr
 // =====================================================================================
 template <int D, int NR2, int RM, int DEPTH, bool SPLIT, bool FUSED>
 __global__ __launch_bounds__((FUSED ? kWpuFusedUnits : kWpuUnits) * kWave, FUSED ? 4 : 1) void wpu_step_kernel(
-    void *k_cache_, const void *q_, const void *k_, int crp_, int Hh_, int B_, int n_mlp, const void *Wq1_,
+    void *k_cache_, const void *q_, const void *k_, int crp_, int hb_, int xs_, int n_mlp, const void *Wq1_,
     const void *Wk1_, const void *Wq2_, const StepArgs a)
 {
   // The first arguments repeat what the head of the kernel needs to request the first rows:
   // scalar arguments can be preloaded into registers by the launch (the compile flag asks for
-  // it), the struct has to be fetched.  crp_ = C | R << 12 | R' << 19.
+  // it), the struct has to be fetched.  crp_ = C | R << 12 | R' << 19, hb_ = Hh | B << 16, xs_ = the
+  // distance in elements between the q / k / v / out rows of consecutive units.
   using T = __half;
   static_assert(!(SPLIT && FUSED), "the fused launch is one wave per unit");
   constexpr int EPL = 8;                   // elements per lane
@@ -78,7 +79,7 @@ __global__ __launch_bounds__((FUSED ? kWpuFusedUnits : kWpuUnits) * kWave, FUSED
 
   extern __shared__ double dyn[];
 
-  const int C = crp_ & 0xfff, R = (crp_ >> 12) & 0x7f, Rp = crp_ >> 19, Hh = Hh_;
+  const int C = crp_ & 0xfff, R = (crp_ >> 12) & 0x7f, Rp = crp_ >> 19, Hh = hb_ & 0xffff, B_ = (int)((unsigned)hb_ >> 16);
   const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
   if constexpr (FUSED) {
@@ -86,7 +87,7 @@ __global__ __launch_bounds__((FUSED ? kWpuFusedUnits : kWpuUnits) * kWave, FUSED
       mlp_parts_job<D, true>(reinterpret_cast<const __half *>(q_), reinterpret_cast<const __half *>(k_),
                              reinterpret_cast<const __half *>(Wq1_), reinterpret_cast<const __half *>(Wk1_),
                              reinterpret_cast<const __half *>(Wq2_), reinterpret_cast<const __half *>(a.Wk2), Hh, Rp, R,
-                             B_, a.mlp_out, (int)blockIdx.x, wave, lane);
+                             B_, xs_, a.mlp_out, (int)blockIdx.x, wave, lane);
       return;
     }
   }
@@ -108,9 +109,9 @@ __global__ __launch_bounds__((FUSED ? kWpuFusedUnits : kWpuUnits) * kWave, FUSED
 
   T *kc = reinterpret_cast<T *>(k_cache_) + (size_t)u * C * D;
   T *vc = reinterpret_cast<T *>(a.v_cache) + (size_t)u * C * D;
-  const T *qn = reinterpret_cast<const T *>(q_) + (size_t)u * D;
-  const T *kn = reinterpret_cast<const T *>(k_) + (size_t)u * D;
-  const T *vn = reinterpret_cast<const T *>(a.v) + (size_t)u * D;
+  const T *qn = reinterpret_cast<const T *>(q_) + (size_t)u * xs_;
+  const T *kn = reinterpret_cast<const T *>(k_) + (size_t)u * xs_;
+  const T *vn = reinterpret_cast<const T *>(a.v) + (size_t)u * xs_;
 
   // ---- requests, in the order they are wanted back ------------------------------------------------
   // Every load here is unconditional, from a clamped address where the wanted one may not
@@ -539,7 +540,7 @@ __global__ __launch_bounds__((FUSED ? kWpuFusedUnits : kWpuUnits) * kWave, FUSED
       __half2 res[2];
       res[0] = __floats2half2_rn((float)((double)o[0] + lscale * (double)fh[0]), (float)((double)o[1] + lscale * (double)fh[1]));
       res[1] = __floats2half2_rn((float)((double)o[2] + lscale * (double)fh[2]), (float)((double)o[3] + lscale * (double)fh[3]));
-      *reinterpret_cast<uint2 *>(reinterpret_cast<T *>(a.out) + (size_t)u * D + col0) = *reinterpret_cast<const uint2 *>(res);
+      *reinterpret_cast<uint2 *>(reinterpret_cast<T *>(a.out) + (size_t)u * xs_ + col0) = *reinterpret_cast<const uint2 *>(res);
     }
     if (ins_slot >= 0 && rb == 0) {
       store_nt(kc + (size_t)ins_slot * D + lr * EPL, knv.raw);
@@ -549,6 +550,7 @@ __global__ __launch_bounds__((FUSED ? kWpuFusedUnits : kWpuUnits) * kWave, FUSED
 
 }
 
+// (batch and heads below 65536 each: the kernel takes them packed in one preloaded argument)
 bool wpu_supported(int dtype, int D, int C, int Rp, int R)
 {
   return dtype == LESSDEC_DTYPE_F16 && (D == 64 || D == 128) && R <= 16 && Rp % 32 == 0 && Rp >= 32 &&
@@ -582,10 +584,10 @@ static hipError_t launch_step_wpu_s(const StepArgs &a, int upb, hipStream_t st, 
   const unsigned grid = n_mlp + (unsigned)(a.Hh * (SPLIT ? a.B : (a.B + upb - 1) / upb));
   const unsigned block = (unsigned)(upb * kWave);
   const int rows = a.C + 1;
-  const int crp = pack_crp(a);
+  const int crp = pack_crp(a), hb = a.Hh | (a.B << 16), xs = a.x_stride ? a.x_stride : D;
   const void *wq1 = fm ? fm->Wq1 : nullptr, *wk1 = fm ? fm->Wk1 : nullptr, *wq2 = fm ? fm->Wq2 : nullptr;
 #define LESSDEC_WPU_LAUNCH(NR2)                                                                                  \
-  wpu_step_kernel<D, NR2, RM, kDepth, SPLIT, FUSED><<<grid, block, lds, st>>>(a.k_cache, a.q, a.k, crp, a.Hh, a.B, \
+  wpu_step_kernel<D, NR2, RM, kDepth, SPLIT, FUSED><<<grid, block, lds, st>>>(a.k_cache, a.q, a.k, crp, hb, xs,    \
                                                                               (int)n_mlp, wq1, wk1, wq2, a)
   if (rows <= 2 * kWave) LESSDEC_WPU_LAUNCH(2);
   else if (rows <= 4 * kWave) LESSDEC_WPU_LAUNCH(4);
