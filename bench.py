@@ -63,7 +63,7 @@ def implementation_extra_bytes_per_unit_step(w) -> dict:
     nparts = (Rp + 63) // 64
     return {"fp64 accumulated scores (8 instead of 4 bytes, read and written)": 2 * 4 * C,
             "fp64 z (read and written)": 2 * 4 * R,
-            "feature-map exchange array (written, read, handed back empty)": 3 * 2 * nparts * 16 * 4,
+            "feature-map exchange array (written, read, handed back empty)": 3 * 2 * nparts * ((R + 3) // 4 * 4) * 4,
             "parked discarded pair: value row and psi (written, read next step), slot word": 2 * (D * e + 4 * R) + 8,
             "q and k rows read by the feature-map jobs as well": 2 * D * e,
             "token counter and eviction log": 12}

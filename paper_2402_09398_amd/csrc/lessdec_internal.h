@@ -34,7 +34,7 @@ hipError_t launch_mlp_pair(const MlpArgs &a, const MlpArgs &b, hipStream_t st); 
 
 // Both feature maps of one decode step, up to the layer-2 sums: phi of q and psi of k for
 // every unit, the hidden units split into parts of kMlpPartHidden.  out[((map * nparts +
-// part) * U + u) * 16 + r] is part's share of the layer-2 pre-activation r of unit u (map 0:
+// part) * U + u) * mlp_entry_stride(R) + r] is part's share of the layer-2 pre-activation r of unit u (map 0:
 // q with Wq, map 1: k with Wk); the reader adds the parts and finishes Eq. 1 / Eq. 2.
 constexpr int kMlpPartHidden = 64;
 struct MlpPartsArgs {
@@ -44,6 +44,9 @@ struct MlpPartsArgs {
   int x_stride = 0;      // elements from a unit's q / k row to the next unit's (0: D, rows packed)
 };
 __host__ __device__ inline int mlp_nparts(int Rp) { return (Rp + kMlpPartHidden - 1) / kMlpPartHidden; }
+// Entries per (map, part, unit) in the exchange array: the rank rounded up to the four outputs a
+// lane of the matrix tile holds.
+__host__ __device__ inline int mlp_entry_stride(int R) { return (R + 3) / 4 * 4; }
 hipError_t launch_mlp_parts(const MlpPartsArgs &a, hipStream_t st);
 
 // pend_slot: -1 nothing; else slot index (C = the step's own pair) | kPendNoFold

@@ -132,7 +132,7 @@ __global__ __launch_bounds__((FUSED ? kWpuFusedUnits : kWpuUnits) * kWave, FUSED
   __builtin_amdgcn_sched_barrier(0);
   // 2. layer-2 sums of the two feature maps by parts (lane r + 16 i reads what lane r reads),
   //    row r of W3
-  const int nparts = mlp_nparts(Rp);
+  const int nparts = mlp_nparts(Rp), rp = mlp_entry_stride(R);
   const int rl = (lane & 15) < R ? (lane & 15) : R - 1;
   float pq[NP], pk[NP];
   // FUSED: device-scope loads, the entries may come from another XCD in this very launch
@@ -140,8 +140,8 @@ __global__ __launch_bounds__((FUSED ? kWpuFusedUnits : kWpuUnits) * kWave, FUSED
 #pragma unroll
     for (int p = 0; p < NP; ++p) {
       const int pc = p < nparts ? p : nparts - 1;
-      const float *eq = a.mlp_parts + ((size_t)pc * a.U + u) * 16 + rl;
-      const float *ek = a.mlp_parts + ((size_t)(nparts + pc) * a.U + u) * 16 + rl;
+      const float *eq = a.mlp_parts + ((size_t)pc * a.U + u) * rp + rl;
+      const float *ek = a.mlp_parts + ((size_t)(nparts + pc) * a.U + u) * rp + rl;
       if constexpr (FUSED) {
         pq[p] = __hip_atomic_load(eq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         pk[p] = __hip_atomic_load(ek, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -230,8 +230,8 @@ __global__ __launch_bounds__((FUSED ? kWpuFusedUnits : kWpuUnits) * kWave, FUSED
         }
       }
       for (int p = NP; p < nparts; ++p) {                  // hidden widths above 512 (never FUSED)
-        sq += (double)a.mlp_parts[((size_t)p * a.U + u) * 16 + rl];
-        sk += (double)a.mlp_parts[((size_t)(nparts + p) * a.U + u) * 16 + rl];
+        sq += (double)a.mlp_parts[((size_t)p * a.U + u) * rp + rl];
+        sk += (double)a.mlp_parts[((size_t)(nparts + p) * a.U + u) * rp + rl];
       }
       f_lane = lane < R ? fabs(gelu_poly_f64(sq)) : 0.0;   // last activation of Eq. 1
       const double h2 = gelu_poly_f64(sk);                 // lane r < R; Eq. 2: |W3 gelu(.)|
@@ -241,10 +241,11 @@ __global__ __launch_bounds__((FUSED ? kWpuFusedUnits : kWpuUnits) * kWave, FUSED
         if (j < R) acc3 = fma(readlane_v(h2, j), (double)__half2float(w3[j]), acc3);
       npsi_lane = (float)fabs(acc3);
       if constexpr (!SPLIT) {
-        // lane = (map * nparts + part) * 4 + quarter of the part's 16 entries
-        for (int e = lane; e < 2 * nparts * 4; e += kWave) {
+        // lane = (map * nparts + part) * quads + quad of the part's entries
+        const int quads = rp / 4;
+        for (int e = lane; e < 2 * nparts * quads; e += kWave) {
           const u4v empty = {kMlpEmpty, kMlpEmpty, kMlpEmpty, kMlpEmpty};
-          __builtin_nontemporal_store(empty, reinterpret_cast<u4v *>(a.mlp_out + ((size_t)(e >> 2) * a.U + u) * 16) + (e & 3));
+          __builtin_nontemporal_store(empty, reinterpret_cast<u4v *>(a.mlp_out + ((size_t)(e / quads) * a.U + u) * rp) + e % quads);
         }
       }
     };
