@@ -119,7 +119,8 @@ typedef struct lessdec_desc {
                                      launch, the feature maps reach the attention waves through
                                      an array in it whose unwritten entries must read as empty;
                                      every step leaves it so).  A workspace serves descriptors
-                                     of one shape                                            */
+                                     of one shape, and calls that share one must be ordered
+                                     by a stream                                             */
   size_t workspace_bytes;
 } lessdec_desc;
 
