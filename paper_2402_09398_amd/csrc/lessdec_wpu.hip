@@ -1,5 +1,6 @@
 // Decode step (Algorithm 1), streaming form: one wave per unit.  The layer-2 sums of the step's
-// feature maps come from the matrix-core launch before it (lessdec_mlp.hip).
+// feature maps come from the feature-map jobs (lessdec_mlp.h): the first workgroups of this very
+// launch (FUSED) or the launch before it (lessdec_mlp.hip).
 #include "lessdec_mlp.h"
 #include "lessdec_wave.h"
 
@@ -12,7 +13,7 @@ constexpr int kWpuFusedUnits = 4;   // FUSED: units (waves) per block, the size 
 constexpr int kWpuSpinLimit = 1 << 14;   // FUSED: polls of the feature-map entries before a wave gives up
 
 // =====================================================================================
-// A block is 8 waves = 8 units that share a head: batch rows 8 * chunk .. 8 * chunk + 7 of
+// A block is up to 8 waves = 8 units that share a head (4 when FUSED): consecutive batch rows of
 // head h (head fastest in blockIdx, so with Hh a multiple of 8 the units of a head run on
 // the XCD whose L2 holds the feature-map sums written for them).  The waves of a block share
 // nothing and never meet at a barrier; each is on its own from the first instruction.
@@ -31,9 +32,10 @@ constexpr int kWpuSpinLimit = 1 << 14;   // FUSED: polls of the feature-map entr
 // requested out of the buffer's range, which returns zeros and moves no data.
 //
 // Phase 1  scores s_j = q . K_j / sqrt(D) of the live slots and the appended key as they
-//          arrive: fp64, reduced over the LPR lanes of a row by DPP, parked in the LDS.
-//          After the first pass over the ring, phi(q) and psi(k) are finished from their
-//          layer-2 sums (last activations of Eq. 1 and Eq. 2, W3) in fp64.
+//          arrive: exact fp32 products added in fp64, reduced over the LPR lanes of a row by
+//          DPP, parked in the LDS.  After the first pass over the ring (FUSED: inside phase 2),
+//          phi(q) and psi(k) are finished from their layer-2 sums (last activations of Eq. 1
+//          and Eq. 2, W3) in fp64.
 // Phase 2  lane j owns rows j, j + 64, ..: shift, exponentials, denominator of Eq. 3 with
 //          phi(q) z^T, probabilities, H2O score accumulation, eviction argmin (Sec. 2.1);
 //          fold of the pair the previous step discarded into z (Eq. 5), which Eq. 3 of this
@@ -53,8 +55,8 @@ constexpr int kWpuSpinLimit = 1 << 14;   // FUSED: polls of the feature-map entr
 // The layer-2 sums travel through the exchange array as 32-bit entries, written through by the
 // jobs and read with device-scope loads.  An entry that no job has written yet holds kMlpEmpty:
 // an attention wave requests its entries behind the last-but-one pass of the key stream (by then
-// the jobs are normally long done), checks them after the last pass, asks again while any is still
-// empty, and puts kMlpEmpty back once it has them, so that the array is all empty again when the
+// the jobs are normally long done), checks them after the sparse part of phase 2, asks again while
+// any is still empty, and puts kMlpEmpty back once it has them, so that the array is all empty again when the
 // step ends.  (The form that gets its entries from a launch before it, !FUSED, empties them as
 // well: either form can follow the other on one workspace.)  A wave that has polled
 // kWpuSpinLimit times gives up and computes with the empty entries, which are NaN: the outputs
