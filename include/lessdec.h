@@ -188,8 +188,10 @@ int lessdec_prefill(const lessdec_desc *desc, const void *Q, const void *K, cons
  * from the previous step into H, z happens first, so Eq. 3 always sees the state Algorithm 1
  * prescribes.  With LESSDEC_FLAG_LAMBDA the discarded pair is instead the oldest one that is
  * neither among the first n_heavy tokens of the sequence nor among the n_recent most recent.
- * With q_per_kv = G > 1: q and out are [B,Hh,G,D] (k, v stay [B,Hh,D]); the step runs on a
- * plain kernel that folds the discarded pair at once (nothing is left pending).
+ * With q_per_kv = G > 1: q and out are [B,Hh,G,D] (k, v stay [B,Hh,D]).  Up to 8 query heads
+ * with fp16 storage run on a streaming kernel (a block per unit, a wave per query head) that
+ * leaves the discarded pair pending like the single-head path; other shapes on a plain kernel
+ * that folds the discarded pair at once.
  */
 int lessdec_step(const lessdec_desc *desc, const void *q, const void *k, const void *v,
                  void *out, int32_t *evicted_pos, void *hip_stream);

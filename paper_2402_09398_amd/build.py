@@ -11,7 +11,7 @@ ROOT = HERE.parent
 CSRC = HERE / "csrc"
 LIB = HERE / "liblessdec.so"
 SOURCES = ["lessdec_api.hip", "lessdec_featmap.hip", "lessdec_mlp.hip", "lessdec_step.hip", "lessdec_wpu.hip",
-           "lessdec_prefill.hip", "lessdec_gqa.hip", "lessdec_probe.hip"]
+           "lessdec_prefill.hip", "lessdec_gqa.hip", "lessdec_gqs.hip", "lessdec_probe.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

@@ -269,6 +269,8 @@ int step_attend_impl(const lessdec_desc *desc, const void *q, const void *k, con
       a.f_phi = reinterpret_cast<double *>(ws + w.off_fphi);
     a.f_psi = reinterpret_cast<float *>(ws + w.off_fpsi);
     a.gqa_parts = reinterpret_cast<double *>(ws + w.off_gqa);
+    if (gqs_supported(desc->dtype, desc->head_dim, (int)s.C, desc->rank, (int)s.G))
+      return launch_step_gqs(a, (int)s.G, desc->head_dim, st) == hipSuccess ? LESSDEC_OK : LESSDEC_EHIP;
     return launch_step_gqa(a, (int)s.G, desc->dtype, desc->head_dim, st) == hipSuccess ? LESSDEC_OK : LESSDEC_EHIP;
   }
   if (use_wpu(desc, s)) {
@@ -332,7 +334,9 @@ int lessdec_step_launches(const lessdec_desc *desc)
 {
   Shape s;
   if (!shape_ok(desc, &s)) return 0;
-  if (s.G > 1) return gqa_head_blocks((long)s.U, (int)s.G) > 1 ? 3 : 2;   // feature maps, heads, (finishing launch)
+  if (s.G > 1)                                                              // feature maps, heads, (finishing launch)
+    return !gqs_supported(desc->dtype, desc->head_dim, (int)s.C, desc->rank, (int)s.G) &&
+                   gqa_head_blocks((long)s.U, (int)s.G) > 1 ? 3 : 2;
   if (use_wpu(desc, s))
     return wpu_fusable(desc->batch, desc->heads, desc->head_dim, (int)s.C, desc->hidden, desc->rank) ? 1 : 2;
   return 3;                                                                 // phi, psi, step

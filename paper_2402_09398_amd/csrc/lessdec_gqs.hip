@@ -1,0 +1,389 @@
+// Decode step (Algorithm 1) with several query heads per key/value head (Sec. 3.2: H2O aggregates
+// the scores of all query heads), streaming form: one block per unit, one wave per query head.
+//
+// Every wave streams the unit's K rows and then its V rows through its own register ring, as the
+// single-head streaming kernel does (lessdec_wpu.hip): the G waves of a block ask for the same
+// lines at nearly the same time, so each line comes from memory once and from the compute unit's
+// cache for the other heads.  A wave has its own query, phi(q), scores, softmax (Eq. 3 with the
+// shared state H, z) and output row.  What the heads share goes through the LDS:
+//   barrier 1  every wave has the unit's state in registers (the lead wave may now store);
+//   phase 2a   per head: shift, exponentials, Eq. 3's denominator, probabilities; the head's
+//              share of every pair's score increment goes to s_inc[head];
+//   barrier 2  all increments visible;
+//   phase 2b   every wave adds the increments in head order to the accumulated scores and works
+//              out the eviction for itself (same data, same result); the lead wave stores;
+//   phase 3/4  per head p . V, phi(q) H, output; the lead wave parks the discarded pair;
+//   barrier 3  every wave is through with the cache rows; the lead wave writes the new pair
+//              into its slot (Sec. 3.2).
+// The fold of the discarded pair into H, z is left to the next step (pend_slot, as on the
+// single-head path).  phi(q) per head and psi(k) come from the feature-map launch before it.
+#include "lessdec_wave.h"
+
+namespace lessdec {
+
+constexpr int kGqsMaxHeads = 8;     // waves per block
+constexpr int kGqsMaxRows = 512;    // C + 1 at most
+
+template <int D, int NR2, int RM, int DEPTH>
+__global__ __launch_bounds__(kGqsMaxHeads * kWave) void gqs_step_kernel(void *k_cache_, const void *q_, const void *k_,
+                                                                       int C_, int G_, const StepArgs a)
+{
+  using T = __half;
+  constexpr int EPL = 8;                   // elements per lane
+  constexpr int LPR = D / EPL;             // lanes per row
+  constexpr int RPI = kWave / LPR;         // rows per load instruction
+  using Vec = typename Store<T>::Vec;
+
+  extern __shared__ double dyn[];
+
+  const int C = C_, R = a.R, G = G_;
+  const int g = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);    // this wave's query head
+  const int lane = threadIdx.x & 63;
+  const int lr = lane % LPR, rb = lane / LPR;
+  const int u = (int)blockIdx.x;
+  const bool lead = g == 0;                                  // the wave that writes the unit's state
+  const int rows_cap = (C + 2) & ~1;
+  double *s_sc = dyn + (size_t)g * rows_cap;                 // [G][C+1] scores
+  double *s_inc = dyn + (size_t)G * rows_cap;                // [G][C+1] a head's share of the score increments
+  float *s_p = reinterpret_cast<float *>(dyn + 2 * (size_t)G * rows_cap) + (size_t)g * rows_cap;   // [G][C+1]
+
+  T *kc = reinterpret_cast<T *>(k_cache_) + (size_t)u * C * D;
+  T *vc = reinterpret_cast<T *>(a.v_cache) + (size_t)u * C * D;
+  const T *qn = reinterpret_cast<const T *>(q_) + ((size_t)u * G + g) * D;
+  const T *kn = reinterpret_cast<const T *>(k_) + (size_t)u * D;
+  const T *vn = reinterpret_cast<const T *>(a.v) + (size_t)u * D;
+
+  // ---- requests, in the order they are wanted back (all unconditional, clamped addresses) ----------
+  const Vec qv = load_vec<T>(qn + lr * EPL);
+  const Vec knv = load_vec<T>(kn + lr * EPL);
+  u4v buf[DEPTH];
+  {
+    const __amdgpu_buffer_rsrc_t rk =
+        __builtin_amdgcn_make_buffer_rsrc(kc, 0, C * D * (int)sizeof(T), 0x00020000);
+#pragma unroll
+    for (int j = 0; j < DEPTH; ++j)
+      buf[j] = __builtin_amdgcn_raw_buffer_load_b128(rk, lane * 16, j * (kWave * 16), 2 /* nt */);
+  }
+  __builtin_amdgcn_sched_barrier(0);
+  const int rl = (lane & 15) < R ? (lane & 15) : R - 1;
+  // phi(q) of this head and psi(k) of the step's key, from the feature-map launch (lane r < R)
+  const size_t fi = ((size_t)u * G + g) * R + rl;
+  double f_lane = a.f_phi32 ? (double)a.f_phi32[fi] : a.f_phi[fi];
+  const float npsi_lane = a.f_psi[(size_t)u * R + rl];
+  // unit state (wanted from phase 2 on)
+  const int n = sane_n_seen(a.n_seen[u]);
+  const Pending pend = decode_pending(a.pend_slot[u], C);
+  const int m = n < C ? n : C;          // live slots are 0..m-1 (slots fill in order)
+  const int rows = m + 1;               // + the appended pair (K', V' of Eq. 3)
+  const bool full = (m == C);
+  double acc_pre[NR2];
+  int pos_pre[NR2];
+#pragma unroll
+  for (int i = 0; i < NR2; ++i) {
+    const int j = lane + i * kWave;
+    const size_t idx = (size_t)u * C + (j < C ? j : C - 1);
+    acc_pre[i] = a.acc[idx];
+    pos_pre[i] = a.pos[idx];
+  }
+  double z_lane = a.z[(size_t)u * R + rl];                   // lane r < R
+  const float ppsi_lane = a.pend_psi[(size_t)u * R + rl];
+  float psie_lane = a.psi[((size_t)u * C + (pend.slot >= 0 && pend.slot < C ? pend.slot : 0)) * R + rl];
+  __builtin_amdgcn_sched_barrier(0);
+
+  // The stream: position s < nitp is load s of K, position nitp + t is load t of V.
+  const int nit = (rows + RPI - 1) / RPI;                    // load instructions per stream (>= 1)
+  const int nitp = (nit + DEPTH - 1) / DEPTH * DEPTH;        // K part of the stream, padded
+  const int live_bytes = m * D * (int)sizeof(T);
+  auto issue = [&](int s) -> u4v {                           // s is wave-uniform
+    const bool isk = s < nitp;
+    const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(isk ? kc : vc, 0, live_bytes, 0x00020000);
+    return __builtin_amdgcn_raw_buffer_load_b128(rs, lane * 16, (isk ? s : s - nitp) * (kWave * 16), 2 /* nt */);
+  };
+
+  // ---- phase 1: this head's scores as the key rows arrive -------------------------------------------
+  {
+    const double inv_sqrt_d = 1.0 / sqrt((double)D);
+    int base = 0;
+    do {                                                     // nitp >= DEPTH
+#pragma unroll
+      for (int j = 0; j < DEPTH; ++j) {
+        const int s = base + j;
+        if (s < nit) {
+          const int r = s * RPI + rb;
+          Vec kv;
+          __builtin_memcpy(&kv.raw, &buf[j], 16);
+          if (r == m) kv = knv;                              // the appended key
+          // a product of two halves is exact in fp32, so fp32 multiply, widen, fp64 add
+          double part = 0.0;
+#pragma unroll
+          for (int i = 0; i < EPL; ++i) part += (double)(Store<T>::get(qv, i) * Store<T>::get(kv, i));
+          part = row_sum<LPR>(part);
+          if (lr == 0 && r < rows) s_sc[r] = part * inv_sqrt_d;
+        }
+        buf[j] = issue(s + DEPTH);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    } while ((base += DEPTH) < nitp);
+  }
+
+  // ---- requests behind the keys: what the value stream and the output want --------------------------
+  const Vec vnv = load_vec<T>(vn + lr * EPL);
+  constexpr int NHB = RPI / 2, HR = RM / NHB;
+  const int col0 = lr * EPL + ((lane & LPR) ? 4 : 0);
+  const int hb = lane / (2 * LPR);                           // which rows of H: r = NHB * i + hb
+  float4 hreg[HR];
+#pragma unroll
+  for (int i = 0; i < HR; ++i) {
+    const int r = NHB * i + hb;
+    hreg[i] = *reinterpret_cast<const float4 *>(a.H + ((size_t)u * R + (r < R ? r : R - 1)) * D + col0);
+  }
+  const uint2 pend_v_h = *reinterpret_cast<const uint2 *>(reinterpret_cast<const T *>(a.pend_v) + (size_t)u * D + col0);
+  // barrier 1: the lead wave's stores must not overtake another wave's loads of the same state:
+  // have those loads back before the waves meet (the value rows requested after them stay in flight)
+#pragma unroll
+  for (int i = 0; i < NR2; ++i) asm volatile("" ::"v"(acc_pre[i]), "v"(pos_pre[i]));
+#pragma unroll
+  for (int i = 0; i < HR; ++i) asm volatile("" ::"v"(hreg[i].x), "v"(hreg[i].y), "v"(hreg[i].z), "v"(hreg[i].w));
+  asm volatile("" ::"v"(z_lane), "v"(ppsi_lane), "v"(psie_lane), "v"(pend_v_h.x), "v"(pend_v_h.y), "v"(npsi_lane), "v"(f_lane));
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+
+  // ---- phase 2a: this head's softmax with the low-rank term -----------------------------------------
+  double lscale = 0.0;
+  if (lane >= R) f_lane = 0.0;
+  {
+    double sc[NR2];
+    double M = -__builtin_inf();
+#pragma unroll
+    for (int i = 0; i < NR2; ++i) {
+      const int j = lane + i * kWave;
+      sc[i] = j < rows ? s_sc[j] : -__builtin_inf();
+      M = fmax(M, sc[i]);
+    }
+    M = wave_allreduce(M, OpMax{});
+    double S = 0.0;
+#pragma unroll
+    for (int i = 0; i < NR2; ++i) {
+      const int j = lane + i * kWave;
+      sc[i] = j < rows ? exp_softmax_f64(sc[i] - M) : 0.0;
+      S += sc[i];
+    }
+    S = wave_allreduce(S, OpAdd{});                          // sparse part of the denominator, shifted
+    // pending fold of z (Eq. 5), then phi(q) z^T
+    if (lane >= R) z_lane = 0.0;
+    if (!pend.fold) psie_lane = 0.f;
+    else if (pend.slot >= C) psie_lane = ppsi_lane;          // the previous step discarded its own pair
+    if (lane < R) {
+      if (pend.fold) {
+        z_lane += (double)psie_lane;
+        if (lead) a.z[(size_t)u * R + lane] = z_lane;
+      }
+      if (lead) {
+        if (pend.slot >= 0 && pend.slot < C) a.psi[((size_t)u * C + pend.slot) * R + lane] = ppsi_lane;
+        a.pend_psi[(size_t)u * R + lane] = npsi_lane;
+      }
+    }
+    const double fz = wave_allreduce(f_lane * z_lane, OpAdd{});
+    double pscale;
+    if (fz > 0.0 && M <= 0.0) {
+      const double w = exp_softmax_f64(M);
+      const double inv = 1.0 / (fz + w * S);
+      pscale = w * inv;
+      lscale = inv;
+    } else {
+      const double eM = (fz > 0.0) ? exp_softmax_f64(-M) : 0.0;
+      const double inv = 1.0 / (fz * eM + S);
+      pscale = inv;
+      lscale = eM * inv;
+    }
+    double ascale = pscale;
+    if (a.flags & LESSDEC_FLAG_SPARSE_DENOM) ascale = 1.0 / S;
+#pragma unroll
+    for (int i = 0; i < NR2; ++i) {
+      const int j = lane + i * kWave;
+      if (j < rows) {
+        s_p[j] = (float)(sc[i] * pscale);
+        s_inc[(size_t)g * rows_cap + j] = sc[i] * ascale;
+      }
+    }
+  }
+  // barrier 2: every head's increments are in the LDS
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+
+  // ---- phase 2b: accumulated scores and the eviction, by every wave for itself ----------------------
+  int eslot = -1, ins_slot = -1;
+  {
+    const bool lambda = (a.flags & LESSDEC_FLAG_LAMBDA) != 0;
+    double na_[NR2];
+    Cand best = cand_none();
+#pragma unroll
+    for (int i = 0; i < NR2; ++i) {
+      const int j = lane + i * kWave;
+      na_[i] = 0.0;
+      if (j < rows) {
+        double inc = 0.0;
+        for (int h = 0; h < G; ++h) inc += s_inc[(size_t)h * rows_cap + j];     // in head order
+        double na = inc;
+        int pj = n;
+        if (j < m) {
+          na += acc_pre[i];
+          pj = pos_pre[i];
+        }
+        na_[i] = na;
+        if (full) {
+          const bool is_cand = (j < m) ? (pj <= n - a.Nr && (!lambda || pj >= a.Nh)) : (a.Nr == 0);
+          const Cand cnd{lambda ? 0.0 : na, pj, j};
+          if (is_cand && cand_less(cnd, best)) best = cnd;
+        }
+      }
+    }
+    int epos = -1;
+    if (full) {
+      const double amin = wave_allreduce(best.acc, OpMin{});
+      const int pmin = wave_allreduce(best.acc == amin ? best.pos : INT_MAX, OpMinI{});
+      const unsigned long long win = __ballot(best.acc == amin && best.pos == pmin && best.slot >= 0);
+      if (win != 0ull) {
+        eslot = __builtin_amdgcn_readlane(best.slot, __ffsll((long long)win) - 1);
+        epos = pmin;
+      }
+    }
+    const bool evict = eslot >= 0;                           // eslot == m: the new pair itself
+    ins_slot = full ? ((evict && eslot < m) ? eslot : -1) : m;
+    if (lead) {
+#pragma unroll
+      for (int i = 0; i < NR2; ++i) {
+        const int j = lane + i * kWave;
+        if (j < m) {
+          if (j != ins_slot) __builtin_nontemporal_store(na_[i], a.acc + (size_t)u * C + j);
+        } else if (j == m && ins_slot >= 0) {
+          a.acc[(size_t)u * C + ins_slot] = na_[i];
+          a.pos[(size_t)u * C + ins_slot] = n;
+        }
+      }
+      if (lane == 0) {
+        a.pend_slot[u] = evict ? (eslot < m ? eslot : C) : (m | kPendNoFold);
+        if (a.evicted_pos) a.evicted_pos[u] = evict ? epos : -1;
+        a.n_seen[u] = n + 1;
+      }
+    }
+  }
+
+  // ---- phase 3: p . V as the value rows arrive ------------------------------------------------------
+  float o[EPL];
+#pragma unroll
+  for (int i = 0; i < EPL; ++i) o[i] = 0.f;
+  float fh[4] = {0.f, 0.f, 0.f, 0.f};                        // phi(q) H, this lane's columns and rows
+  {
+    int base = 0;
+    do {                                                     // nit >= 1
+#pragma unroll
+      for (int j = 0; j < DEPTH; ++j) {
+        const int s = base + j;
+        if (s < nit) {
+          const int r = s * RPI + rb;
+          Vec vv;
+          __builtin_memcpy(&vv.raw, &buf[j], 16);
+          if (r == m) vv = vnv;                              // the appended pair's value row
+          if (r < rows) {
+            const float p = s_p[r];
+#pragma unroll
+            for (int i = 0; i < EPL; ++i) o[i] = fmaf(p, Store<T>::get(vv, i), o[i]);
+          }
+          if (lead && r == eslot)                            // the discarded pair's value row
+            *reinterpret_cast<uint4 *>(reinterpret_cast<T *>(a.pend_v) + (size_t)u * D + lr * EPL) = vv.raw;
+        }
+        buf[j] = issue(nitp + s + DEPTH);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      if (base == 0) {
+        // fold the pending pair into H (Eq. 4; stored by the lead wave), then this head's phi(q) H
+        const float f32 = (float)f_lane;
+        const __half2 *pvh = reinterpret_cast<const __half2 *>(&pend_v_h);
+        const float2 pv01 = __half22float2(pvh[0]), pv23 = __half22float2(pvh[1]);
+        float *Hu = a.H + (size_t)u * R * D;
+#pragma unroll
+        for (int i = 0; i < HR; ++i) {
+          const int r = NHB * i + hb;
+          const int rc = r < R ? r : R - 1;
+          const float fr = r < R ? __shfl(f32, rc) : 0.f;
+          const float pe = __shfl(psie_lane, rc);
+          if (pend.fold) {
+            hreg[i].x = fmaf(pe, pv01.x, hreg[i].x);
+            hreg[i].y = fmaf(pe, pv01.y, hreg[i].y);
+            hreg[i].z = fmaf(pe, pv23.x, hreg[i].z);
+            hreg[i].w = fmaf(pe, pv23.y, hreg[i].w);
+            if (r < R && lead) store_nt(Hu + (size_t)r * D + col0, hreg[i]);
+          }
+          fh[0] = fmaf(fr, hreg[i].x, fh[0]);
+          fh[1] = fmaf(fr, hreg[i].y, fh[1]);
+          fh[2] = fmaf(fr, hreg[i].z, fh[2]);
+          fh[3] = fmaf(fr, hreg[i].w, fh[3]);
+        }
+      }
+    } while ((base += DEPTH) < nit);
+  }
+  // The RPI row groups hold partial sums of the same 8 columns: reduce-scatter over the first
+  // stage (a lane keeps the four columns selected by its bit LPR), all-reduce over the rest,
+  // together with the partial phi(q) H of the row subsets.
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const bool hi = lane & LPR;
+    const float send = hi ? o[i] : o[i + 4], keep = hi ? o[i + 4] : o[i];
+    o[i] = keep + __shfl_xor(send, LPR);
+  }
+#pragma unroll
+  for (int x = 2 * LPR; x < kWave; x *= 2) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      o[i] += __shfl_xor(o[i], x);
+      fh[i] += __shfl_xor(fh[i], x);
+    }
+  }
+  // ---- phase 4: this head's output; the new pair goes into its slot once every head is through ------
+  if (hb == 0) {
+    __half2 res[2];
+    res[0] = __floats2half2_rn((float)((double)o[0] + lscale * (double)fh[0]), (float)((double)o[1] + lscale * (double)fh[1]));
+    res[1] = __floats2half2_rn((float)((double)o[2] + lscale * (double)fh[2]), (float)((double)o[3] + lscale * (double)fh[3]));
+    *reinterpret_cast<uint2 *>(reinterpret_cast<T *>(a.out) + ((size_t)u * G + g) * D + col0) = *reinterpret_cast<const uint2 *>(res);
+  }
+  // barrier 3: the rows still in a ring are requests past the value stream (out of range, zeros),
+  // so every wave that arrives here has all the cache rows it will ever read
+#pragma unroll
+  for (int j = 0; j < DEPTH; ++j) asm volatile("" ::"v"(buf[j]));
+  __builtin_amdgcn_s_barrier();
+  if (lead && ins_slot >= 0 && rb == 0) {
+    store_nt(kc + (size_t)ins_slot * D + lr * EPL, knv.raw);
+    store_nt(vc + (size_t)ins_slot * D + lr * EPL, vnv.raw);
+  }
+}
+
+bool gqs_supported(int dtype, int D, int C, int R, int G)
+{
+  return dtype == LESSDEC_DTYPE_F16 && (D == 64 || D == 128) && R <= 16 && C + 1 <= kGqsMaxRows && G >= 2 &&
+         G <= kGqsMaxHeads;
+}
+
+template <int D, int RM>
+static hipError_t launch_step_gqs_t(const StepArgs &a, int G, hipStream_t st)
+{
+  constexpr int kDepth = 7;
+  const int rows_cap = (a.C + 2) & ~1;
+  const size_t lds = (size_t)G * rows_cap * (2 * sizeof(double) + sizeof(float));
+  const unsigned grid = (unsigned)a.U, block = (unsigned)(G * kWave);
+  const int rows = a.C + 1;
+  if (rows <= 2 * kWave) gqs_step_kernel<D, 2, RM, kDepth><<<grid, block, lds, st>>>(a.k_cache, a.q, a.k, a.C, G, a);
+  else if (rows <= 4 * kWave) gqs_step_kernel<D, 4, RM, kDepth><<<grid, block, lds, st>>>(a.k_cache, a.q, a.k, a.C, G, a);
+  else gqs_step_kernel<D, kGqsMaxRows / kWave, RM, kDepth><<<grid, block, lds, st>>>(a.k_cache, a.q, a.k, a.C, G, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_step_gqs(const StepArgs &a, int G, int D, hipStream_t st)
+{
+  if (D == 64) return launch_step_gqs_t<64, 16>(a, G, st);
+  return a.R <= 8 ? launch_step_gqs_t<128, 8>(a, G, st) : launch_step_gqs_t<128, 16>(a, G, st);
+}
+
+}  // namespace lessdec

@@ -88,6 +88,10 @@ hipError_t launch_step_gqa(const StepArgs &a, int G, int dtype, int D, hipStream
 constexpr int kGqaMaxHeadBlocks = 8;
 int gqa_head_blocks(long units, int G);
 hipError_t launch_state_sync(const StepArgs &a, int dtype, int D, hipStream_t st);
+// several query heads per unit, streaming form: one block per unit, one wave per query head
+// (lessdec_gqs.hip); leaves the discarded pair pending like the single-head streaming path
+bool gqs_supported(int dtype, int D, int C, int R, int G);
+hipError_t launch_step_gqs(const StepArgs &a, int G, int D, hipStream_t st);
 
 // One wave per unit, K and V streamed through a register ring (lessdec_wpu.hip).
 bool wpu_supported(int dtype, int D, int C, int Rp, int R);
