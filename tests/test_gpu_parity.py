@@ -326,6 +326,9 @@ GROUPS = [
     (small("mqa-8-heads-no-prompt", q_per_kv=8, prompt=0, steps=40, n_heavy=5, n_recent=5), 4),
     (small("gqa-2-heads-no-recent-window", q_per_kv=2, n_heavy=6, n_recent=0, prompt=20, steps=20), 4),
     (small("gqa-2-heads-sparse-denominator", q_per_kv=2, prompt=20, steps=20), 5),
+    # more than eight query heads: the plain kernel, heads in chunks of four, spread over blocks
+    (small("mqa-12-heads-plain-kernel", q_per_kv=12, prompt=30, steps=15), 4),
+    (small("mqa-9-heads-plain-kernel-one-shot", q_per_kv=9, prompt=60, steps=12, batch=1, heads=2), 0),
     (small("gqa-5-heads-wide-cache", q_per_kv=5, n_heavy=100, n_recent=60, prompt=200, steps=10, batch=1,
            heads=2, rank=16, hidden=96), 4),
 ]
@@ -405,18 +408,18 @@ def test_query_groups_at_the_benchmark_shape():
 
 def _kind_workload(name, kind, steps):
     """The decode path a small workload takes: one wave per unit, a unit's rows split over
-    several waves (enough slots for that), several query heads per unit, or the any-shape kernels
-    (rank above 16)."""
+    several waves (enough slots for that), several query heads per unit (streaming kernel up to
+    eight, plain kernel beyond), or the any-shape kernels (rank above 16)."""
     if kind == "streaming":
         return small(name, steps=steps)
     if kind == "one-launch":                 # 1024 units and more, one wave each: the whole step is one launch
         return small(name + "-one-launch", steps=steps, batch=70, heads=16, prompt=30)
     if kind == "split":
         return small(name + "-split", steps=steps, n_heavy=35, n_recent=35, prompt=90)
-    if kind == "multi-head":                 # four query heads per unit: one block per unit
+    if kind == "multi-head":                 # four query heads per unit: a block per unit, a wave per head
         return small(name + "-multi-head", steps=steps, q_per_kv=4)
-    if kind == "multi-head-spread":          # eight: a unit's heads over two blocks and a finishing launch
-        return small(name + "-multi-head-spread", steps=steps, q_per_kv=8)
+    if kind == "multi-head-spread":          # sixteen: the plain kernel, a unit's heads over blocks and a finishing launch
+        return small(name + "-multi-head-spread", steps=steps, q_per_kv=16)
     return small(name + "-general", steps=steps, rank=20)
 
 
