@@ -163,7 +163,7 @@ def test_lambda_masking_at_the_benchmark_shape():
     """Config 3's shape and budget with the paper's split for this policy: 4 first tokens,
     the rest of the 102 slots recent."""
     w = wl.WORKLOADS[3].scaled(name="cfg3-lambda", n_heavy=4, n_recent=98)
-    units = sample_units(w, 8, seed=33)
+    units = sample_units(w, 256, seed=33)         # 8 batch rows of every head, first and last unit and block corners
     rep = hz.run_workload(w, units, flags=2, want_prefill_out=False)
     report_ok(rep, min_decisions=len(units) * w.steps)
     assert rep.exempt == 0 and 0.0 < rep.mean_share < 1.0
@@ -275,7 +275,7 @@ def test_masked_prompt_at_the_benchmark_shape():
     """Config 3's shape, 4 first tokens + 98 recent, the policy active through the 1024-token
     prompt: every unit on the GPU, a sample of units through the oracle's token-by-token walk."""
     w = wl.WORKLOADS[3].scaled(name="cfg3-lambda-through-prompt", n_heavy=4, n_recent=98, steps=16)
-    units = sample_units(w, 6, seed=34)
+    units = sample_units(w, 128, seed=34)         # 4 batch rows of every head
     rep = hz.run_workload(w, units, flags=6)
     report_ok(rep, min_decisions=len(units) * w.steps)
     assert rep.exempt == 0
@@ -401,7 +401,7 @@ def test_query_groups_at_the_benchmark_shape():
     1024-token prompt): every unit on the GPU, a sample of units through the oracle."""
     w3 = wl.WORKLOADS[3]
     w = w3.scaled(name="cfg3-gqa4", heads=w3.heads // 4, q_per_kv=4, steps=32)
-    units = sample_units(w, 4, seed=35)
+    units = sample_units(w, 128, seed=35)         # 16 batch rows of every key/value head
     rep = hz.run_workload(w, units)
     report_ok(rep, min_decisions=len(units) * w.steps)
 
