@@ -171,15 +171,21 @@ __global__ __launch_bounds__((FUSED ? kWpuFusedUnits : kWpuUnits) * kWave, FUSED
   const int m = n < C ? n : C;          // live slots are 0..m-1 (slots fill in order)
   const int rows = m + 1;               // + the appended pair (K', V' of Eq. 3)
   const bool full = (m == C);
+  // (accumulated scores and positions: a single wave asks for them in phase 2, two passes of the
+  // value stream before it needs them; waves that share a unit must have them before they meet,
+  // since the lead wave stores the new ones after that)
   double acc_pre[NR2];
   int pos_pre[NR2];
+  auto request_scores = [&]() __attribute__((always_inline)) {
 #pragma unroll
-  for (int i = 0; i < NR2; ++i) {
-    const int j = lane + i * kWave;
-    const size_t idx = (size_t)u * C + (j < C ? j : C - 1);
-    acc_pre[i] = a.acc[idx];
-    pos_pre[i] = a.pos[idx];
-  }
+    for (int i = 0; i < NR2; ++i) {
+      const int j = lane + i * kWave;
+      const size_t idx = (size_t)u * C + (j < C ? j : C - 1);
+      acc_pre[i] = a.acc[idx];
+      pos_pre[i] = a.pos[idx];
+    }
+  };
+  if constexpr (SPLIT) request_scores();
   double z_lane = a.z[(size_t)u * R + rl];                   // lane r < R
   const float ppsi_lane = a.pend_psi[(size_t)u * R + rl];
   float psie_lane = a.psi[((size_t)u * C + (pend.slot >= 0 && pend.slot < C ? pend.slot : 0)) * R + rl];
@@ -200,15 +206,17 @@ __global__ __launch_bounds__((FUSED ? kWpuFusedUnits : kWpuUnits) * kWave, FUSED
   double f_lane = 0.0;                   // phi(q), lane r < R
   float npsi_lane = 0.f;                 // psi(k) of this step's key, lane r < R
   const double inv_sqrt_d = 1.0 / sqrt((double)D);        // folded at compile time
+  u4v knu;
+  __builtin_memcpy(&knu, &knv.raw, 16);
   auto key_pass = [&](int base) {
 #pragma unroll
       for (int j = 0; j < DEPTH; ++j) {
         const int s = base + j;
         if (s < nit) {
           const int r = (s * nw + wv) * RPI + rb;
+          const u4v kraw = (r == m) ? knu : buf[j];       // r == m: the appended key
           Vec kv;
-          __builtin_memcpy(&kv.raw, &buf[j], 16);
-          if (r == m) kv = knv;                           // the appended key
+          __builtin_memcpy(&kv.raw, &kraw, 16);
           // a product of two halves is exact in fp32 (22 bits), so fp32 multiply, widen, fp64 add
           // gives the bits of an fp64 multiply-add with two conversions fewer per element
           double part = 0.0;
@@ -308,198 +316,216 @@ __global__ __launch_bounds__((FUSED ? kWpuFusedUnits : kWpuUnits) * kWave, FUSED
   }
 
   int eslot = -1, ins_slot = -1;
-  double lscale = 0.0;
-  {
-    // ---- phase 2: softmax with the low-rank term, H2O bookkeeping, eviction choice -------------
-    {
-      double sc[NR2];
-      double M = -__builtin_inf();
+  double lscale = 0.0, pscale = 0.0, ascale = 0.0;
+  // ---- phase 2, first part: what the value stream needs, the exponentials e^{s_j - M} ------------
+  // The value rows are weighted with the exponentials as they are and the sum is scaled by
+  // 1 / den at the end, so the stream goes on while the rest of phase 2 (the low-rank term, the
+  // denominator, the H2O bookkeeping and the choice of the discarded pair: one dependent chain of
+  // fp64 reductions) is worked through in three parts between its first passes, each while the
+  // rows requested by the pass before it are on their way.
+  double sc[NR2];
+  double M = -__builtin_inf();
 #pragma unroll
-      for (int i = 0; i < NR2; ++i) {
-        const int j = lane + i * kWave;
-        sc[i] = j < rows ? s_sc[j] : -__builtin_inf();
-        M = fmax(M, sc[i]);
-      }
-      M = wave_allreduce(M, OpMax{});
-      double S = 0.0;
+  for (int i = 0; i < NR2; ++i) {
+    const int j = lane + i * kWave;
+    sc[i] = j < rows ? s_sc[j] : -__builtin_inf();
+    M = fmax(M, sc[i]);
+  }
+  M = wave_allreduce(M, OpMax{});
 #pragma unroll
-      for (int i = 0; i < NR2; ++i) {
-        const int j = lane + i * kWave;
-        sc[i] = j < rows ? exp_softmax_f64(sc[i] - M) : 0.0;
-        S += sc[i];
-      }
-      S = wave_allreduce(S, OpAdd{});                       // sparse part of the denominator, shifted
-      if constexpr (FUSED) {
-        // the feature-map entries, requested during the key stream: all there?
-        auto have_all = [&]() {
-          bool ok = true;
-#pragma unroll
-          for (int p = 0; p < NP; ++p)
-            ok = ok && __float_as_uint(pq[p]) != kMlpEmpty && __float_as_uint(pk[p]) != kMlpEmpty;
-          return __all(ok) != 0;
-        };
-        for (int spin = 0; !have_all() && spin < kWpuSpinLimit; ++spin) {
-          __builtin_amdgcn_s_sleep(32);
-          request_parts();
-        }
-        finish_maps();
-        request_tail();
-      }
-      // pending fold of z (Eq. 5), then phi(q) z^T
-      if (lane >= R) z_lane = 0.0;
-      if (!pend.fold) psie_lane = 0.f;
-      else if (pend.slot >= C) psie_lane = ppsi_lane;        // the previous step discarded its own pair
-      if (lane < R) {
-        if (pend.fold) {
-          z_lane += (double)psie_lane;
-          if (lead) a.z[(size_t)u * R + lane] = z_lane;
-        }
-        if (lead) {
-          if (pend.slot >= 0 && pend.slot < C) a.psi[((size_t)u * C + pend.slot) * R + lane] = ppsi_lane;
-          a.pend_psi[(size_t)u * R + lane] = npsi_lane;
-        }
-      }
-      const double fz = wave_allreduce(f_lane * z_lane, OpAdd{});
-      // den = phi(q) z^T + sum_j e^{s_j}, in whichever scaling cannot overflow:
-      //   M > 0 (or no low-rank term): everything times e^{-M};  M <= 0: unscaled, e^{M} <= 1
-      double pscale;
-      if (fz > 0.0 && M <= 0.0) {
-        const double w = exp_softmax_f64(M);
-        const double inv = 1.0 / (fz + w * S);
-        pscale = w * inv;
-        lscale = inv;
-      } else {
-        const double eM = (fz > 0.0) ? exp_softmax_f64(-M) : 0.0;
-        const double inv = 1.0 / (fz * eM + S);
-        pscale = inv;
-        lscale = eM * inv;
-      }
-      double ascale = pscale;
-      if (a.flags & LESSDEC_FLAG_SPARSE_DENOM) ascale = 1.0 / S;
-
-      const bool lambda = (a.flags & LESSDEC_FLAG_LAMBDA) != 0;
-      Cand best = cand_none();
-#pragma unroll
-      for (int i = 0; i < NR2; ++i) {
-        const int j = lane + i * kWave;
-        if (j < rows) {
-          const double e = sc[i];
-          s_p[j] = (float)(e * pscale);
-          double na = e * ascale;
-          int pj = n;
-          if (j < m) {
-            na += acc_pre[i];
-            pj = pos_pre[i];
-          }
-          sc[i] = na;
-          if (full) {
-            // H2O: every pair that is not among the Nr most recent competes on its score;
-            // Lambda-masking: the first Nh tokens never leave and the oldest of the others does
-            const bool is_cand = (j < m) ? (pj <= n - a.Nr && (!lambda || pj >= a.Nh)) : (a.Nr == 0);
-            const Cand cnd{lambda ? 0.0 : na, pj, j};
-            if (is_cand && cand_less(cnd, best)) best = cnd;
-          }
-        }
-      }
-      // argmin over (score, position): smallest score, then the oldest among equals
-      int epos = -1;
-      if (full) {
-        const double amin = wave_allreduce(best.acc, OpMin{});
-        const int pmin = wave_allreduce(best.acc == amin ? best.pos : INT_MAX, OpMinI{});
-        const unsigned long long win = __ballot(best.acc == amin && best.pos == pmin && best.slot >= 0);
-        if (win != 0ull) {
-          eslot = __builtin_amdgcn_readlane(best.slot, __ffsll((long long)win) - 1);
-          epos = pmin;
-        }
-      }
-      const bool evict = eslot >= 0;                         // eslot == m: the new pair itself
-      ins_slot = full ? ((evict && eslot < m) ? eslot : -1) : m;
-#pragma unroll
-      for (int i = 0; i < NR2; ++i) {
-        const int j = lane + i * kWave;
-        if (!lead) {
-        } else if (j < m) {
-          if (j != ins_slot) __builtin_nontemporal_store(sc[i], a.acc + (size_t)u * C + j);
-        } else if (j == m && ins_slot >= 0) {
-          a.acc[(size_t)u * C + ins_slot] = sc[i];
-          a.pos[(size_t)u * C + ins_slot] = n;
-        }
-      }
-      if (lane == 0 && lead) {
-        // what the next step has to finish: fold of the discarded pair and / or the slot write
-        a.pend_slot[u] = evict ? (eslot < m ? eslot : C) : (m | kPendNoFold);
-        if (a.evicted_pos) a.evicted_pos[u] = evict ? epos : -1;
-        a.n_seen[u] = n + 1;
-      }
-    }
+  for (int i = 0; i < NR2; ++i) {
+    const int j = lane + i * kWave;
+    sc[i] = j < rows ? exp_softmax_f64(sc[i] - M) : 0.0;
+    if (j < rows) s_p[j] = (float)sc[i];
   }
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
   __builtin_amdgcn_wave_barrier();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
-  // ---- phase 3: p . V as the value rows arrive ------------------------------------------------------
+  // second part: low-rank term and denominator
+  auto denominators = [&]() __attribute__((always_inline)) {
+    double S = 0.0;
+#pragma unroll
+    for (int i = 0; i < NR2; ++i) S += sc[i];
+    S = wave_allreduce(S, OpAdd{});                         // sparse part of the denominator, shifted
+    if constexpr (FUSED) {
+      // the feature-map entries, requested during the key stream: all there?
+      auto have_all = [&]() {
+        bool ok = true;
+#pragma unroll
+        for (int p = 0; p < NP; ++p)
+          ok = ok && __float_as_uint(pq[p]) != kMlpEmpty && __float_as_uint(pk[p]) != kMlpEmpty;
+        return __all(ok) != 0;
+      };
+      for (int spin = 0; !have_all() && spin < kWpuSpinLimit; ++spin) {
+        __builtin_amdgcn_s_sleep(32);
+        request_parts();
+      }
+      finish_maps();
+      request_tail();
+    }
+    // pending fold of z (Eq. 5), then phi(q) z^T
+    if (lane >= R) z_lane = 0.0;
+    if (!pend.fold) psie_lane = 0.f;
+    else if (pend.slot >= C) psie_lane = ppsi_lane;        // the previous step discarded its own pair
+    if (lane < R) {
+      if (pend.fold) {
+        z_lane += (double)psie_lane;
+        if (lead) a.z[(size_t)u * R + lane] = z_lane;
+      }
+      if (lead) {
+        if (pend.slot >= 0 && pend.slot < C) a.psi[((size_t)u * C + pend.slot) * R + lane] = ppsi_lane;
+        a.pend_psi[(size_t)u * R + lane] = npsi_lane;
+      }
+    }
+    const double fz = wave_allreduce(f_lane * z_lane, OpAdd{});
+    // den = phi(q) z^T + sum_j e^{s_j}, in whichever scaling cannot overflow:
+    //   M > 0 (or no low-rank term): everything times e^{-M};  M <= 0: unscaled, e^{M} <= 1
+    if (fz > 0.0 && M <= 0.0) {
+      const double w = exp_softmax_f64(M);
+      const double inv = 1.0 / (fz + w * S);
+      pscale = w * inv;
+      lscale = inv;
+    } else {
+      const double eM = (fz > 0.0) ? exp_softmax_f64(-M) : 0.0;
+      const double inv = 1.0 / (fz * eM + S);
+      pscale = inv;
+      lscale = eM * inv;
+    }
+    ascale = pscale;
+    if (a.flags & LESSDEC_FLAG_SPARSE_DENOM) ascale = 1.0 / S;
+    if constexpr (!SPLIT) request_scores();
+  };
+
+  // third part: H2O bookkeeping and the choice of the discarded pair; its value row is asked for
+  // again (the stream may have passed it already) and parked in phase 4
+  u4v pv_row = {0u, 0u, 0u, 0u};
+  auto bookkeeping = [&]() __attribute__((always_inline)) {
+    const bool lambda = (a.flags & LESSDEC_FLAG_LAMBDA) != 0;
+    Cand best = cand_none();
+#pragma unroll
+    for (int i = 0; i < NR2; ++i) {
+      const int j = lane + i * kWave;
+      if (j < rows) {
+        double na = sc[i] * ascale;
+        int pj = n;
+        if (j < m) {
+          na += acc_pre[i];
+          pj = pos_pre[i];
+        }
+        sc[i] = na;
+        if (full) {
+          // H2O: every pair that is not among the Nr most recent competes on its score;
+          // Lambda-masking: the first Nh tokens never leave and the oldest of the others does
+          const bool is_cand = (j < m) ? (pj <= n - a.Nr && (!lambda || pj >= a.Nh)) : (a.Nr == 0);
+          const Cand cnd{lambda ? 0.0 : na, pj, j};
+          if (is_cand && cand_less(cnd, best)) best = cnd;
+        }
+      }
+    }
+    // argmin over (score, position): smallest score, then the oldest among equals
+    int epos = -1;
+    if (full) {
+      const double amin = wave_allreduce(best.acc, OpMin{});
+      const int pmin = wave_allreduce(best.acc == amin ? best.pos : INT_MAX, OpMinI{});
+      const unsigned long long win = __ballot(best.acc == amin && best.pos == pmin && best.slot >= 0);
+      if (win != 0ull) {
+        eslot = __builtin_amdgcn_readlane(best.slot, __ffsll((long long)win) - 1);
+        epos = pmin;
+      }
+    }
+    const bool evict = eslot >= 0;                         // eslot == m: the new pair itself
+    ins_slot = full ? ((evict && eslot < m) ? eslot : -1) : m;
+    {
+      // unconditional, from row 0 where no cached pair leaves
+      const __amdgpu_buffer_rsrc_t rv = __builtin_amdgcn_make_buffer_rsrc(vc, 0, C * D * (int)sizeof(T), 0x00020000);
+      const int er = (evict && eslot < m) ? eslot : 0;
+      pv_row = __builtin_amdgcn_raw_buffer_load_b128(rv, lr * 16, er * (D * (int)sizeof(T)), 0);
+    }
+#pragma unroll
+    for (int i = 0; i < NR2; ++i) {
+      const int j = lane + i * kWave;
+      if (!lead) {
+      } else if (j < m) {
+        if (j != ins_slot) __builtin_nontemporal_store(sc[i], a.acc + (size_t)u * C + j);
+      } else if (j == m && ins_slot >= 0) {
+        a.acc[(size_t)u * C + ins_slot] = sc[i];
+        a.pos[(size_t)u * C + ins_slot] = n;
+      }
+    }
+    if (lane == 0 && lead) {
+      // what the next step has to finish: fold of the discarded pair and / or the slot write
+      a.pend_slot[u] = evict ? (eslot < m ? eslot : C) : (m | kPendNoFold);
+      if (a.evicted_pos) a.evicted_pos[u] = evict ? epos : -1;
+      a.n_seen[u] = n + 1;
+    }
+  };
+
+  // ---- phase 3: e^{s - M} . V as the value rows arrive ------------------------------------------------
   float o[EPL];
 #pragma unroll
   for (int i = 0; i < EPL; ++i) o[i] = 0.f;
   float fh[4] = {0.f, 0.f, 0.f, 0.f};                        // phi(q) H, this lane's columns and rows
-  uint4 pv_keep = {0u, 0u, 0u, 0u};
-  bool pv_have = false;
-  {
-    int base = 0;
-    do {                                                     // nit >= 1
+  auto value_pass = [&](int base) __attribute__((always_inline)) {
 #pragma unroll
-      for (int j = 0; j < DEPTH; ++j) {
-        const int s = base + j;
-        if (s < nit) {
-          const int r = (s * nw + wv) * RPI + rb;
-          Vec vv;
-          __builtin_memcpy(&vv.raw, &buf[j], 16);
-          if (r == m) vv = vnv;                              // the appended pair's value row
-          if (r < rows) {
-            const float p = s_p[r];
+    for (int j = 0; j < DEPTH; ++j) {
+      const int s = base + j;
+      if (s < nit) {
+        const int r = (s * nw + wv) * RPI + rb;
+        Vec vv;
+        __builtin_memcpy(&vv.raw, &buf[j], 16);
+        if (r < m) {
+          const float p = s_p[r];
 #pragma unroll
-            for (int i = 0; i < EPL; ++i) o[i] = fmaf(p, Store<T>::get(vv, i), o[i]);
-          }
-          if (r == eslot) {                                  // the discarded pair's value row
-            if constexpr (SPLIT) {
-              pv_keep = vv.raw;                              // stored once the lead wave has read the old one
-              pv_have = true;
-            } else {
-              *reinterpret_cast<uint4 *>(reinterpret_cast<T *>(a.pend_v) + (size_t)u * D + lr * EPL) = vv.raw;
-            }
-          }
-        }
-        buf[j] = issue(nitp + s + DEPTH);
-        __builtin_amdgcn_sched_barrier(0);
-      }
-      if (base == 0) {
-        // H and the pending value row were requested before the loads this pass re-issued, so
-        // they are back: fold the pending pair into H (Eq. 4) and send H on its way while the
-        // value rows still stream, then phi(q) H for this lane's columns and rows.
-        const float f32 = (float)f_lane;
-        const __half2 *pvh = reinterpret_cast<const __half2 *>(&pend_v_h);
-        const float2 pv01 = __half22float2(pvh[0]), pv23 = __half22float2(pvh[1]);
-        float *Hu = a.H + (size_t)u * R * D;
-#pragma unroll
-        for (int i = 0; i < HR; ++i) {
-          const int r = NHB * i + hb;                        // differs between the halves of the wave
-          const int rc = r < R ? r : R - 1;
-          const float fr = r < R ? __shfl(f32, rc) : 0.f;
-          const float pe = __shfl(psie_lane, rc);
-          if (pend.fold) {
-            hreg[i].x = fmaf(pe, pv01.x, hreg[i].x);
-            hreg[i].y = fmaf(pe, pv01.y, hreg[i].y);
-            hreg[i].z = fmaf(pe, pv23.x, hreg[i].z);
-            hreg[i].w = fmaf(pe, pv23.y, hreg[i].w);
-            if (r < R && lead) store_nt(Hu + (size_t)r * D + col0, hreg[i]);
-          }
-          fh[0] = fmaf(fr, hreg[i].x, fh[0]);
-          fh[1] = fmaf(fr, hreg[i].y, fh[1]);
-          fh[2] = fmaf(fr, hreg[i].z, fh[2]);
-          fh[3] = fmaf(fr, hreg[i].w, fh[3]);
+          for (int i = 0; i < EPL; ++i) o[i] = fmaf(p, Store<T>::get(vv, i), o[i]);
         }
       }
-    } while ((base += DEPTH) < nit);
+      buf[j] = issue(nitp + s + DEPTH);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+  // fourth part: H and the pending value row are back (requested before the loads of the pass
+  // before this): fold the pending pair into H (Eq. 4) and send H on its way while the value rows
+  // still stream, then phi(q) H for this lane's columns and rows.
+  auto fold_state = [&]() __attribute__((always_inline)) {
+    const float f32 = (float)f_lane;
+    const __half2 *pvh = reinterpret_cast<const __half2 *>(&pend_v_h);
+    const float2 pv01 = __half22float2(pvh[0]), pv23 = __half22float2(pvh[1]);
+    float *Hu = a.H + (size_t)u * R * D;
+#pragma unroll
+    for (int i = 0; i < HR; ++i) {
+      const int r = NHB * i + hb;                            // differs between the halves of the wave
+      const int rc = r < R ? r : R - 1;
+      const float fr = r < R ? __shfl(f32, rc) : 0.f;
+      const float pe = __shfl(psie_lane, rc);
+      if (pend.fold) {
+        hreg[i].x = fmaf(pe, pv01.x, hreg[i].x);
+        hreg[i].y = fmaf(pe, pv01.y, hreg[i].y);
+        hreg[i].z = fmaf(pe, pv23.x, hreg[i].z);
+        hreg[i].w = fmaf(pe, pv23.y, hreg[i].w);
+        if (r < R && lead) store_nt(Hu + (size_t)r * D + col0, hreg[i]);
+      }
+      fh[0] = fmaf(fr, hreg[i].x, fh[0]);
+      fh[1] = fmaf(fr, hreg[i].y, fh[1]);
+      fh[2] = fmaf(fr, hreg[i].z, fh[2]);
+      fh[3] = fmaf(fr, hreg[i].w, fh[3]);
+    }
+  };
+  // Passes past the end of the stream consume nothing and request rows outside the buffer's
+  // range, which fetches nothing: the three passes always run, so that no load sits under a
+  // condition.
+  value_pass(0);
+  denominators();
+  value_pass(DEPTH);
+  bookkeeping();
+  value_pass(2 * DEPTH);
+  fold_state();
+  for (int base = 3 * DEPTH; base < nit; base += DEPTH) value_pass(base);
+  // the appended pair's value row
+  if (lead && rb == 0) {
+    const float p = s_p[m];
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) o[i] = fmaf(p, Store<T>::get(vnv, i), o[i]);
   }
   {
     // The RPI row groups hold partial sums of the same 8 columns.  First stage (partner at
@@ -528,7 +554,6 @@ __global__ __launch_bounds__((FUSED ? kWpuFusedUnits : kWpuUnits) * kWave, FUSED
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
       __builtin_amdgcn_s_barrier();
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
-      if (pv_have) *reinterpret_cast<uint4 *>(reinterpret_cast<T *>(a.pend_v) + (size_t)u * D + lr * EPL) = pv_keep;
       if (!lead) return;
       const float4 first = *reinterpret_cast<const float4 *>(s_o + col0);
       o[0] = first.x; o[1] = first.y; o[2] = first.z; o[3] = first.w;
@@ -541,9 +566,16 @@ __global__ __launch_bounds__((FUSED ? kWpuFusedUnits : kWpuUnits) * kWave, FUSED
     // ---- phase 4: output, in-place insert ---------------------------------------------------------
     if (hb == 0) {
       __half2 res[2];
-      res[0] = __floats2half2_rn((float)((double)o[0] + lscale * (double)fh[0]), (float)((double)o[1] + lscale * (double)fh[1]));
-      res[1] = __floats2half2_rn((float)((double)o[2] + lscale * (double)fh[2]), (float)((double)o[3] + lscale * (double)fh[3]));
+      res[0] = __floats2half2_rn((float)(pscale * (double)o[0] + lscale * (double)fh[0]), (float)(pscale * (double)o[1] + lscale * (double)fh[1]));
+      res[1] = __floats2half2_rn((float)(pscale * (double)o[2] + lscale * (double)fh[2]), (float)(pscale * (double)o[3] + lscale * (double)fh[3]));
       *reinterpret_cast<uint2 *>(reinterpret_cast<T *>(a.out) + (size_t)u * xs_ + col0) = *reinterpret_cast<const uint2 *>(res);
+    }
+    // the discarded pair's value row, parked for the next step's fold (before the insert below
+    // overwrites the row it was read from)
+    if (eslot >= 0 && rb == 0) {
+      uint4 row = vnv.raw;
+      if (eslot < m) __builtin_memcpy(&row, &pv_row, 16);
+      *reinterpret_cast<uint4 *>(reinterpret_cast<T *>(a.pend_v) + (size_t)u * D + lr * EPL) = row;
     }
     if (ins_slot >= 0 && rb == 0) {
       store_nt(kc + (size_t)ins_slot * D + lr * EPL, knv.raw);
