@@ -108,8 +108,8 @@ __device__ inline void mlp_load_row(const __half *xr, int g, v8h (&bx)[D / 32])
 // it when this job runs inside the attention launch.  Rows are padded by 16 bytes in the LDS so
 // that the 16 lanes of an operand read (same 16-byte column, 16 rows) fall into different banks.
 // x_stride: elements from unit u's row of q / k to unit u + 1's (D when the rows are packed).
-// out[((map * nparts + part) * U + u) * mlp_entry_stride(R) + r]: part's share of the layer-2 pre-activation r of
-// unit u.  COHERENT: the readers run in the same launch, possibly on another XCD whose L2 is not
+// out[((u * 2 + map) * nparts + part) * mlp_entry_stride(R) + r]: part's share of the layer-2 pre-activation r of
+// unit u (a unit's entries lie together: its wave reads and clears them as one piece).  COHERENT: the readers run in the same launch, possibly on another XCD whose L2 is not
 // coherent with this one's: the results go out as device-scope stores (written through).
 template <int D, bool COHERENT>
 __device__ inline void mlp_parts_job(const __half *q, const __half *k, const __half *Wq1, const __half *Wk1,
@@ -178,8 +178,7 @@ __device__ inline void mlp_parts_job(const __half *q, const __half *k, const __h
   // c2[w]: output r = 4 g + w of row c
   const int rp = mlp_entry_stride(R);
   if (rowv && 4 * g < rp) {                                // outputs past the rank are not kept
-    const size_t U = (size_t)B * Hh;
-    float *dst = out + (((size_t)map * nparts + part) * U + u) * rp + 4 * g;
+    float *dst = out + ((u * 2 + map) * nparts + part) * rp + 4 * g;
     if constexpr (COHERENT) {
       unsigned long long lo, hi;
       const float2 a = {c2[0], c2[1]}, bq = {c2[2], c2[3]};

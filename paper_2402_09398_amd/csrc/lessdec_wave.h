@@ -85,6 +85,35 @@ __device__ inline void store_nt(T *p, const uint4 &v)
   __builtin_nontemporal_store(t, reinterpret_cast<u4v *>(p));
 }
 
+// Stores of state that go through the L2 to memory as they are issued (system scope).  A line
+// that stays dirty in an L2 is written back when the kernel ends, before the next launch can
+// start: with 16 MB written per launch that takes 2.4 us after plain stores, 1.3 us after
+// non-temporal ones and under 0.1 us after these.
+__device__ inline void store_wt(double *p, double v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM); }
+__device__ inline void store_wt(float *p, float v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM); }
+__device__ inline void store_wt(int *p, int v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM); }
+__device__ inline void store_wt8(void *p, const uint2 &v)
+{
+  unsigned long long t;
+  __builtin_memcpy(&t, &v, 8);
+  __hip_atomic_store(reinterpret_cast<unsigned long long *>(p), t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+// 16 bytes per lane at base + offset: base must be the same for the whole wave (it goes into a
+// buffer descriptor, which is how a 16-byte store gets its scope bits)
+__device__ inline void store_wt16(void *base, int offset_bytes, const uint4 &v)
+{
+  const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(base, 0, 0x7fffffff, 0x00020000);
+  u4v t;
+  __builtin_memcpy(&t, &v, 16);
+  __builtin_amdgcn_raw_buffer_store_b128(t, rs, offset_bytes, 0, 17 /* sc0 sc1 */);
+}
+__device__ inline void store_wt16(void *base, int offset_bytes, const float4 &v)
+{
+  uint4 t;
+  __builtin_memcpy(&t, &v, 16);
+  store_wt16(base, offset_bytes, t);
+}
+
 template <typename T>
 __device__ inline typename Store<T>::Vec buffer_load_nt(__amdgpu_buffer_rsrc_t rsrc, int voffset, int soffset)
 {

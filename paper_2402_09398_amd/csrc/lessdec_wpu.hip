@@ -142,8 +142,8 @@ __global__ __launch_bounds__((FUSED ? kWpuFusedUnits : kWpuUnits) * kWave, FUSED
 #pragma unroll
     for (int p = 0; p < NP; ++p) {
       const int pc = p < nparts ? p : nparts - 1;
-      const float *eq = a.mlp_parts + ((size_t)pc * a.U + u) * rp + rl;
-      const float *ek = a.mlp_parts + ((size_t)(nparts + pc) * a.U + u) * rp + rl;
+      const float *eq = a.mlp_parts + ((size_t)u * 2 * nparts + pc) * rp + rl;
+      const float *ek = a.mlp_parts + (((size_t)u * 2 + 1) * nparts + pc) * rp + rl;
       if constexpr (FUSED) {
         pq[p] = __hip_atomic_load(eq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         pk[p] = __hip_atomic_load(ek, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -240,8 +240,8 @@ __global__ __launch_bounds__((FUSED ? kWpuFusedUnits : kWpuUnits) * kWave, FUSED
         }
       }
       for (int p = NP; p < nparts; ++p) {                  // hidden widths above 512 (never FUSED)
-        sq += (double)a.mlp_parts[((size_t)p * a.U + u) * rp + rl];
-        sk += (double)a.mlp_parts[((size_t)(nparts + p) * a.U + u) * rp + rl];
+        sq += (double)a.mlp_parts[((size_t)u * 2 * nparts + p) * rp + rl];
+        sk += (double)a.mlp_parts[(((size_t)u * 2 + 1) * nparts + p) * rp + rl];
       }
       f_lane = lane < R ? fabs(gelu_poly_f64(sq)) : 0.0;   // last activation of Eq. 1
       const double h2 = gelu_poly_f64(sk);                 // lane r < R; Eq. 2: |W3 gelu(.)|
@@ -250,14 +250,6 @@ __global__ __launch_bounds__((FUSED ? kWpuFusedUnits : kWpuUnits) * kWave, FUSED
       for (int j = 0; j < RM; ++j)
         if (j < R) acc3 = fma(readlane_v(h2, j), (double)__half2float(w3[j]), acc3);
       npsi_lane = (float)fabs(acc3);
-      if constexpr (!SPLIT) {
-        // lane = (map * nparts + part) * quads + quad of the part's entries
-        const int quads = rp / 4;
-        for (int e = lane; e < 2 * nparts * quads; e += kWave) {
-          const u4v empty = {kMlpEmpty, kMlpEmpty, kMlpEmpty, kMlpEmpty};
-          __builtin_nontemporal_store(empty, reinterpret_cast<u4v *>(a.mlp_out + ((size_t)(e / quads) * a.U + u) * rp) + e % quads);
-        }
-      }
     };
     if constexpr (FUSED) {
       // The entries are requested before the last pass of the key stream and first looked at after
@@ -350,16 +342,23 @@ __global__ __launch_bounds__((FUSED ? kWpuFusedUnits : kWpuUnits) * kWave, FUSED
     S = wave_allreduce(S, OpAdd{});                         // sparse part of the denominator, shifted
     if constexpr (FUSED) {
       // the feature-map entries, requested during the key stream: all there?
+      // (every entry is looked at, without a way out after the first empty one: a way out would
+      // leave the later requests unaccounted for, and whoever uses them next would wait for
+      // everything in flight)
       auto have_all = [&]() {
-        bool ok = true;
+        unsigned missing = 0;
 #pragma unroll
         for (int p = 0; p < NP; ++p)
-          ok = ok && __float_as_uint(pq[p]) != kMlpEmpty && __float_as_uint(pk[p]) != kMlpEmpty;
-        return __all(ok) != 0;
+          missing |= (unsigned)(__float_as_uint(pq[p]) == kMlpEmpty) | (unsigned)(__float_as_uint(pk[p]) == kMlpEmpty);
+        return __all(missing == 0u) != 0;
       };
-      for (int spin = 0; !have_all() && spin < kWpuSpinLimit; ++spin) {
+      // (the first look stands outside the loop: a look at the loop's head would have to wait
+      // for whatever the loop body may have requested, which is everything in flight)
+      bool have = have_all();
+      for (int spin = 0; !have && spin < kWpuSpinLimit; ++spin) {
         __builtin_amdgcn_s_sleep(32);
         request_parts();
+        have = have_all();
       }
       finish_maps();
       request_tail();
@@ -368,16 +367,7 @@ __global__ __launch_bounds__((FUSED ? kWpuFusedUnits : kWpuUnits) * kWave, FUSED
     if (lane >= R) z_lane = 0.0;
     if (!pend.fold) psie_lane = 0.f;
     else if (pend.slot >= C) psie_lane = ppsi_lane;        // the previous step discarded its own pair
-    if (lane < R) {
-      if (pend.fold) {
-        z_lane += (double)psie_lane;
-        if (lead) a.z[(size_t)u * R + lane] = z_lane;
-      }
-      if (lead) {
-        if (pend.slot >= 0 && pend.slot < C) a.psi[((size_t)u * C + pend.slot) * R + lane] = ppsi_lane;
-        a.pend_psi[(size_t)u * R + lane] = npsi_lane;
-      }
-    }
+    if (lane < R && pend.fold) z_lane += (double)psie_lane;
     const double fz = wave_allreduce(f_lane * z_lane, OpAdd{});
     // den = phi(q) z^T + sum_j e^{s_j}, in whichever scaling cannot overflow:
     //   M > 0 (or no low-rank term): everything times e^{-M};  M <= 0: unscaled, e^{M} <= 1
@@ -400,6 +390,7 @@ __global__ __launch_bounds__((FUSED ? kWpuFusedUnits : kWpuUnits) * kWave, FUSED
   // third part: H2O bookkeeping and the choice of the discarded pair; its value row is asked for
   // again (the stream may have passed it already) and parked in phase 4
   u4v pv_row = {0u, 0u, 0u, 0u};
+  int epos = -1;
   auto bookkeeping = [&]() __attribute__((always_inline)) {
     const bool lambda = (a.flags & LESSDEC_FLAG_LAMBDA) != 0;
     Cand best = cand_none();
@@ -424,7 +415,6 @@ __global__ __launch_bounds__((FUSED ? kWpuFusedUnits : kWpuUnits) * kWave, FUSED
       }
     }
     // argmin over (score, position): smallest score, then the oldest among equals
-    int epos = -1;
     if (full) {
       const double amin = wave_allreduce(best.acc, OpMin{});
       const int pmin = wave_allreduce(best.acc == amin ? best.pos : INT_MAX, OpMinI{});
@@ -441,23 +431,6 @@ __global__ __launch_bounds__((FUSED ? kWpuFusedUnits : kWpuUnits) * kWave, FUSED
       const __amdgpu_buffer_rsrc_t rv = __builtin_amdgcn_make_buffer_rsrc(vc, 0, C * D * (int)sizeof(T), 0x00020000);
       const int er = (evict && eslot < m) ? eslot : 0;
       pv_row = __builtin_amdgcn_raw_buffer_load_b128(rv, lr * 16, er * (D * (int)sizeof(T)), 0);
-    }
-#pragma unroll
-    for (int i = 0; i < NR2; ++i) {
-      const int j = lane + i * kWave;
-      if (!lead) {
-      } else if (j < m) {
-        if (j != ins_slot) __builtin_nontemporal_store(sc[i], a.acc + (size_t)u * C + j);
-      } else if (j == m && ins_slot >= 0) {
-        a.acc[(size_t)u * C + ins_slot] = sc[i];
-        a.pos[(size_t)u * C + ins_slot] = n;
-      }
-    }
-    if (lane == 0 && lead) {
-      // what the next step has to finish: fold of the discarded pair and / or the slot write
-      a.pend_slot[u] = evict ? (eslot < m ? eslot : C) : (m | kPendNoFold);
-      if (a.evicted_pos) a.evicted_pos[u] = evict ? epos : -1;
-      a.n_seen[u] = n + 1;
     }
   };
 
@@ -491,7 +464,6 @@ __global__ __launch_bounds__((FUSED ? kWpuFusedUnits : kWpuUnits) * kWave, FUSED
     const float f32 = (float)f_lane;
     const __half2 *pvh = reinterpret_cast<const __half2 *>(&pend_v_h);
     const float2 pv01 = __half22float2(pvh[0]), pv23 = __half22float2(pvh[1]);
-    float *Hu = a.H + (size_t)u * R * D;
 #pragma unroll
     for (int i = 0; i < HR; ++i) {
       const int r = NHB * i + hb;                            // differs between the halves of the wave
@@ -503,7 +475,6 @@ __global__ __launch_bounds__((FUSED ? kWpuFusedUnits : kWpuUnits) * kWave, FUSED
         hreg[i].y = fmaf(pe, pv01.y, hreg[i].y);
         hreg[i].z = fmaf(pe, pv23.x, hreg[i].z);
         hreg[i].w = fmaf(pe, pv23.y, hreg[i].w);
-        if (r < R && lead) store_nt(Hu + (size_t)r * D + col0, hreg[i]);
       }
       fh[0] = fmaf(fr, hreg[i].x, fh[0]);
       fh[1] = fmaf(fr, hreg[i].y, fh[1]);
@@ -563,26 +534,61 @@ __global__ __launch_bounds__((FUSED ? kWpuFusedUnits : kWpuUnits) * kWave, FUSED
       }
     }
 
-    // ---- phase 4: output, in-place insert ---------------------------------------------------------
+    // ---- phase 4: output, then the unit's new state and the in-place insert -------------------------
+    // Every store of the step stands here, behind the last load: the memory counter of a wave
+    // runs in order, so a store in mid-stream holds up every row requested after it until the
+    // store has been acknowledged.  (SPLIT: only the lead wave gets here.)
     if (hb == 0) {
       __half2 res[2];
       res[0] = __floats2half2_rn((float)(pscale * (double)o[0] + lscale * (double)fh[0]), (float)(pscale * (double)o[1] + lscale * (double)fh[1]));
       res[1] = __floats2half2_rn((float)(pscale * (double)o[2] + lscale * (double)fh[2]), (float)(pscale * (double)o[3] + lscale * (double)fh[3]));
-      *reinterpret_cast<uint2 *>(reinterpret_cast<T *>(a.out) + (size_t)u * xs_ + col0) = *reinterpret_cast<const uint2 *>(res);
+      store_wt8(reinterpret_cast<T *>(a.out) + (size_t)u * xs_ + col0, *reinterpret_cast<const uint2 *>(res));
+    }
+    if (pend.fold) {                                         // H with the pending pair folded in (Eq. 4)
+#pragma unroll
+      for (int i = 0; i < HR; ++i) {
+        const int r = NHB * i + hb;
+        if (r < R) store_wt16(a.H + (size_t)u * R * D, (r * D + col0) * (int)sizeof(float), hreg[i]);
+      }
+    }
+    if (lane < R) {
+      if (pend.fold) store_wt(a.z + (size_t)u * R + lane, z_lane);
+      if (pend.slot >= 0 && pend.slot < C) store_wt(a.psi + ((size_t)u * C + pend.slot) * R + lane, ppsi_lane);
+      store_wt(a.pend_psi + (size_t)u * R + lane, npsi_lane);
+    }
+#pragma unroll
+    for (int i = 0; i < NR2; ++i) {
+      const int j = lane + i * kWave;
+      if (j < m) {
+        if (j != ins_slot) store_wt(a.acc + (size_t)u * C + j, sc[i]);
+      } else if (j == m && ins_slot >= 0) {
+        store_wt(a.acc + (size_t)u * C + ins_slot, sc[i]);
+        store_wt(a.pos + (size_t)u * C + ins_slot, n);
+      }
+    }
+    if (lane == 0) {
+      // what the next step has to finish: fold of the discarded pair and / or the slot write
+      store_wt(a.pend_slot + u, eslot >= 0 ? (eslot < m ? eslot : C) : (m | kPendNoFold));
+      if (a.evicted_pos) store_wt(a.evicted_pos + u, eslot >= 0 ? epos : -1);
+      store_wt(a.n_seen + u, n + 1);
+    }
+    if constexpr (!SPLIT) {
+      // the feature-map entries go back empty (the unit's 2 * nparts entries lie together)
+      for (int e = lane; e < 2 * nparts * (rp / 4); e += kWave)
+        store_wt16(a.mlp_out + (size_t)u * 2 * nparts * rp, e * 16, uint4{kMlpEmpty, kMlpEmpty, kMlpEmpty, kMlpEmpty});
     }
     // the discarded pair's value row, parked for the next step's fold (before the insert below
     // overwrites the row it was read from)
     if (eslot >= 0 && rb == 0) {
       uint4 row = vnv.raw;
       if (eslot < m) __builtin_memcpy(&row, &pv_row, 16);
-      *reinterpret_cast<uint4 *>(reinterpret_cast<T *>(a.pend_v) + (size_t)u * D + lr * EPL) = row;
+      store_wt16(reinterpret_cast<T *>(a.pend_v) + (size_t)u * D, lr * EPL * (int)sizeof(T), row);
     }
     if (ins_slot >= 0 && rb == 0) {
-      store_nt(kc + (size_t)ins_slot * D + lr * EPL, knv.raw);
-      store_nt(vc + (size_t)ins_slot * D + lr * EPL, vnv.raw);
+      store_wt16(kc + (size_t)ins_slot * D, lr * EPL * (int)sizeof(T), knv.raw);
+      store_wt16(vc + (size_t)ins_slot * D, lr * EPL * (int)sizeof(T), vnv.raw);
     }
   }
-
 }
 
 // (batch and heads below 65536 each: the kernel takes them packed in one preloaded argument)
