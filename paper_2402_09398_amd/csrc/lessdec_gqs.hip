@@ -174,16 +174,7 @@ __global__ __launch_bounds__(kGqsMaxHeads * kWave) void gqs_step_kernel(void *k_
     if (lane >= R) z_lane = 0.0;
     if (!pend.fold) psie_lane = 0.f;
     else if (pend.slot >= C) psie_lane = ppsi_lane;          // the previous step discarded its own pair
-    if (lane < R) {
-      if (pend.fold) {
-        z_lane += (double)psie_lane;
-        if (lead) a.z[(size_t)u * R + lane] = z_lane;
-      }
-      if (lead) {
-        if (pend.slot >= 0 && pend.slot < C) a.psi[((size_t)u * C + pend.slot) * R + lane] = ppsi_lane;
-        a.pend_psi[(size_t)u * R + lane] = npsi_lane;
-      }
-    }
+    if (lane < R && pend.fold) z_lane += (double)psie_lane;
     const double fz = wave_allreduce(f_lane * z_lane, OpAdd{});
     double pscale;
     if (fz > 0.0 && M <= 0.0) {
@@ -214,10 +205,10 @@ __global__ __launch_bounds__(kGqsMaxHeads * kWave) void gqs_step_kernel(void *k_
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 
   // ---- phase 2b: accumulated scores and the eviction, by every wave for itself ----------------------
-  int eslot = -1, ins_slot = -1;
+  int eslot = -1, ins_slot = -1, epos = -1;
+  double na_[NR2];
   {
     const bool lambda = (a.flags & LESSDEC_FLAG_LAMBDA) != 0;
-    double na_[NR2];
     Cand best = cand_none();
 #pragma unroll
     for (int i = 0; i < NR2; ++i) {
@@ -240,7 +231,6 @@ __global__ __launch_bounds__(kGqsMaxHeads * kWave) void gqs_step_kernel(void *k_
         }
       }
     }
-    int epos = -1;
     if (full) {
       const double amin = wave_allreduce(best.acc, OpMin{});
       const int pmin = wave_allreduce(best.acc == amin ? best.pos : INT_MAX, OpMinI{});
@@ -252,23 +242,6 @@ __global__ __launch_bounds__(kGqsMaxHeads * kWave) void gqs_step_kernel(void *k_
     }
     const bool evict = eslot >= 0;                           // eslot == m: the new pair itself
     ins_slot = full ? ((evict && eslot < m) ? eslot : -1) : m;
-    if (lead) {
-#pragma unroll
-      for (int i = 0; i < NR2; ++i) {
-        const int j = lane + i * kWave;
-        if (j < m) {
-          if (j != ins_slot) __builtin_nontemporal_store(na_[i], a.acc + (size_t)u * C + j);
-        } else if (j == m && ins_slot >= 0) {
-          a.acc[(size_t)u * C + ins_slot] = na_[i];
-          a.pos[(size_t)u * C + ins_slot] = n;
-        }
-      }
-      if (lane == 0) {
-        a.pend_slot[u] = evict ? (eslot < m ? eslot : C) : (m | kPendNoFold);
-        if (a.evicted_pos) a.evicted_pos[u] = evict ? epos : -1;
-        a.n_seen[u] = n + 1;
-      }
-    }
   }
 
   // ---- phase 3: p . V as the value rows arrive ------------------------------------------------------
@@ -276,6 +249,7 @@ __global__ __launch_bounds__(kGqsMaxHeads * kWave) void gqs_step_kernel(void *k_
 #pragma unroll
   for (int i = 0; i < EPL; ++i) o[i] = 0.f;
   float fh[4] = {0.f, 0.f, 0.f, 0.f};                        // phi(q) H, this lane's columns and rows
+  uint4 pv_keep = {0u, 0u, 0u, 0u};                          // the discarded pair's value row
   {
     int base = 0;
     do {                                                     // nit >= 1
@@ -292,8 +266,7 @@ __global__ __launch_bounds__(kGqsMaxHeads * kWave) void gqs_step_kernel(void *k_
 #pragma unroll
             for (int i = 0; i < EPL; ++i) o[i] = fmaf(p, Store<T>::get(vv, i), o[i]);
           }
-          if (lead && r == eslot)                            // the discarded pair's value row
-            *reinterpret_cast<uint4 *>(reinterpret_cast<T *>(a.pend_v) + (size_t)u * D + lr * EPL) = vv.raw;
+          if (r == eslot) pv_keep = vv.raw;
         }
         buf[j] = issue(nitp + s + DEPTH);
         __builtin_amdgcn_sched_barrier(0);
@@ -303,7 +276,6 @@ __global__ __launch_bounds__(kGqsMaxHeads * kWave) void gqs_step_kernel(void *k_
         const float f32 = (float)f_lane;
         const __half2 *pvh = reinterpret_cast<const __half2 *>(&pend_v_h);
         const float2 pv01 = __half22float2(pvh[0]), pv23 = __half22float2(pvh[1]);
-        float *Hu = a.H + (size_t)u * R * D;
 #pragma unroll
         for (int i = 0; i < HR; ++i) {
           const int r = NHB * i + hb;
@@ -315,7 +287,6 @@ __global__ __launch_bounds__(kGqsMaxHeads * kWave) void gqs_step_kernel(void *k_
             hreg[i].y = fmaf(pe, pv01.y, hreg[i].y);
             hreg[i].z = fmaf(pe, pv23.x, hreg[i].z);
             hreg[i].w = fmaf(pe, pv23.y, hreg[i].w);
-            if (r < R && lead) store_nt(Hu + (size_t)r * D + col0, hreg[i]);
           }
           fh[0] = fmaf(fr, hreg[i].x, fh[0]);
           fh[1] = fmaf(fr, hreg[i].y, fh[1]);
@@ -347,7 +318,42 @@ __global__ __launch_bounds__(kGqsMaxHeads * kWave) void gqs_step_kernel(void *k_
     __half2 res[2];
     res[0] = __floats2half2_rn((float)((double)o[0] + lscale * (double)fh[0]), (float)((double)o[1] + lscale * (double)fh[1]));
     res[1] = __floats2half2_rn((float)((double)o[2] + lscale * (double)fh[2]), (float)((double)o[3] + lscale * (double)fh[3]));
-    *reinterpret_cast<uint2 *>(reinterpret_cast<T *>(a.out) + ((size_t)u * G + g) * D + col0) = *reinterpret_cast<const uint2 *>(res);
+    store_wt8(reinterpret_cast<T *>(a.out) + ((size_t)u * G + g) * D + col0, *reinterpret_cast<const uint2 *>(res));
+  }
+  // The unit's new state, by the lead wave: every store of the step stands behind the last load
+  // (a wave's memory counter runs in order: a store in mid-stream holds up the rows requested
+  // after it) and goes through the L2 to memory (a line left dirty there is written back when
+  // the kernel ends, before the next launch can start).
+  if (lead) {
+    if (pend.fold) {                                         // H with the pending pair folded in (Eq. 4)
+#pragma unroll
+      for (int i = 0; i < HR; ++i) {
+        const int r = NHB * i + hb;
+        if (r < R) store_wt16(a.H + (size_t)u * R * D, (r * D + col0) * (int)sizeof(float), hreg[i]);
+      }
+    }
+    if (lane < R) {
+      if (pend.fold) store_wt(a.z + (size_t)u * R + lane, z_lane);
+      if (pend.slot >= 0 && pend.slot < C) store_wt(a.psi + ((size_t)u * C + pend.slot) * R + lane, ppsi_lane);
+      store_wt(a.pend_psi + (size_t)u * R + lane, npsi_lane);
+    }
+#pragma unroll
+    for (int i = 0; i < NR2; ++i) {
+      const int j = lane + i * kWave;
+      if (j < m) {
+        if (j != ins_slot) store_wt(a.acc + (size_t)u * C + j, na_[i]);
+      } else if (j == m && ins_slot >= 0) {
+        store_wt(a.acc + (size_t)u * C + ins_slot, na_[i]);
+        store_wt(a.pos + (size_t)u * C + ins_slot, n);
+      }
+    }
+    if (lane == 0) {
+      store_wt(a.pend_slot + u, eslot >= 0 ? (eslot < m ? eslot : C) : (m | kPendNoFold));
+      if (a.evicted_pos) store_wt(a.evicted_pos + u, eslot >= 0 ? epos : -1);
+      store_wt(a.n_seen + u, n + 1);
+    }
+    if (eslot >= 0 && rb == eslot % RPI)
+      store_wt16(reinterpret_cast<T *>(a.pend_v) + (size_t)u * D, lr * EPL * (int)sizeof(T), pv_keep);
   }
   // barrier 3: the rows still in a ring are requests past the value stream (out of range, zeros),
   // so every wave that arrives here has all the cache rows it will ever read
@@ -355,8 +361,8 @@ __global__ __launch_bounds__(kGqsMaxHeads * kWave) void gqs_step_kernel(void *k_
   for (int j = 0; j < DEPTH; ++j) asm volatile("" ::"v"(buf[j]));
   __builtin_amdgcn_s_barrier();
   if (lead && ins_slot >= 0 && rb == 0) {
-    store_nt(kc + (size_t)ins_slot * D + lr * EPL, knv.raw);
-    store_nt(vc + (size_t)ins_slot * D + lr * EPL, vnv.raw);
+    store_wt16(kc + (size_t)ins_slot * D, lr * EPL * (int)sizeof(T), knv.raw);
+    store_wt16(vc + (size_t)ins_slot * D, lr * EPL * (int)sizeof(T), vnv.raw);
   }
 }
 
