@@ -37,7 +37,7 @@ HBM_PEAK_GBS = 8000.0        # MI355X published HBM3E bandwidth
 # HBM bytes per step (both directions), from the rocprofv3 FETCH_SIZE / WRITE_SIZE counter runs of
 # this same command on this build (profiles/lessdec_step_cfg3_hbm_traffic.txt: counters cannot be
 # read from inside the process).  Only for the workload and launch shape they were taken on.
-MEASURED_TRAFFIC_BYTES = {3: 150.7e6}        # 135.0 MB read + 15.7 MB written by the one launch of a step
+MEASURED_TRAFFIC_BYTES = {3: 147.8e6}        # 132.0 MB read + 15.8 MB written by the one launch of a step
 
 
 def algorithmic_bytes_per_unit_step(w) -> float:
