@@ -33,8 +33,8 @@ hipError_t launch_mlp(const MlpArgs &a, hipStream_t st);
 hipError_t launch_mlp_pair(const MlpArgs &a, const MlpArgs &b, hipStream_t st);   // both in one launch (same D, R', R)
 
 // Both feature maps of one decode step, up to the layer-2 sums: phi of q and psi of k for
-// every unit, the hidden units split into parts of kMlpPartHidden.  out[((map * nparts +
-// part) * U + u) * mlp_entry_stride(R) + r] is part's share of the layer-2 pre-activation r of unit u (map 0:
+// every unit, the hidden units split into parts of kMlpPartHidden.  out[((u * 2 + map) * nparts +
+// part) * mlp_entry_stride(R) + r] is part's share of the layer-2 pre-activation r of unit u (map 0:
 // q with Wq, map 1: k with Wk); the reader adds the parts and finishes Eq. 1 / Eq. 2.
 constexpr int kMlpPartHidden = 64;
 struct MlpPartsArgs {
