@@ -491,7 +491,58 @@ __global__ __launch_bounds__((FUSED ? kWpuFusedUnits : kWpuUnits) * kWave, FUSED
   bookkeeping();
   value_pass(2 * DEPTH);
   fold_state();
-  for (int base = 3 * DEPTH; base < nit; base += DEPTH) value_pass(base);
+  // The unit's new state.  Its stores stand behind the last load that fetches anything: the memory
+  // counter of a wave runs in order, so a store in mid-stream holds up every row requested after
+  // it until the store has been acknowledged.  The rows of the last pass are requested before
+  // these stores and do not wait for them.  (SPLIT: the lead wave's.)
+  auto state_stores = [&]() __attribute__((always_inline)) {
+    if (pend.fold) {                                         // H with the pending pair folded in (Eq. 4)
+#pragma unroll
+      for (int i = 0; i < HR; ++i) {
+        const int r = NHB * i + hb;
+        if (r < R) store_wt16(a.H + (size_t)u * R * D, (r * D + col0) * (int)sizeof(float), hreg[i]);
+      }
+    }
+    if (lane < R) {
+      if (pend.fold) store_wt(a.z + (size_t)u * R + lane, z_lane);
+      if (pend.slot >= 0 && pend.slot < C) store_wt(a.psi + ((size_t)u * C + pend.slot) * R + lane, ppsi_lane);
+      store_wt(a.pend_psi + (size_t)u * R + lane, npsi_lane);
+    }
+#pragma unroll
+    for (int i = 0; i < NR2; ++i) {
+      const int j = lane + i * kWave;
+      if (j < m) {
+        if (j != ins_slot) store_wt(a.acc + (size_t)u * C + j, sc[i]);
+      } else if (j == m && ins_slot >= 0) {
+        store_wt(a.acc + (size_t)u * C + ins_slot, sc[i]);
+        store_wt(a.pos + (size_t)u * C + ins_slot, n);
+      }
+    }
+    if (lane == 0) {
+      // what the next step has to finish: fold of the discarded pair and / or the slot write
+      store_wt(a.pend_slot + u, eslot >= 0 ? (eslot < m ? eslot : C) : (m | kPendNoFold));
+      if (a.evicted_pos) store_wt(a.evicted_pos + u, eslot >= 0 ? epos : -1);
+      store_wt(a.n_seen + u, n + 1);
+    }
+    if constexpr (!SPLIT) {
+      // the feature-map entries go back empty (the unit's 2 * nparts entries lie together)
+      for (int e = lane; e < 2 * nparts * (rp / 4); e += kWave)
+        store_wt16(a.mlp_out + (size_t)u * 2 * nparts * rp, e * 16, uint4{kMlpEmpty, kMlpEmpty, kMlpEmpty, kMlpEmpty});
+    }
+    // the discarded pair's value row, parked for the next step's fold (before the insert below
+    // overwrites the row it was read from)
+    if (eslot >= 0 && rb == 0) {
+      uint4 row = vnv.raw;
+      if (eslot < m) __builtin_memcpy(&row, &pv_row, 16);
+      store_wt16(reinterpret_cast<T *>(a.pend_v) + (size_t)u * D, lr * EPL * (int)sizeof(T), row);
+    }
+  };
+  {
+    int base = 3 * DEPTH;
+    for (; base + DEPTH < nit; base += DEPTH) value_pass(base);
+    if (lead) state_stores();
+    if (base < nit) value_pass(base);                        // the last pass requests nothing real
+  }
   // the appended pair's value row
   if (lead && rb == 0) {
     const float p = s_p[m];
@@ -534,55 +585,12 @@ __global__ __launch_bounds__((FUSED ? kWpuFusedUnits : kWpuUnits) * kWave, FUSED
       }
     }
 
-    // ---- phase 4: output, then the unit's new state and the in-place insert -------------------------
-    // Every store of the step stands here, behind the last load: the memory counter of a wave
-    // runs in order, so a store in mid-stream holds up every row requested after it until the
-    // store has been acknowledged.  (SPLIT: only the lead wave gets here.)
+    // ---- phase 4: output and the in-place insert (SPLIT: only the lead wave gets here) -------------
     if (hb == 0) {
       __half2 res[2];
       res[0] = __floats2half2_rn((float)(pscale * (double)o[0] + lscale * (double)fh[0]), (float)(pscale * (double)o[1] + lscale * (double)fh[1]));
       res[1] = __floats2half2_rn((float)(pscale * (double)o[2] + lscale * (double)fh[2]), (float)(pscale * (double)o[3] + lscale * (double)fh[3]));
       store_wt8(reinterpret_cast<T *>(a.out) + (size_t)u * xs_ + col0, *reinterpret_cast<const uint2 *>(res));
-    }
-    if (pend.fold) {                                         // H with the pending pair folded in (Eq. 4)
-#pragma unroll
-      for (int i = 0; i < HR; ++i) {
-        const int r = NHB * i + hb;
-        if (r < R) store_wt16(a.H + (size_t)u * R * D, (r * D + col0) * (int)sizeof(float), hreg[i]);
-      }
-    }
-    if (lane < R) {
-      if (pend.fold) store_wt(a.z + (size_t)u * R + lane, z_lane);
-      if (pend.slot >= 0 && pend.slot < C) store_wt(a.psi + ((size_t)u * C + pend.slot) * R + lane, ppsi_lane);
-      store_wt(a.pend_psi + (size_t)u * R + lane, npsi_lane);
-    }
-#pragma unroll
-    for (int i = 0; i < NR2; ++i) {
-      const int j = lane + i * kWave;
-      if (j < m) {
-        if (j != ins_slot) store_wt(a.acc + (size_t)u * C + j, sc[i]);
-      } else if (j == m && ins_slot >= 0) {
-        store_wt(a.acc + (size_t)u * C + ins_slot, sc[i]);
-        store_wt(a.pos + (size_t)u * C + ins_slot, n);
-      }
-    }
-    if (lane == 0) {
-      // what the next step has to finish: fold of the discarded pair and / or the slot write
-      store_wt(a.pend_slot + u, eslot >= 0 ? (eslot < m ? eslot : C) : (m | kPendNoFold));
-      if (a.evicted_pos) store_wt(a.evicted_pos + u, eslot >= 0 ? epos : -1);
-      store_wt(a.n_seen + u, n + 1);
-    }
-    if constexpr (!SPLIT) {
-      // the feature-map entries go back empty (the unit's 2 * nparts entries lie together)
-      for (int e = lane; e < 2 * nparts * (rp / 4); e += kWave)
-        store_wt16(a.mlp_out + (size_t)u * 2 * nparts * rp, e * 16, uint4{kMlpEmpty, kMlpEmpty, kMlpEmpty, kMlpEmpty});
-    }
-    // the discarded pair's value row, parked for the next step's fold (before the insert below
-    // overwrites the row it was read from)
-    if (eslot >= 0 && rb == 0) {
-      uint4 row = vnv.raw;
-      if (eslot < m) __builtin_memcpy(&row, &pv_row, 16);
-      store_wt16(reinterpret_cast<T *>(a.pend_v) + (size_t)u * D, lr * EPL * (int)sizeof(T), row);
     }
     if (ins_slot >= 0 && rb == 0) {
       store_wt16(kc + (size_t)ins_slot * D, lr * EPL * (int)sizeof(T), knv.raw);
