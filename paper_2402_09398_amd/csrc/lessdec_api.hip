@@ -63,7 +63,7 @@ Workspace carve(const Shape &s, size_t P, unsigned flags)
   size_t o = 0;
   w.off_fphi = o; o = align_up(o + s.U * s.G * s.R * sizeof(double), 256);
   w.off_fpsi = o; o = align_up(o + s.U * s.R * sizeof(float), 256);
-  w.off_parts = o; o = align_up(o + 2 * (size_t)mlp_nparts((int)s.Rp) * s.U * 16 * sizeof(float), 256);
+  w.off_parts = o; o = align_up(o + (s.G > 1 ? s.G + 1 : 2) * (size_t)mlp_nparts((int)s.Rp) * s.U * 16 * sizeof(float), 256);
   w.off_gqa = o; o = align_up(o + (s.G > 1 ? s.U * gqa_head_blocks((long)s.U, (int)s.G) * (s.C + 2) * sizeof(double) : 0), 256);
   w.off_stage = o; o = align_up(o + (P ? 4 * s.U * s.G * s.D * sizeof(float) : 0), 256);
   w.off_lse = o; o = align_up(o + s.U * s.G * P * sizeof(double), 256);
@@ -126,6 +126,15 @@ bool use_wpu(const lessdec_desc *desc, const Shape &s)
 {
   return s.G == 1 && desc->batch < 65536 && desc->heads < 65536 &&
          wpu_supported(desc->dtype, desc->head_dim, (int)s.C, desc->hidden, desc->rank);
+}
+
+// Several query heads per unit on the streaming kernel, which finishes the feature maps itself
+// from their parts.
+bool gq_parts(const lessdec_desc *desc, const Shape &s)
+{
+  return s.G > 1 && desc->batch < 65536 && desc->heads < 65536 &&
+         gqs_supported(desc->dtype, desc->head_dim, (int)s.C, desc->rank, (int)s.G) &&
+         mlp_mfma_supported(desc->dtype, desc->head_dim, desc->hidden, desc->rank) && gqs_takes_parts(desc->hidden);
 }
 
 MlpPartsArgs parts_args(const lessdec_desc *desc, const void *q, const void *k, float *out)
@@ -219,6 +228,11 @@ int step_features_impl(const lessdec_desc *desc, const void *q, const void *k, i
     return launch_mlp_parts(fm, st) == hipSuccess ? LESSDEC_OK : LESSDEC_EHIP;
   }
   if (x_stride != desc->head_dim) return LESSDEC_EINVAL;
+  if (gq_parts(desc, s)) {
+    // several query heads per unit, streaming kernel: both maps up to the layer-2 sums
+    MlpPartsArgs fm = parts_args(desc, q, k, reinterpret_cast<float *>(ws + w.off_parts));
+    return launch_mlp_parts_gq(fm, (int)s.G, st) == hipSuccess ? LESSDEC_OK : LESSDEC_EHIP;
+  }
   if (s.G > 1 && mlp_mfma_supported(desc->dtype, desc->head_dim, desc->hidden, desc->rank)) {
     // several query heads per unit: both maps complete on the matrix cores, fp32 results
     MlpArgs fm;
@@ -269,6 +283,7 @@ int step_attend_impl(const lessdec_desc *desc, const void *q, const void *k, con
       a.f_phi = reinterpret_cast<double *>(ws + w.off_fphi);
     a.f_psi = reinterpret_cast<float *>(ws + w.off_fpsi);
     a.gqa_parts = reinterpret_cast<double *>(ws + w.off_gqa);
+    if (gq_parts(desc, s)) a.mlp_parts = reinterpret_cast<float *>(ws + w.off_parts);
     if (gqs_supported(desc->dtype, desc->head_dim, (int)s.C, desc->rank, (int)s.G))
       return launch_step_gqs(a, (int)s.G, desc->head_dim, st) == hipSuccess ? LESSDEC_OK : LESSDEC_EHIP;
     return launch_step_gqa(a, (int)s.G, desc->dtype, desc->head_dim, st) == hipSuccess ? LESSDEC_OK : LESSDEC_EHIP;

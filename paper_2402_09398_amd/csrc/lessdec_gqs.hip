@@ -23,6 +23,7 @@ namespace lessdec {
 
 constexpr int kGqsMaxHeads = 8;     // waves per block
 constexpr int kGqsMaxRows = 512;    // C + 1 at most
+constexpr int kGqsParts = 8;        // feature maps taken as parts up to this many (R' <= 512)
 
 template <int D, int NR2, int RM, int DEPTH>
 __global__ __launch_bounds__(kGqsMaxHeads * kWave) void gqs_step_kernel(void *k_cache_, const void *q_, const void *k_,
@@ -66,10 +67,33 @@ __global__ __launch_bounds__(kGqsMaxHeads * kWave) void gqs_step_kernel(void *k_
   }
   __builtin_amdgcn_sched_barrier(0);
   const int rl = (lane & 15) < R ? (lane & 15) : R - 1;
-  // phi(q) of this head and psi(k) of the step's key, from the feature-map launch (lane r < R)
+  // phi(q) of this head and psi(k) of the step's key (lane r < R): complete from the feature-map
+  // launch, or (a.mlp_parts) as the parts of their layer-2 sums, which this wave adds up and
+  // finishes after the first pass of the key stream (Eq. 1, Eq. 2), where nothing waits for anything
+  constexpr int NP = kGqsParts;
+  const bool parts = a.mlp_parts != nullptr;
+  const int nparts = mlp_nparts(a.Rp), rp = mlp_entry_stride(R);
   const size_t fi = ((size_t)u * G + g) * R + rl;
-  double f_lane = a.f_phi32 ? (double)a.f_phi32[fi] : a.f_phi[fi];
-  const float npsi_lane = a.f_psi[(size_t)u * R + rl];
+  double f_lane = 0.0;
+  float npsi_lane = 0.f;
+  float pq[NP], pk[NP];
+  __half w3[RM];
+  if (parts) {
+    const float *eq = a.mlp_parts + ((size_t)u * G + g) * nparts * rp + rl;
+    const float *ek = a.mlp_parts + ((size_t)a.U * G + u) * nparts * rp + rl;
+#pragma unroll
+    for (int p = 0; p < NP; ++p) {
+      const int pc = p < nparts ? p : nparts - 1;
+      pq[p] = eq[(size_t)pc * rp];
+      pk[p] = ek[(size_t)pc * rp];
+    }
+    const __half *w3row = reinterpret_cast<const __half *>(a.Wk3) + ((size_t)(u % a.Hh) * R + rl) * R;
+#pragma unroll
+    for (int j = 0; j < RM; ++j) w3[j] = w3row[j < R ? j : R - 1];
+  } else {
+    f_lane = a.f_phi32 ? (double)a.f_phi32[fi] : a.f_phi[fi];
+    npsi_lane = a.f_psi[(size_t)u * R + rl];
+  }
   // unit state (wanted from phase 2 on)
   const int n = sane_n_seen(a.n_seen[u]);
   const Pending pend = decode_pending(a.pend_slot[u], C);
@@ -122,6 +146,23 @@ __global__ __launch_bounds__(kGqsMaxHeads * kWave) void gqs_step_kernel(void *k_
         }
         buf[j] = issue(s + DEPTH);
         __builtin_amdgcn_sched_barrier(0);
+      }
+      if (base == 0 && parts) {
+        double sq = 0.0, sk = 0.0;
+#pragma unroll
+        for (int p = 0; p < NP; ++p) {
+          if (p < nparts) {
+            sq += (double)pq[p];
+            sk += (double)pk[p];
+          }
+        }
+        f_lane = lane < R ? fabs(gelu_poly_f64(sq)) : 0.0;   // last activation of Eq. 1
+        const double h2 = gelu_poly_f64(sk);                 // lane r < R; Eq. 2: |W3 gelu(.)|
+        double acc3 = 0.0;
+#pragma unroll
+        for (int j = 0; j < RM; ++j)
+          if (j < R) acc3 = fma(readlane_v(h2, j), (double)__half2float(w3[j]), acc3);
+        npsi_lane = (float)fabs(acc3);
       }
     } while ((base += DEPTH) < nitp);
   }
@@ -371,6 +412,8 @@ bool gqs_supported(int dtype, int D, int C, int R, int G)
   return dtype == LESSDEC_DTYPE_F16 && (D == 64 || D == 128) && R <= 16 && C + 1 <= kGqsMaxRows && G >= 2 &&
          G <= kGqsMaxHeads;
 }
+
+bool gqs_takes_parts(int Rp) { return mlp_nparts(Rp) <= kGqsParts; }
 
 template <int D, int RM>
 static hipError_t launch_step_gqs_t(const StepArgs &a, int G, hipStream_t st)

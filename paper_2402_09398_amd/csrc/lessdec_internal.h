@@ -48,6 +48,9 @@ __host__ __device__ inline int mlp_nparts(int Rp) { return (Rp + kMlpPartHidden 
 // lane of the matrix tile holds.
 __host__ __device__ inline int mlp_entry_stride(int R) { return (R + 3) / 4 * 4; }
 hipError_t launch_mlp_parts(const MlpPartsArgs &a, hipStream_t st);
+// G query heads per key head (a.Hh key heads): entries [query row][part] for phi, then [unit][part]
+// for psi, (G + 1) * B * Hh * nparts * mlp_entry_stride(R) floats
+hipError_t launch_mlp_parts_gq(const MlpPartsArgs &a, int G, hipStream_t st);
 
 // pend_slot: -1 nothing; else slot index (C = the step's own pair) | kPendNoFold
 constexpr int kPendNoFold = 1 << 30;
@@ -91,6 +94,9 @@ hipError_t launch_state_sync(const StepArgs &a, int dtype, int D, hipStream_t st
 // several query heads per unit, streaming form: one block per unit, one wave per query head
 // (lessdec_gqs.hip); leaves the discarded pair pending like the single-head streaming path
 bool gqs_supported(int dtype, int D, int C, int R, int G);
+// whether that kernel finishes the feature maps itself from the parts of launch_mlp_parts_gq
+// (StepArgs::mlp_parts set) instead of taking them complete (f_phi32, f_psi)
+bool gqs_takes_parts(int Rp);
 hipError_t launch_step_gqs(const StepArgs &a, int G, int D, hipStream_t st);
 
 // One wave per unit, K and V streamed through a register ring (lessdec_wpu.hip).

@@ -96,10 +96,8 @@ __device__ inline void mlp_load_row(const __half *xr, int g, v8h (&bx)[D / 32])
 
 // One job of a decode step's feature maps: (head, map, part of kMlpPartHidden hidden units,
 // chunk of 64 batch rows), done by a block of four waves of 16 rows each that take the same two
-// groups of 32 hidden units, so the head's weights are read once per 64 rows.  job = ((chunk *
-// nparts + part) * 2 + map) * Hh + head: head fastest, so with Hh a multiple of 8 a head's jobs,
-// and later its readers, share an XCD and its L2.  wave: 0..3 within the job; every thread of the
-// block must call (one barrier inside).
+// groups of 32 hidden units, so the head's weights are read once per 64 rows.  wave: 0..3 within
+// the job; every thread of the block must call (one barrier inside).
 // The job's 64 rows of W1 are contiguous in memory: the block fetches them with whole-line loads
 // (a wave instruction = 1 KiB = four rows) into the LDS, once for its four waves, and the waves
 // pick their matrix operands out of the LDS.  Operand-shaped loads from memory (16 rows x 64
@@ -107,27 +105,19 @@ __device__ inline void mlp_load_row(const __half *xr, int g, v8h (&bx)[D / 32])
 // on the compute unit's memory pipeline, which is what slows waves streaming the cache next to
 // it when this job runs inside the attention launch.  Rows are padded by 16 bytes in the LDS so
 // that the 16 lanes of an operand read (same 16-byte column, 16 rows) fall into different banks.
-// x_stride: elements from unit u's row of q / k to unit u + 1's (D when the rows are packed).
-// out[((u * 2 + map) * nparts + part) * mlp_entry_stride(R) + r]: part's share of the layer-2 pre-activation r of
-// unit u (a unit's entries lie together: its wave reads and clears them as one piece).  COHERENT: the readers run in the same launch, possibly on another XCD whose L2 is not
-// coherent with this one's: the results go out as device-scope stores (written through).
+// x: the map's rows [B, Hh, .], row b of head h at x + (b Hh + h) x_stride (x_stride = D when the
+// rows are packed); W1, W2: the head's; the part's share of the layer-2 pre-activation r of unit
+// b Hh + h goes to dst_map[unit * ustride + part * mlp_entry_stride(R) + r].  COHERENT: the readers run
+// in the same launch, possibly on another XCD whose L2 is not coherent with this one's: the results
+// go out as device-scope stores (written through).
 template <int D, bool COHERENT>
-__device__ inline void mlp_parts_job(const __half *q, const __half *k, const __half *Wq1, const __half *Wk1,
-                                     const __half *Wq2, const __half *Wk2, int Hh, int Rp, int R, int B,
-                                     int x_stride, float *out, int job, int wave, int l)
+__device__ inline void mlp_parts_core(const __half *x, const __half *W1, const __half *W2, int Hh, int h, int Rp,
+                                      int R, int B, int x_stride, float *dst_map, size_t ustride, int part, int chunk,
+                                      int wave, int l)
 {
   constexpr int kRowBytes = D * 2, kStride = kRowBytes + 16, kChunks = kRowBytes / 16;
   __shared__ __attribute__((aligned(16))) unsigned char s_w1[kMlpPartHidden * kStride];
   const int g = l / 16, c = l % 16;
-  const int nparts = mlp_nparts(Rp);
-  int b = job;
-  const int h = b % Hh; b /= Hh;
-  const int map = b % 2; b /= 2;
-  const int part = b % nparts;
-  const int chunk = b / nparts;
-  const __half *x = map ? k : q;
-  const __half *W1 = (map ? Wk1 : Wq1) + (size_t)h * Rp * D;
-  const __half *W2 = (map ? Wk2 : Wq2) + (size_t)h * R * Rp;
   const int row = chunk * 64 + wave * 16 + c;              // batch row of MFMA column c
   const bool rowv = row < B;
   const size_t u = (size_t)(rowv ? row : 0) * Hh + h;
@@ -178,7 +168,7 @@ __device__ inline void mlp_parts_job(const __half *q, const __half *k, const __h
   // c2[w]: output r = 4 g + w of row c
   const int rp = mlp_entry_stride(R);
   if (rowv && 4 * g < rp) {                                // outputs past the rank are not kept
-    float *dst = out + ((u * 2 + map) * nparts + part) * rp + 4 * g;
+    float *dst = dst_map + u * ustride + (size_t)part * rp + 4 * g;
     if constexpr (COHERENT) {
       unsigned long long lo, hi;
       const float2 a = {c2[0], c2[1]}, bq = {c2[2], c2[3]};
@@ -190,6 +180,47 @@ __device__ inline void mlp_parts_job(const __half *q, const __half *k, const __h
       *reinterpret_cast<float4 *>(dst) = float4{c2[0], c2[1], c2[2], c2[3]};
     }
   }
+}
+
+// Job of a step whose two maps have the same heads (one query head per key head): job = ((chunk *
+// nparts + part) * 2 + map) * Hh + head: head fastest, so with Hh a multiple of 8 a head's jobs, and
+// later its readers, share an XCD and its L2.  out[((u * 2 + map) * nparts + part) *
+// mlp_entry_stride(R) + r]: a unit's entries lie together, its wave reads and clears them as one piece.
+template <int D, bool COHERENT>
+__device__ inline void mlp_parts_job(const __half *q, const __half *k, const __half *Wq1, const __half *Wk1,
+                                     const __half *Wq2, const __half *Wk2, int Hh, int Rp, int R, int B,
+                                     int x_stride, float *out, int job, int wave, int l)
+{
+  const int nparts = mlp_nparts(Rp), rp = mlp_entry_stride(R);
+  int b = job;
+  const int h = b % Hh; b /= Hh;
+  const int map = b % 2; b /= 2;
+  const int part = b % nparts;
+  const int chunk = b / nparts;
+  mlp_parts_core<D, COHERENT>(map ? k : q, (map ? Wk1 : Wq1) + (size_t)h * Rp * D, (map ? Wk2 : Wq2) + (size_t)h * R * Rp,
+                              Hh, h, Rp, R, B, x_stride, out + (size_t)map * nparts * rp, (size_t)2 * nparts * rp, part,
+                              chunk, wave, l);
+}
+
+// Job of a step with G query heads per key head: phi over the B x (Hk G) query rows with a weight
+// set per query head, psi over the B x Hk key rows.  Jobs 0 .. nq - 1 (nq = Hk G nparts chunks) are
+// phi's, head fastest; the rest psi's.  Entries: [query row][part] for phi, then [unit][part] for psi.
+template <int D>
+__device__ inline void mlp_parts_gq_job(const __half *q, const __half *k, const __half *Wq1, const __half *Wk1,
+                                        const __half *Wq2, const __half *Wk2, int Hk, int G, int Rp, int R, int B,
+                                        float *out, int job, int wave, int l)
+{
+  const int nparts = mlp_nparts(Rp), rp = mlp_entry_stride(R), chunks = (B + 63) / 64;
+  const int Hq = Hk * G, nq = Hq * nparts * chunks;
+  const bool psi = job >= nq;
+  int b = psi ? job - nq : job;
+  const int Hh = psi ? Hk : Hq;
+  const int h = b % Hh; b /= Hh;
+  const int part = b % nparts;
+  const int chunk = b / nparts;
+  float *dst = psi ? out + (size_t)B * Hq * nparts * rp : out;
+  mlp_parts_core<D, false>(psi ? k : q, (psi ? Wk1 : Wq1) + (size_t)h * Rp * D, (psi ? Wk2 : Wq2) + (size_t)h * R * Rp,
+                           Hh, h, Rp, R, B, D, dst, (size_t)nparts * rp, part, chunk, wave, l);
 }
 
 }  // namespace lessdec

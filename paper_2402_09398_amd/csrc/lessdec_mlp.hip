@@ -184,6 +184,17 @@ __global__ __launch_bounds__(256) void mlp_parts_kernel(const __half *q, const _
                           (int)threadIdx.x / 64, (int)threadIdx.x % 64);
 }
 
+// Decode step with G query heads per key head: phi of every query row and psi of every key row by
+// parts, one job of mlp_parts_gq_job per block.  hg = Hk | G << 16, rrp = R | R' << 8.
+template <int D>
+__global__ __launch_bounds__(256) void mlp_parts_gq_kernel(const __half *q, const __half *k, const __half *Wq1,
+                                                           const __half *Wk1, const __half *Wq2, const __half *Wk2,
+                                                           int hg, int rrp, int B, float *out)
+{
+  mlp_parts_gq_job<D>(q, k, Wq1, Wk1, Wq2, Wk2, hg & 0xffff, hg >> 16, rrp >> 8, rrp & 0xff, B, out, (int)blockIdx.x,
+                      (int)threadIdx.x / 64, (int)threadIdx.x % 64);
+}
+
 bool mlp_mfma_supported(int dtype, int D, int Rp, int R)
 {
   return dtype == LESSDEC_DTYPE_F16 && (D == 64 || D == 128) && Rp % 32 == 0 && Rp >= 32 && R <= 16;
@@ -234,6 +245,18 @@ hipError_t launch_mlp_parts(const MlpPartsArgs &a, hipStream_t st)
     mlp_parts_kernel<128><<<grid, 256, 0, st>>>(a.q, a.k, a.Wq1, a.Wk1, a.Wq2, a.Wk2, a.Hh, rrp, xs, a.B, a.out);
   else
     mlp_parts_kernel<64><<<grid, 256, 0, st>>>(a.q, a.k, a.Wq1, a.Wk1, a.Wq2, a.Wk2, a.Hh, rrp, xs, a.B, a.out);
+  return hipGetLastError();
+}
+
+// a.Hh: key heads; G query heads each (q rows [B, Hh, G, D], Wq per query head)
+hipError_t launch_mlp_parts_gq(const MlpPartsArgs &a, int G, hipStream_t st)
+{
+  const unsigned grid = (unsigned)((long)a.Hh * (G + 1) * mlp_nparts(a.Rp) * ((a.B + 63) / 64));
+  const int rrp = a.R | (a.Rp << 8), hg = a.Hh | (G << 16);
+  if (a.D == 128)
+    mlp_parts_gq_kernel<128><<<grid, 256, 0, st>>>(a.q, a.k, a.Wq1, a.Wk1, a.Wq2, a.Wk2, hg, rrp, a.B, a.out);
+  else
+    mlp_parts_gq_kernel<64><<<grid, 256, 0, st>>>(a.q, a.k, a.Wq1, a.Wk1, a.Wq2, a.Wk2, hg, rrp, a.B, a.out);
   return hipGetLastError();
 }
 
