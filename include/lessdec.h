@@ -199,7 +199,7 @@ int lessdec_step(const lessdec_desc *desc, const void *q, const void *k, const v
 /*
  * The two halves of lessdec_step, for a caller that has q and k before it wants the
  * attention output.  lessdec_step gives exactly the results of the first followed by the
- * second (on large shapes it runs both in one launch).  Every lessdec_step_features is to be
+ * second (where lessdec_step_launches gives 1 it runs both in one launch).  Every lessdec_step_features is to be
  * followed by its lessdec_step_attend before the next step on that workspace.
  *  lessdec_step_features: evaluates phi(q) (Eq. 1) and psi(k) (Eq. 2) of the step for every
  *    unit into the workspace.  Touches no state.

@@ -151,10 +151,10 @@ MlpPartsArgs parts_args(const lessdec_desc *desc, const void *q, const void *k, 
 // The per-step exchange array of the streaming path starts out empty (see wpu_step_kernel).
 hipError_t empty_exchange(const lessdec_desc *desc, const Shape &s, hipStream_t st)
 {
-  if (!use_wpu(desc, s)) return hipSuccess;
+  if (!use_wpu(desc, s) && !gq_parts(desc, s)) return hipSuccess;
   const Workspace w = carve(s, 0, desc->flags);
   return launch_fill_empty(reinterpret_cast<float *>(static_cast<char *>(desc->workspace) + w.off_parts),
-                           2 * (size_t)mlp_nparts((int)s.Rp) * s.U * 16, st);
+                           (s.G > 1 ? s.G + 1 : 2) * (size_t)mlp_nparts((int)s.Rp) * s.U * 16, st);
 }
 
 // Device address of `scratch` on the current device, looked up once per device.
@@ -283,7 +283,7 @@ int step_attend_impl(const lessdec_desc *desc, const void *q, const void *k, con
       a.f_phi = reinterpret_cast<double *>(ws + w.off_fphi);
     a.f_psi = reinterpret_cast<float *>(ws + w.off_fpsi);
     a.gqa_parts = reinterpret_cast<double *>(ws + w.off_gqa);
-    if (gq_parts(desc, s)) a.mlp_parts = reinterpret_cast<float *>(ws + w.off_parts);
+    if (gq_parts(desc, s)) a.mlp_parts = a.mlp_out = reinterpret_cast<float *>(ws + w.off_parts);
     if (gqs_supported(desc->dtype, desc->head_dim, (int)s.C, desc->rank, (int)s.G))
       return launch_step_gqs(a, (int)s.G, desc->head_dim, st) == hipSuccess ? LESSDEC_OK : LESSDEC_EHIP;
     return launch_step_gqa(a, (int)s.G, desc->dtype, desc->head_dim, st) == hipSuccess ? LESSDEC_OK : LESSDEC_EHIP;
@@ -319,6 +319,18 @@ int step_impl(const lessdec_desc *desc, const void *q, const void *k, const void
     fm.x_stride = x_stride;
     return launch_step_wpu(a, desc->head_dim, (hipStream_t)hip_stream, &fm) == hipSuccess ? LESSDEC_OK : LESSDEC_EHIP;
   }
+  if (gq_parts(desc, s) && x_stride == desc->head_dim &&
+      gqs_fusable(desc->head_dim, (int)s.C, desc->hidden, desc->rank, (int)s.G)) {
+    // several query heads per unit: feature maps and attention in one launch
+    StepArgs a = state_args(desc, s);
+    a.q = q; a.k = k; a.v = v; a.out = out; a.evicted_pos = evicted_pos; a.x_stride = x_stride;
+    const Workspace w = carve(s, 0, desc->flags);
+    float *parts = reinterpret_cast<float *>(static_cast<char *>(desc->workspace) + w.off_parts);
+    a.mlp_parts = a.mlp_out = parts;
+    MlpPartsArgs fm = parts_args(desc, q, k, parts);
+    return launch_step_gqs(a, (int)s.G, desc->head_dim, (hipStream_t)hip_stream, &fm) == hipSuccess ? LESSDEC_OK
+                                                                                                     : LESSDEC_EHIP;
+  }
   rc = step_features_impl(desc, q, k, x_stride, hip_stream);
   if (rc) return rc;
   return step_attend_impl(desc, q, k, v, out, evicted_pos, x_stride, hip_stream);
@@ -349,6 +361,7 @@ int lessdec_step_launches(const lessdec_desc *desc)
 {
   Shape s;
   if (!shape_ok(desc, &s)) return 0;
+  if (gq_parts(desc, s) && gqs_fusable(desc->head_dim, (int)s.C, desc->hidden, desc->rank, (int)s.G)) return 1;
   if (s.G > 1)                                                              // feature maps, heads, (finishing launch)
     return !gqs_supported(desc->dtype, desc->head_dim, (int)s.C, desc->rank, (int)s.G) &&
                    gqa_head_blocks((long)s.U, (int)s.G) > 1 ? 3 : 2;

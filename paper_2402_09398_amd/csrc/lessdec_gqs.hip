@@ -16,7 +16,9 @@
 //   barrier 3  every wave is through with the cache rows; the lead wave writes the new pair
 //              into its slot (Sec. 3.2).
 // The fold of the discarded pair into H, z is left to the next step (pend_slot, as on the
-// single-head path).  phi(q) per head and psi(k) come from the feature-map launch before it.
+// single-head path).  phi(q) per head and psi(k) come from the feature-map launch before it,
+// complete or as the parts of their layer-2 sums, or (FUSED) from jobs inside this launch.
+#include "lessdec_mlp.h"
 #include "lessdec_wave.h"
 
 namespace lessdec {
@@ -25,9 +27,20 @@ constexpr int kGqsMaxHeads = 8;     // waves per block
 constexpr int kGqsMaxRows = 512;    // C + 1 at most
 constexpr int kGqsParts = 8;        // feature maps taken as parts up to this many (R' <= 512)
 
-template <int D, int NR2, int RM, int DEPTH>
-__global__ __launch_bounds__(kGqsMaxHeads * kWave) void gqs_step_kernel(void *k_cache_, const void *q_, const void *k_,
-                                                                       int C_, int G_, const StepArgs a)
+// FUSED: the step's feature-map jobs (mlp_parts_gq_job) are the first n_mlp workgroups of the launch
+// and hand their results to the attention waves through the exchange array, as in the one-wave-
+// per-unit kernel (wpu_step_kernel): an entry no job has written yet holds kMlpEmpty, jobs write
+// through with device-scope stores, waves read with device-scope loads, ask again while any entry
+// is empty (bounded by kGqsSpinLimit polls, then the NaNs of the empty entries show in the unit's
+// outputs), and hand the entries back empty with their other stores.  Workgroups are dispatched in
+// index order and a job waits for nothing, so no cycle of waits exists.  The block is a job's four
+// waves: four query heads per unit.
+constexpr int kGqsFusedHeads = 4;
+constexpr int kGqsSpinLimit = 1 << 14;
+template <int D, int NR2, int RM, int DEPTH, bool FUSED>
+__global__ __launch_bounds__((FUSED ? kGqsFusedHeads : kGqsMaxHeads) * kWave, FUSED ? 4 : 1) void gqs_step_kernel(
+    void *k_cache_, const void *q_, const void *k_, int C_, int G_, int n_mlp, const void *Wq1_, const void *Wk1_,
+    const void *Wq2_, const StepArgs a)
 {
   using T = __half;
   constexpr int EPL = 8;                   // elements per lane
@@ -40,8 +53,17 @@ __global__ __launch_bounds__(kGqsMaxHeads * kWave) void gqs_step_kernel(void *k_
   const int C = C_, R = a.R, G = G_;
   const int g = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);    // this wave's query head
   const int lane = threadIdx.x & 63;
+  if constexpr (FUSED) {
+    if ((int)blockIdx.x < n_mlp) {
+      mlp_parts_gq_job<D, true>(reinterpret_cast<const __half *>(q_), reinterpret_cast<const __half *>(k_),
+                                reinterpret_cast<const __half *>(Wq1_), reinterpret_cast<const __half *>(Wk1_),
+                                reinterpret_cast<const __half *>(Wq2_), reinterpret_cast<const __half *>(a.Wk2), a.Hh, G,
+                                a.Rp, R, a.B, a.mlp_out, (int)blockIdx.x, g, lane);
+      return;
+    }
+  }
   const int lr = lane % LPR, rb = lane / LPR;
-  const int u = (int)blockIdx.x;
+  const int u = FUSED ? (int)blockIdx.x - n_mlp : (int)blockIdx.x;
   const bool lead = g == 0;                                  // the wave that writes the unit's state
   const int rows_cap = (C + 2) & ~1;
   double *s_sc = dyn + (size_t)g * rows_cap;                 // [G][C+1] scores
@@ -78,15 +100,40 @@ __global__ __launch_bounds__(kGqsMaxHeads * kWave) void gqs_step_kernel(void *k_
   float npsi_lane = 0.f;
   float pq[NP], pk[NP];
   __half w3[RM];
-  if (parts) {
-    const float *eq = a.mlp_parts + ((size_t)u * G + g) * nparts * rp + rl;
-    const float *ek = a.mlp_parts + ((size_t)a.U * G + u) * nparts * rp + rl;
+  const float *eq = a.mlp_parts + ((size_t)u * G + g) * nparts * rp + rl;
+  const float *ek = a.mlp_parts + ((size_t)a.U * G + u) * nparts * rp + rl;
+  auto request_parts = [&]() __attribute__((always_inline)) {
 #pragma unroll
     for (int p = 0; p < NP; ++p) {
       const int pc = p < nparts ? p : nparts - 1;
-      pq[p] = eq[(size_t)pc * rp];
-      pk[p] = ek[(size_t)pc * rp];
+      if constexpr (FUSED) {
+        pq[p] = __hip_atomic_load(eq + (size_t)pc * rp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        pk[p] = __hip_atomic_load(ek + (size_t)pc * rp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      } else {
+        pq[p] = eq[(size_t)pc * rp];
+        pk[p] = ek[(size_t)pc * rp];
+      }
     }
+  };
+  auto finish_maps = [&]() __attribute__((always_inline)) {
+    double sq = 0.0, sk = 0.0;
+#pragma unroll
+    for (int p = 0; p < NP; ++p) {
+      if (p < nparts) {
+        sq += (double)pq[p];
+        sk += (double)pk[p];
+      }
+    }
+    f_lane = lane < R ? fabs(gelu_poly_f64(sq)) : 0.0;   // last activation of Eq. 1
+    const double h2 = gelu_poly_f64(sk);                 // lane r < R; Eq. 2: |W3 gelu(.)|
+    double acc3 = 0.0;
+#pragma unroll
+    for (int j = 0; j < RM; ++j)
+      if (j < R) acc3 = fma(readlane_v(h2, j), (double)__half2float(w3[j]), acc3);
+    npsi_lane = (float)fabs(acc3);
+  };
+  if (parts) {
+    if constexpr (!FUSED) request_parts();
     const __half *w3row = reinterpret_cast<const __half *>(a.Wk3) + ((size_t)(u % a.Hh) * R + rl) * R;
 #pragma unroll
     for (int j = 0; j < RM; ++j) w3[j] = w3row[j < R ? j : R - 1];
@@ -100,15 +147,20 @@ __global__ __launch_bounds__(kGqsMaxHeads * kWave) void gqs_step_kernel(void *k_
   const int m = n < C ? n : C;          // live slots are 0..m-1 (slots fill in order)
   const int rows = m + 1;               // + the appended pair (K', V' of Eq. 3)
   const bool full = (m == C);
+  // (FUSED: the accumulated scores are asked for behind the keys, with the rows of H: the kernel
+  // has to stay within the registers of four resident waves per SIMD)
   double acc_pre[NR2];
   int pos_pre[NR2];
+  auto request_scores = [&]() __attribute__((always_inline)) {
 #pragma unroll
-  for (int i = 0; i < NR2; ++i) {
-    const int j = lane + i * kWave;
-    const size_t idx = (size_t)u * C + (j < C ? j : C - 1);
-    acc_pre[i] = a.acc[idx];
-    pos_pre[i] = a.pos[idx];
-  }
+    for (int i = 0; i < NR2; ++i) {
+      const int j = lane + i * kWave;
+      const size_t idx = (size_t)u * C + (j < C ? j : C - 1);
+      acc_pre[i] = a.acc[idx];
+      pos_pre[i] = a.pos[idx];
+    }
+  };
+  if constexpr (!FUSED) request_scores();
   double z_lane = a.z[(size_t)u * R + rl];                   // lane r < R
   const float ppsi_lane = a.pend_psi[(size_t)u * R + rl];
   float psie_lane = a.psi[((size_t)u * C + (pend.slot >= 0 && pend.slot < C ? pend.slot : 0)) * R + rl];
@@ -127,8 +179,7 @@ __global__ __launch_bounds__(kGqsMaxHeads * kWave) void gqs_step_kernel(void *k_
   // ---- phase 1: this head's scores as the key rows arrive -------------------------------------------
   {
     const double inv_sqrt_d = 1.0 / sqrt((double)D);
-    int base = 0;
-    do {                                                     // nitp >= DEPTH
+    auto key_pass = [&](int base) __attribute__((always_inline)) {
 #pragma unroll
       for (int j = 0; j < DEPTH; ++j) {
         const int s = base + j;
@@ -147,24 +198,39 @@ __global__ __launch_bounds__(kGqsMaxHeads * kWave) void gqs_step_kernel(void *k_
         buf[j] = issue(s + DEPTH);
         __builtin_amdgcn_sched_barrier(0);
       }
-      if (base == 0 && parts) {
-        double sq = 0.0, sk = 0.0;
+    };
+    if constexpr (FUSED) {
+      // the entries are asked for before the last pass of the key stream
+      int base = 0;
+      for (; base + DEPTH < nitp; base += DEPTH) key_pass(base);
+      request_parts();
+      key_pass(base);
+      // (looked at here, before the requests behind the keys: the entries give their sixteen
+      // registers back before the rows of H take theirs)
+      // The first look stands outside the loop and looks at every entry: a look at the loop's head,
+      // or one that leaves after the first empty entry, would make whoever uses the entries next
+      // wait for everything in flight.
+      auto have_all = [&]() {
+        unsigned missing = 0;
 #pragma unroll
-        for (int p = 0; p < NP; ++p) {
-          if (p < nparts) {
-            sq += (double)pq[p];
-            sk += (double)pk[p];
-          }
-        }
-        f_lane = lane < R ? fabs(gelu_poly_f64(sq)) : 0.0;   // last activation of Eq. 1
-        const double h2 = gelu_poly_f64(sk);                 // lane r < R; Eq. 2: |W3 gelu(.)|
-        double acc3 = 0.0;
-#pragma unroll
-        for (int j = 0; j < RM; ++j)
-          if (j < R) acc3 = fma(readlane_v(h2, j), (double)__half2float(w3[j]), acc3);
-        npsi_lane = (float)fabs(acc3);
+        for (int p = 0; p < NP; ++p)
+          missing |= (unsigned)(__float_as_uint(pq[p]) == kMlpEmpty) | (unsigned)(__float_as_uint(pk[p]) == kMlpEmpty);
+        return __all(missing == 0u) != 0;
+      };
+      bool have = have_all();
+      for (int spin = 0; !have && spin < kGqsSpinLimit; ++spin) {
+        __builtin_amdgcn_s_sleep(32);
+        request_parts();
+        have = have_all();
       }
-    } while ((base += DEPTH) < nitp);
+      finish_maps();
+    } else {
+      int base = 0;
+      do {                                                   // nitp >= DEPTH
+        key_pass(base);
+        if (base == 0 && parts) finish_maps();
+      } while ((base += DEPTH) < nitp);
+    }
   }
 
   // ---- requests behind the keys: what the value stream and the output want --------------------------
@@ -179,13 +245,15 @@ __global__ __launch_bounds__(kGqsMaxHeads * kWave) void gqs_step_kernel(void *k_
     hreg[i] = *reinterpret_cast<const float4 *>(a.H + ((size_t)u * R + (r < R ? r : R - 1)) * D + col0);
   }
   const uint2 pend_v_h = *reinterpret_cast<const uint2 *>(reinterpret_cast<const T *>(a.pend_v) + (size_t)u * D + col0);
+  if constexpr (FUSED) request_scores();
   // barrier 1: the lead wave's stores must not overtake another wave's loads of the same state:
   // have those loads back before the waves meet (the value rows requested after them stay in flight)
 #pragma unroll
   for (int i = 0; i < NR2; ++i) asm volatile("" ::"v"(acc_pre[i]), "v"(pos_pre[i]));
 #pragma unroll
   for (int i = 0; i < HR; ++i) asm volatile("" ::"v"(hreg[i].x), "v"(hreg[i].y), "v"(hreg[i].z), "v"(hreg[i].w));
-  asm volatile("" ::"v"(z_lane), "v"(ppsi_lane), "v"(psie_lane), "v"(pend_v_h.x), "v"(pend_v_h.y), "v"(npsi_lane), "v"(f_lane));
+  asm volatile("" ::"v"(z_lane), "v"(ppsi_lane), "v"(psie_lane), "v"(pend_v_h.x), "v"(pend_v_h.y));
+  if constexpr (!FUSED) asm volatile("" ::"v"(npsi_lane), "v"(f_lane));
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
   __builtin_amdgcn_s_barrier();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
@@ -361,6 +429,14 @@ __global__ __launch_bounds__(kGqsMaxHeads * kWave) void gqs_step_kernel(void *k_
     res[1] = __floats2half2_rn((float)((double)o[2] + lscale * (double)fh[2]), (float)((double)o[3] + lscale * (double)fh[3]));
     store_wt8(reinterpret_cast<T *>(a.out) + ((size_t)u * G + g) * D + col0, *reinterpret_cast<const uint2 *>(res));
   }
+  // the feature-map entries go back empty: this head's, and (lead wave) the key's
+  if (parts) {
+    for (int e = lane; e < nparts * (rp / 4); e += kWave) {
+      store_wt16(a.mlp_out + ((size_t)u * G + g) * nparts * rp, e * 16, uint4{kMlpEmpty, kMlpEmpty, kMlpEmpty, kMlpEmpty});
+      if (lead)
+        store_wt16(a.mlp_out + ((size_t)a.U * G + u) * nparts * rp, e * 16, uint4{kMlpEmpty, kMlpEmpty, kMlpEmpty, kMlpEmpty});
+    }
+  }
   // The unit's new state, by the lead wave: every store of the step stands behind the last load
   // (a wave's memory counter runs in order: a store in mid-stream holds up the rows requested
   // after it) and goes through the L2 to memory (a line left dirty there is written back when
@@ -415,24 +491,48 @@ bool gqs_supported(int dtype, int D, int C, int R, int G)
 
 bool gqs_takes_parts(int Rp) { return mlp_nparts(Rp) <= kGqsParts; }
 
+// One launch for the whole step: four query heads per unit (the block is a feature-map job's four
+// waves), parts that fit the registers kept for them, and the kernel form that stays within the
+// 128 registers four resident waves per SIMD leave each.
+bool gqs_fusable(int D, int C, int Rp, int R, int G)
+{
+  return G == kGqsFusedHeads && D == 128 && C + 1 <= 2 * kWave && R <= 8 && mlp_nparts(Rp) <= kGqsParts;
+}
+
 template <int D, int RM>
-static hipError_t launch_step_gqs_t(const StepArgs &a, int G, hipStream_t st)
+static hipError_t launch_step_gqs_t(const StepArgs &a, int G, hipStream_t st, const MlpPartsArgs *fm)
 {
   constexpr int kDepth = 7;
   const int rows_cap = (a.C + 2) & ~1;
   const size_t lds = (size_t)G * rows_cap * (2 * sizeof(double) + sizeof(float));
-  const unsigned grid = (unsigned)a.U, block = (unsigned)(G * kWave);
+  const unsigned block = (unsigned)(G * kWave);
   const int rows = a.C + 1;
-  if (rows <= 2 * kWave) gqs_step_kernel<D, 2, RM, kDepth><<<grid, block, lds, st>>>(a.k_cache, a.q, a.k, a.C, G, a);
-  else if (rows <= 4 * kWave) gqs_step_kernel<D, 4, RM, kDepth><<<grid, block, lds, st>>>(a.k_cache, a.q, a.k, a.C, G, a);
-  else gqs_step_kernel<D, kGqsMaxRows / kWave, RM, kDepth><<<grid, block, lds, st>>>(a.k_cache, a.q, a.k, a.C, G, a);
+  if (fm) {
+    if constexpr (D == 128 && RM == 8) {
+      const unsigned n_mlp = (unsigned)((long)a.Hh * (G + 1) * mlp_nparts(a.Rp) * ((a.B + 63) / 64));
+      gqs_step_kernel<D, 2, RM, 6, true><<<n_mlp + (unsigned)a.U, block, lds, st>>>(a.k_cache, a.q, a.k, a.C, G, (int)n_mlp,
+                                                                                   fm->Wq1, fm->Wk1, fm->Wq2, a);
+      return hipGetLastError();
+    } else {
+      return hipErrorInvalidValue;
+    }
+  }
+  const unsigned grid = (unsigned)a.U;
+#define LESSDEC_GQS_LAUNCH(NR2)                                                                                   \
+  gqs_step_kernel<D, NR2, RM, kDepth, false><<<grid, block, lds, st>>>(a.k_cache, a.q, a.k, a.C, G, 0, nullptr, nullptr, \
+                                                                       nullptr, a)
+  if (rows <= 2 * kWave) LESSDEC_GQS_LAUNCH(2);
+  else if (rows <= 4 * kWave) LESSDEC_GQS_LAUNCH(4);
+  else LESSDEC_GQS_LAUNCH(kGqsMaxRows / kWave);
+#undef LESSDEC_GQS_LAUNCH
   return hipGetLastError();
 }
 
-hipError_t launch_step_gqs(const StepArgs &a, int G, int D, hipStream_t st)
+hipError_t launch_step_gqs(const StepArgs &a, int G, int D, hipStream_t st, const MlpPartsArgs *fm)
 {
-  if (D == 64) return launch_step_gqs_t<64, 16>(a, G, st);
-  return a.R <= 8 ? launch_step_gqs_t<128, 8>(a, G, st) : launch_step_gqs_t<128, 16>(a, G, st);
+  if (fm && !gqs_fusable(D, a.C, a.Rp, a.R, G)) return hipErrorInvalidValue;
+  if (D == 64) return launch_step_gqs_t<64, 16>(a, G, st, fm);
+  return a.R <= 8 ? launch_step_gqs_t<128, 8>(a, G, st, fm) : launch_step_gqs_t<128, 16>(a, G, st, fm);
 }
 
 }  // namespace lessdec

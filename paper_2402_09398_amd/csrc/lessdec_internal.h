@@ -97,7 +97,9 @@ bool gqs_supported(int dtype, int D, int C, int R, int G);
 // whether that kernel finishes the feature maps itself from the parts of launch_mlp_parts_gq
 // (StepArgs::mlp_parts set) instead of taking them complete (f_phi32, f_psi)
 bool gqs_takes_parts(int Rp);
-hipError_t launch_step_gqs(const StepArgs &a, int G, int D, hipStream_t st);
+// fm: the step's feature-map jobs run as the first workgroups of the same launch (gqs_fusable shapes)
+hipError_t launch_step_gqs(const StepArgs &a, int G, int D, hipStream_t st, const MlpPartsArgs *fm = nullptr);
+bool gqs_fusable(int D, int C, int Rp, int R, int G);
 
 // One wave per unit, K and V streamed through a register ring (lessdec_wpu.hip).
 bool wpu_supported(int dtype, int D, int C, int Rp, int R);

@@ -205,7 +205,7 @@ __device__ inline void mlp_parts_job(const __half *q, const __half *k, const __h
 // Job of a step with G query heads per key head: phi over the B x (Hk G) query rows with a weight
 // set per query head, psi over the B x Hk key rows.  Jobs 0 .. nq - 1 (nq = Hk G nparts chunks) are
 // phi's, head fastest; the rest psi's.  Entries: [query row][part] for phi, then [unit][part] for psi.
-template <int D>
+template <int D, bool COHERENT>
 __device__ inline void mlp_parts_gq_job(const __half *q, const __half *k, const __half *Wq1, const __half *Wk1,
                                         const __half *Wq2, const __half *Wk2, int Hk, int G, int Rp, int R, int B,
                                         float *out, int job, int wave, int l)
@@ -219,7 +219,7 @@ __device__ inline void mlp_parts_gq_job(const __half *q, const __half *k, const 
   const int part = b % nparts;
   const int chunk = b / nparts;
   float *dst = psi ? out + (size_t)B * Hq * nparts * rp : out;
-  mlp_parts_core<D, false>(psi ? k : q, (psi ? Wk1 : Wq1) + (size_t)h * Rp * D, (psi ? Wk2 : Wq2) + (size_t)h * R * Rp,
+  mlp_parts_core<D, COHERENT>(psi ? k : q, (psi ? Wk1 : Wq1) + (size_t)h * Rp * D, (psi ? Wk2 : Wq2) + (size_t)h * R * Rp,
                            Hh, h, Rp, R, B, D, dst, (size_t)nparts * rp, part, chunk, wave, l);
 }
 

@@ -191,7 +191,7 @@ __global__ __launch_bounds__(256) void mlp_parts_gq_kernel(const __half *q, cons
                                                            const __half *Wk1, const __half *Wq2, const __half *Wk2,
                                                            int hg, int rrp, int B, float *out)
 {
-  mlp_parts_gq_job<D>(q, k, Wq1, Wk1, Wq2, Wk2, hg & 0xffff, hg >> 16, rrp >> 8, rrp & 0xff, B, out, (int)blockIdx.x,
+  mlp_parts_gq_job<D, false>(q, k, Wq1, Wk1, Wq2, Wk2, hg & 0xffff, hg >> 16, rrp >> 8, rrp & 0xff, B, out, (int)blockIdx.x,
                       (int)threadIdx.x / 64, (int)threadIdx.x % 64);
 }
 

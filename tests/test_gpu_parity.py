@@ -329,6 +329,11 @@ GROUPS = [
     # more than eight query heads: the plain kernel, heads in chunks of four, spread over blocks
     (small("mqa-12-heads-plain-kernel", q_per_kv=12, prompt=30, steps=15), 4),
     (small("mqa-9-heads-plain-kernel-one-shot", q_per_kv=9, prompt=60, steps=12, batch=1, heads=2), 0),
+    # four query heads and a cache of at most 127 slots: the whole step is one launch, its feature-map
+    # jobs in front (two chunks of batch rows, the second ragged; eight parts of the hidden layer)
+    (small("gqa-4-heads-one-launch-ragged-batch", q_per_kv=4, batch=70, heads=8, hidden=512, prompt=30, steps=20), 0),
+    (small("gqa-4-heads-one-launch-filling", q_per_kv=4, batch=3, heads=5, hidden=96, prompt=0, steps=30,
+           n_heavy=10, n_recent=10), 0),
     (small("gqa-5-heads-wide-cache", q_per_kv=5, n_heavy=100, n_recent=60, prompt=200, steps=10, batch=1,
            heads=2, rank=16, hidden=96), 4),
 ]
