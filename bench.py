@@ -275,7 +275,9 @@ def main():
                      "traffic": MEASURED_TRAFFIC_BYTES.get(w.cfg) if L >= 8 and w.q_per_kv == 1 and flags == 0 and one_launch else None,
                      "kernel": ("wpu_step_kernel" + (" (one launch per step: feature-map jobs and attention waves)"
                                                      if one_launch else " + mlp_parts_kernel (two launches per step)")
-                                if w.q_per_kv == 1 else "gqa_chunk_kernel + mlp_pair_kernel (two launches per step)"),
+                                if w.q_per_kv == 1 else
+                                ("gqs_step_kernel (one launch per step: feature-map jobs and a wave per query head)"
+                                 if launches == 1 else f"grouped-head step kernel + feature-map kernel ({launches} launches per step)")),
                      "launches_per_step": launches,
                      "bytes_per_launch": bytes_per_step, "ms_per_launch": ms_per_step,
                      "algorithmic_bytes_per_unit_step": algorithmic_bytes_per_unit_step(w),
