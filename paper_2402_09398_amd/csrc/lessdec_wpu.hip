@@ -63,7 +63,7 @@ constexpr int kWpuSpinLimit = 1 << 14;   // FUSED: polls of the feature-map entr
 // of its unit then show it.
 // =====================================================================================
 template <int D, int NR2, int RM, int DEPTH, bool SPLIT, bool FUSED>
-__global__ __launch_bounds__((FUSED ? kWpuFusedUnits : kWpuUnits) * kWave, FUSED ? 4 : 1) void wpu_step_kernel(
+__global__ __launch_bounds__((FUSED ? kWpuFusedUnits : kWpuUnits) * kWave, FUSED ? (SPLIT ? 3 : 4) : 1) void wpu_step_kernel(
     void *k_cache_, const void *q_, const void *k_, int crp_, int hb_, int xs_, int n_mlp, const void *Wq1_,
     const void *Wk1_, const void *Wq2_, const StepArgs a)
 {
@@ -72,7 +72,6 @@ __global__ __launch_bounds__((FUSED ? kWpuFusedUnits : kWpuUnits) * kWave, FUSED
   // it), the struct has to be fetched.  crp_ = C | R << 12 | R' << 19, hb_ = Hh | B << 16, xs_ = the
   // distance in elements between the q / k / v / out rows of consecutive units.
   using T = __half;
-  static_assert(!(SPLIT && FUSED), "the fused launch is one wave per unit");
   constexpr int EPL = 8;                   // elements per lane
   constexpr int LPR = D / EPL;             // lanes per row
   constexpr int RPI = kWave / LPR;         // rows per load instruction
@@ -586,6 +585,11 @@ __global__ __launch_bounds__((FUSED ? kWpuFusedUnits : kWpuUnits) * kWave, FUSED
     }
 
     // ---- phase 4: output and the in-place insert (SPLIT: only the lead wave gets here) -------------
+    if constexpr (SPLIT) {
+      // the feature-map entries go back empty, now that every wave of the unit has read them
+      for (int e = lane; e < 2 * nparts * (rp / 4); e += kWave)
+        store_wt16(a.mlp_out + (size_t)u * 2 * nparts * rp, e * 16, uint4{kMlpEmpty, kMlpEmpty, kMlpEmpty, kMlpEmpty});
+    }
     if (hb == 0) {
       __half2 res[2];
       res[0] = __floats2half2_rn((float)(pscale * (double)o[0] + lscale * (double)fh[0]), (float)(pscale * (double)o[1] + lscale * (double)fh[1]));
@@ -654,14 +658,17 @@ static int wpu_split_waves(long units, int D, int C)
   return nw;
 }
 
-// One launch for the whole step: a wave per unit (no split), enough units that the feature-map
-// jobs and the attention waves fill the chip together, parts that fit the registers kept for
-// them, and a shape whose kernel stays within the 128 registers that four waves per SIMD leave
-// each (at most 128 rows and rank 8: the larger forms spill).
+// One launch for the whole step: either a wave per unit and enough units that the feature-map
+// jobs and the attention waves fill the chip together, or a unit's rows split over four waves
+// (the block is then a job's four waves; few units, where a launch of its own for the feature
+// maps is a third of the step); parts that fit the registers kept for them, and a shape whose
+// kernel stays within the registers that four (split: three) resident waves per SIMD leave each
+// (at most 128 rows and rank 8: the larger forms spill).
 bool wpu_fusable(int B, int Hh, int D, int C, int Rp, int R)
 {
   const long units = (long)B * Hh;
-  return wpu_split_waves(units, D, C) == 1 && units >= 1024 && mlp_nparts(Rp) <= 8 && C + 1 <= 2 * kWave && R <= 8 &&
+  const int nw = wpu_split_waves(units, D, C);
+  return ((nw == 1 && units >= 1024) || nw == kWpuFusedUnits) && mlp_nparts(Rp) <= 8 && C + 1 <= 2 * kWave && R <= 8 &&
          Rp < 4096 && D == 128;
 }
 
@@ -675,11 +682,15 @@ template <int D, int RM>
 static hipError_t launch_step_wpu_t(const StepArgs &a, hipStream_t st, const MlpPartsArgs *fm)
 {
   const long units = (long)a.B * a.Hh;
-  if (fm) {
-    if constexpr (D == 128) return launch_step_wpu_s<D, RM, false, true>(a, kWpuFusedUnits, st, fm);
-    else return hipErrorInvalidValue;
-  }
   const int nw = wpu_split_waves(units, D, a.C);
+  if (fm) {
+    if constexpr (D == 128 && RM == 8) {
+      if (nw == kWpuFusedUnits) return launch_step_wpu_s<D, RM, true, true>(a, kWpuFusedUnits, st, fm);
+      return launch_step_wpu_s<D, RM, false, true>(a, kWpuFusedUnits, st, fm);
+    } else {
+      return hipErrorInvalidValue;
+    }
+  }
   if (nw > 1) return launch_step_wpu_s<D, RM, true, false>(a, nw, st, nullptr);
   int upb = kWpuUnits;
   while (upb > 1 && a.Hh * ((a.B + upb - 1) / upb) < 256) upb >>= 1;
