@@ -63,7 +63,8 @@ constexpr int kWpuSpinLimit = 1 << 14;   // FUSED: polls of the feature-map entr
 // of its unit then show it.
 // =====================================================================================
 template <int D, int NR2, int RM, int DEPTH, bool SPLIT, bool FUSED>
-__global__ __launch_bounds__((FUSED ? kWpuFusedUnits : kWpuUnits) * kWave, FUSED ? (SPLIT ? 3 : 4) : 1) void wpu_step_kernel(
+__global__ __launch_bounds__((FUSED ? kWpuFusedUnits : kWpuUnits) * kWave,
+                             FUSED ? ((SPLIT || NR2 > 2 || RM > 8) ? 3 : 4) : 1) void wpu_step_kernel(
     void *k_cache_, const void *q_, const void *k_, int crp_, int hb_, int xs_, int n_mlp, const void *Wq1_,
     const void *Wk1_, const void *Wq2_, const StepArgs a)
 {
@@ -668,8 +669,9 @@ bool wpu_fusable(int B, int Hh, int D, int C, int Rp, int R)
 {
   const long units = (long)B * Hh;
   const int nw = wpu_split_waves(units, D, C);
-  return ((nw == 1 && units >= 1024) || nw == kWpuFusedUnits) && mlp_nparts(Rp) <= 8 && C + 1 <= 2 * kWave && R <= 8 &&
-         Rp < 4096 && D == 128;
+  if (mlp_nparts(Rp) > 8 || Rp >= 4096 || D != 128) return false;
+  if (nw == kWpuFusedUnits) return C + 1 <= 2 * kWave && R <= 8;
+  return units >= 1024 && C + 1 <= 4 * kWave;
 }
 
 // Launch shape.  With thousands of units a wave per unit saturates the memory system; with
@@ -684,8 +686,9 @@ static hipError_t launch_step_wpu_t(const StepArgs &a, hipStream_t st, const Mlp
   const long units = (long)a.B * a.Hh;
   const int nw = wpu_split_waves(units, D, a.C);
   if (fm) {
-    if constexpr (D == 128 && RM == 8) {
-      if (nw == kWpuFusedUnits) return launch_step_wpu_s<D, RM, true, true>(a, kWpuFusedUnits, st, fm);
+    if constexpr (D == 128) {
+      if constexpr (RM == 8)
+        if (nw == kWpuFusedUnits) return launch_step_wpu_s<D, RM, true, true>(a, kWpuFusedUnits, st, fm);
       return launch_step_wpu_s<D, RM, false, true>(a, kWpuFusedUnits, st, fm);
     } else {
       return hipErrorInvalidValue;
