@@ -48,7 +48,7 @@ __global__ __launch_bounds__((FUSED ? kGqsFusedHeads : kGqsMaxHeads) * kWave, FU
   constexpr int RPI = kWave / LPR;         // rows per load instruction
   using Vec = typename Store<T>::Vec;
 
-  extern __shared__ double dyn[];
+  extern __shared__ __attribute__((aligned(16))) double dyn[];
 
   const int C = C_, R = a.R, G = G_;
   const int g = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);    // this wave's query head
@@ -58,7 +58,7 @@ __global__ __launch_bounds__((FUSED ? kGqsFusedHeads : kGqsMaxHeads) * kWave, FU
       mlp_parts_gq_job<D, true>(reinterpret_cast<const __half *>(q_), reinterpret_cast<const __half *>(k_),
                                 reinterpret_cast<const __half *>(Wq1_), reinterpret_cast<const __half *>(Wk1_),
                                 reinterpret_cast<const __half *>(Wq2_), reinterpret_cast<const __half *>(a.Wk2), a.Hh, G,
-                                a.Rp, R, a.B, a.mlp_out, (int)blockIdx.x, g, lane);
+                                a.Rp, R, a.B, a.mlp_out, (int)blockIdx.x, reinterpret_cast<unsigned char *>(dyn), g, lane);
       return;
     }
   }
@@ -510,7 +510,8 @@ static hipError_t launch_step_gqs_t(const StepArgs &a, int G, hipStream_t st, co
   if (fm) {
     if constexpr (D == 128 && RM == 8) {
       const unsigned n_mlp = (unsigned)((long)a.Hh * (G + 1) * mlp_nparts(a.Rp) * ((a.B + 63) / 64));
-      gqs_step_kernel<D, 2, RM, 6, true><<<n_mlp + (unsigned)a.U, block, lds, st>>>(a.k_cache, a.q, a.k, a.C, G, (int)n_mlp,
+      const size_t lds_f = lds < (size_t)mlp_slab_bytes(D) ? (size_t)mlp_slab_bytes(D) : lds;
+      gqs_step_kernel<D, 2, RM, 6, true><<<n_mlp + (unsigned)a.U, block, lds_f, st>>>(a.k_cache, a.q, a.k, a.C, G, (int)n_mlp,
                                                                                    fm->Wq1, fm->Wk1, fm->Wq2, a);
       return hipGetLastError();
     } else {

@@ -110,28 +110,32 @@ __device__ inline void mlp_load_row(const __half *xr, int g, v8h (&bx)[D / 32])
 // b Hh + h goes to dst_map[unit * ustride + part * mlp_entry_stride(R) + r].  COHERENT: the readers run
 // in the same launch, possibly on another XCD whose L2 is not coherent with this one's: the results
 // go out as device-scope stores (written through).
-template <int D, bool COHERENT>
-__device__ inline void mlp_parts_core(const __half *x, const __half *W1, const __half *W2, int Hh, int h, int Rp,
+// NWJ: the waves of one job (4: the chunk is 64 batch rows; 2: 32 rows, and two jobs share a block
+// of four waves, which keeps batches of up to 32 rows from leaving half of every block idle).
+// s_w1: the job's own mlp_slab_bytes(D) of LDS, 16-byte aligned; valid: false for the filler job of
+// a block past the last job (it works on the last job's data and stores nothing); wave: 0..NWJ-1.
+__host__ __device__ constexpr int mlp_slab_bytes(int D) { return kMlpPartHidden * (D * 2 + 16); }
+template <int D, bool COHERENT, int NWJ>
+__device__ __forceinline__ void mlp_parts_core(const __half *x, const __half *W1, const __half *W2, int Hh, int h, int Rp,
                                       int R, int B, int x_stride, float *dst_map, size_t ustride, int part, int chunk,
-                                      int wave, int l)
+                                      unsigned char *s_w1, bool valid, int wave, int l)
 {
   constexpr int kRowBytes = D * 2, kStride = kRowBytes + 16, kChunks = kRowBytes / 16;
-  __shared__ __attribute__((aligned(16))) unsigned char s_w1[kMlpPartHidden * kStride];
   const int g = l / 16, c = l % 16;
-  const int row = chunk * 64 + wave * 16 + c;              // batch row of MFMA column c
-  const bool rowv = row < B;
+  const int row = chunk * (16 * NWJ) + wave * 16 + c;      // batch row of MFMA column c
+  const bool rowv = valid && row < B;
   const size_t u = (size_t)(rowv ? row : 0) * Hh + h;
   v8h bx[D / 32];
   mlp_load_row<D>(x + u * (size_t)x_stride, g, bx);        // padding: any row
   const int hid = part * kMlpPartHidden;
   const bool two = hid + 32 < Rp;                          // the last part may hold one group
   // the job's rows of W1, whole lines (rows past the last hidden unit repeat it: never used)
-  constexpr int kPerThread = kMlpPartHidden * kChunks / 256;
+  constexpr int kPerThread = kMlpPartHidden * kChunks / (64 * NWJ);
   uint4 wreg[kPerThread];
   const int tid = wave * 64 + l;
 #pragma unroll
   for (int i = 0; i < kPerThread; ++i) {
-    const int idx = tid + 256 * i, wr = idx / kChunks, ch = idx % kChunks;
+    const int idx = tid + 64 * NWJ * i, wr = idx / kChunks, ch = idx % kChunks;
     const int hr = hid + wr < Rp ? hid + wr : Rp - 1;
     wreg[i] = *reinterpret_cast<const uint4 *>(W1 + (size_t)hr * D + ch * 8);
   }
@@ -146,7 +150,7 @@ __device__ inline void mlp_parts_core(const __half *x, const __half *W1, const _
   }
 #pragma unroll
   for (int i = 0; i < kPerThread; ++i) {
-    const int idx = tid + 256 * i, wr = idx / kChunks, ch = idx % kChunks;
+    const int idx = tid + 64 * NWJ * i, wr = idx / kChunks, ch = idx % kChunks;
     *reinterpret_cast<uint4 *>(s_w1 + wr * kStride + ch * 16) = wreg[i];
   }
   __syncthreads();
@@ -157,7 +161,7 @@ __device__ inline void mlp_parts_core(const __half *x, const __half *W1, const _
       t.a0[ks] = *reinterpret_cast<const v8h *>(s_w1 + (32 * grp + c) * kStride + (32 * ks + 8 * g) * 2);
       t.a1[ks] = *reinterpret_cast<const v8h *>(s_w1 + (32 * grp + 16 + c) * kStride + (32 * ks + 8 * g) * 2);
     }
-    t.a2 = a2[grp];
+    t.a2 = grp == 0 ? a2[0] : a2[1];                       // (a select: an index would put a2 into scratch memory)
     return t;
   };
   const MlpTiles<D> t0 = tiles(0);
@@ -182,33 +186,60 @@ __device__ inline void mlp_parts_core(const __half *x, const __half *W1, const _
   }
 }
 
-// Job of a step whose two maps have the same heads (one query head per key head): job = ((chunk *
-// nparts + part) * 2 + map) * Hh + head: head fastest, so with Hh a multiple of 8 a head's jobs, and
-// later its readers, share an XCD and its L2.  out[((u * 2 + map) * nparts + part) *
-// mlp_entry_stride(R) + r]: a unit's entries lie together, its wave reads and clears them as one piece.
-template <int D, bool COHERENT>
-__device__ inline void mlp_parts_job(const __half *q, const __half *k, const __half *Wq1, const __half *Wk1,
+// The jobs of a block of four waves for a step whose two maps have the same heads (one query head
+// per key head): 4 / NWJ jobs, block b taking jobs b * (4 / NWJ) + ..; job = ((chunk * nparts +
+// part) * 2 + map) * Hh + head: head fastest, so with Hh a multiple of 8 a head's jobs, and later
+// its readers, share an XCD and its L2.  out[((u * 2 + map) * nparts + part) * mlp_entry_stride(R) + r]: a
+// unit's entries lie together, its wave reads and clears them as one piece.  slabs: (4 / NWJ) *
+// mlp_slab_bytes(D) of LDS.  wave4: 0..3 within the block; every thread of the block must call.
+__host__ __device__ inline int mlp_parts_jobs(int Hh, int Rp, int B, int nwj)
+{
+  return Hh * 2 * mlp_nparts(Rp) * ((B + 16 * nwj - 1) / (16 * nwj));
+}
+__host__ __device__ inline int mlp_parts_nwj(int B) { return B <= 32 ? 2 : 4; }
+__host__ __device__ inline int mlp_parts_blocks(int Hh, int Rp, int B)
+{
+  const int nwj = mlp_parts_nwj(B), per = 4 / nwj;
+  return (mlp_parts_jobs(Hh, Rp, B, nwj) + per - 1) / per;
+}
+template <int D, bool COHERENT, int NWJ>
+__device__ __forceinline__ void mlp_parts_job(const __half *q, const __half *k, const __half *Wq1, const __half *Wk1,
                                      const __half *Wq2, const __half *Wk2, int Hh, int Rp, int R, int B,
-                                     int x_stride, float *out, int job, int wave, int l)
+                                     int x_stride, float *out, int block, unsigned char *slabs, int wave4, int l)
 {
   const int nparts = mlp_nparts(Rp), rp = mlp_entry_stride(R);
-  int b = job;
+  const int sub = wave4 / NWJ, njobs = mlp_parts_jobs(Hh, Rp, B, NWJ);
+  const int job = block * (4 / NWJ) + sub;
+  int b = job < njobs ? job : njobs - 1;
   const int h = b % Hh; b /= Hh;
   const int map = b % 2; b /= 2;
   const int part = b % nparts;
   const int chunk = b / nparts;
-  mlp_parts_core<D, COHERENT>(map ? k : q, (map ? Wk1 : Wq1) + (size_t)h * Rp * D, (map ? Wk2 : Wq2) + (size_t)h * R * Rp,
-                              Hh, h, Rp, R, B, x_stride, out + (size_t)map * nparts * rp, (size_t)2 * nparts * rp, part,
-                              chunk, wave, l);
+  mlp_parts_core<D, COHERENT, NWJ>(map ? k : q, (map ? Wk1 : Wq1) + (size_t)h * Rp * D,
+                                   (map ? Wk2 : Wq2) + (size_t)h * R * Rp, Hh, h, Rp, R, B, x_stride,
+                                   out + (size_t)map * nparts * rp, (size_t)2 * nparts * rp, part, chunk,
+                                   slabs + sub * mlp_slab_bytes(D), job < njobs, wave4 % NWJ, l);
+}
+// the same with the job width chosen from the batch
+template <int D, bool COHERENT>
+__device__ __forceinline__ void mlp_parts_block(const __half *q, const __half *k, const __half *Wq1, const __half *Wk1,
+                                       const __half *Wq2, const __half *Wk2, int Hh, int Rp, int R, int B,
+                                       int x_stride, float *out, int block, unsigned char *slabs, int wave4, int l)
+{
+  if (mlp_parts_nwj(B) == 2)
+    mlp_parts_job<D, COHERENT, 2>(q, k, Wq1, Wk1, Wq2, Wk2, Hh, Rp, R, B, x_stride, out, block, slabs, wave4, l);
+  else
+    mlp_parts_job<D, COHERENT, 4>(q, k, Wq1, Wk1, Wq2, Wk2, Hh, Rp, R, B, x_stride, out, block, slabs, wave4, l);
 }
 
 // Job of a step with G query heads per key head: phi over the B x (Hk G) query rows with a weight
 // set per query head, psi over the B x Hk key rows.  Jobs 0 .. nq - 1 (nq = Hk G nparts chunks) are
 // phi's, head fastest; the rest psi's.  Entries: [query row][part] for phi, then [unit][part] for psi.
+// slab: mlp_slab_bytes(D) of LDS.
 template <int D, bool COHERENT>
-__device__ inline void mlp_parts_gq_job(const __half *q, const __half *k, const __half *Wq1, const __half *Wk1,
+__device__ __forceinline__ void mlp_parts_gq_job(const __half *q, const __half *k, const __half *Wq1, const __half *Wk1,
                                         const __half *Wq2, const __half *Wk2, int Hk, int G, int Rp, int R, int B,
-                                        float *out, int job, int wave, int l)
+                                        float *out, int job, unsigned char *slab, int wave, int l)
 {
   const int nparts = mlp_nparts(Rp), rp = mlp_entry_stride(R), chunks = (B + 63) / 64;
   const int Hq = Hk * G, nq = Hq * nparts * chunks;
@@ -219,8 +250,9 @@ __device__ inline void mlp_parts_gq_job(const __half *q, const __half *k, const 
   const int part = b % nparts;
   const int chunk = b / nparts;
   float *dst = psi ? out + (size_t)B * Hq * nparts * rp : out;
-  mlp_parts_core<D, COHERENT>(psi ? k : q, (psi ? Wk1 : Wq1) + (size_t)h * Rp * D, (psi ? Wk2 : Wq2) + (size_t)h * R * Rp,
-                           Hh, h, Rp, R, B, D, dst, (size_t)nparts * rp, part, chunk, wave, l);
+  mlp_parts_core<D, COHERENT, 4>(psi ? k : q, (psi ? Wk1 : Wq1) + (size_t)h * Rp * D,
+                                 (psi ? Wk2 : Wq2) + (size_t)h * R * Rp, Hh, h, Rp, R, B, D, dst, (size_t)nparts * rp,
+                                 part, chunk, slab, true, wave, l);
 }
 
 }  // namespace lessdec

@@ -180,8 +180,9 @@ __global__ __launch_bounds__(256) void mlp_parts_kernel(const __half *q, const _
   // Plain scalar arguments, the ones the loads need first: the launch can preload the first
   // sixteen dwords into registers (the compile flag asks for it),
   // which takes the argument fetch out of a kernel that is one chain of latencies.  rrp = R | R' << 8.
-  mlp_parts_job<D, false>(q, k, Wq1, Wk1, Wq2, Wk2, Hh, rrp >> 8, rrp & 0xff, B, x_stride, out, (int)blockIdx.x,
-                          (int)threadIdx.x / 64, (int)threadIdx.x % 64);
+  __shared__ __attribute__((aligned(16))) unsigned char s_slabs[2 * mlp_slab_bytes(D)];
+  mlp_parts_block<D, false>(q, k, Wq1, Wk1, Wq2, Wk2, Hh, rrp >> 8, rrp & 0xff, B, x_stride, out, (int)blockIdx.x,
+                            s_slabs, (int)threadIdx.x / 64, (int)threadIdx.x % 64);
 }
 
 // Decode step with G query heads per key head: phi of every query row and psi of every key row by
@@ -191,8 +192,9 @@ __global__ __launch_bounds__(256) void mlp_parts_gq_kernel(const __half *q, cons
                                                            const __half *Wk1, const __half *Wq2, const __half *Wk2,
                                                            int hg, int rrp, int B, float *out)
 {
-  mlp_parts_gq_job<D, false>(q, k, Wq1, Wk1, Wq2, Wk2, hg & 0xffff, hg >> 16, rrp >> 8, rrp & 0xff, B, out, (int)blockIdx.x,
-                      (int)threadIdx.x / 64, (int)threadIdx.x % 64);
+  __shared__ __attribute__((aligned(16))) unsigned char s_slab[mlp_slab_bytes(D)];
+  mlp_parts_gq_job<D, false>(q, k, Wq1, Wk1, Wq2, Wk2, hg & 0xffff, hg >> 16, rrp >> 8, rrp & 0xff, B, out,
+                             (int)blockIdx.x, s_slab, (int)threadIdx.x / 64, (int)threadIdx.x % 64);
 }
 
 bool mlp_mfma_supported(int dtype, int D, int Rp, int R)
@@ -239,7 +241,7 @@ hipError_t launch_mlp_pair(const MlpArgs &a, const MlpArgs &b, hipStream_t st)
 
 hipError_t launch_mlp_parts(const MlpPartsArgs &a, hipStream_t st)
 {
-  const unsigned grid = (unsigned)(a.Hh * 2 * mlp_nparts(a.Rp) * ((a.B + 63) / 64));
+  const unsigned grid = (unsigned)mlp_parts_blocks(a.Hh, a.Rp, a.B);
   const int rrp = a.R | (a.Rp << 8), xs = a.x_stride ? a.x_stride : a.D;
   if (a.D == 128)
     mlp_parts_kernel<128><<<grid, 256, 0, st>>>(a.q, a.k, a.Wq1, a.Wk1, a.Wq2, a.Wk2, a.Hh, rrp, xs, a.B, a.out);

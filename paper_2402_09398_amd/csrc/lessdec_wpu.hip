@@ -79,17 +79,17 @@ __global__ __launch_bounds__((FUSED ? kWpuFusedUnits : kWpuUnits) * kWave,
   constexpr int NP = 8;                    // feature-map parts requested up front (R' <= 512)
   using Vec = typename Store<T>::Vec;
 
-  extern __shared__ double dyn[];
+  extern __shared__ __attribute__((aligned(16))) double dyn[];
 
   const int C = crp_ & 0xfff, R = (crp_ >> 12) & 0x7f, Rp = crp_ >> 19, Hh = hb_ & 0xffff, B_ = (int)((unsigned)hb_ >> 16);
   const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
   if constexpr (FUSED) {
     if ((int)blockIdx.x < n_mlp) {
-      mlp_parts_job<D, true>(reinterpret_cast<const __half *>(q_), reinterpret_cast<const __half *>(k_),
-                             reinterpret_cast<const __half *>(Wq1_), reinterpret_cast<const __half *>(Wk1_),
-                             reinterpret_cast<const __half *>(Wq2_), reinterpret_cast<const __half *>(a.Wk2), Hh, Rp, R,
-                             B_, xs_, a.mlp_out, (int)blockIdx.x, wave, lane);
+      mlp_parts_block<D, true>(reinterpret_cast<const __half *>(q_), reinterpret_cast<const __half *>(k_),
+                               reinterpret_cast<const __half *>(Wq1_), reinterpret_cast<const __half *>(Wk1_),
+                               reinterpret_cast<const __half *>(Wq2_), reinterpret_cast<const __half *>(a.Wk2), Hh, Rp, R,
+                               B_, xs_, a.mlp_out, (int)blockIdx.x, reinterpret_cast<unsigned char *>(dyn), wave, lane);
       return;
     }
   }
@@ -634,7 +634,11 @@ static hipError_t launch_step_wpu_s(const StepArgs &a, int upb, hipStream_t st, 
   const int rows_cap = (a.C + 2) & ~1;
   size_t lds = (size_t)(SPLIT ? 1 : upb) * rows_cap * sizeof(double) + (size_t)upb * rows_cap * sizeof(float);
   if (SPLIT) lds += (size_t)upb * D * sizeof(float);
-  const unsigned n_mlp = FUSED ? (unsigned)(a.Hh * 2 * mlp_nparts(a.Rp) * ((a.B + 63) / 64)) : 0u;
+  const unsigned n_mlp = FUSED ? (unsigned)mlp_parts_blocks(a.Hh, a.Rp, a.B) : 0u;
+  if (FUSED) {                                             // the feature-map blocks stage their weights there
+    const size_t slabs = (size_t)(4 / mlp_parts_nwj(a.B)) * mlp_slab_bytes(D);
+    if (lds < slabs) lds = slabs;
+  }
   const unsigned grid = n_mlp + (unsigned)(a.Hh * (SPLIT ? a.B : (a.B + upb - 1) / upb));
   const unsigned block = (unsigned)(upb * kWave);
   const int rows = a.C + 1;
