@@ -461,6 +461,42 @@ def test_step_equals_its_two_halves(kind):
         assert torch.equal(got[0][2][n], got[1][2][n]), n
 
 
+@pytest.mark.parametrize("kind", ["one-launch", "split", "multi-head"])
+def test_one_launch_and_two_launch_steps_interleave_on_one_workspace(kind):
+    """Where lessdec_step is one launch, its feature maps travel through an array of the workspace
+    whose entries every step, of either form, must leave empty: a sequence that switches between
+    the forms gives the bits of the sequence that never does (a stale entry would be taken for
+    this step's feature map)."""
+    import torch
+    w = _kind_workload("mixed", kind, 24)
+    inp = wl.all_inputs(w)
+    res = hz.gpu_run(w, {k: (v if k in "QKV" else v[:0]) for k, v in inp.items()})      # prompt phase only
+    gpu = res["gpu"]
+    from paper_2402_09398_amd import binding
+    assert binding.lessdec_step_launches(gpu.desc) == 1
+    names = gpu.STATE
+    saved = {n: getattr(gpu, n).clone() for n in names}
+    q, k, v = (torch.from_numpy(inp[n]).cuda() for n in ("q", "k", "v"))
+    T = q.shape[0]
+    pattern = [0, 1, 1, 0, 0, 1, 0, 1, 1, 1, 0, 0]          # 1: the two halves
+    got = []
+    for mixed in (False, True):
+        for n in names:
+            getattr(gpu, n).copy_(saved[n])
+        outs = torch.empty_like(q); ev = torch.empty((T, w.units), dtype=torch.int32, device="cuda")
+        for t in range(T):
+            if mixed and pattern[t % len(pattern)]:
+                gpu.step_features(q[t], k[t])
+                gpu.step_attend(q[t], k[t], v[t], outs[t], ev[t])
+            else:
+                gpu.step(q[t], k[t], v[t], outs[t], ev[t])
+        torch.cuda.synchronize()
+        got.append((outs.cpu(), ev.cpu(), {n: getattr(gpu, n).cpu().clone() for n in names}))
+    assert torch.equal(got[0][0], got[1][0]) and torch.equal(got[0][1], got[1][1])
+    for n in names:
+        assert torch.equal(got[0][2][n], got[1][2][n]), n
+
+
 @pytest.mark.parametrize("kind", KINDS)
 def test_steps_replayed_from_a_hip_graph_match_eager_steps(kind):
     """The step reads and advances its counters on the device and clears nothing with a memset,
