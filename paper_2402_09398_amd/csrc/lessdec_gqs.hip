@@ -33,12 +33,11 @@ constexpr int kGqsParts = 8;        // feature maps taken as parts up to this ma
 // through with device-scope stores, waves read with device-scope loads, ask again while any entry
 // is empty (bounded by kGqsSpinLimit polls, then the NaNs of the empty entries show in the unit's
 // outputs), and hand the entries back empty with their other stores.  Workgroups are dispatched in
-// index order and a job waits for nothing, so no cycle of waits exists.  The block is a job's four
-// waves: four query heads per unit.
-constexpr int kGqsFusedHeads = 4;
+// index order and a job waits for nothing, so no cycle of waits exists.  A job is four waves: a
+// block of four query heads runs one job, a block of eight two.
 constexpr int kGqsSpinLimit = 1 << 14;
 template <int D, int NR2, int RM, int DEPTH, bool FUSED>
-__global__ __launch_bounds__((FUSED ? kGqsFusedHeads : kGqsMaxHeads) * kWave, FUSED ? 4 : 1) void gqs_step_kernel(
+__global__ __launch_bounds__(kGqsMaxHeads * kWave, FUSED ? 2 : 1) void gqs_step_kernel(
     void *k_cache_, const void *q_, const void *k_, int C_, int G_, int n_mlp, const void *Wq1_, const void *Wk1_,
     const void *Wq2_, const StepArgs a)
 {
@@ -58,7 +57,8 @@ __global__ __launch_bounds__((FUSED ? kGqsFusedHeads : kGqsMaxHeads) * kWave, FU
       mlp_parts_gq_job<D, true>(reinterpret_cast<const __half *>(q_), reinterpret_cast<const __half *>(k_),
                                 reinterpret_cast<const __half *>(Wq1_), reinterpret_cast<const __half *>(Wk1_),
                                 reinterpret_cast<const __half *>(Wq2_), reinterpret_cast<const __half *>(a.Wk2), a.Hh, G,
-                                a.Rp, R, a.B, a.mlp_out, (int)blockIdx.x, reinterpret_cast<unsigned char *>(dyn), g, lane);
+                                a.Rp, R, a.B, a.mlp_out, (int)blockIdx.x * (G / 4) + g / 4,
+                                reinterpret_cast<unsigned char *>(dyn) + (g / 4) * mlp_slab_bytes(D), g % 4, lane);
       return;
     }
   }
@@ -491,12 +491,12 @@ bool gqs_supported(int dtype, int D, int C, int R, int G)
 
 bool gqs_takes_parts(int Rp) { return mlp_nparts(Rp) <= kGqsParts; }
 
-// One launch for the whole step: four query heads per unit (the block is a feature-map job's four
-// waves), parts that fit the registers kept for them, and the kernel form that stays within the
-// 128 registers four resident waves per SIMD leave each.
+// One launch for the whole step: four or eight query heads per unit (the block is then one or two
+// feature-map jobs of four waves), parts that fit the registers kept for them, and the kernel form
+// that stays within the 128 registers four resident waves per SIMD leave each.
 bool gqs_fusable(int D, int C, int Rp, int R, int G)
 {
-  return G == kGqsFusedHeads && D == 128 && C + 1 <= 2 * kWave && R <= 8 && mlp_nparts(Rp) <= kGqsParts;
+  return (G == 4 || G == 8) && D == 128 && C + 1 <= 2 * kWave && R <= 8 && mlp_nparts(Rp) <= kGqsParts;
 }
 
 template <int D, int RM>
@@ -509,8 +509,9 @@ static hipError_t launch_step_gqs_t(const StepArgs &a, int G, hipStream_t st, co
   const int rows = a.C + 1;
   if (fm) {
     if constexpr (D == 128 && RM == 8) {
-      const unsigned n_mlp = (unsigned)((long)a.Hh * (G + 1) * mlp_nparts(a.Rp) * ((a.B + 63) / 64));
-      const size_t lds_f = lds < (size_t)mlp_slab_bytes(D) ? (size_t)mlp_slab_bytes(D) : lds;
+      const int per = G / 4;                               // jobs per block
+      const unsigned n_mlp = (unsigned)((mlp_parts_gq_jobs(a.Hh, G, a.Rp, a.B) + per - 1) / per);
+      const size_t slabs = (size_t)per * mlp_slab_bytes(D), lds_f = lds < slabs ? slabs : lds;
       gqs_step_kernel<D, 2, RM, 6, true><<<n_mlp + (unsigned)a.U, block, lds_f, st>>>(a.k_cache, a.q, a.k, a.C, G, (int)n_mlp,
                                                                                    fm->Wq1, fm->Wk1, fm->Wq2, a);
       return hipGetLastError();

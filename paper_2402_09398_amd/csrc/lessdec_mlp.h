@@ -235,14 +235,20 @@ __device__ __forceinline__ void mlp_parts_block(const __half *q, const __half *k
 // Job of a step with G query heads per key head: phi over the B x (Hk G) query rows with a weight
 // set per query head, psi over the B x Hk key rows.  Jobs 0 .. nq - 1 (nq = Hk G nparts chunks) are
 // phi's, head fastest; the rest psi's.  Entries: [query row][part] for phi, then [unit][part] for psi.
-// slab: mlp_slab_bytes(D) of LDS.
+// slab: mlp_slab_bytes(D) of LDS.  A job index past the last job (mlp_parts_gq_jobs) is a filler: it
+// works on the last job's data and stores nothing.
+__host__ __device__ inline int mlp_parts_gq_jobs(int Hk, int G, int Rp, int B)
+{
+  return Hk * (G + 1) * mlp_nparts(Rp) * ((B + 63) / 64);
+}
 template <int D, bool COHERENT>
 __device__ __forceinline__ void mlp_parts_gq_job(const __half *q, const __half *k, const __half *Wq1, const __half *Wk1,
                                         const __half *Wq2, const __half *Wk2, int Hk, int G, int Rp, int R, int B,
-                                        float *out, int job, unsigned char *slab, int wave, int l)
+                                        float *out, int job_, unsigned char *slab, int wave, int l)
 {
   const int nparts = mlp_nparts(Rp), rp = mlp_entry_stride(R), chunks = (B + 63) / 64;
-  const int Hq = Hk * G, nq = Hq * nparts * chunks;
+  const int Hq = Hk * G, nq = Hq * nparts * chunks, njobs = mlp_parts_gq_jobs(Hk, G, Rp, B);
+  const int job = job_ < njobs ? job_ : njobs - 1;
   const bool psi = job >= nq;
   int b = psi ? job - nq : job;
   const int Hh = psi ? Hk : Hq;
@@ -252,7 +258,7 @@ __device__ __forceinline__ void mlp_parts_gq_job(const __half *q, const __half *
   float *dst = psi ? out + (size_t)B * Hq * nparts * rp : out;
   mlp_parts_core<D, COHERENT, 4>(psi ? k : q, (psi ? Wk1 : Wq1) + (size_t)h * Rp * D,
                                  (psi ? Wk2 : Wq2) + (size_t)h * R * Rp, Hh, h, Rp, R, B, D, dst, (size_t)nparts * rp,
-                                 part, chunk, slab, true, wave, l);
+                                 part, chunk, slab, job_ < njobs, wave, l);
 }
 
 }  // namespace lessdec

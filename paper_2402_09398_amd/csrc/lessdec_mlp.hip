@@ -253,7 +253,7 @@ hipError_t launch_mlp_parts(const MlpPartsArgs &a, hipStream_t st)
 // a.Hh: key heads; G query heads each (q rows [B, Hh, G, D], Wq per query head)
 hipError_t launch_mlp_parts_gq(const MlpPartsArgs &a, int G, hipStream_t st)
 {
-  const unsigned grid = (unsigned)((long)a.Hh * (G + 1) * mlp_nparts(a.Rp) * ((a.B + 63) / 64));
+  const unsigned grid = (unsigned)mlp_parts_gq_jobs(a.Hh, G, a.Rp, a.B);
   const int rrp = a.R | (a.Rp << 8), hg = a.Hh | (G << 16);
   if (a.D == 128)
     mlp_parts_gq_kernel<128><<<grid, 256, 0, st>>>(a.q, a.k, a.Wq1, a.Wk1, a.Wq2, a.Wk2, hg, rrp, a.B, a.out);
