@@ -63,9 +63,9 @@ constexpr int kWpuSpinLimit = 1 << 14;   // FUSED: polls of the feature-map entr
 // of its unit then show it.
 // =====================================================================================
 template <int D, int NR2, int RM, int DEPTH, bool SPLIT, bool FUSED>
-__global__ __launch_bounds__((FUSED ? kWpuFusedUnits : kWpuUnits) * kWave,
-                             FUSED ? ((SPLIT || NR2 > 2 || RM > 8) ? 3 : 4) : 1) void wpu_step_kernel(
-    void *k_cache_, const void *q_, const void *k_, int crp_, int hb_, int xs_, int n_mlp, const void *Wq1_,
+__global__ __launch_bounds__((FUSED && !(SPLIT && NR2 > 2) ? kWpuFusedUnits : kWpuUnits) * kWave,
+                             FUSED && !(SPLIT && NR2 > 2) ? ((SPLIT || NR2 > 2 || RM > 8) ? 3 : 4) : 1) void wpu_step_kernel(
+    void *k_cache_, const void *q_, const void *k_, int crp_, int hb_, int xs_, int n_mlp_, const void *Wq1_,
     const void *Wk1_, const void *Wq2_, const StepArgs a)
 {
   // The first arguments repeat what the head of the kernel needs to request the first rows:
@@ -84,19 +84,29 @@ __global__ __launch_bounds__((FUSED ? kWpuFusedUnits : kWpuUnits) * kWave,
   const int C = crp_ & 0xfff, R = (crp_ >> 12) & 0x7f, Rp = crp_ >> 19, Hh = hb_ & 0xffff, B_ = (int)((unsigned)hb_ >> 16);
   const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
+  // bits 0..23: feature-map blocks; 24..29: waves per block (the block size itself would have to be
+  // fetched from memory before anything else could be asked for); 30..: groups of four waves in a
+  // feature-map block, minus one
+  const int n_mlp = n_mlp_ & 0xffffff;
   if constexpr (FUSED) {
     if ((int)blockIdx.x < n_mlp) {
+      // a block of eight waves (a unit's rows over eight waves) is two groups of four; the count
+      // comes with the (preloaded) arguments: the block size would have to be fetched first, a
+      // round trip to memory ahead of a job that is a chain of them
+      const int groups = 1 + (int)((unsigned)n_mlp_ >> 30), grp4 = wave >> 2;
       mlp_parts_block<D, true>(reinterpret_cast<const __half *>(q_), reinterpret_cast<const __half *>(k_),
                                reinterpret_cast<const __half *>(Wq1_), reinterpret_cast<const __half *>(Wk1_),
                                reinterpret_cast<const __half *>(Wq2_), reinterpret_cast<const __half *>(a.Wk2), Hh, Rp, R,
-                               B_, xs_, a.mlp_out, (int)blockIdx.x, reinterpret_cast<unsigned char *>(dyn), wave, lane);
+                               B_, xs_, a.mlp_out, (int)blockIdx.x * groups + grp4,
+                               reinterpret_cast<unsigned char *>(dyn) + grp4 * (4 / mlp_parts_nwj(B_)) * mlp_slab_bytes(D),
+                               wave & 3, lane);
       return;
     }
   }
   const int bid = FUSED ? (int)blockIdx.x - n_mlp : (int)blockIdx.x;
   const int lr = lane % LPR, rb = lane / LPR;
   const int h = bid % Hh, chunk = bid / Hh;
-  const int upb = (int)blockDim.x >> 6;                      // waves in this block
+  const int upb = (n_mlp_ >> 24) & 0x3f;                     // waves in this block
   // SPLIT: the waves of the block share one unit, wave w taking every nw-th load of each
   // stream; otherwise a wave is a unit.
   const int nw = SPLIT ? upb : 1, wv = SPLIT ? wave : 0;
@@ -634,9 +644,10 @@ static hipError_t launch_step_wpu_s(const StepArgs &a, int upb, hipStream_t st, 
   const int rows_cap = (a.C + 2) & ~1;
   size_t lds = (size_t)(SPLIT ? 1 : upb) * rows_cap * sizeof(double) + (size_t)upb * rows_cap * sizeof(float);
   if (SPLIT) lds += (size_t)upb * D * sizeof(float);
-  const unsigned n_mlp = FUSED ? (unsigned)mlp_parts_blocks(a.Hh, a.Rp, a.B) : 0u;
+  const int groups = FUSED && upb > 4 ? upb / 4 : 1;       // groups of four waves a feature-map block has
+  const unsigned n_mlp = FUSED ? (unsigned)((mlp_parts_blocks(a.Hh, a.Rp, a.B) + groups - 1) / groups) : 0u;
   if (FUSED) {                                             // the feature-map blocks stage their weights there
-    const size_t slabs = (size_t)(4 / mlp_parts_nwj(a.B)) * mlp_slab_bytes(D);
+    const size_t slabs = (size_t)groups * (4 / mlp_parts_nwj(a.B)) * mlp_slab_bytes(D);
     if (lds < slabs) lds = slabs;
   }
   const unsigned grid = n_mlp + (unsigned)(a.Hh * (SPLIT ? a.B : (a.B + upb - 1) / upb));
@@ -644,9 +655,16 @@ static hipError_t launch_step_wpu_s(const StepArgs &a, int upb, hipStream_t st, 
   const int rows = a.C + 1;
   const int crp = pack_crp(a), hb = a.Hh | (a.B << 16), xs = a.x_stride ? a.x_stride : D;
   const void *wq1 = fm ? fm->Wq1 : nullptr, *wk1 = fm ? fm->Wk1 : nullptr, *wq2 = fm ? fm->Wq2 : nullptr;
+  // (more than 64 KiB of LDS per block has to be asked for: a setting of the kernel, no allocation)
 #define LESSDEC_WPU_LAUNCH(NR2)                                                                                  \
-  wpu_step_kernel<D, NR2, RM, kDepth, SPLIT, FUSED><<<grid, block, lds, st>>>(a.k_cache, a.q, a.k, crp, hb, xs,    \
-                                                                              (int)n_mlp, wq1, wk1, wq2, a)
+  do {                                                                                                           \
+    if (lds > (size_t)64 * 1024 &&                                                                               \
+        hipFuncSetAttribute(reinterpret_cast<const void *>(&wpu_step_kernel<D, NR2, RM, kDepth, SPLIT, FUSED>),      \
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)                 \
+      return hipErrorInvalidValue;                                                                               \
+    wpu_step_kernel<D, NR2, RM, kDepth, SPLIT, FUSED><<<grid, block, lds, st>>>(a.k_cache, a.q, a.k, crp, hb, xs,  \
+                                                                                (int)(n_mlp | (unsigned)upb << 24 | (unsigned)(groups - 1) << 30), wq1, wk1, wq2, a); \
+  } while (0)
   if (rows <= 2 * kWave) LESSDEC_WPU_LAUNCH(2);
   else if (rows <= 4 * kWave) LESSDEC_WPU_LAUNCH(4);
   else LESSDEC_WPU_LAUNCH(kWpuMaxRows / kWave);
@@ -664,9 +682,9 @@ static int wpu_split_waves(long units, int D, int C)
 }
 
 // One launch for the whole step: either a wave per unit and enough units that the feature-map
-// jobs and the attention waves fill the chip together, or a unit's rows split over four waves
-// (the block is then a job's four waves; few units, where a launch of its own for the feature
-// maps is a third of the step); parts that fit the registers kept for them, and a shape whose
+// jobs and the attention waves fill the chip together, or a unit's rows split over four or eight
+// waves (the block is then one or two groups of a job's four waves; few units, where a launch of its
+// own for the feature maps is a third of the step); parts that fit the registers kept for them, and a shape whose
 // kernel stays within the registers that four (split: three) resident waves per SIMD leave each
 // (at most 128 rows and rank 8: the larger forms spill).
 bool wpu_fusable(int B, int Hh, int D, int C, int Rp, int R)
@@ -674,7 +692,8 @@ bool wpu_fusable(int B, int Hh, int D, int C, int Rp, int R)
   const long units = (long)B * Hh;
   const int nw = wpu_split_waves(units, D, C);
   if (mlp_nparts(Rp) > 8 || Rp >= 4096 || D != 128) return false;
-  if (nw == kWpuFusedUnits) return C + 1 <= 2 * kWave && R <= 8;
+  if (nw == 4) return C + 1 <= 2 * kWave && R <= 8;
+  if (nw == 8) return C + 1 > 2 * kWave && R <= 8;       // (the form for blocks of eight waves is that of more than 128 rows)
   return units >= 1024 && C + 1 <= 4 * kWave;
 }
 
@@ -692,7 +711,7 @@ static hipError_t launch_step_wpu_t(const StepArgs &a, hipStream_t st, const Mlp
   if (fm) {
     if constexpr (D == 128) {
       if constexpr (RM == 8)
-        if (nw == kWpuFusedUnits) return launch_step_wpu_s<D, RM, true, true>(a, kWpuFusedUnits, st, fm);
+        if (nw == 4 || nw == 8) return launch_step_wpu_s<D, RM, true, true>(a, nw, st, fm);
       return launch_step_wpu_s<D, RM, false, true>(a, kWpuFusedUnits, st, fm);
     } else {
       return hipErrorInvalidValue;
