@@ -658,10 +658,16 @@ static hipError_t launch_step_wpu_s(const StepArgs &a, int upb, hipStream_t st, 
   // (more than 64 KiB of LDS per block has to be asked for: a setting of the kernel, no allocation)
 #define LESSDEC_WPU_LAUNCH(NR2)                                                                                  \
   do {                                                                                                           \
-    if (lds > (size_t)64 * 1024 &&                                                                               \
-        hipFuncSetAttribute(reinterpret_cast<const void *>(&wpu_step_kernel<D, NR2, RM, kDepth, SPLIT, FUSED>),      \
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)                 \
-      return hipErrorInvalidValue;                                                                               \
+    static size_t asked[64];                               /* per kernel form and device: granted so far */      \
+    int dev = 0;                                                                                                 \
+    if (lds > (size_t)64 * 1024 && (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64))                   \
+      return hipErrorInvalidDevice;                                                                              \
+    if (lds > (size_t)64 * 1024 && lds > asked[dev]) {                                                           \
+      if (hipFuncSetAttribute(reinterpret_cast<const void *>(&wpu_step_kernel<D, NR2, RM, kDepth, SPLIT, FUSED>),    \
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)               \
+        return hipErrorInvalidValue;                                                                             \
+      asked[dev] = lds;                                                                                          \
+    }                                                                                                            \
     wpu_step_kernel<D, NR2, RM, kDepth, SPLIT, FUSED><<<grid, block, lds, st>>>(a.k_cache, a.q, a.k, crp, hb, xs,  \
                                                                                 (int)(n_mlp | (unsigned)upb << 24 | (unsigned)(groups - 1) << 30), wq1, wk1, wq2, a); \
   } while (0)
