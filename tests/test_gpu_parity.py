@@ -421,6 +421,8 @@ def _kind_workload(name, kind, steps):
         return small(name + "-one-launch", steps=steps, batch=70, heads=16, prompt=30)
     if kind == "split":
         return small(name + "-split", steps=steps, n_heavy=35, n_recent=35, prompt=90)
+    if kind == "split-eight":                # more than 128 rows over eight waves: blocks of eight waves, one launch
+        return small(name + "-split-eight", steps=steps, n_heavy=70, n_recent=70, prompt=160)
     if kind == "multi-head":                 # four query heads per unit: a block per unit, a wave per head
         return small(name + "-multi-head", steps=steps, q_per_kv=4)
     if kind == "multi-head-spread":          # sixteen: the plain kernel, a unit's heads over blocks and a finishing launch
@@ -428,7 +430,7 @@ def _kind_workload(name, kind, steps):
     return small(name + "-general", steps=steps, rank=20)
 
 
-KINDS = ["streaming", "one-launch", "split", "general", "multi-head", "multi-head-spread"]
+KINDS = ["streaming", "one-launch", "split", "split-eight", "general", "multi-head", "multi-head-spread"]
 
 
 @pytest.mark.parametrize("kind", KINDS)
@@ -461,7 +463,7 @@ def test_step_equals_its_two_halves(kind):
         assert torch.equal(got[0][2][n], got[1][2][n]), n
 
 
-@pytest.mark.parametrize("kind", ["one-launch", "split", "multi-head"])
+@pytest.mark.parametrize("kind", ["one-launch", "split", "split-eight", "multi-head"])
 def test_one_launch_and_two_launch_steps_interleave_on_one_workspace(kind):
     """Where lessdec_step is one launch, its feature maps travel through an array of the workspace
     whose entries every step, of either form, must leave empty: a sequence that switches between
