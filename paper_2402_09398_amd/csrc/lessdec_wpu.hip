@@ -698,6 +698,7 @@ bool wpu_fusable(int B, int Hh, int D, int C, int Rp, int R)
   const long units = (long)B * Hh;
   const int nw = wpu_split_waves(units, D, C);
   if (mlp_nparts(Rp) > 8 || Rp >= 4096 || D != 128) return false;
+  if ((long)Hh * 2 * mlp_nparts(Rp) * ((B + 31) / 32) >= (1L << 24)) return false;   // the block count travels in 24 bits
   if (nw == 4) return C + 1 <= 2 * kWave && R <= 8;
   if (nw == 8) return C + 1 > 2 * kWave && R <= 8;       // (the form for blocks of eight waves is that of more than 128 rows)
   return units >= 1024 && C + 1 <= 4 * kWave;
