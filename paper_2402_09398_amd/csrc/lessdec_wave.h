@@ -69,22 +69,6 @@ __device__ inline typename Store<T>::Vec load_vec_nt(const T *p)
   __builtin_memcpy(&v.raw, &t, 16);
   return v;
 }
-// 16-byte stores of state that the same launch does not read again: non-temporal, so that the
-// lines leave the L2 as they are written instead of in one write-back at the end of the kernel.
-__device__ inline void store_nt(float *p, const float4 &v)
-{
-  typedef float f4v __attribute__((ext_vector_type(4)));
-  const f4v t = {v.x, v.y, v.z, v.w};
-  __builtin_nontemporal_store(t, reinterpret_cast<f4v *>(p));
-}
-template <typename T>
-__device__ inline void store_nt(T *p, const uint4 &v)
-{
-  u4v t;
-  __builtin_memcpy(&t, &v, 16);
-  __builtin_nontemporal_store(t, reinterpret_cast<u4v *>(p));
-}
-
 // Stores of state that go through the L2 to memory as they are issued (system scope).  A line
 // that stays dirty in an L2 is written back when the kernel ends, before the next launch can
 // start: with 16 MB written per launch that takes 2.4 us after plain stores, 1.3 us after

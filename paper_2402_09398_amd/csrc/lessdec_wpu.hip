@@ -26,41 +26,50 @@ constexpr int kWpuSpinLimit = 1 << 14;   // FUSED: polls of the feature-map entr
 // rows.  The rows of K and then of V pass through a ring of DEPTH registers per lane: each
 // load is consumed in issue order and its register re-used for the load DEPTH places
 // ahead, so the number of bytes in flight is constant (DEPTH KiB per wave) from the first
-// key row to the last value row; the value stream starts while the last keys are scored
-// and keeps coming during the softmax.  The K part of the stream is padded to a multiple
-// of DEPTH so that ring positions are compile-time constants; loads past the live rows are
-// requested out of the buffer's range, which returns zeros and moves no data.
+// key row to the last value row.  The K part of the stream is padded to a multiple of DEPTH so
+// that ring positions are compile-time constants; loads past the live rows are requested out of
+// the buffer's range, which returns zeros and moves no data.
 //
 // Phase 1  scores s_j = q . K_j / sqrt(D) of the live slots and the appended key as they
 //          arrive: exact fp32 products added in fp64, reduced over the LPR lanes of a row by
-//          DPP, parked in the LDS.  After the first pass over the ring (FUSED: inside phase 2),
-//          phi(q) and psi(k) are finished from their layer-2 sums (last activations of Eq. 1
-//          and Eq. 2, W3) in fp64.
-// Phase 2  lane j owns rows j, j + 64, ..: shift, exponentials, denominator of Eq. 3 with
-//          phi(q) z^T, probabilities, H2O score accumulation, eviction argmin (Sec. 2.1);
-//          fold of the pair the previous step discarded into z (Eq. 5), which Eq. 3 of this
-//          step must already see.
-// Phase 3  p . V in fp32 as the value rows arrive; the value row of the discarded slot is
-//          written to pend_v by the lanes that hold it; the RPI partial rows are combined
-//          by a reduce-scatter that leaves each lane with the four output columns it also
-//          holds of H.
-// Phase 4  fold of the pending pair into H (Eq. 4); out = p V + phi(q) H / den (Eq. 3); the
-//          new pair goes into the freed slot (Sec. 3.2); the discarded pair is left pending
-//          for the next step.
+//          DPP, parked in the LDS.  (!FUSED: after the first pass over the ring, phi(q) and
+//          psi(k) are finished from their layer-2 sums: last activations of Eq. 1 and Eq. 2, W3,
+//          in fp64.)
+// Phase 2  in parts.  First what the value stream needs: lane j owns rows j, j + 64, ..: the
+//          maximum M and the exponentials e^{s_j - M}, which weight the value rows as they are
+//          (the sum is scaled by 1 / den at the output).  The rest is one dependent chain of fp64
+//          reductions and is worked off between the first three passes of the value stream, each
+//          part while the rows requested by the pass before it are on their way:
+//          (a) FUSED: the feature maps from their entries; the fold of the pair the previous step
+//          discarded into z (Eq. 5), which Eq. 3 of this step must already see; phi(q) z^T and
+//          the denominator of Eq. 3; (b) H2O score accumulation and the eviction argmin
+//          (Sec. 2.1); the value row of the discarded slot is asked for once more (the stream
+//          may have passed it); (c) the fold of the pending pair into H (Eq. 4) and phi(q) H.
+// Phase 3  e^{s - M} . V in fp32 as the value rows arrive; the RPI partial rows are combined by a
+//          reduce-scatter that leaves each lane with the four output columns it also holds of H.
+// Stores   none in mid-stream: a wave's memory counter runs in order, so a store would hold up
+//          every row requested after it until it is acknowledged.  The unit's new state (H, z,
+//          psi, accumulated scores, positions, counters, the parked pair, the feature-map entries
+//          handed back empty) goes out before the last pass of the value stream, whose rows are
+//          requested ahead of it; the output out = (sum / den) + phi(q) H / den (Eq. 3) and the
+//          new pair into the freed slot (Sec. 3.2) at the very end.  All of them go through the
+//          L2 to memory (system scope): a line left dirty in an L2 is written back when the
+//          kernel ends, before the next launch can start.
 //
-// FUSED: the whole step in one launch.  The first n_mlp blocks (four waves each) are the step's
-// feature-map jobs (mlp_parts_job), the blocks behind them the attention waves, four units per
-// block.  Workgroups are dispatched in index order, so every job is on a compute unit before any
-// attention wave that may wait for it, and the jobs wait for nothing: no cycle of waits exists.
+// FUSED: the whole step in one launch.  The first n_mlp blocks are the step's feature-map jobs
+// (mlp_parts_block: four waves a job, or two for batches of up to 32 rows), the blocks behind them
+// the attention waves, four units per block (SPLIT: a unit over four or eight waves).  Workgroups
+// are dispatched in index order, so every job is on a compute unit before any attention wave that
+// may wait for it, and the jobs wait for nothing: no cycle of waits exists.
 // The layer-2 sums travel through the exchange array as 32-bit entries, written through by the
 // jobs and read with device-scope loads.  An entry that no job has written yet holds kMlpEmpty:
-// an attention wave requests its entries behind the last-but-one pass of the key stream (by then
-// the jobs are normally long done), checks them after the sparse part of phase 2, asks again while
-// any is still empty, and puts kMlpEmpty back once it has them, so that the array is all empty again when the
-// step ends.  (The form that gets its entries from a launch before it, !FUSED, empties them as
-// well: either form can follow the other on one workspace.)  A wave that has polled
-// kWpuSpinLimit times gives up and computes with the empty entries, which are NaN: the outputs
-// of its unit then show it.
+// an attention wave requests its entries before the last pass of the key stream (by then the jobs
+// are normally long done), looks at them after the first pass of the value stream, asks again
+// while any is still empty, and puts kMlpEmpty back with its other stores, so that the array is
+// all empty again when the step ends.  (The form that gets its entries from a launch before it,
+// !FUSED, empties them as well: either form can follow the other on one workspace.)  A wave that
+// has polled kWpuSpinLimit times gives up and computes with the empty entries, which are NaN: the
+// outputs of its unit then show it.
 // =====================================================================================
 template <int D, int NR2, int RM, int DEPTH, bool SPLIT, bool FUSED>
 __global__ __launch_bounds__((FUSED && !(SPLIT && NR2 > 2) ? kWpuFusedUnits : kWpuUnits) * kWave,
