@@ -11,8 +11,10 @@
 //              share of every pair's score increment goes to s_inc[head];
 //   barrier 2  all increments visible;
 //   phase 2b   every wave adds the increments in head order to the accumulated scores and works
-//              out the eviction for itself (same data, same result); the lead wave stores;
-//   phase 3/4  per head p . V, phi(q) H, output; the lead wave parks the discarded pair;
+//              out the eviction for itself (same data, same result);
+//   phase 3/4  per head p . V, phi(q) H, output; then, behind its last load, the lead wave stores
+//              the unit's new state and parks the discarded pair (no store stands in mid-stream:
+//              a wave's memory counter runs in order; all stores go through the L2 to memory);
 //   barrier 3  every wave is through with the cache rows; the lead wave writes the new pair
 //              into its slot (Sec. 3.2).
 // The fold of the discarded pair into H, z is left to the next step (pend_slot, as on the
