@@ -7,8 +7,10 @@
 // cache for the other heads.  A wave has its own query, phi(q), scores, softmax (Eq. 3 with the
 // shared state H, z) and output row.  What the heads share goes through the LDS:
 //   barrier 1  every wave has the unit's state in registers (the lead wave may now store);
-//   phase 2a   per head: shift, exponentials, Eq. 3's denominator, probabilities; the head's
-//              share of every pair's score increment goes to s_inc[head];
+//   phase 2a   per head: shift and exponentials, which weight the value rows as they are (the
+//              sum is scaled by 1 / den at the output), so that the value stream starts here and
+//              everything below up to phase 3 is worked off between its first passes; Eq. 3's
+//              denominator; the head's share of every pair's score increment goes to s_inc[head];
 //   barrier 2  all increments visible;
 //   phase 2b   every wave adds the increments in head order to the accumulated scores and works
 //              out the eviction for itself (same data, same result);
@@ -181,15 +183,17 @@ __global__ __launch_bounds__(kGqsMaxHeads * kWave, FUSED ? 2 : 1) void gqs_step_
   // ---- phase 1: this head's scores as the key rows arrive -------------------------------------------
   {
     const double inv_sqrt_d = 1.0 / sqrt((double)D);
+    u4v knu;                                               // (as a value: a choice between addresses would put the ring into scratch memory)
+    __builtin_memcpy(&knu, &knv.raw, 16);
     auto key_pass = [&](int base) __attribute__((always_inline)) {
 #pragma unroll
       for (int j = 0; j < DEPTH; ++j) {
         const int s = base + j;
         if (s < nit) {
           const int r = s * RPI + rb;
+          const u4v kraw = (r == m) ? knu : buf[j];          // r == m: the appended key
           Vec kv;
-          __builtin_memcpy(&kv.raw, &buf[j], 16);
-          if (r == m) kv = knv;                              // the appended key
+          __builtin_memcpy(&kv.raw, &kraw, 16);
           // a product of two halves is exact in fp32, so fp32 multiply, widen, fp64 add
           double part = 0.0;
 #pragma unroll
@@ -260,26 +264,66 @@ __global__ __launch_bounds__(kGqsMaxHeads * kWave, FUSED ? 2 : 1) void gqs_step_
   __builtin_amdgcn_s_barrier();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 
-  // ---- phase 2a: this head's softmax with the low-rank term -----------------------------------------
-  double lscale = 0.0;
+  // ---- phase 2a, first part: what the value stream needs, the exponentials e^{s_j - M} -------------
+  // As on the single-head path the value rows are weighted with the exponentials as they are, the
+  // sum is scaled by 1 / den at the output, and the rest of phase 2 (denominator, the heads'
+  // increments and barrier 2, accumulated scores and eviction, the fold into H) is worked off
+  // between the first passes of the value stream, while the rows requested by the pass before
+  // are on their way.  Every wave runs the same sequence of passes and barriers.
+  double lscale = 0.0, pscale = 0.0;
   if (lane >= R) f_lane = 0.0;
-  {
-    double sc[NR2];
-    double M = -__builtin_inf();
+  double sc[NR2];
+  double M = -__builtin_inf();
 #pragma unroll
-    for (int i = 0; i < NR2; ++i) {
-      const int j = lane + i * kWave;
-      sc[i] = j < rows ? s_sc[j] : -__builtin_inf();
-      M = fmax(M, sc[i]);
+  for (int i = 0; i < NR2; ++i) {
+    const int j = lane + i * kWave;
+    sc[i] = j < rows ? s_sc[j] : -__builtin_inf();
+    M = fmax(M, sc[i]);
+  }
+  M = wave_allreduce(M, OpMax{});
+#pragma unroll
+  for (int i = 0; i < NR2; ++i) {
+    const int j = lane + i * kWave;
+    sc[i] = j < rows ? exp_softmax_f64(sc[i] - M) : 0.0;
+    if (j < rows) s_p[j] = (float)sc[i];
+  }
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+  // ---- phase 3: e^{s - M} . V as the value rows arrive ----------------------------------------------
+  float o[EPL];
+#pragma unroll
+  for (int i = 0; i < EPL; ++i) o[i] = 0.f;
+  float fh[4] = {0.f, 0.f, 0.f, 0.f};                        // phi(q) H, this lane's columns and rows
+  auto value_pass = [&](int base) __attribute__((always_inline)) {
+#pragma unroll
+    for (int j = 0; j < DEPTH; ++j) {
+      const int s = base + j;
+      if (s < nit) {
+        const int r = s * RPI + rb;
+        Vec vv;
+        __builtin_memcpy(&vv.raw, &buf[j], 16);
+        if (r < m) {
+          const float p = s_p[r];
+#pragma unroll
+          for (int i = 0; i < EPL; ++i) o[i] = fmaf(p, Store<T>::get(vv, i), o[i]);
+        }
+      }
+      buf[j] = issue(nitp + s + DEPTH);
+      __builtin_amdgcn_sched_barrier(0);
     }
-    M = wave_allreduce(M, OpMax{});
+  };
+  // Passes past the end of the stream consume nothing and request rows outside the buffer's
+  // range, which fetches nothing: the three passes always run, so that no load sits under a
+  // condition.
+  value_pass(0);
+
+  // ---- phase 2a, second part: Eq. 3's denominator, the head's share of the score increments ---------
+  {
     double S = 0.0;
 #pragma unroll
-    for (int i = 0; i < NR2; ++i) {
-      const int j = lane + i * kWave;
-      sc[i] = j < rows ? exp_softmax_f64(sc[i] - M) : 0.0;
-      S += sc[i];
-    }
+    for (int i = 0; i < NR2; ++i) S += sc[i];
     S = wave_allreduce(S, OpAdd{});                          // sparse part of the denominator, shifted
     // pending fold of z (Eq. 5), then phi(q) z^T
     if (lane >= R) z_lane = 0.0;
@@ -287,7 +331,6 @@ __global__ __launch_bounds__(kGqsMaxHeads * kWave, FUSED ? 2 : 1) void gqs_step_
     else if (pend.slot >= C) psie_lane = ppsi_lane;          // the previous step discarded its own pair
     if (lane < R && pend.fold) z_lane += (double)psie_lane;
     const double fz = wave_allreduce(f_lane * z_lane, OpAdd{});
-    double pscale;
     if (fz > 0.0 && M <= 0.0) {
       const double w = exp_softmax_f64(M);
       const double inv = 1.0 / (fz + w * S);
@@ -304,20 +347,19 @@ __global__ __launch_bounds__(kGqsMaxHeads * kWave, FUSED ? 2 : 1) void gqs_step_
 #pragma unroll
     for (int i = 0; i < NR2; ++i) {
       const int j = lane + i * kWave;
-      if (j < rows) {
-        s_p[j] = (float)(sc[i] * pscale);
-        s_inc[(size_t)g * rows_cap + j] = sc[i] * ascale;
-      }
+      if (j < rows) s_inc[(size_t)g * rows_cap + j] = sc[i] * ascale;
     }
   }
   // barrier 2: every head's increments are in the LDS
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
   __builtin_amdgcn_s_barrier();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+  value_pass(DEPTH);
 
   // ---- phase 2b: accumulated scores and the eviction, by every wave for itself ----------------------
   int eslot = -1, ins_slot = -1, epos = -1;
   double na_[NR2];
+  u4v pv_row = {0u, 0u, 0u, 0u};                            // the discarded pair's value row
   {
     const bool lambda = (a.flags & LESSDEC_FLAG_LAMBDA) != 0;
     Cand best = cand_none();
@@ -353,97 +395,41 @@ __global__ __launch_bounds__(kGqsMaxHeads * kWave, FUSED ? 2 : 1) void gqs_step_
     }
     const bool evict = eslot >= 0;                           // eslot == m: the new pair itself
     ins_slot = full ? ((evict && eslot < m) ? eslot : -1) : m;
+    // its value row once more (the stream may have passed it): unconditional, from row 0 where no
+    // cached pair leaves
+    const __amdgpu_buffer_rsrc_t rv = __builtin_amdgcn_make_buffer_rsrc(vc, 0, C * D * (int)sizeof(T), 0x00020000);
+    const int er = (evict && eslot < m) ? eslot : 0;
+    pv_row = __builtin_amdgcn_raw_buffer_load_b128(rv, lr * 16, er * (D * (int)sizeof(T)), 0);
   }
-
-  // ---- phase 3: p . V as the value rows arrive ------------------------------------------------------
-  float o[EPL];
-#pragma unroll
-  for (int i = 0; i < EPL; ++i) o[i] = 0.f;
-  float fh[4] = {0.f, 0.f, 0.f, 0.f};                        // phi(q) H, this lane's columns and rows
-  uint4 pv_keep = {0u, 0u, 0u, 0u};                          // the discarded pair's value row
+  value_pass(2 * DEPTH);
   {
-    int base = 0;
-    do {                                                     // nit >= 1
+    // fold the pending pair into H (Eq. 4; stored by the lead wave), then this head's phi(q) H
+    const float f32 = (float)f_lane;
+    const __half2 *pvh = reinterpret_cast<const __half2 *>(&pend_v_h);
+    const float2 pv01 = __half22float2(pvh[0]), pv23 = __half22float2(pvh[1]);
 #pragma unroll
-      for (int j = 0; j < DEPTH; ++j) {
-        const int s = base + j;
-        if (s < nit) {
-          const int r = s * RPI + rb;
-          Vec vv;
-          __builtin_memcpy(&vv.raw, &buf[j], 16);
-          if (r == m) vv = vnv;                              // the appended pair's value row
-          if (r < rows) {
-            const float p = s_p[r];
-#pragma unroll
-            for (int i = 0; i < EPL; ++i) o[i] = fmaf(p, Store<T>::get(vv, i), o[i]);
-          }
-          if (r == eslot) pv_keep = vv.raw;
-        }
-        buf[j] = issue(nitp + s + DEPTH);
-        __builtin_amdgcn_sched_barrier(0);
+    for (int i = 0; i < HR; ++i) {
+      const int r = NHB * i + hb;
+      const int rc = r < R ? r : R - 1;
+      const float fr = r < R ? __shfl(f32, rc) : 0.f;
+      const float pe = __shfl(psie_lane, rc);
+      if (pend.fold) {
+        hreg[i].x = fmaf(pe, pv01.x, hreg[i].x);
+        hreg[i].y = fmaf(pe, pv01.y, hreg[i].y);
+        hreg[i].z = fmaf(pe, pv23.x, hreg[i].z);
+        hreg[i].w = fmaf(pe, pv23.y, hreg[i].w);
       }
-      if (base == 0) {
-        // fold the pending pair into H (Eq. 4; stored by the lead wave), then this head's phi(q) H
-        const float f32 = (float)f_lane;
-        const __half2 *pvh = reinterpret_cast<const __half2 *>(&pend_v_h);
-        const float2 pv01 = __half22float2(pvh[0]), pv23 = __half22float2(pvh[1]);
-#pragma unroll
-        for (int i = 0; i < HR; ++i) {
-          const int r = NHB * i + hb;
-          const int rc = r < R ? r : R - 1;
-          const float fr = r < R ? __shfl(f32, rc) : 0.f;
-          const float pe = __shfl(psie_lane, rc);
-          if (pend.fold) {
-            hreg[i].x = fmaf(pe, pv01.x, hreg[i].x);
-            hreg[i].y = fmaf(pe, pv01.y, hreg[i].y);
-            hreg[i].z = fmaf(pe, pv23.x, hreg[i].z);
-            hreg[i].w = fmaf(pe, pv23.y, hreg[i].w);
-          }
-          fh[0] = fmaf(fr, hreg[i].x, fh[0]);
-          fh[1] = fmaf(fr, hreg[i].y, fh[1]);
-          fh[2] = fmaf(fr, hreg[i].z, fh[2]);
-          fh[3] = fmaf(fr, hreg[i].w, fh[3]);
-        }
-      }
-    } while ((base += DEPTH) < nit);
-  }
-  // The RPI row groups hold partial sums of the same 8 columns: reduce-scatter over the first
-  // stage (a lane keeps the four columns selected by its bit LPR), all-reduce over the rest,
-  // together with the partial phi(q) H of the row subsets.
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const bool hi = lane & LPR;
-    const float send = hi ? o[i] : o[i + 4], keep = hi ? o[i + 4] : o[i];
-    o[i] = keep + __shfl_xor(send, LPR);
-  }
-#pragma unroll
-  for (int x = 2 * LPR; x < kWave; x *= 2) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      o[i] += __shfl_xor(o[i], x);
-      fh[i] += __shfl_xor(fh[i], x);
+      fh[0] = fmaf(fr, hreg[i].x, fh[0]);
+      fh[1] = fmaf(fr, hreg[i].y, fh[1]);
+      fh[2] = fmaf(fr, hreg[i].z, fh[2]);
+      fh[3] = fmaf(fr, hreg[i].w, fh[3]);
     }
   }
-  // ---- phase 4: this head's output; the new pair goes into its slot once every head is through ------
-  if (hb == 0) {
-    __half2 res[2];
-    res[0] = __floats2half2_rn((float)((double)o[0] + lscale * (double)fh[0]), (float)((double)o[1] + lscale * (double)fh[1]));
-    res[1] = __floats2half2_rn((float)((double)o[2] + lscale * (double)fh[2]), (float)((double)o[3] + lscale * (double)fh[3]));
-    store_wt8(reinterpret_cast<T *>(a.out) + ((size_t)u * G + g) * D + col0, *reinterpret_cast<const uint2 *>(res));
-  }
-  // the feature-map entries go back empty: this head's, and (lead wave) the key's
-  if (parts) {
-    for (int e = lane; e < nparts * (rp / 4); e += kWave) {
-      store_wt16(a.mlp_out + ((size_t)u * G + g) * nparts * rp, e * 16, uint4{kMlpEmpty, kMlpEmpty, kMlpEmpty, kMlpEmpty});
-      if (lead)
-        store_wt16(a.mlp_out + ((size_t)a.U * G + u) * nparts * rp, e * 16, uint4{kMlpEmpty, kMlpEmpty, kMlpEmpty, kMlpEmpty});
-    }
-  }
-  // The unit's new state, by the lead wave: every store of the step stands behind the last load
-  // (a wave's memory counter runs in order: a store in mid-stream holds up the rows requested
-  // after it) and goes through the L2 to memory (a line left dirty there is written back when
-  // the kernel ends, before the next launch can start).
-  if (lead) {
+  // The unit's new state, by the lead wave.  No store stands in mid-stream (a wave's memory
+  // counter runs in order: a store holds up the rows requested after it): these go out before the
+  // last pass, whose rows are requested ahead of them, and through the L2 to memory (a line left
+  // dirty there is written back when the kernel ends, before the next launch can start).
+  auto state_stores = [&]() __attribute__((always_inline)) {
     if (pend.fold) {                                         // H with the pending pair folded in (Eq. 4)
 #pragma unroll
       for (int i = 0; i < HR; ++i) {
@@ -471,8 +457,55 @@ __global__ __launch_bounds__(kGqsMaxHeads * kWave, FUSED ? 2 : 1) void gqs_step_
       if (a.evicted_pos) store_wt(a.evicted_pos + u, eslot >= 0 ? epos : -1);
       store_wt(a.n_seen + u, n + 1);
     }
-    if (eslot >= 0 && rb == eslot % RPI)
-      store_wt16(reinterpret_cast<T *>(a.pend_v) + (size_t)u * D, lr * EPL * (int)sizeof(T), pv_keep);
+    if (eslot >= 0 && rb == 0) {
+      uint4 row = vnv.raw;
+      if (eslot < m) __builtin_memcpy(&row, &pv_row, 16);
+      store_wt16(reinterpret_cast<T *>(a.pend_v) + (size_t)u * D, lr * EPL * (int)sizeof(T), row);
+    }
+  };
+  {
+    int base = 3 * DEPTH;
+    for (; base + DEPTH < nit; base += DEPTH) value_pass(base);
+    if (lead) state_stores();
+    if (base < nit) value_pass(base);                        // the last pass requests nothing real
+  }
+  // the appended pair's value row
+  if (rb == 0) {
+    const float p = s_p[m];
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) o[i] = fmaf(p, Store<T>::get(vnv, i), o[i]);
+  }
+  // The RPI row groups hold partial sums of the same 8 columns: reduce-scatter over the first
+  // stage (a lane keeps the four columns selected by its bit LPR), all-reduce over the rest,
+  // together with the partial phi(q) H of the row subsets.
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const bool hi = lane & LPR;
+    const float send = hi ? o[i] : o[i + 4], keep = hi ? o[i + 4] : o[i];
+    o[i] = keep + __shfl_xor(send, LPR);
+  }
+#pragma unroll
+  for (int x = 2 * LPR; x < kWave; x *= 2) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      o[i] += __shfl_xor(o[i], x);
+      fh[i] += __shfl_xor(fh[i], x);
+    }
+  }
+  // ---- phase 4: this head's output; the new pair goes into its slot once every head is through ------
+  if (hb == 0) {
+    __half2 res[2];
+    res[0] = __floats2half2_rn((float)(pscale * (double)o[0] + lscale * (double)fh[0]), (float)(pscale * (double)o[1] + lscale * (double)fh[1]));
+    res[1] = __floats2half2_rn((float)(pscale * (double)o[2] + lscale * (double)fh[2]), (float)(pscale * (double)o[3] + lscale * (double)fh[3]));
+    store_wt8(reinterpret_cast<T *>(a.out) + ((size_t)u * G + g) * D + col0, *reinterpret_cast<const uint2 *>(res));
+  }
+  // the feature-map entries go back empty: this head's, and (lead wave) the key's
+  if (parts) {
+    for (int e = lane; e < nparts * (rp / 4); e += kWave) {
+      store_wt16(a.mlp_out + ((size_t)u * G + g) * nparts * rp, e * 16, uint4{kMlpEmpty, kMlpEmpty, kMlpEmpty, kMlpEmpty});
+      if (lead)
+        store_wt16(a.mlp_out + ((size_t)a.U * G + u) * nparts * rp, e * 16, uint4{kMlpEmpty, kMlpEmpty, kMlpEmpty, kMlpEmpty});
+    }
   }
   // barrier 3: the rows still in a ring are requests past the value stream (out of range, zeros),
   // so every wave that arrives here has all the cache rows it will ever read
