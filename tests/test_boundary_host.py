@@ -54,6 +54,31 @@ def _desc(**kw):
     return d
 
 
+def _workload_desc(w, **kw):
+    d = binding.Desc()
+    d.batch, d.heads, d.head_dim = w.batch, w.heads, w.head_dim
+    d.n_heavy, d.n_recent, d.rank, d.hidden = w.n_heavy, w.n_recent, w.rank, w.hidden
+    d.dtype = binding.DTYPE_F16 if w.dtype == "f16" else binding.DTYPE_F32
+    for k, v in kw.items():
+        setattr(d, k, v)
+    return d
+
+
+def test_launches_per_step_of_the_workloads():
+    """Which form of the step a shape takes is decided on the host: the four fp16 workloads run it
+    as one launch (feature-map jobs in front of the attention waves), four or eight query heads per
+    unit too; the other shapes keep a launch of their own for the feature maps."""
+    got = {c: binding.lessdec_step_launches(_workload_desc(wl.WORKLOADS[c])) for c in range(1, 6)}
+    assert got == {1: 3, 2: 1, 3: 1, 4: 1, 5: 1}
+    w3 = wl.WORKLOADS[3]
+    for g, n in [(2, 2), (4, 1), (8, 1), (16, 3)]:
+        assert binding.lessdec_step_launches(_workload_desc(w3, heads=w3.heads // g, q_per_kv=g)) == n
+    assert binding.lessdec_step_launches(_workload_desc(w3, rank=20)) == 3       # any-shape kernels
+    assert binding.lessdec_step_launches(_workload_desc(w3, hidden=1024)) == 2   # more parts than a wave keeps
+    assert binding.lessdec_step_launches(_workload_desc(w3, head_dim=64)) == 2
+    assert binding.lessdec_step_launches(_workload_desc(w3, batch=-1)) == 0      # invalid shape
+
+
 def test_workspace_bytes_and_shape_validation():
     assert binding.lessdec_workspace_bytes(_desc(), 0) > 0
     assert binding.lessdec_workspace_bytes(_desc(), 512) > binding.lessdec_workspace_bytes(_desc(), 0)
