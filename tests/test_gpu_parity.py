@@ -334,6 +334,9 @@ GROUPS = [
     (small("gqa-4-heads-one-launch-ragged-batch", q_per_kv=4, batch=70, heads=8, hidden=512, prompt=30, steps=20), 0),
     (small("gqa-4-heads-one-launch-filling", q_per_kv=4, batch=3, heads=5, hidden=96, prompt=0, steps=30,
            n_heavy=10, n_recent=10), 0),
+    # eight heads: two feature-map jobs to a block; 27 jobs, so the last block's second job is a filler
+    (small("gqa-8-heads-one-launch-odd-jobs", q_per_kv=8, batch=5, heads=3, hidden=64, prompt=20, steps=20), 0),
+    (small("gqa-8-heads-one-launch-ragged-batch", q_per_kv=8, batch=70, heads=4, hidden=512, prompt=30, steps=12), 0),
     (small("gqa-5-heads-wide-cache", q_per_kv=5, n_heavy=100, n_recent=60, prompt=200, steps=10, batch=1,
            heads=2, rank=16, hidden=96), 4),
 ]
