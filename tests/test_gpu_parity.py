@@ -102,6 +102,10 @@ EDGE = [
     small("split-4-waves", n_heavy=35, n_recent=35, prompt=100, steps=30, head_dim=64, rank=16),
     small("split-8-waves-filling", n_heavy=70, n_recent=70, prompt=0, steps=150, batch=1, heads=2),
     small("split-8-waves-no-recent", n_heavy=130, n_recent=0, prompt=200, steps=20, batch=1, heads=2),
+    # one launch with blocks of eight waves: two feature-map jobs of four waves to a block (batch above 32),
+    # four jobs of two waves (6 jobs: the second block carries two fillers)
+    small("split-8-waves-one-launch-batch-40", batch=40, heads=2, n_heavy=70, n_recent=70, prompt=150, steps=12),
+    small("split-8-waves-one-launch-fillers", batch=2, heads=3, hidden=64, n_heavy=70, n_recent=70, prompt=150, steps=12),
     # 1024 units or more with a wave each: the whole step is one launch (feature-map jobs ahead of
     # the attention waves); ragged batch chunks, a cache that is still filling, the largest rank
     small("one-launch-ragged-batch", batch=70, heads=16, prompt=30, steps=16),
